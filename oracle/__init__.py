@@ -1,0 +1,147 @@
+"""Python face of the CPU oracle (chunk_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import this
+package; the GPU library and its binding never do.  The arithmetic is all in the C
+file; this module compiles it with gcc and marshals numpy arrays.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_DIR = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_DIR, "chunk_oracle.c")
+_LIB = os.path.join(_DIR, "libchunk_oracle.so")
+
+# strict IEEE: no fast-math, no FMA contraction, SSE2 scalar arithmetic
+CFLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off",
+          "-Wall", "-Wextra"]
+
+F32, BF16 = 0, 1
+SUM, MAX, MIN, COPY = 0, 1, 2, 3
+NO_FORWARD = 0xFFFFFFFFFFFFFFFF
+ERRORS = {-1: "ARG", -2: "SEQ", -3: "ALIGN", -4: "BOUNDS", -5: "MISMATCH", -6: "OVERLAP"}
+
+DESC = np.dtype([("src_off", "<u8"), ("dst_off", "<u8"), ("out_off", "<u8"),
+                 ("len", "<u4"), ("seq", "<u4")])
+
+
+class OraclePrecondition(ValueError):
+    def __init__(self, code):
+        super().__init__(f"oracle precondition violated: {ERRORS.get(code, code)}")
+        self.code = code
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (always when force, else when stale)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(
+        os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_DIR, "chunk_oracle.h")))
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", *CFLAGS, _SRC, "-o", tmp])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        L = C.CDLL(build())
+        vp, u64, i64 = C.c_void_p, C.c_uint64, C.c_int64
+        L.orc_apply.restype = i64
+        L.orc_apply.argtypes = [vp, u64, vp, u64, vp, u64, vp, u64, vp, u64, C.c_int, C.c_int]
+        L.orc_scatter.restype = i64
+        L.orc_scatter.argtypes = [vp, u64, vp, u64, vp, u64, vp, u64]
+        L.orc_check_call.restype = i64
+        L.orc_check_call.argtypes = [vp, u64, vp, u64]
+        L.orc_pack_bitmap.restype = None
+        L.orc_pack_bitmap.argtypes = [vp, u64, vp]
+        L.orc_ring_allreduce.restype = C.c_int
+        L.orc_ring_allreduce.argtypes = [vp, C.c_uint32, u64, C.c_int, C.c_int, vp]
+        L.orc_combine_f32.restype = C.c_float
+        L.orc_combine_f32.argtypes = [C.c_float, C.c_float, C.c_int]
+        L.orc_combine_bf16.restype = C.c_uint16
+        L.orc_combine_bf16.argtypes = [C.c_uint16, C.c_uint16, C.c_int]
+        L.orc_f32_to_bf16.restype = C.c_uint16
+        L.orc_f32_to_bf16.argtypes = [C.c_float]
+        _lib = L
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data
+
+
+def _descs(descs):
+    d = np.ascontiguousarray(descs)
+    assert d.dtype.itemsize == 32 and d.dtype.names == DESC.names, "descriptor layout"
+    return d
+
+
+def new_seen(n_bits: int) -> np.ndarray:
+    return np.zeros(int(n_bits), dtype=np.uint8)
+
+
+def apply(acc, out_stage, recv_stage, descs, seen, dtype, op, check=True) -> int:
+    """In-place oracle_apply on numpy buffers; returns the number of records applied."""
+    d = _descs(descs)
+    for a in (acc, recv_stage, seen) + ((out_stage,) if out_stage is not None else ()):
+        assert a.flags.c_contiguous
+    if check:
+        rc = lib().orc_check_call(_ptr(recv_stage), recv_stage.nbytes, _ptr(d), len(d))
+        if rc < 0:
+            raise OraclePrecondition(rc)
+    rc = lib().orc_apply(_ptr(acc), acc.nbytes, _ptr(out_stage),
+                         0 if out_stage is None else out_stage.nbytes, _ptr(recv_stage),
+                         recv_stage.nbytes, _ptr(d), len(d), _ptr(seen), len(seen),
+                         int(dtype), int(op))
+    if rc < 0:
+        raise OraclePrecondition(rc)
+    return int(rc)
+
+
+def scatter(dst, recv_stage, descs, seen, check=True) -> int:
+    d = _descs(descs)
+    assert dst.flags.c_contiguous and recv_stage.flags.c_contiguous
+    if check:
+        rc = lib().orc_check_call(_ptr(recv_stage), recv_stage.nbytes, _ptr(d), len(d))
+        if rc < 0:
+            raise OraclePrecondition(rc)
+    rc = lib().orc_scatter(_ptr(dst), dst.nbytes, _ptr(recv_stage), recv_stage.nbytes,
+                           _ptr(d), len(d), _ptr(seen), len(seen))
+    if rc < 0:
+        raise OraclePrecondition(rc)
+    return int(rc)
+
+
+def pack_bitmap(seen) -> np.ndarray:
+    words = np.zeros((len(seen) + 31) // 32, dtype=np.uint32)
+    lib().orc_pack_bitmap(_ptr(seen), len(seen), _ptr(words))
+    return words
+
+
+def ring_allreduce(x, dtype, op=SUM) -> np.ndarray:
+    """x: (R, n) array (fp32, or uint16 bf16 bits).  Returns every rank's final buffer."""
+    x = np.ascontiguousarray(x)
+    R, n = x.shape
+    out = np.empty_like(x)
+    rc = lib().orc_ring_allreduce(_ptr(x), R, n, int(dtype), int(op), _ptr(out))
+    if rc:
+        raise OraclePrecondition(rc)
+    return out
+
+
+def combine_f32(a, r, op) -> np.float32:
+    return np.float32(lib().orc_combine_f32(np.float32(a), np.float32(r), int(op)))
+
+
+def combine_bf16(a, r, op) -> int:
+    return int(lib().orc_combine_bf16(int(a), int(r), int(op)))
+
+
+def f32_to_bf16(f) -> int:
+    return int(lib().orc_f32_to_bf16(np.float32(f)))

@@ -1,0 +1,238 @@
+/*
+ * CPU oracle for the receive-side chunk data path.  TEST INFRASTRUCTURE ONLY:
+ * see chunk_oracle.h for scope, citations and parity status.  Plain C, one
+ * thread, no blocking or fusion: one loop over arrivals, one loop over elements.
+ * Build without fast-math and without fused contraction so that every add is a
+ * single IEEE-754 binary32 operation with subnormals kept.
+ */
+#include "chunk_oracle.h"
+
+#include <stdlib.h>
+#include <string.h>
+
+/* ---- element numerics ------------------------------------------------------ */
+
+static uint32_t f32_bits(float f) { uint32_t u; memcpy(&u, &f, 4); return u; }
+static float bits_f32(uint32_t u) { float f; memcpy(&f, &u, 4); return f; }
+
+/* bf16 is the upper half of a binary32: widening is exact. */
+static float bf16_widen(uint16_t h) { return bits_f32((uint32_t)h << 16); }
+
+/* binary32 -> bf16, round to nearest, ties to even; NaN stays a (quiet) NaN. */
+uint16_t orc_f32_to_bf16(float f) {
+  uint32_t u = f32_bits(f);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);
+  uint32_t lsb = (u >> 16) & 1u;
+  return (uint16_t)((u + 0x7FFFu + lsb) >> 16);
+}
+
+/* The tensor-buffer value a is combined with the received value r.
+ * SUM: one binary32 add.  MAX / MIN: this build defines them as a strict
+ * comparison that keeps the local value on ties and whenever the comparison is
+ * false, i.e. MAX(a,r) = r if r > a else a.  The paper names "sum, max" only
+ * (Section 2.1); NaN and signed-zero behaviour is this build's choice. */
+float orc_combine_f32(float a, float r, int op) {
+  switch (op) {
+    case ORC_SUM: return a + r;
+    case ORC_MAX: return (r > a) ? r : a;
+    case ORC_MIN: return (r < a) ? r : a;
+    default: return r; /* COPY */
+  }
+}
+
+/* bf16: widen both, combine in binary32, round once.  MAX/MIN/COPY select one of
+ * the two 16-bit inputs unchanged. */
+uint16_t orc_combine_bf16(uint16_t a, uint16_t r, int op) {
+  float fa = bf16_widen(a), fr = bf16_widen(r);
+  switch (op) {
+    case ORC_SUM: return orc_f32_to_bf16(fa + fr);
+    case ORC_MAX: return (fr > fa) ? r : a;
+    case ORC_MIN: return (fr < fa) ? r : a;
+    default: return r;
+  }
+}
+
+/* ---- per-record checks ------------------------------------------------------ */
+
+static int range_ok(uint64_t off, uint64_t len, uint64_t size) {
+  return off <= size && len <= size - off;
+}
+
+static int64_t check_record(const orc_desc* d, uint64_t acc_bytes, uint64_t out_bytes,
+                            int have_out, uint64_t recv_bytes, uint64_t n_bits, uint32_t es) {
+  if (d->seq >= n_bits) return ORC_E_SEQ;
+  if ((d->src_off | d->dst_off) & 15u) return ORC_E_ALIGN;
+  if (d->out_off != ORC_NO_FORWARD && (d->out_off & 15u)) return ORC_E_ALIGN;
+  if (d->len % es) return ORC_E_ALIGN;
+  if (!range_ok(d->src_off, d->len, recv_bytes)) return ORC_E_BOUNDS;
+  if (!range_ok(d->dst_off, d->len, acc_bytes)) return ORC_E_BOUNDS;
+  if (d->out_off != ORC_NO_FORWARD) {
+    if (!have_out || !range_ok(d->out_off, d->len, out_bytes)) return ORC_E_BOUNDS;
+  }
+  return 0;
+}
+
+/* ---- the definition --------------------------------------------------------- */
+
+int64_t orc_apply(void* acc, uint64_t acc_bytes, void* out_stage, uint64_t out_bytes,
+                  const void* recv_stage, uint64_t recv_bytes, const orc_desc* descs,
+                  uint64_t n_descs, uint8_t* seen, uint64_t n_bits, int dtype, int op) {
+  if (dtype != ORC_F32 && dtype != ORC_BF16) return ORC_E_ARG;
+  if (op < ORC_SUM || op > ORC_COPY) return ORC_E_ARG;
+  if (n_descs == 0) return 0;
+  if (!acc || !recv_stage || !descs || !seen) return ORC_E_ARG;
+  const uint32_t es = (dtype == ORC_F32) ? 4u : 2u;
+  int64_t applied = 0;
+  for (uint64_t k = 0; k < n_descs; ++k) { /* array order = arrival order */
+    const orc_desc* d = &descs[k];
+    int64_t rc = check_record(d, acc_bytes, out_bytes, out_stage != NULL, recv_bytes, n_bits, es);
+    if (rc) return rc;
+    if (seen[d->seq]) continue; /* a retransmitted copy of a chunk already applied: drop */
+    seen[d->seq] = 1;
+    ++applied;
+    const uint64_t n = d->len / es;
+    const int fwd = d->out_off != ORC_NO_FORWARD;
+    if (dtype == ORC_F32) {
+      const float* r = (const float*)((const char*)recv_stage + d->src_off);
+      float* a = (float*)((char*)acc + d->dst_off);
+      float* o = fwd ? (float*)((char*)out_stage + d->out_off) : NULL;
+      for (uint64_t i = 0; i < n; ++i) {
+        float t = orc_combine_f32(a[i], r[i], op);
+        a[i] = t;
+        if (fwd) o[i] = t;
+      }
+    } else {
+      const uint16_t* r = (const uint16_t*)((const char*)recv_stage + d->src_off);
+      uint16_t* a = (uint16_t*)((char*)acc + d->dst_off);
+      uint16_t* o = fwd ? (uint16_t*)((char*)out_stage + d->out_off) : NULL;
+      for (uint64_t i = 0; i < n; ++i) {
+        uint16_t t = orc_combine_bf16(a[i], r[i], op);
+        a[i] = t;
+        if (fwd) o[i] = t;
+      }
+    }
+  }
+  return applied;
+}
+
+int64_t orc_scatter(void* dst, uint64_t dst_bytes, const void* recv_stage, uint64_t recv_bytes,
+                    const orc_desc* descs, uint64_t n_descs, uint8_t* seen, uint64_t n_bits) {
+  if (n_descs == 0) return 0;
+  if (!dst || !recv_stage || !descs || !seen) return ORC_E_ARG;
+  int64_t applied = 0;
+  for (uint64_t k = 0; k < n_descs; ++k) {
+    const orc_desc* d = &descs[k];
+    if (d->out_off != ORC_NO_FORWARD) return ORC_E_ARG; /* a scatter never forwards */
+    int64_t rc = check_record(d, dst_bytes, 0, 0, recv_bytes, n_bits, 1u);
+    if (rc) return rc;
+    if (seen[d->seq]) continue;
+    seen[d->seq] = 1;
+    ++applied;
+    const unsigned char* r = (const unsigned char*)recv_stage + d->src_off;
+    unsigned char* a = (unsigned char*)dst + d->dst_off;
+    for (uint64_t i = 0; i < d->len; ++i) a[i] = r[i];
+  }
+  return applied;
+}
+
+void orc_pack_bitmap(const uint8_t* seen, uint64_t n_bits, uint32_t* words) {
+  uint64_t nw = (n_bits + 31) / 32;
+  for (uint64_t w = 0; w < nw; ++w) words[w] = 0;
+  for (uint64_t s = 0; s < n_bits; ++s)
+    if (seen[s]) words[s >> 5] |= (uint32_t)1 << (s & 31);
+}
+
+/* ---- whole-call preconditions ---------------------------------------------- */
+
+typedef struct { uint64_t key, end; uint64_t idx; } ivl;
+
+static int cmp_ivl(const void* x, const void* y) {
+  const ivl* a = (const ivl*)x; const ivl* b = (const ivl*)y;
+  if (a->key != b->key) return a->key < b->key ? -1 : 1;
+  if (a->idx != b->idx) return a->idx < b->idx ? -1 : 1;
+  return 0;
+}
+
+int64_t orc_check_call(const void* recv_stage, uint64_t recv_bytes, const orc_desc* descs,
+                       uint64_t n_descs) {
+  if (n_descs == 0) return 0;
+  ivl* v = (ivl*)malloc(sizeof(ivl) * n_descs);
+  if (!v) return ORC_E_ARG;
+  int64_t rc = 0;
+  /* records of one seq must agree in every field and in payload bytes */
+  for (uint64_t k = 0; k < n_descs; ++k) { v[k].key = descs[k].seq; v[k].end = 0; v[k].idx = k; }
+  qsort(v, n_descs, sizeof(ivl), cmp_ivl);
+  uint64_t n_rep = 0;
+  for (uint64_t k = 0; k < n_descs && !rc; ++k) {
+    const orc_desc* d = &descs[v[k].idx];
+    if (!range_ok(d->src_off, d->len, recv_bytes)) { rc = ORC_E_BOUNDS; break; }
+    if (k > 0 && v[k - 1].key == v[k].key) {
+      const orc_desc* p = &descs[v[k - 1].idx];
+      if (p->dst_off != d->dst_off || p->out_off != d->out_off || p->len != d->len ||
+          memcmp((const char*)recv_stage + p->src_off, (const char*)recv_stage + d->src_off, d->len))
+        rc = ORC_E_MISMATCH;
+    } else {
+      v[n_rep++].idx = v[k].idx; /* keep one representative per seq (k >= n_rep always) */
+    }
+  }
+  /* representatives must not overlap in acc, nor in out_stage */
+  for (int pass = 0; pass < 2 && !rc; ++pass) {
+    ivl* w = (ivl*)malloc(sizeof(ivl) * (n_rep ? n_rep : 1));
+    if (!w) { rc = ORC_E_ARG; break; }
+    uint64_t m = 0;
+    for (uint64_t k = 0; k < n_rep; ++k) {
+      const orc_desc* d = &descs[v[k].idx];
+      if (d->len == 0) continue;
+      uint64_t off = pass == 0 ? d->dst_off : d->out_off;
+      if (pass == 1 && off == ORC_NO_FORWARD) continue;
+      w[m].key = off; w[m].end = off + d->len; w[m].idx = k; ++m;
+    }
+    qsort(w, m, sizeof(ivl), cmp_ivl);
+    for (uint64_t k = 1; k < m; ++k)
+      if (w[k].key < w[k - 1].end) { rc = ORC_E_OVERLAP; break; }
+    free(w);
+  }
+  free(v);
+  return rc;
+}
+
+/* ---- textbook ring allreduce ------------------------------------------------- */
+
+/* R ranks in a ring, buffer of n elements cut into R equal segments.  In
+ * reduce-scatter step s rank r combines into its own segment (r-s-1) mod R what
+ * rank r-1 held for that segment before the step; after R-1 steps rank r holds
+ * the complete result of segment (r+1) mod R.  In allgather step s rank r
+ * overwrites segment (r-s) mod R with rank r-1's copy.  All ranks step together,
+ * so each step reads a snapshot of the previous state. */
+int orc_ring_allreduce(const void* x, uint32_t R, uint64_t n, int dtype, int op, void* result) {
+  if (!x || !result || R == 0 || n % R) return ORC_E_ARG;
+  if (dtype != ORC_F32 && dtype != ORC_BF16) return ORC_E_ARG;
+  if (op < ORC_SUM || op > ORC_MIN) return ORC_E_ARG;
+  const uint32_t es = (dtype == ORC_F32) ? 4u : 2u;
+  const uint64_t seg = n / R, total = (uint64_t)R * n * es;
+  char* cur = (char*)result;
+  memcpy(cur, x, total);
+  if (R == 1) return 0;
+  char* prev = (char*)malloc(total);
+  if (!prev) return ORC_E_ARG;
+  for (uint32_t phase = 0; phase < 2; ++phase) {
+    for (uint32_t s = 0; s + 1 < R; ++s) {
+      memcpy(prev, cur, total);
+      for (uint32_t r = 0; r < R; ++r) {
+        uint32_t left = (r + R - 1) % R;
+        uint32_t j = phase == 0 ? (r + 2 * R - s - 1) % R : (r + R - s) % R;
+        for (uint64_t i = j * seg; i < (j + 1) * seg; ++i) {
+          if (dtype == ORC_F32) {
+            float mine = ((float*)prev)[r * n + i], got = ((float*)prev)[left * n + i];
+            ((float*)cur)[r * n + i] = phase == 0 ? orc_combine_f32(mine, got, op) : got;
+          } else {
+            uint16_t mine = ((uint16_t*)prev)[r * n + i], got = ((uint16_t*)prev)[left * n + i];
+            ((uint16_t*)cur)[r * n + i] = phase == 0 ? orc_combine_bf16(mine, got, op) : got;
+          }
+        }
+      }
+    }
+  }
+  free(prev);
+  return 0;
+}

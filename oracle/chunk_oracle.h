@@ -1,0 +1,90 @@
+/*
+ * CPU oracle for the receive-side chunk data path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This is the plain definition of what the GPU library must compute, executed
+ * sequentially on one host thread.  It exists so that tests, the smoke check and
+ * the benchmark's CPU-baseline leg have something independent to compare the GPU
+ * path with.  It shares no code, header or table with the GPU library, and no
+ * product code path may call it.
+ *
+ * What it follows:
+ *  - Section 2.1 (collectives over RDMA): the GPU kernel copies between transport
+ *    buffers and tensor buffers and reduces (sum, max) transport buffers into the
+ *    tensor buffers.
+ *  - Section 3.1 (reassembly challenge): out-of-order payloads are copied to where
+ *    the receiver CPU says they belong, then the reduction runs.
+ *  - Section 3.2 (handling out-of-order packets): sequence numbers identify
+ *    chunks, retransmission creates duplicates, reorder buffers live in GPU memory.
+ *
+ * Parity status: every function is pinned by tests/test_oracle_pins.py except
+ *  - MAX/MIN on NaN or mixed-sign zeros, and which copy of a duplicated sequence
+ *    number supplies the bytes: the paper fixes neither ("parity unpinned"; the
+ *    behaviour below is this build's definition, see the comments at each).
+ */
+#ifndef CHUNK_ORACLE_H
+#define CHUNK_ORACLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+  uint64_t src_off; /* byte offset of the arrival's slot in recv_stage */
+  uint64_t dst_off; /* byte offset in acc */
+  uint64_t out_off; /* byte offset in out_stage, or ORC_NO_FORWARD */
+  uint32_t len;     /* payload bytes */
+  uint32_t seq;     /* logical chunk id = index into seen[] */
+} orc_desc;
+
+#define ORC_NO_FORWARD 0xFFFFFFFFFFFFFFFFull
+
+enum { ORC_F32 = 0, ORC_BF16 = 1 };
+enum { ORC_SUM = 0, ORC_MAX = 1, ORC_MIN = 2, ORC_COPY = 3 };
+
+/* negative return codes: a precondition of the problem statement is violated */
+enum {
+  ORC_E_ARG = -1,      /* bad dtype / op / null pointer */
+  ORC_E_SEQ = -2,      /* seq >= n_bits */
+  ORC_E_ALIGN = -3,    /* offset not 16-byte aligned or len not a multiple of the element size */
+  ORC_E_BOUNDS = -4,   /* a range leaves its buffer, or a forward with no out_stage */
+  ORC_E_MISMATCH = -5, /* two records of one seq differ in dst/out/len or payload bytes */
+  ORC_E_OVERLAP = -6   /* records of different seq overlap in acc or in out_stage */
+};
+
+/* Apply records in array (= arrival) order.  seen[] (one byte per seq) persists
+ * across calls; the caller zeroes it to start a new epoch.  Returns the number
+ * of records applied (first arrivals), or a negative code with nothing further
+ * applied after the offending record. */
+int64_t orc_apply(void* acc, uint64_t acc_bytes, void* out_stage, uint64_t out_bytes,
+                  const void* recv_stage, uint64_t recv_bytes, const orc_desc* descs,
+                  uint64_t n_descs, uint8_t* seen, uint64_t n_bits, int dtype, int op);
+
+/* All-to-all scatter: byte copy, no forward, element type irrelevant. */
+int64_t orc_scatter(void* dst, uint64_t dst_bytes, const void* recv_stage, uint64_t recv_bytes,
+                    const orc_desc* descs, uint64_t n_descs, uint8_t* seen, uint64_t n_bits);
+
+/* Checks the preconditions a single call must satisfy beyond per-record bounds:
+ * records sharing a seq are identical (fields and payload); records of different
+ * seq touch disjoint acc and out_stage ranges.  0 or a negative code. */
+int64_t orc_check_call(const void* recv_stage, uint64_t recv_bytes, const orc_desc* descs,
+                       uint64_t n_descs);
+
+/* Pack seen[] into 32-bit words, bit (s & 31) of word (s >> 5) = seen[s]. */
+void orc_pack_bitmap(const uint8_t* seen, uint64_t n_bits, uint32_t* words);
+
+/* Textbook in-order ring allreduce of R vectors of n elements (n % R == 0),
+ * no chunks, no transport: x is R*n elements (rank-major), result is R*n
+ * elements (every rank's final buffer).  Returns 0 or ORC_E_ARG. */
+int orc_ring_allreduce(const void* x, uint32_t R, uint64_t n, int dtype, int op, void* result);
+
+/* One element-wise combine, exposed so tests can pin the numerics directly. */
+float orc_combine_f32(float a, float r, int op);
+uint16_t orc_combine_bf16(uint16_t a, uint16_t r, int op);
+uint16_t orc_f32_to_bf16(float f);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

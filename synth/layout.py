@@ -1,0 +1,35 @@
+"""Binary layout of the records that cross the library boundary.
+
+The control path (simulated here) hands the GPU a list of per-arrival records,
+the way the paper's receiver CPU hands packet pointers to the fused kernel
+through host/device shared memory (Implementation section) in "the right order
+given by the receiver CPU" (Section 3.1, reassembly challenge).  This module only
+describes bytes; it performs none of the method's arithmetic.
+"""
+import numpy as np
+
+#: one record per ARRIVAL (not per logical chunk), 32 bytes, little endian
+DESC = np.dtype(
+    [
+        ("src_off", "<u8"),  # byte offset of this arrival's slot in recv_stage
+        ("dst_off", "<u8"),  # byte offset in acc (apply) / dst (scatter)
+        ("out_off", "<u8"),  # byte offset in out_stage, or NO_FORWARD
+        ("len", "<u4"),      # payload bytes
+        ("seq", "<u4"),      # bit index in the dedup bitmap = logical chunk id
+    ]
+)
+assert DESC.itemsize == 32
+
+NO_FORWARD = np.uint64(0xFFFFFFFFFFFFFFFF)
+
+# dtype / op codes shared by every caller (values are part of the C ABI)
+F32, BF16 = 0, 1
+SUM, MAX, MIN, COPY = 0, 1, 2, 3
+
+ELEM_SIZE = {F32: 4, BF16: 2}
+OFFSET_ALIGN = 16  # every offset in a record is a multiple of this
+
+
+def bitmap_words(n_bits: int) -> int:
+    """Number of 32-bit words a dedup bitmap of n_bits needs."""
+    return (int(n_bits) + 31) // 32
