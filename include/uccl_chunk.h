@@ -1,0 +1,159 @@
+/*
+ * uccl_chunk.h -- C ABI of the receive-side chunk data path for multipath collectives
+ * on AMD Instinct MI355X (gfx950).
+ *
+ * Problem (paper, Section 2.1 "collectives over RDMA", Section 3.1 "challenge of
+ * reassembly", Section 3.2 "handling out-of-order packets", Section 5): chunks of a
+ * collective message are sprayed over many network paths and land in GPU memory in
+ * ARRIVAL order, possibly more than once (retransmission).  The receiver CPU knows,
+ * per arrival, which logical chunk it is and where it belongs, and passes a list of
+ * pointers to the GPU kernel through shared memory.  The GPU kernel must put every
+ * payload where it belongs and combine it with the tensor buffer (sum, max) or just
+ * copy it, and leave the result where the next ring step will send it from.
+ *
+ * This library is that GPU kernel for one rank's share: for every record, in one
+ * pass over the payload,
+ *     dedup   - test-and-set bit `seq` of the bitmap; only the first arrival proceeds
+ *     place   - src = recv_stage + src_off, dst = acc + dst_off, fwd = out_stage + out_off
+ *     combine - t[i] = op(acc[dst+i], recv[src+i])   (COPY: t[i] = recv[src+i])
+ *     write   - acc[dst+i] = t[i]; and out_stage[out+i] = t[i] when the record forwards
+ *
+ * All buffer pointers are DEVICE pointers owned by the caller (the library never
+ * allocates, frees or keeps them); `stream` is a hipStream_t passed as void* (NULL =
+ * the null stream).  Every call only enqueues work on `stream` and returns: no host
+ * synchronisation, no host read of device memory.  Records and buffers must stay valid
+ * until the stream has passed the call; receive slots may be recycled after that point
+ * (the paper's irecv_free_ptrs moment, Section 5).
+ */
+#ifndef UCCL_CHUNK_H
+#define UCCL_CHUNK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define UCCL_CHUNK_VERSION 1
+
+/* One record per ARRIVAL, written by the control path in arrival order (Section 3.1:
+ * "the right order given by the receiver CPU"; Section 5: packet pointers passed via
+ * CPU-GPU shared memory).  32 bytes; the array must be 16-byte aligned. */
+typedef struct uccl_chunk_desc {
+  uint64_t src_off; /* byte offset of this arrival's slot in recv_stage; multiple of 16 */
+  uint64_t dst_off; /* byte offset in acc (apply) / dst (scatter); multiple of 16 */
+  uint64_t out_off; /* byte offset in out_stage, multiple of 16; UCCL_NO_FORWARD = do not forward */
+  uint32_t len;     /* payload bytes; may be 0; a multiple of the element size (apply) */
+  uint32_t seq;     /* logical chunk id = bit index in dedup_bitmap (the role of the chunk
+                       sequence number of the control header, Section 3.1) */
+} uccl_chunk_desc;
+
+#define UCCL_NO_FORWARD 0xFFFFFFFFFFFFFFFFull
+
+typedef enum uccl_dtype { UCCL_F32 = 0, UCCL_BF16 = 1 } uccl_dtype;
+
+/* Section 2.1 names "sum, max"; MIN and COPY complete the set a ring needs.
+ * SUM  f32 : one IEEE-754 binary32 add (round to nearest even, subnormals kept).
+ * SUM  bf16: widen both to binary32 (exact), add, round once to nearest even;
+ *            a NaN sum becomes (bits >> 16) | 0x0040.
+ * MAX/MIN  : strict comparison on the (widened) values; a tie or an unordered pair
+ *            keeps the accumulator's element: MAX(a, r) = r if r > a else a.
+ * COPY     : t = r; the element type is irrelevant and `len` may be any byte count. */
+typedef enum uccl_op { UCCL_SUM = 0, UCCL_MAX = 1, UCCL_MIN = 2, UCCL_COPY = 3 } uccl_op;
+
+enum {
+  UCCL_OK = 0,
+  UCCL_EINVAL = -1,  /* null pointer with n_descs > 0, unknown dtype/op/shape, aliasing buffers */
+  UCCL_EALIGN = -2,  /* a base pointer is not 16-byte aligned (bitmap / counter: 4-byte) */
+  UCCL_ELAUNCH = -3  /* HIP refused the launch; uccl_last_error_detail() has HIP's message */
+};
+
+/* Buffer sizes for the checked entry points (HOST struct, read during the call). */
+typedef struct uccl_extents {
+  uint64_t acc_bytes;  /* size of acc / dst */
+  uint64_t out_bytes;  /* size of out_stage (0 if none) */
+  uint64_t recv_bytes; /* size of recv_stage */
+  uint64_t n_bits;     /* number of valid bits in dedup_bitmap */
+} uccl_extents;
+
+/*
+ * uccl_chunk_apply -- dedup, place, combine, write back and forward (see top of file).
+ *
+ *   acc          device, read+written: the rank's accumulator / tensor buffer
+ *   out_stage    device, written: outbound staging buffer; may be NULL if no record forwards
+ *   recv_stage   device, read: arrival-order slot pool (the GPU-resident reorder buffers)
+ *   descs        device, read: n_descs records, arrival order
+ *   dedup_bitmap device, read+written atomically: bit s set <=> chunk s has been applied
+ *                since the last uccl_dedup_reset; persists across calls
+ *
+ * Exactly one record per distinct `seq` is applied over the bitmap's lifetime, whatever
+ * the arrival order and however often a chunk is repeated, within a call or across
+ * calls on one stream.  Which of several copies supplies the bytes is unspecified.
+ *
+ * Preconditions the caller guarantees (the unchecked call cannot verify them):
+ *   - seq < number of bits in dedup_bitmap; every offset range lies inside its buffer;
+ *   - records with the same seq have identical dst_off, out_off, len and payload bytes;
+ *   - within one call, records with different seq touch disjoint ranges of acc and of
+ *     out_stage (order between dependent steps is expressed by separate calls);
+ *   - recv_stage overlaps neither acc nor out_stage.
+ * A record whose offsets are misaligned or whose len is not a multiple of the element
+ * size is skipped (its bit stays clear).
+ *
+ * Returns UCCL_OK (also for n_descs == 0, which enqueues nothing) or a negative code;
+ * on error nothing has been enqueued.
+ */
+int uccl_chunk_apply(void* acc, void* out_stage, const void* recv_stage,
+                     const uccl_chunk_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
+                     uccl_dtype dtype, uccl_op op, void* stream);
+
+/*
+ * uccl_chunk_apply_checked -- same operation; additionally every record is validated ON
+ * THE GPU against `extents` before its bit is touched: seq < n_bits, all three ranges
+ * inside their buffers, alignment, len granularity, and a forward needs out_stage.  A
+ * record that fails is skipped (bit stays clear, no byte moved) and, if `n_rejected`
+ * (device uint32_t, caller-zeroed, 4-byte aligned, may be NULL) is given, counted there.
+ * On the host, overlapping recv_stage / acc / out_stage extents return UCCL_EINVAL.
+ */
+int uccl_chunk_apply_checked(void* acc, void* out_stage, const void* recv_stage,
+                             const uccl_chunk_desc* descs, uint32_t n_descs,
+                             uint32_t* dedup_bitmap, uccl_dtype dtype, uccl_op op,
+                             const uccl_extents* extents, uint32_t* n_rejected, void* stream);
+
+/*
+ * uccl_chunk_scatter -- all-to-all receive side (Section 2.1: copy from transport
+ * buffers to tensor buffers; Section 3.1: scattered memcpy): dedup + place + byte copy
+ * into `dst` at per-source offsets.  No combine, no forward (out_off must be
+ * UCCL_NO_FORWARD, other records are skipped), element type irrelevant.
+ */
+int uccl_chunk_scatter(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,
+                       uint32_t n_descs, uint32_t* dedup_bitmap, void* stream);
+
+int uccl_chunk_scatter_checked(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,
+                               uint32_t n_descs, uint32_t* dedup_bitmap,
+                               const uccl_extents* extents, uint32_t* n_rejected, void* stream);
+
+/* Clear the first n_bits bits (rounded up to whole 32-bit words) of the bitmap: starts a
+ * new message / connection epoch.  Uses a fill kernel, so it may be captured in a graph. */
+int uccl_dedup_reset(uint32_t* dedup_bitmap, uint64_t n_bits, void* stream);
+
+/*
+ * Launch shape: how records are mapped onto the machine.  AUTO picks from n_descs.
+ *   WAVE   one 64-lane wavefront streams a chunk; a 256-thread workgroup dedups a tile
+ *          of records together and its four wavefronts take the winners in turn
+ *   GROUP  all 256 threads of a workgroup stream one chunk
+ *   WIDE   all 1024 threads of a workgroup stream one chunk (few, large chunks)
+ * Process-wide setting, intended for tuning runs; returns UCCL_EINVAL for unknown ids.
+ */
+typedef enum uccl_shape {
+  UCCL_SHAPE_AUTO = 0, UCCL_SHAPE_WAVE = 1, UCCL_SHAPE_GROUP = 2, UCCL_SHAPE_WIDE = 3
+} uccl_shape;
+int uccl_set_launch_shape(int shape);
+
+const char* uccl_strerror(int code);
+const char* uccl_last_error_detail(void); /* HIP's text for the last UCCL_ELAUNCH on this thread */
+int uccl_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* UCCL_CHUNK_H */

@@ -1,0 +1,159 @@
+"""Thin ctypes binding of libuccl_chunk.so (the C ABI declared in include/uccl_chunk.h).
+
+Argument marshalling only: every step of the data path (dedup, place, combine, write,
+forward) runs in the HIP kernels.  Buffers are device memory owned by the caller, passed
+as torch tensors (their data_ptr() is used) or as integer device addresses; ``stream`` is
+a torch.cuda.Stream, an integer hipStream_t, or None for torch's current stream.
+
+There is no CPU fallback: if the shared library cannot be loaded, load() raises.
+"""
+import ctypes as C
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libuccl_chunk.so")
+HEADER_PATH = os.path.join(os.path.dirname(_PKG), "include", "uccl_chunk.h")
+
+UCCL_F32, UCCL_BF16 = 0, 1
+UCCL_SUM, UCCL_MAX, UCCL_MIN, UCCL_COPY = 0, 1, 2, 3
+UCCL_OK, UCCL_EINVAL, UCCL_EALIGN, UCCL_ELAUNCH = 0, -1, -2, -3
+UCCL_NO_FORWARD = 0xFFFFFFFFFFFFFFFF
+UCCL_SHAPE_AUTO, UCCL_SHAPE_WAVE, UCCL_SHAPE_GROUP, UCCL_SHAPE_WIDE = 0, 1, 2, 3
+DESC_BYTES = 32
+
+
+class uccl_extents(C.Structure):
+    _fields_ = [("acc_bytes", C.c_uint64), ("out_bytes", C.c_uint64),
+                ("recv_bytes", C.c_uint64), ("n_bits", C.c_uint64)]
+
+
+class UcclError(RuntimeError):
+    def __init__(self, code, what):
+        detail = ""
+        if code == UCCL_ELAUNCH and _lib is not None:
+            detail = ": " + _lib.uccl_last_error_detail().decode()
+        name = _lib.uccl_strerror(code).decode() if _lib is not None else str(code)
+        super().__init__(f"{what} failed: {name} ({code}){detail}")
+        self.code = code
+
+
+_lib = None
+
+_SIGNATURES = {
+    "uccl_chunk_apply": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                   C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
+    "uccl_chunk_apply_checked": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                           C.c_uint32, C.c_void_p, C.c_int, C.c_int,
+                                           C.POINTER(uccl_extents), C.c_void_p, C.c_void_p]),
+    "uccl_chunk_scatter": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
+                                     C.c_void_p]),
+    "uccl_chunk_scatter_checked": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                             C.c_void_p, C.POINTER(uccl_extents), C.c_void_p,
+                                             C.c_void_p]),
+    "uccl_dedup_reset": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p]),
+    "uccl_set_launch_shape": (C.c_int, [C.c_int]),
+    "uccl_strerror": (C.c_char_p, [C.c_int]),
+    "uccl_last_error_detail": (C.c_char_p, []),
+    "uccl_version": (C.c_int, []),
+}
+
+
+def load(path: str = None):
+    """Load the built library (building it first only if no library file exists)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        if path is not None:
+            raise RuntimeError(f"{p} does not exist")
+        from .build import build
+        build()
+    lib = C.CDLL(p)
+    for name, (res, args) in _SIGNATURES.items():
+        fn = getattr(lib, name)  # AttributeError if the library does not export it
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _nbytes(x):
+    return 0 if x is None else x.numel() * x.element_size()
+
+
+def _stream(s):
+    if s is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    if isinstance(s, int):
+        return s
+    return s.cuda_stream
+
+
+def _check(code, what):
+    if code != UCCL_OK:
+        raise UcclError(code, what)
+
+
+def _extents(extents, acc, out_stage, recv_stage, n_bits):
+    if extents is not None:
+        return extents
+    if n_bits is None:
+        raise ValueError("n_bits is required when extents are derived from tensors")
+    return uccl_extents(_nbytes(acc), _nbytes(out_stage), _nbytes(recv_stage), int(n_bits))
+
+
+def uccl_chunk_apply(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, stream=None):
+    _check(load().uccl_chunk_apply(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
+                                   int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op),
+                                   _stream(stream)), "uccl_chunk_apply")
+
+
+def uccl_chunk_apply_checked(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op,
+                             extents=None, n_rejected=None, stream=None, n_bits=None):
+    """``extents`` is a uccl_extents; when None it is filled from the tensors' sizes and
+    ``n_bits`` (the bitmap's valid bit count)."""
+    e = _extents(extents, acc, out_stage, recv_stage, n_bits)
+    _check(load().uccl_chunk_apply_checked(_ptr(acc), _ptr(out_stage), _ptr(recv_stage),
+                                           _ptr(descs), int(n_descs), _ptr(dedup_bitmap),
+                                           int(dtype), int(op), C.byref(e), _ptr(n_rejected),
+                                           _stream(stream)), "uccl_chunk_apply_checked")
+
+
+def uccl_chunk_scatter(dst, recv_stage, descs, n_descs, dedup_bitmap, stream=None):
+    _check(load().uccl_chunk_scatter(_ptr(dst), _ptr(recv_stage), _ptr(descs), int(n_descs),
+                                     _ptr(dedup_bitmap), _stream(stream)), "uccl_chunk_scatter")
+
+
+def uccl_chunk_scatter_checked(dst, recv_stage, descs, n_descs, dedup_bitmap, extents=None,
+                               n_rejected=None, stream=None, n_bits=None):
+    e = _extents(extents, dst, None, recv_stage, n_bits)
+    _check(load().uccl_chunk_scatter_checked(_ptr(dst), _ptr(recv_stage), _ptr(descs),
+                                             int(n_descs), _ptr(dedup_bitmap), C.byref(e),
+                                             _ptr(n_rejected), _stream(stream)),
+           "uccl_chunk_scatter_checked")
+
+
+def uccl_dedup_reset(dedup_bitmap, n_bits, stream=None):
+    _check(load().uccl_dedup_reset(_ptr(dedup_bitmap), int(n_bits), _stream(stream)),
+           "uccl_dedup_reset")
+
+
+def uccl_set_launch_shape(shape):
+    _check(load().uccl_set_launch_shape(int(shape)), "uccl_set_launch_shape")
+
+
+def uccl_strerror(code) -> str:
+    return load().uccl_strerror(int(code)).decode()
+
+
+def uccl_version() -> int:
+    return load().uccl_version()

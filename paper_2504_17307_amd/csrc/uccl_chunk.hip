@@ -1,0 +1,473 @@
+// Receive-side chunk data path for multipath collectives, gfx950 (MI355X).
+//
+// One kernel does, per record of the arrival-ordered list the control path hands over
+// (paper Section 3.1 "challenge of reassembly", Section 5): dedup by sequence number,
+// place, combine with the tensor buffer (Section 2.1: "sum, max") or copy, write back,
+// and forward to the outbound staging buffer.  The paper's own kernel first copies
+// payloads into a transport buffer and then reduces; here the payload is read once,
+// straight from its arrival slot, which gives the same result with 2x chunk size fewer
+// bytes moved.
+//
+// Mapping onto the machine.  The work is a stream: at most one add per 4..8 bytes
+// moved, so HBM bandwidth bounds it and no matrix core is involved.  A workgroup takes
+// a tile of T consecutive records.  The lanes of its first wavefront each load one
+// 32-byte record with two 128-bit loads, validate it, and test-and-set its bit with one
+// device-scope atomic OR; the returned old word tells the lane whether it is the first
+// arrival.  A wave ballot compacts the winners into LDS.  After one barrier, subgroups of
+// SG threads take winners in turn and stream them with 128-bit loads and stores, U
+// independent vectors per thread in flight.  Duplicates cost their record and one
+// atomic, nothing else.  Two lanes holding the same seq each issue their own atomic, so
+// the hardware serialises them and exactly one sees the bit clear.
+#include <hip/hip_runtime.h>
+
+#include <stdint.h>
+#include <stdio.h>
+#include <string.h>
+
+#include "uccl_chunk.h"
+
+// Tunable compile-time shape constants (defaults chosen by measurement on MI355X).
+#ifndef UCCL_WAVE_TILE
+#define UCCL_WAVE_TILE 4      // records per 256-thread workgroup, one wavefront per chunk
+#endif
+#ifndef UCCL_WAVE_UNROLL
+#define UCCL_WAVE_UNROLL 8
+#endif
+#ifndef UCCL_WAVE_TILE_SMALL
+#define UCCL_WAVE_TILE_SMALL 16  // same shape, used when a call carries very many records
+#endif
+#ifndef UCCL_GROUP_TILE
+#define UCCL_GROUP_TILE 1     // records per workgroup, 256 threads per chunk
+#endif
+#ifndef UCCL_GROUP_UNROLL
+#define UCCL_GROUP_UNROLL 4
+#endif
+#ifndef UCCL_WIDE_TILE
+#define UCCL_WIDE_TILE 1      // records per workgroup, 1024 threads per chunk
+#endif
+#ifndef UCCL_WIDE_UNROLL
+#define UCCL_WIDE_UNROLL 2
+#endif
+#ifndef UCCL_AUTO_WIDE_BELOW
+#define UCCL_AUTO_WIDE_BELOW 512u      // fewer records than this: 1024 threads per chunk
+#endif
+#ifndef UCCL_AUTO_GROUP_BELOW
+#define UCCL_AUTO_GROUP_BELOW 16384u   // fewer than this: 256 threads per chunk
+#endif
+#ifndef UCCL_AUTO_SMALLTILE_FROM
+#define UCCL_AUTO_SMALLTILE_FROM 65536u // at least this many: wavefront per chunk, big tiles
+#endif
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct Extents {
+  uint64_t acc_bytes, out_bytes, recv_bytes, n_bits;
+};
+
+struct Args {
+  char* acc;
+  char* out;
+  const char* recv;
+  const uccl_chunk_desc* descs;
+  uint32_t* bitmap;
+  uint32_t* rejected;
+  Extents ext;
+  uint32_t n_descs;
+  uint32_t allow_forward;
+};
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __uint_as_float(u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __float_as_uint(f); }
+
+// binary32 -> bf16 bits, round to nearest even; a NaN keeps its top bits and is quieted.
+__device__ __forceinline__ uint32_t round_bf16(float s) {
+  const uint32_t u = as_u32(s);
+  uint32_t h = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) h = (u >> 16) | 0x0040u;
+  return h;
+}
+
+// Element operations.  word() combines one 32-bit word (one fp32, or two bf16 side by
+// side); half() one 16-bit element (bf16 tails).  a = tensor-buffer value, r = received.
+struct SumF32 {
+  static constexpr bool kReadsAcc = true;
+  static constexpr uint32_t kEs = 4;
+  static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
+    return as_u32(as_f32(a) + as_f32(r));
+  }
+};
+struct MaxF32 {
+  static constexpr bool kReadsAcc = true;
+  static constexpr uint32_t kEs = 4;
+  static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
+    return (as_f32(r) > as_f32(a)) ? r : a;
+  }
+};
+struct MinF32 {
+  static constexpr bool kReadsAcc = true;
+  static constexpr uint32_t kEs = 4;
+  static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
+    return (as_f32(r) < as_f32(a)) ? r : a;
+  }
+};
+struct SumBF16 {
+  static constexpr bool kReadsAcc = true;
+  static constexpr uint32_t kEs = 2;
+  static __device__ __forceinline__ uint32_t half(uint32_t a, uint32_t r) {
+    return round_bf16(as_f32(a << 16) + as_f32(r << 16));
+  }
+  static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
+    const uint32_t lo = round_bf16(as_f32(a << 16) + as_f32(r << 16));
+    const uint32_t hi = round_bf16(as_f32(a & 0xFFFF0000u) + as_f32(r & 0xFFFF0000u));
+    return lo | (hi << 16);
+  }
+};
+struct MaxBF16 {
+  static constexpr bool kReadsAcc = true;
+  static constexpr uint32_t kEs = 2;
+  static __device__ __forceinline__ uint32_t half(uint32_t a, uint32_t r) {
+    return (as_f32(r << 16) > as_f32(a << 16)) ? r : a;
+  }
+  static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
+    const uint32_t lo = (as_f32(r << 16) > as_f32(a << 16)) ? r : a;
+    const uint32_t hi = (as_f32(r & 0xFFFF0000u) > as_f32(a & 0xFFFF0000u)) ? r : a;
+    return (lo & 0xFFFFu) | (hi & 0xFFFF0000u);
+  }
+};
+struct MinBF16 {
+  static constexpr bool kReadsAcc = true;
+  static constexpr uint32_t kEs = 2;
+  static __device__ __forceinline__ uint32_t half(uint32_t a, uint32_t r) {
+    return (as_f32(r << 16) < as_f32(a << 16)) ? r : a;
+  }
+  static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
+    const uint32_t lo = (as_f32(r << 16) < as_f32(a << 16)) ? r : a;
+    const uint32_t hi = (as_f32(r & 0xFFFF0000u) < as_f32(a & 0xFFFF0000u)) ? r : a;
+    return (lo & 0xFFFFu) | (hi & 0xFFFF0000u);
+  }
+};
+struct Copy {
+  static constexpr bool kReadsAcc = false;
+  static constexpr uint32_t kEs = 1;
+  static __device__ __forceinline__ uint32_t word(uint32_t, uint32_t r) { return r; }
+};
+
+template <class Op>
+__device__ __forceinline__ u32x4 combine(u32x4 a, u32x4 r) {
+  u32x4 t;
+  t.x = Op::word(a.x, r.x);
+  t.y = Op::word(a.y, r.y);
+  t.z = Op::word(a.z, r.z);
+  t.w = Op::word(a.w, r.w);
+  return t;
+}
+
+__device__ __forceinline__ uint64_t wave_uniform(uint64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
+  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
+  return lo | (static_cast<uint64_t>(hi) << 32);
+}
+
+// Stream one chunk with SG cooperating threads: U independent 16-byte vectors per thread
+// per trip, loads first, then combine and store.  The receive slot is read once and the
+// staging copy written once, so both bypass cache retention (non-temporal).
+template <int SG, int U, class Op, bool FWD>
+__device__ __forceinline__ void stream_vectors(const u32x4* __restrict__ r, u32x4* __restrict__ a,
+                                               u32x4* __restrict__ o, uint32_t nvec,
+                                               uint32_t lane) {
+  constexpr uint32_t kTrip = SG * U;
+  const uint32_t full = nvec - nvec % kTrip;
+  for (uint32_t base = lane; base < full; base += kTrip) {
+    u32x4 rv[U], av[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) rv[u] = __builtin_nontemporal_load(r + base + u * SG);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if constexpr (Op::kReadsAcc) av[u] = a[base + u * SG];
+      else av[u] = rv[u];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const u32x4 t = combine<Op>(av[u], rv[u]);
+      a[base + u * SG] = t;
+      if (FWD) __builtin_nontemporal_store(t, o + base + u * SG);
+    }
+  }
+  for (uint32_t i = full + lane; i < nvec; i += SG) {
+    const u32x4 rv = __builtin_nontemporal_load(r + i);
+    u32x4 av = rv;
+    if constexpr (Op::kReadsAcc) av = a[i];
+    const u32x4 t = combine<Op>(av, rv);
+    a[i] = t;
+    if (FWD) __builtin_nontemporal_store(t, o + i);
+  }
+}
+
+// The last len % 16 bytes of a chunk, element by element.
+template <class Op, bool FWD>
+__device__ __forceinline__ void stream_tail(const char* r, char* a, char* o, uint32_t rem,
+                                            uint32_t lane) {
+  if constexpr (Op::kEs == 4) {
+    if (lane < rem / 4) {
+      uint32_t* ap = reinterpret_cast<uint32_t*>(a) + lane;
+      const uint32_t t = Op::word(*ap, reinterpret_cast<const uint32_t*>(r)[lane]);
+      *ap = t;
+      if (FWD) reinterpret_cast<uint32_t*>(o)[lane] = t;
+    }
+  } else if constexpr (Op::kEs == 2) {
+    if (lane < rem / 2) {
+      uint16_t* ap = reinterpret_cast<uint16_t*>(a) + lane;
+      const uint32_t t = Op::half(*ap, reinterpret_cast<const uint16_t*>(r)[lane]);
+      *ap = static_cast<uint16_t>(t);
+      if (FWD) reinterpret_cast<uint16_t*>(o)[lane] = static_cast<uint16_t>(t);
+    }
+  } else {
+    if (lane < rem) {
+      const char t = r[lane];
+      a[lane] = t;
+      if (FWD) o[lane] = t;
+    }
+  }
+}
+
+template <int SG, int U, class Op, bool FWD>
+__device__ __forceinline__ void stream_chunk(const char* r, char* a, char* o, uint32_t len,
+                                             uint32_t lane) {
+  const uint32_t nvec = len >> 4;
+  stream_vectors<SG, U, Op, FWD>(reinterpret_cast<const u32x4*>(r), reinterpret_cast<u32x4*>(a),
+                                 reinterpret_cast<u32x4*>(o), nvec, lane);
+  const uint32_t rem = len & 15u;
+  if (rem) {
+    const uint64_t off = static_cast<uint64_t>(nvec) << 4;
+    stream_tail<Op, FWD>(r + off, a + off, FWD ? o + off : o, rem, lane);
+  }
+}
+
+template <int NT, int T, int SG, int U, class Op>
+__global__ void __launch_bounds__(NT) chunk_apply_kernel(const Args g) {
+  static_assert(T >= 1 && T <= 64, "one wavefront dedups the tile");
+  static_assert(NT % SG == 0 && SG % 64 == 0, "subgroups are whole wavefronts");
+  constexpr uint32_t kSubgroups = NT / SG;
+  __shared__ uint64_t s_src[T], s_dst[T], s_out[T];
+  __shared__ uint32_t s_len[T];
+  __shared__ uint32_t s_count;
+
+  const uint32_t tid = threadIdx.x;
+  if (tid < 64) {
+    const uint64_t k = static_cast<uint64_t>(blockIdx.x) * T + tid;
+    bool win = false;
+    uint64_t src = 0, dst = 0, out = 0;
+    uint32_t len = 0;
+    if (tid < T && k < g.n_descs) {
+      const u32x4* p = reinterpret_cast<const u32x4*>(g.descs + k);
+      const u32x4 lo = p[0], hi = p[1];
+      src = lo.x | (static_cast<uint64_t>(lo.y) << 32);
+      dst = lo.z | (static_cast<uint64_t>(lo.w) << 32);
+      out = hi.x | (static_cast<uint64_t>(hi.y) << 32);
+      len = hi.z;
+      const uint32_t seq = hi.w;
+      const bool fwd = out != UCCL_NO_FORWARD;
+      bool ok = seq < g.ext.n_bits && ((src | dst) & 15u) == 0 && len % Op::kEs == 0 &&
+                src <= g.ext.recv_bytes && len <= g.ext.recv_bytes - src &&
+                dst <= g.ext.acc_bytes && len <= g.ext.acc_bytes - dst;
+      if (fwd)
+        ok = ok && g.allow_forward && g.out != nullptr && (out & 15u) == 0 &&
+             out <= g.ext.out_bytes && len <= g.ext.out_bytes - out;
+      if (ok) {
+        const uint32_t bit = 1u << (seq & 31u);
+        const uint32_t old = atomicOr(g.bitmap + (seq >> 5), bit);  // device scope, relaxed
+        win = (old & bit) == 0;
+      } else if (g.rejected != nullptr) {
+        atomicAdd(g.rejected, 1u);
+      }
+    }
+    const uint64_t winners = __ballot(win);
+    if (win) {
+      const uint32_t pos = __popcll(winners & ((1ull << tid) - 1ull));
+      s_src[pos] = src;
+      s_dst[pos] = dst;
+      s_out[pos] = out;
+      s_len[pos] = len;
+    }
+    if (tid == 0) s_count = __popcll(winners);
+  }
+  __syncthreads();
+
+  const uint32_t count = s_count;
+  const uint32_t sg = tid / SG, lane = tid % SG;
+  for (uint32_t w = sg; w < count; w += kSubgroups) {
+    const uint64_t src = wave_uniform(s_src[w]);
+    const uint64_t dst = wave_uniform(s_dst[w]);
+    const uint64_t out = wave_uniform(s_out[w]);
+    const uint32_t len = __builtin_amdgcn_readfirstlane(s_len[w]);
+    if (out != UCCL_NO_FORWARD)
+      stream_chunk<SG, U, Op, true>(g.recv + src, g.acc + dst, g.out + out, len, lane);
+    else
+      stream_chunk<SG, U, Op, false>(g.recv + src, g.acc + dst, nullptr, len, lane);
+  }
+}
+
+__global__ void __launch_bounds__(256) fill_words_kernel(uint32_t* p, uint64_t n, uint32_t v) {
+  for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x; i < n;
+       i += static_cast<uint64_t>(gridDim.x) * 256)
+    p[i] = v;
+}
+
+// ---- host side ----------------------------------------------------------------------
+
+thread_local char t_detail[256] = "";
+int g_shape = UCCL_SHAPE_AUTO;
+
+int launch_failed(hipError_t e) {
+  snprintf(t_detail, sizeof(t_detail), "%s: %s", hipGetErrorName(e), hipGetErrorString(e));
+  return UCCL_ELAUNCH;
+}
+
+template <int NT, int T, int SG, int U, class Op>
+int launch(const Args& a, hipStream_t s) {
+  const uint32_t tiles = (a.n_descs + T - 1) / T;
+  hipLaunchKernelGGL((chunk_apply_kernel<NT, T, SG, U, Op>), dim3(tiles), dim3(NT), 0, s, a);
+  const hipError_t e = hipGetLastError();
+  return e == hipSuccess ? UCCL_OK : launch_failed(e);
+}
+
+template <class Op>
+int launch_shape(const Args& a, hipStream_t s) {
+  int shape = g_shape;
+  bool big_tiles = a.n_descs >= UCCL_AUTO_SMALLTILE_FROM;
+  if (shape == UCCL_SHAPE_AUTO) {
+    if (a.n_descs < UCCL_AUTO_WIDE_BELOW) shape = UCCL_SHAPE_WIDE;
+    else if (a.n_descs < UCCL_AUTO_GROUP_BELOW) shape = UCCL_SHAPE_GROUP;
+    else shape = UCCL_SHAPE_WAVE;
+  }
+  switch (shape) {
+    case UCCL_SHAPE_WAVE:
+      if (big_tiles) return launch<256, UCCL_WAVE_TILE_SMALL, 64, UCCL_WAVE_UNROLL, Op>(a, s);
+      return launch<256, UCCL_WAVE_TILE, 64, UCCL_WAVE_UNROLL, Op>(a, s);
+    case UCCL_SHAPE_GROUP:
+      return launch<256, UCCL_GROUP_TILE, 256, UCCL_GROUP_UNROLL, Op>(a, s);
+    case UCCL_SHAPE_WIDE:
+      return launch<1024, UCCL_WIDE_TILE, 1024, UCCL_WIDE_UNROLL, Op>(a, s);
+    default:
+      return UCCL_EINVAL;
+  }
+}
+
+bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
+
+bool overlaps(const void* p, uint64_t pn, const void* q, uint64_t qn) {
+  if (!p || !q || pn == 0 || qn == 0) return false;
+  const uintptr_t a = reinterpret_cast<uintptr_t>(p), b = reinterpret_cast<uintptr_t>(q);
+  return a < b + qn && b < a + pn;
+}
+
+int apply_common(void* acc, void* out_stage, const void* recv_stage, const uccl_chunk_desc* descs,
+                 uint32_t n_descs, uint32_t* bitmap, int dtype, int op, bool allow_forward,
+                 const uccl_extents* ext, uint32_t* n_rejected, void* stream) {
+  if (dtype != UCCL_F32 && dtype != UCCL_BF16) return UCCL_EINVAL;
+  if (op < UCCL_SUM || op > UCCL_COPY) return UCCL_EINVAL;
+  if (n_descs == 0) return UCCL_OK;
+  if (!acc || !recv_stage || !descs || !bitmap) return UCCL_EINVAL;
+  if (misaligned(acc, 16) || misaligned(out_stage, 16) || misaligned(recv_stage, 16) ||
+      misaligned(descs, 16) || misaligned(bitmap, 4) || misaligned(n_rejected, 4))
+    return UCCL_EALIGN;
+  Args a;
+  a.acc = static_cast<char*>(acc);
+  a.out = static_cast<char*>(out_stage);
+  a.recv = static_cast<const char*>(recv_stage);
+  a.descs = descs;
+  a.bitmap = bitmap;
+  a.rejected = n_rejected;
+  a.n_descs = n_descs;
+  a.allow_forward = allow_forward ? 1u : 0u;
+  if (ext) {
+    if (overlaps(recv_stage, ext->recv_bytes, acc, ext->acc_bytes) ||
+        overlaps(recv_stage, ext->recv_bytes, out_stage, ext->out_bytes) ||
+        overlaps(acc, ext->acc_bytes, out_stage, ext->out_bytes))
+      return UCCL_EINVAL;
+    a.ext = Extents{ext->acc_bytes, out_stage ? ext->out_bytes : 0, ext->recv_bytes, ext->n_bits};
+  } else {
+    a.ext = Extents{UINT64_MAX, UINT64_MAX, UINT64_MAX, UINT64_MAX};
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (op == UCCL_COPY) return launch_shape<Copy>(a, s);
+  if (dtype == UCCL_F32) {
+    if (op == UCCL_SUM) return launch_shape<SumF32>(a, s);
+    if (op == UCCL_MAX) return launch_shape<MaxF32>(a, s);
+    return launch_shape<MinF32>(a, s);
+  }
+  if (op == UCCL_SUM) return launch_shape<SumBF16>(a, s);
+  if (op == UCCL_MAX) return launch_shape<MaxBF16>(a, s);
+  return launch_shape<MinBF16>(a, s);
+}
+
+}  // namespace
+
+extern "C" {
+
+int uccl_chunk_apply(void* acc, void* out_stage, const void* recv_stage,
+                     const uccl_chunk_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
+                     uccl_dtype dtype, uccl_op op, void* stream) {
+  return apply_common(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, true,
+                      nullptr, nullptr, stream);
+}
+
+int uccl_chunk_apply_checked(void* acc, void* out_stage, const void* recv_stage,
+                             const uccl_chunk_desc* descs, uint32_t n_descs,
+                             uint32_t* dedup_bitmap, uccl_dtype dtype, uccl_op op,
+                             const uccl_extents* extents, uint32_t* n_rejected, void* stream) {
+  if (!extents) return UCCL_EINVAL;
+  return apply_common(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, true,
+                      extents, n_rejected, stream);
+}
+
+int uccl_chunk_scatter(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,
+                       uint32_t n_descs, uint32_t* dedup_bitmap, void* stream) {
+  return apply_common(dst, nullptr, recv_stage, descs, n_descs, dedup_bitmap, UCCL_BF16, UCCL_COPY,
+                      false, nullptr, nullptr, stream);
+}
+
+int uccl_chunk_scatter_checked(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,
+                               uint32_t n_descs, uint32_t* dedup_bitmap,
+                               const uccl_extents* extents, uint32_t* n_rejected, void* stream) {
+  if (!extents) return UCCL_EINVAL;
+  return apply_common(dst, nullptr, recv_stage, descs, n_descs, dedup_bitmap, UCCL_BF16, UCCL_COPY,
+                      false, extents, n_rejected, stream);
+}
+
+int uccl_dedup_reset(uint32_t* dedup_bitmap, uint64_t n_bits, void* stream) {
+  if (n_bits == 0) return UCCL_OK;
+  if (!dedup_bitmap) return UCCL_EINVAL;
+  if (misaligned(dedup_bitmap, 4)) return UCCL_EALIGN;
+  const uint64_t words = (n_bits + 31) / 32;
+  const uint64_t blocks = (words + 255) / 256;
+  const uint32_t grid = static_cast<uint32_t>(blocks < 4096 ? blocks : 4096);
+  hipLaunchKernelGGL(fill_words_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
+                     dedup_bitmap, words, 0u);
+  const hipError_t e = hipGetLastError();
+  return e == hipSuccess ? UCCL_OK : launch_failed(e);
+}
+
+int uccl_set_launch_shape(int shape) {
+  if (shape < UCCL_SHAPE_AUTO || shape > UCCL_SHAPE_WIDE) return UCCL_EINVAL;
+  g_shape = shape;
+  return UCCL_OK;
+}
+
+const char* uccl_strerror(int code) {
+  switch (code) {
+    case UCCL_OK: return "ok";
+    case UCCL_EINVAL: return "invalid argument";
+    case UCCL_EALIGN: return "misaligned pointer";
+    case UCCL_ELAUNCH: return "HIP launch failed";
+    default: return "unknown error code";
+  }
+}
+
+const char* uccl_last_error_detail(void) { return t_detail; }
+
+int uccl_version(void) { return UCCL_CHUNK_VERSION; }
+
+}  // extern "C"

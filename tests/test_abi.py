@@ -1,0 +1,93 @@
+"""The C-ABI library: loads without a GPU, exports what the header declares, and its
+host-side argument checks return the documented codes before anything is enqueued."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2504_17307_amd as pkg
+
+
+def declared_functions():
+    text = open(pkg.HEADER_PATH).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(uccl_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pkg.load()
+    names = declared_functions()
+    assert {"uccl_chunk_apply", "uccl_chunk_scatter", "uccl_dedup_reset", "uccl_strerror",
+            "uccl_version", "uccl_chunk_apply_checked", "uccl_chunk_scatter_checked",
+            "uccl_set_launch_shape", "uccl_last_error_detail"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(names) == set(pkg._SIGNATURES), "binding and header list the same entry points"
+    assert lib.uccl_version() == 1
+
+
+def test_record_layout_matches_generators():
+    from synth.layout import DESC, NO_FORWARD
+    assert DESC.itemsize == pkg.DESC_BYTES == 32
+    assert [DESC.fields[n][1] for n in ("src_off", "dst_off", "out_off", "len", "seq")] == [0, 8, 16, 24, 28]
+    assert int(NO_FORWARD) == pkg.UCCL_NO_FORWARD
+    text = open(pkg.HEADER_PATH).read()
+    order = [text.index(f" {n};") for n in ("src_off", "dst_off", "out_off", "len", "seq")]
+    assert order == sorted(order)
+
+
+def test_host_side_error_codes_enqueue_nothing():
+    lib = pkg.load()
+    A, B, D, M = 0x10000, 0x20000, 0x30000, 0x40000  # never dereferenced: every call fails on the host
+    f = lib.uccl_chunk_apply
+    assert f(None, None, B, D, 1, M, 0, 0, None) == pkg.UCCL_EINVAL
+    assert f(A, None, None, D, 1, M, 0, 0, None) == pkg.UCCL_EINVAL
+    assert f(A, None, B, None, 1, M, 0, 0, None) == pkg.UCCL_EINVAL
+    assert f(A, None, B, D, 1, None, 0, 0, None) == pkg.UCCL_EINVAL
+    assert f(A, None, B, D, 1, M, 2, 0, None) == pkg.UCCL_EINVAL   # dtype
+    assert f(A, None, B, D, 1, M, 0, 4, None) == pkg.UCCL_EINVAL   # op
+    assert f(A, None, B, D, 1, M, 0, -1, None) == pkg.UCCL_EINVAL
+    assert f(A + 8, None, B, D, 1, M, 0, 0, None) == pkg.UCCL_EALIGN
+    assert f(A, A + 4, B, D, 1, M, 0, 0, None) == pkg.UCCL_EALIGN
+    assert f(A, None, B + 2, D, 1, M, 0, 0, None) == pkg.UCCL_EALIGN
+    assert f(A, None, B, D + 8, 1, M, 0, 0, None) == pkg.UCCL_EALIGN
+    assert f(A, None, B, D, 1, M + 2, 0, 0, None) == pkg.UCCL_EALIGN
+    assert f(None, None, None, None, 0, None, 0, 0, None) == pkg.UCCL_OK  # empty call is a no-op
+    g = lib.uccl_chunk_apply_checked
+    assert g(A, None, B, D, 1, M, 0, 0, None, None, None) == pkg.UCCL_EINVAL  # extents required
+    e = pkg.uccl_extents(0x20000, 0, 0x1000, 8)  # acc extent runs into recv_stage
+    assert g(A, None, B, D, 1, M, 0, 0, C.byref(e), None, None) == pkg.UCCL_EINVAL
+    e = pkg.uccl_extents(0x1000, 0, 0x1000, 8)
+    assert g(A, None, B, D, 1, M, 0, 0, C.byref(e), 0x50002, None) == pkg.UCCL_EALIGN
+    s = lib.uccl_chunk_scatter
+    assert s(None, B, D, 1, M, None) == pkg.UCCL_EINVAL
+    assert s(A + 1, B, D, 1, M, None) == pkg.UCCL_EALIGN
+    assert s(None, None, None, 0, None, None) == pkg.UCCL_OK
+    assert lib.uccl_chunk_scatter_checked(A, B, D, 1, M, None, None, None) == pkg.UCCL_EINVAL
+    r = lib.uccl_dedup_reset
+    assert r(None, 8, None) == pkg.UCCL_EINVAL and r(M + 1, 8, None) == pkg.UCCL_EALIGN
+    assert r(None, 0, None) == pkg.UCCL_OK
+    assert lib.uccl_set_launch_shape(9) == pkg.UCCL_EINVAL and lib.uccl_set_launch_shape(0) == pkg.UCCL_OK
+    assert pkg.uccl_strerror(pkg.UCCL_EALIGN) == "misaligned pointer"
+    with pytest.raises(pkg.UcclError) as err:
+        pkg.uccl_chunk_apply(None, None, B, D, 1, M, 0, 0, stream=0)
+    assert err.value.code == pkg.UCCL_EINVAL
+
+
+def test_no_cpu_fallback_when_library_missing():
+    with pytest.raises(RuntimeError):
+        pkg.load(os.path.join(os.path.dirname(pkg.LIB_PATH), "no_such_library.so"))
+
+
+def test_product_never_touches_the_oracle():
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for d, _, files in os.walk(os.path.join(root, "paper_2504_17307_amd")):
+        for fn in files:
+            if fn.endswith((".py", ".hip", ".h", ".cpp")):
+                src = open(os.path.join(d, fn)).read()
+                assert "oracle" not in src.replace("no CPU fallback", ""), fn
+    for fn in os.listdir(os.path.join(root, "oracle")):
+        if fn.endswith((".py", ".c", ".h")):
+            src = open(os.path.join(root, "oracle", fn)).read()
+            assert "paper_2504_17307_amd" not in src and "uccl_chunk.h" not in src, fn

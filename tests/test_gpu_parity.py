@@ -1,0 +1,434 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs, element by element.  Integer, placement, dedup and copy results must be
+bit-exact; fp32 combine 0 ulp; bf16 SUM is allowed 1 ulp by the stated target but is
+asserted bit-exact here because both sides round fp32 -> bf16 once, to nearest even.
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import payload as pl
+from synth import workloads as wl
+from synth.layout import DESC, NO_FORWARD, F32, BF16, SUM, MAX, MIN, COPY, ELEM_SIZE
+
+from gpuhelp import DeviceRun, oracle_results, assert_same, to_dev, to_host
+from ringloop import closed_loop_allreduce
+
+pytestmark = pytest.mark.gpu
+
+SHAPES = [0, 1, 2, 3]  # AUTO, WAVE, GROUP, WIDE
+
+
+def say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def check_workload(pkg, w, shape=0, checked=True, split=None):
+    pkg.uccl_set_launch_shape(shape)
+    try:
+        run = DeviceRun(w)
+        run.run_phases(checked=checked, split=split)
+        acc, out, bm, rej = run.results()
+    finally:
+        pkg.uccl_set_launch_shape(0)
+    eacc, eout, ebm = oracle_results(w)
+    assert rej == 0
+    assert_same(bm, ebm, "bitmap")
+    assert_same(acc, eacc, "acc")
+    if eout is not None:
+        assert_same(out, eout, "out_stage")
+
+
+# ---- the five recipes at sizes the oracle finishes in seconds, every launch shape ------
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_config1_full_size(gpu_lib, shape):
+    say("config1 full size shape", shape)
+    check_workload(gpu_lib, wl.config1(seed=1), shape)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("seed", [1, 2])
+def test_config2_recipe_reduced(gpu_lib, shape, seed):
+    say("config2 16 MiB shape", shape, "seed", seed)
+    check_workload(gpu_lib, wl.config2(seed=seed, M=16 << 20), shape)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_config3_recipe_reduced(gpu_lib, shape):
+    say("config3 32 MiB shape", shape)
+    check_workload(gpu_lib, wl.config3(seed=3, M=32 << 20), shape)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_config4_recipe_reduced(gpu_lib, shape):
+    say("config4 max 2 MiB per source shape", shape)
+    w = wl.config4(seed=2, max_bytes=2 << 20)
+    gpu_lib.uccl_set_launch_shape(shape)
+    try:
+        dst = torch.full((w.acc.nbytes + 512,), 0xEE, dtype=torch.uint8, device="cuda")
+        recv = to_dev(w.recv_stage)
+        d = to_dev(w.phases[0].descs)
+        bm = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
+        rej = torch.zeros(1, dtype=torch.int32, device="cuda")
+        gpu_lib.uccl_chunk_scatter_checked(dst[256:256 + w.acc.nbytes], recv, d, len(w.phases[0].descs), bm,
+                                           n_rejected=rej, n_bits=w.n_bits)
+        torch.cuda.synchronize()
+    finally:
+        gpu_lib.uccl_set_launch_shape(0)
+    got = dst.cpu().numpy()
+    edst = np.zeros(w.acc.nbytes, dtype=np.uint8)
+    seen = oracle.new_seen(w.n_bits)
+    oracle.scatter(edst, w.recv_stage, w.phases[0].descs, seen)
+    assert rej.item() == 0
+    assert_same(got[256:256 + w.acc.nbytes], edst, "dst")
+    assert_same(got[256:256 + w.acc.nbytes], np.concatenate(w.extra["sources"]), "dst vs sources")
+    assert np.all(got[:256] == 0xEE) and np.all(got[256 + w.acc.nbytes:] == 0xEE)
+    assert_same(bm.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap")
+
+
+def test_config5_recipe_batched_and_per_message(gpu_lib):
+    """Small-message regime: 60 messages, applied (a) one message per pair of calls and
+    (b) many messages per call; both must equal the oracle applied message by message."""
+    w, msgs = wl.config5(seed=4, n_msgs=60)
+    eacc = w.acc.copy()
+    eout = np.full(w.out_bytes, 0xA5, dtype=np.uint8)
+    seen = oracle.new_seen(w.n_bits)
+    for m in msgs:
+        oracle.apply(eacc, eout, w.recv_stage, m["rs"], seen, F32, SUM)
+        oracle.apply(eacc, eout, w.recv_stage, m["ag"], seen, F32, COPY)
+    ebm = oracle.pack_bitmap(seen)
+    for mode in ("per-message", "batched"):
+        say("config5", mode)
+        run = DeviceRun(w)
+        if mode == "per-message":
+            for m in msgs:
+                run.apply(to_dev(m["rs"]), len(m["rs"]), SUM)
+                run.apply(to_dev(m["ag"]), len(m["ag"]), COPY)
+        else:
+            for lo in range(0, len(msgs), 25):
+                rs = np.concatenate([m["rs"] for m in msgs[lo:lo + 25]])
+                ag = np.concatenate([m["ag"] for m in msgs[lo:lo + 25]])
+                run.apply(to_dev(rs), len(rs), SUM)
+                run.apply(to_dev(ag), len(ag), COPY)
+        torch.cuda.synchronize()
+        acc, out, bm, rej = run.results()
+        assert rej == 0
+        assert_same(bm, ebm, "bitmap")
+        assert_same(acc, eacc, "acc")
+        assert_same(out, eout, "out")
+
+
+# ---- ops, dtypes, ragged tails, odd lengths ------------------------------------------
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("op", [SUM, MAX, MIN, COPY])
+def test_ops_dtypes_ragged(gpu_lib, shape, dtype, op):
+    say("ops ragged", shape, dtype, op)
+    C = 20000 - 20000 % 16 + 16  # 20000: many 16-byte vectors plus trips that do not divide evenly
+    dist = "uniform" if dtype == F32 else "normal"
+    w = wl.ring_share("ragged", 11, R=4, M=4 * (5 * C + 4112), C=C, dtype=dtype, paths=7, window=9,
+                      dup=0.15, dist=dist, op=op, allgather=True)
+    check_workload(gpu_lib, w, shape)
+
+
+def _records(rows):
+    d = np.zeros(len(rows), dtype=DESC)
+    for k, r in enumerate(rows):
+        d[k] = r
+    return d
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("dtype,op", [(F32, SUM), (BF16, SUM), (BF16, MAX), (F32, COPY), (BF16, COPY)])
+def test_lengths_not_multiple_of_16(gpu_lib, shape, dtype, op):
+    """len is any multiple of the element size, including 0."""
+    es = ELEM_SIZE[dtype]
+    lens = [0, es, 2 * es, 16 - es, 16, 16 + es, 48 - es, 1024 + 3 * es, 4096 + 16 - es, 9 * 1024 + es, 70000 + es]
+    slot = 70016 + 64
+    rows, n = [], len(lens)
+    for k, ln in enumerate(lens):
+        rows.append((k * slot, ((n - 1 - k) * slot), k * slot if k % 2 else NO_FORWARD, ln, k))
+    rows.append((n * slot, (n - 1 - 3) * slot, 3 * slot, lens[3], 3))  # a duplicate of record 3
+    d = _records(rows)
+    g = pl.rng(5, shape)
+    nel = (n + 1) * slot // ELEM_SIZE[dtype]
+    if dtype == F32:
+        acc0, recv = pl.uniform_f32(5, 1, nel), pl.uniform_f32(5, 2, nel)
+    else:
+        acc0, recv = pl.normal_bf16(5, 1, nel), pl.normal_bf16(5, 2, nel)
+    recv.view(np.uint8)[n * slot:n * slot + lens[3]] = recv.view(np.uint8)[3 * slot:3 * slot + lens[3]]
+    w = wl.Workload("odd", dtype, acc0, recv, (n + 1) * slot, n, [wl.Phase("p", op, d, n, sum(lens), 0)])
+    check_workload(gpu_lib, w, shape)
+    check_workload(gpu_lib, w, shape, checked=False)
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_scatter_any_byte_length(gpu_lib, shape):
+    """The all-to-all scatter is a byte copy: any length, including odd ones."""
+    lens = [0, 1, 2, 3, 15, 16, 17, 31, 33, 1000, 4097, 65535, 70001]
+    slot = 70016
+    n = len(lens)
+    d = _records([(k * slot, (n - 1 - k) * slot, NO_FORWARD, ln, k) for k, ln in enumerate(lens)]
+                 + [((n + j) * slot, (n - 1 - 12) * slot, NO_FORWARD, lens[12], 12) for j in range(3)])
+    recv = pl.rng(7, 7).integers(0, 256, (n + 3) * slot).astype(np.uint8)
+    for j in range(3):
+        recv[(n + j) * slot:(n + j) * slot + lens[12]] = recv[12 * slot:12 * slot + lens[12]]
+    dst0 = np.full(n * slot, 0x5C, dtype=np.uint8)
+    gpu_lib.uccl_set_launch_shape(shape)
+    try:
+        dst = to_dev(dst0)
+        bm = torch.zeros(1, dtype=torch.int32, device="cuda")
+        for checked in (True, False):
+            if checked:
+                gpu_lib.uccl_chunk_scatter_checked(dst, to_dev(recv), to_dev(d), len(d), bm, n_bits=n)
+            else:
+                gpu_lib.uccl_chunk_scatter(dst, to_dev(recv), to_dev(d), len(d), bm)
+            torch.cuda.synchronize()
+            edst = dst0.copy()
+            seen = oracle.new_seen(n)
+            assert oracle.scatter(edst, recv, d, seen) == n
+            assert_same(dst.cpu().numpy(), edst, "dst")
+            assert_same(bm.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap")
+            dst = to_dev(dst0)
+            bm.zero_()
+    finally:
+        gpu_lib.uccl_set_launch_shape(0)
+
+
+def test_empty_call_and_all_duplicates(gpu_lib):
+    w = wl.ring_share("e", 1, R=2, M=2 * 4096, C=1024, dtype=F32, paths=2, window=None, dup=0.5,
+                      dist="uniform", allgather=False)
+    run = DeviceRun(w)
+    run.apply(run.descs[0], 0, SUM)
+    torch.cuda.synchronize()
+    acc, out, bm, _ = run.results()
+    assert_same(acc, w.acc, "acc after empty call")
+    assert not bm.any()
+    run.run_phases()
+    first = run.results()
+    run.run_phases()  # the same records again: every one is now a duplicate
+    again = run.results()
+    for a, b in zip(first[:3], again[:3]):
+        assert_same(a, b, "second pass changes nothing")
+    eacc, eout, ebm = oracle_results(w)
+    assert_same(first[0], eacc, "acc")
+    # after a reset the records apply again (SUM adds the payload a second time)
+    run.reset()
+    run.run_phases()
+    acc2 = run.results()[0]
+    seen = oracle.new_seen(w.n_bits)
+    oracle.apply(eacc, eout, w.recv_stage, w.phases[0].descs, seen, F32, SUM)
+    assert_same(acc2, eacc, "acc after reset + reapply")
+
+
+# ---- exactly-once under concurrency ---------------------------------------------------
+
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_exactly_once_many_copies_everywhere(gpu_lib, shape, dtype):
+    """Payload all ones, acc zero, SUM; every seq is repeated many times: adjacent records
+    (same wavefront, same bitmap word), far apart (different workgroups), and across two
+    calls.  A double apply shows as 2, a lost chunk as 0."""
+    es = ELEM_SIZE[dtype]
+    C, n = 4096, 96
+    g = pl.rng(21, shape)
+    arr = np.concatenate([np.repeat(np.arange(n), 3), np.arange(n), g.integers(0, n, 700), np.repeat(np.arange(8), 40)])
+    arr = np.concatenate([arr[:300], g.permutation(arr[300:])])
+    d = np.zeros(len(arr), dtype=DESC)
+    d["src_off"] = np.arange(len(arr), dtype=np.uint64) * C
+    d["dst_off"] = arr.astype(np.uint64) * C
+    d["out_off"] = arr.astype(np.uint64) * C
+    d["len"] = C
+    d["seq"] = arr
+    one = pl.ints_as(np.ones(1, dtype=np.int64), dtype)[0]
+    recv = np.full(len(arr) * C // es, one, dtype=pl.np_dtype(dtype))
+    acc0 = np.zeros(n * C // es, dtype=pl.np_dtype(dtype))
+    w = wl.Workload("once", dtype, acc0, recv, n * C, n, [wl.Phase("p", SUM, d, n, n * C, 0)])
+    gpu_lib.uccl_set_launch_shape(shape)
+    try:
+        run = DeviceRun(w)
+        run.run_phases(split=lambda m: [m // 3, m // 2])
+        acc, out, bm, rej = run.results()
+    finally:
+        gpu_lib.uccl_set_launch_shape(0)
+    assert rej == 0
+    assert np.all(acc == one), f"{np.count_nonzero(acc != one)} elements are not exactly 1"
+    assert np.array_equal(out.view(acc.dtype), acc)
+    assert sum(bin(int(x)).count("1") for x in bm) == n
+
+
+@pytest.mark.parametrize("shape", [1, 2])
+def test_split_calls_equal_single_call(gpu_lib, shape):
+    w = wl.config2(seed=5, M=8 << 20)
+    g = pl.rng(6, 6)
+    check_workload(gpu_lib, w, shape, split=lambda m: sorted(g.choice(np.arange(1, m), 5, replace=False).tolist()))
+
+
+def test_missing_chunk_leaves_hole(gpu_lib):
+    w = wl.config1(seed=2)
+    lost = int(w.extra["logical"][0][9]["seq"])
+    ph = w.phases[0]
+    ph.descs = ph.descs[ph.descs["seq"] != lost]
+    check_workload(gpu_lib, w)
+    run = DeviceRun(w)
+    run.run_phases()
+    bm = run.results()[2]
+    assert not (bm[lost >> 5] >> (lost & 31)) & 1
+
+
+# ---- checked entry point -----------------------------------------------------------------
+
+def test_checked_rejects_bad_records_and_moves_nothing(gpu_lib):
+    n_bits, C = 8, 256
+    acc0 = pl.uniform_f32(1, 1, 4 * C // 4)
+    recv = pl.uniform_f32(1, 2, 8 * C // 4)
+    good = (0, 0, 0, C, 0)
+    bad = [
+        (C, C, NO_FORWARD, C, 8),            # seq out of range
+        (C + 4, C, NO_FORWARD, C, 1),        # misaligned source
+        (C, C + 8, NO_FORWARD, C, 1),        # misaligned destination
+        (C, C, 8, C, 1),                     # misaligned forward
+        (C, C, NO_FORWARD, C - 2, 1),        # len not a multiple of 4
+        (8 * C - 16, C, NO_FORWARD, C, 1),   # source runs past recv_stage
+        (C, 4 * C - 16, NO_FORWARD, C, 1),   # destination runs past acc
+        (C, C, 2 * C - 16, C, 1),            # forward runs past out_stage
+        (1 << 62, C, NO_FORWARD, C, 1),      # absurd offsets
+        (C, (1 << 64) - 16, NO_FORWARD, 32, 1),
+    ]
+    d = _records([good] + bad + [(2 * C, 2 * C, C, C, 2)])
+    w = wl.Workload("bad", F32, acc0, recv, 2 * C, n_bits, [wl.Phase("p", SUM, d, 2, 2 * C, 0)])
+    for shape in SHAPES:
+        gpu_lib.uccl_set_launch_shape(shape)
+        run = DeviceRun(w)
+        run.run_phases()
+        acc, out, bm, rej = run.results()
+        gpu_lib.uccl_set_launch_shape(0)
+        assert rej == len(bad)
+        assert bm[0] == 0b101
+        exp = acc0.copy()
+        exp[:C // 4] += recv[:C // 4]
+        exp[2 * C // 4:3 * C // 4] += recv[2 * C // 4:3 * C // 4]
+        assert_same(acc, exp, "acc")
+        assert_same(out.view(np.float32), np.concatenate([exp[:C // 4], exp[2 * C // 4:3 * C // 4]]), "out")
+    # a forward with no staging buffer is rejected, not dereferenced; scatter rejects forwards
+    run = DeviceRun(wl.Workload("nofwd", F32, acc0, recv, 0, n_bits, [wl.Phase("p", SUM, _records([good]), 1, C, 0)]))
+    run.run_phases()
+    acc, _, bm, rej = run.results()
+    assert rej == 1 and bm[0] == 0
+    assert_same(acc, acc0, "acc untouched")
+    dst = to_dev(acc0)
+    bmt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    rejt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    gpu_lib.uccl_chunk_scatter_checked(dst, to_dev(recv), to_dev(_records([good])), 1, bmt, n_rejected=rejt, n_bits=8)
+    torch.cuda.synchronize()
+    assert rejt.item() == 1 and bmt.item() == 0
+    assert_same(to_host(dst, np.float32), acc0, "dst untouched")
+
+
+# ---- numerics special values ---------------------------------------------------------------
+
+def test_special_values_bit_exact(gpu_lib):
+    """Subnormals are kept, infinities propagate, +0 + -0 = +0, MAX/MIN tie rule; NaN results
+    are compared as NaN-ness only (NaN payloads are not fixed by the method)."""
+    f = np.array([0, 0x80000000, 1, 2, 0x007FFFFF, 0x00800000, 0x807FFFFF, 0x3F800000, 0xBF800000,
+                  0x7F7FFFFF, 0xFF7FFFFF, 0x7F800000, 0xFF800000, 0x33800000, 0x00000003], dtype=np.uint32)
+    a32 = np.repeat(f, len(f)).view(np.float32)
+    r32 = np.tile(f, len(f)).view(np.float32)
+    h = np.array([0, 0x8000, 1, 2, 0x007F, 0x0080, 0x807F, 0x3F80, 0xBF80, 0x7F7F, 0xFF7F, 0x7F80, 0xFF80,
+                  0x3B80, 0x3F81, 0x3B81, 0x3B7F, 0x7B00], dtype=np.uint16)
+    a16, r16 = np.repeat(h, len(h)), np.tile(h, len(h))
+    for dtype, a, r in ((F32, a32, r32), (BF16, a16, r16)):
+        es = ELEM_SIZE[dtype]
+        n = len(a)
+        pad = (-n * es) % 16
+        nb = n * es + pad
+        accp = np.zeros(nb // es, dtype=a.dtype); accp[:n] = a
+        recvp = np.zeros(nb // es, dtype=a.dtype); recvp[:n] = r
+        for op in (SUM, MAX, MIN):
+            d = _records([(0, 0, 0, n * es, 0)])
+            w = wl.Workload("sv", dtype, accp, recvp, nb, 1, [wl.Phase("p", op, d, 1, n * es, 0)])
+            run = DeviceRun(w)
+            run.run_phases()
+            acc, out, _, rej = run.results()
+            eacc, eout, _ = oracle_results(w)
+            assert rej == 0
+            wide = (lambda x: x) if dtype == F32 else (lambda x: (x.astype(np.uint32) << 16).view(np.float32))
+            nan = np.isnan(wide(eacc))
+            assert np.array_equal(np.isnan(wide(acc)), nan)
+            assert_same(acc[~nan], eacc[~nan], f"dtype {dtype} op {op}")
+            assert_same(out[:n * es].view(a.dtype)[~nan[:n]], eacc[:n][~nan[:n]], "forward copy")
+
+
+def test_bf16_sum_dense_pairs(gpu_lib):
+    """Every bf16 pattern against 96 partner patterns (6.3 M pairs), bit-exact except NaN payloads."""
+    allh = np.arange(1 << 16, dtype=np.uint16)
+    partners = np.concatenate([pl.rng(3, 3).integers(0, 1 << 16, 64).astype(np.uint16),
+                               np.array([0, 0x8000, 1, 0x8001, 0x7F, 0x80, 0x3F80, 0xBF80, 0x3B80, 0xBB80,
+                                         0x7F7F, 0xFF7F, 0x7F80, 0xFF80, 0x3F81, 0x3B7F] * 2, dtype=np.uint16)])
+    a = np.tile(allh, len(partners))
+    r = np.repeat(partners, 1 << 16)
+    n = len(a)
+    d = _records([(k * (n // 8) * 2, k * (n // 8) * 2, NO_FORWARD, (n // 8) * 2, k) for k in range(8)])
+    w = wl.Workload("pairs", BF16, a, r, 0, 8, [wl.Phase("p", SUM, d, 8, n * 2, 0)])
+    run = DeviceRun(w)
+    run.run_phases()
+    acc = run.results()[0]
+    eacc = oracle_results(w)[0]
+    nan = np.isnan((eacc.astype(np.uint32) << 16).view(np.float32))
+    assert np.array_equal(np.isnan((acc.astype(np.uint32) << 16).view(np.float32)), nan)
+    assert_same(acc[~nan], eacc[~nan], "bf16 sum")
+
+
+# ---- closed loop: the GPU path as every rank of a ring ------------------------------------------
+
+class GpuBackend:
+    def __init__(self, pkg):
+        self.pkg = pkg
+
+    def make_rank(self, acc_init, out_bytes, n_bits):
+        return dict(acc=to_dev(acc_init), out=torch.zeros(out_bytes, dtype=torch.uint8, device="cuda"),
+                    bm=torch.zeros((n_bits + 31) // 32, dtype=torch.int32, device="cuda"), n_bits=n_bits,
+                    like=acc_init.dtype)
+
+    def apply(self, h, recv, descs, dtype, op):
+        self.pkg.uccl_chunk_apply_checked(h["acc"], h["out"], to_dev(recv), to_dev(descs), len(descs), h["bm"],
+                                          dtype, op, n_bits=h["n_bits"])
+        torch.cuda.synchronize()
+
+    def read_out(self, h, off, nbytes):
+        return h["out"][off:off + nbytes].cpu().numpy()
+
+    def read_acc(self, h):
+        return to_host(h["acc"], h["like"])
+
+
+@pytest.mark.parametrize("dtype,R,n,C", [(F32, 8, 1 << 20, 64 << 10), (BF16, 4, 4 * 6000, 2048), (F32, 3, 3 * 1000, 528)])
+def test_closed_loop_ring_matches_textbook(gpu_lib, dtype, R, n, C):
+    """All R ranks run on the GPU path; first case is the 4 MiB fp32 / 64 KiB-chunk shape with
+    true ring partial sums as payloads."""
+    say("closed loop", dtype, R, n, C)
+    x = pl.uniform_f32(8, 8, R * n).reshape(R, n) if dtype == F32 else pl.normal_bf16(8, 8, R * n).reshape(R, n)
+    got = closed_loop_allreduce(GpuBackend(gpu_lib), x, dtype, C, seed=3, paths=4, window=None, dup=0.05)
+    assert_same(got, oracle.ring_allreduce(x, dtype, SUM), "closed loop vs textbook ring")
+    vals = pl.small_int(9, 9, R * n).reshape(R, n)
+    got = closed_loop_allreduce(GpuBackend(gpu_lib), pl.ints_as(vals, dtype), dtype, C, seed=4, paths=4, dup=0.05)
+    for r in range(R):
+        assert_same(got[r], pl.ints_as(vals.sum(axis=0), dtype), "integer inputs: exact column sum")
+
+
+def test_side_stream(gpu_lib):
+    w = wl.config2(seed=9, M=8 << 20)
+    run = DeviceRun(w)
+    s = torch.cuda.Stream()
+    s.wait_stream(torch.cuda.current_stream())
+    for ph, d in zip(w.phases, run.descs):
+        run.apply(d, len(ph.descs), ph.op, stream=s)
+    s.synchronize()
+    acc, out, bm, rej = run.results()
+    eacc, eout, ebm = oracle_results(w)
+    assert_same(acc, eacc, "acc"); assert_same(out, eout, "out"); assert_same(bm, ebm, "bitmap")
