@@ -27,6 +27,7 @@ def say(*a):
 
 
 def check_workload(pkg, w, shape=0, checked=True, split=None):
+    eacc, eout, ebm = oracle_results(w)  # first: the oracle also validates the records
     pkg.uccl_set_launch_shape(shape)
     try:
         run = DeviceRun(w)
@@ -34,7 +35,6 @@ def check_workload(pkg, w, shape=0, checked=True, split=None):
         acc, out, bm, rej = run.results()
     finally:
         pkg.uccl_set_launch_shape(0)
-    eacc, eout, ebm = oracle_results(w)
     assert rej == 0
     assert_same(bm, ebm, "bitmap")
     assert_same(acc, eacc, "acc")
@@ -201,7 +201,7 @@ def test_scatter_any_byte_length(gpu_lib, shape):
 
 
 def test_empty_call_and_all_duplicates(gpu_lib):
-    w = wl.ring_share("e", 1, R=2, M=2 * 4096, C=1024, dtype=F32, paths=2, window=None, dup=0.5,
+    w = wl.ring_share("e", 1, R=3, M=3 * 4096, C=1024, dtype=F32, paths=2, window=None, dup=0.5,
                       dist="uniform", allgather=False)
     run = DeviceRun(w)
     run.apply(run.descs[0], 0, SUM)
@@ -214,7 +214,8 @@ def test_empty_call_and_all_duplicates(gpu_lib):
     run.run_phases()  # the same records again: every one is now a duplicate
     again = run.results()
     for a, b in zip(first[:3], again[:3]):
-        assert_same(a, b, "second pass changes nothing")
+        if a is not None:
+            assert_same(a, b, "second pass changes nothing")
     eacc, eout, ebm = oracle_results(w)
     assert_same(first[0], eacc, "acc")
     # after a reset the records apply again (SUM adds the payload a second time)
