@@ -43,6 +43,9 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--shape", type=int, default=0, help="launch shape id (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic that "
+                         "hardware counters of the same run can be scaled by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU's share on one GPU; --gpus N>1 is not supported "
@@ -107,6 +110,14 @@ def main():
         torch.cuda.synchronize()
         t = np.array([a.elapsed_time(b) for a, b in evs])
         kernel_ms.append((float(t.mean()), float(np.median(t)), float(t.min())))
+
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        dstc = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dstc.copy_(src)
+        torch.cuda.synchronize()
+        del src, dstc
 
     payload = sum(ph.payload_bytes for ph in w.phases)
     unique = sum(ph.n_unique for ph in w.phases)

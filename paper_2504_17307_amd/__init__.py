@@ -64,6 +64,12 @@ def load(path: str = None):
     if _lib is not None and path is None:
         return _lib
     p = path or LIB_PATH
+    try:
+        # PyTorch ships its own HIP runtime under the same soname; it has to be the first
+        # one the process loads, or device memory made by torch is unknown to this library.
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     if not os.path.exists(p):
         if path is not None:
             raise RuntimeError(f"{p} does not exist")
