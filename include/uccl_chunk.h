@@ -137,17 +137,25 @@ int uccl_chunk_scatter_checked(void* dst, const void* recv_stage, const uccl_chu
 int uccl_dedup_reset(uint32_t* dedup_bitmap, uint64_t n_bits, void* stream);
 
 /*
- * Launch shape: how records are mapped onto the machine.  AUTO picks from n_descs.
- *   WAVE   one 64-lane wavefront streams a chunk; a 256-thread workgroup dedups a tile
- *          of records together and its four wavefronts take the winners in turn
+ * Launch shape: how records are mapped onto the machine.
+ *   AUTO   = FLAT
+ *   FLAT   a 1024-thread workgroup dedups a tile of records, cuts the winners into
+ *          2 KiB units and deals the units to its 16 wavefronts (any chunk size)
+ *   WAVE   a 256-thread workgroup dedups a tile of records and each of its four
+ *          wavefronts streams whole chunks
  *   GROUP  all 256 threads of a workgroup stream one chunk
- *   WIDE   all 1024 threads of a workgroup stream one chunk (few, large chunks)
+ * WAVE and GROUP exist so that the alternatives can be measured; FLAT is the fastest.
  * Process-wide setting, intended for tuning runs; returns UCCL_EINVAL for unknown ids.
  */
 typedef enum uccl_shape {
-  UCCL_SHAPE_AUTO = 0, UCCL_SHAPE_WAVE = 1, UCCL_SHAPE_GROUP = 2, UCCL_SHAPE_WIDE = 3
+  UCCL_SHAPE_AUTO = 0, UCCL_SHAPE_WAVE = 1, UCCL_SHAPE_GROUP = 2, UCCL_SHAPE_FLAT = 4
 } uccl_shape;
 int uccl_set_launch_shape(int shape);
+
+/* The transport's chunk size in bytes (the control path chooses it per connection:
+ * 32 KB by default, Section 3.3 "control coalescing"), 0 = unknown.  Only a tuning hint:
+ * it sets how many records a workgroup takes; results never depend on it. */
+int uccl_set_chunk_hint(uint32_t chunk_bytes);
 
 const char* uccl_strerror(int code);
 const char* uccl_last_error_detail(void); /* HIP's text for the last UCCL_ELAUNCH on this thread */

@@ -18,7 +18,7 @@ UCCL_F32, UCCL_BF16 = 0, 1
 UCCL_SUM, UCCL_MAX, UCCL_MIN, UCCL_COPY = 0, 1, 2, 3
 UCCL_OK, UCCL_EINVAL, UCCL_EALIGN, UCCL_ELAUNCH = 0, -1, -2, -3
 UCCL_NO_FORWARD = 0xFFFFFFFFFFFFFFFF
-UCCL_SHAPE_AUTO, UCCL_SHAPE_WAVE, UCCL_SHAPE_GROUP, UCCL_SHAPE_WIDE = 0, 1, 2, 3
+UCCL_SHAPE_AUTO, UCCL_SHAPE_WAVE, UCCL_SHAPE_GROUP, UCCL_SHAPE_FLAT = 0, 1, 2, 4
 DESC_BYTES = 32
 
 
@@ -52,6 +52,7 @@ _SIGNATURES = {
                                              C.c_void_p]),
     "uccl_dedup_reset": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p]),
     "uccl_set_launch_shape": (C.c_int, [C.c_int]),
+    "uccl_set_chunk_hint": (C.c_int, [C.c_uint32]),
     "uccl_strerror": (C.c_char_p, [C.c_int]),
     "uccl_last_error_detail": (C.c_char_p, []),
     "uccl_version": (C.c_int, []),
@@ -155,6 +156,10 @@ def uccl_dedup_reset(dedup_bitmap, n_bits, stream=None):
 
 def uccl_set_launch_shape(shape):
     _check(load().uccl_set_launch_shape(int(shape)), "uccl_set_launch_shape")
+
+
+def uccl_set_chunk_hint(chunk_bytes):
+    _check(load().uccl_set_chunk_hint(int(chunk_bytes)), "uccl_set_chunk_hint")
 
 
 def uccl_strerror(code) -> str:

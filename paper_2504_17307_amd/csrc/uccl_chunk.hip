@@ -9,13 +9,14 @@
 // bytes moved.
 //
 // Mapping onto the machine.  The work is a stream: at most one add per 4..8 bytes
-// moved, so HBM bandwidth bounds it and no matrix core is involved.  A workgroup takes
-// a tile of T consecutive records.  The lanes of its first wavefront each load one
-// 32-byte record with two 128-bit loads, validate it, and test-and-set its bit with one
-// device-scope atomic OR; the returned old word tells the lane whether it is the first
-// arrival.  A wave ballot compacts the winners into LDS.  After one barrier, subgroups of
-// SG threads take winners in turn and stream them with 128-bit loads and stores, U
-// independent vectors per thread in flight.  Duplicates cost their record and one
+// moved, so HBM bandwidth bounds it and no matrix core is involved.  A 1024-thread
+// workgroup takes a tile of T consecutive records.  The lanes of its first wavefront each
+// load one 32-byte record with two 128-bit loads, validate it, and test-and-set its bit
+// with one device-scope atomic OR; the returned old word tells the lane whether it is the
+// first arrival.  A wave ballot compacts the winners into LDS and a wave scan numbers
+// their 2 KiB units.  After one barrier the 16 wavefronts take units round-robin and
+// stream them with 128-bit loads and stores: every thread issues all its loads, then
+// combines, then stores, and the workgroup retires.  Duplicates cost their record and one
 // atomic, nothing else.  Two lanes holding the same seq each issue their own atomic, so
 // the hardware serialises them and exactly one sees the bit clear.
 #include <hip/hip_runtime.h>
@@ -31,7 +32,7 @@
 #define UCCL_WAVE_TILE 4      // records per 256-thread workgroup, one wavefront per chunk
 #endif
 #ifndef UCCL_WAVE_UNROLL
-#define UCCL_WAVE_UNROLL 8
+#define UCCL_WAVE_UNROLL 4
 #endif
 #ifndef UCCL_WAVE_TILE_SMALL
 #define UCCL_WAVE_TILE_SMALL 16  // same shape, used when a call carries very many records
@@ -42,25 +43,40 @@
 #ifndef UCCL_GROUP_UNROLL
 #define UCCL_GROUP_UNROLL 4
 #endif
-#ifndef UCCL_WIDE_TILE
-#define UCCL_WIDE_TILE 1      // records per workgroup, 1024 threads per chunk
+#ifndef UCCL_FLAT_UNROLL
+#define UCCL_FLAT_UNROLL 2    // vectors per lane per unit: a unit is 64*U*16 bytes per stream
 #endif
-#ifndef UCCL_WIDE_UNROLL
-#define UCCL_WIDE_UNROLL 2
+// Cache policy of the four streams, one 4-bit mask per kind of chunk (measured on
+// MI355X with buffers too large to stay cache resident).  Bit 3: non-temporal load of the
+// arrival slot; bit 2: non-temporal store of the staging copy; bit 1: non-temporal load
+// of the accumulator; bit 0: non-temporal store of the accumulator.
+#ifndef UCCL_POLICY_REDUCE_FWD
+#define UCCL_POLICY_REDUCE_FWD 0xD   // slot read once, staging written once, acc line dropped after its write
 #endif
-#ifndef UCCL_AUTO_WIDE_BELOW
-#define UCCL_AUTO_WIDE_BELOW 512u      // fewer records than this: 1024 threads per chunk
+#ifndef UCCL_POLICY_REDUCE_KEEP
+#define UCCL_POLICY_REDUCE_KEEP 0x9
 #endif
-#ifndef UCCL_AUTO_GROUP_BELOW
-#define UCCL_AUTO_GROUP_BELOW 16384u   // fewer than this: 256 threads per chunk
+#ifndef UCCL_POLICY_COPY_FWD
+#define UCCL_POLICY_COPY_FWD 0xC
 #endif
-#ifndef UCCL_AUTO_SMALLTILE_FROM
-#define UCCL_AUTO_SMALLTILE_FROM 65536u // at least this many: wavefront per chunk, big tiles
+#ifndef UCCL_POLICY_COPY_KEEP
+#define UCCL_POLICY_COPY_KEEP 0x9
 #endif
 
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool NT>
+__device__ __forceinline__ u32x4 load16(const u32x4* p) {
+  if constexpr (NT) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool NT>
+__device__ __forceinline__ void store16(u32x4* p, u32x4 v) {
+  if constexpr (NT) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
 
 struct Extents {
   uint64_t acc_bytes, out_bytes, recv_bytes, n_bits;
@@ -171,37 +187,41 @@ __device__ __forceinline__ uint64_t wave_uniform(uint64_t v) {
 }
 
 // Stream one chunk with SG cooperating threads: U independent 16-byte vectors per thread
-// per trip, loads first, then combine and store.  The receive slot is read once and the
-// staging copy written once, so both bypass cache retention (non-temporal).
+// per trip, loads first, then combine and store.  Which streams carry a non-temporal
+// hint depends on the kind of chunk (see the policy masks above).
 template <int SG, int U, class Op, bool FWD>
 __device__ __forceinline__ void stream_vectors(const u32x4* __restrict__ r, u32x4* __restrict__ a,
                                                u32x4* __restrict__ o, uint32_t nvec,
                                                uint32_t lane) {
+  constexpr uint32_t kPolicy = Op::kReadsAcc ? (FWD ? UCCL_POLICY_REDUCE_FWD : UCCL_POLICY_REDUCE_KEEP)
+                                             : (FWD ? UCCL_POLICY_COPY_FWD : UCCL_POLICY_COPY_KEEP);
+  constexpr bool kNtRecv = (kPolicy & 8u) != 0, kNtOut = (kPolicy & 4u) != 0;
+  constexpr bool kNtAccLoad = (kPolicy & 2u) != 0, kNtAccStore = (kPolicy & 1u) != 0;
   constexpr uint32_t kTrip = SG * U;
   const uint32_t full = nvec - nvec % kTrip;
   for (uint32_t base = lane; base < full; base += kTrip) {
     u32x4 rv[U], av[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) rv[u] = __builtin_nontemporal_load(r + base + u * SG);
+    for (int u = 0; u < U; ++u) rv[u] = load16<kNtRecv>(r + base + u * SG);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      if constexpr (Op::kReadsAcc) av[u] = a[base + u * SG];
+      if constexpr (Op::kReadsAcc) av[u] = load16<kNtAccLoad>(a + base + u * SG);
       else av[u] = rv[u];
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const u32x4 t = combine<Op>(av[u], rv[u]);
-      a[base + u * SG] = t;
-      if (FWD) __builtin_nontemporal_store(t, o + base + u * SG);
+      store16<kNtAccStore>(a + base + u * SG, t);
+      if (FWD) store16<kNtOut>(o + base + u * SG, t);
     }
   }
   for (uint32_t i = full + lane; i < nvec; i += SG) {
-    const u32x4 rv = __builtin_nontemporal_load(r + i);
+    const u32x4 rv = load16<kNtRecv>(r + i);
     u32x4 av = rv;
-    if constexpr (Op::kReadsAcc) av = a[i];
+    if constexpr (Op::kReadsAcc) av = load16<kNtAccLoad>(a + i);
     const u32x4 t = combine<Op>(av, rv);
-    a[i] = t;
-    if (FWD) __builtin_nontemporal_store(t, o + i);
+    store16<kNtAccStore>(a + i, t);
+    if (FWD) store16<kNtOut>(o + i, t);
   }
 }
 
@@ -245,67 +265,179 @@ __device__ __forceinline__ void stream_chunk(const char* r, char* a, char* o, ui
   }
 }
 
+// Winners of one tile of records, compacted; first[] is the exclusive prefix sum of
+// their unit counts (flat shape only) with the total in first[count].
+template <int T>
+struct Tile {
+  uint64_t src[T], dst[T], out[T];
+  uint32_t len[T];
+  uint32_t first[T + 1];
+  uint32_t count;
+};
+
+// Run by the first wavefront of a workgroup: lane i takes record tile*T + i, validates
+// it, claims its sequence number, and the winners are compacted into LDS in record order.
+// kUnitVecs > 0 also computes how many units of kUnitVecs 16-byte vectors each winner has.
+template <int T, class Op, uint32_t kUnitVecs>
+__device__ __forceinline__ void dedup_tile(const Args& g, Tile<T>& s, uint32_t tid) {
+  static_assert(T >= 1 && T <= 64, "one wavefront dedups the tile");
+  const uint64_t k = static_cast<uint64_t>(blockIdx.x) * T + tid;
+  bool win = false;
+  uint64_t src = 0, dst = 0, out = 0;
+  uint32_t len = 0;
+  if (tid < T && k < g.n_descs) {
+    const u32x4* p = reinterpret_cast<const u32x4*>(g.descs + k);
+    const u32x4 lo = p[0], hi = p[1];
+    src = lo.x | (static_cast<uint64_t>(lo.y) << 32);
+    dst = lo.z | (static_cast<uint64_t>(lo.w) << 32);
+    out = hi.x | (static_cast<uint64_t>(hi.y) << 32);
+    len = hi.z;
+    const uint32_t seq = hi.w;
+    const bool fwd = out != UCCL_NO_FORWARD;
+    bool ok = seq < g.ext.n_bits && ((src | dst) & 15u) == 0 && len % Op::kEs == 0 &&
+              src <= g.ext.recv_bytes && len <= g.ext.recv_bytes - src &&
+              dst <= g.ext.acc_bytes && len <= g.ext.acc_bytes - dst;
+    if (fwd)
+      ok = ok && g.allow_forward && g.out != nullptr && (out & 15u) == 0 &&
+           out <= g.ext.out_bytes && len <= g.ext.out_bytes - out;
+    if (ok) {
+      const uint32_t bit = 1u << (seq & 31u);
+      const uint32_t old = atomicOr(g.bitmap + (seq >> 5), bit);  // device scope, relaxed
+      win = (old & bit) == 0;
+    } else if (g.rejected != nullptr) {
+      atomicAdd(g.rejected, 1u);
+    }
+  }
+  const uint64_t winners = __ballot(win);
+  const uint32_t pos = __popcll(winners & ((1ull << tid) - 1ull));
+  const uint32_t count = __popcll(winners);
+  if (win) {
+    s.src[pos] = src;
+    s.dst[pos] = dst;
+    s.out[pos] = out;
+    s.len[pos] = len;
+  }
+  if (tid == 0) s.count = count;
+  if (kUnitVecs > 0) {
+    // a partial last vector (len % 16 != 0) counts as a vector of its unit
+    const uint32_t units = win ? (((len + 15u) >> 4) + kUnitVecs - 1u) / kUnitVecs : 0u;
+    uint32_t incl = units;
+#pragma unroll
+    for (uint32_t d = 1; d < 64; d <<= 1) {
+      const uint32_t below = __shfl_up(incl, d, 64);
+      if (tid >= d) incl += below;
+    }
+    if (win) s.first[pos] = incl - units;
+    if (tid == 63) s.first[count] = incl;
+  }
+}
+
+// Shapes WAVE / GROUP: subgroups of SG threads take whole winners in turn.  Kept
+// selectable because they are the obvious alternatives (one wavefront per chunk, one
+// workgroup per chunk); both measure slower than the flat shape on MI355X.
 template <int NT, int T, int SG, int U, class Op>
 __global__ void __launch_bounds__(NT) chunk_apply_kernel(const Args g) {
-  static_assert(T >= 1 && T <= 64, "one wavefront dedups the tile");
   static_assert(NT % SG == 0 && SG % 64 == 0, "subgroups are whole wavefronts");
   constexpr uint32_t kSubgroups = NT / SG;
-  __shared__ uint64_t s_src[T], s_dst[T], s_out[T];
-  __shared__ uint32_t s_len[T];
-  __shared__ uint32_t s_count;
-
+  __shared__ Tile<T> s;
   const uint32_t tid = threadIdx.x;
-  if (tid < 64) {
-    const uint64_t k = static_cast<uint64_t>(blockIdx.x) * T + tid;
-    bool win = false;
-    uint64_t src = 0, dst = 0, out = 0;
-    uint32_t len = 0;
-    if (tid < T && k < g.n_descs) {
-      const u32x4* p = reinterpret_cast<const u32x4*>(g.descs + k);
-      const u32x4 lo = p[0], hi = p[1];
-      src = lo.x | (static_cast<uint64_t>(lo.y) << 32);
-      dst = lo.z | (static_cast<uint64_t>(lo.w) << 32);
-      out = hi.x | (static_cast<uint64_t>(hi.y) << 32);
-      len = hi.z;
-      const uint32_t seq = hi.w;
-      const bool fwd = out != UCCL_NO_FORWARD;
-      bool ok = seq < g.ext.n_bits && ((src | dst) & 15u) == 0 && len % Op::kEs == 0 &&
-                src <= g.ext.recv_bytes && len <= g.ext.recv_bytes - src &&
-                dst <= g.ext.acc_bytes && len <= g.ext.acc_bytes - dst;
-      if (fwd)
-        ok = ok && g.allow_forward && g.out != nullptr && (out & 15u) == 0 &&
-             out <= g.ext.out_bytes && len <= g.ext.out_bytes - out;
-      if (ok) {
-        const uint32_t bit = 1u << (seq & 31u);
-        const uint32_t old = atomicOr(g.bitmap + (seq >> 5), bit);  // device scope, relaxed
-        win = (old & bit) == 0;
-      } else if (g.rejected != nullptr) {
-        atomicAdd(g.rejected, 1u);
-      }
-    }
-    const uint64_t winners = __ballot(win);
-    if (win) {
-      const uint32_t pos = __popcll(winners & ((1ull << tid) - 1ull));
-      s_src[pos] = src;
-      s_dst[pos] = dst;
-      s_out[pos] = out;
-      s_len[pos] = len;
-    }
-    if (tid == 0) s_count = __popcll(winners);
-  }
+  if (tid < 64) dedup_tile<T, Op, 0>(g, s, tid);
   __syncthreads();
 
-  const uint32_t count = s_count;
+  const uint32_t count = s.count;
   const uint32_t sg = tid / SG, lane = tid % SG;
   for (uint32_t w = sg; w < count; w += kSubgroups) {
-    const uint64_t src = wave_uniform(s_src[w]);
-    const uint64_t dst = wave_uniform(s_dst[w]);
-    const uint64_t out = wave_uniform(s_out[w]);
-    const uint32_t len = __builtin_amdgcn_readfirstlane(s_len[w]);
+    const uint64_t src = wave_uniform(s.src[w]);
+    const uint64_t dst = wave_uniform(s.dst[w]);
+    const uint64_t out = wave_uniform(s.out[w]);
+    const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
     if (out != UCCL_NO_FORWARD)
       stream_chunk<SG, U, Op, true>(g.recv + src, g.acc + dst, g.out + out, len, lane);
     else
       stream_chunk<SG, U, Op, false>(g.recv + src, g.acc + dst, nullptr, len, lane);
+  }
+}
+
+// One unit = 64*U consecutive 16-byte vectors of a chunk, streamed by one wavefront.
+template <int U, class Op, bool FWD>
+__device__ __forceinline__ void stream_unit(const char* r, char* a, char* o, uint32_t len,
+                                            uint32_t trip, uint32_t lane) {
+  constexpr uint32_t kPolicy = Op::kReadsAcc ? (FWD ? UCCL_POLICY_REDUCE_FWD : UCCL_POLICY_REDUCE_KEEP)
+                                             : (FWD ? UCCL_POLICY_COPY_FWD : UCCL_POLICY_COPY_KEEP);
+  constexpr bool kNtRecv = (kPolicy & 8u) != 0, kNtOut = (kPolicy & 4u) != 0;
+  constexpr bool kNtAccLoad = (kPolicy & 2u) != 0, kNtAccStore = (kPolicy & 1u) != 0;
+  constexpr uint32_t kUnit = 64u * U;
+  const uint32_t nvec = len >> 4;
+  const uint32_t v0 = trip * kUnit;
+  const u32x4* rp = reinterpret_cast<const u32x4*>(r) + v0 + lane;
+  u32x4* ap = reinterpret_cast<u32x4*>(a) + v0 + lane;
+  u32x4* op = reinterpret_cast<u32x4*>(o) + v0 + lane;
+  if (v0 + kUnit <= nvec) {
+    u32x4 rv[U], av[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) rv[u] = load16<kNtRecv>(rp + u * 64);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if constexpr (Op::kReadsAcc) av[u] = load16<kNtAccLoad>(ap + u * 64);
+      else av[u] = rv[u];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const u32x4 t = combine<Op>(av[u], rv[u]);
+      store16<kNtAccStore>(ap + u * 64, t);
+      if (FWD) store16<kNtOut>(op + u * 64, t);
+    }
+    return;
+  }
+  // last unit of the chunk: ragged
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (v0 + lane + u * 64 < nvec) {
+      const u32x4 rv = load16<kNtRecv>(rp + u * 64);
+      u32x4 av = rv;
+      if constexpr (Op::kReadsAcc) av = load16<kNtAccLoad>(ap + u * 64);
+      const u32x4 t = combine<Op>(av, rv);
+      store16<kNtAccStore>(ap + u * 64, t);
+      if (FWD) store16<kNtOut>(op + u * 64, t);
+    }
+  }
+  const uint32_t rem = len & 15u;
+  if (rem) {  // nvec lies in this unit, or the chunk would have had one unit fewer
+    const uint64_t off = static_cast<uint64_t>(nvec) << 4;
+    stream_tail<Op, FWD>(r + off, a + off, FWD ? o + off : o, rem, lane);
+  }
+}
+
+// Shape FLAT: the winners' units are numbered consecutively across the tile and dealt
+// round-robin to the 16 wavefronts of a 1024-thread workgroup, so the machine sees the
+// same stream whether a tile holds one 128 KiB chunk or thirty-two 4 KiB chunks.
+template <int T, int U, class Op>
+__global__ void __launch_bounds__(1024) chunk_flat_kernel(const Args g) {
+  constexpr uint32_t kUnit = 64u * U;
+  __shared__ Tile<T> s;
+  const uint32_t tid = threadIdx.x;
+  if (tid < 64) dedup_tile<T, Op, kUnit>(g, s, tid);
+  __syncthreads();
+
+  const uint32_t count = s.count;
+  const uint32_t total = s.first[count];
+  const uint32_t wave = tid >> 6, lane = tid & 63u;
+  for (uint32_t u = wave; u < total; u += 16u) {
+    uint32_t w = 0;
+    if (T > 1) {
+      const bool mine = lane < count && s.first[lane] <= u && u < s.first[lane + 1];
+      w = __ffsll(static_cast<unsigned long long>(__ballot(mine))) - 1;  // exactly one lane
+    }
+    w = __builtin_amdgcn_readfirstlane(w);
+    const uint32_t trip = u - __builtin_amdgcn_readfirstlane(s.first[w]);
+    const uint64_t src = wave_uniform(s.src[w]);
+    const uint64_t dst = wave_uniform(s.dst[w]);
+    const uint64_t out = wave_uniform(s.out[w]);
+    const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
+    if (out != UCCL_NO_FORWARD)
+      stream_unit<U, Op, true>(g.recv + src, g.acc + dst, g.out + out, len, trip, lane);
+    else
+      stream_unit<U, Op, false>(g.recv + src, g.acc + dst, nullptr, len, trip, lane);
   }
 }
 
@@ -319,6 +451,7 @@ __global__ void __launch_bounds__(256) fill_words_kernel(uint32_t* p, uint64_t n
 
 thread_local char t_detail[256] = "";
 int g_shape = UCCL_SHAPE_AUTO;
+uint32_t g_chunk_hint = 0;
 
 int launch_failed(hipError_t e) {
   snprintf(t_detail, sizeof(t_detail), "%s: %s", hipGetErrorName(e), hipGetErrorString(e));
@@ -333,26 +466,46 @@ int launch(const Args& a, hipStream_t s) {
   return e == hipSuccess ? UCCL_OK : launch_failed(e);
 }
 
+template <int T, int U, class Op>
+int launch_flat(const Args& a, hipStream_t s) {
+  const uint32_t tiles = (a.n_descs + T - 1) / T;
+  hipLaunchKernelGGL((chunk_flat_kernel<T, U, Op>), dim3(tiles), dim3(1024), 0, s, a);
+  const hipError_t e = hipGetLastError();
+  return e == hipSuccess ? UCCL_OK : launch_failed(e);
+}
+
+// Records per workgroup for the flat shape: enough that a tile holds about 32 KiB of
+// payload per stream when the chunk size is known, otherwise grown with the record count.
+uint32_t flat_tile(uint32_t n_descs) {
+  uint32_t t;
+  if (g_chunk_hint) {
+    t = (32768u + g_chunk_hint - 1) / g_chunk_hint;
+  } else {
+    t = n_descs < 16384u ? 1u : n_descs < 65536u ? 4u : 16u;
+  }
+  return t < 1u ? 1u : t > 32u ? 32u : t;
+}
+
+template <class Op>
+int launch_flat_tile(const Args& a, hipStream_t s) {
+  const uint32_t t = flat_tile(a.n_descs);
+  if (t >= 32) return launch_flat<32, UCCL_FLAT_UNROLL, Op>(a, s);
+  if (t >= 16) return launch_flat<16, UCCL_FLAT_UNROLL, Op>(a, s);
+  if (t >= 8) return launch_flat<8, UCCL_FLAT_UNROLL, Op>(a, s);
+  if (t >= 4) return launch_flat<4, UCCL_FLAT_UNROLL, Op>(a, s);
+  if (t >= 2) return launch_flat<2, UCCL_FLAT_UNROLL, Op>(a, s);
+  return launch_flat<1, UCCL_FLAT_UNROLL, Op>(a, s);
+}
+
 template <class Op>
 int launch_shape(const Args& a, hipStream_t s) {
-  int shape = g_shape;
-  bool big_tiles = a.n_descs >= UCCL_AUTO_SMALLTILE_FROM;
-  if (shape == UCCL_SHAPE_AUTO) {
-    if (a.n_descs < UCCL_AUTO_WIDE_BELOW) shape = UCCL_SHAPE_WIDE;
-    else if (a.n_descs < UCCL_AUTO_GROUP_BELOW) shape = UCCL_SHAPE_GROUP;
-    else shape = UCCL_SHAPE_WAVE;
+  if (g_shape == UCCL_SHAPE_AUTO || g_shape == UCCL_SHAPE_FLAT) return launch_flat_tile<Op>(a, s);
+  if (g_shape == UCCL_SHAPE_WAVE) {
+    if (a.n_descs >= 65536u) return launch<256, UCCL_WAVE_TILE_SMALL, 64, UCCL_WAVE_UNROLL, Op>(a, s);
+    return launch<256, UCCL_WAVE_TILE, 64, UCCL_WAVE_UNROLL, Op>(a, s);
   }
-  switch (shape) {
-    case UCCL_SHAPE_WAVE:
-      if (big_tiles) return launch<256, UCCL_WAVE_TILE_SMALL, 64, UCCL_WAVE_UNROLL, Op>(a, s);
-      return launch<256, UCCL_WAVE_TILE, 64, UCCL_WAVE_UNROLL, Op>(a, s);
-    case UCCL_SHAPE_GROUP:
-      return launch<256, UCCL_GROUP_TILE, 256, UCCL_GROUP_UNROLL, Op>(a, s);
-    case UCCL_SHAPE_WIDE:
-      return launch<1024, UCCL_WIDE_TILE, 1024, UCCL_WIDE_UNROLL, Op>(a, s);
-    default:
-      return UCCL_EINVAL;
-  }
+  if (g_shape == UCCL_SHAPE_GROUP) return launch<256, UCCL_GROUP_TILE, 256, UCCL_GROUP_UNROLL, Op>(a, s);
+  return UCCL_EINVAL;
 }
 
 bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
@@ -450,8 +603,15 @@ int uccl_dedup_reset(uint32_t* dedup_bitmap, uint64_t n_bits, void* stream) {
   return e == hipSuccess ? UCCL_OK : launch_failed(e);
 }
 
+int uccl_set_chunk_hint(uint32_t chunk_bytes) {
+  g_chunk_hint = chunk_bytes;
+  return UCCL_OK;
+}
+
 int uccl_set_launch_shape(int shape) {
-  if (shape < UCCL_SHAPE_AUTO || shape > UCCL_SHAPE_WIDE) return UCCL_EINVAL;
+  if (shape != UCCL_SHAPE_AUTO && shape != UCCL_SHAPE_WAVE && shape != UCCL_SHAPE_GROUP &&
+      shape != UCCL_SHAPE_FLAT)
+    return UCCL_EINVAL;
   g_shape = shape;
   return UCCL_OK;
 }

@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"uccl_chunk_apply", "uccl_chunk_scatter", "uccl_dedup_reset", "uccl_strerror",
             "uccl_version", "uccl_chunk_apply_checked", "uccl_chunk_scatter_checked",
-            "uccl_set_launch_shape", "uccl_last_error_detail"} <= set(names)
+            "uccl_set_launch_shape", "uccl_set_chunk_hint", "uccl_last_error_detail"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     assert set(names) == set(pkg._SIGNATURES), "binding and header list the same entry points"
@@ -68,7 +68,7 @@ def test_host_side_error_codes_enqueue_nothing():
     r = lib.uccl_dedup_reset
     assert r(None, 8, None) == pkg.UCCL_EINVAL and r(M + 1, 8, None) == pkg.UCCL_EALIGN
     assert r(None, 0, None) == pkg.UCCL_OK
-    assert lib.uccl_set_launch_shape(9) == pkg.UCCL_EINVAL and lib.uccl_set_launch_shape(0) == pkg.UCCL_OK
+    assert lib.uccl_set_launch_shape(9) == pkg.UCCL_EINVAL and lib.uccl_set_launch_shape(3) == pkg.UCCL_EINVAL and lib.uccl_set_launch_shape(0) == pkg.UCCL_OK
     assert pkg.uccl_strerror(pkg.UCCL_EALIGN) == "misaligned pointer"
     with pytest.raises(pkg.UcclError) as err:
         pkg.uccl_chunk_apply(None, None, B, D, 1, M, 0, 0, stream=0)

@@ -19,7 +19,7 @@ from ringloop import closed_loop_allreduce
 
 pytestmark = pytest.mark.gpu
 
-SHAPES = [0, 1, 2, 3]  # AUTO, WAVE, GROUP, WIDE
+SHAPES = [0, 1, 2, 4]  # AUTO (= FLAT), WAVE, GROUP, FLAT
 
 
 def say(*a):
@@ -101,9 +101,12 @@ def test_config5_recipe_batched_and_per_message(gpu_lib):
         oracle.apply(eacc, eout, w.recv_stage, m["rs"], seen, F32, SUM)
         oracle.apply(eacc, eout, w.recv_stage, m["ag"], seen, F32, COPY)
     ebm = oracle.pack_bitmap(seen)
-    for mode in ("per-message", "batched"):
+    for mode in ("per-message", "batched", "batched-flat-hint"):
         say("config5", mode)
         run = DeviceRun(w)
+        if mode == "batched-flat-hint":
+            gpu_lib.uccl_set_launch_shape(4)
+            gpu_lib.uccl_set_chunk_hint(4096)
         if mode == "per-message":
             for m in msgs:
                 run.apply(to_dev(m["rs"]), len(m["rs"]), SUM)
@@ -115,11 +118,26 @@ def test_config5_recipe_batched_and_per_message(gpu_lib):
                 run.apply(to_dev(rs), len(rs), SUM)
                 run.apply(to_dev(ag), len(ag), COPY)
         torch.cuda.synchronize()
+        gpu_lib.uccl_set_launch_shape(0)
+        gpu_lib.uccl_set_chunk_hint(0)
         acc, out, bm, rej = run.results()
         assert rej == 0
         assert_same(bm, ebm, "bitmap")
         assert_same(acc, eacc, "acc")
         assert_same(out, eout, "out")
+
+
+@pytest.mark.parametrize("hint", [512, 1024, 4096, 16384, 1 << 20])
+def test_flat_shape_every_tile_size(gpu_lib, hint):
+    """The chunk-size hint only changes how many records a workgroup takes (32, 32, 8, 2, 1)."""
+    gpu_lib.uccl_set_chunk_hint(hint)
+    try:
+        C = 5008
+        w = wl.ring_share("tiles", 13, R=4, M=4 * (9 * C + 1040), C=C, dtype=BF16, paths=5, window=11,
+                          dup=0.2, dist="normal")
+        check_workload(gpu_lib, w, 4)
+    finally:
+        gpu_lib.uccl_set_chunk_hint(0)
 
 
 # ---- ops, dtypes, ragged tails, odd lengths ------------------------------------------
