@@ -157,6 +157,13 @@ int uccl_set_launch_shape(int shape);
  * it sets how many records a workgroup takes; results never depend on it. */
 int uccl_set_chunk_hint(uint32_t chunk_bytes);
 
+/* Measurement aid: the next apply / scatter call made by THIS host thread attaches the
+ * two hipEvent_t (either may be NULL) to its kernel dispatch, so that
+ * hipEventElapsedTime(start, stop) is that kernel's own execution time on the device,
+ * without the queueing and launch gaps an event pair recorded around the call would
+ * include.  One-shot: cleared by the launch (also by a launch that fails). */
+int uccl_time_next_launch(void* start_event, void* stop_event);
+
 const char* uccl_strerror(int code);
 const char* uccl_last_error_detail(void); /* HIP's text for the last UCCL_ELAUNCH on this thread */
 int uccl_version(void);

@@ -53,6 +53,7 @@ _SIGNATURES = {
     "uccl_dedup_reset": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p]),
     "uccl_set_launch_shape": (C.c_int, [C.c_int]),
     "uccl_set_chunk_hint": (C.c_int, [C.c_uint32]),
+    "uccl_time_next_launch": (C.c_int, [C.c_void_p, C.c_void_p]),
     "uccl_strerror": (C.c_char_p, [C.c_int]),
     "uccl_last_error_detail": (C.c_char_p, []),
     "uccl_version": (C.c_int, []),
@@ -76,6 +77,10 @@ def load(path: str = None):
             raise RuntimeError(f"{p} does not exist")
         from .build import build
         build()
+    elif path is None:
+        src = os.path.join(_PKG, "csrc", "uccl_chunk.hip")
+        if max(os.path.getmtime(src), os.path.getmtime(HEADER_PATH)) > os.path.getmtime(p):
+            raise RuntimeError(f"{p} is older than its sources: rebuild (python -m paper_2504_17307_amd.build)")
     lib = C.CDLL(p)
     for name, (res, args) in _SIGNATURES.items():
         fn = getattr(lib, name)  # AttributeError if the library does not export it
@@ -160,6 +165,13 @@ def uccl_set_launch_shape(shape):
 
 def uccl_set_chunk_hint(chunk_bytes):
     _check(load().uccl_set_chunk_hint(int(chunk_bytes)), "uccl_set_chunk_hint")
+
+
+def uccl_time_next_launch(start_event, stop_event):
+    """Events are torch.cuda.Event(enable_timing=True) objects (recorded once before, so
+    that their HIP handles exist) or integer hipEvent_t handles."""
+    h = lambda e: None if e is None else (e if isinstance(e, int) else e.cuda_event)
+    _check(load().uccl_time_next_launch(h(start_event), h(stop_event)), "uccl_time_next_launch")
 
 
 def uccl_strerror(code) -> str:

@@ -20,6 +20,7 @@
 // atomic, nothing else.  Two lanes holding the same seq each issue their own atomic, so
 // the hardware serialises them and exactly one sees the bit clear.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <stdint.h>
 #include <stdio.h>
@@ -42,6 +43,9 @@
 #endif
 #ifndef UCCL_GROUP_UNROLL
 #define UCCL_GROUP_UNROLL 4
+#endif
+#ifndef UCCL_FLAT_THREADS
+#define UCCL_FLAT_THREADS 1024  // workgroup size of the flat shape
 #endif
 #ifndef UCCL_FLAT_UNROLL
 #define UCCL_FLAT_UNROLL 2    // vectors per lane per unit: a unit is 64*U*16 bytes per stream
@@ -411,9 +415,10 @@ __device__ __forceinline__ void stream_unit(const char* r, char* a, char* o, uin
 // Shape FLAT: the winners' units are numbered consecutively across the tile and dealt
 // round-robin to the 16 wavefronts of a 1024-thread workgroup, so the machine sees the
 // same stream whether a tile holds one 128 KiB chunk or thirty-two 4 KiB chunks.
-template <int T, int U, class Op>
-__global__ void __launch_bounds__(1024) chunk_flat_kernel(const Args g) {
+template <int NT, int T, int U, class Op>
+__global__ void __launch_bounds__(NT) chunk_flat_kernel(const Args g) {
   constexpr uint32_t kUnit = 64u * U;
+  constexpr uint32_t kWaves = NT / 64;
   __shared__ Tile<T> s;
   const uint32_t tid = threadIdx.x;
   if (tid < 64) dedup_tile<T, Op, kUnit>(g, s, tid);
@@ -422,7 +427,7 @@ __global__ void __launch_bounds__(1024) chunk_flat_kernel(const Args g) {
   const uint32_t count = s.count;
   const uint32_t total = s.first[count];
   const uint32_t wave = tid >> 6, lane = tid & 63u;
-  for (uint32_t u = wave; u < total; u += 16u) {
+  for (uint32_t u = wave; u < total; u += kWaves) {
     uint32_t w = 0;
     if (T > 1) {
       const bool mine = lane < count && s.first[lane] <= u && u < s.first[lane + 1];
@@ -450,6 +455,7 @@ __global__ void __launch_bounds__(256) fill_words_kernel(uint32_t* p, uint64_t n
 // ---- host side ----------------------------------------------------------------------
 
 thread_local char t_detail[256] = "";
+thread_local hipEvent_t t_start = nullptr, t_stop = nullptr;  // one-shot, see uccl_time_next_launch
 int g_shape = UCCL_SHAPE_AUTO;
 uint32_t g_chunk_hint = 0;
 
@@ -458,20 +464,28 @@ int launch_failed(hipError_t e) {
   return UCCL_ELAUNCH;
 }
 
-template <int NT, int T, int SG, int U, class Op>
-int launch(const Args& a, hipStream_t s) {
-  const uint32_t tiles = (a.n_descs + T - 1) / T;
-  hipLaunchKernelGGL((chunk_apply_kernel<NT, T, SG, U, Op>), dim3(tiles), dim3(NT), 0, s, a);
+// Launch, attaching the one-shot timing events (if any) to this very dispatch.
+template <class Kernel>
+int launch_kernel(Kernel kernel, uint32_t tiles, uint32_t threads, const Args& a, hipStream_t s) {
+  if (t_start != nullptr || t_stop != nullptr) {
+    hipExtLaunchKernelGGL(kernel, dim3(tiles), dim3(threads), 0, s, t_start, t_stop, 0, a);
+    t_start = t_stop = nullptr;
+  } else {
+    hipLaunchKernelGGL(kernel, dim3(tiles), dim3(threads), 0, s, a);
+  }
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? UCCL_OK : launch_failed(e);
 }
 
+template <int NT, int T, int SG, int U, class Op>
+int launch(const Args& a, hipStream_t s) {
+  return launch_kernel(chunk_apply_kernel<NT, T, SG, U, Op>, (a.n_descs + T - 1) / T, NT, a, s);
+}
+
 template <int T, int U, class Op>
 int launch_flat(const Args& a, hipStream_t s) {
-  const uint32_t tiles = (a.n_descs + T - 1) / T;
-  hipLaunchKernelGGL((chunk_flat_kernel<T, U, Op>), dim3(tiles), dim3(1024), 0, s, a);
-  const hipError_t e = hipGetLastError();
-  return e == hipSuccess ? UCCL_OK : launch_failed(e);
+  return launch_kernel(chunk_flat_kernel<UCCL_FLAT_THREADS, T, U, Op>, (a.n_descs + T - 1) / T,
+                       UCCL_FLAT_THREADS, a, s);
 }
 
 // Records per workgroup for the flat shape: enough that a tile holds about 32 KiB of
@@ -601,6 +615,12 @@ int uccl_dedup_reset(uint32_t* dedup_bitmap, uint64_t n_bits, void* stream) {
                      dedup_bitmap, words, 0u);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? UCCL_OK : launch_failed(e);
+}
+
+int uccl_time_next_launch(void* start_event, void* stop_event) {
+  t_start = static_cast<hipEvent_t>(start_event);
+  t_stop = static_cast<hipEvent_t>(stop_event);
+  return UCCL_OK;
 }
 
 int uccl_set_chunk_hint(uint32_t chunk_bytes) {

@@ -20,7 +20,8 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"uccl_chunk_apply", "uccl_chunk_scatter", "uccl_dedup_reset", "uccl_strerror",
             "uccl_version", "uccl_chunk_apply_checked", "uccl_chunk_scatter_checked",
-            "uccl_set_launch_shape", "uccl_set_chunk_hint", "uccl_last_error_detail"} <= set(names)
+            "uccl_set_launch_shape", "uccl_set_chunk_hint", "uccl_time_next_launch",
+            "uccl_last_error_detail"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
     assert set(names) == set(pkg._SIGNATURES), "binding and header list the same entry points"

@@ -1,0 +1,100 @@
+"""Full-size parity, in the launch configuration bench.py times: the unchecked entry
+point, automatic launch shape, the transport's chunk size given as a hint.  Every output
+element of every configuration is compared with the oracle (the oracle finishes each of
+them in seconds, so no sampling is needed)."""
+import sys
+import time
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import workloads as wl
+from synth.layout import SUM, COPY, F32
+
+from gpuhelp import DeviceRun, oracle_results, assert_same, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+def say(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def run_full(pkg, w, chunk):
+    pkg.uccl_set_launch_shape(0)
+    pkg.uccl_set_chunk_hint(chunk)
+    try:
+        run = DeviceRun(w)
+        run.reset()
+        run.run_phases(checked=False)
+        return run.results()
+    finally:
+        pkg.uccl_set_chunk_hint(0)
+
+
+@pytest.mark.parametrize("name,chunk", [("config2", 32 << 10), ("config3", 128 << 10)])
+def test_ring_share_full_size(gpu_lib, name, chunk):
+    t0 = time.time()
+    w = getattr(wl, name)(seed=1)
+    say(f"{name}: built in {time.time() - t0:.1f}s, {sum(len(p.descs) for p in w.phases)} arrivals")
+    eacc, eout, ebm = oracle_results(w)
+    say(f"{name}: oracle done at {time.time() - t0:.1f}s")
+    acc, out, bm, _ = run_full(gpu_lib, w, chunk)
+    assert_same(bm, ebm, "bitmap")
+    assert_same(acc, eacc, "acc")
+    assert_same(out, eout, "out_stage")
+    # properties that hold at any size: the untouched segment keeps its initial bytes,
+    # every distinct seq has its bit, nothing else has
+    S = w.acc.nbytes // (16 if name == "config2" else 8)
+    if name == "config3":
+        assert_same(acc.view(np.uint8)[:S], w.acc.view(np.uint8)[:S], "segment 0 untouched by reduce-scatter")
+    assert sum(int(x).bit_count() for x in bm) == sum(p.n_unique for p in w.phases) == w.n_bits
+
+
+def test_alltoall_full_size(gpu_lib):
+    w = wl.config4(seed=1)
+    ph = w.phases[0]
+    gpu_lib.uccl_set_chunk_hint(16 << 10)
+    try:
+        dst = torch.zeros(w.acc.nbytes, dtype=torch.uint8, device="cuda")
+        bm = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
+        gpu_lib.uccl_chunk_scatter(dst, to_dev(w.recv_stage), to_dev(ph.descs), len(ph.descs), bm)
+        torch.cuda.synchronize()
+    finally:
+        gpu_lib.uccl_set_chunk_hint(0)
+    edst = np.zeros(w.acc.nbytes, dtype=np.uint8)
+    seen = oracle.new_seen(w.n_bits)
+    assert oracle.scatter(edst, w.recv_stage, ph.descs, seen) == ph.n_unique
+    got = dst.cpu().numpy()
+    assert_same(got, edst, "dst")
+    assert_same(got, np.concatenate(w.extra["sources"]), "dst is the concatenation of the sources")
+    assert_same(bm.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap")
+
+
+def test_small_messages_2000(gpu_lib):
+    """2000 of the 10000 small allreduces (same recipe), 128 messages per call."""
+    t0 = time.time()
+    w, msgs = wl.config5(seed=1, n_msgs=2000)
+    say(f"config5: built {len(msgs)} messages in {time.time() - t0:.1f}s")
+    eacc = w.acc.copy()
+    eout = np.zeros(w.out_bytes, dtype=np.uint8)
+    seen = oracle.new_seen(w.n_bits)
+    gpu_lib.uccl_set_chunk_hint(4 << 10)
+    try:
+        run = DeviceRun(w, guard=0)
+        for lo in range(0, len(msgs), 128):
+            rs = np.concatenate([m["rs"] for m in msgs[lo:lo + 128]])
+            ag = np.concatenate([m["ag"] for m in msgs[lo:lo + 128]])
+            run.apply(to_dev(rs), len(rs), SUM, checked=False)
+            run.apply(to_dev(ag), len(ag), COPY, checked=False)
+            oracle.apply(eacc, eout, w.recv_stage, rs, seen, F32, SUM, check=False)
+            oracle.apply(eacc, eout, w.recv_stage, ag, seen, F32, COPY, check=False)
+        torch.cuda.synchronize()
+    finally:
+        gpu_lib.uccl_set_chunk_hint(0)
+    acc, out, bm, _ = run.results()
+    assert_same(bm, oracle.pack_bitmap(seen), "bitmap")
+    assert_same(acc, eacc, "acc")
+    assert_same(out, eout, "out_stage")
