@@ -30,7 +30,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, see profiles/): valid only for the kernel
 # source it was measured on, identified by the hash of the HIP source file.
 MEASURED_TRAFFIC = {
-    # (workload, sha256 of csrc/uccl_chunk.hip): bytes per launch
+    # (workload, first 16 hex digits of sha256 of csrc/uccl_chunk.hip): bytes per launch
+    ("config2", "4958e6d038fdf867"): 1007997270,
 }
 
 WORKLOADS = {
