@@ -105,6 +105,7 @@ def main():
     ap.add_argument("--messages", type=int, default=1000, help="config5: number of messages")
     ap.add_argument("--shape", type=int, default=0, help="launch shape id (0 = auto)")
     ap.add_argument("--no-chunk-hint", action="store_true")
+    ap.add_argument("--chunk-hint", type=int, default=None, help="override the chunk-size hint (bytes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--also-warm", action="store_true",
                     help="additionally time the same loop over a single buffer set (cache-resident accumulator)")
@@ -125,6 +126,8 @@ def main():
     pkg.uccl_set_launch_shape(args.shape)
     t0 = time.time()
     w, calls, chunk_bytes = build_job(args.workload, args.seed, args.messages)
+    if args.chunk_hint is not None:
+        chunk_bytes = args.chunk_hint
     if not args.no_chunk_hint:
         pkg.uccl_set_chunk_hint(chunk_bytes)
     print(f"[bench] built {w.name} in {time.time() - t0:.1f}s: {w.note}", file=sys.stderr, flush=True)

@@ -495,7 +495,10 @@ uint32_t flat_tile(uint32_t n_descs) {
   if (g_chunk_hint) {
     t = (32768u + g_chunk_hint - 1) / g_chunk_hint;
   } else {
-    t = n_descs < 16384u ? 1u : n_descs < 65536u ? 4u : 16u;
+    // Unknown chunk size: a tile too large for big chunks costs a few percent, a tile too
+    // small for 4 KiB chunks costs a factor of two, so grow the tile once the record count
+    // leaves enough workgroups either way.
+    t = n_descs < 8192u ? 1u : n_descs < 32768u ? 4u : n_descs < 131072u ? 8u : 16u;
   }
   return t < 1u ? 1u : t > 32u ? 32u : t;
 }

@@ -98,3 +98,38 @@ def test_small_messages_2000(gpu_lib):
     assert_same(bm, oracle.pack_bitmap(seen), "bitmap")
     assert_same(acc, eacc, "acc")
     assert_same(out, eout, "out_stage")
+
+
+def test_bf16_sum_every_pair(gpu_lib):
+    """All 65536 x 65536 pairs of bf16 bit patterns through the SUM path, bit-exact against
+    the oracle (NaN results: NaN-ness only, their payload is not fixed by the method)."""
+    from synth.layout import DESC, NO_FORWARD, BF16
+    blk = 2048                                     # a-values per block: 134 M pairs
+    n = blk * 65536
+    r_np = np.tile(np.arange(65536, dtype=np.uint16), blk)
+    r_dev = to_dev(r_np)
+    pieces = 64
+    d = np.zeros(pieces, dtype=DESC)
+    for k in range(pieces):
+        d[k] = (k * (n // pieces) * 2, k * (n // pieces) * 2, NO_FORWARD, (n // pieces) * 2, k)
+    d_dev = to_dev(d)
+    bm = torch.zeros(pieces // 32, dtype=torch.int32, device="cuda")
+    wide = lambda h: (h.astype(np.uint32) << 16).view(np.float32)
+    t0 = time.time()
+    for b in range(65536 // blk):
+        a_np = np.repeat(np.arange(b * blk, (b + 1) * blk, dtype=np.uint16), 65536)
+        acc = to_dev(a_np)
+        bm.zero_()
+        gpu_lib.uccl_chunk_apply(acc, None, r_dev, d_dev, pieces, bm, BF16, SUM)
+        exp = a_np.copy()
+        seen = oracle.new_seen(pieces)
+        oracle.apply(exp, None, r_np, d, seen, BF16, SUM, check=False)
+        got = acc.cpu().numpy().view(np.uint16)
+        if not np.array_equal(got, exp):
+            nan = np.isnan(wide(exp))
+            assert np.array_equal(np.isnan(wide(got)), nan), f"block {b}: NaN-ness differs"
+            bad = np.flatnonzero((got != exp) & ~nan)
+            assert len(bad) == 0, (f"block {b}: {len(bad)} mismatches, first a={a_np[bad[0]]:#06x} "
+                                   f"r={r_np[bad[0]]:#06x} got={got[bad[0]]:#06x} exp={exp[bad[0]]:#06x}")
+        if b % 8 == 7:
+            say(f"bf16 pairs: block {b + 1}/{65536 // blk} at {time.time() - t0:.0f}s")
