@@ -120,6 +120,24 @@ int uccl_chunk_apply_checked(void* acc, void* out_stage, const void* recv_stage,
                              const uccl_extents* extents, uint32_t* n_rejected, void* stream);
 
 /*
+ * uccl_chunk_apply_indirect -- the same operation fed from a descriptor slot the control
+ * path refills, with no argument changing between launches (Section 5: the receiver CPU
+ * passes the pointer list through CPU-GPU shared memory; Appendix C.4: per-batch kernel
+ * launches are what hurts small messages).  `descs` has room for `max_descs` records and
+ * `*n_descs_ptr` (uint32_t, 4-byte aligned) says how many are live; both may be pinned
+ * host memory mapped into the device (hipHostMalloc) or device memory, and are read when
+ * the kernel runs, not when the call is made.  A count above max_descs is capped.  Because
+ * every argument is fixed, the call can be captured once in a HIP graph and replayed after
+ * the control path has rewritten the slot.  The launch is sized for max_descs.  `extents`
+ * and `n_rejected` are as in uccl_chunk_apply_checked; both may be NULL (unchecked).
+ */
+int uccl_chunk_apply_indirect(void* acc, void* out_stage, const void* recv_stage,
+                              const uccl_chunk_desc* descs, const uint32_t* n_descs_ptr,
+                              uint32_t max_descs, uint32_t* dedup_bitmap, uccl_dtype dtype,
+                              uccl_op op, const uccl_extents* extents, uint32_t* n_rejected,
+                              void* stream);
+
+/*
  * uccl_chunk_scatter -- all-to-all receive side (Section 2.1: copy from transport
  * buffers to tensor buffers; Section 3.1: scattered memcpy): dedup + place + byte copy
  * into `dst` at per-source offsets.  No combine, no forward (out_off must be

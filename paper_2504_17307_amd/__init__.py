@@ -45,6 +45,9 @@ _SIGNATURES = {
     "uccl_chunk_apply_checked": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_uint32, C.c_void_p, C.c_int, C.c_int,
                                            C.POINTER(uccl_extents), C.c_void_p, C.c_void_p]),
+    "uccl_chunk_apply_indirect": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_uint32, C.c_void_p, C.c_int, C.c_int,
+                                            C.POINTER(uccl_extents), C.c_void_p, C.c_void_p]),
     "uccl_chunk_scatter": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
                                      C.c_void_p]),
     "uccl_chunk_scatter_checked": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
@@ -138,6 +141,19 @@ def uccl_chunk_apply_checked(acc, out_stage, recv_stage, descs, n_descs, dedup_b
                                            _ptr(descs), int(n_descs), _ptr(dedup_bitmap),
                                            int(dtype), int(op), C.byref(e), _ptr(n_rejected),
                                            _stream(stream)), "uccl_chunk_apply_checked")
+
+
+def uccl_chunk_apply_indirect(acc, out_stage, recv_stage, descs, n_descs_ptr, max_descs, dedup_bitmap,
+                              dtype, op, extents=None, n_rejected=None, stream=None, n_bits=None):
+    """``descs`` / ``n_descs_ptr`` may be pinned host tensors.  With ``n_bits`` given (or an
+    explicit ``extents``) records are validated on the GPU, otherwise the call is unchecked."""
+    e = None
+    if extents is not None or n_bits is not None:
+        e = C.byref(_extents(extents, acc, out_stage, recv_stage, n_bits))
+    _check(load().uccl_chunk_apply_indirect(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
+                                            _ptr(n_descs_ptr), int(max_descs), _ptr(dedup_bitmap),
+                                            int(dtype), int(op), e, _ptr(n_rejected), _stream(stream)),
+           "uccl_chunk_apply_indirect")
 
 
 def uccl_chunk_scatter(dst, recv_stage, descs, n_descs, dedup_bitmap, stream=None):

@@ -94,6 +94,7 @@ struct Args {
   uint32_t* bitmap;
   uint32_t* rejected;
   Extents ext;
+  const uint32_t* n_ptr;  // optional: the record count is read from here (capped by n_descs)
   uint32_t n_descs;
   uint32_t allow_forward;
 };
@@ -289,9 +290,10 @@ __device__ __forceinline__ void dedup_tile(const Args& g, Tile<T>& s, uint32_t t
   bool win = false;
   uint64_t src = 0, dst = 0, out = 0;
   uint32_t len = 0;
-  if (tid < T && k < g.n_descs) {
+  if (tid < T && k < g.n_descs) {  // inside the array's capacity: safe to load
     const u32x4* p = reinterpret_cast<const u32x4*>(g.descs + k);
     const u32x4 lo = p[0], hi = p[1];
+    const uint32_t live = g.n_ptr != nullptr ? *g.n_ptr : g.n_descs;
     src = lo.x | (static_cast<uint64_t>(lo.y) << 32);
     dst = lo.z | (static_cast<uint64_t>(lo.w) << 32);
     out = hi.x | (static_cast<uint64_t>(hi.y) << 32);
@@ -304,7 +306,9 @@ __device__ __forceinline__ void dedup_tile(const Args& g, Tile<T>& s, uint32_t t
     if (fwd)
       ok = ok && g.allow_forward && g.out != nullptr && (out & 15u) == 0 &&
            out <= g.ext.out_bytes && len <= g.ext.out_bytes - out;
-    if (ok) {
+    if (k >= live) {
+      // beyond the published count: not a record at all, neither applied nor rejected
+    } else if (ok) {
       const uint32_t bit = 1u << (seq & 31u);
       const uint32_t old = atomicOr(g.bitmap + (seq >> 5), bit);  // device scope, relaxed
       win = (old & bit) == 0;
@@ -535,13 +539,15 @@ bool overlaps(const void* p, uint64_t pn, const void* q, uint64_t qn) {
 
 int apply_common(void* acc, void* out_stage, const void* recv_stage, const uccl_chunk_desc* descs,
                  uint32_t n_descs, uint32_t* bitmap, int dtype, int op, bool allow_forward,
-                 const uccl_extents* ext, uint32_t* n_rejected, void* stream) {
+                 const uccl_extents* ext, uint32_t* n_rejected, void* stream,
+                 const uint32_t* n_ptr = nullptr) {
   if (dtype != UCCL_F32 && dtype != UCCL_BF16) return UCCL_EINVAL;
   if (op < UCCL_SUM || op > UCCL_COPY) return UCCL_EINVAL;
   if (n_descs == 0) return UCCL_OK;
   if (!acc || !recv_stage || !descs || !bitmap) return UCCL_EINVAL;
   if (misaligned(acc, 16) || misaligned(out_stage, 16) || misaligned(recv_stage, 16) ||
-      misaligned(descs, 16) || misaligned(bitmap, 4) || misaligned(n_rejected, 4))
+      misaligned(descs, 16) || misaligned(bitmap, 4) || misaligned(n_rejected, 4) ||
+      misaligned(n_ptr, 4))
     return UCCL_EALIGN;
   Args a;
   a.acc = static_cast<char*>(acc);
@@ -550,6 +556,7 @@ int apply_common(void* acc, void* out_stage, const void* recv_stage, const uccl_
   a.descs = descs;
   a.bitmap = bitmap;
   a.rejected = n_rejected;
+  a.n_ptr = n_ptr;
   a.n_descs = n_descs;
   a.allow_forward = allow_forward ? 1u : 0u;
   if (ext) {
@@ -591,6 +598,16 @@ int uccl_chunk_apply_checked(void* acc, void* out_stage, const void* recv_stage,
   if (!extents) return UCCL_EINVAL;
   return apply_common(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, true,
                       extents, n_rejected, stream);
+}
+
+int uccl_chunk_apply_indirect(void* acc, void* out_stage, const void* recv_stage,
+                              const uccl_chunk_desc* descs, const uint32_t* n_descs_ptr,
+                              uint32_t max_descs, uint32_t* dedup_bitmap, uccl_dtype dtype,
+                              uccl_op op, const uccl_extents* extents, uint32_t* n_rejected,
+                              void* stream) {
+  if (max_descs > 0 && !n_descs_ptr) return UCCL_EINVAL;
+  return apply_common(acc, out_stage, recv_stage, descs, max_descs, dedup_bitmap, dtype, op, true,
+                      extents, n_rejected, stream, n_descs_ptr);
 }
 
 int uccl_chunk_scatter(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,

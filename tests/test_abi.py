@@ -19,7 +19,7 @@ def test_library_exports_every_declared_symbol():
     lib = pkg.load()
     names = declared_functions()
     assert {"uccl_chunk_apply", "uccl_chunk_scatter", "uccl_dedup_reset", "uccl_strerror",
-            "uccl_version", "uccl_chunk_apply_checked", "uccl_chunk_scatter_checked",
+            "uccl_version", "uccl_chunk_apply_checked", "uccl_chunk_apply_indirect", "uccl_chunk_scatter_checked",
             "uccl_set_launch_shape", "uccl_set_chunk_hint", "uccl_time_next_launch",
             "uccl_last_error_detail"} <= set(names)
     for n in names:
@@ -61,6 +61,10 @@ def test_host_side_error_codes_enqueue_nothing():
     assert g(A, None, B, D, 1, M, 0, 0, C.byref(e), None, None) == pkg.UCCL_EINVAL
     e = pkg.uccl_extents(0x1000, 0, 0x1000, 8)
     assert g(A, None, B, D, 1, M, 0, 0, C.byref(e), 0x50002, None) == pkg.UCCL_EALIGN
+    i = lib.uccl_chunk_apply_indirect
+    assert i(A, None, B, D, None, 4, M, 0, 0, None, None, None) == pkg.UCCL_EINVAL   # count pointer required
+    assert i(A, None, B, D, 0x60002, 4, M, 0, 0, None, None, None) == pkg.UCCL_EALIGN
+    assert i(None, None, None, None, None, 0, None, 0, 0, None, None, None) == pkg.UCCL_OK
     s = lib.uccl_chunk_scatter
     assert s(None, B, D, 1, M, None) == pkg.UCCL_EINVAL
     assert s(A + 1, B, D, 1, M, None) == pkg.UCCL_EALIGN

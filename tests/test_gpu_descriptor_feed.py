@@ -1,0 +1,110 @@
+"""Descriptor feed without per-batch argument changes: records and their count live in a
+slot (pinned host memory, mapped into the device) that the control path rewrites; the
+library call has fixed arguments, is captured once in a graph and replayed per message."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from synth import workloads as wl
+from synth.layout import DESC, NO_FORWARD, F32, SUM, COPY
+
+from gpuhelp import DeviceRun, oracle_results, assert_same, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def pinned(nbytes):
+    t = torch.zeros(nbytes, dtype=torch.uint8, pin_memory=True)
+    return t, t.numpy()
+
+
+def test_records_read_from_pinned_host_memory(gpu_lib):
+    w = wl.config2(seed=3, M=8 << 20)
+    eacc, eout, ebm = oracle_results(w)
+    run = DeviceRun(w)
+    keep = []
+    for ph in w.phases:
+        t, v = pinned(ph.descs.nbytes)
+        v[:] = ph.descs.view(np.uint8).reshape(-1)
+        keep.append(t)
+        run.apply(t, len(ph.descs), ph.op)
+    torch.cuda.synchronize()
+    acc, out, bm, rej = run.results()
+    assert rej == 0
+    assert_same(acc, eacc, "acc"); assert_same(out, eout, "out"); assert_same(bm, ebm, "bitmap")
+
+
+def test_indirect_count(gpu_lib):
+    w = wl.config2(seed=4, M=8 << 20)
+    ph = w.phases[0]
+    n = len(ph.descs)
+    cnt_t, cnt_v = pinned(4)
+    for live in (0, 1, n // 3, n, n + 1000):
+        run = DeviceRun(w)
+        cnt_v.view(np.uint32)[0] = live
+        gpu_lib.uccl_chunk_apply_indirect(run.acc, run.out, run.recv, run.descs[0], cnt_t, n, run.bitmap,
+                                          w.dtype, ph.op, n_rejected=run.rejected, n_bits=w.n_bits)
+        torch.cuda.synchronize()
+        acc, out, bm, rej = run.results()
+        eacc, eout, seen = w.acc.copy(), np.full(w.out_bytes, 0xA5, np.uint8), oracle.new_seen(w.n_bits)
+        oracle.apply(eacc, eout, w.recv_stage, ph.descs[:min(live, n)], seen, w.dtype, ph.op)
+        assert rej == 0
+        assert_same(acc, eacc, f"acc live={live}"); assert_same(out, eout, "out")
+        assert_same(bm, oracle.pack_bitmap(seen), "bitmap")
+    # device-resident count, unchecked call
+    run = DeviceRun(w)
+    cnt_d = torch.tensor([n // 2], dtype=torch.int32, device="cuda")
+    gpu_lib.uccl_chunk_apply_indirect(run.acc, run.out, run.recv, run.descs[0], cnt_d, n, run.bitmap, w.dtype, ph.op)
+    torch.cuda.synchronize()
+    eacc, eout, seen = w.acc.copy(), np.full(w.out_bytes, 0xA5, np.uint8), oracle.new_seen(w.n_bits)
+    oracle.apply(eacc, eout, w.recv_stage, ph.descs[:n // 2], seen, w.dtype, ph.op)
+    assert_same(run.results()[0], eacc, "acc")
+
+
+def test_graph_replay_per_message(gpu_lib):
+    """One captured graph (reduce-scatter call + allgather call on fixed arguments) replayed for
+    every message after the host rewrote the slot; every replay is checked against the oracle,
+    with eager work and synchronisation between replays."""
+    w, msgs = wl.config5(seed=6, n_msgs=24)
+    cap = max(max(len(m["rs"]), len(m["ag"])) for m in msgs) + 7
+    run = DeviceRun(w, guard=0)
+    slots = {k: pinned(cap * 32) for k in ("rs", "ag")}
+    counts_t, counts_v = pinned(8)
+    counts = counts_v.view(np.uint32)
+    gpu_lib.uccl_set_chunk_hint(4096)
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(g, stream=side):
+        gpu_lib.uccl_chunk_apply_indirect(run.acc, run.out, run.recv, slots["rs"][0], counts_t[0:4], cap,
+                                          run.bitmap, F32, SUM, n_rejected=run.rejected, n_bits=w.n_bits)
+        gpu_lib.uccl_chunk_apply_indirect(run.acc, run.out, run.recv, slots["ag"][0], counts_t[4:8], cap,
+                                          run.bitmap, F32, COPY, n_rejected=run.rejected, n_bits=w.n_bits)
+    gpu_lib.uccl_set_chunk_hint(0)
+    eacc = w.acc.copy()
+    eout = np.zeros(w.out_bytes, dtype=np.uint8)
+    seen = oracle.new_seen(w.n_bits)
+    scratch = torch.zeros(1 << 16, device="cuda")
+    for i, m in enumerate(msgs):
+        for j, key in enumerate(("rs", "ag")):
+            d = m[key].view(np.uint8).reshape(-1)
+            slots[key][1][:len(d)] = d
+            slots[key][1][len(d):] = 0xFF  # stale bytes beyond the count must never be used
+            counts[j] = len(m[key])
+        g.replay()
+        torch.cuda.synchronize()
+        scratch.add_(1.0).sum().item()  # the program's own eager work between replays
+        oracle.apply(eacc, eout, w.recv_stage, m["rs"], seen, F32, SUM)
+        oracle.apply(eacc, eout, w.recv_stage, m["ag"], seen, F32, COPY)
+        acc, out, bm, rej = run.results()
+        assert rej == 0, f"message {i}"
+        assert_same(bm, oracle.pack_bitmap(seen), f"bitmap after message {i}")
+        assert_same(acc, eacc, f"acc after message {i}")
+        assert_same(out, eout, f"out after message {i}")
+    counts[:] = 0
+    g.replay()  # an empty slot is a no-op
+    torch.cuda.synchronize()
+    assert_same(run.results()[0], eacc, "acc after empty replay")
