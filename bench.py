@@ -58,19 +58,21 @@ def call_stats(descs, op):
     costs its 32 bytes and one 4-byte bitmap word update."""
     _, first = np.unique(descs["seq"], return_index=True)
     ln = descs["len"][first].astype(np.int64)
-    fwd = descs["out_off"][first] != np.uint64(0xFFFFFFFFFFFFFFFF)
+    off = descs["out_off"][first]
+    fwd = off != np.uint64(0xFFFFFFFFFFFFFFFF)
+    relay = fwd & ((off & np.uint64(0x8000000000000000)) != 0)  # forwarded, not written back
     reads = ln if op == 3 else 2 * ln
-    algo = int(reads.sum() + ln.sum() + ln[fwd].sum()) + 36 * len(descs)
+    algo = int(reads.sum() + ln[~relay].sum() + ln[fwd].sum()) + 36 * len(descs)
     return len(first), int(ln.sum()), algo
 
 
-def build_job(name, seed, n_msgs):
+def build_job(name, seed, n_msgs, relay=False):
     """Returns (workload, calls, chunk_bytes) with calls = list of dicts
     {name, op, descs (numpy), n_unique, payload_bytes, algo_bytes, scatter}."""
     from synth import workloads as wl
     from synth.layout import SUM, COPY
     if name in ("config1", "config2", "config3"):
-        w = getattr(wl, name)(seed=seed)
+        w = getattr(wl, name)(seed=seed, relay=relay)
         calls = [dict(name=ph.name, op=ph.op, descs=ph.descs, n_unique=ph.n_unique,
                       payload_bytes=ph.payload_bytes, algo_bytes=ph.algo_bytes, scatter=False)
                  for ph in w.phases]
@@ -224,6 +226,9 @@ def main():
     ap.add_argument("--shape", type=int, default=0, help="launch shape id (0 = auto)")
     ap.add_argument("--no-chunk-hint", action="store_true")
     ap.add_argument("--chunk-hint", type=int, default=None, help="override the chunk-size hint (bytes)")
+    ap.add_argument("--relay", action="store_true",
+                    help="ring workloads: flag intermediate reduce-scatter steps forward-only (their partial "
+                         "sums are not written back to the accumulator: 3 instead of 4 bytes per payload byte)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--also-warm", action="store_true",
                     help="additionally time the same loop over a single buffer set (cache-resident accumulator)")
@@ -245,7 +250,7 @@ def main():
     if args.workload == "config5-graph":
         return bench_graph_feed(args, pkg, torch)
     t0 = time.time()
-    w, calls, chunk_bytes = build_job(args.workload, args.seed, args.messages)
+    w, calls, chunk_bytes = build_job(args.workload, args.seed, args.messages, args.relay)
     if args.chunk_hint is not None:
         chunk_bytes = args.chunk_hint
     if not args.no_chunk_hint:
@@ -363,6 +368,7 @@ def main():
                    "unique_chunks": unique, "arrivals": arrivals, "payload_bytes": payload,
                    "algorithmic_bytes": algo, "launch_shape": args.shape,
                    "chunk_hint": 0 if args.no_chunk_hint else chunk_bytes, "buffer_sets": len(sets),
+                   "forward_only_intermediate_steps": bool(args.relay),
                    "calls_per_step": 1 + len(calls), "cache": cache_note},
         "chunks_per_s": round(unique / per_step, 1),
         "arrivals_per_s": round(arrivals / per_step, 1),

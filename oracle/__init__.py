@@ -21,6 +21,7 @@ CFLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contrac
 F32, BF16 = 0, 1
 SUM, MAX, MIN, COPY = 0, 1, 2, 3
 NO_FORWARD = 0xFFFFFFFFFFFFFFFF
+FORWARD_ONLY = 0x8000000000000000
 ERRORS = {-1: "ARG", -2: "SEQ", -3: "ALIGN", -4: "BOUNDS", -5: "MISMATCH", -6: "OVERLAP"}
 
 DESC = np.dtype([("src_off", "<u8"), ("dst_off", "<u8"), ("out_off", "<u8"),

@@ -62,12 +62,13 @@ static int64_t check_record(const orc_desc* d, uint64_t acc_bytes, uint64_t out_
                             int have_out, uint64_t recv_bytes, uint64_t n_bits, uint32_t es) {
   if (d->seq >= n_bits) return ORC_E_SEQ;
   if ((d->src_off | d->dst_off) & 15u) return ORC_E_ALIGN;
-  if (d->out_off != ORC_NO_FORWARD && (d->out_off & 15u)) return ORC_E_ALIGN;
+  const uint64_t out_at = d->out_off & ~ORC_FORWARD_ONLY;
+  if (d->out_off != ORC_NO_FORWARD && (out_at & 15u)) return ORC_E_ALIGN;
   if (d->len % es) return ORC_E_ALIGN;
   if (!range_ok(d->src_off, d->len, recv_bytes)) return ORC_E_BOUNDS;
   if (!range_ok(d->dst_off, d->len, acc_bytes)) return ORC_E_BOUNDS;
   if (d->out_off != ORC_NO_FORWARD) {
-    if (!have_out || !range_ok(d->out_off, d->len, out_bytes)) return ORC_E_BOUNDS;
+    if (!have_out || !range_ok(out_at, d->len, out_bytes)) return ORC_E_BOUNDS;
   }
   return 0;
 }
@@ -92,22 +93,24 @@ int64_t orc_apply(void* acc, uint64_t acc_bytes, void* out_stage, uint64_t out_b
     ++applied;
     const uint64_t n = d->len / es;
     const int fwd = d->out_off != ORC_NO_FORWARD;
+    const int keep = !(fwd && (d->out_off & ORC_FORWARD_ONLY)); /* write the result back to acc */
+    const uint64_t out_at = d->out_off & ~ORC_FORWARD_ONLY;
     if (dtype == ORC_F32) {
       const float* r = (const float*)((const char*)recv_stage + d->src_off);
       float* a = (float*)((char*)acc + d->dst_off);
-      float* o = fwd ? (float*)((char*)out_stage + d->out_off) : NULL;
+      float* o = fwd ? (float*)((char*)out_stage + out_at) : NULL;
       for (uint64_t i = 0; i < n; ++i) {
         float t = orc_combine_f32(a[i], r[i], op);
-        a[i] = t;
+        if (keep) a[i] = t;
         if (fwd) o[i] = t;
       }
     } else {
       const uint16_t* r = (const uint16_t*)((const char*)recv_stage + d->src_off);
       uint16_t* a = (uint16_t*)((char*)acc + d->dst_off);
-      uint16_t* o = fwd ? (uint16_t*)((char*)out_stage + d->out_off) : NULL;
+      uint16_t* o = fwd ? (uint16_t*)((char*)out_stage + out_at) : NULL;
       for (uint64_t i = 0; i < n; ++i) {
         uint16_t t = orc_combine_bf16(a[i], r[i], op);
-        a[i] = t;
+        if (keep) a[i] = t;
         if (fwd) o[i] = t;
       }
     }
@@ -185,6 +188,7 @@ int64_t orc_check_call(const void* recv_stage, uint64_t recv_bytes, const orc_de
       if (d->len == 0) continue;
       uint64_t off = pass == 0 ? d->dst_off : d->out_off;
       if (pass == 1 && off == ORC_NO_FORWARD) continue;
+      if (pass == 1) off &= ~ORC_FORWARD_ONLY;
       w[m].key = off; w[m].end = off + d->len; w[m].idx = k; ++m;
     }
     qsort(w, m, sizeof(ivl), cmp_ivl);

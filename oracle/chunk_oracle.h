@@ -39,6 +39,8 @@ typedef struct {
 } orc_desc;
 
 #define ORC_NO_FORWARD 0xFFFFFFFFFFFFFFFFull
+/* flag in out_off: the combined value goes to out_stage only, acc is read but not written */
+#define ORC_FORWARD_ONLY 0x8000000000000000ull
 
 enum { ORC_F32 = 0, ORC_BF16 = 1 };
 enum { ORC_SUM = 0, ORC_MAX = 1, ORC_MIN = 2, ORC_COPY = 3 };

@@ -63,6 +63,12 @@
 #ifndef UCCL_POLICY_COPY_FWD
 #define UCCL_POLICY_COPY_FWD 0xC
 #endif
+#ifndef UCCL_POLICY_REDUCE_RELAY
+#define UCCL_POLICY_REDUCE_RELAY 0xE  // forward-only: the accumulator is read once and not written
+#endif
+#ifndef UCCL_POLICY_COPY_RELAY
+#define UCCL_POLICY_COPY_RELAY 0xC
+#endif
 #ifndef UCCL_POLICY_COPY_KEEP
 #define UCCL_POLICY_COPY_KEEP 0x9
 #endif
@@ -175,6 +181,14 @@ struct Copy {
   static __device__ __forceinline__ uint32_t word(uint32_t, uint32_t r) { return r; }
 };
 
+// Which streams of a chunk exist: FWD = the staging copy is written, WB = the accumulator
+// is written back (a forward-only record relays the combined value without keeping it).
+template <class Op, bool FWD, bool WB>
+constexpr uint32_t cache_policy() {
+  if (Op::kReadsAcc) return FWD ? (WB ? UCCL_POLICY_REDUCE_FWD : UCCL_POLICY_REDUCE_RELAY) : UCCL_POLICY_REDUCE_KEEP;
+  return FWD ? (WB ? UCCL_POLICY_COPY_FWD : UCCL_POLICY_COPY_RELAY) : UCCL_POLICY_COPY_KEEP;
+}
+
 template <class Op>
 __device__ __forceinline__ u32x4 combine(u32x4 a, u32x4 r) {
   u32x4 t;
@@ -194,12 +208,11 @@ __device__ __forceinline__ uint64_t wave_uniform(uint64_t v) {
 // Stream one chunk with SG cooperating threads: U independent 16-byte vectors per thread
 // per trip, loads first, then combine and store.  Which streams carry a non-temporal
 // hint depends on the kind of chunk (see the policy masks above).
-template <int SG, int U, class Op, bool FWD>
+template <int SG, int U, class Op, bool FWD, bool WB>
 __device__ __forceinline__ void stream_vectors(const u32x4* __restrict__ r, u32x4* __restrict__ a,
                                                u32x4* __restrict__ o, uint32_t nvec,
                                                uint32_t lane) {
-  constexpr uint32_t kPolicy = Op::kReadsAcc ? (FWD ? UCCL_POLICY_REDUCE_FWD : UCCL_POLICY_REDUCE_KEEP)
-                                             : (FWD ? UCCL_POLICY_COPY_FWD : UCCL_POLICY_COPY_KEEP);
+  constexpr uint32_t kPolicy = cache_policy<Op, FWD, WB>();
   constexpr bool kNtRecv = (kPolicy & 8u) != 0, kNtOut = (kPolicy & 4u) != 0;
   constexpr bool kNtAccLoad = (kPolicy & 2u) != 0, kNtAccStore = (kPolicy & 1u) != 0;
   constexpr uint32_t kTrip = SG * U;
@@ -216,7 +229,7 @@ __device__ __forceinline__ void stream_vectors(const u32x4* __restrict__ r, u32x
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const u32x4 t = combine<Op>(av[u], rv[u]);
-      store16<kNtAccStore>(a + base + u * SG, t);
+      if (WB) store16<kNtAccStore>(a + base + u * SG, t);
       if (FWD) store16<kNtOut>(o + base + u * SG, t);
     }
   }
@@ -225,48 +238,48 @@ __device__ __forceinline__ void stream_vectors(const u32x4* __restrict__ r, u32x
     u32x4 av = rv;
     if constexpr (Op::kReadsAcc) av = load16<kNtAccLoad>(a + i);
     const u32x4 t = combine<Op>(av, rv);
-    store16<kNtAccStore>(a + i, t);
+    if (WB) store16<kNtAccStore>(a + i, t);
     if (FWD) store16<kNtOut>(o + i, t);
   }
 }
 
 // The last len % 16 bytes of a chunk, element by element.
-template <class Op, bool FWD>
+template <class Op, bool FWD, bool WB>
 __device__ __forceinline__ void stream_tail(const char* r, char* a, char* o, uint32_t rem,
                                             uint32_t lane) {
   if constexpr (Op::kEs == 4) {
     if (lane < rem / 4) {
       uint32_t* ap = reinterpret_cast<uint32_t*>(a) + lane;
       const uint32_t t = Op::word(*ap, reinterpret_cast<const uint32_t*>(r)[lane]);
-      *ap = t;
+      if (WB) *ap = t;
       if (FWD) reinterpret_cast<uint32_t*>(o)[lane] = t;
     }
   } else if constexpr (Op::kEs == 2) {
     if (lane < rem / 2) {
       uint16_t* ap = reinterpret_cast<uint16_t*>(a) + lane;
       const uint32_t t = Op::half(*ap, reinterpret_cast<const uint16_t*>(r)[lane]);
-      *ap = static_cast<uint16_t>(t);
+      if (WB) *ap = static_cast<uint16_t>(t);
       if (FWD) reinterpret_cast<uint16_t*>(o)[lane] = static_cast<uint16_t>(t);
     }
   } else {
     if (lane < rem) {
       const char t = r[lane];
-      a[lane] = t;
+      if (WB) a[lane] = t;
       if (FWD) o[lane] = t;
     }
   }
 }
 
-template <int SG, int U, class Op, bool FWD>
+template <int SG, int U, class Op, bool FWD, bool WB>
 __device__ __forceinline__ void stream_chunk(const char* r, char* a, char* o, uint32_t len,
                                              uint32_t lane) {
   const uint32_t nvec = len >> 4;
-  stream_vectors<SG, U, Op, FWD>(reinterpret_cast<const u32x4*>(r), reinterpret_cast<u32x4*>(a),
+  stream_vectors<SG, U, Op, FWD, WB>(reinterpret_cast<const u32x4*>(r), reinterpret_cast<u32x4*>(a),
                                  reinterpret_cast<u32x4*>(o), nvec, lane);
   const uint32_t rem = len & 15u;
   if (rem) {
     const uint64_t off = static_cast<uint64_t>(nvec) << 4;
-    stream_tail<Op, FWD>(r + off, a + off, FWD ? o + off : o, rem, lane);
+    stream_tail<Op, FWD, WB>(r + off, a + off, FWD ? o + off : o, rem, lane);
   }
 }
 
@@ -300,12 +313,13 @@ __device__ __forceinline__ void dedup_tile(const Args& g, Tile<T>& s, uint32_t t
     len = hi.z;
     const uint32_t seq = hi.w;
     const bool fwd = out != UCCL_NO_FORWARD;
+    const uint64_t out_at = out & ~UCCL_FORWARD_ONLY;
     bool ok = seq < g.ext.n_bits && ((src | dst) & 15u) == 0 && len % Op::kEs == 0 &&
               src <= g.ext.recv_bytes && len <= g.ext.recv_bytes - src &&
               dst <= g.ext.acc_bytes && len <= g.ext.acc_bytes - dst;
     if (fwd)
-      ok = ok && g.allow_forward && g.out != nullptr && (out & 15u) == 0 &&
-           out <= g.ext.out_bytes && len <= g.ext.out_bytes - out;
+      ok = ok && g.allow_forward && g.out != nullptr && (out_at & 15u) == 0 &&
+           out_at <= g.ext.out_bytes && len <= g.ext.out_bytes - out_at;
     if (k >= live) {
       // beyond the published count: not a record at all, neither applied nor rejected
     } else if (ok) {
@@ -359,19 +373,20 @@ __global__ void __launch_bounds__(NT) chunk_apply_kernel(const Args g) {
     const uint64_t dst = wave_uniform(s.dst[w]);
     const uint64_t out = wave_uniform(s.out[w]);
     const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
-    if (out != UCCL_NO_FORWARD)
-      stream_chunk<SG, U, Op, true>(g.recv + src, g.acc + dst, g.out + out, len, lane);
+    if (out == UCCL_NO_FORWARD)
+      stream_chunk<SG, U, Op, false, true>(g.recv + src, g.acc + dst, nullptr, len, lane);
+    else if (out & UCCL_FORWARD_ONLY)
+      stream_chunk<SG, U, Op, true, false>(g.recv + src, g.acc + dst, g.out + (out & ~UCCL_FORWARD_ONLY), len, lane);
     else
-      stream_chunk<SG, U, Op, false>(g.recv + src, g.acc + dst, nullptr, len, lane);
+      stream_chunk<SG, U, Op, true, true>(g.recv + src, g.acc + dst, g.out + out, len, lane);
   }
 }
 
 // One unit = 64*U consecutive 16-byte vectors of a chunk, streamed by one wavefront.
-template <int U, class Op, bool FWD>
+template <int U, class Op, bool FWD, bool WB>
 __device__ __forceinline__ void stream_unit(const char* r, char* a, char* o, uint32_t len,
                                             uint32_t trip, uint32_t lane) {
-  constexpr uint32_t kPolicy = Op::kReadsAcc ? (FWD ? UCCL_POLICY_REDUCE_FWD : UCCL_POLICY_REDUCE_KEEP)
-                                             : (FWD ? UCCL_POLICY_COPY_FWD : UCCL_POLICY_COPY_KEEP);
+  constexpr uint32_t kPolicy = cache_policy<Op, FWD, WB>();
   constexpr bool kNtRecv = (kPolicy & 8u) != 0, kNtOut = (kPolicy & 4u) != 0;
   constexpr bool kNtAccLoad = (kPolicy & 2u) != 0, kNtAccStore = (kPolicy & 1u) != 0;
   constexpr uint32_t kUnit = 64u * U;
@@ -392,7 +407,7 @@ __device__ __forceinline__ void stream_unit(const char* r, char* a, char* o, uin
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       const u32x4 t = combine<Op>(av[u], rv[u]);
-      store16<kNtAccStore>(ap + u * 64, t);
+      if (WB) store16<kNtAccStore>(ap + u * 64, t);
       if (FWD) store16<kNtOut>(op + u * 64, t);
     }
     return;
@@ -405,14 +420,14 @@ __device__ __forceinline__ void stream_unit(const char* r, char* a, char* o, uin
       u32x4 av = rv;
       if constexpr (Op::kReadsAcc) av = load16<kNtAccLoad>(ap + u * 64);
       const u32x4 t = combine<Op>(av, rv);
-      store16<kNtAccStore>(ap + u * 64, t);
+      if (WB) store16<kNtAccStore>(ap + u * 64, t);
       if (FWD) store16<kNtOut>(op + u * 64, t);
     }
   }
   const uint32_t rem = len & 15u;
   if (rem) {  // nvec lies in this unit, or the chunk would have had one unit fewer
     const uint64_t off = static_cast<uint64_t>(nvec) << 4;
-    stream_tail<Op, FWD>(r + off, a + off, FWD ? o + off : o, rem, lane);
+    stream_tail<Op, FWD, WB>(r + off, a + off, FWD ? o + off : o, rem, lane);
   }
 }
 
@@ -443,10 +458,12 @@ __global__ void __launch_bounds__(NT) chunk_flat_kernel(const Args g) {
     const uint64_t dst = wave_uniform(s.dst[w]);
     const uint64_t out = wave_uniform(s.out[w]);
     const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
-    if (out != UCCL_NO_FORWARD)
-      stream_unit<U, Op, true>(g.recv + src, g.acc + dst, g.out + out, len, trip, lane);
+    if (out == UCCL_NO_FORWARD)
+      stream_unit<U, Op, false, true>(g.recv + src, g.acc + dst, nullptr, len, trip, lane);
+    else if (out & UCCL_FORWARD_ONLY)
+      stream_unit<U, Op, true, false>(g.recv + src, g.acc + dst, g.out + (out & ~UCCL_FORWARD_ONLY), len, trip, lane);
     else
-      stream_unit<U, Op, false>(g.recv + src, g.acc + dst, nullptr, len, trip, lane);
+      stream_unit<U, Op, true, true>(g.recv + src, g.acc + dst, g.out + out, len, trip, lane);
   }
 }
 

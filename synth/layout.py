@@ -21,6 +21,7 @@ DESC = np.dtype(
 assert DESC.itemsize == 32
 
 NO_FORWARD = np.uint64(0xFFFFFFFFFFFFFFFF)
+FORWARD_ONLY = np.uint64(0x8000000000000000)  # flag in out_off: relay the result, do not write acc
 
 # dtype / op codes shared by every caller (values are part of the C ABI)
 F32, BF16 = 0, 1

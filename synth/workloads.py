@@ -23,7 +23,7 @@ import numpy as np
 
 from . import payload as pl
 from .arrivals import gen_arrivals, identity_arrivals, merge_streams
-from .layout import DESC, NO_FORWARD, ELEM_SIZE, SUM, COPY, F32, BF16
+from .layout import DESC, NO_FORWARD, FORWARD_ONLY, ELEM_SIZE, SUM, COPY, F32, BF16
 
 LOGICAL = np.dtype([("seq", "<u4"), ("dst_off", "<u8"), ("out_off", "<u8"), ("len", "<u4")])
 
@@ -61,21 +61,24 @@ def byte_model(op: int, logical: np.ndarray, n_arrivals: int) -> int:
     its 32-byte record and one 4-byte bitmap word update."""
     ln = logical["len"].astype(np.int64)
     fwd = logical["out_off"] != NO_FORWARD
+    relay = fwd & ((logical["out_off"] & FORWARD_ONLY) != 0)  # forwarded but not written back
     reads = ln if op == COPY else 2 * ln
-    writes = ln + np.where(fwd, ln, 0)
+    writes = np.where(relay, 0, ln) + np.where(fwd, ln, 0)
     return int(reads.sum() + writes.sum()) + 36 * int(n_arrivals)
 
 
 def ring_logical(R: int, M: int, C: int, rank: int = 0, allgather: bool = True,
                  forward_last_rs: Optional[bool] = None, seq_base: int = 0,
-                 acc_base: int = 0, out_base: int = 0):
+                 acc_base: int = 0, out_base: int = 0, relay: bool = False):
     """Logical chunks one rank receives in a ring allreduce (or reduce-scatter).
 
     Returns (rs, ag, n_out_chunks): LOGICAL arrays in sender order.  Sequence
     numbers run step-major over both phases; forwarded chunks get consecutive
     C-byte slots of the staging buffer.  ``forward_last_rs`` defaults to
     ``allgather`` (an allreduce sends the finished segment on; a bare
-    reduce-scatter keeps it).
+    reduce-scatter keeps it).  With ``relay`` the intermediate reduce-scatter steps
+    (all but the last) carry the forward-only flag: their partial sums are needed by
+    the next rank only and are not written back to the accumulator.
     """
     assert M % R == 0
     if forward_last_rs is None:
@@ -84,7 +87,7 @@ def ring_logical(R: int, M: int, C: int, rank: int = 0, allgather: bool = True,
     cps = -(-S // C)
     n_out = 0
 
-    def build(steps, seg_of, fwd_of, seq0):
+    def build(steps, seg_of, fwd_of, seq0, relay_of=lambda s: False):
         nonlocal n_out
         rec = np.zeros(steps * cps, dtype=LOGICAL)
         k = 0
@@ -96,14 +99,15 @@ def ring_logical(R: int, M: int, C: int, rank: int = 0, allgather: bool = True,
                 rec[k]["dst_off"] = acc_base + seg * S + c * C
                 rec[k]["len"] = ln
                 if fwd_of(s):
-                    rec[k]["out_off"] = out_base + n_out * C
+                    rec[k]["out_off"] = np.uint64(out_base + n_out * C) | (FORWARD_ONLY if relay_of(s) else np.uint64(0))
                     n_out += 1
                 else:
                     rec[k]["out_off"] = NO_FORWARD
                 k += 1
         return rec
 
-    rs = build(R - 1, lambda s: rank - s - 1, lambda s: s < R - 2 or forward_last_rs, seq_base)
+    rs = build(R - 1, lambda s: rank - s - 1, lambda s: s < R - 2 or forward_last_rs, seq_base,
+               lambda s: relay and s < R - 2)
     if allgather:
         ag = build(R - 1, lambda s: rank - s, lambda s: s < R - 2, seq_base + (R - 1) * cps)
     else:
@@ -150,7 +154,7 @@ def _draw(dist: str, dtype: int, seed: int, stream: int, n: int) -> np.ndarray:
 
 def ring_share(name: str, seed: int, R: int, M: int, C: int, dtype: int, paths: int,
                window, dup: float, dist: str, allgather: bool = True, op: int = SUM,
-               identity: bool = False, arrival_seed=None, arrivals=None) -> Workload:
+               identity: bool = False, arrival_seed=None, arrivals=None, relay: bool = False) -> Workload:
     """One rank's receive share of a ring allreduce (allgather=True) or ring
     reduce-scatter, with i.i.d. payload values from ``dist``.
 
@@ -160,7 +164,7 @@ def ring_share(name: str, seed: int, R: int, M: int, C: int, dtype: int, paths: 
     stream can be replayed under different interleavings."""
     es = ELEM_SIZE[dtype]
     assert C % 16 == 0 and (M // R) % es == 0
-    rs, ag, n_out = ring_logical(R, M, C, allgather=allgather)
+    rs, ag, n_out = ring_logical(R, M, C, allgather=allgather, relay=relay)
     acc = _draw(dist, dtype, seed, 1, M // es)
     phases_l = [("reduce-scatter", op, rs)] + ([("allgather", COPY, ag)] if allgather else [])
     arrs = []

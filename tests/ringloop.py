@@ -13,11 +13,11 @@ library), passed in as an object with:
 import numpy as np
 
 from synth.arrivals import gen_arrivals
-from synth.layout import COPY, ELEM_SIZE
+from synth.layout import COPY, ELEM_SIZE, FORWARD_ONLY
 from synth.workloads import ring_logical, materialize
 
 
-def closed_loop_allreduce(backend, x, dtype, C, seed, paths=4, window=None, dup=0.1, op=0):
+def closed_loop_allreduce(backend, x, dtype, C, seed, paths=4, window=None, dup=0.1, op=0, relay=False):
     R, n = x.shape
     es = ELEM_SIZE[dtype]
     M = n * es
@@ -26,7 +26,7 @@ def closed_loop_allreduce(backend, x, dtype, C, seed, paths=4, window=None, dup=
     xb = np.ascontiguousarray(x).view(np.uint8).reshape(R, M)
     plans, ranks = [], []
     for r in range(R):
-        rs, ag, n_out = ring_logical(R, M, C, rank=r)
+        rs, ag, n_out = ring_logical(R, M, C, rank=r, relay=relay)
         plans.append((rs, ag))
         ranks.append(backend.make_rank(x[r].copy(), n_out * C, len(rs) + len(ag)))
     prev = [None] * R  # LOGICAL records of what each rank produced in the previous step
@@ -45,7 +45,8 @@ def closed_loop_allreduce(backend, x, dtype, C, seed, paths=4, window=None, dup=
                         o = left * S + c * C
                         chunks.append(xb[left, o:o + ln])
                     else:
-                        chunks.append(backend.read_out(ranks[left], int(prev[left][c]["out_off"]), ln))
+                        off = int(prev[left][c]["out_off"]) & ~int(FORWARD_ONLY)  # flag bit is not an address bit
+                        chunks.append(backend.read_out(ranks[left], off, ln))
                 arr = gen_arrivals(seed, cps, paths, window, dup, stream=(phase * R + s) * R + r)[0]
                 recv = np.zeros(len(arr) * C, dtype=np.uint8)
                 for k, i in enumerate(arr):

@@ -218,6 +218,25 @@ def test_scatter_any_byte_length(gpu_lib, shape):
         gpu_lib.uccl_set_launch_shape(0)
 
 
+@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("dtype,op", [(BF16, SUM), (F32, MAX), (F32, COPY)])
+def test_forward_only_records(gpu_lib, shape, dtype, op):
+    """Intermediate reduce-scatter steps flagged forward-only: staging gets the combined
+    value, the accumulator keeps its bytes; ragged chunk sizes."""
+    C = 12304
+    w = wl.ring_share("relay", 17, R=5, M=5 * (4 * C + 2064), C=C, dtype=dtype, paths=6, window=8, dup=0.15,
+                      dist="uniform" if dtype == F32 else "normal", op=op, relay=True)
+    check_workload(gpu_lib, w, shape)
+    check_workload(gpu_lib, w, shape, checked=False)
+
+
+def test_closed_loop_ring_with_relay(gpu_lib):
+    R, n, C = 4, 4 * 5000, 4096
+    x = pl.normal_bf16(8, 9, R * n).reshape(R, n)
+    got = closed_loop_allreduce(GpuBackend(gpu_lib), x, BF16, C, seed=5, paths=4, window=None, dup=0.1, relay=True)
+    assert_same(got, oracle.ring_allreduce(x, BF16, SUM), "closed loop with forward-only steps")
+
+
 def test_empty_call_and_all_duplicates(gpu_lib):
     w = wl.ring_share("e", 1, R=3, M=3 * 4096, C=1024, dtype=F32, paths=2, window=None, dup=0.5,
                       dist="uniform", allgather=False)

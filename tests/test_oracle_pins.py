@@ -15,7 +15,7 @@ import oracle
 from synth import payload as pl
 from synth import workloads as wl
 from synth.arrivals import gen_arrivals
-from synth.layout import DESC, NO_FORWARD, F32, BF16, SUM, MAX, MIN, COPY, ELEM_SIZE
+from synth.layout import DESC, NO_FORWARD, FORWARD_ONLY, F32, BF16, SUM, MAX, MIN, COPY, ELEM_SIZE
 
 from ringloop import closed_loop_allreduce
 
@@ -200,6 +200,45 @@ def test_identity_stream_is_slicewise_numpy(op):
     # the last reduce-scatter step keeps its result: some records forward, some do not
     fw = w.phases[0].descs["out_off"] != NO_FORWARD
     assert fw.any() and (~fw).any()
+
+
+# --- forward-only records: relay the combined value, leave the accumulator alone ---------
+
+def test_forward_only_records_relay_without_write_back():
+    C = 256
+    w = wl.ring_share("relay", 6, R=4, M=4 * 3 * C + 4 * 32, C=C, dtype=F32, paths=1, window=None,
+                      dup=0.0, dist="uniform", allgather=False, identity=True, relay=True)
+    d = w.phases[0].descs
+    flagged = (d["out_off"] != NO_FORWARD) & ((d["out_off"] & FORWARD_ONLY) != 0)
+    assert flagged.any() and (~flagged).any()
+    acc, out, bm = run_workload(w)
+    expect = w.acc.copy()
+    eout = np.full(w.out_bytes, 0xA5, dtype=np.uint8)
+    for r, f in zip(d, flagged):
+        n, s, t = r["len"] // 4, r["src_off"] // 4, r["dst_off"] // 4
+        val = expect[t:t + n] + w.recv_stage[s:s + n]  # numpy fp32 add: one rounding
+        if not f:
+            expect[t:t + n] = val
+        if r["out_off"] != NO_FORWARD:
+            o = int(r["out_off"] & ~FORWARD_ONLY)
+            eout[o:o + int(r["len"])] = val.view(np.uint8)
+    assert np.array_equal(acc, expect) and np.array_equal(out, eout)
+    assert sum(bin(int(x)).count("1") for x in bm) == len(d)
+    # byte model: a relayed chunk moves 3 bytes per payload byte
+    C4 = int(d["len"][flagged].astype(np.int64).sum())
+    plain = wl.ring_share("plain", 6, R=4, M=4 * 3 * C + 4 * 32, C=C, dtype=F32, paths=1, window=None,
+                          dup=0.0, dist="uniform", allgather=False, identity=True)
+    assert plain.phases[0].algo_bytes - w.phases[0].algo_bytes == C4
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_closed_loop_with_relay_equals_textbook_ring(dtype):
+    """Not writing intermediate partial sums back must not change the allreduce result:
+    those segments are overwritten by the allgather phase."""
+    R, n, C = 6, 6 * 160, 96
+    x = pl.uniform_f32(4, 5, R * n).reshape(R, n) if dtype == F32 else pl.normal_bf16(4, 5, R * n).reshape(R, n)
+    got = closed_loop_allreduce(OracleBackend(), x, dtype, C, seed=3, paths=5, window=4, dup=0.2, relay=True)
+    assert np.array_equal(got, oracle.ring_allreduce(x, dtype, SUM))
 
 
 # --- P5: all-to-all is a placement of the source bytes -----------------------------
