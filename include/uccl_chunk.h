@@ -55,16 +55,20 @@ typedef struct uccl_chunk_desc {
  * proper is out_off & ~UCCL_FORWARD_ONLY. */
 #define UCCL_FORWARD_ONLY 0x8000000000000000ull
 
-typedef enum uccl_dtype { UCCL_F32 = 0, UCCL_BF16 = 1 } uccl_dtype;
+typedef enum uccl_dtype { UCCL_F32 = 0, UCCL_BF16 = 1, UCCL_F16 = 2, UCCL_I32 = 3 } uccl_dtype;
 
-/* Section 2.1 names "sum, max"; MIN and COPY complete the set a ring needs.
- * SUM  f32 : one IEEE-754 binary32 add (round to nearest even, subnormals kept).
- * SUM  bf16: widen both to binary32 (exact), add, round once to nearest even;
- *            a NaN sum becomes (bits >> 16) | 0x0040.
- * MAX/MIN  : strict comparison on the (widened) values; a tie or an unordered pair
- *            keeps the accumulator's element: MAX(a, r) = r if r > a else a.
- * COPY     : t = r; the element type is irrelevant and `len` may be any byte count. */
-typedef enum uccl_op { UCCL_SUM = 0, UCCL_MAX = 1, UCCL_MIN = 2, UCCL_COPY = 3 } uccl_op;
+/* Section 2.1 names "sum, max"; MIN, PROD and COPY complete the set a collective library
+ * offers.  a = accumulator element, r = received element.
+ * SUM / PROD f32       : one IEEE-754 binary32 add / multiply (nearest even, subnormals kept).
+ * SUM / PROD bf16, f16 : widen both to binary32 (exact), add / multiply, round once to the
+ *                        storage type, nearest even; a bf16 NaN result is (bits >> 16) | 0x0040.
+ * SUM / PROD i32       : two's complement, wrapping modulo 2^32.
+ * MAX / MIN            : strict comparison on the (widened) values, signed for i32; a tie or an
+ *                        unordered pair keeps the accumulator's element: MAX(a, r) = r if r > a else a.
+ * COPY                 : t = r; the element type is irrelevant and `len` may be any byte count. */
+typedef enum uccl_op {
+  UCCL_SUM = 0, UCCL_MAX = 1, UCCL_MIN = 2, UCCL_COPY = 3, UCCL_PROD = 4
+} uccl_op;
 
 enum {
   UCCL_OK = 0,

@@ -18,8 +18,8 @@ _LIB = os.path.join(_DIR, "libchunk_oracle.so")
 CFLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off",
           "-Wall", "-Wextra"]
 
-F32, BF16 = 0, 1
-SUM, MAX, MIN, COPY = 0, 1, 2, 3
+F32, BF16, F16, I32 = 0, 1, 2, 3
+SUM, MAX, MIN, COPY, PROD = 0, 1, 2, 3, 4
 NO_FORWARD = 0xFFFFFFFFFFFFFFFF
 FORWARD_ONLY = 0x8000000000000000
 ERRORS = {-1: "ARG", -2: "SEQ", -3: "ALIGN", -4: "BOUNDS", -5: "MISMATCH", -6: "OVERLAP"}
@@ -69,6 +69,14 @@ def lib():
         L.orc_combine_bf16.argtypes = [C.c_uint16, C.c_uint16, C.c_int]
         L.orc_f32_to_bf16.restype = C.c_uint16
         L.orc_f32_to_bf16.argtypes = [C.c_float]
+        L.orc_combine_f16.restype = C.c_uint16
+        L.orc_combine_f16.argtypes = [C.c_uint16, C.c_uint16, C.c_int]
+        L.orc_combine_i32.restype = C.c_int32
+        L.orc_combine_i32.argtypes = [C.c_int32, C.c_int32, C.c_int]
+        L.orc_f32_to_f16.restype = C.c_uint16
+        L.orc_f32_to_f16.argtypes = [C.c_float]
+        L.orc_f16_to_f32.restype = C.c_float
+        L.orc_f16_to_f32.argtypes = [C.c_uint16]
         _lib = L
     return _lib
 
@@ -146,3 +154,19 @@ def combine_bf16(a, r, op) -> int:
 
 def f32_to_bf16(f) -> int:
     return int(lib().orc_f32_to_bf16(np.float32(f)))
+
+
+def combine_f16(a, r, op) -> int:
+    return int(lib().orc_combine_f16(int(a), int(r), int(op)))
+
+
+def combine_i32(a, r, op) -> int:
+    return int(lib().orc_combine_i32(int(a), int(r), int(op)))
+
+
+def f32_to_f16(f) -> int:
+    return int(lib().orc_f32_to_f16(np.float32(f)))
+
+
+def f16_to_f32(h) -> np.float32:
+    return np.float32(lib().orc_f16_to_f32(int(h)))

@@ -26,6 +26,41 @@ uint16_t orc_f32_to_bf16(float f) {
   return (uint16_t)((u + 0x7FFFu + lsb) >> 16);
 }
 
+/* IEEE binary16 (1 sign, 5 exponent, 10 fraction bits) -> binary32, exact. */
+float orc_f16_to_f32(uint16_t h) {
+  uint32_t sign = (uint32_t)(h & 0x8000u) << 16, e = (h >> 10) & 31u, m = h & 0x3FFu;
+  if (e == 31u) return bits_f32(sign | 0x7F800000u | (m << 13)); /* inf / NaN */
+  if (e == 0u) {                                                  /* zero / subnormal: m * 2^-24 */
+    float v = (float)m * 5.9604644775390625e-08f;                 /* exact: m < 2^10 */
+    return sign ? -v : v;
+  }
+  return bits_f32(sign | ((e + 112u) << 23) | (m << 13));
+}
+
+/* binary32 -> binary16, round to nearest, ties to even, gradual underflow. */
+uint16_t orc_f32_to_f16(float f) {
+  uint32_t u = f32_bits(f);
+  uint16_t sign = (uint16_t)((u >> 16) & 0x8000u);
+  uint32_t mag = u & 0x7FFFFFFFu;
+  if (mag > 0x7F800000u) return (uint16_t)(sign | 0x7E00u | ((mag >> 13) & 0x1FFu)); /* NaN, quieted */
+  if (mag >= 0x47800000u) return (uint16_t)(sign | 0x7C00u);                         /* >= 2^16, and inf */
+  int32_t e = (int32_t)(mag >> 23) - 127;
+  uint32_t m = mag & 0x7FFFFFu;
+  if (e >= -14) { /* normal range: drop 13 fraction bits; a carry may run into the exponent, up to inf */
+    uint32_t h = ((uint32_t)(e + 15) << 10) | (m >> 13);
+    uint32_t rem = m & 0x1FFFu;
+    if (rem > 0x1000u || (rem == 0x1000u && (h & 1u))) ++h;
+    return (uint16_t)(sign | h);
+  }
+  if (e < -25) return sign; /* below half of the smallest subnormal (2^-25 itself is a tie to even 0) */
+  /* subnormal result: value = (2^23 + m) * 2^(e-23), unit 2^-24  =>  shift right by -(e+1) */
+  uint32_t full = m | 0x800000u;
+  uint32_t s = (uint32_t)(-(e + 1));
+  uint32_t h = full >> s, rem = full & ((1u << s) - 1u), half = 1u << (s - 1u);
+  if (rem > half || (rem == half && (h & 1u))) ++h;
+  return (uint16_t)(sign | h);
+}
+
 /* The tensor-buffer value a is combined with the received value r.
  * SUM: one binary32 add.  MAX / MIN: this build defines them as a strict
  * comparison that keeps the local value on ties and whenever the comparison is
@@ -34,6 +69,7 @@ uint16_t orc_f32_to_bf16(float f) {
 float orc_combine_f32(float a, float r, int op) {
   switch (op) {
     case ORC_SUM: return a + r;
+    case ORC_PROD: return a * r;
     case ORC_MAX: return (r > a) ? r : a;
     case ORC_MIN: return (r < a) ? r : a;
     default: return r; /* COPY */
@@ -46,8 +82,32 @@ uint16_t orc_combine_bf16(uint16_t a, uint16_t r, int op) {
   float fa = bf16_widen(a), fr = bf16_widen(r);
   switch (op) {
     case ORC_SUM: return orc_f32_to_bf16(fa + fr);
+    case ORC_PROD: return orc_f32_to_bf16(fa * fr);
     case ORC_MAX: return (fr > fa) ? r : a;
     case ORC_MIN: return (fr < fa) ? r : a;
+    default: return r;
+  }
+}
+
+/* binary16: the same scheme -- widen, combine in binary32, round once. */
+uint16_t orc_combine_f16(uint16_t a, uint16_t r, int op) {
+  float fa = orc_f16_to_f32(a), fr = orc_f16_to_f32(r);
+  switch (op) {
+    case ORC_SUM: return orc_f32_to_f16(fa + fr);
+    case ORC_PROD: return orc_f32_to_f16(fa * fr);
+    case ORC_MAX: return (fr > fa) ? r : a;
+    case ORC_MIN: return (fr < fa) ? r : a;
+    default: return r;
+  }
+}
+
+/* int32: two's complement; SUM and PROD wrap modulo 2^32 (done in unsigned arithmetic). */
+int32_t orc_combine_i32(int32_t a, int32_t r, int op) {
+  switch (op) {
+    case ORC_SUM: return (int32_t)((uint32_t)a + (uint32_t)r);
+    case ORC_PROD: return (int32_t)((uint32_t)a * (uint32_t)r);
+    case ORC_MAX: return (r > a) ? r : a;
+    case ORC_MIN: return (r < a) ? r : a;
     default: return r;
   }
 }
@@ -78,11 +138,11 @@ static int64_t check_record(const orc_desc* d, uint64_t acc_bytes, uint64_t out_
 int64_t orc_apply(void* acc, uint64_t acc_bytes, void* out_stage, uint64_t out_bytes,
                   const void* recv_stage, uint64_t recv_bytes, const orc_desc* descs,
                   uint64_t n_descs, uint8_t* seen, uint64_t n_bits, int dtype, int op) {
-  if (dtype != ORC_F32 && dtype != ORC_BF16) return ORC_E_ARG;
-  if (op < ORC_SUM || op > ORC_COPY) return ORC_E_ARG;
+  if (dtype < ORC_F32 || dtype > ORC_I32) return ORC_E_ARG;
+  if (op < ORC_SUM || op > ORC_PROD) return ORC_E_ARG;
   if (n_descs == 0) return 0;
   if (!acc || !recv_stage || !descs || !seen) return ORC_E_ARG;
-  const uint32_t es = (dtype == ORC_F32) ? 4u : 2u;
+  const uint32_t es = (dtype == ORC_F32 || dtype == ORC_I32) ? 4u : 2u;
   int64_t applied = 0;
   for (uint64_t k = 0; k < n_descs; ++k) { /* array order = arrival order */
     const orc_desc* d = &descs[k];
@@ -104,12 +164,21 @@ int64_t orc_apply(void* acc, uint64_t acc_bytes, void* out_stage, uint64_t out_b
         if (keep) a[i] = t;
         if (fwd) o[i] = t;
       }
+    } else if (dtype == ORC_I32) {
+      const int32_t* r = (const int32_t*)((const char*)recv_stage + d->src_off);
+      int32_t* a = (int32_t*)((char*)acc + d->dst_off);
+      int32_t* o = fwd ? (int32_t*)((char*)out_stage + out_at) : NULL;
+      for (uint64_t i = 0; i < n; ++i) {
+        int32_t t = orc_combine_i32(a[i], r[i], op);
+        if (keep) a[i] = t;
+        if (fwd) o[i] = t;
+      }
     } else {
       const uint16_t* r = (const uint16_t*)((const char*)recv_stage + d->src_off);
       uint16_t* a = (uint16_t*)((char*)acc + d->dst_off);
       uint16_t* o = fwd ? (uint16_t*)((char*)out_stage + out_at) : NULL;
       for (uint64_t i = 0; i < n; ++i) {
-        uint16_t t = orc_combine_bf16(a[i], r[i], op);
+        uint16_t t = dtype == ORC_BF16 ? orc_combine_bf16(a[i], r[i], op) : orc_combine_f16(a[i], r[i], op);
         if (keep) a[i] = t;
         if (fwd) o[i] = t;
       }
@@ -210,9 +279,9 @@ int64_t orc_check_call(const void* recv_stage, uint64_t recv_bytes, const orc_de
  * so each step reads a snapshot of the previous state. */
 int orc_ring_allreduce(const void* x, uint32_t R, uint64_t n, int dtype, int op, void* result) {
   if (!x || !result || R == 0 || n % R) return ORC_E_ARG;
-  if (dtype != ORC_F32 && dtype != ORC_BF16) return ORC_E_ARG;
-  if (op < ORC_SUM || op > ORC_MIN) return ORC_E_ARG;
-  const uint32_t es = (dtype == ORC_F32) ? 4u : 2u;
+  if (dtype < ORC_F32 || dtype > ORC_I32) return ORC_E_ARG;
+  if (op != ORC_SUM && op != ORC_MAX && op != ORC_MIN && op != ORC_PROD) return ORC_E_ARG;
+  const uint32_t es = (dtype == ORC_F32 || dtype == ORC_I32) ? 4u : 2u;
   const uint64_t seg = n / R, total = (uint64_t)R * n * es;
   char* cur = (char*)result;
   memcpy(cur, x, total);
@@ -229,9 +298,13 @@ int orc_ring_allreduce(const void* x, uint32_t R, uint64_t n, int dtype, int op,
           if (dtype == ORC_F32) {
             float mine = ((float*)prev)[r * n + i], got = ((float*)prev)[left * n + i];
             ((float*)cur)[r * n + i] = phase == 0 ? orc_combine_f32(mine, got, op) : got;
+          } else if (dtype == ORC_I32) {
+            int32_t mine = ((int32_t*)prev)[r * n + i], got = ((int32_t*)prev)[left * n + i];
+            ((int32_t*)cur)[r * n + i] = phase == 0 ? orc_combine_i32(mine, got, op) : got;
           } else {
             uint16_t mine = ((uint16_t*)prev)[r * n + i], got = ((uint16_t*)prev)[left * n + i];
-            ((uint16_t*)cur)[r * n + i] = phase == 0 ? orc_combine_bf16(mine, got, op) : got;
+            uint16_t t = dtype == ORC_BF16 ? orc_combine_bf16(mine, got, op) : orc_combine_f16(mine, got, op);
+            ((uint16_t*)cur)[r * n + i] = phase == 0 ? t : got;
           }
         }
       }

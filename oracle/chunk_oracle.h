@@ -42,8 +42,8 @@ typedef struct {
 /* flag in out_off: the combined value goes to out_stage only, acc is read but not written */
 #define ORC_FORWARD_ONLY 0x8000000000000000ull
 
-enum { ORC_F32 = 0, ORC_BF16 = 1 };
-enum { ORC_SUM = 0, ORC_MAX = 1, ORC_MIN = 2, ORC_COPY = 3 };
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2, ORC_I32 = 3 };
+enum { ORC_SUM = 0, ORC_MAX = 1, ORC_MIN = 2, ORC_COPY = 3, ORC_PROD = 4 };
 
 /* negative return codes: a precondition of the problem statement is violated */
 enum {
@@ -84,7 +84,11 @@ int orc_ring_allreduce(const void* x, uint32_t R, uint64_t n, int dtype, int op,
 /* One element-wise combine, exposed so tests can pin the numerics directly. */
 float orc_combine_f32(float a, float r, int op);
 uint16_t orc_combine_bf16(uint16_t a, uint16_t r, int op);
+uint16_t orc_combine_f16(uint16_t a, uint16_t r, int op);
+int32_t orc_combine_i32(int32_t a, int32_t r, int op);
 uint16_t orc_f32_to_bf16(float f);
+uint16_t orc_f32_to_f16(float f);
+float orc_f16_to_f32(uint16_t h);
 
 #ifdef __cplusplus
 }

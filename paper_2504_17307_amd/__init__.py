@@ -14,8 +14,8 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libuccl_chunk.so")
 HEADER_PATH = os.path.join(os.path.dirname(_PKG), "include", "uccl_chunk.h")
 
-UCCL_F32, UCCL_BF16 = 0, 1
-UCCL_SUM, UCCL_MAX, UCCL_MIN, UCCL_COPY = 0, 1, 2, 3
+UCCL_F32, UCCL_BF16, UCCL_F16, UCCL_I32 = 0, 1, 2, 3
+UCCL_SUM, UCCL_MAX, UCCL_MIN, UCCL_COPY, UCCL_PROD = 0, 1, 2, 3, 4
 UCCL_OK, UCCL_EINVAL, UCCL_EALIGN, UCCL_ELAUNCH = 0, -1, -2, -3
 UCCL_NO_FORWARD = 0xFFFFFFFFFFFFFFFF
 UCCL_SHAPE_AUTO, UCCL_SHAPE_WAVE, UCCL_SHAPE_GROUP, UCCL_SHAPE_FLAT = 0, 1, 2, 4

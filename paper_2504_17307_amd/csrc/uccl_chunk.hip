@@ -116,65 +116,73 @@ __device__ __forceinline__ uint32_t round_bf16(float s) {
   return h;
 }
 
-// Element operations.  word() combines one 32-bit word (one fp32, or two bf16 side by
-// side); half() one 16-bit element (bf16 tails).  a = tensor-buffer value, r = received.
-struct SumF32 {
+// Element operations.  word() combines one 32-bit word (one fp32 / int32, or two 16-bit
+// elements side by side); half() one 16-bit element (tails).  a = tensor-buffer value,
+// r = received value.  SUM and PROD compute in binary32 and round once to the storage
+// type; MAX and MIN compare the (widened) values strictly and select one of the two
+// inputs unchanged, the accumulator's on a tie or an unordered pair.
+enum Kind { kSum = 0, kMax = 1, kMin = 2, kProd = 4 };
+
+template <int K>
+__device__ __forceinline__ float arith(float a, float r) {
+  return K == kSum ? a + r : a * r;
+}
+template <int K>
+__device__ __forceinline__ bool takes_received(float a, float r) {
+  return K == kMax ? r > a : r < a;
+}
+
+struct WidenBF16 {
+  static __device__ __forceinline__ float widen(uint32_t h) { return as_f32(h << 16); }
+  static __device__ __forceinline__ uint32_t narrow(float f) { return round_bf16(f); }
+};
+// IEEE binary16 through the hardware converts (round to nearest even, subnormals kept).
+struct WidenF16 {
+  static __device__ __forceinline__ float widen(uint32_t h) {
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));
+  }
+  static __device__ __forceinline__ uint32_t narrow(float f) {
+    return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f));
+  }
+};
+
+template <int K>
+struct OpF32 {
   static constexpr bool kReadsAcc = true;
   static constexpr uint32_t kEs = 4;
   static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
-    return as_u32(as_f32(a) + as_f32(r));
+    if constexpr (K == kSum || K == kProd) return as_u32(arith<K>(as_f32(a), as_f32(r)));
+    else return takes_received<K>(as_f32(a), as_f32(r)) ? r : a;
   }
 };
-struct MaxF32 {
+
+template <int K>
+struct OpI32 {  // two's complement; SUM and PROD wrap modulo 2^32
   static constexpr bool kReadsAcc = true;
   static constexpr uint32_t kEs = 4;
   static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
-    return (as_f32(r) > as_f32(a)) ? r : a;
+    if constexpr (K == kSum) return a + r;
+    else if constexpr (K == kProd) return a * r;
+    else if constexpr (K == kMax) return static_cast<int32_t>(r) > static_cast<int32_t>(a) ? r : a;
+    else return static_cast<int32_t>(r) < static_cast<int32_t>(a) ? r : a;
   }
 };
-struct MinF32 {
-  static constexpr bool kReadsAcc = true;
-  static constexpr uint32_t kEs = 4;
-  static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
-    return (as_f32(r) < as_f32(a)) ? r : a;
-  }
-};
-struct SumBF16 {
+
+template <int K, class W>
+struct Op16 {
   static constexpr bool kReadsAcc = true;
   static constexpr uint32_t kEs = 2;
-  static __device__ __forceinline__ uint32_t half(uint32_t a, uint32_t r) {
-    return round_bf16(as_f32(a << 16) + as_f32(r << 16));
+  static __device__ __forceinline__ uint32_t half(uint32_t a, uint32_t r) {  // low 16 bits
+    if constexpr (K == kSum || K == kProd) return W::narrow(arith<K>(W::widen(a), W::widen(r)));
+    else return takes_received<K>(W::widen(a), W::widen(r)) ? r : a;
   }
   static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
-    const uint32_t lo = round_bf16(as_f32(a << 16) + as_f32(r << 16));
-    const uint32_t hi = round_bf16(as_f32(a & 0xFFFF0000u) + as_f32(r & 0xFFFF0000u));
-    return lo | (hi << 16);
+    const uint32_t lo = half(a & 0xFFFFu, r & 0xFFFFu);
+    const uint32_t hi = half(a >> 16, r >> 16);
+    return (lo & 0xFFFFu) | (hi << 16);
   }
 };
-struct MaxBF16 {
-  static constexpr bool kReadsAcc = true;
-  static constexpr uint32_t kEs = 2;
-  static __device__ __forceinline__ uint32_t half(uint32_t a, uint32_t r) {
-    return (as_f32(r << 16) > as_f32(a << 16)) ? r : a;
-  }
-  static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
-    const uint32_t lo = (as_f32(r << 16) > as_f32(a << 16)) ? r : a;
-    const uint32_t hi = (as_f32(r & 0xFFFF0000u) > as_f32(a & 0xFFFF0000u)) ? r : a;
-    return (lo & 0xFFFFu) | (hi & 0xFFFF0000u);
-  }
-};
-struct MinBF16 {
-  static constexpr bool kReadsAcc = true;
-  static constexpr uint32_t kEs = 2;
-  static __device__ __forceinline__ uint32_t half(uint32_t a, uint32_t r) {
-    return (as_f32(r << 16) < as_f32(a << 16)) ? r : a;
-  }
-  static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
-    const uint32_t lo = (as_f32(r << 16) < as_f32(a << 16)) ? r : a;
-    const uint32_t hi = (as_f32(r & 0xFFFF0000u) < as_f32(a & 0xFFFF0000u)) ? r : a;
-    return (lo & 0xFFFFu) | (hi & 0xFFFF0000u);
-  }
-};
+
 struct Copy {
   static constexpr bool kReadsAcc = false;
   static constexpr uint32_t kEs = 1;
@@ -558,8 +566,8 @@ int apply_common(void* acc, void* out_stage, const void* recv_stage, const uccl_
                  uint32_t n_descs, uint32_t* bitmap, int dtype, int op, bool allow_forward,
                  const uccl_extents* ext, uint32_t* n_rejected, void* stream,
                  const uint32_t* n_ptr = nullptr) {
-  if (dtype != UCCL_F32 && dtype != UCCL_BF16) return UCCL_EINVAL;
-  if (op < UCCL_SUM || op > UCCL_COPY) return UCCL_EINVAL;
+  if (dtype < UCCL_F32 || dtype > UCCL_I32) return UCCL_EINVAL;
+  if (op < UCCL_SUM || op > UCCL_PROD) return UCCL_EINVAL;
   if (n_descs == 0) return UCCL_OK;
   if (!acc || !recv_stage || !descs || !bitmap) return UCCL_EINVAL;
   if (misaligned(acc, 16) || misaligned(out_stage, 16) || misaligned(recv_stage, 16) ||
@@ -587,14 +595,25 @@ int apply_common(void* acc, void* out_stage, const void* recv_stage, const uccl_
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   if (op == UCCL_COPY) return launch_shape<Copy>(a, s);
-  if (dtype == UCCL_F32) {
-    if (op == UCCL_SUM) return launch_shape<SumF32>(a, s);
-    if (op == UCCL_MAX) return launch_shape<MaxF32>(a, s);
-    return launch_shape<MinF32>(a, s);
+  switch (dtype * 8 + op) {
+    case UCCL_F32 * 8 + UCCL_SUM: return launch_shape<OpF32<kSum>>(a, s);
+    case UCCL_F32 * 8 + UCCL_MAX: return launch_shape<OpF32<kMax>>(a, s);
+    case UCCL_F32 * 8 + UCCL_MIN: return launch_shape<OpF32<kMin>>(a, s);
+    case UCCL_F32 * 8 + UCCL_PROD: return launch_shape<OpF32<kProd>>(a, s);
+    case UCCL_BF16 * 8 + UCCL_SUM: return launch_shape<Op16<kSum, WidenBF16>>(a, s);
+    case UCCL_BF16 * 8 + UCCL_MAX: return launch_shape<Op16<kMax, WidenBF16>>(a, s);
+    case UCCL_BF16 * 8 + UCCL_MIN: return launch_shape<Op16<kMin, WidenBF16>>(a, s);
+    case UCCL_BF16 * 8 + UCCL_PROD: return launch_shape<Op16<kProd, WidenBF16>>(a, s);
+    case UCCL_F16 * 8 + UCCL_SUM: return launch_shape<Op16<kSum, WidenF16>>(a, s);
+    case UCCL_F16 * 8 + UCCL_MAX: return launch_shape<Op16<kMax, WidenF16>>(a, s);
+    case UCCL_F16 * 8 + UCCL_MIN: return launch_shape<Op16<kMin, WidenF16>>(a, s);
+    case UCCL_F16 * 8 + UCCL_PROD: return launch_shape<Op16<kProd, WidenF16>>(a, s);
+    case UCCL_I32 * 8 + UCCL_SUM: return launch_shape<OpI32<kSum>>(a, s);
+    case UCCL_I32 * 8 + UCCL_MAX: return launch_shape<OpI32<kMax>>(a, s);
+    case UCCL_I32 * 8 + UCCL_MIN: return launch_shape<OpI32<kMin>>(a, s);
+    case UCCL_I32 * 8 + UCCL_PROD: return launch_shape<OpI32<kProd>>(a, s);
+    default: return UCCL_EINVAL;
   }
-  if (op == UCCL_SUM) return launch_shape<SumBF16>(a, s);
-  if (op == UCCL_MAX) return launch_shape<MaxBF16>(a, s);
-  return launch_shape<MinBF16>(a, s);
 }
 
 }  // namespace

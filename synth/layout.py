@@ -24,10 +24,10 @@ NO_FORWARD = np.uint64(0xFFFFFFFFFFFFFFFF)
 FORWARD_ONLY = np.uint64(0x8000000000000000)  # flag in out_off: relay the result, do not write acc
 
 # dtype / op codes shared by every caller (values are part of the C ABI)
-F32, BF16 = 0, 1
-SUM, MAX, MIN, COPY = 0, 1, 2, 3
+F32, BF16, F16, I32 = 0, 1, 2, 3
+SUM, MAX, MIN, COPY, PROD = 0, 1, 2, 3, 4
 
-ELEM_SIZE = {F32: 4, BF16: 2}
+ELEM_SIZE = {F32: 4, BF16: 2, F16: 2, I32: 4}
 OFFSET_ALIGN = 16  # every offset in a record is a multiple of this
 
 

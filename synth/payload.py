@@ -54,6 +54,12 @@ def ints_as(values: np.ndarray, dtype_code: int) -> np.ndarray:
     f = np.asarray(values).astype(np.float32)
     if dtype_code == 0:
         return f
+    if dtype_code == 3:
+        return np.asarray(values).astype(np.int32)
+    if dtype_code == 2:
+        h = f.astype(np.float16)
+        assert np.array_equal(h.astype(np.float32), f), "value not exactly representable in binary16"
+        return h.view(np.uint16)
     bits = f.view(np.uint32)
     assert not np.any(bits & np.uint32(0xFFFF)), "value not exactly representable in bf16"
     return (bits >> np.uint32(16)).astype(np.uint16)
@@ -64,6 +70,17 @@ def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
     return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
 
 
+def uniform_f16(seed: int, stream: int, n: int, scale: float = 1.0) -> np.ndarray:
+    """n binary16 bit patterns (uint16): uniform[-scale, scale) fp32 draws converted by numpy."""
+    return (uniform_f32(seed, stream, n) * np.float32(scale)).astype(np.float16).view(np.uint16)
+
+
+def uniform_i32(seed: int, stream: int, n: int, lo: int = -(1 << 31), hi: int = (1 << 31) - 1) -> np.ndarray:
+    """n int32 values uniform on {lo..hi} (full range by default, so sums and products wrap)."""
+    return rng(seed, stream).integers(lo, hi + 1, int(n), dtype=np.int64).astype(np.int32)
+
+
 def np_dtype(dtype_code: int):
-    """Storage dtype of a buffer holding elements of the given ABI dtype code."""
-    return np.float32 if dtype_code == 0 else np.uint16
+    """Storage dtype of a buffer holding elements of the given ABI dtype code
+    (0 fp32, 1 bf16 bits, 2 binary16 bits, 3 int32)."""
+    return {0: np.float32, 1: np.uint16, 2: np.uint16, 3: np.int32}[dtype_code]

@@ -23,7 +23,7 @@ import numpy as np
 
 from . import payload as pl
 from .arrivals import gen_arrivals, identity_arrivals, merge_streams
-from .layout import DESC, NO_FORWARD, FORWARD_ONLY, ELEM_SIZE, SUM, COPY, F32, BF16
+from .layout import DESC, NO_FORWARD, FORWARD_ONLY, ELEM_SIZE, SUM, COPY, F32, BF16, F16, I32
 
 LOGICAL = np.dtype([("seq", "<u4"), ("dst_off", "<u8"), ("out_off", "<u8"), ("len", "<u4")])
 
@@ -141,6 +141,10 @@ def fill_slots(recv_stage: np.ndarray, unique_payload: np.ndarray, arr_idx: np.n
 
 def _draw(dist: str, dtype: int, seed: int, stream: int, n: int) -> np.ndarray:
     if dist == "uniform":
+        if dtype == F16:
+            return pl.uniform_f16(seed, stream, n, 4.0)
+        if dtype == I32:
+            return pl.uniform_i32(seed, stream, n)
         return pl.uniform_f32(seed, stream, n) if dtype == F32 else pl.uniform_bf16(seed, stream, n)
     if dist == "normal":
         assert dtype == BF16

@@ -46,8 +46,9 @@ def test_host_side_error_codes_enqueue_nothing():
     assert f(A, None, None, D, 1, M, 0, 0, None) == pkg.UCCL_EINVAL
     assert f(A, None, B, None, 1, M, 0, 0, None) == pkg.UCCL_EINVAL
     assert f(A, None, B, D, 1, None, 0, 0, None) == pkg.UCCL_EINVAL
-    assert f(A, None, B, D, 1, M, 2, 0, None) == pkg.UCCL_EINVAL   # dtype
-    assert f(A, None, B, D, 1, M, 0, 4, None) == pkg.UCCL_EINVAL   # op
+    assert f(A, None, B, D, 1, M, 4, 0, None) == pkg.UCCL_EINVAL   # dtype
+    assert f(A, None, B, D, 1, M, -1, 0, None) == pkg.UCCL_EINVAL
+    assert f(A, None, B, D, 1, M, 0, 5, None) == pkg.UCCL_EINVAL   # op
     assert f(A, None, B, D, 1, M, 0, -1, None) == pkg.UCCL_EINVAL
     assert f(A + 8, None, B, D, 1, M, 0, 0, None) == pkg.UCCL_EALIGN
     assert f(A, A + 4, B, D, 1, M, 0, 0, None) == pkg.UCCL_EALIGN

@@ -100,10 +100,12 @@ def test_small_messages_2000(gpu_lib):
     assert_same(out, eout, "out_stage")
 
 
-def test_bf16_sum_every_pair(gpu_lib):
-    """All 65536 x 65536 pairs of bf16 bit patterns through the SUM path, bit-exact against
-    the oracle (NaN results: NaN-ness only, their payload is not fixed by the method)."""
-    from synth.layout import DESC, NO_FORWARD, BF16
+@pytest.mark.parametrize("dtype,op", [(1, 0), (2, 0), (1, 4), (2, 4)])
+def test_16bit_every_pair(gpu_lib, dtype, op):
+    """All 65536 x 65536 pairs of bf16 / binary16 bit patterns through SUM and PROD, bit-exact
+    against the oracle (NaN results: NaN-ness only, their payload is not fixed by the method)."""
+    from synth.layout import DESC, NO_FORWARD
+    BF16, SUM = dtype, op  # the body below was written for bf16 SUM; the codes are parameters now
     blk = 2048                                     # a-values per block: 134 M pairs
     n = blk * 65536
     r_np = np.tile(np.arange(65536, dtype=np.uint16), blk)
@@ -114,7 +116,8 @@ def test_bf16_sum_every_pair(gpu_lib):
         d[k] = (k * (n // pieces) * 2, k * (n // pieces) * 2, NO_FORWARD, (n // pieces) * 2, k)
     d_dev = to_dev(d)
     bm = torch.zeros(pieces // 32, dtype=torch.int32, device="cuda")
-    wide = lambda h: (h.astype(np.uint32) << 16).view(np.float32)
+    wide = (lambda h: (h.astype(np.uint32) << 16).view(np.float32)) if dtype == 1 else \
+           (lambda h: h.view(np.float16).astype(np.float32))
     t0 = time.time()
     for b in range(65536 // blk):
         a_np = np.repeat(np.arange(b * blk, (b + 1) * blk, dtype=np.uint16), 65536)

@@ -12,7 +12,7 @@ import torch
 import oracle
 from synth import payload as pl
 from synth import workloads as wl
-from synth.layout import DESC, NO_FORWARD, F32, BF16, SUM, MAX, MIN, COPY, ELEM_SIZE
+from synth.layout import DESC, NO_FORWARD, F32, BF16, F16, I32, SUM, MAX, MIN, COPY, PROD, ELEM_SIZE
 
 from gpuhelp import DeviceRun, oracle_results, assert_same, to_dev, to_host
 from ringloop import closed_loop_allreduce
@@ -143,12 +143,12 @@ def test_flat_shape_every_tile_size(gpu_lib, hint):
 # ---- ops, dtypes, ragged tails, odd lengths ------------------------------------------
 
 @pytest.mark.parametrize("shape", SHAPES)
-@pytest.mark.parametrize("dtype", [F32, BF16])
-@pytest.mark.parametrize("op", [SUM, MAX, MIN, COPY])
+@pytest.mark.parametrize("dtype", [F32, BF16, F16, I32])
+@pytest.mark.parametrize("op", [SUM, MAX, MIN, COPY, PROD])
 def test_ops_dtypes_ragged(gpu_lib, shape, dtype, op):
     say("ops ragged", shape, dtype, op)
     C = 20000 - 20000 % 16 + 16  # 20000: many 16-byte vectors plus trips that do not divide evenly
-    dist = "uniform" if dtype == F32 else "normal"
+    dist = "normal" if dtype == BF16 else "uniform"
     w = wl.ring_share("ragged", 11, R=4, M=4 * (5 * C + 4112), C=C, dtype=dtype, paths=7, window=9,
                       dup=0.15, dist=dist, op=op, allgather=True)
     check_workload(gpu_lib, w, shape)
@@ -162,7 +162,8 @@ def _records(rows):
 
 
 @pytest.mark.parametrize("shape", SHAPES)
-@pytest.mark.parametrize("dtype,op", [(F32, SUM), (BF16, SUM), (BF16, MAX), (F32, COPY), (BF16, COPY)])
+@pytest.mark.parametrize("dtype,op", [(F32, SUM), (BF16, SUM), (BF16, MAX), (F32, COPY), (BF16, COPY), (F16, PROD),
+                                      (I32, MIN)])
 def test_lengths_not_multiple_of_16(gpu_lib, shape, dtype, op):
     """len is any multiple of the element size, including 0."""
     es = ELEM_SIZE[dtype]
@@ -175,10 +176,8 @@ def test_lengths_not_multiple_of_16(gpu_lib, shape, dtype, op):
     d = _records(rows)
     g = pl.rng(5, shape)
     nel = (n + 1) * slot // ELEM_SIZE[dtype]
-    if dtype == F32:
-        acc0, recv = pl.uniform_f32(5, 1, nel), pl.uniform_f32(5, 2, nel)
-    else:
-        acc0, recv = pl.normal_bf16(5, 1, nel), pl.normal_bf16(5, 2, nel)
+    acc0 = wl._draw("normal" if dtype == BF16 else "uniform", dtype, 5, 1, nel)
+    recv = wl._draw("normal" if dtype == BF16 else "uniform", dtype, 5, 2, nel)
     recv.view(np.uint8)[n * slot:n * slot + lens[3]] = recv.view(np.uint8)[3 * slot:3 * slot + lens[3]]
     w = wl.Workload("odd", dtype, acc0, recv, (n + 1) * slot, n, [wl.Phase("p", op, d, n, sum(lens), 0)])
     check_workload(gpu_lib, w, shape)
@@ -380,14 +379,19 @@ def test_special_values_bit_exact(gpu_lib):
     h = np.array([0, 0x8000, 1, 2, 0x007F, 0x0080, 0x807F, 0x3F80, 0xBF80, 0x7F7F, 0xFF7F, 0x7F80, 0xFF80,
                   0x3B80, 0x3F81, 0x3B81, 0x3B7F, 0x7B00], dtype=np.uint16)
     a16, r16 = np.repeat(h, len(h)), np.tile(h, len(h))
-    for dtype, a, r in ((F32, a32, r32), (BF16, a16, r16)):
+    q = np.array([0, 0x8000, 1, 2, 0x03FF, 0x0400, 0x83FF, 0x3C00, 0xBC00, 0x7BFF, 0xFBFF, 0x7C00, 0xFC00,
+                  0x1400, 0x3C01, 0x1401, 0x13FF, 0x6C00, 0x7BFE], dtype=np.uint16)  # binary16
+    aq, rq = np.repeat(q, len(q)), np.tile(q, len(q))
+    i = np.array([0, 1, -1, 2 ** 31 - 1, -2 ** 31, 65536, -65536, 46341, 3, -7], dtype=np.int32)
+    ai, ri = np.repeat(i, len(i)), np.tile(i, len(i))
+    for dtype, a, r in ((F32, a32, r32), (BF16, a16, r16), (F16, aq, rq), (I32, ai, ri)):
         es = ELEM_SIZE[dtype]
         n = len(a)
         pad = (-n * es) % 16
         nb = n * es + pad
         accp = np.zeros(nb // es, dtype=a.dtype); accp[:n] = a
         recvp = np.zeros(nb // es, dtype=a.dtype); recvp[:n] = r
-        for op in (SUM, MAX, MIN):
+        for op in (SUM, MAX, MIN, PROD):
             d = _records([(0, 0, 0, n * es, 0)])
             w = wl.Workload("sv", dtype, accp, recvp, nb, 1, [wl.Phase("p", op, d, 1, n * es, 0)])
             run = DeviceRun(w)
@@ -395,7 +399,8 @@ def test_special_values_bit_exact(gpu_lib):
             acc, out, _, rej = run.results()
             eacc, eout, _ = oracle_results(w)
             assert rej == 0
-            wide = (lambda x: x) if dtype == F32 else (lambda x: (x.astype(np.uint32) << 16).view(np.float32))
+            wide = {F32: lambda x: x, BF16: lambda x: (x.astype(np.uint32) << 16).view(np.float32),
+                    F16: lambda x: x.view(np.float16).astype(np.float32), I32: lambda x: x.astype(np.float32)}[dtype]
             nan = np.isnan(wide(eacc))
             assert np.array_equal(np.isnan(wide(acc)), nan)
             assert_same(acc[~nan], eacc[~nan], f"dtype {dtype} op {op}")

@@ -15,7 +15,8 @@ import oracle
 from synth import payload as pl
 from synth import workloads as wl
 from synth.arrivals import gen_arrivals
-from synth.layout import DESC, NO_FORWARD, FORWARD_ONLY, F32, BF16, SUM, MAX, MIN, COPY, ELEM_SIZE
+from synth.layout import (DESC, NO_FORWARD, FORWARD_ONLY, F32, BF16, F16, I32, SUM, MAX, MIN, COPY, PROD,
+                          ELEM_SIZE)
 
 from ringloop import closed_loop_allreduce
 
@@ -353,6 +354,74 @@ def test_max_min_select_and_tie_rule():
     assert oracle.combine_f32(-0.0, 0.0, MAX).view(np.uint32) == 0x80000000
     assert np.isnan(oracle.combine_f32(float("nan"), 1.0, MAX)) and oracle.combine_f32(1.0, float("nan"), MAX) == 1.0
     assert oracle.combine_f32(5.0, 7.0, COPY) == 7.0 and oracle.combine_bf16(1, 2, COPY) == 2
+
+
+# --- binary16, int32, PROD ---------------------------------------------------------------
+
+def test_f16_conversions_against_numpy():
+    """numpy's float16 is an independent IEEE binary16: widening must agree on all 65536
+    patterns, narrowing (nearest even, gradual underflow, overflow to inf) on every pattern
+    around each binary16 boundary and on random binary32 values."""
+    allh = np.arange(1 << 16, dtype=np.uint16)
+    wide = np.array([oracle.f16_to_f32(int(h)) for h in allh], dtype=np.float32)
+    ref = allh.view(np.float16).astype(np.float32)
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(wide), nan) and np.array_equal(wide[~nan].view(np.uint32), ref[~nan].view(np.uint32))
+    # binary32 patterns: each finite half value's fp32 image, +- a few ulps, and exact midpoints
+    base = ref[~nan & np.isfinite(ref)].view(np.uint32)
+    cand = np.concatenate([base + np.uint32(d) for d in (0, 1, 0xFFF, 0x1000, 0x1001, 0x1FFF, 0x2000)]
+                          + [base - np.uint32(d) for d in (1, 0x1000, 0x1001)]
+                          + [pl.rng(2, 2).integers(0, 2 ** 32, 200000, dtype=np.uint64).astype(np.uint32),
+                             np.array([0x33000000, 0x33000001, 0x32FFFFFF, 0x33800000, 0x33C00000, 0x477FE000,
+                                       0x477FEFFF, 0x477FF000, 0x477FFFFF, 0x47800000, 0x7F7FFFFF, 0x387FC000,
+                                       0x387FE000, 0x38800000, 0x387FFFFF], dtype=np.uint32)])
+    f = cand.view(np.float32)
+    f = f[np.isfinite(f)][::7]
+    with np.errstate(over="ignore"):
+        expect = f.astype(np.float16).view(np.uint16)
+    got = np.array([oracle.f32_to_f16(v) for v in f], dtype=np.uint16)
+    assert np.array_equal(got, expect)
+
+
+@pytest.mark.parametrize("op,npf", [(SUM, np.add), (PROD, np.multiply), (MAX, np.maximum), (MIN, np.minimum)])
+def test_f16_i32_f32_ops_against_numpy(op, npf):
+    n = 30000
+    # binary16: numpy computes in fp32 when given fp32 inputs; round once with astype
+    a, r = pl.uniform_f16(5, 1, n, 300.0), pl.uniform_f16(5, 2, n, 300.0)
+    r[::9] = a[::9]
+    with np.errstate(over="ignore"):
+        expect = npf(a.view(np.float16).astype(np.float32), r.view(np.float16).astype(np.float32)).astype(np.float16)
+    got = np.array([oracle.combine_f16(int(x), int(y), op) for x, y in zip(a, r)], dtype=np.uint16)
+    assert np.array_equal(got, expect.view(np.uint16))
+    # int32: wrapping add / multiply, signed max / min
+    a, r = pl.uniform_i32(6, 1, n), pl.uniform_i32(6, 2, n)
+    with np.errstate(over="ignore"):
+        expect = npf(a, r)
+    got = np.array([oracle.combine_i32(int(x), int(y), op) for x, y in zip(a, r)], dtype=np.int32)
+    assert np.array_equal(got, expect)
+    # fp32: one correctly rounded operation
+    a, r = pl.uniform_f32(7, 1, n) * 1e3, pl.uniform_f32(7, 2, n)
+    got = np.array([oracle.combine_f32(float(x), float(y), op) for x, y in zip(a, r)], dtype=np.float32)
+    assert np.array_equal(got.view(np.uint32), npf(a, r).view(np.uint32))
+
+
+def test_bf16_prod_is_f32_multiply_then_nearest_even():
+    a, r = pl.normal_bf16(8, 3, 40000), pl.normal_bf16(8, 4, 40000)
+    wide = lambda h: (h.astype(np.uint32) << 16).view(np.float32)
+    expect = nearest_even_bf16(wide(a) * wide(r))  # product of two 8-bit significands is exact in fp32
+    got = np.array([oracle.combine_bf16(int(x), int(y), PROD) for x, y in zip(a, r)], dtype=np.uint16)
+    assert np.array_equal(got, expect)
+
+
+@pytest.mark.parametrize("dtype,op", [(F16, SUM), (I32, SUM), (I32, PROD), (F16, MAX), (F32, PROD)])
+def test_closed_loop_new_types_match_textbook_ring(dtype, op):
+    R, n, C = 4, 4 * 192, 80
+    x = wl._draw("uniform", dtype, 12, 3, R * n).reshape(R, n)
+    got = closed_loop_allreduce(OracleBackend(), x, dtype, C, seed=7, paths=4, window=5, dup=0.2, op=op)
+    expect = oracle.ring_allreduce(x, dtype, op)
+    assert np.array_equal(got, expect)
+    if dtype == I32 and op == SUM:  # wrapping integer sum: independent of order, equals the int64 sum mod 2^32
+        assert np.array_equal(expect[0], x.astype(np.int64).sum(axis=0).astype(np.int32))
 
 
 # --- P7: a chunk that never arrives ------------------------------------------------
