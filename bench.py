@@ -333,6 +333,22 @@ def main():
                             hbm_frac=round(c["algo_bytes"] / (t.mean() * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)))
     dom = max(kernels, key=lambda k: k["algorithmic_bytes"])
 
+    # receiver feedback (cumulative ack + selective ranges) read off this workload's bitmap
+    report = torch.zeros(32 + 16 * 64, dtype=torch.uint8, device="cuda")
+    evs = []
+    for _ in range(30):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        b.record()
+        pkg.uccl_time_next_launch(a, b)
+        pkg.uccl_dedup_report(bitmap, w.n_bits, report, 64)
+        evs.append((a, b))
+    torch.cuda.synchronize()
+    report_us = float(np.median([a.elapsed_time(b) for a, b in evs[5:]])) * 1e3
+    hdr = report.cpu().numpy()
+    assert int(hdr[:8].view(np.uint64)[0]) == w.n_bits and int(hdr[20:24].view(np.uint32)[0]) == 1, \
+        "after a full step every chunk is acknowledged"
+
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dstc = torch.empty_like(src)
@@ -390,6 +406,8 @@ def main():
             "avg_launch_ms": dom["avg_ms"],
         },
         "kernels": kernels,
+        "dedup_report": {"n_bits": w.n_bits, "median_us": round(report_us, 2),
+                         "what": "ack_report_kernel: cumulative ack, applied count, selective ranges"},
     }
     if args.workload.startswith("config5"):
         result["us_per_message"] = round(per_step * 1e6 / w.extra["n_msgs"], 3)

@@ -164,6 +164,31 @@ int uccl_chunk_scatter_checked(void* dst, const void* recv_stage, const uccl_chu
 int uccl_dedup_reset(uint32_t* dedup_bitmap, uint64_t n_bits, void* stream);
 
 /*
+ * uccl_dedup_report -- receiver feedback for the control path, read off the bitmap
+ * (Section 3.2: seq / ack numbers guide retransmission; Section 4.3: selective
+ * retransmission needs to know which chunks above the cumulative point have arrived;
+ * Section 3.1: the control header's last-chunk bit marks message completion).
+ * Writes to `report` (device memory or pinned host memory, 8-byte aligned, room for
+ * sizeof(uccl_ack_report) + max_ranges * 16 bytes):
+ *   cum_ack    first clear bit in [0, n_bits), n_bits if none: every chunk below it is applied
+ *   n_applied  number of set bits in [0, n_bits)
+ *   n_ranges   number of maximal runs of set bits that start above cum_ack (may exceed
+ *              max_ranges; only the first max_ranges are written)
+ *   complete   1 if n_applied == n_bits
+ * followed by the runs in ascending order as pairs {start, end} of uint64_t, end exclusive.
+ * Bits at and above n_bits in the last word are ignored.  n_bits < 2^40.  Stream ordered.
+ */
+typedef struct uccl_ack_report {
+  uint64_t cum_ack;
+  uint64_t n_applied;
+  uint32_t n_ranges;
+  uint32_t complete;
+  uint64_t reserved;
+} uccl_ack_report;
+int uccl_dedup_report(const uint32_t* dedup_bitmap, uint64_t n_bits, void* report,
+                      uint32_t max_ranges, void* stream);
+
+/*
  * Launch shape: how records are mapped onto the machine.
  *   AUTO   = FLAT
  *   FLAT   a 1024-thread workgroup dedups a tile of records, cuts the winners into
@@ -184,7 +209,7 @@ int uccl_set_launch_shape(int shape);
  * it sets how many records a workgroup takes; results never depend on it. */
 int uccl_set_chunk_hint(uint32_t chunk_bytes);
 
-/* Measurement aid: the next apply / scatter call made by THIS host thread attaches the
+/* Measurement aid: the next apply / scatter / report call made by THIS host thread attaches the
  * two hipEvent_t (either may be NULL) to its kernel dispatch, so that
  * hipEventElapsedTime(start, stop) is that kernel's own execution time on the device,
  * without the queueing and launch gaps an event pair recorded around the call would

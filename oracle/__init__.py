@@ -61,6 +61,8 @@ def lib():
         L.orc_check_call.argtypes = [vp, u64, vp, u64]
         L.orc_pack_bitmap.restype = None
         L.orc_pack_bitmap.argtypes = [vp, u64, vp]
+        L.orc_ack_report.restype = None
+        L.orc_ack_report.argtypes = [vp, u64, vp, vp, vp, vp, C.c_uint32]
         L.orc_ring_allreduce.restype = C.c_int
         L.orc_ring_allreduce.argtypes = [vp, C.c_uint32, u64, C.c_int, C.c_int, vp]
         L.orc_combine_f32.restype = C.c_float
@@ -131,6 +133,18 @@ def pack_bitmap(seen) -> np.ndarray:
     words = np.zeros((len(seen) + 31) // 32, dtype=np.uint32)
     lib().orc_pack_bitmap(_ptr(seen), len(seen), _ptr(words))
     return words
+
+
+def ack_report(words, n_bits, max_ranges):
+    """Returns (cum_ack, n_applied, n_ranges, ranges[min(n_ranges, max_ranges)][2])."""
+    words = np.ascontiguousarray(words, dtype=np.uint32)
+    assert len(words) * 32 >= n_bits
+    ca, na = C.c_uint64(0), C.c_uint64(0)
+    nr = C.c_uint32(0)
+    ranges = np.zeros((max(max_ranges, 1), 2), dtype=np.uint64)
+    lib().orc_ack_report(_ptr(words), int(n_bits), C.addressof(ca), C.addressof(na), C.addressof(nr),
+                         _ptr(ranges), int(max_ranges))
+    return ca.value, na.value, nr.value, ranges[:min(nr.value, max_ranges)]
 
 
 def ring_allreduce(x, dtype, op=SUM) -> np.ndarray:

@@ -214,6 +214,33 @@ void orc_pack_bitmap(const uint8_t* seen, uint64_t n_bits, uint32_t* words) {
     if (seen[s]) words[s >> 5] |= (uint32_t)1 << (s & 31);
 }
 
+/* One pass over the bits, in order. */
+void orc_ack_report(const uint32_t* words, uint64_t n_bits, uint64_t* cum_ack, uint64_t* n_applied,
+                    uint32_t* n_ranges, uint64_t* ranges, uint32_t max_ranges) {
+  uint64_t first_clear = n_bits, count = 0, run_start = 0;
+  uint32_t runs = 0;
+  int in_run = 0;
+  for (uint64_t s = 0; s <= n_bits; ++s) {
+    int bit = s < n_bits ? (int)((words[s >> 5] >> (s & 31)) & 1u) : 0; /* a clear bit past the end closes a run */
+    if (bit) {
+      ++count;
+      if (!in_run) { in_run = 1; run_start = s; }
+    } else {
+      if (s < n_bits && first_clear == n_bits) first_clear = s;
+      if (in_run) {
+        in_run = 0;
+        if (run_start > 0) { /* the run that begins at bit 0 is the cumulative part */
+          if (runs < max_ranges) { ranges[2 * runs] = run_start; ranges[2 * runs + 1] = s; }
+          ++runs;
+        }
+      }
+    }
+  }
+  *cum_ack = first_clear;
+  *n_applied = count;
+  *n_ranges = runs;
+}
+
 /* ---- whole-call preconditions ---------------------------------------------- */
 
 typedef struct { uint64_t key, end; uint64_t idx; } ivl;

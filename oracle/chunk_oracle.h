@@ -76,6 +76,13 @@ int64_t orc_check_call(const void* recv_stage, uint64_t recv_bytes, const orc_de
 /* Pack seen[] into 32-bit words, bit (s & 31) of word (s >> 5) = seen[s]. */
 void orc_pack_bitmap(const uint8_t* seen, uint64_t n_bits, uint32_t* words);
 
+/* Receiver feedback read off a packed bitmap (Section 3.2 seq/ack, Section 4.3 selective
+ * retransmission): cum_ack = first clear bit (n_bits if none); n_applied = set bits;
+ * n_ranges = maximal runs of set bits starting above cum_ack, the first max_ranges of them
+ * written to ranges[] as {start, end} pairs with end exclusive, ascending. */
+void orc_ack_report(const uint32_t* words, uint64_t n_bits, uint64_t* cum_ack, uint64_t* n_applied,
+                    uint32_t* n_ranges, uint64_t* ranges, uint32_t max_ranges);
+
 /* Textbook in-order ring allreduce of R vectors of n elements (n % R == 0),
  * no chunks, no transport: x is R*n elements (rank-major), result is R*n
  * elements (every rank's final buffer).  Returns 0 or ORC_E_ARG. */

@@ -54,6 +54,7 @@ _SIGNATURES = {
                                              C.c_void_p, C.POINTER(uccl_extents), C.c_void_p,
                                              C.c_void_p]),
     "uccl_dedup_reset": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p]),
+    "uccl_dedup_report": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p]),
     "uccl_set_launch_shape": (C.c_int, [C.c_int]),
     "uccl_set_chunk_hint": (C.c_int, [C.c_uint32]),
     "uccl_time_next_launch": (C.c_int, [C.c_void_p, C.c_void_p]),
@@ -173,6 +174,15 @@ def uccl_chunk_scatter_checked(dst, recv_stage, descs, n_descs, dedup_bitmap, ex
 def uccl_dedup_reset(dedup_bitmap, n_bits, stream=None):
     _check(load().uccl_dedup_reset(_ptr(dedup_bitmap), int(n_bits), _stream(stream)),
            "uccl_dedup_reset")
+
+
+ACK_HEADER_BYTES = 32
+
+
+def uccl_dedup_report(dedup_bitmap, n_bits, report, max_ranges, stream=None):
+    """``report``: a tensor of at least 32 + 16 * max_ranges bytes (device or pinned host)."""
+    _check(load().uccl_dedup_report(_ptr(dedup_bitmap), int(n_bits), _ptr(report), int(max_ranges),
+                                    _stream(stream)), "uccl_dedup_report")
 
 
 def uccl_set_launch_shape(shape):

@@ -481,6 +481,106 @@ __global__ void __launch_bounds__(256) fill_words_kernel(uint32_t* p, uint64_t n
     p[i] = v;
 }
 
+// Receiver feedback from the dedup bitmap: cumulative acknowledgement (first clear bit),
+// number of applied chunks, and the runs of set bits above the cumulative point in
+// ascending order (what a selective-acknowledgement option would carry).  One 1024-thread
+// workgroup walks the words in order, 1024 words per round: thread i owns word i of the
+// round, finds run starts (bit set, previous bit clear) and run ends (bit set, next bit
+// clear) with two word-wide shifts, and a block-wide exclusive scan of the per-word counts
+// gives every start and end its ordinal, so the k-th start and the k-th end land in the
+// same output pair.  The bitmap is tiny next to the payload (one bit per chunk), so this is
+// a latency problem, not a bandwidth one: one workgroup, no atomics, no second pass.
+struct AckHeader {
+  uint64_t cum_ack, n_applied;
+  uint32_t n_ranges, complete;
+  uint64_t reserved;
+};
+
+__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t tid, uint32_t* s_wave,
+                                                         uint32_t* total) {
+  uint32_t incl = v;
+#pragma unroll
+  for (uint32_t d = 1; d < 64; d <<= 1) {
+    const uint32_t below = __shfl_up(incl, d, 64);
+    if ((tid & 63u) >= d) incl += below;
+  }
+  if ((tid & 63u) == 63u) s_wave[tid >> 6] = incl;
+  __syncthreads();
+  uint32_t base = 0, sum = 0;
+  for (uint32_t w = 0; w < 16; ++w) {
+    const uint32_t x = s_wave[w];
+    if (w < (tid >> 6)) base += x;
+    sum += x;
+  }
+  __syncthreads();  // s_wave is reused by the next scan
+  *total = sum;
+  return base + incl - v;
+}
+
+__global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __restrict__ bitmap,
+                                                          uint64_t n_bits, AckHeader* hdr,
+                                                          uint64_t* ranges, uint32_t max_ranges) {
+  __shared__ uint32_t s_wave[16];
+  __shared__ unsigned long long s_first_clear;
+  const uint32_t tid = threadIdx.x;
+  const uint64_t n_words = (n_bits + 31) / 32;
+  if (tid == 0) s_first_clear = ~0ull;
+  __syncthreads();
+  uint64_t applied = 0;      // per-thread partial popcount
+  uint32_t starts_seen = 0;  // runs started / ended in earlier rounds (same in every thread)
+  uint32_t ends_seen = 0;
+  for (uint64_t w0 = 0; w0 < n_words; w0 += 1024) {
+    const uint64_t w = w0 + tid;
+    uint32_t word = 0, prev_msb = 0, next_lsb = 0;
+    if (w < n_words) {
+      word = bitmap[w];
+      const uint64_t valid = n_bits - w * 32;  // bits of this word inside the bitmap
+      if (valid < 32) word &= (1u << valid) - 1u;
+      if (w > 0) prev_msb = bitmap[w - 1] >> 31;
+      if (w + 1 < n_words) {
+        uint32_t nx = bitmap[w + 1];
+        const uint64_t nvalid = n_bits - (w + 1) * 32;
+        if (nvalid < 32) nx &= (1u << nvalid) - 1u;
+        next_lsb = nx & 1u;
+      }
+      applied += __popc(word);
+      const uint32_t clear = ~word & (valid < 32 ? (1u << valid) - 1u : ~0u);
+      if (clear) atomicMin(&s_first_clear, w * 32 + (__ffs(clear) - 1));  // LDS atomic
+    }
+    const uint32_t starts = word & ~((word << 1) | prev_msb);
+    const uint32_t ends = word & ~((word >> 1) | (next_lsb << 31));
+    uint32_t n_starts, n_ends;
+    const uint32_t s_at = starts_seen + block_exclusive_scan(__popc(starts), tid, s_wave, &n_starts);
+    const uint32_t e_at = ends_seen + block_exclusive_scan(__popc(ends), tid, s_wave, &n_ends);
+    // ordinal 0 is the run that begins at bit 0, if there is one: that is the cumulative
+    // part, not a selective range; `skip` shifts the ordinals accordingly
+    const uint32_t skip = bitmap[0] & 1u;
+    uint32_t k = s_at;
+    for (uint32_t m = starts; m; m &= m - 1, ++k)
+      if (k >= skip && k - skip < max_ranges) ranges[2 * (k - skip)] = w * 32 + (__ffs(m) - 1);
+    k = e_at;
+    for (uint32_t m = ends; m; m &= m - 1, ++k)
+      if (k >= skip && k - skip < max_ranges) ranges[2 * (k - skip) + 1] = w * 32 + (__ffs(m) - 1) + 1;
+    starts_seen += n_starts;
+    ends_seen += n_ends;
+  }
+  // block-wide sum of the popcounts: 64-bit totals as two 32-bit scans would overflow only
+  // beyond 2^32 set bits per thread-lane, impossible for n_bits < 2^42; keep it simple
+  uint32_t tot_lo, tot_hi;
+  block_exclusive_scan(static_cast<uint32_t>(applied & 0xFFFFFu), tid, s_wave, &tot_lo);
+  block_exclusive_scan(static_cast<uint32_t>(applied >> 20), tid, s_wave, &tot_hi);
+  if (tid == 0) {
+    const uint64_t total = static_cast<uint64_t>(tot_lo) + (static_cast<uint64_t>(tot_hi) << 20);
+    const uint64_t first_clear = s_first_clear == ~0ull ? n_bits : s_first_clear;
+    const uint32_t skip = n_bits > 0 ? (bitmap[0] & 1u) : 0u;
+    hdr->cum_ack = first_clear;
+    hdr->n_applied = total;
+    hdr->n_ranges = starts_seen - skip;
+    hdr->complete = (total == n_bits) ? 1u : 0u;
+    hdr->reserved = 0;
+  }
+}
+
 // ---- host side ----------------------------------------------------------------------
 
 thread_local char t_detail[256] = "";
@@ -494,13 +594,13 @@ int launch_failed(hipError_t e) {
 }
 
 // Launch, attaching the one-shot timing events (if any) to this very dispatch.
-template <class Kernel>
-int launch_kernel(Kernel kernel, uint32_t tiles, uint32_t threads, const Args& a, hipStream_t s) {
+template <class Kernel, class... KernelArgs>
+int launch_kernel(Kernel kernel, uint32_t tiles, uint32_t threads, hipStream_t s, KernelArgs... a) {
   if (t_start != nullptr || t_stop != nullptr) {
-    hipExtLaunchKernelGGL(kernel, dim3(tiles), dim3(threads), 0, s, t_start, t_stop, 0, a);
+    hipExtLaunchKernelGGL(kernel, dim3(tiles), dim3(threads), 0, s, t_start, t_stop, 0, a...);
     t_start = t_stop = nullptr;
   } else {
-    hipLaunchKernelGGL(kernel, dim3(tiles), dim3(threads), 0, s, a);
+    hipLaunchKernelGGL(kernel, dim3(tiles), dim3(threads), 0, s, a...);
   }
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? UCCL_OK : launch_failed(e);
@@ -508,13 +608,13 @@ int launch_kernel(Kernel kernel, uint32_t tiles, uint32_t threads, const Args& a
 
 template <int NT, int T, int SG, int U, class Op>
 int launch(const Args& a, hipStream_t s) {
-  return launch_kernel(chunk_apply_kernel<NT, T, SG, U, Op>, (a.n_descs + T - 1) / T, NT, a, s);
+  return launch_kernel(chunk_apply_kernel<NT, T, SG, U, Op>, (a.n_descs + T - 1) / T, NT, s, a);
 }
 
 template <int T, int U, class Op>
 int launch_flat(const Args& a, hipStream_t s) {
   return launch_kernel(chunk_flat_kernel<UCCL_FLAT_THREADS, T, U, Op>, (a.n_descs + T - 1) / T,
-                       UCCL_FLAT_THREADS, a, s);
+                       UCCL_FLAT_THREADS, s, a);
 }
 
 // Records per workgroup for the flat shape: enough that a tile holds about 32 KiB of
@@ -671,6 +771,17 @@ int uccl_dedup_reset(uint32_t* dedup_bitmap, uint64_t n_bits, void* stream) {
                      dedup_bitmap, words, 0u);
   const hipError_t e = hipGetLastError();
   return e == hipSuccess ? UCCL_OK : launch_failed(e);
+}
+
+int uccl_dedup_report(const uint32_t* dedup_bitmap, uint64_t n_bits, void* report,
+                      uint32_t max_ranges, void* stream) {
+  if (!report || (n_bits > 0 && !dedup_bitmap)) return UCCL_EINVAL;
+  if (n_bits >= (1ull << 40)) return UCCL_EINVAL;
+  if (misaligned(dedup_bitmap, 4) || misaligned(report, 8)) return UCCL_EALIGN;
+  AckHeader* hdr = static_cast<AckHeader*>(report);
+  uint64_t* ranges = reinterpret_cast<uint64_t*>(hdr + 1);
+  return launch_kernel(ack_report_kernel, 1, 1024, static_cast<hipStream_t>(stream), dedup_bitmap,
+                       n_bits, hdr, ranges, max_ranges);
 }
 
 int uccl_time_next_launch(void* start_event, void* stop_event) {

@@ -20,7 +20,7 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"uccl_chunk_apply", "uccl_chunk_scatter", "uccl_dedup_reset", "uccl_strerror",
             "uccl_version", "uccl_chunk_apply_checked", "uccl_chunk_apply_indirect", "uccl_chunk_scatter_checked",
-            "uccl_set_launch_shape", "uccl_set_chunk_hint", "uccl_time_next_launch",
+            "uccl_set_launch_shape", "uccl_set_chunk_hint", "uccl_dedup_report", "uccl_time_next_launch",
             "uccl_last_error_detail"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
@@ -74,6 +74,10 @@ def test_host_side_error_codes_enqueue_nothing():
     r = lib.uccl_dedup_reset
     assert r(None, 8, None) == pkg.UCCL_EINVAL and r(M + 1, 8, None) == pkg.UCCL_EALIGN
     assert r(None, 0, None) == pkg.UCCL_OK
+    q = lib.uccl_dedup_report
+    assert q(M, 64, None, 4, None) == pkg.UCCL_EINVAL and q(None, 64, A, 4, None) == pkg.UCCL_EINVAL
+    assert q(M + 2, 64, A, 4, None) == pkg.UCCL_EALIGN and q(M, 64, A + 4, 4, None) == pkg.UCCL_EALIGN
+    assert q(M, 1 << 40, A, 4, None) == pkg.UCCL_EINVAL
     assert lib.uccl_set_launch_shape(9) == pkg.UCCL_EINVAL and lib.uccl_set_launch_shape(3) == pkg.UCCL_EINVAL and lib.uccl_set_launch_shape(0) == pkg.UCCL_OK
     assert pkg.uccl_strerror(pkg.UCCL_EALIGN) == "misaligned pointer"
     with pytest.raises(pkg.UcclError) as err:

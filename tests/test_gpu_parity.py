@@ -427,6 +427,58 @@ def test_bf16_sum_dense_pairs(gpu_lib):
     assert_same(acc[~nan], eacc[~nan], "bf16 sum")
 
 
+# ---- receiver feedback from the bitmap ---------------------------------------------------------
+
+@pytest.mark.parametrize("n_bits,density", [(0, 0.5), (1, 1.0), (31, 0.9), (32, 1.0), (33, 0.5), (1024, 0.98),
+                                            (1025, 0.5), (15360, 0.999), (100000, 0.7), (1 << 21, 0.9995)])
+def test_ack_report(gpu_lib, n_bits, density):
+    g = pl.rng(n_bits + 1, 4)
+    for trial in range(3):
+        bits = (g.random(n_bits) < density).astype(np.uint8)
+        if trial == 1 and n_bits:
+            bits[: n_bits * 2 // 3] = 1
+        b = np.zeros((n_bits + 31) // 32 * 32 + 32, dtype=np.uint8)
+        b[:n_bits] = bits
+        b[n_bits:] = 1  # bits past the end must be ignored
+        words = np.packbits(b, bitorder="little").view(np.uint32)
+        for max_ranges in (0, 3, 4096):
+            ca, na, nr, rg = oracle.ack_report(words, n_bits, max_ranges)
+            rep = torch.full((32 + 16 * max_ranges + 16,), 0xCD, dtype=torch.uint8, device="cuda")
+            gpu_lib.uccl_dedup_report(to_dev(words), n_bits, rep, max_ranges)
+            torch.cuda.synchronize()
+            raw = rep.cpu().numpy()
+            hdr = raw[:32].view(np.uint64)
+            assert (int(hdr[0]), int(hdr[1])) == (ca, na), (n_bits, trial)
+            assert (int(raw[16:20].view(np.uint32)[0]), int(raw[20:24].view(np.uint32)[0])) == (nr, int(na == n_bits))
+            got = raw[32:32 + 16 * min(nr, max_ranges)].view(np.uint64).reshape(-1, 2)
+            assert np.array_equal(got, rg), (n_bits, trial, max_ranges)
+            assert np.all(raw[32 + 16 * max_ranges:] == 0xCD), "wrote past the room given"
+
+
+def test_ack_report_after_a_lossy_phase(gpu_lib):
+    """Drop some chunks of a reduce-scatter phase, apply the rest, ask for the report into pinned
+    host memory: the holes are exactly the complement of cum_ack + ranges."""
+    w = wl.config2(seed=8, M=16 << 20)
+    ph = w.phases[0]
+    lost = {3, 4, 200, 201, 202, 479}
+    ph.descs = ph.descs[~np.isin(ph.descs["seq"], list(lost))]
+    run = DeviceRun(w)
+    run.apply(run.descs[0][:0], 0, SUM)
+    run.apply(to_dev(ph.descs), len(ph.descs), SUM)
+    rep = torch.zeros(32 + 16 * 16, dtype=torch.uint8, pin_memory=True)
+    gpu_lib.uccl_dedup_report(run.bitmap, 480, rep, 16)
+    torch.cuda.synchronize()
+    raw = rep.numpy()
+    cum, applied = int(raw[:8].view(np.uint64)[0]), int(raw[8:16].view(np.uint64)[0])
+    nr = int(raw[16:20].view(np.uint32)[0])
+    rg = raw[32:32 + 16 * nr].view(np.uint64).reshape(-1, 2)
+    assert cum == 3 and applied == 480 - len(lost) and raw[20] == 0
+    have = set(range(cum))
+    for a, b in rg:
+        have |= set(range(int(a), int(b)))
+    assert have == set(range(480)) - lost
+
+
 # ---- closed loop: the GPU path as every rank of a ring ------------------------------------------
 
 class GpuBackend:

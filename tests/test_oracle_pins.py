@@ -424,6 +424,60 @@ def test_closed_loop_new_types_match_textbook_ring(dtype, op):
         assert np.array_equal(expect[0], x.astype(np.int64).sum(axis=0).astype(np.int32))
 
 
+# --- receiver feedback from the bitmap -----------------------------------------------------
+
+def numpy_ack(bits):
+    """Independent reading of the same definition with numpy: first zero, popcount, and runs
+    from the positions where the padded bit sequence changes value."""
+    n = len(bits)
+    zeros = np.flatnonzero(bits == 0)
+    cum = int(zeros[0]) if len(zeros) else n
+    edges = np.flatnonzero(np.diff(np.concatenate([[0], bits, [0]]).astype(np.int8)))
+    runs = edges.reshape(-1, 2)
+    runs = runs[runs[:, 0] > 0]
+    return cum, int(bits.sum()), runs
+
+
+def test_ack_report_hand_cases():
+    pack = lambda bits: np.packbits(np.array(bits, dtype=np.uint8), bitorder="little").view(np.uint8)
+    def words_of(bits):
+        b = np.zeros((len(bits) + 31) // 32 * 32, dtype=np.uint8)
+        b[:len(bits)] = bits
+        return np.packbits(b, bitorder="little").view(np.uint32)
+    # 1110 0110 1: cumulative 3, applied 6, runs [5,7) and [8,9)
+    ca, na, nr, rg = oracle.ack_report(words_of([1, 1, 1, 0, 0, 1, 1, 0, 1]), 9, 8)
+    assert (ca, na, nr) == (3, 6, 2) and rg.tolist() == [[5, 7], [8, 9]]
+    ca, na, nr, rg = oracle.ack_report(words_of([0, 1, 1]), 3, 8)
+    assert (ca, na, nr) == (0, 2, 1) and rg.tolist() == [[1, 3]]
+    ca, na, nr, rg = oracle.ack_report(words_of([1] * 70), 70, 8)
+    assert (ca, na, nr) == (70, 70, 0)
+    ca, na, nr, rg = oracle.ack_report(words_of([0] * 40), 40, 8)
+    assert (ca, na, nr) == (0, 0, 0)
+    # a run across a word boundary; garbage above n_bits is ignored; more runs than room
+    bits = [1] * 30 + [0] + [1] * 5 + [0, 1, 0, 1, 0, 1]
+    w = words_of(bits).copy()
+    w[-1] |= np.uint32(0xFFFFFFFF) << np.uint32(len(bits) - 32)
+    ca, na, nr, rg = oracle.ack_report(w, len(bits), 2)
+    assert (ca, na, nr) == (30, 38, 4) and rg.tolist() == [[31, 36], [37, 38]]
+    assert oracle.ack_report(np.zeros(0, np.uint32), 0, 4)[:3] == (0, 0, 0)
+
+
+@pytest.mark.parametrize("n_bits,density", [(1, 0.5), (31, 0.9), (32, 0.9), (33, 0.5), (1000, 0.97), (5000, 0.5), (4097, 0.999)])
+def test_ack_report_against_numpy(n_bits, density):
+    g = pl.rng(n_bits, 3)
+    for trial in range(6):
+        bits = (g.random(n_bits) < density).astype(np.uint8)
+        if trial == 0:
+            bits[: n_bits // 2] = 1
+        b = np.zeros((n_bits + 31) // 32 * 32, dtype=np.uint8)
+        b[:n_bits] = bits
+        words = np.packbits(b, bitorder="little").view(np.uint32)
+        cum, cnt, runs = numpy_ack(bits)
+        ca, na, nr, rg = oracle.ack_report(words, n_bits, len(runs) + 3)
+        assert (ca, na, nr) == (cum, cnt, len(runs))
+        assert np.array_equal(rg.astype(np.int64), runs)
+
+
 # --- P7: a chunk that never arrives ------------------------------------------------
 
 def test_missing_chunk_leaves_hole_and_clear_bit():
