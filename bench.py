@@ -12,7 +12,7 @@ an HBM number.  `--also-warm` adds the same loop over a single buffer set (`warm
 
 Prints one JSON line: whole-job reduced-payload GB/s, the HBM-roofline fraction of the
 dominant kernel (algorithmic bytes / measured kernel time / 8 TB/s), and the CPU oracle
-timed on the host cores of the same box as a reported baseline.
+timed on the host cores of the same machine as a reported baseline.
 """
 import argparse
 import hashlib
@@ -237,7 +237,7 @@ def main():
                          "hardware counters of the same run can be scaled by)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: this build measures one GPU's share on one GPU; --gpus N>1 is not supported "
+        print("bench.py: the path is measured as one GPU's share on one GPU; --gpus N>1 is not supported "
               "(the path shards as one independent rank per GPU, there is nothing to aggregate)", file=sys.stderr)
         sys.exit(2)
 

@@ -62,10 +62,10 @@ uint16_t orc_f32_to_f16(float f) {
 }
 
 /* The tensor-buffer value a is combined with the received value r.
- * SUM: one binary32 add.  MAX / MIN: this build defines them as a strict
+ * SUM: one binary32 add.  MAX / MIN are defined here as a strict
  * comparison that keeps the local value on ties and whenever the comparison is
  * false, i.e. MAX(a,r) = r if r > a else a.  The paper names "sum, max" only
- * (Section 2.1); NaN and signed-zero behaviour is this build's choice. */
+ * (Section 2.1); NaN and signed-zero behaviour is a choice made here. */
 float orc_combine_f32(float a, float r, int op) {
   switch (op) {
     case ORC_SUM: return a + r;

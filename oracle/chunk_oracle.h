@@ -19,7 +19,7 @@
  * Parity status: every function is pinned by tests/test_oracle_pins.py except
  *  - MAX/MIN on NaN or mixed-sign zeros, and which copy of a duplicated sequence
  *    number supplies the bytes: the paper fixes neither ("parity unpinned"; the
- *    behaviour below is this build's definition, see the comments at each).
+ *    behaviour below is a definition made here, see the comments at each).
  */
 #ifndef CHUNK_ORACLE_H
 #define CHUNK_ORACLE_H

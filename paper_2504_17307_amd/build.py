@@ -12,7 +12,7 @@ LIB = os.path.join(PKG, "libuccl_chunk.so")
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-fno-fast-math", "-ffp-contract=off", "-fno-gpu-flush-denormals-to-zero",
-    # packed fp32 VALU forms are kept out of the generated code on the test machines
+    # keep packed fp32 VALU forms out of the generated code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
 ]

@@ -606,14 +606,18 @@ int launch_kernel(Kernel kernel, uint32_t tiles, uint32_t threads, hipStream_t s
   return e == hipSuccess ? UCCL_OK : launch_failed(e);
 }
 
+uint32_t tiles_for(uint32_t n_descs, uint32_t tile) {
+  return static_cast<uint32_t>((static_cast<uint64_t>(n_descs) + tile - 1) / tile);
+}
+
 template <int NT, int T, int SG, int U, class Op>
 int launch(const Args& a, hipStream_t s) {
-  return launch_kernel(chunk_apply_kernel<NT, T, SG, U, Op>, (a.n_descs + T - 1) / T, NT, s, a);
+  return launch_kernel(chunk_apply_kernel<NT, T, SG, U, Op>, tiles_for(a.n_descs, T), NT, s, a);
 }
 
 template <int T, int U, class Op>
 int launch_flat(const Args& a, hipStream_t s) {
-  return launch_kernel(chunk_flat_kernel<UCCL_FLAT_THREADS, T, U, Op>, (a.n_descs + T - 1) / T,
+  return launch_kernel(chunk_flat_kernel<UCCL_FLAT_THREADS, T, U, Op>, tiles_for(a.n_descs, T),
                        UCCL_FLAT_THREADS, s, a);
 }
 

@@ -349,7 +349,7 @@ def test_max_min_select_and_tie_rule():
     assert oracle.combine_f32(1.0, 2.0, MAX) == 2.0 and oracle.combine_f32(2.0, 1.0, MAX) == 2.0
     assert oracle.combine_f32(1.0, 2.0, MIN) == 1.0 and oracle.combine_f32(-3.0, 1.0, MIN) == -3.0
     assert oracle.combine_bf16(0x3F80, 0x4000, MAX) == 0x4000 and oracle.combine_bf16(0xC000, 0x3F80, MIN) == 0xC000
-    # this build's definition (not fixed by the paper): a tie or an unordered pair keeps the local value
+    # defined here (not fixed by the paper): a tie or an unordered pair keeps the local value
     assert oracle.combine_f32(0.0, -0.0, MAX).view(np.uint32) == 0
     assert oracle.combine_f32(-0.0, 0.0, MAX).view(np.uint32) == 0x80000000
     assert np.isnan(oracle.combine_f32(float("nan"), 1.0, MAX)) and oracle.combine_f32(1.0, float("nan"), MAX) == 1.0
