@@ -66,6 +66,31 @@ def call_stats(descs, op):
     return len(first), int(ln.sum()), algo
 
 
+def two_pass_calls(w, chunk):
+    """The paper's literal form (Section 3.1): first a scattered memcpy of the arrivals into an
+    in-order transport buffer (dedup + place), then the reduction from the transport buffer.
+    Returns the call list and the transport buffer size."""
+    from synth.layout import DESC, COPY
+    calls, seq0, most = [], 0, 0
+    for ph, lg in zip(w.phases, w.extra["logical"]):
+        d1 = ph.descs.copy()
+        d1["dst_off"] = (d1["seq"].astype(np.uint64) - np.uint64(seq0)) * np.uint64(chunk)
+        d1["out_off"] = np.uint64(0xFFFFFFFFFFFFFFFF)
+        u, pay, algo = call_stats(d1, COPY)
+        calls.append(dict(name=ph.name + ": scatter to transport buffer", op=COPY, descs=d1, n_unique=0,
+                          payload_bytes=0, algo_bytes=algo, scatter=True, dst="transport", src="recv", bm="bitmap"))
+        d2 = np.zeros(len(lg), dtype=DESC)
+        d2["src_off"] = np.arange(len(lg), dtype=np.uint64) * np.uint64(chunk)
+        d2["dst_off"], d2["out_off"], d2["len"] = lg["dst_off"], lg["out_off"], lg["len"]
+        d2["seq"] = lg["seq"]
+        u, pay, algo = call_stats(d2, ph.op)
+        calls.append(dict(name=ph.name + ": reduce from transport buffer", op=ph.op, descs=d2, n_unique=u,
+                          payload_bytes=pay, algo_bytes=algo, scatter=False, dst="acc", src="transport", bm="bitmap2"))
+        seq0 += len(lg)
+        most = max(most, len(lg))
+    return calls, most * chunk
+
+
 def build_job(name, seed, n_msgs, relay=False):
     """Returns (workload, calls, chunk_bytes) with calls = list of dicts
     {name, op, descs (numpy), n_unique, payload_bytes, algo_bytes, scatter}."""
@@ -229,6 +254,9 @@ def main():
     ap.add_argument("--relay", action="store_true",
                     help="ring workloads: flag intermediate reduce-scatter steps forward-only (their partial "
                          "sums are not written back to the accumulator: 3 instead of 4 bytes per payload byte)")
+    ap.add_argument("--two-pass", action="store_true",
+                    help="ring workloads: run the paper's literal two-pass form (scattered memcpy into a transport "
+                         "buffer, then reduce) instead of the fused single pass, for comparison")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--also-warm", action="store_true",
                     help="additionally time the same loop over a single buffer set (cache-resident accumulator)")
@@ -255,27 +283,37 @@ def main():
         chunk_bytes = args.chunk_hint
     if not args.no_chunk_hint:
         pkg.uccl_set_chunk_hint(chunk_bytes)
+    transport_bytes = 0
+    if args.two_pass:
+        calls, transport_bytes = two_pass_calls(w, chunk_bytes)
+        args.no_cpu_baseline = True  # the oracle defines the fused result; parity of this mode is checked below
     print(f"[bench] built {w.name} in {time.time() - t0:.1f}s: {w.note}", file=sys.stderr, flush=True)
 
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1)).cuda()
     sets = []
     for _ in range(max(1, args.sets)):
         sets.append(dict(acc=dev(w.acc), recv=dev(w.recv_stage),
-                         out=torch.zeros(max(w.out_bytes, 16), dtype=torch.uint8, device="cuda")))
+                         out=torch.zeros(max(w.out_bytes, 16), dtype=torch.uint8, device="cuda"),
+                         transport=torch.zeros(max(transport_bytes, 16), dtype=torch.uint8, device="cuda")))
     bitmap = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
+    bitmap2 = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
     descs = [dev(c["descs"]) for c in calls]
     counts = [len(c["descs"]) for c in calls]
 
     def call(i, s):
         c = calls[i]
+        bm = bitmap2 if c.get("bm") == "bitmap2" else bitmap
         if c["scatter"]:
-            pkg.uccl_chunk_scatter(s["acc"], s["recv"], descs[i], counts[i], bitmap)
+            pkg.uccl_chunk_scatter(s[c.get("dst", "acc")], s[c.get("src", "recv")], descs[i], counts[i], bm)
         else:
-            pkg.uccl_chunk_apply(s["acc"], s["out"], s["recv"], descs[i], counts[i], bitmap, w.dtype, c["op"])
+            pkg.uccl_chunk_apply(s["acc"], s["out"], s[c.get("src", "recv")], descs[i], counts[i], bm, w.dtype,
+                                 c["op"])
 
     def step(k, timed=None):
         s = sets[k % len(sets)]
         pkg.uccl_dedup_reset(bitmap, w.n_bits)
+        if args.two_pass:
+            pkg.uccl_dedup_reset(bitmap2, w.n_bits)
         for i in range(len(calls)):
             if timed is not None and i in timed:
                 # events attached to the dispatch itself: the kernel's own begin and end
@@ -384,7 +422,7 @@ def main():
                    "unique_chunks": unique, "arrivals": arrivals, "payload_bytes": payload,
                    "algorithmic_bytes": algo, "launch_shape": args.shape,
                    "chunk_hint": 0 if args.no_chunk_hint else chunk_bytes, "buffer_sets": len(sets),
-                   "forward_only_intermediate_steps": bool(args.relay),
+                   "forward_only_intermediate_steps": bool(args.relay), "two_pass": bool(args.two_pass),
                    "calls_per_step": 1 + len(calls), "cache": cache_note},
         "chunks_per_s": round(unique / per_step, 1),
         "arrivals_per_s": round(arrivals / per_step, 1),
@@ -413,6 +451,18 @@ def main():
         result["us_per_message"] = round(per_step * 1e6 / w.extra["n_msgs"], 3)
         result["config"]["messages"] = w.extra["n_msgs"]
 
+    if args.two_pass:
+        import oracle
+        eacc, eout, seen = w.acc.copy(), np.zeros(max(w.out_bytes, 16), dtype=np.uint8), oracle.new_seen(w.n_bits)
+        for ph in w.phases:
+            oracle.apply(eacc, eout, w.recv_stage, ph.descs, seen, w.dtype, ph.op, check=False)
+        same = (np.array_equal(first[0], eacc.view(np.uint8).reshape(-1)) and
+                np.array_equal(first[1], eout[:w.out_bytes]))
+        result["parity_first_pass"] = ("two-pass result bit-exact vs the oracle's single-pass definition (acc, out_stage)"
+                                       if same else "MISMATCH")
+        if not same:
+            print(json.dumps(result))
+            sys.exit(1)
     if not args.no_cpu_baseline:
         import oracle
         reps, cpu_t, exp = 0, 0.0, None

@@ -1,0 +1,134 @@
+/*
+ * The C ABI used from plain C, no Python and no PyTorch: device memory from hipMalloc, a
+ * small deterministic chunk stream built here (reordered, with duplicates), one call of
+ * each entry point, results compared byte for byte with the CPU oracle (linked as a
+ * separate library).  Prints "C ABI OK" and exits 0 on success.
+ *
+ * Build: hipcc -I include -I oracle tests/c_abi_check.c -L<pkg> -luccl_chunk -L oracle -lchunk_oracle
+ */
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include "chunk_oracle.h"
+#include "uccl_chunk.h"
+
+#define CK(x)                                                                          \
+  do {                                                                                 \
+    hipError_t e_ = (x);                                                               \
+    if (e_ != hipSuccess) {                                                            \
+      fprintf(stderr, "HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__);   \
+      return 2;                                                                        \
+    }                                                                                  \
+  } while (0)
+#define UC(x)                                                                          \
+  do {                                                                                 \
+    int c_ = (x);                                                                      \
+    if (c_ != UCCL_OK) {                                                               \
+      fprintf(stderr, "%s at line %d: %s\n", uccl_strerror(c_), __LINE__,              \
+              uccl_last_error_detail());                                               \
+      return 3;                                                                        \
+    }                                                                                  \
+  } while (0)
+
+static uint32_t lcg(uint32_t* s) { *s = *s * 1664525u + 1013904223u; return *s >> 8; }
+
+int main(void) {
+  enum { N = 300, C = 8192, DUP = 37 }; /* 300 logical chunks of 8 KiB, 37 retransmitted */
+  const uint64_t n_arr = N + DUP, acc_bytes = (uint64_t)N * C, recv_bytes = n_arr * C;
+  uint32_t seed = 12345u;
+
+  /* arrival order: a shuffle of all chunks plus duplicates of the first DUP of them */
+  uint32_t* order = (uint32_t*)malloc(sizeof(uint32_t) * n_arr);
+  for (uint32_t i = 0; i < N; ++i) order[i] = i;
+  for (uint32_t i = 0; i < DUP; ++i) order[N + i] = (i * 7u) % N;
+  for (uint64_t i = n_arr - 1; i > 0; --i) {
+    uint64_t j = lcg(&seed) % (i + 1);
+    uint32_t t = order[i]; order[i] = order[j]; order[j] = t;
+  }
+  float* chunk_val = (float*)malloc(acc_bytes); /* payload of logical chunk s */
+  for (uint64_t i = 0; i < acc_bytes / 4; ++i) chunk_val[i] = (float)(lcg(&seed) % 2001) / 1000.0f - 1.0f;
+  float* h_recv = (float*)malloc(recv_bytes);
+  float* h_acc = (float*)malloc(acc_bytes);
+  for (uint64_t i = 0; i < acc_bytes / 4; ++i) h_acc[i] = (float)(lcg(&seed) % 2001) / 500.0f - 2.0f;
+  uccl_chunk_desc* h_desc = (uccl_chunk_desc*)malloc(sizeof(uccl_chunk_desc) * n_arr);
+  for (uint64_t k = 0; k < n_arr; ++k) {
+    uint32_t s = order[k];
+    memcpy((char*)h_recv + k * C, (char*)chunk_val + (uint64_t)s * C, C);
+    h_desc[k].src_off = k * C;
+    h_desc[k].dst_off = (uint64_t)(N - 1 - s) * C; /* placed in reverse */
+    h_desc[k].out_off = (s % 3 == 0) ? UCCL_NO_FORWARD : (uint64_t)s * C;
+    h_desc[k].len = (s % 5 == 0) ? C - 48 : C;      /* some short chunks */
+    h_desc[k].seq = s;
+  }
+
+  /* oracle (its record layout is byte-compatible by construction of the interface) */
+  float* o_acc = (float*)malloc(acc_bytes);
+  unsigned char* o_out = (unsigned char*)calloc(acc_bytes, 1);
+  uint8_t* seen = (uint8_t*)calloc(N, 1);
+  memcpy(o_acc, h_acc, acc_bytes);
+  if (sizeof(orc_desc) != sizeof(uccl_chunk_desc)) return 4;
+  int64_t applied = orc_apply(o_acc, acc_bytes, o_out, acc_bytes, h_recv, recv_bytes, (const orc_desc*)h_desc,
+                              n_arr, seen, N, ORC_F32, ORC_SUM);
+  if (applied != N) { fprintf(stderr, "oracle applied %lld\n", (long long)applied); return 4; }
+  uint32_t o_words[(N + 31) / 32];
+  orc_pack_bitmap(seen, N, o_words);
+
+  /* GPU */
+  void *d_acc, *d_out, *d_recv, *d_desc, *d_bm, *d_rej, *d_rep;
+  hipStream_t st;
+  CK(hipStreamCreate(&st));
+  CK(hipMalloc(&d_acc, acc_bytes)); CK(hipMalloc(&d_out, acc_bytes)); CK(hipMalloc(&d_recv, recv_bytes));
+  CK(hipMalloc(&d_desc, sizeof(uccl_chunk_desc) * n_arr)); CK(hipMalloc(&d_bm, sizeof(o_words)));
+  CK(hipMalloc(&d_rej, 4)); CK(hipMalloc(&d_rep, sizeof(uccl_ack_report) + 16 * 8));
+  CK(hipMemcpy(d_acc, h_acc, acc_bytes, hipMemcpyHostToDevice));
+  CK(hipMemcpy(d_recv, h_recv, recv_bytes, hipMemcpyHostToDevice));
+  CK(hipMemcpy(d_desc, h_desc, sizeof(uccl_chunk_desc) * n_arr, hipMemcpyHostToDevice));
+  CK(hipMemset(d_out, 0, acc_bytes)); CK(hipMemset(d_rej, 0, 4)); CK(hipMemset(d_bm, 0xFF, sizeof(o_words)));
+  UC(uccl_dedup_reset((uint32_t*)d_bm, N, st));
+  uccl_extents ext = {acc_bytes, acc_bytes, recv_bytes, N};
+  /* first half through the checked entry point, second half through the plain one */
+  UC(uccl_chunk_apply_checked(d_acc, d_out, d_recv, (const uccl_chunk_desc*)d_desc, (uint32_t)(n_arr / 2),
+                              (uint32_t*)d_bm, UCCL_F32, UCCL_SUM, &ext, (uint32_t*)d_rej, st));
+  UC(uccl_chunk_apply(d_acc, d_out, d_recv, (const uccl_chunk_desc*)d_desc + n_arr / 2,
+                      (uint32_t)(n_arr - n_arr / 2), (uint32_t*)d_bm, UCCL_F32, UCCL_SUM, st));
+  UC(uccl_dedup_report((const uint32_t*)d_bm, N, d_rep, 8, st));
+  CK(hipStreamSynchronize(st));
+
+  float* g_acc = (float*)malloc(acc_bytes);
+  unsigned char* g_out = (unsigned char*)malloc(acc_bytes);
+  uint32_t g_words[(N + 31) / 32], rejected = 99;
+  uccl_ack_report rep;
+  CK(hipMemcpy(g_acc, d_acc, acc_bytes, hipMemcpyDeviceToHost));
+  CK(hipMemcpy(g_out, d_out, acc_bytes, hipMemcpyDeviceToHost));
+  CK(hipMemcpy(g_words, d_bm, sizeof(g_words), hipMemcpyDeviceToHost));
+  CK(hipMemcpy(&rejected, d_rej, 4, hipMemcpyDeviceToHost));
+  CK(hipMemcpy(&rep, d_rep, sizeof(rep), hipMemcpyDeviceToHost));
+  if (memcmp(g_acc, o_acc, acc_bytes)) { fprintf(stderr, "acc differs\n"); return 5; }
+  if (memcmp(g_out, o_out, acc_bytes)) { fprintf(stderr, "out_stage differs\n"); return 5; }
+  if (memcmp(g_words, o_words, sizeof(o_words))) { fprintf(stderr, "bitmap differs\n"); return 5; }
+  if (rejected != 0) { fprintf(stderr, "rejected %u\n", rejected); return 5; }
+  if (rep.cum_ack != N || rep.n_applied != N || rep.n_ranges != 0 || rep.complete != 1) {
+    fprintf(stderr, "report: cum %llu applied %llu ranges %u complete %u\n", (unsigned long long)rep.cum_ack,
+            (unsigned long long)rep.n_applied, rep.n_ranges, rep.complete);
+    return 5;
+  }
+
+  /* all-to-all scatter of the same stream into a fresh destination */
+  unsigned char* o_dst = (unsigned char*)calloc(acc_bytes, 1);
+  memset(seen, 0, N);
+  for (uint64_t k = 0; k < n_arr; ++k) h_desc[k].out_off = UCCL_NO_FORWARD;
+  if (orc_scatter(o_dst, acc_bytes, h_recv, recv_bytes, (const orc_desc*)h_desc, n_arr, seen, N) != N) return 6;
+  CK(hipMemcpy(d_desc, h_desc, sizeof(uccl_chunk_desc) * n_arr, hipMemcpyHostToDevice));
+  CK(hipMemset(d_acc, 0, acc_bytes));
+  UC(uccl_dedup_reset((uint32_t*)d_bm, N, st));
+  UC(uccl_chunk_scatter(d_acc, d_recv, (const uccl_chunk_desc*)d_desc, (uint32_t)n_arr, (uint32_t*)d_bm, st));
+  CK(hipStreamSynchronize(st));
+  CK(hipMemcpy(g_out, d_acc, acc_bytes, hipMemcpyDeviceToHost));
+  if (memcmp(g_out, o_dst, acc_bytes)) { fprintf(stderr, "scatter differs\n"); return 6; }
+
+  printf("C ABI OK: %d chunks, %d duplicates, version %d\n", (int)N, (int)DUP, uccl_version());
+  return 0;
+}

@@ -530,6 +530,16 @@ def test_stream_from_control_path_model(gpu_lib, shape):
     check_workload(gpu_lib, w, shape)
 
 
+def test_c_abi_from_plain_c(gpu_lib):
+    """A C program (no Python, no PyTorch) drives the library and checks it against the oracle."""
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi_check")
+    assert os.path.exists(exe), "tests/c_abi_check is not built: run __graft_entry__.build()"
+    r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "C ABI OK" in r.stdout, (r.returncode, r.stdout, r.stderr)
+
+
 def test_side_stream(gpu_lib):
     w = wl.config2(seed=9, M=8 << 20)
     run = DeviceRun(w)
