@@ -147,6 +147,38 @@ int uccl_chunk_apply_indirect(void* acc, void* out_stage, const void* recv_stage
                               void* stream);
 
 /*
+ * uccl_chunk_reduce_gather -- several senders' chunks for ONE destination chunk in one
+ * record (Section 2.1: the kernel reduces the transport buffers "from multiple sender GPUs"
+ * into the tensor buffer; direct reduce-scatter and tree steps have this shape).  For each
+ * first-arriving record:
+ *     t = acc[dst + i]
+ *     for j = 0 .. n_src-1:  t = op(t, recv_stage[src_off[j] + i])      -- in this order
+ *     acc[dst + i] = t  (unless UCCL_FORWARD_ONLY);  out_stage[out + i] = t  (if forwarding)
+ * SUM / PROD on bf16 and f16 keep t in binary32 across the whole fold and round once at the
+ * end; on f32 every step is one binary32 operation; MAX / MIN select as in uccl_chunk_apply.
+ * The order of sources is part of the record, so the result does not depend on arrival
+ * timing.  COPY is not defined here (UCCL_EINVAL).  The accumulator is read and written
+ * once per chunk: (n_src + 1) reads and 1 (+1 forwarding) writes per payload byte of one source.
+ * `seq` dedups the record as a whole: the control path issues it when all its sources are
+ * in, and may issue it again.  `extents` / `n_rejected` as in uccl_chunk_apply_checked, both
+ * may be NULL.  Records: 160 bytes, 16-byte aligned array.
+ */
+#define UCCL_MAX_SOURCES 16
+typedef struct uccl_gather_desc {
+  uint64_t dst_off;                    /* byte offset in acc, multiple of 16 */
+  uint64_t out_off;                    /* as in uccl_chunk_desc, incl. UCCL_NO_FORWARD / UCCL_FORWARD_ONLY */
+  uint32_t len;                        /* payload bytes of each source, multiple of the element size */
+  uint32_t seq;                        /* bit index in dedup_bitmap */
+  uint32_t n_src;                      /* 1 .. UCCL_MAX_SOURCES */
+  uint32_t reserved;
+  uint64_t src_off[UCCL_MAX_SOURCES];  /* byte offsets in recv_stage, multiples of 16, fold order */
+} uccl_gather_desc;
+int uccl_chunk_reduce_gather(void* acc, void* out_stage, const void* recv_stage,
+                             const uccl_gather_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
+                             uccl_dtype dtype, uccl_op op, const uccl_extents* extents,
+                             uint32_t* n_rejected, void* stream);
+
+/*
  * uccl_chunk_scatter -- all-to-all receive side (Section 2.1: copy from transport
  * buffers to tensor buffers; Section 3.1: scattered memcpy): dedup + place + byte copy
  * into `dst` at per-source offsets.  No combine, no forward (out_off must be

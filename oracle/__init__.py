@@ -26,6 +26,8 @@ ERRORS = {-1: "ARG", -2: "SEQ", -3: "ALIGN", -4: "BOUNDS", -5: "MISMATCH", -6: "
 
 DESC = np.dtype([("src_off", "<u8"), ("dst_off", "<u8"), ("out_off", "<u8"),
                  ("len", "<u4"), ("seq", "<u4")])
+GATHER_DESC = np.dtype([("dst_off", "<u8"), ("out_off", "<u8"), ("len", "<u4"), ("seq", "<u4"),
+                        ("n_src", "<u4"), ("reserved", "<u4"), ("src_off", "<u8", (16,))])
 
 
 class OraclePrecondition(ValueError):
@@ -55,6 +57,8 @@ def lib():
         vp, u64, i64 = C.c_void_p, C.c_uint64, C.c_int64
         L.orc_apply.restype = i64
         L.orc_apply.argtypes = [vp, u64, vp, u64, vp, u64, vp, u64, vp, u64, C.c_int, C.c_int]
+        L.orc_reduce_gather.restype = i64
+        L.orc_reduce_gather.argtypes = [vp, u64, vp, u64, vp, u64, vp, u64, vp, u64, C.c_int, C.c_int]
         L.orc_scatter.restype = i64
         L.orc_scatter.argtypes = [vp, u64, vp, u64, vp, u64, vp, u64]
         L.orc_check_call.restype = i64
@@ -110,6 +114,17 @@ def apply(acc, out_stage, recv_stage, descs, seen, dtype, op, check=True) -> int
                          0 if out_stage is None else out_stage.nbytes, _ptr(recv_stage),
                          recv_stage.nbytes, _ptr(d), len(d), _ptr(seen), len(seen),
                          int(dtype), int(op))
+    if rc < 0:
+        raise OraclePrecondition(rc)
+    return int(rc)
+
+
+def reduce_gather(acc, out_stage, recv_stage, descs, seen, dtype, op) -> int:
+    d = np.ascontiguousarray(descs)
+    assert d.dtype.itemsize == 160 and d.dtype.names == GATHER_DESC.names, "gather record layout"
+    rc = lib().orc_reduce_gather(_ptr(acc), acc.nbytes, _ptr(out_stage),
+                                 0 if out_stage is None else out_stage.nbytes, _ptr(recv_stage),
+                                 recv_stage.nbytes, _ptr(d), len(d), _ptr(seen), len(seen), int(dtype), int(op))
     if rc < 0:
         raise OraclePrecondition(rc)
     return int(rc)

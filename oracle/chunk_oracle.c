@@ -187,6 +187,71 @@ int64_t orc_apply(void* acc, uint64_t acc_bytes, void* out_stage, uint64_t out_b
   return applied;
 }
 
+int64_t orc_reduce_gather(void* acc, uint64_t acc_bytes, void* out_stage, uint64_t out_bytes,
+                          const void* recv_stage, uint64_t recv_bytes, const orc_gather_desc* descs,
+                          uint64_t n_descs, uint8_t* seen, uint64_t n_bits, int dtype, int op) {
+  if (dtype < ORC_F32 || dtype > ORC_I32) return ORC_E_ARG;
+  if (op != ORC_SUM && op != ORC_MAX && op != ORC_MIN && op != ORC_PROD) return ORC_E_ARG;
+  if (n_descs == 0) return 0;
+  if (!acc || !recv_stage || !descs || !seen) return ORC_E_ARG;
+  const uint32_t es = (dtype == ORC_F32 || dtype == ORC_I32) ? 4u : 2u;
+  int64_t applied = 0;
+  for (uint64_t k = 0; k < n_descs; ++k) {
+    const orc_gather_desc* d = &descs[k];
+    if (d->n_src < 1 || d->n_src > ORC_MAX_SOURCES) return ORC_E_ARG;
+    for (uint32_t j = 0; j < d->n_src; ++j) { /* every source slot obeys the single-source rules */
+      orc_desc one = {d->src_off[j], d->dst_off, d->out_off, d->len, d->seq};
+      int64_t rc = check_record(&one, acc_bytes, out_bytes, out_stage != NULL, recv_bytes, n_bits, es);
+      if (rc) return rc;
+    }
+    if (seen[d->seq]) continue;
+    seen[d->seq] = 1;
+    ++applied;
+    const uint64_t n = d->len / es;
+    const int fwd = d->out_off != ORC_NO_FORWARD;
+    const int keep = !(fwd && (d->out_off & ORC_FORWARD_ONLY));
+    const uint64_t out_at = d->out_off & ~ORC_FORWARD_ONLY;
+    for (uint64_t i = 0; i < n; ++i) {
+      if (dtype == ORC_F32) {
+        float* a = (float*)((char*)acc + d->dst_off) + i;
+        float t = *a;
+        for (uint32_t j = 0; j < d->n_src; ++j)
+          t = orc_combine_f32(t, ((const float*)((const char*)recv_stage + d->src_off[j]))[i], op);
+        if (keep) *a = t;
+        if (fwd) ((float*)((char*)out_stage + out_at))[i] = t;
+      } else if (dtype == ORC_I32) {
+        int32_t* a = (int32_t*)((char*)acc + d->dst_off) + i;
+        int32_t t = *a;
+        for (uint32_t j = 0; j < d->n_src; ++j)
+          t = orc_combine_i32(t, ((const int32_t*)((const char*)recv_stage + d->src_off[j]))[i], op);
+        if (keep) *a = t;
+        if (fwd) ((int32_t*)((char*)out_stage + out_at))[i] = t;
+      } else {
+        uint16_t* a = (uint16_t*)((char*)acc + d->dst_off) + i;
+        uint16_t t;
+        if (op == ORC_SUM || op == ORC_PROD) { /* binary32 running value, one rounding at the end */
+          float f = dtype == ORC_BF16 ? bf16_widen(*a) : orc_f16_to_f32(*a);
+          for (uint32_t j = 0; j < d->n_src; ++j) {
+            uint16_t r = ((const uint16_t*)((const char*)recv_stage + d->src_off[j]))[i];
+            float fr = dtype == ORC_BF16 ? bf16_widen(r) : orc_f16_to_f32(r);
+            f = op == ORC_SUM ? f + fr : f * fr;
+          }
+          t = dtype == ORC_BF16 ? orc_f32_to_bf16(f) : orc_f32_to_f16(f);
+        } else {
+          t = *a;
+          for (uint32_t j = 0; j < d->n_src; ++j) {
+            uint16_t r = ((const uint16_t*)((const char*)recv_stage + d->src_off[j]))[i];
+            t = dtype == ORC_BF16 ? orc_combine_bf16(t, r, op) : orc_combine_f16(t, r, op);
+          }
+        }
+        if (keep) *a = t;
+        if (fwd) ((uint16_t*)((char*)out_stage + out_at))[i] = t;
+      }
+    }
+  }
+  return applied;
+}
+
 int64_t orc_scatter(void* dst, uint64_t dst_bytes, const void* recv_stage, uint64_t recv_bytes,
                     const orc_desc* descs, uint64_t n_descs, uint8_t* seen, uint64_t n_bits) {
   if (n_descs == 0) return 0;

@@ -63,6 +63,19 @@ int64_t orc_apply(void* acc, uint64_t acc_bytes, void* out_stage, uint64_t out_b
                   const void* recv_stage, uint64_t recv_bytes, const orc_desc* descs,
                   uint64_t n_descs, uint8_t* seen, uint64_t n_bits, int dtype, int op);
 
+/* Several senders' chunks for one destination chunk (Section 2.1: reductions "from multiple
+ * sender GPUs"): t = acc; for each source in the listed order t = op(t, source); acc = t.
+ * 16-bit SUM / PROD keep t in binary32 over the whole fold and round once at the end. */
+#define ORC_MAX_SOURCES 16
+typedef struct {
+  uint64_t dst_off, out_off;
+  uint32_t len, seq, n_src, reserved;
+  uint64_t src_off[ORC_MAX_SOURCES];
+} orc_gather_desc;
+int64_t orc_reduce_gather(void* acc, uint64_t acc_bytes, void* out_stage, uint64_t out_bytes,
+                          const void* recv_stage, uint64_t recv_bytes, const orc_gather_desc* descs,
+                          uint64_t n_descs, uint8_t* seen, uint64_t n_bits, int dtype, int op);
+
 /* All-to-all scatter: byte copy, no forward, element type irrelevant. */
 int64_t orc_scatter(void* dst, uint64_t dst_bytes, const void* recv_stage, uint64_t recv_bytes,
                     const orc_desc* descs, uint64_t n_descs, uint8_t* seen, uint64_t n_bits);

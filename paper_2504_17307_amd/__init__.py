@@ -20,6 +20,8 @@ UCCL_OK, UCCL_EINVAL, UCCL_EALIGN, UCCL_ELAUNCH = 0, -1, -2, -3
 UCCL_NO_FORWARD = 0xFFFFFFFFFFFFFFFF
 UCCL_SHAPE_AUTO, UCCL_SHAPE_WAVE, UCCL_SHAPE_GROUP, UCCL_SHAPE_FLAT = 0, 1, 2, 4
 DESC_BYTES = 32
+GATHER_DESC_BYTES = 160
+UCCL_MAX_SOURCES = 16
 
 
 class uccl_extents(C.Structure):
@@ -48,6 +50,9 @@ _SIGNATURES = {
     "uccl_chunk_apply_indirect": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_uint32, C.c_void_p, C.c_int, C.c_int,
                                             C.POINTER(uccl_extents), C.c_void_p, C.c_void_p]),
+    "uccl_chunk_reduce_gather": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                           C.c_void_p, C.c_int, C.c_int, C.POINTER(uccl_extents),
+                                           C.c_void_p, C.c_void_p]),
     "uccl_chunk_scatter": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
                                      C.c_void_p]),
     "uccl_chunk_scatter_checked": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
@@ -155,6 +160,16 @@ def uccl_chunk_apply_indirect(acc, out_stage, recv_stage, descs, n_descs_ptr, ma
                                             _ptr(n_descs_ptr), int(max_descs), _ptr(dedup_bitmap),
                                             int(dtype), int(op), e, _ptr(n_rejected), _stream(stream)),
            "uccl_chunk_apply_indirect")
+
+
+def uccl_chunk_reduce_gather(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op,
+                             extents=None, n_rejected=None, stream=None, n_bits=None):
+    e = None
+    if extents is not None or n_bits is not None:
+        e = C.byref(_extents(extents, acc, out_stage, recv_stage, n_bits))
+    _check(load().uccl_chunk_reduce_gather(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
+                                           int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op), e,
+                                           _ptr(n_rejected), _stream(stream)), "uccl_chunk_reduce_gather")
 
 
 def uccl_chunk_scatter(dst, recv_stage, descs, n_descs, dedup_bitmap, stream=None):

@@ -154,6 +154,11 @@ struct OpF32 {
     if constexpr (K == kSum || K == kProd) return as_u32(arith<K>(as_f32(a), as_f32(r)));
     else return takes_received<K>(as_f32(a), as_f32(r)) ? r : a;
   }
+  // Folding several received words into one accumulator word, in the order given.
+  struct State { uint32_t v; };
+  static __device__ __forceinline__ State open(uint32_t a) { return State{a}; }
+  static __device__ __forceinline__ void fold(State& t, uint32_t r) { t.v = word(t.v, r); }
+  static __device__ __forceinline__ uint32_t close(const State& t) { return t.v; }
 };
 
 template <int K>
@@ -166,6 +171,10 @@ struct OpI32 {  // two's complement; SUM and PROD wrap modulo 2^32
     else if constexpr (K == kMax) return static_cast<int32_t>(r) > static_cast<int32_t>(a) ? r : a;
     else return static_cast<int32_t>(r) < static_cast<int32_t>(a) ? r : a;
   }
+  struct State { uint32_t v; };
+  static __device__ __forceinline__ State open(uint32_t a) { return State{a}; }
+  static __device__ __forceinline__ void fold(State& t, uint32_t r) { t.v = word(t.v, r); }
+  static __device__ __forceinline__ uint32_t close(const State& t) { return t.v; }
 };
 
 template <int K, class W>
@@ -180,6 +189,26 @@ struct Op16 {
     const uint32_t lo = half(a & 0xFFFFu, r & 0xFFFFu);
     const uint32_t hi = half(a >> 16, r >> 16);
     return (lo & 0xFFFFu) | (hi << 16);
+  }
+  // Several sources: SUM / PROD stay in binary32 across the whole fold and round once at
+  // the end; MAX / MIN carry the selected 16-bit pattern along with its widened value.
+  struct State { float lo, hi; uint32_t bits; };
+  static __device__ __forceinline__ State open(uint32_t a) {
+    return State{W::widen(a & 0xFFFFu), W::widen(a >> 16), a};
+  }
+  static __device__ __forceinline__ void fold(State& t, uint32_t r) {
+    const float rl = W::widen(r & 0xFFFFu), rh = W::widen(r >> 16);
+    if constexpr (K == kSum || K == kProd) {
+      t.lo = arith<K>(t.lo, rl);
+      t.hi = arith<K>(t.hi, rh);
+    } else {
+      if (takes_received<K>(t.lo, rl)) { t.lo = rl; t.bits = (t.bits & 0xFFFF0000u) | (r & 0xFFFFu); }
+      if (takes_received<K>(t.hi, rh)) { t.hi = rh; t.bits = (t.bits & 0x0000FFFFu) | (r & 0xFFFF0000u); }
+    }
+  }
+  static __device__ __forceinline__ uint32_t close(const State& t) {
+    if constexpr (K == kSum || K == kProd) return (W::narrow(t.lo) & 0xFFFFu) | (W::narrow(t.hi) << 16);
+    else return t.bits;
   }
 };
 
@@ -475,6 +504,183 @@ __global__ void __launch_bounds__(NT) chunk_flat_kernel(const Args g) {
   }
 }
 
+// ---- several sources per destination chunk ---------------------------------------------
+//
+// Section 2.1: the kernel reduces transport buffers "from multiple sender GPUs" into the
+// tensor buffer.  A gather record names up to UCCL_MAX_SOURCES receive slots for one
+// destination chunk; they are folded into the accumulator's value in the order listed, so
+// the floating-point result is fixed by the record, not by arrival timing.  The accumulator
+// is read and written once per chunk however many sources there are.  Same tile / unit
+// dealing as the flat shape; per unit a wavefront keeps the running value in registers
+// (widened to binary32 for 16-bit types) and streams one source after the other, the next
+// source's vectors already in flight while the current ones are folded.
+struct GatherArgs {
+  char* acc;
+  char* out;
+  const char* recv;
+  const uccl_gather_desc* descs;
+  uint32_t* bitmap;
+  uint32_t* rejected;
+  Extents ext;
+  uint32_t n_descs;
+};
+
+template <int T>
+struct GatherTile {
+  uint64_t dst[T], out[T];
+  uint64_t src[T][UCCL_MAX_SOURCES];
+  uint32_t len[T], n_src[T];
+  uint32_t first[T + 1];
+  uint32_t count;
+};
+
+template <int T, int U, class Op>
+__global__ void __launch_bounds__(1024) chunk_gather_kernel(const GatherArgs g) {
+  static_assert(T >= 1 && T <= 64, "one wavefront dedups the tile");
+  constexpr uint32_t kUnit = 64u * U;
+  __shared__ GatherTile<T> s;
+  const uint32_t tid = threadIdx.x;
+  if (tid < 64) {
+    const uint64_t k = static_cast<uint64_t>(blockIdx.x) * T + tid;
+    bool win = false;
+    uint64_t dst = 0, out = 0;
+    uint32_t len = 0, n_src = 0;
+    const uccl_gather_desc* d = g.descs + k;
+    if (tid < T && k < g.n_descs) {
+      const u32x4* p = reinterpret_cast<const u32x4*>(d);
+      const u32x4 lo = p[0], hi = p[1];
+      dst = lo.x | (static_cast<uint64_t>(lo.y) << 32);
+      out = lo.z | (static_cast<uint64_t>(lo.w) << 32);
+      len = hi.x;
+      const uint32_t seq = hi.y;
+      n_src = hi.z;
+      const bool fwd = out != UCCL_NO_FORWARD;
+      const uint64_t out_at = out & ~UCCL_FORWARD_ONLY;
+      bool ok = seq < g.ext.n_bits && (dst & 15u) == 0 && len % Op::kEs == 0 && n_src >= 1 &&
+                n_src <= UCCL_MAX_SOURCES && dst <= g.ext.acc_bytes && len <= g.ext.acc_bytes - dst;
+      if (fwd)
+        ok = ok && g.out != nullptr && (out_at & 15u) == 0 && out_at <= g.ext.out_bytes &&
+             len <= g.ext.out_bytes - out_at;
+      if (ok) {
+        for (uint32_t j = 0; j < n_src; ++j) {
+          const uint64_t so = d->src_off[j];
+          ok = ok && (so & 15u) == 0 && so <= g.ext.recv_bytes && len <= g.ext.recv_bytes - so;
+        }
+      }
+      if (ok) {
+        const uint32_t bit = 1u << (seq & 31u);
+        const uint32_t old = atomicOr(g.bitmap + (seq >> 5), bit);
+        win = (old & bit) == 0;
+      } else if (g.rejected != nullptr) {
+        atomicAdd(g.rejected, 1u);
+      }
+    }
+    const uint64_t winners = __ballot(win);
+    const uint32_t pos = __popcll(winners & ((1ull << tid) - 1ull));
+    const uint32_t count = __popcll(winners);
+    if (win) {
+      s.dst[pos] = dst;
+      s.out[pos] = out;
+      s.len[pos] = len;
+      s.n_src[pos] = n_src;
+      for (uint32_t j = 0; j < n_src; ++j) s.src[pos][j] = d->src_off[j];
+    }
+    if (tid == 0) s.count = count;
+    const uint32_t units = win ? (((len + 15u) >> 4) + kUnit - 1u) / kUnit : 0u;
+    uint32_t incl = units;
+#pragma unroll
+    for (uint32_t dlt = 1; dlt < 64; dlt <<= 1) {
+      const uint32_t below = __shfl_up(incl, dlt, 64);
+      if (tid >= dlt) incl += below;
+    }
+    if (win) s.first[pos] = incl - units;
+    if (tid == 63) s.first[count] = incl;
+  }
+  __syncthreads();
+
+  const uint32_t count = s.count;
+  const uint32_t total = s.first[count];
+  const uint32_t wave = tid >> 6, lane = tid & 63u;
+  for (uint32_t u = wave; u < total; u += 16u) {
+    uint32_t w = 0;
+    if (T > 1) {
+      const bool mine = lane < count && s.first[lane] <= u && u < s.first[lane + 1];
+      w = __ffsll(static_cast<unsigned long long>(__ballot(mine))) - 1;
+    }
+    w = __builtin_amdgcn_readfirstlane(w);
+    const uint32_t v0 = (u - __builtin_amdgcn_readfirstlane(s.first[w])) * kUnit;
+    const uint64_t dst = wave_uniform(s.dst[w]);
+    const uint64_t out = wave_uniform(s.out[w]);
+    const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
+    const uint32_t n_src = __builtin_amdgcn_readfirstlane(s.n_src[w]);
+    const uint32_t nvec = len >> 4;
+    const bool fwd = out != UCCL_NO_FORWARD;
+    const bool keep = !(fwd && (out & UCCL_FORWARD_ONLY));
+    u32x4* ap = reinterpret_cast<u32x4*>(g.acc + dst) + v0 + lane;
+    u32x4* op = reinterpret_cast<u32x4*>(g.out + (out & ~UCCL_FORWARD_ONLY)) + v0 + lane;
+    bool live[U];
+    typename Op::State st[U][4];
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      live[i] = v0 + lane + i * 64 < nvec;
+      u32x4 a = {0u, 0u, 0u, 0u};
+      if (live[i]) a = ap[i * 64];
+      st[i][0] = Op::open(a.x); st[i][1] = Op::open(a.y); st[i][2] = Op::open(a.z); st[i][3] = Op::open(a.w);
+    }
+    u32x4 cur[U], nxt[U];
+    {
+      const u32x4* rp = reinterpret_cast<const u32x4*>(g.recv + wave_uniform(s.src[w][0])) + v0 + lane;
+#pragma unroll
+      for (int i = 0; i < U; ++i) { cur[i] = u32x4{0u, 0u, 0u, 0u}; if (live[i]) cur[i] = __builtin_nontemporal_load(rp + i * 64); }
+    }
+    for (uint32_t j = 0; j < n_src; ++j) {
+      if (j + 1 < n_src) {
+        const u32x4* rp = reinterpret_cast<const u32x4*>(g.recv + wave_uniform(s.src[w][j + 1])) + v0 + lane;
+#pragma unroll
+        for (int i = 0; i < U; ++i) { nxt[i] = u32x4{0u, 0u, 0u, 0u}; if (live[i]) nxt[i] = __builtin_nontemporal_load(rp + i * 64); }
+      }
+#pragma unroll
+      for (int i = 0; i < U; ++i) {
+        Op::fold(st[i][0], cur[i].x); Op::fold(st[i][1], cur[i].y);
+        Op::fold(st[i][2], cur[i].z); Op::fold(st[i][3], cur[i].w);
+        cur[i] = nxt[i];
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      if (!live[i]) continue;
+      u32x4 t;
+      t.x = Op::close(st[i][0]); t.y = Op::close(st[i][1]); t.z = Op::close(st[i][2]); t.w = Op::close(st[i][3]);
+      if (keep) ap[i * 64] = t;
+      if (fwd) __builtin_nontemporal_store(t, op + i * 64);
+    }
+    // the last len % 16 bytes, element by element, by the unit that holds vector index nvec
+    const uint32_t rem = len & 15u;
+    if (rem && nvec >= v0 && nvec < v0 + kUnit && lane < rem / Op::kEs) {
+      const uint64_t off = (static_cast<uint64_t>(nvec) << 4) + lane * Op::kEs;
+      uint32_t a_el;
+      if constexpr (Op::kEs == 4) a_el = *reinterpret_cast<const uint32_t*>(g.acc + dst + off);
+      else a_el = *reinterpret_cast<const uint16_t*>(g.acc + dst + off);
+      typename Op::State t = Op::open(a_el);
+      for (uint32_t j = 0; j < n_src; ++j) {
+        const char* rp = g.recv + wave_uniform(s.src[w][j]) + off;
+        uint32_t r_el;
+        if constexpr (Op::kEs == 4) r_el = *reinterpret_cast<const uint32_t*>(rp);
+        else r_el = *reinterpret_cast<const uint16_t*>(rp);
+        Op::fold(t, r_el);
+      }
+      const uint32_t res = Op::close(t);
+      if constexpr (Op::kEs == 4) {
+        if (keep) *reinterpret_cast<uint32_t*>(g.acc + dst + off) = res;
+        if (fwd) *reinterpret_cast<uint32_t*>(g.out + (out & ~UCCL_FORWARD_ONLY) + off) = res;
+      } else {
+        if (keep) *reinterpret_cast<uint16_t*>(g.acc + dst + off) = static_cast<uint16_t>(res);
+        if (fwd) *reinterpret_cast<uint16_t*>(g.out + (out & ~UCCL_FORWARD_ONLY) + off) = static_cast<uint16_t>(res);
+      }
+    }
+  }
+}
+
 __global__ void __launch_bounds__(256) fill_words_kernel(uint32_t* p, uint64_t n, uint32_t v) {
   for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x; i < n;
        i += static_cast<uint64_t>(gridDim.x) * 256)
@@ -658,6 +864,22 @@ int launch_shape(const Args& a, hipStream_t s) {
   return UCCL_EINVAL;
 }
 
+
+template <int T, class Op>
+int launch_gather(const GatherArgs& a, hipStream_t s) {
+  return launch_kernel(chunk_gather_kernel<T, UCCL_FLAT_UNROLL, Op>, tiles_for(a.n_descs, T), 1024, s, a);
+}
+
+template <class Op>
+int launch_gather_tile(const GatherArgs& a, hipStream_t s) {
+  const uint32_t t = flat_tile(a.n_descs);
+  if (t >= 16) return launch_gather<16, Op>(a, s);
+  if (t >= 8) return launch_gather<8, Op>(a, s);
+  if (t >= 4) return launch_gather<4, Op>(a, s);
+  if (t >= 2) return launch_gather<2, Op>(a, s);
+  return launch_gather<1, Op>(a, s);
+}
+
 bool misaligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) != 0; }
 
 bool overlaps(const void* p, uint64_t pn, const void* q, uint64_t qn) {
@@ -748,6 +970,56 @@ int uccl_chunk_apply_indirect(void* acc, void* out_stage, const void* recv_stage
   if (max_descs > 0 && !n_descs_ptr) return UCCL_EINVAL;
   return apply_common(acc, out_stage, recv_stage, descs, max_descs, dedup_bitmap, dtype, op, true,
                       extents, n_rejected, stream, n_descs_ptr);
+}
+
+int uccl_chunk_reduce_gather(void* acc, void* out_stage, const void* recv_stage,
+                             const uccl_gather_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
+                             uccl_dtype dtype, uccl_op op, const uccl_extents* extents,
+                             uint32_t* n_rejected, void* stream) {
+  if (dtype < UCCL_F32 || dtype > UCCL_I32) return UCCL_EINVAL;
+  if (op != UCCL_SUM && op != UCCL_MAX && op != UCCL_MIN && op != UCCL_PROD) return UCCL_EINVAL;
+  if (n_descs == 0) return UCCL_OK;
+  if (!acc || !recv_stage || !descs || !dedup_bitmap) return UCCL_EINVAL;
+  if (misaligned(acc, 16) || misaligned(out_stage, 16) || misaligned(recv_stage, 16) ||
+      misaligned(descs, 16) || misaligned(dedup_bitmap, 4) || misaligned(n_rejected, 4))
+    return UCCL_EALIGN;
+  GatherArgs a;
+  a.acc = static_cast<char*>(acc);
+  a.out = static_cast<char*>(out_stage);
+  a.recv = static_cast<const char*>(recv_stage);
+  a.descs = descs;
+  a.bitmap = dedup_bitmap;
+  a.rejected = n_rejected;
+  a.n_descs = n_descs;
+  if (extents) {
+    if (overlaps(recv_stage, extents->recv_bytes, acc, extents->acc_bytes) ||
+        overlaps(recv_stage, extents->recv_bytes, out_stage, extents->out_bytes) ||
+        overlaps(acc, extents->acc_bytes, out_stage, extents->out_bytes))
+      return UCCL_EINVAL;
+    a.ext = Extents{extents->acc_bytes, out_stage ? extents->out_bytes : 0, extents->recv_bytes, extents->n_bits};
+  } else {
+    a.ext = Extents{UINT64_MAX, UINT64_MAX, UINT64_MAX, UINT64_MAX};
+  }
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  switch (dtype * 8 + op) {
+    case UCCL_F32 * 8 + UCCL_SUM: return launch_gather_tile<OpF32<kSum>>(a, s);
+    case UCCL_F32 * 8 + UCCL_MAX: return launch_gather_tile<OpF32<kMax>>(a, s);
+    case UCCL_F32 * 8 + UCCL_MIN: return launch_gather_tile<OpF32<kMin>>(a, s);
+    case UCCL_F32 * 8 + UCCL_PROD: return launch_gather_tile<OpF32<kProd>>(a, s);
+    case UCCL_BF16 * 8 + UCCL_SUM: return launch_gather_tile<Op16<kSum, WidenBF16>>(a, s);
+    case UCCL_BF16 * 8 + UCCL_MAX: return launch_gather_tile<Op16<kMax, WidenBF16>>(a, s);
+    case UCCL_BF16 * 8 + UCCL_MIN: return launch_gather_tile<Op16<kMin, WidenBF16>>(a, s);
+    case UCCL_BF16 * 8 + UCCL_PROD: return launch_gather_tile<Op16<kProd, WidenBF16>>(a, s);
+    case UCCL_F16 * 8 + UCCL_SUM: return launch_gather_tile<Op16<kSum, WidenF16>>(a, s);
+    case UCCL_F16 * 8 + UCCL_MAX: return launch_gather_tile<Op16<kMax, WidenF16>>(a, s);
+    case UCCL_F16 * 8 + UCCL_MIN: return launch_gather_tile<Op16<kMin, WidenF16>>(a, s);
+    case UCCL_F16 * 8 + UCCL_PROD: return launch_gather_tile<Op16<kProd, WidenF16>>(a, s);
+    case UCCL_I32 * 8 + UCCL_SUM: return launch_gather_tile<OpI32<kSum>>(a, s);
+    case UCCL_I32 * 8 + UCCL_MAX: return launch_gather_tile<OpI32<kMax>>(a, s);
+    case UCCL_I32 * 8 + UCCL_MIN: return launch_gather_tile<OpI32<kMin>>(a, s);
+    case UCCL_I32 * 8 + UCCL_PROD: return launch_gather_tile<OpI32<kProd>>(a, s);
+    default: return UCCL_EINVAL;
+  }
 }
 
 int uccl_chunk_scatter(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,

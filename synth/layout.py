@@ -20,6 +20,16 @@ DESC = np.dtype(
 )
 assert DESC.itemsize == 32
 
+#: one record per DESTINATION chunk with up to 16 source slots (multi-sender reduce), 160 bytes
+MAX_SOURCES = 16
+GATHER_DESC = np.dtype(
+    [
+        ("dst_off", "<u8"), ("out_off", "<u8"), ("len", "<u4"), ("seq", "<u4"),
+        ("n_src", "<u4"), ("reserved", "<u4"), ("src_off", "<u8", (MAX_SOURCES,)),
+    ]
+)
+assert GATHER_DESC.itemsize == 160
+
 NO_FORWARD = np.uint64(0xFFFFFFFFFFFFFFFF)
 FORWARD_ONLY = np.uint64(0x8000000000000000)  # flag in out_off: relay the result, do not write acc
 

@@ -23,7 +23,8 @@ import numpy as np
 
 from . import payload as pl
 from .arrivals import gen_arrivals, identity_arrivals, merge_streams
-from .layout import DESC, NO_FORWARD, FORWARD_ONLY, ELEM_SIZE, SUM, COPY, F32, BF16, F16, I32
+from .layout import (DESC, GATHER_DESC, MAX_SOURCES, NO_FORWARD, FORWARD_ONLY, ELEM_SIZE, SUM, COPY, F32, BF16,
+                     F16, I32)
 
 LOGICAL = np.dtype([("seq", "<u4"), ("dst_off", "<u8"), ("out_off", "<u8"), ("len", "<u4")])
 
@@ -250,6 +251,67 @@ def alltoall_dispatch(name: str, seed: int, n_src: int, row_bytes: int, max_byte
     ]
     w.extra["lengths"] = lengths
     return w
+
+
+def direct_reduce_scatter(name: str, seed: int, R: int, M: int, C: int, dtype: int, paths: int, dup: float,
+                          dist: str, op: int = SUM, reissue: float = 0.02) -> Workload:
+    """Direct (one-hop) reduce-scatter receive side: each of the R-1 peers sends its copy
+    of this rank's segment (M/R bytes, chunked at C) over its own multipath connection; the
+    streams interleave at the receiver.  The control path emits one gather record per
+    destination chunk at the moment the last of its R-1 source chunks has arrived, listing
+    the first-arrived slot of every source in source-rank order; retransmitted source chunks
+    occupy slots but produce no record.  With probability ``reissue`` a record is emitted a
+    second time later on (a repeated hand-over the GPU must drop).  workload.phases[0].descs
+    holds GATHER_DESC records; the accumulator is the rank's own segment."""
+    es = ELEM_SIZE[dtype]
+    n_src = R - 1
+    assert 1 <= n_src <= MAX_SOURCES and M % R == 0
+    S = M // R
+    n = -(-S // C)
+    per_src = [gen_arrivals(seed, n, paths, None, dup, stream=200 + p)[0] for p in range(n_src)]
+    order = merge_streams(seed, [len(a) for a in per_src], stream=7)
+    cursor = [0] * n_src
+    first_slot = np.full((n_src, n), -1, dtype=np.int64)
+    have = np.zeros(n, dtype=np.int64)
+    src_of_slot, chunk_of_slot, emit = [], [], []
+    for k, p in enumerate(order):
+        c = int(per_src[p][cursor[p]])
+        cursor[p] += 1
+        src_of_slot.append(p)
+        chunk_of_slot.append(c)
+        if first_slot[p, c] < 0:
+            first_slot[p, c] = k
+            have[c] += 1
+            if have[c] == n_src:
+                emit.append(c)
+    g = pl.rng(seed, 0xD1D)
+    again = [c for c in emit if g.random() < reissue]
+    seq_list = list(emit)
+    for c in again:  # somewhere after the original
+        at = seq_list.index(c) + 1 + int(g.integers(0, max(1, len(seq_list) // 4)))
+        seq_list.insert(min(at, len(seq_list)), c)
+    d = np.zeros(len(seq_list), dtype=GATHER_DESC)
+    for i, c in enumerate(seq_list):
+        d[i]["dst_off"] = c * C
+        d[i]["out_off"] = NO_FORWARD
+        d[i]["len"] = min(C, S - c * C)
+        d[i]["seq"] = c
+        d[i]["n_src"] = n_src
+        d[i]["src_off"][:n_src] = first_slot[:, c] * C
+    per = C // es
+    recv = np.zeros(len(order) * per, dtype=pl.np_dtype(dtype))
+    view = recv.reshape(-1, per)
+    sos, cos = np.array(src_of_slot), np.array(chunk_of_slot)
+    for p in range(n_src):
+        uq = _draw(dist, dtype, seed, 300 + p, n * per).reshape(n, per)
+        idx = np.flatnonzero(sos == p)
+        view[idx] = uq[cos[idx]]
+    acc = _draw(dist, dtype, seed, 1, S // es)
+    ln = np.minimum(C, S - np.arange(n, dtype=np.int64) * C)
+    algo = int((n_src + 1) * ln.sum() + ln.sum()) + (160 + 4) * len(d)
+    ph = Phase("gather-reduce", op, d, n, int(n_src * ln.sum()), algo)
+    return Workload(name, dtype, acc, recv, 0, n, [ph],
+                    note=f"direct reduce-scatter R={R} M={M} C={C} paths={paths} dup={dup} dist={dist}")
 
 
 def small_messages(name: str, seed: int, n_msgs: int, R: int, C: int, paths: int, dup: float,

@@ -1,0 +1,238 @@
+"""Multi-sender reduce (one record folds several receive slots into one destination chunk):
+oracle pins on the CPU, parity of the GPU path under -m gpu."""
+import numpy as np
+import pytest
+
+import oracle
+from synth import payload as pl
+from synth import workloads as wl
+from synth.layout import GATHER_DESC, DESC, NO_FORWARD, FORWARD_ONLY, F32, BF16, F16, I32, SUM, MAX, MIN, PROD, ELEM_SIZE
+
+from test_oracle_pins import nearest_even_bf16
+
+
+def run_oracle(w, op=None):
+    acc = w.acc.copy()
+    out = np.zeros(max(w.out_bytes, 16), dtype=np.uint8) if w.out_bytes else None
+    seen = oracle.new_seen(w.n_bits)
+    ph = w.phases[0]
+    n = oracle.reduce_gather(acc, out, w.recv_stage, ph.descs, seen, w.dtype, ph.op if op is None else op)
+    return acc, out, oracle.pack_bitmap(seen), n
+
+
+def numpy_fold(w, f, order=None):
+    """Third opinion for fp32 / int32: fold each destination chunk with numpy, one
+    operation (one rounding) per source, in the record's order."""
+    acc = w.acc.copy()
+    es = ELEM_SIZE[w.dtype]
+    done = set()
+    for d in w.phases[0].descs:
+        if int(d["seq"]) in done:
+            continue
+        done.add(int(d["seq"]))
+        n, t = d["len"] // es, d["dst_off"] // es
+        val = acc[t:t + n]
+        srcs = d["src_off"][:d["n_src"]]
+        for so in (srcs if order is None else srcs[order]):
+            val = f(val, w.recv_stage[so // es: so // es + n])
+        acc[t:t + n] = val
+    return acc
+
+
+def make(dtype, dist="uniform", op=SUM, R=8, C=1024, chunks=37, seed=3, **kw):
+    es = ELEM_SIZE[dtype]
+    M = R * (chunks * C - 3 * 16)  # the last chunk is short
+    return wl.direct_reduce_scatter("g", seed, R=R, M=M, C=C, dtype=dtype, paths=5, dup=0.15, dist=dist, op=op,
+                                    reissue=0.3, **kw)
+
+
+def test_fp32_fold_in_listed_order_against_numpy():
+    w = make(F32)
+    with np.errstate(over="ignore"):
+        acc, _, bm, n = run_oracle(w)
+        assert n == w.phases[0].n_unique and len(w.phases[0].descs) > n, "stream re-issues some records"
+        assert np.array_equal(acc, numpy_fold(w, np.add))
+        # the order of sources is part of the result: another order gives another rounding somewhere
+        rev = w.phases[0].descs.copy()
+        k = int(rev["n_src"][0])
+        rev["src_off"][:, :k] = rev["src_off"][:, :k][:, ::-1]
+        w.phases[0].descs = rev
+        acc_rev = run_oracle(w)[0]
+        assert np.array_equal(acc_rev, numpy_fold(w, np.add))
+        assert not np.array_equal(acc_rev, acc)
+        assert np.allclose(acc_rev, acc, rtol=1e-5, atol=1e-5)
+
+
+@pytest.mark.parametrize("op,f", [(MAX, np.maximum), (MIN, np.minimum), (PROD, np.multiply)])
+def test_fp32_other_ops_against_numpy(op, f):
+    w = make(F32, op=op, R=4)
+    assert np.array_equal(run_oracle(w)[0], numpy_fold(w, f))
+
+
+def test_int32_wraps_and_matches_numpy():
+    w = make(I32, R=6)
+    with np.errstate(over="ignore"):
+        assert np.array_equal(run_oracle(w)[0], numpy_fold(w, np.add))
+        assert np.array_equal(run_oracle(w, PROD)[0], numpy_fold(w, np.multiply))
+    assert np.array_equal(run_oracle(w, MAX)[0], numpy_fold(w, np.maximum))
+
+
+def test_bf16_accumulates_in_fp32_and_rounds_once():
+    w = make(BF16, dist="normal", R=8)
+    wide = lambda h: (h.astype(np.uint32) << 16).view(np.float32)
+    acc32 = wide(w.acc).copy()
+    per_hop = w.acc.copy()
+    done = set()
+    for d in w.phases[0].descs:
+        if int(d["seq"]) in done:
+            continue
+        done.add(int(d["seq"]))
+        n, t = d["len"] // 2, d["dst_off"] // 2
+        for so in d["src_off"][:d["n_src"]]:
+            r = wide(w.recv_stage[so // 2: so // 2 + n])
+            acc32[t:t + n] = acc32[t:t + n] + r                       # numpy fp32 add
+            per_hop[t:t + n] = nearest_even_bf16(wide(per_hop[t:t + n]) + r)
+    expect = w.acc.copy()
+    S = len(expect)
+    expect[:] = nearest_even_bf16(acc32)
+    got = run_oracle(w)[0]
+    assert np.array_equal(got, expect)
+    # and that is not the same as rounding after every source (what chained single applies do)
+    assert not np.array_equal(got, per_hop)
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16, F16, I32])
+def test_integer_inputs_give_the_exact_sum(dtype):
+    es = ELEM_SIZE[dtype]
+    w = make(dtype, dist="smallint", R=9)
+    got = run_oracle(w)[0]
+    vals = {F32: lambda x: x.astype(np.int64), I32: lambda x: x.astype(np.int64),
+            BF16: lambda x: pl.bf16_bits_to_f64(x).astype(np.int64),
+            F16: lambda x: x.view(np.float16).astype(np.int64)}[dtype]
+    total = vals(w.acc).copy()
+    done = set()
+    for d in w.phases[0].descs:
+        if int(d["seq"]) in done:
+            continue
+        done.add(int(d["seq"]))
+        n, t = d["len"] // es, d["dst_off"] // es
+        for so in d["src_off"][:d["n_src"]]:
+            total[t:t + n] += vals(w.recv_stage[so // es: so // es + n])
+    assert np.array_equal(vals(got), total) and np.abs(total).max() <= 9 * 8
+
+
+def test_one_source_is_the_plain_apply():
+    w = make(F32, R=2)
+    g = w.phases[0].descs
+    d = np.zeros(len(g), dtype=DESC)
+    d["src_off"], d["dst_off"], d["out_off"], d["len"], d["seq"] = g["src_off"][:, 0], g["dst_off"], g["out_off"], g["len"], g["seq"]
+    acc = w.acc.copy()
+    oracle.apply(acc, None, w.recv_stage, d, oracle.new_seen(w.n_bits), F32, SUM)
+    assert np.array_equal(acc, run_oracle(w)[0])
+
+
+def test_forwarding_and_relay_flags():
+    w = make(F32, R=4)
+    d = w.phases[0].descs.copy()
+    d["out_off"] = d["dst_off"]
+    d["out_off"][d["seq"] % 2 == 1] |= FORWARD_ONLY
+    w.phases[0].descs = d
+    w.out_bytes = w.acc.nbytes
+    acc, out, _, _ = run_oracle(w)
+    full = numpy_fold(w, np.add)
+    S = 1024 // 4
+    for c in range(w.n_bits):
+        seg = slice(c * S, min((c + 1) * S, len(full)))
+        assert np.array_equal(out.view(np.float32)[seg], full[seg])
+        assert np.array_equal(acc[seg], w.acc[seg] if c % 2 else full[seg])
+
+
+def test_rejects_malformed_records():
+    acc, recv = np.zeros(64, np.float32), np.zeros(256, np.float32)
+    def rec(n_src=2, src=(0, 256), dst=0, ln=64):
+        d = np.zeros(1, dtype=GATHER_DESC)
+        d["dst_off"], d["out_off"], d["len"], d["seq"], d["n_src"] = dst, NO_FORWARD, ln, 0, n_src
+        d["src_off"][0, :len(src)] = src
+        return d
+    for bad, code in ((rec(n_src=0), -1), (rec(n_src=17), -1), (rec(src=(0, 8)), -3), (rec(src=(0, 1024 - 32)), -4),
+                      (rec(dst=256), -4), (rec(ln=62), -3)):
+        with pytest.raises(oracle.OraclePrecondition) as e:
+            oracle.reduce_gather(acc, None, recv, bad, oracle.new_seen(1), F32, SUM)
+        assert e.value.code == code
+    with pytest.raises(oracle.OraclePrecondition):
+        oracle.reduce_gather(acc, None, recv, rec(), oracle.new_seen(1), F32, 3)  # COPY is not a fold
+
+
+# ---- GPU parity ----------------------------------------------------------------------------------
+
+def gpu_run(pkg, w, op=None, checked=True):
+    import torch
+    from gpuhelp import to_dev, to_host
+    ph = w.phases[0]
+    acc, recv = to_dev(w.acc), to_dev(w.recv_stage)
+    out = torch.zeros(max(w.out_bytes, 16), dtype=torch.uint8, device="cuda") if w.out_bytes else None
+    bm = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
+    rej = torch.zeros(1, dtype=torch.int32, device="cuda")
+    pkg.uccl_chunk_reduce_gather(acc, out, recv, to_dev(ph.descs), len(ph.descs), bm, w.dtype,
+                                 ph.op if op is None else op, n_rejected=rej if checked else None,
+                                 n_bits=w.n_bits if checked else None)
+    torch.cuda.synchronize()
+    return (to_host(acc, w.acc.dtype), None if out is None else out.cpu().numpy(),
+            bm.cpu().numpy().view(np.uint32), int(rej.item()))
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("hint", [0, 1024, 4096, 65536])
+@pytest.mark.parametrize("dtype,op", [(F32, SUM), (BF16, SUM), (F16, SUM), (I32, SUM), (BF16, MAX), (F16, MIN),
+                                      (F32, PROD), (BF16, PROD), (I32, MAX)])
+def test_gpu_gather_reduce_parity(gpu_lib, dtype, op, hint):
+    from gpuhelp import assert_same
+    w = make(dtype, dist="normal" if dtype == BF16 else "uniform", op=op, R=8, C=4112, chunks=29)
+    gpu_lib.uccl_set_chunk_hint(hint)
+    try:
+        for checked in (True, False):
+            acc, out, bm, rej = gpu_run(gpu_lib, w, checked=checked)
+            eacc, eout, ebm, _ = run_oracle(w)
+            assert rej == 0
+            assert_same(bm, ebm, "bitmap")
+            wide = {F32: lambda x: x, BF16: lambda x: (x.astype(np.uint32) << 16).view(np.float32),
+                    F16: lambda x: x.view(np.float16).astype(np.float32), I32: lambda x: x.astype(np.float32)}[dtype]
+            with np.errstate(over="ignore", invalid="ignore"):
+                nan = np.isnan(wide(eacc))
+            assert np.array_equal(np.isnan(wide(acc)), nan)
+            assert_same(acc[~nan], eacc[~nan], "acc")
+    finally:
+        gpu_lib.uccl_set_chunk_hint(0)
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("R", [2, 3, 17])
+def test_gpu_gather_source_counts_forward_and_rejects(gpu_lib, R):
+    from gpuhelp import assert_same
+    w = make(F32, R=R, C=2064, chunks=11)
+    d = w.phases[0].descs.copy()
+    d["out_off"] = d["dst_off"]
+    d["out_off"][d["seq"] % 3 == 1] |= FORWARD_ONLY
+    d["out_off"][d["seq"] % 3 == 2] = NO_FORWARD
+    bad = d[:3].copy()
+    bad["seq"] = [w.n_bits + 5, 0, 1]           # out of range seq; too many / zero sources
+    bad["n_src"][1], bad["n_src"][2] = 17, 0
+    w.phases[0].descs = np.concatenate([bad, d])
+    w.out_bytes = w.acc.nbytes
+    acc, out, bm, rej = gpu_run(gpu_lib, w)
+    assert rej == 3
+    w.phases[0].descs = d
+    eacc, eout, ebm, _ = run_oracle(w)
+    assert_same(acc, eacc, "acc"); assert_same(out[:w.out_bytes], eout[:w.out_bytes], "out_stage"); assert_same(bm, ebm, "bitmap")
+
+
+@pytest.mark.gpu
+def test_gpu_gather_exactly_once_all_ones(gpu_lib):
+    w = make(BF16, dist="ones", R=16, C=8192, chunks=64)
+    w.acc[:] = pl.ints_as(np.zeros(1, dtype=np.int64), BF16)[0]
+    d = w.phases[0].descs
+    w.phases[0].descs = np.concatenate([d, d[::2], d[::-1]])  # every record several times, far apart
+    acc, _, bm, rej = gpu_run(gpu_lib, w)
+    fifteen = pl.ints_as(np.array([15]), BF16)[0]
+    assert rej == 0 and np.all(acc == fifteen)
+    assert sum(int(x).bit_count() for x in bm) == w.n_bits
