@@ -40,6 +40,8 @@ WORKLOADS = {
     "config3": "reduce-scatter rank share: R=8, 1 GiB fp32 uniform[-1,1], 128 KiB chunks, 64 paths, window 256, 0.5% duplicates",
     "config4": "all-to-all dispatch: 7 sources x U[0,16 MiB] of 14336-byte bf16 rows, 16 KiB chunks, 128 paths, 1% duplicates",
     "config5": "small allreduces: fp32, 64 KiB-1 MiB log-uniform, R=8, 4 KiB chunks, 32 paths, 3% duplicates, 128 messages per call",
+    "direct-rs": "direct (one-hop) reduce-scatter: R=8, 1 GiB fp32, 7 senders' copies of this rank's 128 MiB segment "
+                 "folded in rank order by gather records, 128 KiB chunks, 64 paths per sender, 0.5% duplicates",
     "config5-single": "small allreduces, one message at a time (two calls per message)",
     "config5-graph": "small allreduces, one message at a time: the control path rewrites a pinned descriptor "
                      "slot and replays a captured graph of the two calls (no per-message argument marshalling)",
@@ -102,6 +104,12 @@ def build_job(name, seed, n_msgs, relay=False):
                       payload_bytes=ph.payload_bytes, algo_bytes=ph.algo_bytes, scatter=False)
                  for ph in w.phases]
         return w, calls, {"config1": 64 << 10, "config2": 32 << 10, "config3": 128 << 10}[name]
+    if name == "direct-rs":
+        w = wl.direct_reduce_scatter("direct-reduce-scatter-1GiB-f32", seed, R=8, M=1 << 30, C=128 << 10, dtype=0,
+                                     paths=64, dup=0.005, dist="uniform")
+        ph = w.phases[0]
+        return w, [dict(name="gather-reduce", op=SUM, descs=ph.descs, n_unique=ph.n_unique,
+                        payload_bytes=ph.payload_bytes, algo_bytes=ph.algo_bytes, scatter=False, gather=True)], 128 << 10
     if name == "config4":
         w = wl.config4(seed=seed)
         ph = w.phases[0]
@@ -303,7 +311,9 @@ def main():
     def call(i, s):
         c = calls[i]
         bm = bitmap2 if c.get("bm") == "bitmap2" else bitmap
-        if c["scatter"]:
+        if c.get("gather"):
+            pkg.uccl_chunk_reduce_gather(s["acc"], None, s["recv"], descs[i], counts[i], bm, w.dtype, c["op"])
+        elif c["scatter"]:
             pkg.uccl_chunk_scatter(s[c.get("dst", "acc")], s[c.get("src", "recv")], descs[i], counts[i], bm)
         else:
             pkg.uccl_chunk_apply(s["acc"], s["out"], s[c.get("src", "recv")], descs[i], counts[i], bm, w.dtype,
@@ -434,7 +444,9 @@ def main():
             "note": "same loop over one buffer set; the accumulator stays in the last-level cache"},
         "roofline": {
             "bound": "hbm",
-            "kernel": f"chunk_flat_kernel, {dom['call']} call ({dom['op']})" if args.shape in (0, 4) else f"chunk_apply_kernel, {dom['call']} call ({dom['op']})",
+            "kernel": (f"chunk_gather_kernel, {dom['call']} call ({dom['op']})" if calls[0].get("gather") else
+                       f"chunk_flat_kernel, {dom['call']} call ({dom['op']})" if args.shape in (0, 4) else
+                       f"chunk_apply_kernel, {dom['call']} call ({dom['op']})"),
             "achieved": round(achieved, 1),
             "peak": PEAK_HBM_GBS,
             "unit": "GB/s",
@@ -472,7 +484,9 @@ def main():
             seen = oracle.new_seen(w.n_bits)
             t0 = time.perf_counter()
             for c in calls:
-                if c["scatter"]:
+                if c.get("gather"):
+                    oracle.reduce_gather(eacc, None, w.recv_stage, c["descs"], seen, w.dtype, c["op"])
+                elif c["scatter"]:
                     oracle.scatter(eacc.view(np.uint8), w.recv_stage, c["descs"], seen, check=False)
                 else:
                     oracle.apply(eacc, eout, w.recv_stage, c["descs"], seen, w.dtype, c["op"], check=False)

@@ -29,22 +29,5 @@ def build(extra_flags=(), out=LIB, verbose=False) -> str:
     return out
 
 
-def build_c_check(verbose=False) -> str:
-    """Compile tests/c_abi_check.c: a plain-C user of the library (and of the C oracle, as its
-    checker).  Needs both shared libraries to exist already."""
-    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
-    src = os.path.join(ROOT, "tests", "c_abi_check.c")
-    out = os.path.join(ROOT, "tests", "c_abi_check")
-    orc = os.path.join(ROOT, "oracle")
-    cmd = ["gcc", "-O1", "-std=c11", "-Wall", "-D__HIP_PLATFORM_AMD__", f"-I{rocm}/include", f"-I{INC}", f"-I{orc}",
-           src, f"-L{PKG}", "-luccl_chunk", f"-L{orc}", "-lchunk_oracle", f"-L{rocm}/lib", "-lamdhip64",
-           "-Wl,-rpath,$ORIGIN/../paper_2504_17307_amd", "-Wl,-rpath,$ORIGIN/../oracle", f"-Wl,-rpath,{rocm}/lib",
-           "-o", out]
-    if verbose:
-        print(" ".join(cmd), flush=True)
-    subprocess.check_call(cmd)
-    return out
-
-
 if __name__ == "__main__":
     print(build(sys.argv[1:], verbose=True))

@@ -44,6 +44,12 @@
 #ifndef UCCL_GROUP_UNROLL
 #define UCCL_GROUP_UNROLL 4
 #endif
+#ifndef UCCL_GATHER_UNROLL
+#define UCCL_GATHER_UNROLL 2  // multi-sender reduce: vectors per lane per unit
+#endif
+#ifndef UCCL_GATHER_BATCH
+#define UCCL_GATHER_BATCH 4   // and how many sources are loaded before the folds start
+#endif
 #ifndef UCCL_FLAT_THREADS
 #define UCCL_FLAT_THREADS 1024  // workgroup size of the flat shape
 #endif
@@ -512,8 +518,8 @@ __global__ void __launch_bounds__(NT) chunk_flat_kernel(const Args g) {
 // the floating-point result is fixed by the record, not by arrival timing.  The accumulator
 // is read and written once per chunk however many sources there are.  Same tile / unit
 // dealing as the flat shape; per unit a wavefront keeps the running value in registers
-// (widened to binary32 for 16-bit types) and streams one source after the other, the next
-// source's vectors already in flight while the current ones are folded.
+// (widened to binary32 for 16-bit types); sources are loaded in batches, all loads of a
+// batch in flight before the folds, which then run in the listed order.
 struct GatherArgs {
   char* acc;
   char* out;
@@ -534,10 +540,11 @@ struct GatherTile {
   uint32_t count;
 };
 
-template <int T, int U, class Op>
-__global__ void __launch_bounds__(1024) chunk_gather_kernel(const GatherArgs g) {
+template <int NT, int T, int U, class Op>
+__global__ void __launch_bounds__(NT) chunk_gather_kernel(const GatherArgs g) {
   static_assert(T >= 1 && T <= 64, "one wavefront dedups the tile");
   constexpr uint32_t kUnit = 64u * U;
+  constexpr uint32_t kBatch = UCCL_GATHER_BATCH;
   __shared__ GatherTile<T> s;
   const uint32_t tid = threadIdx.x;
   if (tid < 64) {
@@ -601,7 +608,7 @@ __global__ void __launch_bounds__(1024) chunk_gather_kernel(const GatherArgs g) 
   const uint32_t count = s.count;
   const uint32_t total = s.first[count];
   const uint32_t wave = tid >> 6, lane = tid & 63u;
-  for (uint32_t u = wave; u < total; u += 16u) {
+  for (uint32_t u = wave; u < total; u += NT / 64) {
     uint32_t w = 0;
     if (T > 1) {
       const bool mine = lane < count && s.first[lane] <= u && u < s.first[lane + 1];
@@ -627,23 +634,29 @@ __global__ void __launch_bounds__(1024) chunk_gather_kernel(const GatherArgs g) 
       if (live[i]) a = ap[i * 64];
       st[i][0] = Op::open(a.x); st[i][1] = Op::open(a.y); st[i][2] = Op::open(a.z); st[i][3] = Op::open(a.w);
     }
-    u32x4 cur[U], nxt[U];
-    {
-      const u32x4* rp = reinterpret_cast<const u32x4*>(g.recv + wave_uniform(s.src[w][0])) + v0 + lane;
+    // sources in batches: all loads of a batch are issued before the first fold waits
+    for (uint32_t j0 = 0; j0 < n_src; j0 += kBatch) {
+      u32x4 rv[kBatch][U];
 #pragma unroll
-      for (int i = 0; i < U; ++i) { cur[i] = u32x4{0u, 0u, 0u, 0u}; if (live[i]) cur[i] = __builtin_nontemporal_load(rp + i * 64); }
-    }
-    for (uint32_t j = 0; j < n_src; ++j) {
-      if (j + 1 < n_src) {
-        const u32x4* rp = reinterpret_cast<const u32x4*>(g.recv + wave_uniform(s.src[w][j + 1])) + v0 + lane;
+      for (uint32_t b = 0; b < kBatch; ++b) {
+        if (j0 + b < n_src) {
+          const u32x4* rp = reinterpret_cast<const u32x4*>(g.recv + wave_uniform(s.src[w][j0 + b])) + v0 + lane;
 #pragma unroll
-        for (int i = 0; i < U; ++i) { nxt[i] = u32x4{0u, 0u, 0u, 0u}; if (live[i]) nxt[i] = __builtin_nontemporal_load(rp + i * 64); }
+          for (int i = 0; i < U; ++i) {
+            rv[b][i] = u32x4{0u, 0u, 0u, 0u};
+            if (live[i]) rv[b][i] = __builtin_nontemporal_load(rp + i * 64);
+          }
+        }
       }
 #pragma unroll
-      for (int i = 0; i < U; ++i) {
-        Op::fold(st[i][0], cur[i].x); Op::fold(st[i][1], cur[i].y);
-        Op::fold(st[i][2], cur[i].z); Op::fold(st[i][3], cur[i].w);
-        cur[i] = nxt[i];
+      for (uint32_t b = 0; b < kBatch; ++b) {
+        if (j0 + b < n_src) {
+#pragma unroll
+          for (int i = 0; i < U; ++i) {
+            Op::fold(st[i][0], rv[b][i].x); Op::fold(st[i][1], rv[b][i].y);
+            Op::fold(st[i][2], rv[b][i].z); Op::fold(st[i][3], rv[b][i].w);
+          }
+        }
       }
     }
 #pragma unroll
@@ -867,7 +880,7 @@ int launch_shape(const Args& a, hipStream_t s) {
 
 template <int T, class Op>
 int launch_gather(const GatherArgs& a, hipStream_t s) {
-  return launch_kernel(chunk_gather_kernel<T, UCCL_FLAT_UNROLL, Op>, tiles_for(a.n_descs, T), 1024, s, a);
+  return launch_kernel(chunk_gather_kernel<1024, T, UCCL_GATHER_UNROLL, Op>, tiles_for(a.n_descs, T), 1024, s, a);
 }
 
 template <class Op>
