@@ -31,7 +31,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 # source it was measured on, identified by the hash of the HIP source file.
 MEASURED_TRAFFIC = {
     # (workload, first 16 hex digits of sha256 of csrc/uccl_chunk.hip): bytes per launch
-    ("config2", "8e9b05fed32bd16a"): 1008008263,
+    ("config2", "fc876b554adf3680"): 1008018939,
+    ("config3", "fc876b554adf3680"): 3625033669,
+    ("direct-rs", "fc876b554adf3680"): 1208236830,
 }
 
 WORKLOADS = {
