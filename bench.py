@@ -95,7 +95,7 @@ def two_pass_calls(w, chunk):
     return calls, most * chunk
 
 
-def build_job(name, seed, n_msgs, relay=False):
+def build_job(name, seed, n_msgs, relay=False, per_call=128):
     """Returns (workload, calls, chunk_bytes) with calls = list of dicts
     {name, op, descs (numpy), n_unique, payload_bytes, algo_bytes, scatter}."""
     from synth import workloads as wl
@@ -119,7 +119,7 @@ def build_job(name, seed, n_msgs, relay=False):
                         payload_bytes=ph.payload_bytes, algo_bytes=ph.algo_bytes, scatter=True)], 16 << 10
     if name in ("config5", "config5-single"):
         w, msgs = wl.config5(seed=seed, n_msgs=n_msgs)
-        group = 128 if name == "config5" else 1  # at most 128 messages in flight per connection
+        group = per_call if name == "config5" else 1  # at most 128 messages in flight per connection
         calls = []
         for lo in range(0, len(msgs), group):
             ms = msgs[lo:lo + group]
@@ -258,6 +258,8 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--sets", type=int, default=4, help="buffer sets the steps rotate over")
     ap.add_argument("--messages", type=int, default=1000, help="config5: number of messages")
+    ap.add_argument("--messages-per-call", type=int, default=128,
+                    help="config5: messages batched into one call (128 = in-flight messages of one connection)")
     ap.add_argument("--shape", type=int, default=0, help="launch shape id (0 = auto)")
     ap.add_argument("--no-chunk-hint", action="store_true")
     ap.add_argument("--chunk-hint", type=int, default=None, help="override the chunk-size hint (bytes)")
@@ -288,7 +290,7 @@ def main():
     if args.workload == "config5-graph":
         return bench_graph_feed(args, pkg, torch)
     t0 = time.time()
-    w, calls, chunk_bytes = build_job(args.workload, args.seed, args.messages, args.relay)
+    w, calls, chunk_bytes = build_job(args.workload, args.seed, args.messages, args.relay, args.messages_per_call)
     if args.chunk_hint is not None:
         chunk_bytes = args.chunk_hint
     if not args.no_chunk_hint:
@@ -399,6 +401,24 @@ def main():
     assert int(hdr[:8].view(np.uint64)[0]) == w.n_bits and int(hdr[20:24].view(np.uint32)[0]) == 1, \
         "after a full step every chunk is acknowledged"
 
+    # the machine's own streaming ceilings, beside the published peak: plain c = a + b and
+    # c = a of the framework's kernels on buffers of this workload's order of size, rotating
+    def ceiling(fn, streams, nbytes=240 << 20, nsets=4, reps=20):
+        bufs = [[torch.empty(nbytes // 2, dtype=torch.bfloat16, device="cuda").normal_() for _ in range(3)]
+                for _ in range(nsets)]
+        for k in range(4):
+            fn(*bufs[k % nsets])
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for k in range(reps):
+            fn(*bufs[k % nsets])
+        b.record()
+        torch.cuda.synchronize()
+        return round(streams * nbytes * reps / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
+    stream_ceiling = {"copy_1r1w_GBps": ceiling(lambda x, y, z: z.copy_(x), 2),
+                      "add_2r1w_GBps": ceiling(lambda x, y, z: torch.add(x, y, out=z), 3),
+                      "what": "torch copy_ and add on 240 MiB bf16 tensors rotating over 4 sets, same run"}
+
     if args.calibration_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
         dstc = torch.empty_like(src)
@@ -458,6 +478,7 @@ def main():
             "avg_launch_ms": dom["avg_ms"],
         },
         "kernels": kernels,
+        "stream_ceiling": stream_ceiling,
         "dedup_report": {"n_bits": w.n_bits, "median_us": round(report_us, 2),
                          "what": "ack_report_kernel: cumulative ack, applied count, selective ranges"},
     }
@@ -480,7 +501,7 @@ def main():
     if not args.no_cpu_baseline:
         import oracle
         reps, cpu_t, exp = 0, 0.0, None
-        while cpu_t < 10.0 and reps < 8:
+        while cpu_t < 10.0 and reps < 64:
             eacc = w.acc.copy()
             eout = np.zeros(max(w.out_bytes, 16), dtype=np.uint8)
             seen = oracle.new_seen(w.n_bits)

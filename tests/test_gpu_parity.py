@@ -530,6 +530,25 @@ def test_stream_from_control_path_model(gpu_lib, shape):
     check_workload(gpu_lib, w, shape)
 
 
+def test_rejected_calls_leave_buffers_untouched(gpu_lib):
+    """Host-side argument errors enqueue nothing: device buffers keep their bytes."""
+    w = wl.config2(seed=2, M=4 << 20)
+    run = DeviceRun(w)
+    lib = gpu_lib.load()
+    n = len(w.phases[0].descs)
+    args = [run.acc.data_ptr(), run.out.data_ptr(), run.recv.data_ptr(), run.descs[0].data_ptr(), n,
+            run.bitmap.data_ptr(), BF16, SUM, None]
+    bad = [(0, None), (2, None), (3, None), (5, None), (6, 9), (7, 7), (0, args[0] + 8), (3, args[3] + 16 - 8),
+           (5, args[5] + 2)]
+    for pos, val in bad:
+        a = list(args)
+        a[pos] = val
+        assert lib.uccl_chunk_apply(*a) in (gpu_lib.UCCL_EINVAL, gpu_lib.UCCL_EALIGN), (pos, val)
+    torch.cuda.synchronize()
+    acc, out, bm, _ = run.results()
+    assert_same(acc, w.acc, "acc"); assert not bm.any() and np.all(out == 0xA5)
+
+
 def test_c_abi_from_plain_c(gpu_lib):
     """A C program (no Python, no PyTorch) drives the library and checks it against the oracle."""
     import os
