@@ -258,6 +258,9 @@ def main():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--sets", type=int, default=4, help="buffer sets the steps rotate over")
     ap.add_argument("--messages", type=int, default=1000, help="config5: number of messages")
+    ap.add_argument("--streams", type=int, default=1,
+                    help="config5: issue consecutive message batches round-robin on this many streams "
+                         "(batches are independent of each other; the two calls of a batch stay ordered)")
     ap.add_argument("--messages-per-call", type=int, default=128,
                     help="config5: messages batched into one call (128 = in-flight messages of one connection)")
     ap.add_argument("--shape", type=int, default=0, help="launch shape id (0 = auto)")
@@ -312,7 +315,16 @@ def main():
     descs = [dev(c["descs"]) for c in calls]
     counts = [len(c["descs"]) for c in calls]
 
+    streams = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else None
+
     def call(i, s):
+        c = calls[i]
+        if streams is not None:  # calls come in (reduce-scatter, allgather) pairs per batch
+            with torch.cuda.stream(streams[(i // 2) % len(streams)]):
+                return call_on_current(i, s)
+        return call_on_current(i, s)
+
+    def call_on_current(i, s):
         c = calls[i]
         bm = bitmap2 if c.get("bm") == "bitmap2" else bitmap
         if c.get("gather"):
@@ -325,7 +337,13 @@ def main():
 
     def step(k, timed=None):
         s = sets[k % len(sets)]
+        if streams is not None:
+            for st in streams:
+                torch.cuda.current_stream().wait_stream(st)
         pkg.uccl_dedup_reset(bitmap, w.n_bits)
+        if streams is not None:
+            for st in streams:
+                st.wait_stream(torch.cuda.current_stream())
         if args.two_pass:
             pkg.uccl_dedup_reset(bitmap2, w.n_bits)
         for i in range(len(calls)):
@@ -455,7 +473,7 @@ def main():
                    "algorithmic_bytes": algo, "launch_shape": args.shape,
                    "chunk_hint": 0 if args.no_chunk_hint else chunk_bytes, "buffer_sets": len(sets),
                    "forward_only_intermediate_steps": bool(args.relay), "two_pass": bool(args.two_pass),
-                   "calls_per_step": 1 + len(calls), "cache": cache_note},
+                   "calls_per_step": 1 + len(calls), "streams": args.streams, "cache": cache_note},
         "chunks_per_s": round(unique / per_step, 1),
         "arrivals_per_s": round(arrivals / per_step, 1),
         "step_hbm_frac": round(algo / per_step / 1e9 / PEAK_HBM_GBS, 4),
