@@ -24,6 +24,9 @@ import time
 import numpy as np
 
 PEAK_HBM_GBS = 8000.0  # MI355X published HBM3E peak, GB/s
+# Kernel durations are sampled on every EVENT_STRIDE-th timed step: an event pair on a dispatch
+# adds a completion signal between kernels (about 5 us each), which would otherwise slow every step.
+EVENT_STRIDE = 4
 ROOT = os.path.dirname(os.path.abspath(__file__))
 
 # HBM bytes per launch of the dominant kernel of config2 from rocprofv3 counters
@@ -347,16 +350,10 @@ def main():
         if args.two_pass:
             pkg.uccl_dedup_reset(bitmap2, w.n_bits)
         for i in range(len(calls)):
-            if timed is not None and i in timed:
-                # events attached to the dispatch itself: the kernel's own begin and end
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                b.record()
-                pkg.uccl_time_next_launch(a, b)
-                call(i, s)
-                timed[i].append((a, b))
-            else:
-                call(i, s)
+            if timed is not None and i in timed and k % EVENT_STRIDE == 0:
+                # a pre-made event pair attached to the dispatch itself: the kernel's own begin and end
+                pkg.uccl_time_next_launch(*timed[i][k // EVENT_STRIDE])
+            call(i, s)
 
     # one pass from the pristine state, kept for the parity check against the oracle
     step(0)
@@ -364,7 +361,25 @@ def main():
     first = (sets[0]["acc"].cpu().numpy(), sets[0]["out"][:w.out_bytes].cpu().numpy(),
              bitmap.cpu().numpy().view(np.uint32))
 
-    def timed_loop(n_sets):
+    # Per-launch durations are taken INSIDE the timed steps (every EVENT_STRIDE-th one): a HIP
+    # event pair, made and recorded once beforehand, is attached to the dispatch of the kernel on
+    # the stream it runs on (torch's current stream).  Workloads with many calls per step time the largest call
+    # of each op.
+    by_op = {}
+    for i, c in enumerate(calls):
+        if c["op"] not in by_op or c["algo_bytes"] > calls[by_op[c["op"]]]["algo_bytes"]:
+            by_op[c["op"]] = i
+    timed = {}
+    if streams is None:
+        for i in by_op.values():
+            timed[i] = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                        for _ in range((args.steps + EVENT_STRIDE - 1) // EVENT_STRIDE)]
+            for a, b in timed[i]:
+                a.record()
+                b.record()
+    torch.cuda.synchronize()
+
+    def timed_loop(n_sets, events=None):
         nonlocal sets
         keep, sets = sets, sets[:n_sets]
         for k in range(args.warmup):
@@ -372,30 +387,19 @@ def main():
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for k in range(args.steps):
-            step(k)
+            step(k, events)
         torch.cuda.synchronize()
         el = time.perf_counter() - t0
         sets = keep
         return el
 
-    elapsed = timed_loop(len(sets))
+    elapsed = timed_loop(len(sets), timed)
     warm_elapsed = timed_loop(1) if (args.also_warm and len(sets) > 1) else None
-
-    # per-launch durations: a HIP event pair attached to each launch on the stream the
-    # kernels run on (torch's current stream), inside the same rotating loop.  Workloads with
-    # many calls per step time the largest call of each op.
-    by_op = {}
-    for i, c in enumerate(calls):
-        if c["op"] not in by_op or c["algo_bytes"] > calls[by_op[c["op"]]]["algo_bytes"]:
-            by_op[c["op"]] = i
-    timed = {i: [] for i in by_op.values()}
-    ksteps = min(args.steps, 50)
-    for k in range(ksteps):
-        step(k, timed)
-    torch.cuda.synchronize()
+    if streams is not None:  # kernels of different streams overlap: no per-kernel attribution
+        timed = {i: [] for i in by_op.values()}
     kernels = []
     for i, evs in timed.items():
-        t = np.array([a.elapsed_time(b) for a, b in evs])
+        t = np.array([a.elapsed_time(b) for a, b in evs]) if evs else np.array([float("nan")])
         c = calls[i]
         kernels.append(dict(call=c["name"], op=["SUM", "MAX", "MIN", "COPY"][c["op"]], records=counts[i],
                             algorithmic_bytes=c["algo_bytes"], avg_ms=round(float(t.mean()), 5),
@@ -450,7 +454,8 @@ def main():
     arrivals = sum(counts)
     algo = sum(c["algo_bytes"] for c in calls)
     per_step = elapsed / args.steps
-    achieved = dom["algorithmic_bytes"] / (dom["avg_ms"] * 1e-3) / 1e9
+    per_kernel = not np.isnan(dom["avg_ms"])
+    achieved = dom["algorithmic_bytes"] / (dom["avg_ms"] * 1e-3) / 1e9 if per_kernel else algo / per_step / 1e9
     cache_note = ("buffers rotate over %d sets: HBM resident, not cache resident" % len(sets)
                   if (w.acc.nbytes + w.recv_stage.nbytes + w.out_bytes) * len(sets) > (1 << 30)
                   else "working set fits the 256 MB last-level cache: an effective, not an HBM, figure")
@@ -487,15 +492,16 @@ def main():
             "kernel": (f"chunk_gather_kernel, {dom['call']} call ({dom['op']})" if calls[0].get("gather") else
                        f"chunk_flat_kernel, {dom['call']} call ({dom['op']})" if args.shape in (0, 4) else
                        f"chunk_apply_kernel, {dom['call']} call ({dom['op']})"),
+            "basis": "the dominant kernel's own duration" if per_kernel else "whole step (kernels of several streams overlap)",
             "achieved": round(achieved, 1),
             "peak": PEAK_HBM_GBS,
             "unit": "GB/s",
             "frac": round(achieved / PEAK_HBM_GBS, 4),
             "traffic": MEASURED_TRAFFIC.get((args.workload, source_hash())),
             "algorithmic_bytes_per_launch": dom["algorithmic_bytes"],
-            "avg_launch_ms": dom["avg_ms"],
+            "avg_launch_ms": dom["avg_ms"] if per_kernel else None,
         },
-        "kernels": kernels,
+        "kernels": kernels if per_kernel else [],
         "stream_ceiling": stream_ceiling,
         "dedup_report": {"n_bits": w.n_bits, "median_us": round(report_us, 2),
                          "what": "ack_report_kernel: cumulative ack, applied count, selective ranges"},
