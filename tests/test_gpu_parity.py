@@ -127,9 +127,9 @@ def test_config5_recipe_batched_and_per_message(gpu_lib):
         assert_same(out, eout, "out")
 
 
-@pytest.mark.parametrize("hint", [512, 1024, 4096, 16384, 1 << 20])
+@pytest.mark.parametrize("hint", [512, 1024, 2048, 4096, 8192, 16384, 1 << 20])
 def test_flat_shape_every_tile_size(gpu_lib, hint):
-    """The chunk-size hint only changes how many records a workgroup takes (32, 32, 8, 2, 1)."""
+    """The chunk-size hint only changes how many records a workgroup takes (32, 32, 16, 8, 4, 2, 1)."""
     gpu_lib.uccl_set_chunk_hint(hint)
     try:
         C = 5008
@@ -138,6 +138,26 @@ def test_flat_shape_every_tile_size(gpu_lib, hint):
         check_workload(gpu_lib, w, 4)
     finally:
         gpu_lib.uccl_set_chunk_hint(0)
+
+
+def test_very_many_tiny_records_without_hint(gpu_lib):
+    """150 000 records of 64 bytes, no chunk-size hint: the tile grows with the record count
+    (every tile size of the heuristic is crossed by cutting the call at 5 000 / 20 000 / 100 000)."""
+    n, C = 150000, 64
+    g = pl.rng(31, 1)
+    seq = np.concatenate([g.permutation(n), g.integers(0, n, 6000)])
+    seq = seq[g.permutation(len(seq))]
+    d = np.zeros(len(seq), dtype=DESC)
+    d["src_off"] = np.arange(len(seq), dtype=np.uint64) * C
+    d["dst_off"] = seq.astype(np.uint64) * C
+    d["out_off"] = np.where(seq % 2 == 0, seq.astype(np.uint64) * C, NO_FORWARD)
+    d["len"], d["seq"] = C, seq
+    vals = pl.uniform_f32(31, 2, n * C // 4).reshape(n, C // 4)
+    recv = vals[seq].reshape(-1).copy()
+    w = wl.Workload("tiny", F32, pl.uniform_f32(31, 3, n * C // 4), recv, n * C, n,
+                    [wl.Phase("p", SUM, d, n, n * C, 0)])
+    check_workload(gpu_lib, w, 0, checked=False, split=lambda m: [5000, 25000, 125000])
+    check_workload(gpu_lib, w, 0, checked=True)
 
 
 # ---- ops, dtypes, ragged tails, odd lengths ------------------------------------------
