@@ -590,3 +590,55 @@ def test_side_stream(gpu_lib):
     acc, out, bm, rej = run.results()
     eacc, eout, ebm = oracle_results(w)
     assert_same(acc, eacc, "acc"); assert_same(out, eout, "out"); assert_same(bm, ebm, "bitmap")
+
+
+# ---- randomized mix of every feature --------------------------------------------------------------
+
+@pytest.mark.parametrize("dtype", [F32, BF16, F16, I32])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_random_streams_all_features(gpu_lib, dtype, shape):
+    """200 random small streams per (type, shape): odd and zero lengths, duplicates adjacent
+    and far, forward / keep / forward-only, every op, checked and unchecked entry, one call or
+    two, with and without a chunk-size hint."""
+    from randstream import random_stream
+    gpu_lib.uccl_set_launch_shape(shape)
+    try:
+        for seed in range(50):
+            for op in (SUM, MAX, COPY, PROD):
+                s = random_stream(7000 + 100 * dtype + 17 * seed + op, dtype, op, max_chunks=48, max_len=9000)
+                gpu_lib.uccl_set_chunk_hint([0, 1024, 4096, 65536][seed % 4])
+                acc, recv = to_dev(s["acc"]), to_dev(s["recv"])
+                out = torch.full((s["out_bytes"],), 0x3C, dtype=torch.uint8, device="cuda")
+                bm = torch.zeros((s["n_bits"] + 31) // 32, dtype=torch.int32, device="cuda")
+                rej = torch.zeros(1, dtype=torch.int32, device="cuda")
+                d = to_dev(s["descs"])
+                n = len(s["descs"])
+                cuts = [0, n] if seed % 3 else [0, n // 2, n]
+                for lo, hi in zip(cuts[:-1], cuts[1:]):
+                    if seed % 2:
+                        gpu_lib.uccl_chunk_apply_checked(acc, out, recv, d[lo * 32:], hi - lo, bm, dtype, op,
+                                                         n_rejected=rej, n_bits=s["n_bits"])
+                    else:
+                        gpu_lib.uccl_chunk_apply(acc, out, recv, d[lo * 32:], hi - lo, bm, dtype, op)
+                torch.cuda.synchronize()
+                eacc, eout, seen = s["acc"].copy(), np.full(s["out_bytes"], 0x3C, np.uint8), oracle.new_seen(s["n_bits"])
+                oracle.apply(eacc, eout, s["recv"], s["descs"], seen, dtype, op)
+                what = f"dtype {dtype} shape {shape} seed {seed} op {op}"
+                assert rej.item() == 0, what
+                assert_same(bm.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap " + what)
+                got = to_host(acc, s["acc"].dtype)
+                if dtype in (F32, BF16, F16):
+                    wide = {F32: lambda x: x, BF16: lambda x: (x.astype(np.uint32) << 16).view(np.float32),
+                            F16: lambda x: x.view(np.float16).astype(np.float32)}[dtype]
+                    nan = np.isnan(wide(eacc))
+                    assert np.array_equal(np.isnan(wide(got)), nan), what
+                    assert_same(got[~nan], eacc[~nan], "acc " + what)
+                    go, eo = out.cpu().numpy().view(s["acc"].dtype), eout.view(s["acc"].dtype)
+                    nan_o = np.isnan(wide(eo))
+                    assert_same(go[~nan_o], eo[~nan_o], "out " + what)
+                else:
+                    assert_same(got, eacc, "acc " + what)
+                    assert_same(out.cpu().numpy(), eout, "out " + what)
+    finally:
+        gpu_lib.uccl_set_launch_shape(0)
+        gpu_lib.uccl_set_chunk_hint(0)
