@@ -642,3 +642,27 @@ def test_random_streams_all_features(gpu_lib, dtype, shape):
     finally:
         gpu_lib.uccl_set_launch_shape(0)
         gpu_lib.uccl_set_chunk_hint(0)
+
+
+def test_same_records_on_two_streams_apply_once(gpu_lib):
+    """The whole record list is issued twice, concurrently, on two streams (a retransmitted
+    batch handed over by another engine thread): the bitmap atomics decide each chunk once."""
+    dtype, C, n = BF16, 16384, 3000
+    one = pl.ints_as(np.ones(1, dtype=np.int64), dtype)[0]
+    arr = pl.rng(41, 1).permutation(n)
+    d = np.zeros(n, dtype=DESC)
+    d["src_off"] = np.arange(n, dtype=np.uint64) * C
+    d["dst_off"] = d["out_off"] = arr.astype(np.uint64) * C
+    d["len"], d["seq"] = C, arr
+    recv = np.full(n * C // 2, one, dtype=np.uint16)
+    w = wl.Workload("two", dtype, np.zeros(n * C // 2, dtype=np.uint16), recv, n * C, n, [wl.Phase("p", SUM, d, n, n * C, 0)])
+    for trial in range(3):
+        run = DeviceRun(w)
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        run.apply(run.descs[0], n, SUM, stream=s1)
+        run.apply(run.descs[0], n, SUM, stream=s2)
+        s1.synchronize(); s2.synchronize()
+        acc, out, bm, rej = run.results()
+        assert rej == 0 and np.all(acc == one), f"trial {trial}: {np.count_nonzero(acc != one)} elements not exactly 1"
+        assert np.array_equal(out.view(np.uint16), acc) and sum(int(x).bit_count() for x in bm) == n
