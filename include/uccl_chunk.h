@@ -105,8 +105,8 @@ typedef struct uccl_extents {
  *   - within one call, records with different seq touch disjoint ranges of acc and of
  *     out_stage (order between dependent steps is expressed by separate calls);
  *   - recv_stage overlaps neither acc nor out_stage.
- * A record whose offsets are misaligned or whose len is not a multiple of the element
- * size is skipped (its bit stays clear).
+ * A record whose offsets are misaligned, whose len is not a multiple of the element size,
+ * or which forwards although out_stage is NULL, is skipped (its bit stays clear).
  *
  * Returns UCCL_OK (also for n_descs == 0, which enqueues nothing) or a negative code;
  * on error nothing has been enqueued.
