@@ -18,8 +18,8 @@
  *     combine - t[i] = op(acc[dst+i], recv[src+i])   (COPY: t[i] = recv[src+i])
  *     write   - acc[dst+i] = t[i]; and out_stage[out+i] = t[i] when the record forwards
  *
- * All buffer pointers are DEVICE pointers owned by the caller (the library never
- * allocates, frees or keeps them); `stream` is a hipStream_t passed as void* (NULL =
+ * All buffer pointers are DEVICE pointers owned by the caller (the data-path calls never
+ * allocate, free or keep them; only the optional uccl_feed object owns memory); `stream` is a hipStream_t passed as void* (NULL =
  * the null stream).  Every call only enqueues work on `stream` and returns: no host
  * synchronisation, no host read of device memory.  Records and buffers must stay valid
  * until the stream has passed the call; receive slots may be recycled after that point
@@ -74,7 +74,8 @@ enum {
   UCCL_OK = 0,
   UCCL_EINVAL = -1,  /* null pointer with n_descs > 0, unknown dtype/op/shape, aliasing buffers */
   UCCL_EALIGN = -2,  /* a base pointer is not 16-byte aligned (bitmap / counter: 4-byte) */
-  UCCL_ELAUNCH = -3  /* HIP refused the launch; uccl_last_error_detail() has HIP's message */
+  UCCL_ELAUNCH = -3, /* HIP refused the launch; uccl_last_error_detail() has HIP's message */
+  UCCL_ENOMEM = -4   /* uccl_feed_create could not get host, pinned or device memory */
 };
 
 /* Buffer sizes for the checked entry points (HOST struct, read during the call). */
@@ -219,6 +220,40 @@ typedef struct uccl_ack_report {
 } uccl_ack_report;
 int uccl_dedup_report(const uint32_t* dedup_bitmap, uint64_t n_bits, void* report,
                       uint32_t max_ranges, void* stream);
+
+/*
+ * uccl_feed -- host-side batcher between the control path and the kernels (Appendix C.4:
+ * kernel launches per batch hurt small messages; adaptive batching is the remedy).
+ * The ONLY part of this library that allocates: `n_slots` (2..1024) slots, each two lanes of
+ * `capacity_records` records in pinned host memory plus the same in device memory.
+ *   push   copies `n` HOST records into lane 0 or 1 of the current slot; a full lane flushes
+ *   flush  hands the current slot over: per non-empty lane one asynchronous record copy and
+ *          one uccl_chunk_apply on the feed's stream, lane 0 before lane 1 (so a message whose
+ *          reduce-scatter records went to lane 0 before its allgather records went to lane 1
+ *          is applied in that order); then moves to the next slot, waiting only if that slot's
+ *          previous hand-over has not finished
+ *   poll   flushes pending records if the previous hand-over has finished -- the GPU would
+ *          otherwise idle -- and keeps batching if it has not
+ *   sync   flush, then wait until every hand-over has finished
+ * Buffers, bitmap and element type are fixed at creation; lane ops are given there too.
+ * A feed is used by one host thread at a time.  All calls return UCCL_OK or a negative code.
+ */
+typedef struct uccl_feed uccl_feed;
+typedef struct uccl_feed_stats {
+  uint64_t flushes;    /* hand-overs so far */
+  uint64_t records;    /* records handed over */
+  uint64_t max_batch;  /* largest hand-over, in records (both lanes) */
+  uint64_t slot_waits; /* times push/flush had to wait for a slot to come back */
+} uccl_feed_stats;
+int uccl_feed_create(uccl_feed** feed, void* acc, void* out_stage, const void* recv_stage,
+                     uint32_t* dedup_bitmap, uccl_dtype dtype, uccl_op lane0_op, uccl_op lane1_op,
+                     uint32_t capacity_records, uint32_t n_slots, void* stream);
+int uccl_feed_push(uccl_feed* feed, int lane, const uccl_chunk_desc* host_records, uint32_t n);
+int uccl_feed_poll(uccl_feed* feed);
+int uccl_feed_flush(uccl_feed* feed);
+int uccl_feed_sync(uccl_feed* feed);
+int uccl_feed_get_stats(const uccl_feed* feed, uccl_feed_stats* stats);
+int uccl_feed_destroy(uccl_feed* feed);
 
 /*
  * Launch shape: how records are mapped onto the machine.

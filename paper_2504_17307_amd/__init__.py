@@ -16,7 +16,7 @@ HEADER_PATH = os.path.join(os.path.dirname(_PKG), "include", "uccl_chunk.h")
 
 UCCL_F32, UCCL_BF16, UCCL_F16, UCCL_I32 = 0, 1, 2, 3
 UCCL_SUM, UCCL_MAX, UCCL_MIN, UCCL_COPY, UCCL_PROD = 0, 1, 2, 3, 4
-UCCL_OK, UCCL_EINVAL, UCCL_EALIGN, UCCL_ELAUNCH = 0, -1, -2, -3
+UCCL_OK, UCCL_EINVAL, UCCL_EALIGN, UCCL_ELAUNCH, UCCL_ENOMEM = 0, -1, -2, -3, -4
 UCCL_NO_FORWARD = 0xFFFFFFFFFFFFFFFF
 UCCL_SHAPE_AUTO, UCCL_SHAPE_WAVE, UCCL_SHAPE_GROUP, UCCL_SHAPE_FLAT = 0, 1, 2, 4
 DESC_BYTES = 32
@@ -27,6 +27,11 @@ UCCL_MAX_SOURCES = 16
 class uccl_extents(C.Structure):
     _fields_ = [("acc_bytes", C.c_uint64), ("out_bytes", C.c_uint64),
                 ("recv_bytes", C.c_uint64), ("n_bits", C.c_uint64)]
+
+
+class uccl_feed_stats(C.Structure):
+    _fields_ = [("flushes", C.c_uint64), ("records", C.c_uint64), ("max_batch", C.c_uint64),
+                ("slot_waits", C.c_uint64)]
 
 
 class UcclError(RuntimeError):
@@ -59,6 +64,14 @@ _SIGNATURES = {
                                              C.c_void_p, C.POINTER(uccl_extents), C.c_void_p,
                                              C.c_void_p]),
     "uccl_dedup_reset": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p]),
+    "uccl_feed_create": (C.c_int, [C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_int, C.c_int, C.c_int, C.c_uint32, C.c_uint32, C.c_void_p]),
+    "uccl_feed_push": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_uint32]),
+    "uccl_feed_poll": (C.c_int, [C.c_void_p]),
+    "uccl_feed_flush": (C.c_int, [C.c_void_p]),
+    "uccl_feed_sync": (C.c_int, [C.c_void_p]),
+    "uccl_feed_get_stats": (C.c_int, [C.c_void_p, C.POINTER(uccl_feed_stats)]),
+    "uccl_feed_destroy": (C.c_int, [C.c_void_p]),
     "uccl_dedup_report": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p]),
     "uccl_set_launch_shape": (C.c_int, [C.c_int]),
     "uccl_set_chunk_hint": (C.c_int, [C.c_uint32]),
@@ -189,6 +202,43 @@ def uccl_chunk_scatter_checked(dst, recv_stage, descs, n_descs, dedup_bitmap, ex
 def uccl_dedup_reset(dedup_bitmap, n_bits, stream=None):
     _check(load().uccl_dedup_reset(_ptr(dedup_bitmap), int(n_bits), _stream(stream)),
            "uccl_dedup_reset")
+
+
+def uccl_feed_create(acc, out_stage, recv_stage, dedup_bitmap, dtype, lane0_op, lane1_op, capacity_records,
+                     n_slots, stream=None):
+    """Returns an opaque feed handle (keep the tensors alive for as long as the feed is)."""
+    h = C.c_void_p()
+    _check(load().uccl_feed_create(C.byref(h), _ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(dedup_bitmap),
+                                   int(dtype), int(lane0_op), int(lane1_op), int(capacity_records), int(n_slots),
+                                   _stream(stream)), "uccl_feed_create")
+    return h
+
+
+def uccl_feed_push(feed, lane, host_records):
+    """``host_records``: a contiguous numpy array of 32-byte records in host memory."""
+    _check(load().uccl_feed_push(feed, int(lane), host_records.ctypes.data, len(host_records)), "uccl_feed_push")
+
+
+def uccl_feed_poll(feed):
+    _check(load().uccl_feed_poll(feed), "uccl_feed_poll")
+
+
+def uccl_feed_flush(feed):
+    _check(load().uccl_feed_flush(feed), "uccl_feed_flush")
+
+
+def uccl_feed_sync(feed):
+    _check(load().uccl_feed_sync(feed), "uccl_feed_sync")
+
+
+def uccl_feed_get_stats(feed) -> dict:
+    s = uccl_feed_stats()
+    _check(load().uccl_feed_get_stats(feed, C.byref(s)), "uccl_feed_get_stats")
+    return {k: getattr(s, k) for k, _ in uccl_feed_stats._fields_}
+
+
+def uccl_feed_destroy(feed):
+    _check(load().uccl_feed_destroy(feed), "uccl_feed_destroy")
 
 
 ACK_HEADER_BYTES = 32

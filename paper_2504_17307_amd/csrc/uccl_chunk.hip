@@ -26,6 +26,8 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <new>
+
 #include "uccl_chunk.h"
 
 // Tunable compile-time shape constants (defaults chosen by measurement on MI355X).
@@ -955,7 +957,204 @@ int apply_common(void* acc, void* out_stage, const void* recv_stage, const uccl_
   }
 }
 
+// ---- host-side batcher -------------------------------------------------------------------
+//
+// Appendix C.4: launching a kernel per batch is what hurts small messages, and batching
+// adaptively is the remedy.  The feed collects records on the host in pinned slots and
+// hands a slot to the GPU (one asynchronous copy of the records, one kernel per lane) when
+// the slot is full, when the caller says so, or -- uccl_feed_poll -- as soon as the previous
+// hand-over has finished, so that batches grow exactly as large as the GPU's backlog
+// requires and a lone message is launched at once.  Lanes keep records of dependent phases
+// apart: a flush issues lane 0 before lane 1, so a message whose reduce-scatter records go
+// to lane 0 before its allgather records go to lane 1 is always applied in that order.
+struct FeedSlot {
+  uccl_chunk_desc* host[2];
+  uccl_chunk_desc* dev[2];
+  uint32_t count[2];
+  hipEvent_t done;
+  bool in_flight;
+};
+
 }  // namespace
+
+struct uccl_feed {
+  void* acc;
+  void* out_stage;
+  const void* recv_stage;
+  uint32_t* bitmap;
+  int dtype;
+  int op[2];
+  uint32_t capacity, n_slots, cur;
+  hipStream_t stream;
+  FeedSlot* slots;
+  uccl_feed_stats stats;
+};
+
+namespace {
+
+void feed_free(uccl_feed* f) {
+  if (!f) return;
+  if (f->slots) {
+    for (uint32_t i = 0; i < f->n_slots; ++i) {
+      for (int l = 0; l < 2; ++l) {
+        if (f->slots[i].host[l]) (void)hipHostFree(f->slots[i].host[l]);
+        if (f->slots[i].dev[l]) (void)hipFree(f->slots[i].dev[l]);
+      }
+      if (f->slots[i].done) (void)hipEventDestroy(f->slots[i].done);
+    }
+    delete[] f->slots;
+  }
+  delete f;
+}
+
+int feed_flush(uccl_feed* f) {
+  FeedSlot& sl = f->slots[f->cur];
+  const uint32_t n = sl.count[0] + sl.count[1];
+  if (n == 0) return UCCL_OK;
+  for (int l = 0; l < 2; ++l) {
+    if (sl.count[l] == 0) continue;
+    const hipError_t e = hipMemcpyAsync(sl.dev[l], sl.host[l], sizeof(uccl_chunk_desc) * sl.count[l],
+                                        hipMemcpyHostToDevice, f->stream);
+    if (e != hipSuccess) return launch_failed(e);
+    const int rc = apply_common(f->acc, f->out_stage, f->recv_stage, sl.dev[l], sl.count[l], f->bitmap,
+                                f->dtype, f->op[l], true, nullptr, nullptr, f->stream);
+    if (rc != UCCL_OK) return rc;
+  }
+  const hipError_t e = hipEventRecord(sl.done, f->stream);
+  if (e != hipSuccess) return launch_failed(e);
+  sl.in_flight = true;
+  f->stats.flushes += 1;
+  f->stats.records += n;
+  if (n > f->stats.max_batch) f->stats.max_batch = n;
+  sl.count[0] = sl.count[1] = 0;
+  // move on to the next slot; it may still be read by the copy of an earlier flush
+  f->cur = (f->cur + 1) % f->n_slots;
+  FeedSlot& nx = f->slots[f->cur];
+  if (nx.in_flight) {
+    if (hipEventQuery(nx.done) != hipSuccess) {
+      (void)hipGetLastError();  // hipErrorNotReady is not an error here
+      const hipError_t w = hipEventSynchronize(nx.done);
+      if (w != hipSuccess) return launch_failed(w);
+      f->stats.slot_waits += 1;
+    }
+    nx.in_flight = false;
+  }
+  return UCCL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int uccl_feed_create(uccl_feed** feed, void* acc, void* out_stage, const void* recv_stage,
+                     uint32_t* dedup_bitmap, uccl_dtype dtype, uccl_op lane0_op, uccl_op lane1_op,
+                     uint32_t capacity_records, uint32_t n_slots, void* stream) {
+  if (!feed) return UCCL_EINVAL;
+  *feed = nullptr;
+  if (!acc || !recv_stage || !dedup_bitmap || capacity_records == 0 || n_slots < 2 || n_slots > 1024)
+    return UCCL_EINVAL;
+  if (dtype < UCCL_F32 || dtype > UCCL_I32) return UCCL_EINVAL;
+  if (lane0_op < UCCL_SUM || lane0_op > UCCL_PROD || lane1_op < UCCL_SUM || lane1_op > UCCL_PROD)
+    return UCCL_EINVAL;
+  if (misaligned(acc, 16) || misaligned(out_stage, 16) || misaligned(recv_stage, 16) ||
+      misaligned(dedup_bitmap, 4))
+    return UCCL_EALIGN;
+  uccl_feed* f = new (std::nothrow) uccl_feed();
+  if (!f) return UCCL_ENOMEM;
+  f->acc = acc;
+  f->out_stage = out_stage;
+  f->recv_stage = recv_stage;
+  f->bitmap = dedup_bitmap;
+  f->dtype = dtype;
+  f->op[0] = lane0_op;
+  f->op[1] = lane1_op;
+  f->capacity = capacity_records;
+  f->n_slots = n_slots;
+  f->cur = 0;
+  f->stream = static_cast<hipStream_t>(stream);
+  f->stats = uccl_feed_stats{0, 0, 0, 0};
+  f->slots = new (std::nothrow) FeedSlot[n_slots]();
+  if (!f->slots) { feed_free(f); return UCCL_ENOMEM; }
+  const size_t bytes = sizeof(uccl_chunk_desc) * static_cast<size_t>(capacity_records);
+  for (uint32_t i = 0; i < n_slots; ++i) {
+    for (int l = 0; l < 2; ++l) {
+      if (hipHostMalloc(reinterpret_cast<void**>(&f->slots[i].host[l]), bytes, hipHostMallocDefault) != hipSuccess ||
+          hipMalloc(reinterpret_cast<void**>(&f->slots[i].dev[l]), bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        feed_free(f);
+        return UCCL_ENOMEM;
+      }
+    }
+    if (hipEventCreateWithFlags(&f->slots[i].done, hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      feed_free(f);
+      return UCCL_ENOMEM;
+    }
+  }
+  *feed = f;
+  return UCCL_OK;
+}
+
+int uccl_feed_push(uccl_feed* f, int lane, const uccl_chunk_desc* host_records, uint32_t n) {
+  if (!f || (lane != 0 && lane != 1) || (n > 0 && !host_records)) return UCCL_EINVAL;
+  while (n > 0) {
+    FeedSlot& sl = f->slots[f->cur];
+    const uint32_t room = f->capacity - sl.count[lane];
+    const uint32_t take = n < room ? n : room;
+    memcpy(sl.host[lane] + sl.count[lane], host_records, sizeof(uccl_chunk_desc) * take);
+    sl.count[lane] += take;
+    host_records += take;
+    n -= take;
+    if (sl.count[lane] == f->capacity) {
+      const int rc = feed_flush(f);
+      if (rc != UCCL_OK) return rc;
+    }
+  }
+  return UCCL_OK;
+}
+
+int uccl_feed_poll(uccl_feed* f) {
+  if (!f) return UCCL_EINVAL;
+  const FeedSlot& sl = f->slots[f->cur];
+  if (sl.count[0] + sl.count[1] == 0) return UCCL_OK;
+  const FeedSlot& prev = f->slots[(f->cur + f->n_slots - 1) % f->n_slots];
+  if (prev.in_flight && hipEventQuery(prev.done) == hipErrorNotReady) return UCCL_OK;  // GPU still busy: keep batching
+  (void)hipGetLastError();
+  return feed_flush(f);
+}
+
+int uccl_feed_flush(uccl_feed* f) { return f ? feed_flush(f) : UCCL_EINVAL; }
+
+int uccl_feed_sync(uccl_feed* f) {
+  if (!f) return UCCL_EINVAL;
+  const int rc = feed_flush(f);
+  if (rc != UCCL_OK) return rc;
+  for (uint32_t i = 0; i < f->n_slots; ++i) {
+    if (f->slots[i].in_flight) {
+      const hipError_t e = hipEventSynchronize(f->slots[i].done);
+      if (e != hipSuccess) return launch_failed(e);
+      f->slots[i].in_flight = false;
+    }
+  }
+  return UCCL_OK;
+}
+
+int uccl_feed_get_stats(const uccl_feed* f, uccl_feed_stats* stats) {
+  if (!f || !stats) return UCCL_EINVAL;
+  *stats = f->stats;
+  return UCCL_OK;
+}
+
+int uccl_feed_destroy(uccl_feed* f) {
+  if (!f) return UCCL_EINVAL;
+  int rc = UCCL_OK;
+  for (uint32_t i = 0; i < f->n_slots; ++i)
+    if (f->slots[i].in_flight && hipEventSynchronize(f->slots[i].done) != hipSuccess) rc = UCCL_ELAUNCH;
+  feed_free(f);
+  return rc;
+}
+
+}  // extern "C"
 
 extern "C" {
 
@@ -1098,6 +1297,7 @@ const char* uccl_strerror(int code) {
     case UCCL_EINVAL: return "invalid argument";
     case UCCL_EALIGN: return "misaligned pointer";
     case UCCL_ELAUNCH: return "HIP launch failed";
+    case UCCL_ENOMEM: return "out of memory";
     default: return "unknown error code";
   }
 }

@@ -78,6 +78,18 @@ def test_host_side_error_codes_enqueue_nothing():
     assert q(M, 64, None, 4, None) == pkg.UCCL_EINVAL and q(None, 64, A, 4, None) == pkg.UCCL_EINVAL
     assert q(M + 2, 64, A, 4, None) == pkg.UCCL_EALIGN and q(M, 64, A + 4, 4, None) == pkg.UCCL_EALIGN
     assert q(M, 1 << 40, A, 4, None) == pkg.UCCL_EINVAL
+    h = C.c_void_p()
+    fc = lib.uccl_feed_create
+    assert fc(None, A, None, B, M, 0, 0, 3, 64, 4, None) == pkg.UCCL_EINVAL
+    assert fc(C.byref(h), None, None, B, M, 0, 0, 3, 64, 4, None) == pkg.UCCL_EINVAL
+    assert fc(C.byref(h), A, None, B, M, 0, 0, 3, 0, 4, None) == pkg.UCCL_EINVAL     # capacity
+    assert fc(C.byref(h), A, None, B, M, 0, 0, 3, 64, 1, None) == pkg.UCCL_EINVAL     # slots
+    assert fc(C.byref(h), A, None, B, M, 0, 9, 3, 64, 4, None) == pkg.UCCL_EINVAL     # op
+    assert fc(C.byref(h), A + 4, None, B, M, 0, 0, 3, 64, 4, None) == pkg.UCCL_EALIGN
+    assert h.value is None
+    for fn in (lib.uccl_feed_poll, lib.uccl_feed_flush, lib.uccl_feed_sync, lib.uccl_feed_destroy):
+        assert fn(None) == pkg.UCCL_EINVAL
+    assert lib.uccl_feed_push(None, 0, D, 1) == pkg.UCCL_EINVAL
     assert lib.uccl_set_launch_shape(9) == pkg.UCCL_EINVAL and lib.uccl_set_launch_shape(3) == pkg.UCCL_EINVAL and lib.uccl_set_launch_shape(0) == pkg.UCCL_OK
     assert pkg.uccl_strerror(pkg.UCCL_EALIGN) == "misaligned pointer"
     with pytest.raises(pkg.UcclError) as err:

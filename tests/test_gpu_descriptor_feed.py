@@ -108,3 +108,35 @@ def test_graph_replay_per_message(gpu_lib):
     g.replay()  # an empty slot is a no-op
     torch.cuda.synchronize()
     assert_same(run.results()[0], eacc, "acc after empty replay")
+
+
+@pytest.mark.parametrize("capacity,poll", [(4096, True), (100, True), (37, False), (100000, False)])
+def test_host_side_feed_batches_messages(gpu_lib, capacity, poll):
+    """Records pushed message by message (reduce-scatter records to lane 0, then allgather
+    records to lane 1), with slots far smaller than a message, equal to several messages, or
+    larger than everything: the result is the oracle's, and the batcher really batched."""
+    w, msgs = wl.config5(seed=8, n_msgs=40)
+    run = DeviceRun(w, guard=0)
+    gpu_lib.uccl_set_chunk_hint(4096)
+    feed = gpu_lib.uccl_feed_create(run.acc, run.out, run.recv, run.bitmap, F32, SUM, COPY, capacity, 4)
+    try:
+        for m in msgs:
+            gpu_lib.uccl_feed_push(feed, 0, np.ascontiguousarray(m["rs"]))
+            gpu_lib.uccl_feed_push(feed, 1, np.ascontiguousarray(m["ag"]))
+            if poll:
+                gpu_lib.uccl_feed_poll(feed)
+        gpu_lib.uccl_feed_sync(feed)
+        stats = gpu_lib.uccl_feed_get_stats(feed)
+    finally:
+        gpu_lib.uccl_feed_destroy(feed)
+        gpu_lib.uccl_set_chunk_hint(0)
+    total = sum(len(m["rs"]) + len(m["ag"]) for m in msgs)
+    assert stats["records"] == total and stats["flushes"] >= 1 and stats["max_batch"] <= 2 * capacity
+    if capacity == 100000 and not poll:
+        assert stats["flushes"] == 1
+    eacc, eout, seen = w.acc.copy(), np.zeros(w.out_bytes, dtype=np.uint8), oracle.new_seen(w.n_bits)
+    for m in msgs:
+        oracle.apply(eacc, eout, w.recv_stage, m["rs"], seen, F32, SUM)
+        oracle.apply(eacc, eout, w.recv_stage, m["ag"], seen, F32, COPY)
+    acc, out, bm, _ = run.results()
+    assert_same(bm, oracle.pack_bitmap(seen), "bitmap"); assert_same(acc, eacc, "acc"); assert_same(out, eout, "out")
