@@ -352,6 +352,8 @@ def main():
     ap.add_argument("--shape", type=int, default=0, help="launch shape id (0 = auto)")
     ap.add_argument("--no-chunk-hint", action="store_true")
     ap.add_argument("--chunk-hint", type=int, default=None, help="override the chunk-size hint (bytes)")
+    ap.add_argument("--records-per-call", type=int, default=0,
+                    help="cut every phase into calls of this many records, queued back to back (0 = one call per phase)")
     ap.add_argument("--relay", action="store_true",
                     help="ring workloads: flag intermediate reduce-scatter steps forward-only (their partial "
                          "sums are not written back to the accumulator: 3 instead of 4 bytes per payload byte)")
@@ -415,13 +417,17 @@ def main():
     def call_on_current(i, s):
         c = calls[i]
         bm = bitmap2 if c.get("bm") == "bitmap2" else bitmap
-        if c.get("gather"):
-            pkg.uccl_chunk_reduce_gather(s["acc"], None, s["recv"], descs[i], counts[i], bm, w.dtype, c["op"])
-        elif c["scatter"]:
-            pkg.uccl_chunk_scatter(s[c.get("dst", "acc")], s[c.get("src", "recv")], descs[i], counts[i], bm)
-        else:
-            pkg.uccl_chunk_apply(s["acc"], s["out"], s[c.get("src", "recv")], descs[i], counts[i], bm, w.dtype,
-                                 c["op"])
+        rec = 160 if c.get("gather") else 32
+        per = args.records_per_call or counts[i]
+        for lo in range(0, counts[i], max(per, 1)):
+            n = min(per, counts[i] - lo)
+            d = descs[i][lo * rec:(lo + n) * rec]
+            if c.get("gather"):
+                pkg.uccl_chunk_reduce_gather(s["acc"], None, s["recv"], d, n, bm, w.dtype, c["op"])
+            elif c["scatter"]:
+                pkg.uccl_chunk_scatter(s[c.get("dst", "acc")], s[c.get("src", "recv")], d, n, bm)
+            else:
+                pkg.uccl_chunk_apply(s["acc"], s["out"], s[c.get("src", "recv")], d, n, bm, w.dtype, c["op"])
 
     def step(k, timed=None):
         s = sets[k % len(sets)]
@@ -455,7 +461,7 @@ def main():
         if c["op"] not in by_op or c["algo_bytes"] > calls[by_op[c["op"]]]["algo_bytes"]:
             by_op[c["op"]] = i
     timed = {}
-    if streams is None:
+    if streams is None and not args.records_per_call:
         for i in by_op.values():
             timed[i] = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                         for _ in range((args.steps + EVENT_STRIDE - 1) // EVENT_STRIDE)]
@@ -480,7 +486,7 @@ def main():
 
     elapsed = timed_loop(len(sets), timed)
     warm_elapsed = timed_loop(1) if (args.also_warm and len(sets) > 1) else None
-    if streams is not None:  # kernels of different streams overlap: no per-kernel attribution
+    if not timed:  # overlapping streams, or phases cut into several launches: no per-kernel attribution
         timed = {i: [] for i in by_op.values()}
     kernels = []
     for i, evs in timed.items():
@@ -563,7 +569,8 @@ def main():
                    "algorithmic_bytes": algo, "launch_shape": args.shape,
                    "chunk_hint": 0 if args.no_chunk_hint else chunk_bytes, "buffer_sets": len(sets),
                    "forward_only_intermediate_steps": bool(args.relay), "two_pass": bool(args.two_pass),
-                   "calls_per_step": 1 + len(calls), "streams": args.streams, "cache": cache_note},
+                   "calls_per_step": 1 + sum(-(-n // (args.records_per_call or max(n, 1))) for n in counts),
+                   "records_per_call": args.records_per_call or None, "streams": args.streams, "cache": cache_note},
         "chunks_per_s": round(unique / per_step, 1),
         "arrivals_per_s": round(arrivals / per_step, 1),
         "step_hbm_frac": round(algo / per_step / 1e9 / PEAK_HBM_GBS, 4),

@@ -65,6 +65,8 @@ def lib():
         L.orc_check_call.argtypes = [vp, u64, vp, u64]
         L.orc_pack_bitmap.restype = None
         L.orc_pack_bitmap.argtypes = [vp, u64, vp]
+        L.orc_message_status.restype = None
+        L.orc_message_status.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, C.c_int]
         L.orc_ack_report.restype = None
         L.orc_ack_report.argtypes = [vp, u64, vp, vp, vp, vp, C.c_uint32]
         L.orc_ring_allreduce.restype = C.c_int
@@ -160,6 +162,17 @@ def ack_report(words, n_bits, max_ranges):
     lib().orc_ack_report(_ptr(words), int(n_bits), C.addressof(ca), C.addressof(na), C.addressof(nr),
                          _ptr(ranges), int(max_ranges))
     return ca.value, na.value, nr.value, ranges[:min(nr.value, max_ranges)]
+
+
+def message_status(words, n_chunks, bits_per_slot, recycle=False):
+    """Per-slot (cum_ack, n_applied, complete, 0) rows; `words` is updated in place when recycling."""
+    assert words.dtype == np.uint32 and words.flags.c_contiguous
+    n_chunks = np.ascontiguousarray(n_chunks, dtype=np.uint32)
+    assert bits_per_slot % 32 == 0 and len(words) * 32 >= len(n_chunks) * bits_per_slot
+    out = np.zeros((len(n_chunks), 4), dtype=np.uint32)
+    lib().orc_message_status(_ptr(words), _ptr(n_chunks), len(n_chunks), int(bits_per_slot), _ptr(out),
+                             int(bool(recycle)))
+    return out
 
 
 def ring_allreduce(x, dtype, op=SUM) -> np.ndarray:

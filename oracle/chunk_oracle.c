@@ -306,6 +306,31 @@ void orc_ack_report(const uint32_t* words, uint64_t n_bits, uint64_t* cum_ack, u
   *n_ranges = runs;
 }
 
+void orc_message_status(uint32_t* words, const uint32_t* n_chunks, uint32_t n_slots,
+                        uint32_t bits_per_slot, uint32_t* out4, int recycle) {
+  for (uint32_t i = 0; i < n_slots; ++i) {
+    const uint64_t base = (uint64_t)i * bits_per_slot;
+    uint32_t limit = n_chunks[i] == 0 ? bits_per_slot : n_chunks[i];
+    if (limit > bits_per_slot) limit = bits_per_slot;
+    uint32_t first_clear = limit, count = 0;
+    for (uint32_t b = 0; b < limit; ++b) {
+      const uint64_t s = base + b;
+      if ((words[s >> 5] >> (s & 31)) & 1u) ++count;
+      else if (first_clear == limit) first_clear = b;
+    }
+    const uint32_t complete = (n_chunks[i] != 0 && count == limit) ? 1u : 0u;
+    out4[4 * i + 0] = first_clear;
+    out4[4 * i + 1] = count;
+    out4[4 * i + 2] = complete;
+    out4[4 * i + 3] = 0;
+    if (recycle && complete)
+      for (uint32_t b = 0; b < bits_per_slot; ++b) {
+        const uint64_t s = base + b;
+        words[s >> 5] &= ~(1u << (s & 31));
+      }
+  }
+}
+
 /* ---- whole-call preconditions ---------------------------------------------- */
 
 typedef struct { uint64_t key, end; uint64_t idx; } ivl;

@@ -96,6 +96,16 @@ void orc_pack_bitmap(const uint8_t* seen, uint64_t n_bits, uint32_t* words);
 void orc_ack_report(const uint32_t* words, uint64_t n_bits, uint64_t* cum_ack, uint64_t* n_applied,
                     uint32_t* n_ranges, uint64_t* ranges, uint32_t max_ranges);
 
+/* Per-message receiver state (Section 3.2: up to 128 messages in flight per connection, each
+ * of up to 256 chunks, a last-chunk mark that tells the receiver the chunk count).  The bitmap
+ * is n_slots windows of bits_per_slot bits (a multiple of 32); window i holds message slot i
+ * at bits [i * bits_per_slot, + limit) with limit = n_chunks[i] clamped to bits_per_slot, or
+ * bits_per_slot while n_chunks[i] == 0 (count not known yet).  out[i] = {cum_ack = first clear
+ * bit below limit (limit if none), n_applied = set bits below limit, complete = count known and
+ * all set, 0}.  recycle != 0 clears the whole window of every complete slot afterwards. */
+void orc_message_status(uint32_t* words, const uint32_t* n_chunks, uint32_t n_slots,
+                        uint32_t bits_per_slot, uint32_t* out4, int recycle);
+
 /* Textbook in-order ring allreduce of R vectors of n elements (n % R == 0),
  * no chunks, no transport: x is R*n elements (rank-major), result is R*n
  * elements (every rank's final buffer).  Returns 0 or ORC_E_ARG. */

@@ -2,15 +2,18 @@
  * The C ABI used from plain C, no Python and no PyTorch: device memory from hipMalloc, a
  * small deterministic chunk stream built here (reordered, with duplicates), one call of
  * each entry point, results compared byte for byte with the CPU oracle (linked as a
- * separate library).  Prints "C ABI OK" and exits 0 on success.
+ * separate library); then a stream of small messages through the host-side batcher.
+ * Prints "C ABI OK" and "FEED OK" and exits 0 on success.
  *
  * Build: hipcc -I include -I oracle tests/c_abi_check.c -L<pkg> -luccl_chunk -L oracle -lchunk_oracle
  */
+#define _POSIX_C_SOURCE 199309L
 #include <hip/hip_runtime_api.h>
 #include <stdint.h>
 #include <stdio.h>
 #include <stdlib.h>
 #include <string.h>
+#include <time.h>
 
 #include "chunk_oracle.h"
 #include "uccl_chunk.h"
@@ -34,6 +37,121 @@
   } while (0)
 
 static uint32_t lcg(uint32_t* s) { *s = *s * 1664525u + 1013904223u; return *s >> 8; }
+
+static double now_us(void) {
+  struct timespec t;
+  clock_gettime(CLOCK_MONOTONIC, &t);
+  return t.tv_sec * 1e6 + t.tv_nsec * 1e-3;
+}
+
+/*
+ * Small allreduces (ring share of R = 8, 4 KiB chunks, 2..32 chunks per segment) pushed message
+ * by message into uccl_feed from C: reduce-scatter records to lane 0, allgather records to
+ * lane 1, then poll.  Run twice from the same initial state -- once with poll deciding when
+ * to hand over (adaptive batching), once flushing after every message -- and each result is
+ * compared with the oracle.  Prints the host time per message of both.
+ */
+static int feed_check(hipStream_t st) {
+  enum { M = 400, R = 8, CH = 4096 };
+  uint32_t seed = 777u;
+  uint32_t cps[M];
+  uint64_t acc_off[M], bit_off[M], rec_off[M], n_rec = 0, acc_bytes = 0, n_bits = 0, out_bytes = 0, out_off[M];
+  for (int m = 0; m < M; ++m) {
+    cps[m] = 2 + lcg(&seed) % 31;
+    acc_off[m] = acc_bytes; bit_off[m] = n_bits; rec_off[m] = n_rec; out_off[m] = out_bytes;
+    acc_bytes += (uint64_t)R * cps[m] * CH;
+    n_bits += 2ull * (R - 1) * cps[m];
+    n_rec += 2ull * (R - 1) * cps[m] + 2; /* one retransmitted record per phase */
+    out_bytes += (2ull * (R - 1) - 1) * cps[m] * CH;
+  }
+  const uint64_t recv_bytes = n_rec * CH;
+  float* h_acc = (float*)malloc(acc_bytes);
+  float* h_recv = (float*)malloc(recv_bytes);
+  uccl_chunk_desc* rec = (uccl_chunk_desc*)malloc(sizeof(uccl_chunk_desc) * n_rec);
+  if (!h_acc || !h_recv || !rec) return 7;
+  for (uint64_t i = 0; i < acc_bytes / 4; ++i) h_acc[i] = (float)(lcg(&seed) % 4001) / 1000.0f - 2.0f;
+  for (uint64_t i = 0; i < recv_bytes / 4; ++i) h_recv[i] = (float)(lcg(&seed) % 4001) / 1000.0f - 2.0f;
+  /* records of message m: [rec_off, +7 cps + 1) reduce-scatter, then 7 cps + 1 allgather; rank r = 0 */
+  for (int m = 0; m < M; ++m) {
+    const uint32_t c = cps[m], per = (R - 1) * c;
+    for (int phase = 0; phase < 2; ++phase) {
+      uccl_chunk_desc* d = rec + rec_off[m] + (uint64_t)phase * (per + 1);
+      for (uint32_t k = 0; k < per; ++k) {
+        const uint32_t s = k / c, j = k % c;
+        const uint32_t seg = phase == 0 ? (2 * R - s - 1) % R : (R - s) % R;
+        d[k].dst_off = acc_off[m] + ((uint64_t)seg * c + j) * CH;
+        const uint64_t fwd_index = (uint64_t)phase * per + k; /* the last allgather step does not forward */
+        d[k].out_off = (phase == 1 && s == R - 2) ? UCCL_NO_FORWARD : out_off[m] + fwd_index * CH;
+        d[k].len = CH;
+        d[k].seq = (uint32_t)(bit_off[m] + (uint64_t)phase * per + k);
+      }
+      for (uint32_t k = per - 1; k > 0; --k) { /* arrival order within the phase: shuffled */
+        uint32_t j = lcg(&seed) % (k + 1);
+        uccl_chunk_desc t = d[k]; d[k] = d[j]; d[j] = t;
+      }
+      d[per] = d[lcg(&seed) % per]; /* a retransmission of one of them, in a slot of its own */
+      for (uint32_t k = 0; k <= per; ++k) d[k].src_off = (rec_off[m] + (uint64_t)phase * (per + 1) + k) * CH;
+      /* identical payload for the two copies */
+      for (uint32_t k = 0; k < per; ++k)
+        if (d[k].seq == d[per].seq) memcpy((char*)h_recv + d[per].src_off, (char*)h_recv + d[k].src_off, CH);
+    }
+  }
+
+  /* oracle: per message, reduce-scatter records then allgather records */
+  float* o_acc = (float*)malloc(acc_bytes);
+  unsigned char* o_out = (unsigned char*)calloc(out_bytes, 1);
+  uint8_t* seen = (uint8_t*)calloc(n_bits, 1);
+  memcpy(o_acc, h_acc, acc_bytes);
+  for (int m = 0; m < M; ++m) {
+    const uint32_t per = (R - 1) * cps[m];
+    const orc_desc* d = (const orc_desc*)(rec + rec_off[m]);
+    if (orc_apply(o_acc, acc_bytes, o_out, out_bytes, h_recv, recv_bytes, d, per + 1, seen, n_bits, ORC_F32, ORC_SUM) != per ||
+        orc_apply(o_acc, acc_bytes, o_out, out_bytes, h_recv, recv_bytes, d + per + 1, per + 1, seen, n_bits, ORC_F32, ORC_COPY) != per) {
+      fprintf(stderr, "feed: oracle refused message %d\n", m);
+      return 7;
+    }
+  }
+
+  void *d_acc, *d_out, *d_recv, *d_bm;
+  CK(hipMalloc(&d_acc, acc_bytes)); CK(hipMalloc(&d_out, out_bytes)); CK(hipMalloc(&d_recv, recv_bytes));
+  CK(hipMalloc(&d_bm, (n_bits + 31) / 32 * 4));
+  CK(hipMemcpy(d_recv, h_recv, recv_bytes, hipMemcpyHostToDevice));
+  float* g_acc = (float*)malloc(acc_bytes);
+  unsigned char* g_out = (unsigned char*)malloc(out_bytes);
+  UC(uccl_set_chunk_hint(CH));
+  double us[2];
+  uccl_feed_stats stats[2];
+  for (int mode = 0; mode < 2; ++mode) { /* 0: adaptive (poll), 1: hand over after every message */
+    CK(hipMemcpy(d_acc, h_acc, acc_bytes, hipMemcpyHostToDevice));
+    CK(hipMemset(d_out, 0, out_bytes));
+    UC(uccl_dedup_reset((uint32_t*)d_bm, n_bits, st));
+    CK(hipStreamSynchronize(st));
+    uccl_feed* f = NULL;
+    UC(uccl_feed_create(&f, d_acc, d_out, d_recv, (uint32_t*)d_bm, UCCL_F32, UCCL_SUM, UCCL_COPY, 1u << 15, 8, st));
+    const double t0 = now_us();
+    for (int m = 0; m < M; ++m) {
+      const uint32_t per = (R - 1) * cps[m];
+      UC(uccl_feed_push(f, 0, rec + rec_off[m], per + 1));
+      UC(uccl_feed_push(f, 1, rec + rec_off[m] + per + 1, per + 1));
+      UC(mode == 0 ? uccl_feed_poll(f) : uccl_feed_flush(f));
+    }
+    UC(uccl_feed_sync(f));
+    us[mode] = (now_us() - t0) / M;
+    UC(uccl_feed_get_stats(f, &stats[mode]));
+    UC(uccl_feed_destroy(f));
+    CK(hipMemcpy(g_acc, d_acc, acc_bytes, hipMemcpyDeviceToHost));
+    CK(hipMemcpy(g_out, d_out, out_bytes, hipMemcpyDeviceToHost));
+    if (memcmp(g_acc, o_acc, acc_bytes)) { fprintf(stderr, "feed mode %d: acc differs\n", mode); return 8; }
+    if (memcmp(g_out, o_out, out_bytes)) { fprintf(stderr, "feed mode %d: out_stage differs\n", mode); return 8; }
+  }
+  UC(uccl_set_chunk_hint(0));
+  printf("FEED OK: %d messages, %llu records; adaptive %.2f us/message (%llu hand-overs, largest %llu records, "
+         "%llu slot waits); one hand-over per message %.2f us/message (%llu hand-overs, %llu slot waits)\n",
+         (int)M, (unsigned long long)n_rec, us[0], (unsigned long long)stats[0].flushes,
+         (unsigned long long)stats[0].max_batch, (unsigned long long)stats[0].slot_waits, us[1],
+         (unsigned long long)stats[1].flushes, (unsigned long long)stats[1].slot_waits);
+  return 0;
+}
 
 int main(void) {
   enum { N = 300, C = 8192, DUP = 37 }; /* 300 logical chunks of 8 KiB, 37 retransmitted */
@@ -130,5 +248,5 @@ int main(void) {
   if (memcmp(g_out, o_dst, acc_bytes)) { fprintf(stderr, "scatter differs\n"); return 6; }
 
   printf("C ABI OK: %d chunks, %d duplicates, version %d\n", (int)N, (int)DUP, uccl_version());
-  return 0;
+  return feed_check(st);
 }

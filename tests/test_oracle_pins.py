@@ -478,6 +478,67 @@ def test_ack_report_against_numpy(n_bits, density):
         assert np.array_equal(rg.astype(np.int64), runs)
 
 
+def _slot_words(rows, bits_per_slot):
+    """rows: one list of 0/1 per slot (shorter than the window = zero padded)."""
+    b = np.zeros((len(rows), bits_per_slot), dtype=np.uint8)
+    for i, r in enumerate(rows):
+        b[i, :len(r)] = r
+    return np.packbits(b.reshape(-1), bitorder="little").view(np.uint32).copy()
+
+
+def test_message_status_hand_cases():
+    """Section 3.2's message window: hand-worked slots of 64 bits."""
+    rows = [
+        [1, 1, 1, 0, 1],            # count 5 known: cumulative 3, applied 4, incomplete
+        [1] * 5,                    # count 5: complete
+        [1] * 5 + [1, 1],           # count 5 with stray bits above it: still complete, strays not counted
+        [1] * 40,                   # count unknown (0): window-wide reading, never complete
+        [],                         # empty slot, count 7
+        [1] * 64,                   # full window, count 64
+        [0] + [1] * 63,             # first bit missing
+        [1] * 33 + [0] + [1] * 4,   # hole right after a word boundary
+    ]
+    counts = [5, 5, 5, 0, 7, 64, 64, 38]
+    w = _slot_words(rows, 64)
+    before = w.copy()
+    st = oracle.message_status(w, counts, 64)
+    assert st.tolist() == [[3, 4, 0, 0], [5, 5, 1, 0], [5, 5, 1, 0], [40, 40, 0, 0], [0, 0, 0, 0],
+                           [64, 64, 1, 0], [0, 63, 0, 0], [33, 37, 0, 0]]
+    assert np.array_equal(w, before), "without recycling the bitmap is only read"
+    st2 = oracle.message_status(w, counts, 64, recycle=True)
+    assert np.array_equal(st2, st)
+    after = w.view(np.uint64)
+    for i in range(len(rows)):
+        assert after[i] == (0 if st[i, 2] else before.view(np.uint64)[i]), i   # strays of slot 2 are cleared too
+    # a count beyond the window is clamped to the window
+    assert oracle.message_status(_slot_words([[1] * 32], 32), [100], 32).tolist() == [[32, 32, 1, 0]]
+
+
+@pytest.mark.parametrize("bits_per_slot,n_slots", [(32, 5), (256, 128), (96, 7), (2048, 3)])
+def test_message_status_against_numpy(bits_per_slot, n_slots):
+    """An independent reading of the same definition with array operations."""
+    g = pl.rng(bits_per_slot, n_slots)
+    for trial in range(4):
+        counts = g.integers(0, bits_per_slot + 1, n_slots).astype(np.uint32)
+        bits = (g.random((n_slots, bits_per_slot)) < [0.5, 0.9, 0.99, 1.0][trial]).astype(np.uint8)
+        bits[::3] = 1                                     # every third slot has everything
+        bits[1::3, : bits_per_slot // 3] = 1              # a cumulative prefix
+        words = np.packbits(bits.reshape(-1), bitorder="little").view(np.uint32).copy()
+        limit = np.where(counts == 0, bits_per_slot, counts)
+        below = np.arange(bits_per_slot)[None, :] < limit[:, None]
+        seen = bits.astype(bool) & below
+        missing = ~bits.astype(bool) & below
+        cum = np.where(missing.any(1), missing.argmax(1), limit)
+        cnt = seen.sum(1)
+        done = (counts != 0) & (cnt == limit)
+        st = oracle.message_status(words, counts, bits_per_slot, recycle=True)
+        assert np.array_equal(st[:, 0], cum) and np.array_equal(st[:, 1], cnt)
+        assert np.array_equal(st[:, 2], done.astype(np.uint32)) and not st[:, 3].any()
+        kept = bits.copy()
+        kept[done] = 0
+        assert np.array_equal(words, np.packbits(kept.reshape(-1), bitorder="little").view(np.uint32))
+
+
 # --- P7: a chunk that never arrives ------------------------------------------------
 
 def test_missing_chunk_leaves_hole_and_clear_bit():
