@@ -514,6 +514,23 @@ def main():
     assert int(hdr[:8].view(np.uint64)[0]) == w.n_bits and int(hdr[20:24].view(np.uint32)[0]) == 1, \
         "after a full step every chunk is acknowledged"
 
+    # per-message status of one connection's window (128 slots x 256 bits), half of the slots complete
+    win = torch.zeros(128 * 8, dtype=torch.int32, device="cuda")
+    win[: 64 * 8] = -1
+    n_chunks = torch.full((128,), 200, dtype=torch.int32, device="cuda")
+    status = torch.zeros(128 * 4, dtype=torch.int32, device="cuda")
+    evs = []
+    for _ in range(30):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        b.record()
+        pkg.uccl_time_next_launch(a, b)
+        pkg.uccl_message_status(win, n_chunks, 128, 256, status, False)
+        evs.append((a, b))
+    torch.cuda.synchronize()
+    status_us = float(np.median([a.elapsed_time(b) for a, b in evs[5:]])) * 1e3
+    assert int(status.view(128, 4)[:, 2].sum()) == 64
+
     # the machine's own streaming ceilings, beside the published peak: plain c = a + b and
     # c = a of the framework's kernels on buffers of this workload's order of size, rotating
     def ceiling(fn, streams, nbytes=240 << 20, nsets=4, reps=20):
@@ -597,6 +614,8 @@ def main():
         "stream_ceiling": stream_ceiling,
         "dedup_report": {"n_bits": w.n_bits, "median_us": round(report_us, 2),
                          "what": "ack_report_kernel: cumulative ack, applied count, selective ranges"},
+        "message_status": {"slots": 128, "bits_per_slot": 256, "median_us": round(status_us, 2),
+                           "what": "message_status_kernel: per-slot cumulative point, applied count, completion"},
     }
     if args.workload.startswith("config5"):
         result["us_per_message"] = round(per_step * 1e6 / w.extra["n_msgs"], 3)

@@ -222,6 +222,31 @@ int uccl_dedup_report(const uint32_t* dedup_bitmap, uint64_t n_bits, void* repor
                       uint32_t max_ranges, void* stream);
 
 /*
+ * uccl_message_status -- per-message receiver state for one connection's window of in-flight
+ * messages (Section 3.2: a 7-bit message id allows 128 messages in flight, an 8-bit chunk
+ * sequence number 256 chunks each, and a last-chunk mark tells the receiver the chunk count).
+ * The bitmap is read as n_slots windows of bits_per_slot bits; window i holds the chunks of
+ * the message in slot i at bits [i * bits_per_slot, + limit), where limit = n_chunks[i]
+ * (clamped to bits_per_slot), or bits_per_slot while the count is not known (n_chunks[i] == 0).
+ *   status[i].cum_ack    first clear bit of the window below limit, limit if none
+ *   status[i].n_applied  set bits below limit
+ *   status[i].complete   1 iff n_chunks[i] != 0 and every bit below limit is set
+ * recycle != 0: after its status is taken, the whole window of every complete slot is cleared,
+ * so that the slot's message id can be reused; only then does the call write the bitmap.
+ * dedup_bitmap, n_chunks, status: DEVICE memory (status may be pinned host memory), 4-byte
+ * aligned, status 16-byte aligned.  bits_per_slot: multiple of 32 in 32..2048 (UCCL_EINVAL
+ * otherwise).  n_slots == 0 is a no-op.  Stream ordered.
+ */
+typedef struct uccl_msg_status {
+  uint32_t cum_ack;
+  uint32_t n_applied;
+  uint32_t complete;
+  uint32_t reserved; /* written as 0 */
+} uccl_msg_status;
+int uccl_message_status(uint32_t* dedup_bitmap, const uint32_t* n_chunks, uint32_t n_slots,
+                        uint32_t bits_per_slot, uccl_msg_status* status, int recycle, void* stream);
+
+/*
  * uccl_feed -- host-side batcher between the control path and the kernels (Appendix C.4:
  * kernel launches per batch hurt small messages; adaptive batching is the remedy).
  * The ONLY part of this library that allocates: `n_slots` (2..1024) slots, each two lanes of

@@ -73,6 +73,8 @@ _SIGNATURES = {
     "uccl_feed_get_stats": (C.c_int, [C.c_void_p, C.POINTER(uccl_feed_stats)]),
     "uccl_feed_destroy": (C.c_int, [C.c_void_p]),
     "uccl_dedup_report": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p]),
+    "uccl_message_status": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_int,
+                                      C.c_void_p]),
     "uccl_set_launch_shape": (C.c_int, [C.c_int]),
     "uccl_set_chunk_hint": (C.c_int, [C.c_uint32]),
     "uccl_time_next_launch": (C.c_int, [C.c_void_p, C.c_void_p]),
@@ -242,6 +244,12 @@ def uccl_feed_destroy(feed):
 
 
 ACK_HEADER_BYTES = 32
+
+
+def uccl_message_status(dedup_bitmap, n_chunks, n_slots, bits_per_slot, status, recycle=False, stream=None):
+    """Per-slot {cum_ack, n_applied, complete, 0} of a connection's message window into `status`."""
+    _check(load().uccl_message_status(_ptr(dedup_bitmap), _ptr(n_chunks), int(n_slots), int(bits_per_slot),
+                                      _ptr(status), int(bool(recycle)), _stream(stream)), "uccl_message_status")
 
 
 def uccl_dedup_report(dedup_bitmap, n_bits, report, max_ranges, stream=None):

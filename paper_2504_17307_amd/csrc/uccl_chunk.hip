@@ -802,6 +802,43 @@ __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __rest
   }
 }
 
+// Per-message window status (Section 3.2's message id / chunk sequence number / last-chunk
+// mark): one wavefront per slot.  Lane l owns word l of the slot's window (a window is at
+// most 64 words), masks it to the slot's limit, and the wavefront combines: a ballot of
+// "has a clear bit below the limit" locates the first hole, a butterfly sum gives the
+// applied count.  With `recycle`, the lanes of a complete slot store zeros over its window.
+__global__ void __launch_bounds__(256) message_status_kernel(uint32_t* __restrict__ bitmap,
+                                                             const uint32_t* __restrict__ n_chunks,
+                                                             uint32_t n_slots, uint32_t words_per_slot,
+                                                             uint4* __restrict__ status, uint32_t recycle) {
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t slot = blockIdx.x * 4u + (threadIdx.x >> 6);
+  if (slot >= n_slots) return;  // whole wavefronts leave together; no barrier follows
+  const uint32_t window = words_per_slot * 32u;
+  const uint32_t known = n_chunks[slot];
+  const uint32_t limit = known == 0u ? window : (known < window ? known : window);
+  uint32_t* w = bitmap + static_cast<uint64_t>(slot) * words_per_slot + lane;
+  uint32_t word = 0u, mask = 0u;
+  if (lane < words_per_slot) {
+    word = *w;
+    const uint32_t lo = lane * 32u;
+    mask = limit >= lo + 32u ? ~0u : (limit > lo ? (1u << (limit - lo)) - 1u : 0u);
+  }
+  const uint32_t clear = ~word & mask;
+  const unsigned long long holes = __ballot(clear != 0u);
+  uint32_t cum = limit;
+  if (holes) {
+    const int first = __ffsll(holes) - 1;
+    cum = static_cast<uint32_t>(first) * 32u + static_cast<uint32_t>(__shfl(__ffs(clear) - 1, first, 64));
+  }
+  uint32_t count = __popc(word & mask);
+#pragma unroll
+  for (uint32_t d = 32; d >= 1; d >>= 1) count += __shfl_xor(count, d, 64);
+  const uint32_t complete = (known != 0u && count == limit) ? 1u : 0u;
+  if (lane == 0) status[slot] = make_uint4(cum, count, complete, 0u);
+  if (recycle && complete && lane < words_per_slot) *w = 0u;
+}
+
 // ---- host side ----------------------------------------------------------------------
 
 thread_local char t_detail[256] = "";
@@ -1270,6 +1307,18 @@ int uccl_dedup_report(const uint32_t* dedup_bitmap, uint64_t n_bits, void* repor
   uint64_t* ranges = reinterpret_cast<uint64_t*>(hdr + 1);
   return launch_kernel(ack_report_kernel, 1, 1024, static_cast<hipStream_t>(stream), dedup_bitmap,
                        n_bits, hdr, ranges, max_ranges);
+}
+
+int uccl_message_status(uint32_t* dedup_bitmap, const uint32_t* n_chunks, uint32_t n_slots,
+                        uint32_t bits_per_slot, uccl_msg_status* status, int recycle, void* stream) {
+  if (bits_per_slot < 32 || bits_per_slot > 2048 || (bits_per_slot & 31u)) return UCCL_EINVAL;
+  if (n_slots == 0) return UCCL_OK;
+  if (!dedup_bitmap || !n_chunks || !status) return UCCL_EINVAL;
+  if (misaligned(dedup_bitmap, 4) || misaligned(n_chunks, 4) || misaligned(status, 16)) return UCCL_EALIGN;
+  const uint32_t grid = (n_slots + 3) / 4;  // one wavefront per slot, four per workgroup
+  return launch_kernel(message_status_kernel, grid, 256, static_cast<hipStream_t>(stream), dedup_bitmap,
+                       n_chunks, n_slots, bits_per_slot / 32, reinterpret_cast<uint4*>(status),
+                       recycle ? 1u : 0u);
 }
 
 int uccl_time_next_launch(void* start_event, void* stop_event) {

@@ -78,6 +78,12 @@ def test_host_side_error_codes_enqueue_nothing():
     assert q(M, 64, None, 4, None) == pkg.UCCL_EINVAL and q(None, 64, A, 4, None) == pkg.UCCL_EINVAL
     assert q(M + 2, 64, A, 4, None) == pkg.UCCL_EALIGN and q(M, 64, A + 4, 4, None) == pkg.UCCL_EALIGN
     assert q(M, 1 << 40, A, 4, None) == pkg.UCCL_EINVAL
+    ms = lib.uccl_message_status
+    assert ms(M, M, 4, 0, A, 0, None) == pkg.UCCL_EINVAL and ms(M, M, 4, 48, A, 0, None) == pkg.UCCL_EINVAL
+    assert ms(M, M, 4, 4096, A, 0, None) == pkg.UCCL_EINVAL and ms(None, M, 4, 256, A, 0, None) == pkg.UCCL_EINVAL
+    assert ms(M, None, 4, 256, A, 0, None) == pkg.UCCL_EINVAL and ms(M, M, 4, 256, None, 0, None) == pkg.UCCL_EINVAL
+    assert ms(M + 2, M, 4, 256, A, 0, None) == pkg.UCCL_EALIGN and ms(M, M, 4, 256, A + 8, 0, None) == pkg.UCCL_EALIGN
+    assert ms(None, None, 0, 256, None, 0, None) == pkg.UCCL_OK
     h = C.c_void_p()
     fc = lib.uccl_feed_create
     assert fc(None, A, None, B, M, 0, 0, 3, 64, 4, None) == pkg.UCCL_EINVAL

@@ -475,6 +475,96 @@ def test_ack_report(gpu_lib, n_bits, density):
             assert np.all(raw[32 + 16 * max_ranges:] == 0xCD), "wrote past the room given"
 
 
+@pytest.mark.parametrize("bits_per_slot,n_slots", [(32, 1), (32, 9), (64, 130), (256, 128), (96, 1000), (2048, 5),
+                                                   (1024, 64)])
+def test_message_status(gpu_lib, bits_per_slot, n_slots):
+    g = pl.rng(bits_per_slot * 7 + n_slots, 6)
+    for trial, density in enumerate((0.5, 0.95, 0.999, 1.0)):
+        counts = g.integers(0, bits_per_slot + 1, n_slots).astype(np.uint32)
+        counts[::5] = bits_per_slot
+        if n_slots > 2:
+            counts[2] = bits_per_slot + 77  # clamped to the window
+        bits = (g.random((n_slots, bits_per_slot)) < density).astype(np.uint8)
+        bits[::3] = 1
+        bits[1::3, : bits_per_slot // 3] = 1
+        words = np.packbits(bits.reshape(-1), bitorder="little").view(np.uint32).copy()
+        for recycle in (False, True):
+            ewords = words.copy()
+            est = oracle.message_status(ewords, counts, bits_per_slot, recycle)
+            d_words = torch.cat([to_dev(words).view(torch.int32), torch.full((8,), 0x5A5A5A5A, dtype=torch.int32, device="cuda")])
+            st = torch.full((n_slots * 4 + 4,), 0x7B7B7B7B, dtype=torch.int32, device="cuda")
+            gpu_lib.uccl_message_status(d_words, to_dev(counts), n_slots, bits_per_slot, st, recycle)
+            torch.cuda.synchronize()
+            got = st.cpu().numpy().view(np.uint32)
+            assert np.array_equal(got[:n_slots * 4].reshape(-1, 4), est), (trial, recycle)
+            assert np.all(got[n_slots * 4:] == 0x7B7B7B7B), "wrote past the status rows"
+            gw = d_words.cpu().numpy().view(np.uint32)
+            assert np.array_equal(gw[:len(words)], ewords), (trial, recycle)
+            assert np.all(gw[len(words):] == 0x5A5A5A5A), "wrote past the bitmap"
+            if recycle and trial == 3:
+                assert est[::5, 2].all() and not ewords.reshape(n_slots, -1)[::5].any()
+
+
+def test_message_window_over_small_allreduces(gpu_lib):
+    """A connection's message window driven the way Section 3.1 lays it out: a message has at
+    most 256 chunks and sits in one of 128 slots, the bit index of a chunk is slot * 256 + chunk
+    sequence number, the last chunk's mark gives the count, and a slot is reused once its
+    message is complete (status with recycling).  Three rounds over the window, each with other
+    lengths, some chunks retransmitted, some messages finished only a round later."""
+    from synth import header as hd
+    C_ = 1024
+    g = pl.rng(41, 41)
+    n_slots, per = hd.MESSAGES_IN_FLIGHT, hd.CHUNKS_PER_MESSAGE
+    acc = pl.uniform_f32(41, 1, n_slots * per * C_ // 4)
+    eacc = acc.copy()
+    d_acc = to_dev(acc)
+    bitmap = torch.zeros(n_slots * per // 32, dtype=torch.int32, device="cuda")
+    seen = oracle.new_seen(n_slots * per)
+    counts = np.zeros(n_slots, dtype=np.uint32)    # the receiver's knowledge of message lengths
+    pending = {}                                   # slot -> (chunks in the message, csns still to come)
+    for rnd in range(3):
+        held, hdrs = {}, []
+        for slot in range(n_slots):
+            if slot in pending:                    # the rest of an unfinished message arrives now
+                total, missing = pending[slot]
+                csn = np.array(sorted(missing), dtype=np.int64)
+            else:
+                total = int(g.integers(1, per + 1))
+                csn = np.arange(total, dtype=np.int64)
+                if slot % 17 == rnd:               # hold a quarter of this message back for a round
+                    hold = set(g.choice(total, size=max(1, total // 4), replace=False).tolist())
+                    held[slot] = (total, hold)
+                    csn = np.array([c for c in csn if c not in hold], dtype=np.int64)
+            again = csn[g.random(len(csn)) < 0.05]                      # retransmitted copies
+            csn = g.permutation(np.concatenate([csn, again]))
+            hdrs.append(hd.pack(7, slot, csn, csn == total - 1))
+        pending = held
+        hdr = np.concatenate(hdrs)
+        hdr = hdr[g.permutation(len(hdr))]                              # paths interleave the messages
+        seq = hd.seq_of(hdr)
+        recv = pl.uniform_f32(41, 10 + rnd, n_slots * per * C_ // 4)    # payload of (slot, csn) at its own place
+        d = np.zeros(len(hdr), dtype=DESC)
+        d["src_off"] = seq.astype(np.uint64) * C_
+        d["dst_off"] = seq.astype(np.uint64) * C_
+        d["out_off"] = NO_FORWARD
+        d["len"], d["seq"] = C_, seq
+        oracle.apply(eacc, None, recv, d, seen, F32, SUM, check=False)
+        gpu_lib.uccl_chunk_apply(d_acc, None, to_dev(recv), to_dev(d), len(d), bitmap, F32, SUM)
+        counts = np.maximum(counts, hd.chunk_counts(hdr))
+        ewords = oracle.pack_bitmap(seen)
+        est = oracle.message_status(ewords, counts, per, recycle=True)
+        st = torch.zeros(n_slots * 4, dtype=torch.int32, device="cuda")
+        gpu_lib.uccl_message_status(bitmap, to_dev(counts), n_slots, per, st, True)
+        torch.cuda.synchronize()
+        assert np.array_equal(st.cpu().numpy().view(np.uint32).reshape(-1, 4), est), rnd
+        assert np.array_equal(bitmap.cpu().numpy().view(np.uint32), ewords), rnd
+        assert_same(d_acc.cpu().numpy().view(np.float32), eacc, f"acc after round {rnd}")
+        done = est[:, 2] == 1
+        assert set(np.flatnonzero(~done).tolist()) == set(pending), "exactly the held-back messages are incomplete"
+        seen[:] = np.unpackbits(ewords.view(np.uint8), bitorder="little")[:len(seen)]   # recycled slots start over
+        counts[done] = 0
+
+
 def test_ack_report_after_a_lossy_phase(gpu_lib):
     """Drop some chunks of a reduce-scatter phase, apply the rest, ask for the report into pinned
     host memory: the holes are exactly the complement of cum_ack + ranges."""

@@ -107,3 +107,33 @@ def test_small_messages_layout():
     ends = np.cumsum(sizes)
     for m, lo, hi in zip(msgs, ends - sizes, ends):
         assert m["rs"]["dst_off"].min() >= lo and (m["rs"]["dst_off"] + m["rs"]["len"]).max() <= hi
+
+
+def test_control_header_fields_roundtrip():
+    """Section 3.1: 8 + 7 + 8 + 1 + 8 bits; every field survives packing, fields do not overlap."""
+    from synth import header as hd
+    from synth import payload as pl
+    g = pl.rng(5, 5)
+    n = 5000
+    f = dict(conn=g.integers(0, 256, n), msg=g.integers(0, 128, n), csn=g.integers(0, 256, n),
+             last=g.integers(0, 2, n), spare=g.integers(0, 256, n))
+    h = hd.pack(**f)
+    assert h.dtype == np.uint32
+    back = hd.unpack(h)
+    for k in f:
+        assert np.array_equal(back[k], f[k]), k
+    # one field at its maximum, the others zero: exactly that field's bits are set
+    widths = dict(conn=8, msg=7, csn=8, last=1, spare=8)
+    seen = 0
+    for k, bits in widths.items():
+        one = int(hd.pack(**{x: ((1 << bits) - 1 if x == k else 0) for x in widths}))
+        assert bin(one).count("1") == bits and one & seen == 0
+        seen |= one
+    assert seen == 0xFFFFFFFF
+    assert hd.MESSAGES_IN_FLIGHT == 128 and hd.CHUNKS_PER_MESSAGE == 256
+    assert np.array_equal(hd.seq_of(h), f["msg"] * 256 + f["csn"])
+    with pytest.raises(AssertionError):
+        hd.pack(0, 128, 0, 0)
+    hs = hd.pack(3, [5, 5, 9], [0, 41, 7], [0, 1, 0])
+    c = hd.chunk_counts(hs)
+    assert c[5] == 42 and c[9] == 0 and c.sum() == 42
