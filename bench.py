@@ -34,9 +34,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 # source it was measured on, identified by the hash of the HIP source file.
 MEASURED_TRAFFIC = {
     # (workload, first 16 hex digits of sha256 of csrc/uccl_chunk.hip): bytes per launch
-    ("config2", "fc876b554adf3680"): 1008025631,
-    ("config3", "fc876b554adf3680"): 3625072844,
-    ("direct-rs", "fc876b554adf3680"): 1208244249,
+    ("config2", "df3eb96c456cc612"): 1008011460,
+    ("config3", "df3eb96c456cc612"): 3625076494,
+    ("direct-rs", "df3eb96c456cc612"): 1208234029,
 }
 
 WORKLOADS = {
