@@ -260,7 +260,12 @@ int uccl_message_status(uint32_t* dedup_bitmap, const uint32_t* n_chunks, uint32
  *   poll   flushes pending records if the previous hand-over has finished -- the GPU would
  *          otherwise idle -- and keeps batching if it has not
  *   sync   flush, then wait until every hand-over has finished
- * Buffers, bitmap and element type are fixed at creation; lane ops are given there too.
+ *   destroy  waits for the hand-overs in flight, frees the slots; records pushed but not yet
+ *          handed over are dropped (call sync first to keep them)
+ * Buffers, bitmap and element type are fixed at creation; lane ops are given there too.  The
+ * slots live on the device that is current at creation; use the feed with that device current.
+ * If a hand-over fails half way (UCCL_ELAUNCH), its records stay in the slot and the next
+ * flush offers them again; records already applied are then dropped by the bitmap.
  * A feed is used by one host thread at a time.  All calls return UCCL_OK or a negative code.
  */
 typedef struct uccl_feed uccl_feed;

@@ -27,6 +27,8 @@
 #include <string.h>
 
 #include <new>
+#include <tuple>
+#include <utility>
 
 #include "uccl_chunk.h"
 
@@ -851,16 +853,26 @@ int launch_failed(hipError_t e) {
   return UCCL_ELAUNCH;
 }
 
-// Launch, attaching the one-shot timing events (if any) to this very dispatch.
-template <class Kernel, class... KernelArgs>
-int launch_kernel(Kernel kernel, uint32_t tiles, uint32_t threads, hipStream_t s, KernelArgs... a) {
-  if (t_start != nullptr || t_stop != nullptr) {
-    hipExtLaunchKernelGGL(kernel, dim3(tiles), dim3(threads), 0, s, t_start, t_stop, 0, a...);
-    t_start = t_stop = nullptr;
-  } else {
-    hipLaunchKernelGGL(kernel, dim3(tiles), dim3(threads), 0, s, a...);
-  }
-  const hipError_t e = hipGetLastError();
+// Launch through the calls that RETURN the launch status (the <<<>>> form leaves it in the
+// thread's last-error slot, where an earlier, unrelated error could be mistaken for ours and
+// reading it would clear the caller's).  The one-shot timing events, if any, are attached to
+// this very dispatch.
+template <class... Params, size_t... I>
+hipError_t launch_raw(void (*kernel)(Params...), dim3 grid, dim3 block, hipStream_t s,
+                      std::tuple<Params...>& params, std::index_sequence<I...>) {
+  void* ptrs[] = {static_cast<void*>(&std::get<I>(params))...};
+  hipEvent_t t0 = t_start, t1 = t_stop;
+  t_start = t_stop = nullptr;
+  if (t0 != nullptr || t1 != nullptr)
+    return hipExtLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, s, t0, t1, 0);
+  return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, ptrs, 0, s);
+}
+
+template <class... Params, class... KernelArgs>
+int launch_kernel(void (*kernel)(Params...), uint32_t tiles, uint32_t threads, hipStream_t s, KernelArgs... a) {
+  static_assert(sizeof...(Params) == sizeof...(KernelArgs), "one argument per kernel parameter");
+  std::tuple<Params...> params(static_cast<Params>(a)...);  // objects of the kernel's own parameter types
+  const hipError_t e = launch_raw(kernel, dim3(tiles), dim3(threads), s, params, std::index_sequence_for<Params...>{});
   return e == hipSuccess ? UCCL_OK : launch_failed(e);
 }
 
@@ -1155,8 +1167,10 @@ int uccl_feed_poll(uccl_feed* f) {
   const FeedSlot& sl = f->slots[f->cur];
   if (sl.count[0] + sl.count[1] == 0) return UCCL_OK;
   const FeedSlot& prev = f->slots[(f->cur + f->n_slots - 1) % f->n_slots];
-  if (prev.in_flight && hipEventQuery(prev.done) == hipErrorNotReady) return UCCL_OK;  // GPU still busy: keep batching
-  (void)hipGetLastError();
+  if (prev.in_flight && hipEventQuery(prev.done) == hipErrorNotReady) {
+    (void)hipGetLastError();  // "not ready" is an answer, not an error to leave behind
+    return UCCL_OK;           // GPU still busy: keep batching
+  }
   return feed_flush(f);
 }
 
@@ -1292,10 +1306,7 @@ int uccl_dedup_reset(uint32_t* dedup_bitmap, uint64_t n_bits, void* stream) {
   const uint64_t words = (n_bits + 31) / 32;
   const uint64_t blocks = (words + 255) / 256;
   const uint32_t grid = static_cast<uint32_t>(blocks < 4096 ? blocks : 4096);
-  hipLaunchKernelGGL(fill_words_kernel, dim3(grid), dim3(256), 0, static_cast<hipStream_t>(stream),
-                     dedup_bitmap, words, 0u);
-  const hipError_t e = hipGetLastError();
-  return e == hipSuccess ? UCCL_OK : launch_failed(e);
+  return launch_kernel(fill_words_kernel, grid, 256, static_cast<hipStream_t>(stream), dedup_bitmap, words, 0u);
 }
 
 int uccl_dedup_report(const uint32_t* dedup_bitmap, uint64_t n_bits, void* report,
