@@ -26,6 +26,7 @@
 #include <stdio.h>
 #include <string.h>
 
+#include <atomic>
 #include <new>
 #include <tuple>
 #include <utility>
@@ -845,8 +846,10 @@ __global__ void __launch_bounds__(256) message_status_kernel(uint32_t* __restric
 
 thread_local char t_detail[256] = "";
 thread_local hipEvent_t t_start = nullptr, t_stop = nullptr;  // one-shot, see uccl_time_next_launch
-int g_shape = UCCL_SHAPE_AUTO;
-uint32_t g_chunk_hint = 0;
+// process-wide tuning knobs; atomics so that a setter racing with a launch on another thread
+// yields the old or the new value, never a torn one
+std::atomic<int> g_shape{UCCL_SHAPE_AUTO};
+std::atomic<uint32_t> g_chunk_hint{0};
 
 int launch_failed(hipError_t e) {
   snprintf(t_detail, sizeof(t_detail), "%s: %s", hipGetErrorName(e), hipGetErrorString(e));
@@ -895,8 +898,9 @@ int launch_flat(const Args& a, hipStream_t s) {
 // payload per stream when the chunk size is known, otherwise grown with the record count.
 uint32_t flat_tile(uint32_t n_descs) {
   uint32_t t;
-  if (g_chunk_hint) {
-    t = (32768u + g_chunk_hint - 1) / g_chunk_hint;
+  const uint32_t hint = g_chunk_hint.load(std::memory_order_relaxed);
+  if (hint) {
+    t = (32768u + hint - 1) / hint;
   } else {
     // Unknown chunk size: a tile too large for big chunks costs a few percent, a tile too
     // small for 4 KiB chunks costs a factor of two, so grow the tile once the record count
@@ -919,12 +923,13 @@ int launch_flat_tile(const Args& a, hipStream_t s) {
 
 template <class Op>
 int launch_shape(const Args& a, hipStream_t s) {
-  if (g_shape == UCCL_SHAPE_AUTO || g_shape == UCCL_SHAPE_FLAT) return launch_flat_tile<Op>(a, s);
-  if (g_shape == UCCL_SHAPE_WAVE) {
+  const int shape = g_shape.load(std::memory_order_relaxed);
+  if (shape == UCCL_SHAPE_AUTO || shape == UCCL_SHAPE_FLAT) return launch_flat_tile<Op>(a, s);
+  if (shape == UCCL_SHAPE_WAVE) {
     if (a.n_descs >= 65536u) return launch<256, UCCL_WAVE_TILE_SMALL, 64, UCCL_WAVE_UNROLL, Op>(a, s);
     return launch<256, UCCL_WAVE_TILE, 64, UCCL_WAVE_UNROLL, Op>(a, s);
   }
-  if (g_shape == UCCL_SHAPE_GROUP) return launch<256, UCCL_GROUP_TILE, 256, UCCL_GROUP_UNROLL, Op>(a, s);
+  if (shape == UCCL_SHAPE_GROUP) return launch<256, UCCL_GROUP_TILE, 256, UCCL_GROUP_UNROLL, Op>(a, s);
   return UCCL_EINVAL;
 }
 
@@ -1016,6 +1021,11 @@ int apply_common(void* acc, void* out_stage, const void* recv_stage, const uccl_
 // requires and a lone message is launched at once.  Lanes keep records of dependent phases
 // apart: a flush issues lane 0 before lane 1, so a message whose reduce-scatter records go
 // to lane 0 before its allgather records go to lane 1 is always applied in that order.
+// Hand-overs of at most this many records per lane are read from pinned host memory directly.
+#ifndef UCCL_FEED_DIRECT_RECORDS
+#define UCCL_FEED_DIRECT_RECORDS 16384
+#endif
+
 struct FeedSlot {
   uccl_chunk_desc* host[2];
   uccl_chunk_desc* dev[2];
@@ -1062,10 +1072,17 @@ int feed_flush(uccl_feed* f) {
   if (n == 0) return UCCL_OK;
   for (int l = 0; l < 2; ++l) {
     if (sl.count[l] == 0) continue;
-    const hipError_t e = hipMemcpyAsync(sl.dev[l], sl.host[l], sizeof(uccl_chunk_desc) * sl.count[l],
-                                        hipMemcpyHostToDevice, f->stream);
-    if (e != hipSuccess) return launch_failed(e);
-    const int rc = apply_common(f->acc, f->out_stage, f->recv_stage, sl.dev[l], sl.count[l], f->bitmap,
+    // A small batch is read by the kernel straight from the pinned slot (one bus round trip per
+    // workgroup, no copy to enqueue); a large one is copied to device memory first, so that
+    // thousands of workgroups do not each wait on the host bus.
+    const uccl_chunk_desc* records = sl.host[l];
+    if (sl.count[l] > UCCL_FEED_DIRECT_RECORDS) {
+      const hipError_t e = hipMemcpyAsync(sl.dev[l], sl.host[l], sizeof(uccl_chunk_desc) * sl.count[l],
+                                          hipMemcpyHostToDevice, f->stream);
+      if (e != hipSuccess) return launch_failed(e);
+      records = sl.dev[l];
+    }
+    const int rc = apply_common(f->acc, f->out_stage, f->recv_stage, records, sl.count[l], f->bitmap,
                                 f->dtype, f->op[l], true, nullptr, nullptr, f->stream);
     if (rc != UCCL_OK) return rc;
   }
@@ -1339,7 +1356,7 @@ int uccl_time_next_launch(void* start_event, void* stop_event) {
 }
 
 int uccl_set_chunk_hint(uint32_t chunk_bytes) {
-  g_chunk_hint = chunk_bytes;
+  g_chunk_hint.store(chunk_bytes, std::memory_order_relaxed);
   return UCCL_OK;
 }
 
@@ -1347,7 +1364,7 @@ int uccl_set_launch_shape(int shape) {
   if (shape != UCCL_SHAPE_AUTO && shape != UCCL_SHAPE_WAVE && shape != UCCL_SHAPE_GROUP &&
       shape != UCCL_SHAPE_FLAT)
     return UCCL_EINVAL;
-  g_shape = shape;
+  g_shape.store(shape, std::memory_order_relaxed);
   return UCCL_OK;
 }
 
