@@ -34,9 +34,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 # source it was measured on, identified by the hash of the HIP source file.
 MEASURED_TRAFFIC = {
     # (workload, first 16 hex digits of sha256 of csrc/uccl_chunk.hip): bytes per launch
-    ("config2", "35fc59beb69108ec"): 1008009664,
-    ("config3", "35fc59beb69108ec"): 3625073814,
-    ("direct-rs", "35fc59beb69108ec"): 1208232886,
+    ("config2", "99a5c67979113e2e"): 1008012165,
+    ("config3", "99a5c67979113e2e"): 3625076937,
+    ("direct-rs", "99a5c67979113e2e"): 1208234758,
 }
 
 WORKLOADS = {
