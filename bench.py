@@ -656,6 +656,29 @@ def main():
             "value": round(payload * reps / cpu_t / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
             "sample": f"the whole step ({len(calls)} calls, {arrivals} arrivals, {payload} payload bytes) x {reps} repetitions, {cpu_t:.1f} s",
         }
+        # the same definition on all host cores of this machine's share (serial dedup, then the unique
+        # chunks dealt to threads); reported beside the single-core figure, only for plain apply calls
+        if not any(c.get("gather") or c["scatter"] for c in calls):
+            threads = max(1, min(16, os.cpu_count() or 1))
+            reps_t, cpu_tt, same_t = 0, 0.0, True
+            while cpu_tt < 5.0 and reps_t < 64:
+                tacc = w.acc.copy()
+                tout = np.zeros(max(w.out_bytes, 16), dtype=np.uint8)
+                seen = oracle.new_seen(w.n_bits)
+                t0 = time.perf_counter()
+                for c in calls:
+                    oracle.apply_threaded(tacc, tout, w.recv_stage, c["descs"], seen, w.dtype, c["op"], threads)
+                cpu_tt += time.perf_counter() - t0
+                reps_t += 1
+                if reps_t == 1:
+                    same_t = (np.array_equal(tacc.view(np.uint8), exp[0].view(np.uint8)) and
+                              np.array_equal(tout[:w.out_bytes], exp[1]))
+            result["cpu_baseline_threaded"] = {
+                "value": round(payload * reps_t / cpu_tt / 1e9, 3), "unit": "GB/s", "cores": threads,
+                "kind": "oracle, unique chunks dealt to threads after a serial dedup pass",
+                "equals_single_core_result": bool(same_t),
+                "sample": f"the whole step x {reps_t} repetitions, {cpu_tt:.1f} s",
+            }
         same = all(np.array_equal(np.ascontiguousarray(g).view(np.uint8).reshape(-1),
                                   np.ascontiguousarray(e).view(np.uint8).reshape(-1))
                    for g, e in zip(first, exp))

@@ -12,6 +12,7 @@ import numpy as np
 
 _DIR = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_DIR, "chunk_oracle.c")
+_SRC_THREADED = os.path.join(_DIR, "chunk_threaded.c")
 _LIB = os.path.join(_DIR, "libchunk_oracle.so")
 
 # strict IEEE: no fast-math, no FMA contraction, SSE2 scalar arithmetic
@@ -39,10 +40,10 @@ class OraclePrecondition(ValueError):
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (always when force, else when stale)."""
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(
-        os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_DIR, "chunk_oracle.h")))
+        os.path.getmtime(_SRC), os.path.getmtime(_SRC_THREADED), os.path.getmtime(os.path.join(_DIR, "chunk_oracle.h")))
     if force or stale:
         tmp = _LIB + f".tmp{os.getpid()}"
-        subprocess.check_call(["gcc", *CFLAGS, _SRC, "-o", tmp])
+        subprocess.check_call(["gcc", *CFLAGS, "-pthread", _SRC, _SRC_THREADED, "-o", tmp])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -57,6 +58,8 @@ def lib():
         vp, u64, i64 = C.c_void_p, C.c_uint64, C.c_int64
         L.orc_apply.restype = i64
         L.orc_apply.argtypes = [vp, u64, vp, u64, vp, u64, vp, u64, vp, u64, C.c_int, C.c_int]
+        L.orc_apply_threaded.restype = i64
+        L.orc_apply_threaded.argtypes = [vp, u64, vp, u64, vp, u64, vp, u64, vp, u64, C.c_int, C.c_int, C.c_int]
         L.orc_reduce_gather.restype = i64
         L.orc_reduce_gather.argtypes = [vp, u64, vp, u64, vp, u64, vp, u64, vp, u64, C.c_int, C.c_int]
         L.orc_scatter.restype = i64
@@ -119,6 +122,18 @@ def apply(acc, out_stage, recv_stage, descs, seen, dtype, op, check=True) -> int
     if rc < 0:
         raise OraclePrecondition(rc)
     return int(rc)
+
+
+def apply_threaded(acc, out_stage, recv_stage, descs, seen, dtype, op, threads) -> int:
+    """oracle.apply on `threads` cores (the benchmark's multi-core CPU baseline); same result."""
+    d = _descs(descs)
+    rc = lib().orc_apply_threaded(_ptr(acc), acc.nbytes, _ptr(out_stage),
+                                  0 if out_stage is None else out_stage.nbytes, _ptr(recv_stage),
+                                  recv_stage.nbytes, _ptr(d), len(d), _ptr(seen), len(seen),
+                                  int(dtype), int(op), int(threads))
+    if rc < 0:
+        raise OraclePrecondition(rc)
+    return rc
 
 
 def reduce_gather(acc, out_stage, recv_stage, descs, seen, dtype, op) -> int:

@@ -89,6 +89,14 @@ int64_t orc_check_call(const void* recv_stage, uint64_t recv_bytes, const orc_de
 /* Pack seen[] into 32-bit words, bit (s & 31) of word (s >> 5) = seen[s]. */
 void orc_pack_bitmap(const uint8_t* seen, uint64_t n_bits, uint32_t* words);
 
+/* The same call on n_threads cores (chunk_threaded.c): serial dedup in arrival order, then the
+ * chosen records dealt to threads, each applied through orc_apply().  Equals orc_apply() bit
+ * for bit when the call's preconditions hold; returns the number applied or a negative code. */
+int64_t orc_apply_threaded(void* acc, uint64_t acc_bytes, void* out_stage, uint64_t out_bytes,
+                           const void* recv_stage, uint64_t recv_bytes, const orc_desc* descs,
+                           uint64_t n_descs, uint8_t* seen, uint64_t n_bits, int dtype, int op,
+                           int n_threads);
+
 /* Receiver feedback read off a packed bitmap (Section 3.2 seq/ack, Section 4.3 selective
  * retransmission): cum_ack = first clear bit (n_bits if none); n_applied = set bits;
  * n_ranges = maximal runs of set bits starting above cum_ack, the first max_ranges of them

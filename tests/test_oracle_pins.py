@@ -539,6 +539,30 @@ def test_message_status_against_numpy(bits_per_slot, n_slots):
         assert np.array_equal(words, np.packbits(kept.reshape(-1), bitorder="little").view(np.uint32))
 
 
+@pytest.mark.parametrize("dtype,op", [(F32, SUM), (BF16, SUM), (BF16, MAX), (F32, COPY)])
+@pytest.mark.parametrize("threads", [1, 3, 16])
+def test_threaded_baseline_equals_the_definition(dtype, op, threads):
+    """The multi-core CPU baseline is the definition on more cores: same bytes, same bitmap, for a
+    reordered stream with duplicates, relayed chunks and a call cut in two."""
+    kw = dict(R=4, M=4 * 16 * 256, C=256, dtype=dtype, paths=5, window=9, dup=0.3, dist="uniform")
+    for relay in (False, True):
+        w = wl.ring_share("thr", 11, relay=relay, **kw)
+        a1, o1, s1 = w.acc.copy(), np.zeros(w.out_bytes, np.uint8), oracle.new_seen(w.n_bits)
+        a2, o2, s2 = w.acc.copy(), np.zeros(w.out_bytes, np.uint8), oracle.new_seen(w.n_bits)
+        for ph in w.phases:
+            this_op = COPY if ph.op == COPY else op
+            n1 = oracle.apply(a1, o1, w.recv_stage, ph.descs, s1, dtype, this_op)
+            cut = len(ph.descs) // 3
+            n2 = oracle.apply_threaded(a2, o2, w.recv_stage, ph.descs[:cut], s2, dtype, this_op, threads)
+            n2 += oracle.apply_threaded(a2, o2, w.recv_stage, ph.descs[cut:], s2, dtype, this_op, threads)
+            assert n1 == n2 == ph.n_unique
+        assert np.array_equal(a1.view(np.uint8), a2.view(np.uint8)) and np.array_equal(o1, o2) and np.array_equal(s1, s2)
+    d = w.phases[0].descs.copy()
+    d["seq"][0] = w.n_bits + 5
+    with pytest.raises(oracle.OraclePrecondition):
+        oracle.apply_threaded(a2, o2, w.recv_stage, d, oracle.new_seen(w.n_bits), dtype, op, threads)
+
+
 # --- P7: a chunk that never arrives ------------------------------------------------
 
 def test_missing_chunk_leaves_hole_and_clear_bit():
