@@ -43,7 +43,7 @@ typedef struct uccl_chunk_desc {
   uint64_t src_off; /* byte offset of this arrival's slot in recv_stage; multiple of 16 */
   uint64_t dst_off; /* byte offset in acc (apply) / dst (scatter); multiple of 16 */
   uint64_t out_off; /* byte offset in out_stage, multiple of 16; UCCL_NO_FORWARD = do not forward */
-  uint32_t len;     /* payload bytes; may be 0; a multiple of the element size (apply) */
+  uint32_t len;     /* payload bytes, 0 .. 2^32 - 1; a multiple of the element size (apply) */
   uint32_t seq;     /* logical chunk id = bit index in dedup_bitmap (the role of the chunk
                        sequence number of the control header, Section 3.1) */
 } uccl_chunk_desc;
@@ -235,7 +235,7 @@ int uccl_dedup_report(const uint32_t* dedup_bitmap, uint64_t n_bits, void* repor
  * so that the slot's message id can be reused; only then does the call write the bitmap.
  * dedup_bitmap, n_chunks, status: DEVICE memory (status may be pinned host memory), 4-byte
  * aligned, status 16-byte aligned.  bits_per_slot: multiple of 32 in 32..2048 (UCCL_EINVAL
- * otherwise).  n_slots == 0 is a no-op.  Stream ordered.
+ * otherwise).  n_slots == 0 is a no-op; more than 2^24 slots is UCCL_EINVAL.  Stream ordered.
  */
 typedef struct uccl_msg_status {
   uint32_t cum_ack;

@@ -390,7 +390,8 @@ __device__ __forceinline__ void dedup_tile(const Args& g, Tile<T>& s, uint32_t t
   if (tid == 0) s.count = count;
   if (kUnitVecs > 0) {
     // a partial last vector (len % 16 != 0) counts as a vector of its unit
-    const uint32_t units = win ? (((len + 15u) >> 4) + kUnitVecs - 1u) / kUnitVecs : 0u;
+    const uint32_t vecs = (len >> 4) + ((len & 15u) != 0u ? 1u : 0u);  // no overflow for len up to 2^32 - 1
+    const uint32_t units = win ? (vecs + kUnitVecs - 1u) / kUnitVecs : 0u;
     uint32_t incl = units;
 #pragma unroll
     for (uint32_t d = 1; d < 64; d <<= 1) {
@@ -598,7 +599,8 @@ __global__ void __launch_bounds__(NT) chunk_gather_kernel(const GatherArgs g) {
       for (uint32_t j = 0; j < n_src; ++j) s.src[pos][j] = d->src_off[j];
     }
     if (tid == 0) s.count = count;
-    const uint32_t units = win ? (((len + 15u) >> 4) + kUnit - 1u) / kUnit : 0u;
+    const uint32_t vecs = (len >> 4) + ((len & 15u) != 0u ? 1u : 0u);  // no overflow for len up to 2^32 - 1
+    const uint32_t units = win ? (vecs + kUnit - 1u) / kUnit : 0u;
     uint32_t incl = units;
 #pragma unroll
     for (uint32_t dlt = 1; dlt < 64; dlt <<= 1) {
@@ -1341,6 +1343,7 @@ int uccl_message_status(uint32_t* dedup_bitmap, const uint32_t* n_chunks, uint32
                         uint32_t bits_per_slot, uccl_msg_status* status, int recycle, void* stream) {
   if (bits_per_slot < 32 || bits_per_slot > 2048 || (bits_per_slot & 31u)) return UCCL_EINVAL;
   if (n_slots == 0) return UCCL_OK;
+  if (n_slots > (1u << 24)) return UCCL_EINVAL;
   if (!dedup_bitmap || !n_chunks || !status) return UCCL_EINVAL;
   if (misaligned(dedup_bitmap, 4) || misaligned(n_chunks, 4) || misaligned(status, 16)) return UCCL_EALIGN;
   const uint32_t grid = (n_slots + 3) / 4;  // one wavefront per slot, four per workgroup

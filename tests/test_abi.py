@@ -84,6 +84,7 @@ def test_host_side_error_codes_enqueue_nothing():
     assert ms(M, None, 4, 256, A, 0, None) == pkg.UCCL_EINVAL and ms(M, M, 4, 256, None, 0, None) == pkg.UCCL_EINVAL
     assert ms(M + 2, M, 4, 256, A, 0, None) == pkg.UCCL_EALIGN and ms(M, M, 4, 256, A + 8, 0, None) == pkg.UCCL_EALIGN
     assert ms(None, None, 0, 256, None, 0, None) == pkg.UCCL_OK
+    assert ms(M, M, (1 << 24) + 1, 256, A, 0, None) == pkg.UCCL_EINVAL
     h = C.c_void_p()
     fc = lib.uccl_feed_create
     assert fc(None, A, None, B, M, 0, 0, 3, 64, 4, None) == pkg.UCCL_EINVAL

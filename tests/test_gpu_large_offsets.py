@@ -134,3 +134,29 @@ def test_scatter_and_gather_beyond_4gib(gpu_lib):
     assert np.array_equal(got.reshape(-1), eacc.view(np.uint8)) and not bool(dst_big.any())
     del dst_big, recv
     torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("length", [0xFFFFFFF0, 0xFFFFFFFC])
+def test_one_record_of_almost_4gib(gpu_lib, length):
+    """The largest chunk a record can name (len is 32 bits wide): one workgroup walks two million
+    units.  Too large for the host oracle to be worth it; the expected value is the device
+    library's own IEEE fp32 add, which equals one correctly rounded add per element."""
+    n = 1 << 30                                     # fp32 elements in 4 GiB
+    g = torch.Generator(device="cuda").manual_seed(5)
+    acc = torch.empty(n, dtype=torch.float32, device="cuda").uniform_(-1, 1, generator=g)
+    recv = torch.empty(n, dtype=torch.float32, device="cuda").uniform_(-1, 1, generator=g)
+    out = torch.zeros(n, dtype=torch.float32, device="cuda")
+    ref = acc + recv
+    k = length // 4
+    ref[k:] = acc[k:]                               # beyond the chunk the accumulator is untouched
+    d = np.zeros(2, dtype=DESC)
+    d[0] = (0, 0, 0, length, 0)
+    d[1] = (0, 0, 0, length, 0)                     # and its retransmitted copy
+    bitmap = torch.zeros(1, dtype=torch.int32, device="cuda")
+    gpu_lib.uccl_chunk_apply(acc, out, recv, to_dev(d), 2, bitmap, F32, SUM)
+    torch.cuda.synchronize()
+    assert int(bitmap.item()) == 1
+    assert torch.equal(acc.view(torch.int32), ref.view(torch.int32))
+    assert torch.equal(out[:k].view(torch.int32), ref[:k].view(torch.int32)) and not bool(out[k:].any())
+    del acc, recv, out, ref
+    torch.cuda.empty_cache()
