@@ -34,9 +34,9 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 # source it was measured on, identified by the hash of the HIP source file.
 MEASURED_TRAFFIC = {
     # (workload, first 16 hex digits of sha256 of csrc/uccl_chunk.hip): bytes per launch
-    ("config2", "99a5c67979113e2e"): 1008012165,
-    ("config3", "99a5c67979113e2e"): 3625076937,
-    ("direct-rs", "99a5c67979113e2e"): 1208234758,
+    ("config2", "bb6450e4470f2487"): 1008005077,
+    ("config3", "bb6450e4470f2487"): 3625075668,
+    ("direct-rs", "bb6450e4470f2487"): 1208243402,
 }
 
 WORKLOADS = {
