@@ -75,9 +75,11 @@ def call_stats(descs, op):
     return len(first), int(ln.sum()), algo
 
 
-def two_pass_calls(w, chunk):
+def two_pass_calls(w, chunk, group=1):
     """The paper's literal form (Section 3.1): first a scattered memcpy of the arrivals into an
     in-order transport buffer (dedup + place), then the reduction from the transport buffer.
+    With group > 1 the arrivals are packets of `chunk` bytes and the reduction reads the
+    transport buffer in pieces of `group` packets (the collective's own chunk size).
     Returns the call list and the transport buffer size."""
     from synth.layout import DESC, COPY
     calls, seq0, most = [], 0, 0
@@ -88,10 +90,17 @@ def two_pass_calls(w, chunk):
         u, pay, algo = call_stats(d1, COPY)
         calls.append(dict(name=ph.name + ": scatter to transport buffer", op=COPY, descs=d1, n_unique=0,
                           payload_bytes=0, algo_bytes=algo, scatter=True, dst="transport", src="recv", bm="bitmap"))
-        d2 = np.zeros(len(lg), dtype=DESC)
-        d2["src_off"] = np.arange(len(lg), dtype=np.uint64) * np.uint64(chunk)
-        d2["dst_off"], d2["out_off"], d2["len"] = lg["dst_off"], lg["out_off"], lg["len"]
-        d2["seq"] = lg["seq"]
+        assert len(lg) % group == 0 and np.all(lg["len"] == chunk), "whole groups of full packets"
+        head = lg[::group]
+        d2 = np.zeros(len(head), dtype=DESC)
+        d2["src_off"] = np.arange(len(head), dtype=np.uint64) * np.uint64(chunk * group)
+        d2["dst_off"], d2["out_off"], d2["len"] = head["dst_off"], head["out_off"], chunk * group
+        d2["seq"] = head["seq"]
+        if group > 1:  # the packets of a group are consecutive in the accumulator and in the staging buffer
+            nxt = lg[1::group]
+            assert np.all(nxt["dst_off"] == head["dst_off"] + np.uint64(chunk))
+            fwd = head["out_off"] != np.uint64(0xFFFFFFFFFFFFFFFF)
+            assert np.all(nxt["out_off"][fwd] == head["out_off"][fwd] + np.uint64(chunk))
         u, pay, algo = call_stats(d2, ph.op)
         calls.append(dict(name=ph.name + ": reduce from transport buffer", op=ph.op, descs=d2, n_unique=u,
                           payload_bytes=pay, algo_bytes=algo, scatter=False, dst="acc", src="transport", bm="bitmap2"))
@@ -100,17 +109,22 @@ def two_pass_calls(w, chunk):
     return calls, most * chunk
 
 
-def build_job(name, seed, n_msgs, relay=False, per_call=128):
+def build_job(name, seed, n_msgs, relay=False, per_call=128, packet_bytes=0):
     """Returns (workload, calls, chunk_bytes) with calls = list of dicts
     {name, op, descs (numpy), n_unique, payload_bytes, algo_bytes, scatter}."""
     from synth import workloads as wl
     from synth.layout import SUM, COPY
     if name in ("config1", "config2", "config3"):
-        w = getattr(wl, name)(seed=seed, relay=relay)
+        chunk = {"config1": 64 << 10, "config2": 32 << 10, "config3": 128 << 10}[name]
+        kw = {}
+        if packet_bytes:  # arrivals are MTU-sized packets; the reorder window keeps its size in bytes
+            window = {"config1": None, "config2": 1024, "config3": 256}[name]
+            kw = dict(C=packet_bytes, window=None if window is None else window * chunk // packet_bytes)
+        w = getattr(wl, name)(seed=seed, relay=relay, **kw)
         calls = [dict(name=ph.name, op=ph.op, descs=ph.descs, n_unique=ph.n_unique,
                       payload_bytes=ph.payload_bytes, algo_bytes=ph.algo_bytes, scatter=False)
                  for ph in w.phases]
-        return w, calls, {"config1": 64 << 10, "config2": 32 << 10, "config3": 128 << 10}[name]
+        return w, calls, packet_bytes or chunk
     if name == "direct-rs":
         w = wl.direct_reduce_scatter("direct-reduce-scatter-1GiB-f32", seed, R=8, M=1 << 30, C=128 << 10, dtype=0,
                                      paths=64, dup=0.005, dist="uniform")
@@ -354,6 +368,10 @@ def main():
     ap.add_argument("--chunk-hint", type=int, default=None, help="override the chunk-size hint (bytes)")
     ap.add_argument("--records-per-call", type=int, default=0,
                     help="cut every phase into calls of this many records, queued back to back (0 = one call per phase)")
+    ap.add_argument("--packet-bytes", type=int, default=0,
+                    help="config1-3: arrivals are packets of this many bytes instead of whole chunks (Section 3.1, "
+                         "unreliable datagrams: one MTU-sized payload per arrival); with --two-pass the reduction "
+                         "reads the transport buffer at the configuration's chunk size")
     ap.add_argument("--relay", action="store_true",
                     help="ring workloads: flag intermediate reduce-scatter steps forward-only (their partial "
                          "sums are not written back to the accumulator: 3 instead of 4 bytes per payload byte)")
@@ -383,14 +401,16 @@ def main():
     if args.workload == "config5-feed":
         return bench_feed(args, pkg, torch)
     t0 = time.time()
-    w, calls, chunk_bytes = build_job(args.workload, args.seed, args.messages, args.relay, args.messages_per_call)
+    w, calls, chunk_bytes = build_job(args.workload, args.seed, args.messages, args.relay, args.messages_per_call,
+                                      args.packet_bytes)
+    collective_chunk = {"config1": 64 << 10, "config2": 32 << 10, "config3": 128 << 10}.get(args.workload, chunk_bytes)
     if args.chunk_hint is not None:
         chunk_bytes = args.chunk_hint
     if not args.no_chunk_hint:
         pkg.uccl_set_chunk_hint(chunk_bytes)
     transport_bytes = 0
     if args.two_pass:
-        calls, transport_bytes = two_pass_calls(w, chunk_bytes)
+        calls, transport_bytes = two_pass_calls(w, chunk_bytes, collective_chunk // chunk_bytes if args.packet_bytes else 1)
         args.no_cpu_baseline = True  # the oracle defines the fused result; parity of this mode is checked below
     print(f"[bench] built {w.name} in {time.time() - t0:.1f}s: {w.note}", file=sys.stderr, flush=True)
 
@@ -585,7 +605,7 @@ def main():
                    "unique_chunks": unique, "arrivals": arrivals, "payload_bytes": payload,
                    "algorithmic_bytes": algo, "launch_shape": args.shape,
                    "chunk_hint": 0 if args.no_chunk_hint else chunk_bytes, "buffer_sets": len(sets),
-                   "forward_only_intermediate_steps": bool(args.relay), "two_pass": bool(args.two_pass),
+                   "forward_only_intermediate_steps": bool(args.relay), "two_pass": bool(args.two_pass), "packet_bytes": args.packet_bytes or None,
                    "calls_per_step": 1 + sum(-(-n // (args.records_per_call or max(n, 1))) for n in counts),
                    "records_per_call": args.records_per_call or None, "streams": args.streams, "cache": cache_note},
         "chunks_per_s": round(unique / per_step, 1),
