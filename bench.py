@@ -37,6 +37,8 @@ MEASURED_TRAFFIC = {
     ("config2", "bb6450e4470f2487"): 1008005077,
     ("config3", "bb6450e4470f2487"): 3625075668,
     ("direct-rs", "bb6450e4470f2487"): 1208243402,
+    ("config1", "bb6450e4470f2487"): 14752531,
+    ("config4", "bb6450e4470f2487"): 107504410,
 }
 
 WORKLOADS = {
