@@ -15,7 +15,9 @@ A retransmission of a chunk that was only delayed reaches the receiver as a DUPL
 that, and the interleaving of paths, is what the GPU path has to absorb.
 
 The eight extension points the paper lists (Appendix A) appear as overridable methods with
-the paper's names.  Only integer / float bookkeeping of the transport lives here; payload
+the paper's names; SwiftWindow (delay-based window) and ReceiverCredit (credits granted by the
+receiver, in the manner of EQDS) are two extensions written against them, as the paper's own
+case studies are.  Only integer / float bookkeeping of the transport lives here; payload
 bytes are never touched.
 """
 import heapq
@@ -69,8 +71,11 @@ class ControlPath:
         self.srtt[path] += 0.125 * (rtt - self.srtt[path])
         self.cwnd = min(self.max_cwnd, self.cwnd + 1.0 / max(self.cwnd, 1.0))
 
-    def onRxCredit(self, credit):          # receiver-driven schemes would grant credit here
+    def onRxCredit(self, credit):          # sender: a credit from the receiver arrived
         pass
+
+    def creditFor(self, seq, now):         # receiver side of a receiver-driven scheme: credit granted per arrival
+        return 0
 
     # ---- the event loop --------------------------------------------------------------------
     def _send(self, now, seq, copy):
@@ -120,6 +125,9 @@ class ControlPath:
                 # the ACK carries the receiver's picture at this moment (cumulative + selective ranges)
                 heapq.heappush(self.events, (now + self.delay[p], self.tick(), "ack", seq, copy, p, sent_at,
                                              received.copy()))
+                grant = self.creditFor(seq, now)
+                if grant:
+                    heapq.heappush(self.events, (now + self.delay[p], self.tick(), "credit", grant, 0, p, now, None))
             elif kind == "ack":
                 self.onRxACK(p, now - sent_at)
                 acked |= picture
@@ -135,6 +143,9 @@ class ControlPath:
                             self.onTxRtxChunk(h, "fast")
                             self._send(now, int(h), self.sent_copy.get(int(h), 0) + 1)
                 pump(now)
+            elif kind == "credit":
+                self.onRxCredit(seq)               # the amount travels in the seq field of the event
+                pump(now)
             elif kind == "rto":
                 if not acked[seq] and self.sent_copy.get(seq) == copy:
                     self.onTxRtxChunk(seq, "timeout")
@@ -145,9 +156,64 @@ class ControlPath:
         return a[:, 0].astype(np.int64), a[:, 1].astype(np.int64), a[:, 2].astype(np.int64), a[:, 3]
 
 
-def simulated_arrivals(seed, n, **kw):
+class SwiftWindow(ControlPath):
+    """Delay-based window in the manner of Swift (Section 4: one of the paper's two sender-driven
+    schemes): grow additively while the measured RTT is under a target, shrink in proportion to
+    the excess otherwise, at most once per RTT; a retransmission shrinks it like any other."""
+
+    def __init__(self, *a, target_margin_us=12.0, beta=0.8, **kw):
+        super().__init__(*a, **kw)
+        self.target = float(np.min(self.srtt)) + target_margin_us
+        self.beta, self.acks, self.cut_at = beta, 0, -10**9
+
+    def onRxACK(self, path, rtt):
+        self.srtt[path] += 0.125 * (rtt - self.srtt[path])
+        self.acks += 1                     # the hook gets no clock: cuts are spaced by counting acknowledgements
+        if rtt <= self.target:
+            self.cwnd = min(self.max_cwnd, self.cwnd + 1.0 / max(self.cwnd, 1.0))
+        elif self.acks - self.cut_at >= max(int(self.cwnd), 1):                        # about one RTT of acks
+            self.cut_at = self.acks
+            self.cwnd = max(2.0, self.cwnd * max(1.0 - self.beta * (rtt - self.target) / rtt, 0.5))
+
+
+class ReceiverCredit(ControlPath):
+    """Receiver-driven scheme in the manner of EQDS (Section 4.2, Appendix B): the sender may use
+    an initial allowance without asking, after which every chunk leaves against a credit; the
+    receiver grants one credit per arrival, so the sender is clocked at the pace the receiver
+    drains.  Retransmissions go out without credit (the request-to-send exchange is not modelled)."""
+
+    def __init__(self, *a, **kw):
+        super().__init__(*a, **kw)
+        self.credit = float(self.cwnd)     # the initial allowance
+        self.credits_seen = 0
+
+    def onPacingChunk(self, now):
+        if self.credit >= 1.0 and len(self.inflight) < self.max_cwnd:
+            self.credit -= 1.0
+            return True
+        return False
+
+    def creditFor(self, seq, now):
+        return 1
+
+    def onRxCredit(self, credit):
+        self.credit += credit
+        self.credits_seen += credit
+
+    def onRxACK(self, path, rtt):          # no window to adapt; keep the RTT estimate for path choice
+        self.srtt[path] += 0.125 * (rtt - self.srtt[path])
+
+    def onTxRtxChunk(self, seq, why):
+        self.stats["retransmitted"] += 1
+        self.stats[why] += 1
+
+
+SCHEMES = {"window": ControlPath, "swift": SwiftWindow, "credit": ReceiverCredit}
+
+
+def simulated_arrivals(seed, n, scheme="window", **kw):
     """Arrival order of chunks 0..n-1 under the control-path model; same return convention
     as synth.arrivals.gen_arrivals (seq, copy, path), plus the model for its statistics."""
-    cp = ControlPath(seed, n, **kw)
+    cp = SCHEMES[scheme](seed, n, **kw)
     seq, copy, path, _ = cp.run()
     return seq, copy, path, cp

@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 from synth import workloads as wl
-from synth.control_sim import ControlPath, simulated_arrivals
+from synth.control_sim import ControlPath, ReceiverCredit, SwiftWindow, simulated_arrivals
 from synth.layout import BF16, SUM
 
 
@@ -99,12 +99,36 @@ def test_hooks_are_called():
                                               "onRxRtxChunk", "onRxACK")), calls
 
 
-def test_data_path_result_does_not_depend_on_the_transport():
+@pytest.mark.parametrize("scheme", ["swift", "credit"])
+@pytest.mark.parametrize("loss", [0.0, 1 / 64])
+def test_schemes_written_against_the_extension_points(scheme, loss):
+    """A delay-based window and a receiver-credit scheme (Section 4), each a subclass that only
+    overrides extension points: every chunk is delivered, the books balance, and each scheme
+    shows its own signature."""
+    n = 3000
+    seq, copy, path, cp = simulated_arrivals(5, n, scheme=scheme, paths=32, loss=loss, jitter_us=8.0)
+    assert np.array_equal(np.unique(seq), np.arange(n))
+    assert len(seq) == cp.stats["sent"] - cp.stats["lost"]
+    assert cp.stats["sent"] == n + cp.stats["retransmitted"]
+    assert cp.stats["duplicates"] == len(seq) - n
+    if scheme == "credit":
+        assert isinstance(cp, ReceiverCredit)
+        assert cp.credits_seen == len(seq), "one credit per arrival came back to the sender"
+        assert cp.credit >= 0
+    else:
+        assert isinstance(cp, SwiftWindow)
+        # the delay target keeps the window, and with it the queueing delay, below the loss-based scheme's
+        base = simulated_arrivals(5, n, scheme="window", paths=32, loss=loss, jitter_us=8.0)[3]
+        assert cp.stats["retransmitted"] <= base.stats["retransmitted"]
+
+
+@pytest.mark.parametrize("scheme", ["window", "swift", "credit"])
+def test_data_path_result_does_not_depend_on_the_transport(scheme):
     """The same logical stream delivered by the random-spray model and by the control-path
-    model (with loss and retransmission) gives byte-identical results."""
+    model (with loss and retransmission, under each scheme) gives byte-identical results."""
     kw = dict(R=4, M=4 * 40 * 512, C=512, dtype=BF16, paths=16, window=32, dup=0.05, dist="normal")
     base = wl.ring_share("spray", 11, **kw)
-    arr = [simulated_arrivals(11, len(lg), paths=16, loss=0.03, jitter_us=15.0, rto_us=80.0, stream=i)[0]
+    arr = [simulated_arrivals(11, len(lg), scheme=scheme, paths=16, loss=0.03, jitter_us=15.0, rto_us=80.0, stream=i)[0]
            for i, lg in enumerate(base.extra["logical"])]
     sim = wl.ring_share("sim", 11, arrivals=arr, **kw)
     assert any(len(a) > len(lg) for a, lg in zip(arr, base.extra["logical"])), "the model must produce duplicates"

@@ -627,13 +627,14 @@ def test_closed_loop_ring_matches_textbook(gpu_lib, dtype, R, n, C):
 
 
 @pytest.mark.parametrize("shape", [0, 1])
-def test_stream_from_control_path_model(gpu_lib, shape):
-    """Arrival order from the discrete-event control-path model (power-of-two path choice,
-    windowing, loss, fast and timeout retransmission) instead of the random-spray model."""
+@pytest.mark.parametrize("scheme", ["window", "swift", "credit"])
+def test_stream_from_control_path_model(gpu_lib, shape, scheme):
+    """Arrival order from the discrete-event control-path model (power-of-two path choice, loss, fast
+    and timeout retransmission; window-, delay- or credit-based sending) instead of the random-spray model."""
     from synth.control_sim import simulated_arrivals
     kw = dict(R=16, M=16 << 20, C=32 << 10, dtype=BF16, paths=256, window=1024, dup=0.02, dist="normal")
     lg = wl.ring_logical(16, 16 << 20, 32 << 10)
-    arr = [simulated_arrivals(21, len(l), paths=256, loss=1 / 64, jitter_us=12.0, rto_us=90.0, stream=i)[0]
+    arr = [simulated_arrivals(21, len(l), scheme=scheme, paths=256, loss=1 / 64, jitter_us=12.0, rto_us=90.0, stream=i)[0]
            for i, l in enumerate(lg[:2])]
     w = wl.ring_share("sim", 21, arrivals=arr, **kw)
     assert sum(len(a) for a in arr) > w.n_bits, "the model produced duplicates"
