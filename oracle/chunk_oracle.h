@@ -16,7 +16,9 @@
  *  - Section 3.2 (handling out-of-order packets): sequence numbers identify
  *    chunks, retransmission creates duplicates, reorder buffers live in GPU memory.
  *
- * Parity status: every function is pinned by tests/test_oracle_pins.py except
+ * Parity status: every function is pinned by tests/test_oracle_pins.py (multi-source fold:
+ * tests/test_gather_reduce.py; whole definition against a brute-force model:
+ * tests/test_oracle_bruteforce.py) except
  *  - MAX/MIN on NaN or mixed-sign zeros, and which copy of a duplicated sequence
  *    number supplies the bytes: the paper fixes neither ("parity unpinned"; the
  *    behaviour below is a definition made here, see the comments at each).
