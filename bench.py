@@ -31,14 +31,14 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 
 # HBM bytes per launch of the dominant kernel of config2 from rocprofv3 counters
 # (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, see profiles/): valid only for the kernel
-# source it was measured on, identified by the hash of the HIP source file.
+# source it was measured on, identified by the hash of the HIP source files.
 MEASURED_TRAFFIC = {
-    # (workload, first 16 hex digits of sha256 of csrc/uccl_chunk.hip): bytes per launch
-    ("config2", "bb6450e4470f2487"): 1008005077,
-    ("config3", "bb6450e4470f2487"): 3625075668,
-    ("direct-rs", "bb6450e4470f2487"): 1208243402,
-    ("config1", "bb6450e4470f2487"): 14752531,
-    ("config4", "bb6450e4470f2487"): 107504410,
+    # (workload, source_hash() of the files under csrc/): bytes per launch
+    ("config2", "8426488e76ddd234"): 1008010977,
+    ("config3", "8426488e76ddd234"): 3625079117,
+    ("direct-rs", "8426488e76ddd234"): 1208243707,
+    ("config1", "8426488e76ddd234"): 14752641,
+    ("config4", "8426488e76ddd234"): 107500355,
 }
 
 WORKLOADS = {
@@ -58,8 +58,14 @@ WORKLOADS = {
 
 
 def source_hash():
-    with open(os.path.join(ROOT, "paper_2504_17307_amd", "csrc", "uccl_chunk.hip"), "rb") as f:
-        return hashlib.sha256(f.read()).hexdigest()[:16]
+    """First 16 hex digits of sha256 over the kernel sources (every file under csrc/, by name order)."""
+    d = os.path.join(ROOT, "paper_2504_17307_amd", "csrc")
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".hpp")):
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(name.encode() + b"\0" + f.read())
+    return h.hexdigest()[:16]
 
 
 def call_stats(descs, op):

@@ -102,8 +102,8 @@ def load(path: str = None):
         from .build import build
         build()
     elif path is None:
-        src = os.path.join(_PKG, "csrc", "uccl_chunk.hip")
-        if max(os.path.getmtime(src), os.path.getmtime(HEADER_PATH)) > os.path.getmtime(p):
+        from .build import sources
+        if max(os.path.getmtime(f) for f in sources()) > os.path.getmtime(p):
             raise RuntimeError(f"{p} is older than its sources: rebuild (python -m paper_2504_17307_amd.build)")
     lib = C.CDLL(p)
     for name, (res, args) in _SIGNATURES.items():

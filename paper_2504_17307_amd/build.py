@@ -5,7 +5,8 @@ import sys
 
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
-SRC = os.path.join(PKG, "csrc", "uccl_chunk.hip")
+CSRC = os.path.join(PKG, "csrc")
+SRC = os.path.join(CSRC, "uccl_chunk.hip")  # the one translation unit; it includes the .hpp files beside it
 INC = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libuccl_chunk.so")
 
@@ -18,10 +19,16 @@ HIPCC_FLAGS = [
 ]
 
 
+def sources():
+    """Every file the library is built from (kernel sources and the public header)."""
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".hip", ".hpp")))
+    return files + [os.path.join(INC, "uccl_chunk.h")]
+
+
 def build(extra_flags=(), out=LIB, verbose=False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = out + f".tmp{os.getpid()}"
-    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, f"-I{INC}", SRC, "-o", tmp]
+    cmd = [hipcc, *HIPCC_FLAGS, *extra_flags, f"-I{INC}", f"-I{CSRC}", SRC, "-o", tmp]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)

@@ -33,816 +33,11 @@
 
 #include "uccl_chunk.h"
 
-// Tunable compile-time shape constants (defaults chosen by measurement on MI355X).
-#ifndef UCCL_WAVE_TILE
-#define UCCL_WAVE_TILE 4      // records per 256-thread workgroup, one wavefront per chunk
-#endif
-#ifndef UCCL_WAVE_UNROLL
-#define UCCL_WAVE_UNROLL 4
-#endif
-#ifndef UCCL_WAVE_TILE_SMALL
-#define UCCL_WAVE_TILE_SMALL 16  // same shape, used when a call carries very many records
-#endif
-#ifndef UCCL_GROUP_TILE
-#define UCCL_GROUP_TILE 1     // records per workgroup, 256 threads per chunk
-#endif
-#ifndef UCCL_GROUP_UNROLL
-#define UCCL_GROUP_UNROLL 4
-#endif
-#ifndef UCCL_GATHER_UNROLL
-#define UCCL_GATHER_UNROLL 2  // multi-sender reduce: vectors per lane per unit
-#endif
-#ifndef UCCL_GATHER_BATCH
-#define UCCL_GATHER_BATCH 4   // and how many sources are loaded before the folds start
-#endif
-#ifndef UCCL_FLAT_THREADS
-#define UCCL_FLAT_THREADS 1024  // workgroup size of the flat shape
-#endif
-#ifndef UCCL_FLAT_UNROLL
-#define UCCL_FLAT_UNROLL 2    // vectors per lane per unit: a unit is 64*U*16 bytes per stream
-#endif
-// Cache policy of the four streams, one 4-bit mask per kind of chunk (measured on
-// MI355X with buffers too large to stay cache resident).  Bit 3: non-temporal load of the
-// arrival slot; bit 2: non-temporal store of the staging copy; bit 1: non-temporal load
-// of the accumulator; bit 0: non-temporal store of the accumulator.
-#ifndef UCCL_POLICY_REDUCE_FWD
-#define UCCL_POLICY_REDUCE_FWD 0xD   // slot read once, staging written once, acc line dropped after its write
-#endif
-#ifndef UCCL_POLICY_REDUCE_KEEP
-#define UCCL_POLICY_REDUCE_KEEP 0x9
-#endif
-#ifndef UCCL_POLICY_COPY_FWD
-#define UCCL_POLICY_COPY_FWD 0xC
-#endif
-#ifndef UCCL_POLICY_REDUCE_RELAY
-#define UCCL_POLICY_REDUCE_RELAY 0xE  // forward-only: the accumulator is read once and not written
-#endif
-#ifndef UCCL_POLICY_COPY_RELAY
-#define UCCL_POLICY_COPY_RELAY 0xC
-#endif
-#ifndef UCCL_POLICY_COPY_KEEP
-#define UCCL_POLICY_COPY_KEEP 0x9
-#endif
+#include "uccl_elements.hpp"
+#include "uccl_data_kernels.hpp"
+#include "uccl_feedback_kernels.hpp"
 
 namespace {
-
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-template <bool NT>
-__device__ __forceinline__ u32x4 load16(const u32x4* p) {
-  if constexpr (NT) return __builtin_nontemporal_load(p);
-  else return *p;
-}
-template <bool NT>
-__device__ __forceinline__ void store16(u32x4* p, u32x4 v) {
-  if constexpr (NT) __builtin_nontemporal_store(v, p);
-  else *p = v;
-}
-
-struct Extents {
-  uint64_t acc_bytes, out_bytes, recv_bytes, n_bits;
-};
-
-struct Args {
-  char* acc;
-  char* out;
-  const char* recv;
-  const uccl_chunk_desc* descs;
-  uint32_t* bitmap;
-  uint32_t* rejected;
-  Extents ext;
-  const uint32_t* n_ptr;  // optional: the record count is read from here (capped by n_descs)
-  uint32_t n_descs;
-  uint32_t allow_forward;
-};
-
-__device__ __forceinline__ float as_f32(uint32_t u) { return __uint_as_float(u); }
-__device__ __forceinline__ uint32_t as_u32(float f) { return __float_as_uint(f); }
-
-// binary32 -> bf16 bits, round to nearest even; a NaN keeps its top bits and is quieted.
-__device__ __forceinline__ uint32_t round_bf16(float s) {
-  const uint32_t u = as_u32(s);
-  uint32_t h = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-  if ((u & 0x7FFFFFFFu) > 0x7F800000u) h = (u >> 16) | 0x0040u;
-  return h;
-}
-
-// Element operations.  word() combines one 32-bit word (one fp32 / int32, or two 16-bit
-// elements side by side); half() one 16-bit element (tails).  a = tensor-buffer value,
-// r = received value.  SUM and PROD compute in binary32 and round once to the storage
-// type; MAX and MIN compare the (widened) values strictly and select one of the two
-// inputs unchanged, the accumulator's on a tie or an unordered pair.
-enum Kind { kSum = 0, kMax = 1, kMin = 2, kProd = 4 };
-
-template <int K>
-__device__ __forceinline__ float arith(float a, float r) {
-  return K == kSum ? a + r : a * r;
-}
-template <int K>
-__device__ __forceinline__ bool takes_received(float a, float r) {
-  return K == kMax ? r > a : r < a;
-}
-
-struct WidenBF16 {
-  static __device__ __forceinline__ float widen(uint32_t h) { return as_f32(h << 16); }
-  static __device__ __forceinline__ uint32_t narrow(float f) { return round_bf16(f); }
-};
-// IEEE binary16 through the hardware converts (round to nearest even, subnormals kept).
-struct WidenF16 {
-  static __device__ __forceinline__ float widen(uint32_t h) {
-    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));
-  }
-  static __device__ __forceinline__ uint32_t narrow(float f) {
-    return __builtin_bit_cast(uint16_t, static_cast<_Float16>(f));
-  }
-};
-
-template <int K>
-struct OpF32 {
-  static constexpr bool kReadsAcc = true;
-  static constexpr uint32_t kEs = 4;
-  static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
-    if constexpr (K == kSum || K == kProd) return as_u32(arith<K>(as_f32(a), as_f32(r)));
-    else return takes_received<K>(as_f32(a), as_f32(r)) ? r : a;
-  }
-  // Folding several received words into one accumulator word, in the order given.
-  struct State { uint32_t v; };
-  static __device__ __forceinline__ State open(uint32_t a) { return State{a}; }
-  static __device__ __forceinline__ void fold(State& t, uint32_t r) { t.v = word(t.v, r); }
-  static __device__ __forceinline__ uint32_t close(const State& t) { return t.v; }
-};
-
-template <int K>
-struct OpI32 {  // two's complement; SUM and PROD wrap modulo 2^32
-  static constexpr bool kReadsAcc = true;
-  static constexpr uint32_t kEs = 4;
-  static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
-    if constexpr (K == kSum) return a + r;
-    else if constexpr (K == kProd) return a * r;
-    else if constexpr (K == kMax) return static_cast<int32_t>(r) > static_cast<int32_t>(a) ? r : a;
-    else return static_cast<int32_t>(r) < static_cast<int32_t>(a) ? r : a;
-  }
-  struct State { uint32_t v; };
-  static __device__ __forceinline__ State open(uint32_t a) { return State{a}; }
-  static __device__ __forceinline__ void fold(State& t, uint32_t r) { t.v = word(t.v, r); }
-  static __device__ __forceinline__ uint32_t close(const State& t) { return t.v; }
-};
-
-template <int K, class W>
-struct Op16 {
-  static constexpr bool kReadsAcc = true;
-  static constexpr uint32_t kEs = 2;
-  static __device__ __forceinline__ uint32_t half(uint32_t a, uint32_t r) {  // low 16 bits
-    if constexpr (K == kSum || K == kProd) return W::narrow(arith<K>(W::widen(a), W::widen(r)));
-    else return takes_received<K>(W::widen(a), W::widen(r)) ? r : a;
-  }
-  static __device__ __forceinline__ uint32_t word(uint32_t a, uint32_t r) {
-    const uint32_t lo = half(a & 0xFFFFu, r & 0xFFFFu);
-    const uint32_t hi = half(a >> 16, r >> 16);
-    return (lo & 0xFFFFu) | (hi << 16);
-  }
-  // Several sources: SUM / PROD stay in binary32 across the whole fold and round once at
-  // the end; MAX / MIN carry the selected 16-bit pattern along with its widened value.
-  struct State { float lo, hi; uint32_t bits; };
-  static __device__ __forceinline__ State open(uint32_t a) {
-    return State{W::widen(a & 0xFFFFu), W::widen(a >> 16), a};
-  }
-  static __device__ __forceinline__ void fold(State& t, uint32_t r) {
-    const float rl = W::widen(r & 0xFFFFu), rh = W::widen(r >> 16);
-    if constexpr (K == kSum || K == kProd) {
-      t.lo = arith<K>(t.lo, rl);
-      t.hi = arith<K>(t.hi, rh);
-    } else {
-      if (takes_received<K>(t.lo, rl)) { t.lo = rl; t.bits = (t.bits & 0xFFFF0000u) | (r & 0xFFFFu); }
-      if (takes_received<K>(t.hi, rh)) { t.hi = rh; t.bits = (t.bits & 0x0000FFFFu) | (r & 0xFFFF0000u); }
-    }
-  }
-  static __device__ __forceinline__ uint32_t close(const State& t) {
-    if constexpr (K == kSum || K == kProd) return (W::narrow(t.lo) & 0xFFFFu) | (W::narrow(t.hi) << 16);
-    else return t.bits;
-  }
-};
-
-struct Copy {
-  static constexpr bool kReadsAcc = false;
-  static constexpr uint32_t kEs = 1;
-  static __device__ __forceinline__ uint32_t word(uint32_t, uint32_t r) { return r; }
-};
-
-// Which streams of a chunk exist: FWD = the staging copy is written, WB = the accumulator
-// is written back (a forward-only record relays the combined value without keeping it).
-template <class Op, bool FWD, bool WB>
-constexpr uint32_t cache_policy() {
-  if (Op::kReadsAcc) return FWD ? (WB ? UCCL_POLICY_REDUCE_FWD : UCCL_POLICY_REDUCE_RELAY) : UCCL_POLICY_REDUCE_KEEP;
-  return FWD ? (WB ? UCCL_POLICY_COPY_FWD : UCCL_POLICY_COPY_RELAY) : UCCL_POLICY_COPY_KEEP;
-}
-
-template <class Op>
-__device__ __forceinline__ u32x4 combine(u32x4 a, u32x4 r) {
-  u32x4 t;
-  t.x = Op::word(a.x, r.x);
-  t.y = Op::word(a.y, r.y);
-  t.z = Op::word(a.z, r.z);
-  t.w = Op::word(a.w, r.w);
-  return t;
-}
-
-__device__ __forceinline__ uint64_t wave_uniform(uint64_t v) {
-  const uint32_t lo = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v));
-  const uint32_t hi = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(v >> 32));
-  return lo | (static_cast<uint64_t>(hi) << 32);
-}
-
-// Stream one chunk with SG cooperating threads: U independent 16-byte vectors per thread
-// per trip, loads first, then combine and store.  Which streams carry a non-temporal
-// hint depends on the kind of chunk (see the policy masks above).
-template <int SG, int U, class Op, bool FWD, bool WB>
-__device__ __forceinline__ void stream_vectors(const u32x4* __restrict__ r, u32x4* __restrict__ a,
-                                               u32x4* __restrict__ o, uint32_t nvec,
-                                               uint32_t lane) {
-  constexpr uint32_t kPolicy = cache_policy<Op, FWD, WB>();
-  constexpr bool kNtRecv = (kPolicy & 8u) != 0, kNtOut = (kPolicy & 4u) != 0;
-  constexpr bool kNtAccLoad = (kPolicy & 2u) != 0, kNtAccStore = (kPolicy & 1u) != 0;
-  constexpr uint32_t kTrip = SG * U;
-  const uint32_t full = nvec - nvec % kTrip;
-  for (uint32_t base = lane; base < full; base += kTrip) {
-    u32x4 rv[U], av[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) rv[u] = load16<kNtRecv>(r + base + u * SG);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if constexpr (Op::kReadsAcc) av[u] = load16<kNtAccLoad>(a + base + u * SG);
-      else av[u] = rv[u];
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const u32x4 t = combine<Op>(av[u], rv[u]);
-      if (WB) store16<kNtAccStore>(a + base + u * SG, t);
-      if (FWD) store16<kNtOut>(o + base + u * SG, t);
-    }
-  }
-  for (uint32_t i = full + lane; i < nvec; i += SG) {
-    const u32x4 rv = load16<kNtRecv>(r + i);
-    u32x4 av = rv;
-    if constexpr (Op::kReadsAcc) av = load16<kNtAccLoad>(a + i);
-    const u32x4 t = combine<Op>(av, rv);
-    if (WB) store16<kNtAccStore>(a + i, t);
-    if (FWD) store16<kNtOut>(o + i, t);
-  }
-}
-
-// The last len % 16 bytes of a chunk, element by element.
-template <class Op, bool FWD, bool WB>
-__device__ __forceinline__ void stream_tail(const char* r, char* a, char* o, uint32_t rem,
-                                            uint32_t lane) {
-  if constexpr (Op::kEs == 4) {
-    if (lane < rem / 4) {
-      uint32_t* ap = reinterpret_cast<uint32_t*>(a) + lane;
-      const uint32_t t = Op::word(*ap, reinterpret_cast<const uint32_t*>(r)[lane]);
-      if (WB) *ap = t;
-      if (FWD) reinterpret_cast<uint32_t*>(o)[lane] = t;
-    }
-  } else if constexpr (Op::kEs == 2) {
-    if (lane < rem / 2) {
-      uint16_t* ap = reinterpret_cast<uint16_t*>(a) + lane;
-      const uint32_t t = Op::half(*ap, reinterpret_cast<const uint16_t*>(r)[lane]);
-      if (WB) *ap = static_cast<uint16_t>(t);
-      if (FWD) reinterpret_cast<uint16_t*>(o)[lane] = static_cast<uint16_t>(t);
-    }
-  } else {
-    if (lane < rem) {
-      const char t = r[lane];
-      if (WB) a[lane] = t;
-      if (FWD) o[lane] = t;
-    }
-  }
-}
-
-template <int SG, int U, class Op, bool FWD, bool WB>
-__device__ __forceinline__ void stream_chunk(const char* r, char* a, char* o, uint32_t len,
-                                             uint32_t lane) {
-  const uint32_t nvec = len >> 4;
-  stream_vectors<SG, U, Op, FWD, WB>(reinterpret_cast<const u32x4*>(r), reinterpret_cast<u32x4*>(a),
-                                 reinterpret_cast<u32x4*>(o), nvec, lane);
-  const uint32_t rem = len & 15u;
-  if (rem) {
-    const uint64_t off = static_cast<uint64_t>(nvec) << 4;
-    stream_tail<Op, FWD, WB>(r + off, a + off, FWD ? o + off : o, rem, lane);
-  }
-}
-
-// Winners of one tile of records, compacted; first[] is the exclusive prefix sum of
-// their unit counts (flat shape only) with the total in first[count].
-template <int T>
-struct Tile {
-  uint64_t src[T], dst[T], out[T];
-  uint32_t len[T];
-  uint32_t first[T + 1];
-  uint32_t count;
-};
-
-// Run by the first wavefront of a workgroup: lane i takes record tile*T + i, validates
-// it, claims its sequence number, and the winners are compacted into LDS in record order.
-// kUnitVecs > 0 also computes how many units of kUnitVecs 16-byte vectors each winner has.
-template <int T, class Op, uint32_t kUnitVecs>
-__device__ __forceinline__ void dedup_tile(const Args& g, Tile<T>& s, uint32_t tid) {
-  static_assert(T >= 1 && T <= 64, "one wavefront dedups the tile");
-  const uint64_t k = static_cast<uint64_t>(blockIdx.x) * T + tid;
-  bool win = false;
-  uint64_t src = 0, dst = 0, out = 0;
-  uint32_t len = 0;
-  if (tid < T && k < g.n_descs) {  // inside the array's capacity: safe to load
-    const u32x4* p = reinterpret_cast<const u32x4*>(g.descs + k);
-    const u32x4 lo = p[0], hi = p[1];
-    const uint32_t live = g.n_ptr != nullptr ? *g.n_ptr : g.n_descs;
-    src = lo.x | (static_cast<uint64_t>(lo.y) << 32);
-    dst = lo.z | (static_cast<uint64_t>(lo.w) << 32);
-    out = hi.x | (static_cast<uint64_t>(hi.y) << 32);
-    len = hi.z;
-    const uint32_t seq = hi.w;
-    const bool fwd = out != UCCL_NO_FORWARD;
-    const uint64_t out_at = out & ~UCCL_FORWARD_ONLY;
-    bool ok = seq < g.ext.n_bits && ((src | dst) & 15u) == 0 && len % Op::kEs == 0 &&
-              src <= g.ext.recv_bytes && len <= g.ext.recv_bytes - src &&
-              dst <= g.ext.acc_bytes && len <= g.ext.acc_bytes - dst;
-    if (fwd)
-      ok = ok && g.allow_forward && g.out != nullptr && (out_at & 15u) == 0 &&
-           out_at <= g.ext.out_bytes && len <= g.ext.out_bytes - out_at;
-    if (k >= live) {
-      // beyond the published count: not a record at all, neither applied nor rejected
-    } else if (ok) {
-      const uint32_t bit = 1u << (seq & 31u);
-      const uint32_t old = atomicOr(g.bitmap + (seq >> 5), bit);  // device scope, relaxed
-      win = (old & bit) == 0;
-    } else if (g.rejected != nullptr) {
-      atomicAdd(g.rejected, 1u);
-    }
-  }
-  const uint64_t winners = __ballot(win);
-  const uint32_t pos = __popcll(winners & ((1ull << tid) - 1ull));
-  const uint32_t count = __popcll(winners);
-  if (win) {
-    s.src[pos] = src;
-    s.dst[pos] = dst;
-    s.out[pos] = out;
-    s.len[pos] = len;
-  }
-  if (tid == 0) s.count = count;
-  if (kUnitVecs > 0) {
-    // a partial last vector (len % 16 != 0) counts as a vector of its unit
-    const uint32_t vecs = (len >> 4) + ((len & 15u) != 0u ? 1u : 0u);  // no overflow for len up to 2^32 - 1
-    const uint32_t units = win ? (vecs + kUnitVecs - 1u) / kUnitVecs : 0u;
-    uint32_t incl = units;
-#pragma unroll
-    for (uint32_t d = 1; d < 64; d <<= 1) {
-      const uint32_t below = __shfl_up(incl, d, 64);
-      if (tid >= d) incl += below;
-    }
-    if (win) s.first[pos] = incl - units;
-    if (tid == 63) s.first[count] = incl;
-  }
-}
-
-// Shapes WAVE / GROUP: subgroups of SG threads take whole winners in turn.  Kept
-// selectable because they are the obvious alternatives (one wavefront per chunk, one
-// workgroup per chunk); both measure slower than the flat shape on MI355X.
-template <int NT, int T, int SG, int U, class Op>
-__global__ void __launch_bounds__(NT) chunk_apply_kernel(const Args g) {
-  static_assert(NT % SG == 0 && SG % 64 == 0, "subgroups are whole wavefronts");
-  constexpr uint32_t kSubgroups = NT / SG;
-  __shared__ Tile<T> s;
-  const uint32_t tid = threadIdx.x;
-  if (tid < 64) dedup_tile<T, Op, 0>(g, s, tid);
-  __syncthreads();
-
-  const uint32_t count = s.count;
-  const uint32_t sg = tid / SG, lane = tid % SG;
-  for (uint32_t w = sg; w < count; w += kSubgroups) {
-    const uint64_t src = wave_uniform(s.src[w]);
-    const uint64_t dst = wave_uniform(s.dst[w]);
-    const uint64_t out = wave_uniform(s.out[w]);
-    const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
-    if (out == UCCL_NO_FORWARD)
-      stream_chunk<SG, U, Op, false, true>(g.recv + src, g.acc + dst, nullptr, len, lane);
-    else if (out & UCCL_FORWARD_ONLY)
-      stream_chunk<SG, U, Op, true, false>(g.recv + src, g.acc + dst, g.out + (out & ~UCCL_FORWARD_ONLY), len, lane);
-    else
-      stream_chunk<SG, U, Op, true, true>(g.recv + src, g.acc + dst, g.out + out, len, lane);
-  }
-}
-
-// One unit = 64*U consecutive 16-byte vectors of a chunk, streamed by one wavefront.
-template <int U, class Op, bool FWD, bool WB>
-__device__ __forceinline__ void stream_unit(const char* r, char* a, char* o, uint32_t len,
-                                            uint32_t trip, uint32_t lane) {
-  constexpr uint32_t kPolicy = cache_policy<Op, FWD, WB>();
-  constexpr bool kNtRecv = (kPolicy & 8u) != 0, kNtOut = (kPolicy & 4u) != 0;
-  constexpr bool kNtAccLoad = (kPolicy & 2u) != 0, kNtAccStore = (kPolicy & 1u) != 0;
-  constexpr uint32_t kUnit = 64u * U;
-  const uint32_t nvec = len >> 4;
-  const uint32_t v0 = trip * kUnit;
-  const u32x4* rp = reinterpret_cast<const u32x4*>(r) + v0 + lane;
-  u32x4* ap = reinterpret_cast<u32x4*>(a) + v0 + lane;
-  u32x4* op = reinterpret_cast<u32x4*>(o) + v0 + lane;
-  if (v0 + kUnit <= nvec) {
-    u32x4 rv[U], av[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) rv[u] = load16<kNtRecv>(rp + u * 64);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if constexpr (Op::kReadsAcc) av[u] = load16<kNtAccLoad>(ap + u * 64);
-      else av[u] = rv[u];
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const u32x4 t = combine<Op>(av[u], rv[u]);
-      if (WB) store16<kNtAccStore>(ap + u * 64, t);
-      if (FWD) store16<kNtOut>(op + u * 64, t);
-    }
-    return;
-  }
-  // last unit of the chunk: ragged
-#pragma unroll
-  for (int u = 0; u < U; ++u) {
-    if (v0 + lane + u * 64 < nvec) {
-      const u32x4 rv = load16<kNtRecv>(rp + u * 64);
-      u32x4 av = rv;
-      if constexpr (Op::kReadsAcc) av = load16<kNtAccLoad>(ap + u * 64);
-      const u32x4 t = combine<Op>(av, rv);
-      if (WB) store16<kNtAccStore>(ap + u * 64, t);
-      if (FWD) store16<kNtOut>(op + u * 64, t);
-    }
-  }
-  const uint32_t rem = len & 15u;
-  if (rem) {  // nvec lies in this unit, or the chunk would have had one unit fewer
-    const uint64_t off = static_cast<uint64_t>(nvec) << 4;
-    stream_tail<Op, FWD, WB>(r + off, a + off, FWD ? o + off : o, rem, lane);
-  }
-}
-
-// Shape FLAT: the winners' units are numbered consecutively across the tile and dealt
-// round-robin to the 16 wavefronts of a 1024-thread workgroup, so the machine sees the
-// same stream whether a tile holds one 128 KiB chunk or thirty-two 4 KiB chunks.
-template <int NT, int T, int U, class Op>
-__global__ void __launch_bounds__(NT) chunk_flat_kernel(const Args g) {
-  constexpr uint32_t kUnit = 64u * U;
-  constexpr uint32_t kWaves = NT / 64;
-  __shared__ Tile<T> s;
-  const uint32_t tid = threadIdx.x;
-  if (tid < 64) dedup_tile<T, Op, kUnit>(g, s, tid);
-  __syncthreads();
-
-  const uint32_t count = s.count;
-  const uint32_t total = s.first[count];
-  const uint32_t wave = tid >> 6, lane = tid & 63u;
-  for (uint32_t u = wave; u < total; u += kWaves) {
-    uint32_t w = 0;
-    if (T > 1) {
-      const bool mine = lane < count && s.first[lane] <= u && u < s.first[lane + 1];
-      w = __ffsll(static_cast<unsigned long long>(__ballot(mine))) - 1;  // exactly one lane
-    }
-    w = __builtin_amdgcn_readfirstlane(w);
-    const uint32_t trip = u - __builtin_amdgcn_readfirstlane(s.first[w]);
-    const uint64_t src = wave_uniform(s.src[w]);
-    const uint64_t dst = wave_uniform(s.dst[w]);
-    const uint64_t out = wave_uniform(s.out[w]);
-    const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
-    if (out == UCCL_NO_FORWARD)
-      stream_unit<U, Op, false, true>(g.recv + src, g.acc + dst, nullptr, len, trip, lane);
-    else if (out & UCCL_FORWARD_ONLY)
-      stream_unit<U, Op, true, false>(g.recv + src, g.acc + dst, g.out + (out & ~UCCL_FORWARD_ONLY), len, trip, lane);
-    else
-      stream_unit<U, Op, true, true>(g.recv + src, g.acc + dst, g.out + out, len, trip, lane);
-  }
-}
-
-// ---- several sources per destination chunk ---------------------------------------------
-//
-// Section 2.1: the kernel reduces transport buffers "from multiple sender GPUs" into the
-// tensor buffer.  A gather record names up to UCCL_MAX_SOURCES receive slots for one
-// destination chunk; they are folded into the accumulator's value in the order listed, so
-// the floating-point result is fixed by the record, not by arrival timing.  The accumulator
-// is read and written once per chunk however many sources there are.  Same tile / unit
-// dealing as the flat shape; per unit a wavefront keeps the running value in registers
-// (widened to binary32 for 16-bit types); sources are loaded in batches, all loads of a
-// batch in flight before the folds, which then run in the listed order.
-struct GatherArgs {
-  char* acc;
-  char* out;
-  const char* recv;
-  const uccl_gather_desc* descs;
-  uint32_t* bitmap;
-  uint32_t* rejected;
-  Extents ext;
-  uint32_t n_descs;
-};
-
-template <int T>
-struct GatherTile {
-  uint64_t dst[T], out[T];
-  uint64_t src[T][UCCL_MAX_SOURCES];
-  uint32_t len[T], n_src[T];
-  uint32_t first[T + 1];
-  uint32_t count;
-};
-
-template <int NT, int T, int U, class Op>
-__global__ void __launch_bounds__(NT) chunk_gather_kernel(const GatherArgs g) {
-  static_assert(T >= 1 && T <= 64, "one wavefront dedups the tile");
-  constexpr uint32_t kUnit = 64u * U;
-  constexpr uint32_t kBatch = UCCL_GATHER_BATCH;
-  __shared__ GatherTile<T> s;
-  const uint32_t tid = threadIdx.x;
-  if (tid < 64) {
-    const uint64_t k = static_cast<uint64_t>(blockIdx.x) * T + tid;
-    bool win = false;
-    uint64_t dst = 0, out = 0;
-    uint32_t len = 0, n_src = 0;
-    const uccl_gather_desc* d = g.descs + k;
-    if (tid < T && k < g.n_descs) {
-      const u32x4* p = reinterpret_cast<const u32x4*>(d);
-      const u32x4 lo = p[0], hi = p[1];
-      dst = lo.x | (static_cast<uint64_t>(lo.y) << 32);
-      out = lo.z | (static_cast<uint64_t>(lo.w) << 32);
-      len = hi.x;
-      const uint32_t seq = hi.y;
-      n_src = hi.z;
-      const bool fwd = out != UCCL_NO_FORWARD;
-      const uint64_t out_at = out & ~UCCL_FORWARD_ONLY;
-      bool ok = seq < g.ext.n_bits && (dst & 15u) == 0 && len % Op::kEs == 0 && n_src >= 1 &&
-                n_src <= UCCL_MAX_SOURCES && dst <= g.ext.acc_bytes && len <= g.ext.acc_bytes - dst;
-      if (fwd)
-        ok = ok && g.out != nullptr && (out_at & 15u) == 0 && out_at <= g.ext.out_bytes &&
-             len <= g.ext.out_bytes - out_at;
-      if (ok) {
-        for (uint32_t j = 0; j < n_src; ++j) {
-          const uint64_t so = d->src_off[j];
-          ok = ok && (so & 15u) == 0 && so <= g.ext.recv_bytes && len <= g.ext.recv_bytes - so;
-        }
-      }
-      if (ok) {
-        const uint32_t bit = 1u << (seq & 31u);
-        const uint32_t old = atomicOr(g.bitmap + (seq >> 5), bit);
-        win = (old & bit) == 0;
-      } else if (g.rejected != nullptr) {
-        atomicAdd(g.rejected, 1u);
-      }
-    }
-    const uint64_t winners = __ballot(win);
-    const uint32_t pos = __popcll(winners & ((1ull << tid) - 1ull));
-    const uint32_t count = __popcll(winners);
-    if (win) {
-      s.dst[pos] = dst;
-      s.out[pos] = out;
-      s.len[pos] = len;
-      s.n_src[pos] = n_src;
-      for (uint32_t j = 0; j < n_src; ++j) s.src[pos][j] = d->src_off[j];
-    }
-    if (tid == 0) s.count = count;
-    const uint32_t vecs = (len >> 4) + ((len & 15u) != 0u ? 1u : 0u);  // no overflow for len up to 2^32 - 1
-    const uint32_t units = win ? (vecs + kUnit - 1u) / kUnit : 0u;
-    uint32_t incl = units;
-#pragma unroll
-    for (uint32_t dlt = 1; dlt < 64; dlt <<= 1) {
-      const uint32_t below = __shfl_up(incl, dlt, 64);
-      if (tid >= dlt) incl += below;
-    }
-    if (win) s.first[pos] = incl - units;
-    if (tid == 63) s.first[count] = incl;
-  }
-  __syncthreads();
-
-  const uint32_t count = s.count;
-  const uint32_t total = s.first[count];
-  const uint32_t wave = tid >> 6, lane = tid & 63u;
-  for (uint32_t u = wave; u < total; u += NT / 64) {
-    uint32_t w = 0;
-    if (T > 1) {
-      const bool mine = lane < count && s.first[lane] <= u && u < s.first[lane + 1];
-      w = __ffsll(static_cast<unsigned long long>(__ballot(mine))) - 1;
-    }
-    w = __builtin_amdgcn_readfirstlane(w);
-    const uint32_t v0 = (u - __builtin_amdgcn_readfirstlane(s.first[w])) * kUnit;
-    const uint64_t dst = wave_uniform(s.dst[w]);
-    const uint64_t out = wave_uniform(s.out[w]);
-    const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
-    const uint32_t n_src = __builtin_amdgcn_readfirstlane(s.n_src[w]);
-    const uint32_t nvec = len >> 4;
-    const bool fwd = out != UCCL_NO_FORWARD;
-    const bool keep = !(fwd && (out & UCCL_FORWARD_ONLY));
-    u32x4* ap = reinterpret_cast<u32x4*>(g.acc + dst) + v0 + lane;
-    u32x4* op = reinterpret_cast<u32x4*>(g.out + (out & ~UCCL_FORWARD_ONLY)) + v0 + lane;
-    bool live[U];
-    typename Op::State st[U][4];
-#pragma unroll
-    for (int i = 0; i < U; ++i) {
-      live[i] = v0 + lane + i * 64 < nvec;
-      u32x4 a = {0u, 0u, 0u, 0u};
-      if (live[i]) a = ap[i * 64];
-      st[i][0] = Op::open(a.x); st[i][1] = Op::open(a.y); st[i][2] = Op::open(a.z); st[i][3] = Op::open(a.w);
-    }
-    // sources in batches: all loads of a batch are issued before the first fold waits
-    for (uint32_t j0 = 0; j0 < n_src; j0 += kBatch) {
-      u32x4 rv[kBatch][U];
-#pragma unroll
-      for (uint32_t b = 0; b < kBatch; ++b) {
-        if (j0 + b < n_src) {
-          const u32x4* rp = reinterpret_cast<const u32x4*>(g.recv + wave_uniform(s.src[w][j0 + b])) + v0 + lane;
-#pragma unroll
-          for (int i = 0; i < U; ++i) {
-            rv[b][i] = u32x4{0u, 0u, 0u, 0u};
-            if (live[i]) rv[b][i] = __builtin_nontemporal_load(rp + i * 64);
-          }
-        }
-      }
-#pragma unroll
-      for (uint32_t b = 0; b < kBatch; ++b) {
-        if (j0 + b < n_src) {
-#pragma unroll
-          for (int i = 0; i < U; ++i) {
-            Op::fold(st[i][0], rv[b][i].x); Op::fold(st[i][1], rv[b][i].y);
-            Op::fold(st[i][2], rv[b][i].z); Op::fold(st[i][3], rv[b][i].w);
-          }
-        }
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < U; ++i) {
-      if (!live[i]) continue;
-      u32x4 t;
-      t.x = Op::close(st[i][0]); t.y = Op::close(st[i][1]); t.z = Op::close(st[i][2]); t.w = Op::close(st[i][3]);
-      if (keep) ap[i * 64] = t;
-      if (fwd) __builtin_nontemporal_store(t, op + i * 64);
-    }
-    // the last len % 16 bytes, element by element, by the unit that holds vector index nvec
-    const uint32_t rem = len & 15u;
-    if (rem && nvec >= v0 && nvec < v0 + kUnit && lane < rem / Op::kEs) {
-      const uint64_t off = (static_cast<uint64_t>(nvec) << 4) + lane * Op::kEs;
-      uint32_t a_el;
-      if constexpr (Op::kEs == 4) a_el = *reinterpret_cast<const uint32_t*>(g.acc + dst + off);
-      else a_el = *reinterpret_cast<const uint16_t*>(g.acc + dst + off);
-      typename Op::State t = Op::open(a_el);
-      for (uint32_t j = 0; j < n_src; ++j) {
-        const char* rp = g.recv + wave_uniform(s.src[w][j]) + off;
-        uint32_t r_el;
-        if constexpr (Op::kEs == 4) r_el = *reinterpret_cast<const uint32_t*>(rp);
-        else r_el = *reinterpret_cast<const uint16_t*>(rp);
-        Op::fold(t, r_el);
-      }
-      const uint32_t res = Op::close(t);
-      if constexpr (Op::kEs == 4) {
-        if (keep) *reinterpret_cast<uint32_t*>(g.acc + dst + off) = res;
-        if (fwd) *reinterpret_cast<uint32_t*>(g.out + (out & ~UCCL_FORWARD_ONLY) + off) = res;
-      } else {
-        if (keep) *reinterpret_cast<uint16_t*>(g.acc + dst + off) = static_cast<uint16_t>(res);
-        if (fwd) *reinterpret_cast<uint16_t*>(g.out + (out & ~UCCL_FORWARD_ONLY) + off) = static_cast<uint16_t>(res);
-      }
-    }
-  }
-}
-
-__global__ void __launch_bounds__(256) fill_words_kernel(uint32_t* p, uint64_t n, uint32_t v) {
-  for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x; i < n;
-       i += static_cast<uint64_t>(gridDim.x) * 256)
-    p[i] = v;
-}
-
-// Receiver feedback from the dedup bitmap: cumulative acknowledgement (first clear bit),
-// number of applied chunks, and the runs of set bits above the cumulative point in
-// ascending order (what a selective-acknowledgement option would carry).  One 1024-thread
-// workgroup walks the words in order, 1024 words per round: thread i owns word i of the
-// round, finds run starts (bit set, previous bit clear) and run ends (bit set, next bit
-// clear) with two word-wide shifts, and a block-wide exclusive scan of the per-word counts
-// gives every start and end its ordinal, so the k-th start and the k-th end land in the
-// same output pair.  The bitmap is tiny next to the payload (one bit per chunk), so this is
-// a latency problem, not a bandwidth one: one workgroup, no atomics, no second pass.
-struct AckHeader {
-  uint64_t cum_ack, n_applied;
-  uint32_t n_ranges, complete;
-  uint64_t reserved;
-};
-
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t tid, uint32_t* s_wave,
-                                                         uint32_t* total) {
-  uint32_t incl = v;
-#pragma unroll
-  for (uint32_t d = 1; d < 64; d <<= 1) {
-    const uint32_t below = __shfl_up(incl, d, 64);
-    if ((tid & 63u) >= d) incl += below;
-  }
-  if ((tid & 63u) == 63u) s_wave[tid >> 6] = incl;
-  __syncthreads();
-  uint32_t base = 0, sum = 0;
-  for (uint32_t w = 0; w < 16; ++w) {
-    const uint32_t x = s_wave[w];
-    if (w < (tid >> 6)) base += x;
-    sum += x;
-  }
-  __syncthreads();  // s_wave is reused by the next scan
-  *total = sum;
-  return base + incl - v;
-}
-
-__global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __restrict__ bitmap,
-                                                          uint64_t n_bits, AckHeader* hdr,
-                                                          uint64_t* ranges, uint32_t max_ranges) {
-  __shared__ uint32_t s_wave[16];
-  __shared__ unsigned long long s_first_clear;
-  const uint32_t tid = threadIdx.x;
-  const uint64_t n_words = (n_bits + 31) / 32;
-  if (tid == 0) s_first_clear = ~0ull;
-  __syncthreads();
-  uint64_t applied = 0;      // per-thread partial popcount
-  uint32_t starts_seen = 0;  // runs started / ended in earlier rounds (same in every thread)
-  uint32_t ends_seen = 0;
-  for (uint64_t w0 = 0; w0 < n_words; w0 += 1024) {
-    const uint64_t w = w0 + tid;
-    uint32_t word = 0, prev_msb = 0, next_lsb = 0;
-    if (w < n_words) {
-      word = bitmap[w];
-      const uint64_t valid = n_bits - w * 32;  // bits of this word inside the bitmap
-      if (valid < 32) word &= (1u << valid) - 1u;
-      if (w > 0) prev_msb = bitmap[w - 1] >> 31;
-      if (w + 1 < n_words) {
-        uint32_t nx = bitmap[w + 1];
-        const uint64_t nvalid = n_bits - (w + 1) * 32;
-        if (nvalid < 32) nx &= (1u << nvalid) - 1u;
-        next_lsb = nx & 1u;
-      }
-      applied += __popc(word);
-      const uint32_t clear = ~word & (valid < 32 ? (1u << valid) - 1u : ~0u);
-      if (clear) atomicMin(&s_first_clear, w * 32 + (__ffs(clear) - 1));  // LDS atomic
-    }
-    const uint32_t starts = word & ~((word << 1) | prev_msb);
-    const uint32_t ends = word & ~((word >> 1) | (next_lsb << 31));
-    uint32_t n_starts, n_ends;
-    const uint32_t s_at = starts_seen + block_exclusive_scan(__popc(starts), tid, s_wave, &n_starts);
-    const uint32_t e_at = ends_seen + block_exclusive_scan(__popc(ends), tid, s_wave, &n_ends);
-    // ordinal 0 is the run that begins at bit 0, if there is one: that is the cumulative
-    // part, not a selective range; `skip` shifts the ordinals accordingly
-    const uint32_t skip = bitmap[0] & 1u;
-    uint32_t k = s_at;
-    for (uint32_t m = starts; m; m &= m - 1, ++k)
-      if (k >= skip && k - skip < max_ranges) ranges[2 * (k - skip)] = w * 32 + (__ffs(m) - 1);
-    k = e_at;
-    for (uint32_t m = ends; m; m &= m - 1, ++k)
-      if (k >= skip && k - skip < max_ranges) ranges[2 * (k - skip) + 1] = w * 32 + (__ffs(m) - 1) + 1;
-    starts_seen += n_starts;
-    ends_seen += n_ends;
-  }
-  // block-wide sum of the popcounts: 64-bit totals as two 32-bit scans would overflow only
-  // beyond 2^32 set bits per thread-lane, impossible for n_bits < 2^42; keep it simple
-  uint32_t tot_lo, tot_hi;
-  block_exclusive_scan(static_cast<uint32_t>(applied & 0xFFFFFu), tid, s_wave, &tot_lo);
-  block_exclusive_scan(static_cast<uint32_t>(applied >> 20), tid, s_wave, &tot_hi);
-  if (tid == 0) {
-    const uint64_t total = static_cast<uint64_t>(tot_lo) + (static_cast<uint64_t>(tot_hi) << 20);
-    const uint64_t first_clear = s_first_clear == ~0ull ? n_bits : s_first_clear;
-    const uint32_t skip = n_bits > 0 ? (bitmap[0] & 1u) : 0u;
-    hdr->cum_ack = first_clear;
-    hdr->n_applied = total;
-    hdr->n_ranges = starts_seen - skip;
-    hdr->complete = (total == n_bits) ? 1u : 0u;
-    hdr->reserved = 0;
-  }
-}
-
-// Per-message window status (Section 3.2's message id / chunk sequence number / last-chunk
-// mark): one wavefront per slot.  Lane l owns word l of the slot's window (a window is at
-// most 64 words), masks it to the slot's limit, and the wavefront combines: a ballot of
-// "has a clear bit below the limit" locates the first hole, a butterfly sum gives the
-// applied count.  With `recycle`, the lanes of a complete slot store zeros over its window.
-__global__ void __launch_bounds__(256) message_status_kernel(uint32_t* __restrict__ bitmap,
-                                                             const uint32_t* __restrict__ n_chunks,
-                                                             uint32_t n_slots, uint32_t words_per_slot,
-                                                             uint4* __restrict__ status, uint32_t recycle) {
-  const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t slot = blockIdx.x * 4u + (threadIdx.x >> 6);
-  if (slot >= n_slots) return;  // whole wavefronts leave together; no barrier follows
-  const uint32_t window = words_per_slot * 32u;
-  const uint32_t known = n_chunks[slot];
-  const uint32_t limit = known == 0u ? window : (known < window ? known : window);
-  uint32_t* w = bitmap + static_cast<uint64_t>(slot) * words_per_slot + lane;
-  uint32_t word = 0u, mask = 0u;
-  if (lane < words_per_slot) {
-    word = *w;
-    const uint32_t lo = lane * 32u;
-    mask = limit >= lo + 32u ? ~0u : (limit > lo ? (1u << (limit - lo)) - 1u : 0u);
-  }
-  const uint32_t clear = ~word & mask;
-  const unsigned long long holes = __ballot(clear != 0u);
-  uint32_t cum = limit;
-  if (holes) {
-    const int first = __ffsll(holes) - 1;
-    cum = static_cast<uint32_t>(first) * 32u + static_cast<uint32_t>(__shfl(__ffs(clear) - 1, first, 64));
-  }
-  uint32_t count = __popc(word & mask);
-#pragma unroll
-  for (uint32_t d = 32; d >= 1; d >>= 1) count += __shfl_xor(count, d, 64);
-  const uint32_t complete = (known != 0u && count == limit) ? 1u : 0u;
-  if (lane == 0) status[slot] = make_uint4(cum, count, complete, 0u);
-  if (recycle && complete && lane < words_per_slot) *w = 0u;
-}
 
 // ---- host side ----------------------------------------------------------------------
 

@@ -1,0 +1,510 @@
+// Data-path kernels: dedup of a tile of records, and the three launch shapes that stream the
+// winners (flat, one wavefront per chunk, one workgroup per chunk), the multi-source fold, and the
+// bitmap fill.  Internal to the library: included by uccl_chunk.hip only.
+#pragma once
+
+#include "uccl_chunk.h"
+#include "uccl_elements.hpp"
+
+// Tunable compile-time shape constants (defaults chosen by measurement on MI355X).
+#ifndef UCCL_WAVE_TILE
+#define UCCL_WAVE_TILE 4      // records per 256-thread workgroup, one wavefront per chunk
+#endif
+#ifndef UCCL_WAVE_UNROLL
+#define UCCL_WAVE_UNROLL 4
+#endif
+#ifndef UCCL_WAVE_TILE_SMALL
+#define UCCL_WAVE_TILE_SMALL 16  // same shape, used when a call carries very many records
+#endif
+#ifndef UCCL_GROUP_TILE
+#define UCCL_GROUP_TILE 1     // records per workgroup, 256 threads per chunk
+#endif
+#ifndef UCCL_GROUP_UNROLL
+#define UCCL_GROUP_UNROLL 4
+#endif
+#ifndef UCCL_GATHER_UNROLL
+#define UCCL_GATHER_UNROLL 2  // multi-sender reduce: vectors per lane per unit
+#endif
+#ifndef UCCL_GATHER_BATCH
+#define UCCL_GATHER_BATCH 4   // and how many sources are loaded before the folds start
+#endif
+#ifndef UCCL_FLAT_THREADS
+#define UCCL_FLAT_THREADS 1024  // workgroup size of the flat shape
+#endif
+#ifndef UCCL_FLAT_UNROLL
+#define UCCL_FLAT_UNROLL 2    // vectors per lane per unit: a unit is 64*U*16 bytes per stream
+#endif
+namespace {
+
+struct Extents {
+  uint64_t acc_bytes, out_bytes, recv_bytes, n_bits;
+};
+
+struct Args {
+  char* acc;
+  char* out;
+  const char* recv;
+  const uccl_chunk_desc* descs;
+  uint32_t* bitmap;
+  uint32_t* rejected;
+  Extents ext;
+  const uint32_t* n_ptr;  // optional: the record count is read from here (capped by n_descs)
+  uint32_t n_descs;
+  uint32_t allow_forward;
+};
+
+// Stream one chunk with SG cooperating threads: U independent 16-byte vectors per thread
+// per trip, loads first, then combine and store.  Which streams carry a non-temporal
+// hint depends on the kind of chunk (see the policy masks above).
+template <int SG, int U, class Op, bool FWD, bool WB>
+__device__ __forceinline__ void stream_vectors(const u32x4* __restrict__ r, u32x4* __restrict__ a,
+                                               u32x4* __restrict__ o, uint32_t nvec,
+                                               uint32_t lane) {
+  constexpr uint32_t kPolicy = cache_policy<Op, FWD, WB>();
+  constexpr bool kNtRecv = (kPolicy & 8u) != 0, kNtOut = (kPolicy & 4u) != 0;
+  constexpr bool kNtAccLoad = (kPolicy & 2u) != 0, kNtAccStore = (kPolicy & 1u) != 0;
+  constexpr uint32_t kTrip = SG * U;
+  const uint32_t full = nvec - nvec % kTrip;
+  for (uint32_t base = lane; base < full; base += kTrip) {
+    u32x4 rv[U], av[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) rv[u] = load16<kNtRecv>(r + base + u * SG);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if constexpr (Op::kReadsAcc) av[u] = load16<kNtAccLoad>(a + base + u * SG);
+      else av[u] = rv[u];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const u32x4 t = combine<Op>(av[u], rv[u]);
+      if (WB) store16<kNtAccStore>(a + base + u * SG, t);
+      if (FWD) store16<kNtOut>(o + base + u * SG, t);
+    }
+  }
+  for (uint32_t i = full + lane; i < nvec; i += SG) {
+    const u32x4 rv = load16<kNtRecv>(r + i);
+    u32x4 av = rv;
+    if constexpr (Op::kReadsAcc) av = load16<kNtAccLoad>(a + i);
+    const u32x4 t = combine<Op>(av, rv);
+    if (WB) store16<kNtAccStore>(a + i, t);
+    if (FWD) store16<kNtOut>(o + i, t);
+  }
+}
+
+// The last len % 16 bytes of a chunk, element by element.
+template <class Op, bool FWD, bool WB>
+__device__ __forceinline__ void stream_tail(const char* r, char* a, char* o, uint32_t rem,
+                                            uint32_t lane) {
+  if constexpr (Op::kEs == 4) {
+    if (lane < rem / 4) {
+      uint32_t* ap = reinterpret_cast<uint32_t*>(a) + lane;
+      const uint32_t t = Op::word(*ap, reinterpret_cast<const uint32_t*>(r)[lane]);
+      if (WB) *ap = t;
+      if (FWD) reinterpret_cast<uint32_t*>(o)[lane] = t;
+    }
+  } else if constexpr (Op::kEs == 2) {
+    if (lane < rem / 2) {
+      uint16_t* ap = reinterpret_cast<uint16_t*>(a) + lane;
+      const uint32_t t = Op::half(*ap, reinterpret_cast<const uint16_t*>(r)[lane]);
+      if (WB) *ap = static_cast<uint16_t>(t);
+      if (FWD) reinterpret_cast<uint16_t*>(o)[lane] = static_cast<uint16_t>(t);
+    }
+  } else {
+    if (lane < rem) {
+      const char t = r[lane];
+      if (WB) a[lane] = t;
+      if (FWD) o[lane] = t;
+    }
+  }
+}
+
+template <int SG, int U, class Op, bool FWD, bool WB>
+__device__ __forceinline__ void stream_chunk(const char* r, char* a, char* o, uint32_t len,
+                                             uint32_t lane) {
+  const uint32_t nvec = len >> 4;
+  stream_vectors<SG, U, Op, FWD, WB>(reinterpret_cast<const u32x4*>(r), reinterpret_cast<u32x4*>(a),
+                                 reinterpret_cast<u32x4*>(o), nvec, lane);
+  const uint32_t rem = len & 15u;
+  if (rem) {
+    const uint64_t off = static_cast<uint64_t>(nvec) << 4;
+    stream_tail<Op, FWD, WB>(r + off, a + off, FWD ? o + off : o, rem, lane);
+  }
+}
+
+// Winners of one tile of records, compacted; first[] is the exclusive prefix sum of
+// their unit counts (flat shape only) with the total in first[count].
+template <int T>
+struct Tile {
+  uint64_t src[T], dst[T], out[T];
+  uint32_t len[T];
+  uint32_t first[T + 1];
+  uint32_t count;
+};
+
+// Run by the first wavefront of a workgroup: lane i takes record tile*T + i, validates
+// it, claims its sequence number, and the winners are compacted into LDS in record order.
+// kUnitVecs > 0 also computes how many units of kUnitVecs 16-byte vectors each winner has.
+template <int T, class Op, uint32_t kUnitVecs>
+__device__ __forceinline__ void dedup_tile(const Args& g, Tile<T>& s, uint32_t tid) {
+  static_assert(T >= 1 && T <= 64, "one wavefront dedups the tile");
+  const uint64_t k = static_cast<uint64_t>(blockIdx.x) * T + tid;
+  bool win = false;
+  uint64_t src = 0, dst = 0, out = 0;
+  uint32_t len = 0;
+  if (tid < T && k < g.n_descs) {  // inside the array's capacity: safe to load
+    const u32x4* p = reinterpret_cast<const u32x4*>(g.descs + k);
+    const u32x4 lo = p[0], hi = p[1];
+    const uint32_t live = g.n_ptr != nullptr ? *g.n_ptr : g.n_descs;
+    src = lo.x | (static_cast<uint64_t>(lo.y) << 32);
+    dst = lo.z | (static_cast<uint64_t>(lo.w) << 32);
+    out = hi.x | (static_cast<uint64_t>(hi.y) << 32);
+    len = hi.z;
+    const uint32_t seq = hi.w;
+    const bool fwd = out != UCCL_NO_FORWARD;
+    const uint64_t out_at = out & ~UCCL_FORWARD_ONLY;
+    bool ok = seq < g.ext.n_bits && ((src | dst) & 15u) == 0 && len % Op::kEs == 0 &&
+              src <= g.ext.recv_bytes && len <= g.ext.recv_bytes - src &&
+              dst <= g.ext.acc_bytes && len <= g.ext.acc_bytes - dst;
+    if (fwd)
+      ok = ok && g.allow_forward && g.out != nullptr && (out_at & 15u) == 0 &&
+           out_at <= g.ext.out_bytes && len <= g.ext.out_bytes - out_at;
+    if (k >= live) {
+      // beyond the published count: not a record at all, neither applied nor rejected
+    } else if (ok) {
+      const uint32_t bit = 1u << (seq & 31u);
+      const uint32_t old = atomicOr(g.bitmap + (seq >> 5), bit);  // device scope, relaxed
+      win = (old & bit) == 0;
+    } else if (g.rejected != nullptr) {
+      atomicAdd(g.rejected, 1u);
+    }
+  }
+  const uint64_t winners = __ballot(win);
+  const uint32_t pos = __popcll(winners & ((1ull << tid) - 1ull));
+  const uint32_t count = __popcll(winners);
+  if (win) {
+    s.src[pos] = src;
+    s.dst[pos] = dst;
+    s.out[pos] = out;
+    s.len[pos] = len;
+  }
+  if (tid == 0) s.count = count;
+  if (kUnitVecs > 0) {
+    // a partial last vector (len % 16 != 0) counts as a vector of its unit
+    const uint32_t vecs = (len >> 4) + ((len & 15u) != 0u ? 1u : 0u);  // no overflow for len up to 2^32 - 1
+    const uint32_t units = win ? (vecs + kUnitVecs - 1u) / kUnitVecs : 0u;
+    uint32_t incl = units;
+#pragma unroll
+    for (uint32_t d = 1; d < 64; d <<= 1) {
+      const uint32_t below = __shfl_up(incl, d, 64);
+      if (tid >= d) incl += below;
+    }
+    if (win) s.first[pos] = incl - units;
+    if (tid == 63) s.first[count] = incl;
+  }
+}
+
+// Shapes WAVE / GROUP: subgroups of SG threads take whole winners in turn.  Kept
+// selectable because they are the obvious alternatives (one wavefront per chunk, one
+// workgroup per chunk); both measure slower than the flat shape on MI355X.
+template <int NT, int T, int SG, int U, class Op>
+__global__ void __launch_bounds__(NT) chunk_apply_kernel(const Args g) {
+  static_assert(NT % SG == 0 && SG % 64 == 0, "subgroups are whole wavefronts");
+  constexpr uint32_t kSubgroups = NT / SG;
+  __shared__ Tile<T> s;
+  const uint32_t tid = threadIdx.x;
+  if (tid < 64) dedup_tile<T, Op, 0>(g, s, tid);
+  __syncthreads();
+
+  const uint32_t count = s.count;
+  const uint32_t sg = tid / SG, lane = tid % SG;
+  for (uint32_t w = sg; w < count; w += kSubgroups) {
+    const uint64_t src = wave_uniform(s.src[w]);
+    const uint64_t dst = wave_uniform(s.dst[w]);
+    const uint64_t out = wave_uniform(s.out[w]);
+    const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
+    if (out == UCCL_NO_FORWARD)
+      stream_chunk<SG, U, Op, false, true>(g.recv + src, g.acc + dst, nullptr, len, lane);
+    else if (out & UCCL_FORWARD_ONLY)
+      stream_chunk<SG, U, Op, true, false>(g.recv + src, g.acc + dst, g.out + (out & ~UCCL_FORWARD_ONLY), len, lane);
+    else
+      stream_chunk<SG, U, Op, true, true>(g.recv + src, g.acc + dst, g.out + out, len, lane);
+  }
+}
+
+// One unit = 64*U consecutive 16-byte vectors of a chunk, streamed by one wavefront.
+template <int U, class Op, bool FWD, bool WB>
+__device__ __forceinline__ void stream_unit(const char* r, char* a, char* o, uint32_t len,
+                                            uint32_t trip, uint32_t lane) {
+  constexpr uint32_t kPolicy = cache_policy<Op, FWD, WB>();
+  constexpr bool kNtRecv = (kPolicy & 8u) != 0, kNtOut = (kPolicy & 4u) != 0;
+  constexpr bool kNtAccLoad = (kPolicy & 2u) != 0, kNtAccStore = (kPolicy & 1u) != 0;
+  constexpr uint32_t kUnit = 64u * U;
+  const uint32_t nvec = len >> 4;
+  const uint32_t v0 = trip * kUnit;
+  const u32x4* rp = reinterpret_cast<const u32x4*>(r) + v0 + lane;
+  u32x4* ap = reinterpret_cast<u32x4*>(a) + v0 + lane;
+  u32x4* op = reinterpret_cast<u32x4*>(o) + v0 + lane;
+  if (v0 + kUnit <= nvec) {
+    u32x4 rv[U], av[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) rv[u] = load16<kNtRecv>(rp + u * 64);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if constexpr (Op::kReadsAcc) av[u] = load16<kNtAccLoad>(ap + u * 64);
+      else av[u] = rv[u];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const u32x4 t = combine<Op>(av[u], rv[u]);
+      if (WB) store16<kNtAccStore>(ap + u * 64, t);
+      if (FWD) store16<kNtOut>(op + u * 64, t);
+    }
+    return;
+  }
+  // last unit of the chunk: ragged
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (v0 + lane + u * 64 < nvec) {
+      const u32x4 rv = load16<kNtRecv>(rp + u * 64);
+      u32x4 av = rv;
+      if constexpr (Op::kReadsAcc) av = load16<kNtAccLoad>(ap + u * 64);
+      const u32x4 t = combine<Op>(av, rv);
+      if (WB) store16<kNtAccStore>(ap + u * 64, t);
+      if (FWD) store16<kNtOut>(op + u * 64, t);
+    }
+  }
+  const uint32_t rem = len & 15u;
+  if (rem) {  // nvec lies in this unit, or the chunk would have had one unit fewer
+    const uint64_t off = static_cast<uint64_t>(nvec) << 4;
+    stream_tail<Op, FWD, WB>(r + off, a + off, FWD ? o + off : o, rem, lane);
+  }
+}
+
+// Shape FLAT: the winners' units are numbered consecutively across the tile and dealt
+// round-robin to the 16 wavefronts of a 1024-thread workgroup, so the machine sees the
+// same stream whether a tile holds one 128 KiB chunk or thirty-two 4 KiB chunks.
+template <int NT, int T, int U, class Op>
+__global__ void __launch_bounds__(NT) chunk_flat_kernel(const Args g) {
+  constexpr uint32_t kUnit = 64u * U;
+  constexpr uint32_t kWaves = NT / 64;
+  __shared__ Tile<T> s;
+  const uint32_t tid = threadIdx.x;
+  if (tid < 64) dedup_tile<T, Op, kUnit>(g, s, tid);
+  __syncthreads();
+
+  const uint32_t count = s.count;
+  const uint32_t total = s.first[count];
+  const uint32_t wave = tid >> 6, lane = tid & 63u;
+  for (uint32_t u = wave; u < total; u += kWaves) {
+    uint32_t w = 0;
+    if (T > 1) {
+      const bool mine = lane < count && s.first[lane] <= u && u < s.first[lane + 1];
+      w = __ffsll(static_cast<unsigned long long>(__ballot(mine))) - 1;  // exactly one lane
+    }
+    w = __builtin_amdgcn_readfirstlane(w);
+    const uint32_t trip = u - __builtin_amdgcn_readfirstlane(s.first[w]);
+    const uint64_t src = wave_uniform(s.src[w]);
+    const uint64_t dst = wave_uniform(s.dst[w]);
+    const uint64_t out = wave_uniform(s.out[w]);
+    const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
+    if (out == UCCL_NO_FORWARD)
+      stream_unit<U, Op, false, true>(g.recv + src, g.acc + dst, nullptr, len, trip, lane);
+    else if (out & UCCL_FORWARD_ONLY)
+      stream_unit<U, Op, true, false>(g.recv + src, g.acc + dst, g.out + (out & ~UCCL_FORWARD_ONLY), len, trip, lane);
+    else
+      stream_unit<U, Op, true, true>(g.recv + src, g.acc + dst, g.out + out, len, trip, lane);
+  }
+}
+
+// ---- several sources per destination chunk ---------------------------------------------
+//
+// Section 2.1: the kernel reduces transport buffers "from multiple sender GPUs" into the
+// tensor buffer.  A gather record names up to UCCL_MAX_SOURCES receive slots for one
+// destination chunk; they are folded into the accumulator's value in the order listed, so
+// the floating-point result is fixed by the record, not by arrival timing.  The accumulator
+// is read and written once per chunk however many sources there are.  Same tile / unit
+// dealing as the flat shape; per unit a wavefront keeps the running value in registers
+// (widened to binary32 for 16-bit types); sources are loaded in batches, all loads of a
+// batch in flight before the folds, which then run in the listed order.
+struct GatherArgs {
+  char* acc;
+  char* out;
+  const char* recv;
+  const uccl_gather_desc* descs;
+  uint32_t* bitmap;
+  uint32_t* rejected;
+  Extents ext;
+  uint32_t n_descs;
+};
+
+template <int T>
+struct GatherTile {
+  uint64_t dst[T], out[T];
+  uint64_t src[T][UCCL_MAX_SOURCES];
+  uint32_t len[T], n_src[T];
+  uint32_t first[T + 1];
+  uint32_t count;
+};
+
+template <int NT, int T, int U, class Op>
+__global__ void __launch_bounds__(NT) chunk_gather_kernel(const GatherArgs g) {
+  static_assert(T >= 1 && T <= 64, "one wavefront dedups the tile");
+  constexpr uint32_t kUnit = 64u * U;
+  constexpr uint32_t kBatch = UCCL_GATHER_BATCH;
+  __shared__ GatherTile<T> s;
+  const uint32_t tid = threadIdx.x;
+  if (tid < 64) {
+    const uint64_t k = static_cast<uint64_t>(blockIdx.x) * T + tid;
+    bool win = false;
+    uint64_t dst = 0, out = 0;
+    uint32_t len = 0, n_src = 0;
+    const uccl_gather_desc* d = g.descs + k;
+    if (tid < T && k < g.n_descs) {
+      const u32x4* p = reinterpret_cast<const u32x4*>(d);
+      const u32x4 lo = p[0], hi = p[1];
+      dst = lo.x | (static_cast<uint64_t>(lo.y) << 32);
+      out = lo.z | (static_cast<uint64_t>(lo.w) << 32);
+      len = hi.x;
+      const uint32_t seq = hi.y;
+      n_src = hi.z;
+      const bool fwd = out != UCCL_NO_FORWARD;
+      const uint64_t out_at = out & ~UCCL_FORWARD_ONLY;
+      bool ok = seq < g.ext.n_bits && (dst & 15u) == 0 && len % Op::kEs == 0 && n_src >= 1 &&
+                n_src <= UCCL_MAX_SOURCES && dst <= g.ext.acc_bytes && len <= g.ext.acc_bytes - dst;
+      if (fwd)
+        ok = ok && g.out != nullptr && (out_at & 15u) == 0 && out_at <= g.ext.out_bytes &&
+             len <= g.ext.out_bytes - out_at;
+      if (ok) {
+        for (uint32_t j = 0; j < n_src; ++j) {
+          const uint64_t so = d->src_off[j];
+          ok = ok && (so & 15u) == 0 && so <= g.ext.recv_bytes && len <= g.ext.recv_bytes - so;
+        }
+      }
+      if (ok) {
+        const uint32_t bit = 1u << (seq & 31u);
+        const uint32_t old = atomicOr(g.bitmap + (seq >> 5), bit);
+        win = (old & bit) == 0;
+      } else if (g.rejected != nullptr) {
+        atomicAdd(g.rejected, 1u);
+      }
+    }
+    const uint64_t winners = __ballot(win);
+    const uint32_t pos = __popcll(winners & ((1ull << tid) - 1ull));
+    const uint32_t count = __popcll(winners);
+    if (win) {
+      s.dst[pos] = dst;
+      s.out[pos] = out;
+      s.len[pos] = len;
+      s.n_src[pos] = n_src;
+      for (uint32_t j = 0; j < n_src; ++j) s.src[pos][j] = d->src_off[j];
+    }
+    if (tid == 0) s.count = count;
+    const uint32_t vecs = (len >> 4) + ((len & 15u) != 0u ? 1u : 0u);  // no overflow for len up to 2^32 - 1
+    const uint32_t units = win ? (vecs + kUnit - 1u) / kUnit : 0u;
+    uint32_t incl = units;
+#pragma unroll
+    for (uint32_t dlt = 1; dlt < 64; dlt <<= 1) {
+      const uint32_t below = __shfl_up(incl, dlt, 64);
+      if (tid >= dlt) incl += below;
+    }
+    if (win) s.first[pos] = incl - units;
+    if (tid == 63) s.first[count] = incl;
+  }
+  __syncthreads();
+
+  const uint32_t count = s.count;
+  const uint32_t total = s.first[count];
+  const uint32_t wave = tid >> 6, lane = tid & 63u;
+  for (uint32_t u = wave; u < total; u += NT / 64) {
+    uint32_t w = 0;
+    if (T > 1) {
+      const bool mine = lane < count && s.first[lane] <= u && u < s.first[lane + 1];
+      w = __ffsll(static_cast<unsigned long long>(__ballot(mine))) - 1;
+    }
+    w = __builtin_amdgcn_readfirstlane(w);
+    const uint32_t v0 = (u - __builtin_amdgcn_readfirstlane(s.first[w])) * kUnit;
+    const uint64_t dst = wave_uniform(s.dst[w]);
+    const uint64_t out = wave_uniform(s.out[w]);
+    const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
+    const uint32_t n_src = __builtin_amdgcn_readfirstlane(s.n_src[w]);
+    const uint32_t nvec = len >> 4;
+    const bool fwd = out != UCCL_NO_FORWARD;
+    const bool keep = !(fwd && (out & UCCL_FORWARD_ONLY));
+    u32x4* ap = reinterpret_cast<u32x4*>(g.acc + dst) + v0 + lane;
+    u32x4* op = reinterpret_cast<u32x4*>(g.out + (out & ~UCCL_FORWARD_ONLY)) + v0 + lane;
+    bool live[U];
+    typename Op::State st[U][4];
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      live[i] = v0 + lane + i * 64 < nvec;
+      u32x4 a = {0u, 0u, 0u, 0u};
+      if (live[i]) a = ap[i * 64];
+      st[i][0] = Op::open(a.x); st[i][1] = Op::open(a.y); st[i][2] = Op::open(a.z); st[i][3] = Op::open(a.w);
+    }
+    // sources in batches: all loads of a batch are issued before the first fold waits
+    for (uint32_t j0 = 0; j0 < n_src; j0 += kBatch) {
+      u32x4 rv[kBatch][U];
+#pragma unroll
+      for (uint32_t b = 0; b < kBatch; ++b) {
+        if (j0 + b < n_src) {
+          const u32x4* rp = reinterpret_cast<const u32x4*>(g.recv + wave_uniform(s.src[w][j0 + b])) + v0 + lane;
+#pragma unroll
+          for (int i = 0; i < U; ++i) {
+            rv[b][i] = u32x4{0u, 0u, 0u, 0u};
+            if (live[i]) rv[b][i] = __builtin_nontemporal_load(rp + i * 64);
+          }
+        }
+      }
+#pragma unroll
+      for (uint32_t b = 0; b < kBatch; ++b) {
+        if (j0 + b < n_src) {
+#pragma unroll
+          for (int i = 0; i < U; ++i) {
+            Op::fold(st[i][0], rv[b][i].x); Op::fold(st[i][1], rv[b][i].y);
+            Op::fold(st[i][2], rv[b][i].z); Op::fold(st[i][3], rv[b][i].w);
+          }
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < U; ++i) {
+      if (!live[i]) continue;
+      u32x4 t;
+      t.x = Op::close(st[i][0]); t.y = Op::close(st[i][1]); t.z = Op::close(st[i][2]); t.w = Op::close(st[i][3]);
+      if (keep) ap[i * 64] = t;
+      if (fwd) __builtin_nontemporal_store(t, op + i * 64);
+    }
+    // the last len % 16 bytes, element by element, by the unit that holds vector index nvec
+    const uint32_t rem = len & 15u;
+    if (rem && nvec >= v0 && nvec < v0 + kUnit && lane < rem / Op::kEs) {
+      const uint64_t off = (static_cast<uint64_t>(nvec) << 4) + lane * Op::kEs;
+      uint32_t a_el;
+      if constexpr (Op::kEs == 4) a_el = *reinterpret_cast<const uint32_t*>(g.acc + dst + off);
+      else a_el = *reinterpret_cast<const uint16_t*>(g.acc + dst + off);
+      typename Op::State t = Op::open(a_el);
+      for (uint32_t j = 0; j < n_src; ++j) {
+        const char* rp = g.recv + wave_uniform(s.src[w][j]) + off;
+        uint32_t r_el;
+        if constexpr (Op::kEs == 4) r_el = *reinterpret_cast<const uint32_t*>(rp);
+        else r_el = *reinterpret_cast<const uint16_t*>(rp);
+        Op::fold(t, r_el);
+      }
+      const uint32_t res = Op::close(t);
+      if constexpr (Op::kEs == 4) {
+        if (keep) *reinterpret_cast<uint32_t*>(g.acc + dst + off) = res;
+        if (fwd) *reinterpret_cast<uint32_t*>(g.out + (out & ~UCCL_FORWARD_ONLY) + off) = res;
+      } else {
+        if (keep) *reinterpret_cast<uint16_t*>(g.acc + dst + off) = static_cast<uint16_t>(res);
+        if (fwd) *reinterpret_cast<uint16_t*>(g.out + (out & ~UCCL_FORWARD_ONLY) + off) = static_cast<uint16_t>(res);
+      }
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256) fill_words_kernel(uint32_t* p, uint64_t n, uint32_t v) {
+  for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x; i < n;
+       i += static_cast<uint64_t>(gridDim.x) * 256)
+    p[i] = v;
+}
+
+}  // namespace
