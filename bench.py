@@ -68,6 +68,17 @@ def source_hash():
     return h.hexdigest()[:16]
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def call_stats(descs, op):
     """(unique chunks, payload bytes, algorithmic bytes) of one call's record list, by the
     single-pass byte model: a reduce reads slot + accumulator, a copy reads the slot; every
@@ -682,6 +693,7 @@ def main():
                 exp = (eacc, eout[:w.out_bytes], oracle.pack_bitmap(seen))
         result["cpu_baseline"] = {
             "value": round(payload * reps / cpu_t / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "cpu": cpu_model(),
             "sample": f"the whole step ({len(calls)} calls, {arrivals} arrivals, {payload} payload bytes) x {reps} repetitions, {cpu_t:.1f} s",
         }
         # the same definition on all host cores of this machine's share (serial dedup, then the unique
