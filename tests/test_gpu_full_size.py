@@ -136,3 +136,27 @@ def test_16bit_every_pair(gpu_lib, dtype, op):
                                    f"r={r_np[bad[0]]:#06x} got={got[bad[0]]:#06x} exp={exp[bad[0]]:#06x}")
         if b % 8 == 7:
             say(f"bf16 pairs: block {b + 1}/{65536 // blk} at {time.time() - t0:.0f}s")
+
+
+def test_direct_reduce_scatter_full_size(gpu_lib):
+    """The multi-source fold at the size bench.py times it (R = 8, 1 GiB fp32: seven senders'
+    128 MiB copies folded into this rank's segment, 128 KiB chunks), every element against the oracle."""
+    t0 = time.time()
+    w = wl.direct_reduce_scatter("direct-reduce-scatter-1GiB-f32", 1, R=8, M=1 << 30, C=128 << 10, dtype=F32,
+                                 paths=64, dup=0.005, dist="uniform")
+    ph = w.phases[0]
+    say(f"direct-rs: built in {time.time() - t0:.1f}s, {len(ph.descs)} records")
+    eacc, seen = w.acc.copy(), oracle.new_seen(w.n_bits)
+    assert oracle.reduce_gather(eacc, None, w.recv_stage, ph.descs, seen, F32, SUM) == ph.n_unique
+    say(f"direct-rs: oracle done at {time.time() - t0:.1f}s")
+    acc, recv = to_dev(w.acc), to_dev(w.recv_stage)
+    bitmap = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
+    gpu_lib.uccl_set_launch_shape(0)
+    gpu_lib.uccl_set_chunk_hint(128 << 10)
+    try:
+        gpu_lib.uccl_chunk_reduce_gather(acc, None, recv, to_dev(ph.descs), len(ph.descs), bitmap, F32, SUM)
+        torch.cuda.synchronize()
+    finally:
+        gpu_lib.uccl_set_chunk_hint(0)
+    assert_same(bitmap.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap")
+    assert_same(acc.cpu().numpy().view(np.float32), eacc, "acc")
