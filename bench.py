@@ -46,7 +46,7 @@ WORKLOADS = {
     "config2": "allreduce rank share: R=16, 256 MiB bf16 normal(0,1), 32 KiB chunks, 256 paths, window 1024, 2% duplicates",
     "config3": "reduce-scatter rank share: R=8, 1 GiB fp32 uniform[-1,1], 128 KiB chunks, 64 paths, window 256, 0.5% duplicates",
     "config4": "all-to-all dispatch: 7 sources x U[0,16 MiB] of 14336-byte bf16 rows, 16 KiB chunks, 128 paths, 1% duplicates",
-    "config5": "small allreduces: fp32, 64 KiB-1 MiB log-uniform, R=8, 4 KiB chunks, 32 paths, 3% duplicates, 128 messages per call",
+    "config5": "small allreduces: 10,000 messages, fp32, 64 KiB-1 MiB log-uniform, R=8, 4 KiB chunks, 32 paths, 3% duplicates, 128 messages per call",
     "direct-rs": "direct (one-hop) reduce-scatter: R=8, 1 GiB fp32, 7 senders' copies of this rank's 128 MiB segment "
                  "folded in rank order by gather records, 128 KiB chunks, 64 paths per sender, 0.5% duplicates",
     "config5-single": "small allreduces, one message at a time (two calls per message)",
@@ -376,7 +376,7 @@ def main():
     ap.add_argument("--workload", default="config2", choices=sorted(WORKLOADS))
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--sets", type=int, default=4, help="buffer sets the steps rotate over")
-    ap.add_argument("--messages", type=int, default=1000, help="config5: number of messages")
+    ap.add_argument("--messages", type=int, default=10000, help="config5: number of messages")
     ap.add_argument("--streams", type=int, default=1,
                     help="config5: issue consecutive message batches round-robin on this many streams "
                          "(batches are independent of each other; the two calls of a batch stay ordered)")
