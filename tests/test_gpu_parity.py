@@ -3,6 +3,7 @@ seeded inputs, element by element.  Integer, placement, dedup and copy results m
 bit-exact; fp32 combine 0 ulp; bf16 SUM is allowed 1 ulp by the stated target but is
 asserted bit-exact here because both sides round fp32 -> bf16 once, to nearest even.
 """
+import os
 import sys
 
 import numpy as np
@@ -695,9 +696,10 @@ def test_random_streams_all_features(gpu_lib, dtype, shape):
     from randstream import random_stream
     gpu_lib.uccl_set_launch_shape(shape)
     try:
-        for seed in range(50):
+        base = int(os.environ.get("UCCL_TEST_SEED_BASE", "7000"))      # other seeds and more streams for a soak run
+        for seed in range(int(os.environ.get("UCCL_TEST_STREAMS", "50"))):
             for op in (SUM, MAX, COPY, PROD):
-                s = random_stream(7000 + 100 * dtype + 17 * seed + op, dtype, op, max_chunks=48, max_len=9000)
+                s = random_stream(base + 100 * dtype + 17 * seed + op, dtype, op, max_chunks=48, max_len=9000)
                 gpu_lib.uccl_set_chunk_hint([0, 1024, 4096, 65536][seed % 4])
                 acc, recv = to_dev(s["acc"]), to_dev(s["recv"])
                 out = torch.full((s["out_bytes"],), 0x3C, dtype=torch.uint8, device="cuda")
