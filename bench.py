@@ -537,6 +537,10 @@ def main():
                             hbm_frac=round(c["algo_bytes"] / (t.mean() * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)))
     dom = max(kernels, key=lambda k: k["algorithmic_bytes"])
 
+    def timed_ms(i):
+        evs = timed.get(i) or []
+        return float(np.mean([a.elapsed_time(b) for a, b in evs])) if evs else 0.0
+
     # receiver feedback (cumulative ack + selective ranges) read off this workload's bitmap
     report = torch.zeros(32 + 16 * 64, dtype=torch.uint8, device="cuda")
     evs = []
@@ -650,6 +654,9 @@ def main():
             "avg_launch_ms": dom["avg_ms"] if per_kernel else None,
         },
         "kernels": kernels if per_kernel else [],
+        # the reduce phase alone (its call's unique payload over its kernel's own duration)
+        "reduce_phase_payload_GBps": (round(calls[by_op[0]]["payload_bytes"] / (timed_ms(by_op[0]) * 1e-3) / 1e9, 1)
+                                      if per_kernel and 0 in by_op and timed_ms(by_op[0]) > 0 else None),
         "stream_ceiling": stream_ceiling,
         "dedup_report": {"n_bits": w.n_bits, "median_us": round(report_us, 2),
                          "what": "ack_report_kernel: cumulative ack, applied count, selective ranges"},
