@@ -140,3 +140,30 @@ def test_host_side_feed_batches_messages(gpu_lib, capacity, poll):
         oracle.apply(eacc, eout, w.recv_stage, m["ag"], seen, F32, COPY)
     acc, out, bm, _ = run.results()
     assert_same(bm, oracle.pack_bitmap(seen), "bitmap"); assert_same(acc, eacc, "acc"); assert_same(out, eout, "out")
+
+
+def test_host_side_feed_large_hand_over(gpu_lib):
+    """One hand-over of tens of thousands of records per lane: large batches are copied to device
+    memory before the kernel reads them (small ones are read from the pinned slot directly);
+    same result either way."""
+    w, msgs = wl.config5(seed=9, n_msgs=220)
+    run = DeviceRun(w, guard=0)
+    gpu_lib.uccl_set_chunk_hint(4096)
+    feed = gpu_lib.uccl_feed_create(run.acc, run.out, run.recv, run.bitmap, F32, SUM, COPY, 1 << 17, 2)
+    try:
+        for m in msgs:
+            gpu_lib.uccl_feed_push(feed, 0, np.ascontiguousarray(m["rs"]))
+            gpu_lib.uccl_feed_push(feed, 1, np.ascontiguousarray(m["ag"]))
+        gpu_lib.uccl_feed_sync(feed)
+        stats = gpu_lib.uccl_feed_get_stats(feed)
+    finally:
+        gpu_lib.uccl_feed_destroy(feed)
+        gpu_lib.uccl_set_chunk_hint(0)
+    assert stats["flushes"] == 1 and stats["max_batch"] > 2 * 16384, stats  # both lanes above the direct-read limit
+    eacc, eout, seen = w.acc.copy(), np.zeros(w.out_bytes, dtype=np.uint8), oracle.new_seen(w.n_bits)
+    for m in msgs:
+        oracle.apply(eacc, eout, w.recv_stage, m["rs"], seen, F32, SUM)
+    for m in msgs:
+        oracle.apply(eacc, eout, w.recv_stage, m["ag"], seen, F32, COPY)
+    acc, out, bm, _ = run.results()
+    assert_same(bm, oracle.pack_bitmap(seen), "bitmap"); assert_same(acc, eacc, "acc"); assert_same(out, eout, "out")
