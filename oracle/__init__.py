@@ -38,7 +38,11 @@ class OraclePrecondition(ValueError):
 
 
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (always when force, else when stale)."""
+    """Compile the oracle with gcc (always when force, else when stale).  CHUNK_ORACLE_LIB in the
+    environment names another, already built library to load instead: the mutation test uses it to
+    run the pins against copies of the oracle with a mistake planted."""
+    if os.environ.get("CHUNK_ORACLE_LIB"):
+        return os.environ["CHUNK_ORACLE_LIB"]
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < max(
         os.path.getmtime(_SRC), os.path.getmtime(_SRC_THREADED), os.path.getmtime(os.path.join(_DIR, "chunk_oracle.h")))
     if force or stale:
