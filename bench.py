@@ -68,6 +68,16 @@ def source_hash():
     return h.hexdigest()[:16]
 
 
+def device_info(torch):
+    """What the runtime says about the GPU the numbers were taken on (machines of one model differ)."""
+    p = torch.cuda.get_device_properties(0)
+    info = {"name": p.name, "compute_units": p.multi_processor_count, "memory_GiB": round(p.total_memory / 2**30, 1)}
+    for key in ("clock_rate", "memory_clock_rate", "memory_bus_width", "L2_cache_size", "gcnArchName"):
+        if hasattr(p, key):
+            info[key] = getattr(p, key)
+    return info
+
+
 def cpu_model():
     try:
         with open("/proc/cpuinfo") as f:
@@ -716,6 +726,7 @@ def main():
         "reduce_phase_payload_GBps": (round(calls[by_op[0]]["payload_bytes"] / (timed_ms(by_op[0]) * 1e-3) / 1e9, 1)
                                       if per_kernel and 0 in by_op and timed_ms(by_op[0]) > 0 else None),
         "stream_ceiling": stream_ceiling,
+        "device": device_info(torch),
         "dedup_report": {"n_bits": w.n_bits, "median_us": round(report_us, 2),
                          "what": "ack_report_kernel: cumulative ack, applied count, selective ranges"},
         "message_status": {"slots": 128, "bits_per_slot": 256, "median_us": round(status_us, 2),
@@ -1128,6 +1139,7 @@ def main():
         "reduce_phase_payload_GBps": (round(calls[by_op[0]]["payload_bytes"] / (timed_ms(by_op[0]) * 1e-3) / 1e9, 1)
                                       if per_kernel and 0 in by_op and timed_ms(by_op[0]) > 0 else None),
         "stream_ceiling": stream_ceiling,
+        "device": device_info(torch),
         "dedup_report": {"n_bits": w.n_bits, "median_us": round(report_us, 2),
                          "what": "ack_report_kernel: cumulative ack, applied count, selective ranges"},
         "message_status": {"slots": 128, "bits_per_slot": 256, "median_us": round(status_us, 2),
