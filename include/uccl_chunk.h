@@ -19,8 +19,9 @@
  *     write   - acc[dst+i] = t[i]; and out_stage[out+i] = t[i] when the record forwards
  *
  * All buffer pointers are DEVICE pointers owned by the caller (the data-path calls never
- * allocate, free or keep them; only the optional uccl_feed object owns memory); `stream` is a hipStream_t passed as void* (NULL =
- * the null stream).  Every call only enqueues work on `stream` and returns: no host
+ * allocate, free or keep them; only the optional uccl_feed object owns memory); `stream`
+ * is a hipStream_t passed as void* (NULL = the null stream).  Every call only enqueues
+ * work on `stream` and returns: no host
  * synchronisation, no host read of device memory.  Records and buffers must stay valid
  * until the stream has passed the call; receive slots may be recycled after that point
  * (the paper's irecv_free_ptrs moment, Section 5).
