@@ -34,11 +34,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 # source it was measured on, identified by the hash of the HIP source files.
 MEASURED_TRAFFIC = {
     # (workload, source_hash() of the files under csrc/): bytes per launch
-    ("config2", "8426488e76ddd234"): 1008010977,
-    ("config3", "8426488e76ddd234"): 3625079117,
-    ("direct-rs", "8426488e76ddd234"): 1208243707,
-    ("config1", "8426488e76ddd234"): 14752641,
-    ("config4", "8426488e76ddd234"): 107500355,
+    ("config2", "8426488e76ddd234"): 1008004812,
+    ("config3", "8426488e76ddd234"): 3625074368,
+    ("direct-rs", "8426488e76ddd234"): 1208242841,
+    ("config1", "8426488e76ddd234"): 14752659,
+    ("config4", "8426488e76ddd234"): 107503647,
 }
 
 WORKLOADS = {
