@@ -111,7 +111,9 @@ typedef struct uccl_extents {
  * or which forwards although out_stage is NULL, is skipped (its bit stays clear).
  *
  * Returns UCCL_OK (also for n_descs == 0, which enqueues nothing) or a negative code;
- * on error nothing has been enqueued.
+ * on error nothing has been enqueued.  One launch covers the whole call with one workgroup
+ * per 1..32 records; a record count whose workgroup count exceeds what the device accepts
+ * in one launch comes back as UCCL_ELAUNCH (split the call).
  */
 int uccl_chunk_apply(void* acc, void* out_stage, const void* recv_stage,
                      const uccl_chunk_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
