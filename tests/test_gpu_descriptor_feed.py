@@ -167,3 +167,58 @@ def test_host_side_feed_large_hand_over(gpu_lib):
         oracle.apply(eacc, eout, w.recv_stage, m["ag"], seen, F32, COPY)
     acc, out, bm, _ = run.results()
     assert_same(bm, oracle.pack_bitmap(seen), "bitmap"); assert_same(acc, eacc, "acc"); assert_same(out, eout, "out")
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_host_side_feed_random_push_pattern(gpu_lib, seed):
+    """Pushes of random sizes into either lane, polls, flushes and syncs in random order, a slot
+    capacity that many pushes overflow: every record is handed over exactly once, whatever the
+    pattern.  Lane 0 reduces into one half of the accumulator, lane 1 copies into the other, so
+    the two lanes never depend on each other and any interleaving has the same result."""
+    from synth import payload as pl
+    from synth.layout import DESC, NO_FORWARD
+    g = pl.rng(900 + seed, 1)
+    C_, n = 2048, 3000
+    acc = pl.uniform_f32(900 + seed, 2, 2 * n * C_ // 4)
+    recv = pl.uniform_f32(900 + seed, 3, 2 * n * C_ // 4)
+    lanes = []
+    for lane in (0, 1):
+        arrivals = np.concatenate([g.permutation(n), g.integers(0, n, n // 10)])     # 10 % retransmitted
+        d = np.zeros(len(arrivals), dtype=DESC)
+        d["seq"] = arrivals + lane * n
+        d["src_off"] = (arrivals + lane * n).astype(np.uint64) * C_
+        d["dst_off"] = d["src_off"]
+        d["out_off"] = np.where(arrivals % 3 == 0, NO_FORWARD, d["src_off"])
+        d["len"] = C_ - 16 * (arrivals % 5)
+        lanes.append(d)
+    d_acc, d_recv = to_dev(acc), to_dev(recv)
+    d_out = torch.zeros(acc.nbytes, dtype=torch.uint8, device="cuda")
+    bitmap = torch.zeros((2 * n + 31) // 32, dtype=torch.int32, device="cuda")
+    feed = gpu_lib.uccl_feed_create(d_acc, d_out, d_recv, bitmap, F32, SUM, COPY, 257, 3)
+    at = [0, 0]
+    try:
+        while at[0] < len(lanes[0]) or at[1] < len(lanes[1]):
+            lane = int(g.integers(0, 2))
+            if at[lane] >= len(lanes[lane]):
+                lane = 1 - lane
+            k = int(min(g.integers(0, 700), len(lanes[lane]) - at[lane]))
+            gpu_lib.uccl_feed_push(feed, lane, np.ascontiguousarray(lanes[lane][at[lane]:at[lane] + k]))
+            at[lane] += k
+            what = int(g.integers(0, 6))
+            if what == 0:
+                gpu_lib.uccl_feed_flush(feed)
+            elif what == 1:
+                gpu_lib.uccl_feed_sync(feed)
+            elif what < 5:
+                gpu_lib.uccl_feed_poll(feed)
+        gpu_lib.uccl_feed_sync(feed)
+        stats = gpu_lib.uccl_feed_get_stats(feed)
+    finally:
+        gpu_lib.uccl_feed_destroy(feed)
+    assert stats["records"] == len(lanes[0]) + len(lanes[1]) and stats["max_batch"] <= 2 * 257
+    eacc, eout, seen = acc.copy(), np.zeros(acc.nbytes, dtype=np.uint8), oracle.new_seen(2 * n)
+    assert oracle.apply(eacc, eout, recv, lanes[0], seen, F32, SUM) == n
+    assert oracle.apply(eacc, eout, recv, lanes[1], seen, F32, COPY) == n
+    assert_same(bitmap.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap")
+    assert_same(d_acc.cpu().numpy().view(np.float32), eacc, "acc")
+    assert_same(d_out.cpu().numpy(), eout, "out")
