@@ -506,6 +506,21 @@ def test_message_status(gpu_lib, bits_per_slot, n_slots):
                 assert est[::5, 2].all() and not ewords.reshape(n_slots, -1)[::5].any()
 
 
+def test_message_status_into_pinned_host_memory(gpu_lib):
+    """The status rows may live in pinned host memory: the control path reads them without a copy."""
+    g = pl.rng(55, 5)
+    n_slots, per = 128, 256
+    counts = g.integers(0, per + 1, n_slots).astype(np.uint32)
+    bits = (g.random((n_slots, per)) < 0.97).astype(np.uint8)
+    bits[::2] = 1
+    words = np.packbits(bits.reshape(-1), bitorder="little").view(np.uint32).copy()
+    est = oracle.message_status(words.copy(), counts, per)
+    st = torch.zeros(n_slots * 4, dtype=torch.int32, pin_memory=True)
+    gpu_lib.uccl_message_status(to_dev(words), to_dev(counts), n_slots, per, st, False)
+    torch.cuda.synchronize()
+    assert np.array_equal(st.numpy().view(np.uint32).reshape(-1, 4), est)
+
+
 def test_message_window_over_small_allreduces(gpu_lib):
     """A connection's message window driven the way Section 3.1 lays it out: a message has at
     most 256 chunks and sits in one of 128 slots, the bit index of a chunk is slot * 256 + chunk
