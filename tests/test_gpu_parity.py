@@ -775,3 +775,34 @@ def test_same_records_on_two_streams_apply_once(gpu_lib):
         acc, out, bm, rej = run.results()
         assert rej == 0 and np.all(acc == one), f"trial {trial}: {np.count_nonzero(acc != one)} elements not exactly 1"
         assert np.array_equal(out.view(np.uint16), acc) and sum(int(x).bit_count() for x in bm) == n
+
+
+@pytest.mark.parametrize("name,dtype", [("bf16_sum_cases.txt", BF16), ("f16_sum_cases.txt", F16)])
+def test_hand_derived_rounding_cases_on_the_gpu(gpu_lib, name, dtype):
+    """The hand-derived tie / overflow / subnormal cases of tests/golden, through the GPU path:
+    one record whose elements are the cases (both operand orders), against the expected bits
+    written in the file, not against the oracle."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", name)
+    rows = [l.split() for l in open(path) if l.strip() and l[0] != "#"]
+    a = np.array([int(x, 16) for x, _, _ in rows] + [int(y, 16) for _, y, _ in rows], dtype=np.uint16)
+    r = np.array([int(y, 16) for _, y, _ in rows] + [int(x, 16) for x, _, _ in rows], dtype=np.uint16)
+    e = np.array([int(z, 16) for _, _, z in rows] * 2, dtype=np.uint16)
+    pad = (-len(a)) % 8                                  # buffers in whole 16-byte vectors; the record is not
+    acc = to_dev(np.concatenate([a, np.zeros(pad, np.uint16)]))
+    recv = to_dev(np.concatenate([r, np.zeros(pad, np.uint16)]))
+    out = torch.zeros_like(acc)
+    d = np.zeros(1, dtype=DESC)
+    d[0] = (0, 0, 0, 2 * len(a), 0)
+    bitmap = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for shape in SHAPES:
+        gpu_lib.uccl_set_launch_shape(shape)
+        try:
+            acc_k = acc.clone()
+            bitmap.zero_()
+            gpu_lib.uccl_chunk_apply(acc_k, out, recv, to_dev(d), 1, bitmap, dtype, SUM)
+            torch.cuda.synchronize()
+        finally:
+            gpu_lib.uccl_set_launch_shape(0)
+        got = acc_k.cpu().numpy().view(np.uint16)[:len(a)]
+        assert np.array_equal(got, e), (shape, [f"{x:04X}" for x in got], [f"{x:04X}" for x in e])
+        assert np.array_equal(out.cpu().numpy().view(np.uint16)[:len(a)], e)

@@ -318,6 +318,15 @@ def test_bf16_golden_ties():
         assert oracle.combine_bf16(int(r, 16), int(a, 16), SUM) == int(e, 16), (r, a, e)
 
 
+def test_f16_golden_ties():
+    """Hand-derived binary16 cases: ties, overflow threshold, subnormals."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "f16_sum_cases.txt")) if l.strip() and l[0] != "#"]
+    assert len(rows) >= 10
+    for a, r, e in rows:
+        assert oracle.combine_f16(int(a, 16), int(r, 16), SUM) == int(e, 16), (a, r, e)
+        assert oracle.combine_f16(int(r, 16), int(a, 16), SUM) == int(e, 16), (r, a, e)
+
+
 def test_bf16_sum_is_f32_add_then_nearest_even():
     g = pl.rng(8, 8)
     a = pl.normal_bf16(8, 1, 50000)
