@@ -101,6 +101,81 @@ def test_bf16_accumulates_in_fp32_and_rounds_once():
     assert not np.array_equal(got, per_hop)
 
 
+def _widen16(dtype):
+    """uint16 patterns -> float32 values, through numpy's own types (exact for both formats)."""
+    if dtype == BF16:
+        return lambda h: (h.astype(np.uint32) << 16).view(np.float32)
+    return lambda h: h.view(np.float16).astype(np.float32)
+
+
+def _fold16(w, step):
+    """Per destination chunk: fp32 running array seeded from acc, `step(running, source_bits)` per
+    source in the record's order.  Returns {chunk start element: (n, running)}."""
+    wide = _widen16(w.dtype)
+    runs, done = {}, set()
+    for d in w.phases[0].descs:
+        if int(d["seq"]) in done:
+            continue
+        done.add(int(d["seq"]))
+        n, t = d["len"] // 2, d["dst_off"] // 2
+        val = wide(w.acc[t:t + n])
+        for so in d["src_off"][:d["n_src"]]:
+            val = step(val, w.recv_stage[so // 2: so // 2 + n])
+        runs[int(t)] = (int(n), val)
+    return runs
+
+
+@pytest.mark.parametrize("dtype", [BF16, F16])
+def test_16bit_product_fold_runs_in_fp32_and_rounds_once(dtype):
+    """numpy multiplies fp32 arrays source by source (one rounding each, in fp32); the 16-bit result is
+    that running product rounded once: nearest-even by the exact definition for bf16, numpy's own
+    binary16 conversion for f16.  A fold that adds, or that rounds after every source, differs."""
+    w = make(dtype, dist="normal" if dtype == BF16 else "uniform", op=PROD, R=6)
+    wide = _widen16(dtype)
+    narrow = nearest_even_bf16 if dtype == BF16 else (lambda f: f.astype(np.float16).view(np.uint16))
+    with np.errstate(over="ignore", under="ignore"):
+        runs = _fold16(w, lambda val, r: val * wide(r))
+        hops = _fold16(w, lambda val, r: wide(narrow(val * wide(r))))
+    got = run_oracle(w)[0]
+    expect, per_hop = w.acc.copy(), w.acc.copy()
+    for t, (n, val) in runs.items():
+        expect[t:t + n] = narrow(val)
+        per_hop[t:t + n] = narrow(hops[t][1])
+    assert np.array_equal(got, expect)
+    assert not np.array_equal(got, per_hop), "the inputs must tell one rounding from a rounding per source"
+    assert len(np.unique(got)) > 100, "products neither all vanish nor all overflow"
+
+
+@pytest.mark.parametrize("dtype", [BF16, F16])
+@pytest.mark.parametrize("op,npf", [(MAX, np.maximum), (MIN, np.minimum)])
+def test_16bit_selection_fold_against_numpy(dtype, op, npf):
+    """Selection is exact: the result is numpy's maximum / minimum over the widened values, and it
+    is one of the input patterns unchanged."""
+    w = make(dtype, dist="normal" if dtype == BF16 else "uniform", op=op, R=7)
+    wide = _widen16(dtype)
+    runs = _fold16(w, lambda val, r: npf(val, wide(r)))
+    got = run_oracle(w)[0]
+    expect = w.acc.copy()
+    for t, (n, val) in runs.items():
+        # val holds exactly representable 16-bit values: narrowing it back loses nothing
+        expect[t:t + n] = (val.view(np.uint32) >> 16).astype(np.uint16) if dtype == BF16 else val.astype(np.float16).view(np.uint16)
+        assert np.array_equal(wide(expect[t:t + n]), val)
+    assert np.array_equal(got, expect)
+    assert not np.array_equal(got, w.acc), "some source beats the local value somewhere"
+    last = w.acc.copy()   # a fold that merely copies the last source would give this instead
+    for d in w.phases[0].descs:
+        n, t, so = d["len"] // 2, d["dst_off"] // 2, d["src_off"][d["n_src"] - 1] // 2
+        last[t:t + n] = w.recv_stage[so:so + n]
+    assert not np.array_equal(got, last)
+
+
+def test_int32_min_fold_against_numpy():
+    w = make(I32, R=5, op=MIN)
+    got = run_oracle(w)[0]
+    assert np.array_equal(got, numpy_fold(w, np.minimum))
+    assert not np.array_equal(got, numpy_fold(w, np.maximum))
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16, F16, I32])
 def test_integer_inputs_give_the_exact_sum(dtype):
     es = ELEM_SIZE[dtype]

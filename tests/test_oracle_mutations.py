@@ -79,6 +79,36 @@ MISTAKES = [
      PINS + "test_ack_report_hand_cases"),
     ("ack report: inclusive range end", "ranges[2 * runs + 1] = s; }", "ranges[2 * runs + 1] = s - 1; }", False,
      PINS + "test_ack_report_hand_cases"),
+    ("multi-source 16-bit product adds", "f = op == ORC_SUM ? f + fr : f * fr;", "f = f + fr;", False,
+     GATHER + "test_16bit_product_fold_runs_in_fp32_and_rounds_once"),
+    ("multi-source 16-bit product rounds per source", "f = op == ORC_SUM ? f + fr : f * fr;",
+     "f = op == ORC_SUM ? f + fr : f * fr; f = dtype == ORC_BF16 ? bf16_widen(orc_f32_to_bf16(f)) : orc_f16_to_f32(orc_f32_to_f16(f));",
+     False, GATHER + "test_16bit_product_fold_runs_in_fp32_and_rounds_once"),
+    ("multi-source 16-bit max / min copies the source",
+     "t = dtype == ORC_BF16 ? orc_combine_bf16(t, r, op) : orc_combine_f16(t, r, op);", "t = r;", False,
+     GATHER + "test_16bit_selection_fold_against_numpy"),
+    ("multi-source 16-bit min is max",
+     "t = dtype == ORC_BF16 ? orc_combine_bf16(t, r, op) : orc_combine_f16(t, r, op);",
+     "t = dtype == ORC_BF16 ? orc_combine_bf16(t, r, ORC_MAX) : orc_combine_f16(t, r, ORC_MAX);", False,
+     GATHER + "test_16bit_selection_fold_against_numpy"),
+    ("multi-source int32 min is max",
+     "t = orc_combine_i32(t, ((const int32_t*)((const char*)recv_stage + d->src_off[j]))[i], op);",
+     "t = orc_combine_i32(t, ((const int32_t*)((const char*)recv_stage + d->src_off[j]))[i], op == ORC_MIN ? ORC_MAX : op);",
+     False, GATHER + "test_int32_min_fold_against_numpy"),
+    ("bf16 narrowing has no NaN branch",
+     "if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);", ";", False,
+     PINS + "test_narrowing_a_nan_gives_a_quiet_nan_of_the_same_sign"),
+    ("bf16 NaN not quieted",
+     "if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0040u);",
+     "if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x0001u);", False,
+     PINS + "test_narrowing_a_nan_gives_a_quiet_nan_of_the_same_sign"),
+    ("binary16 narrowing has no NaN branch",
+     "if (mag > 0x7F800000u) return (uint16_t)(sign | 0x7E00u | ((mag >> 13) & 0x1FFu)); /* NaN, quieted */", ";", False,
+     PINS + "test_narrowing_a_nan_gives_a_quiet_nan_of_the_same_sign"),
+    ("binary16 NaN loses its sign",
+     "if (mag > 0x7F800000u) return (uint16_t)(sign | 0x7E00u | ((mag >> 13) & 0x1FFu)); /* NaN, quieted */",
+     "if (mag > 0x7F800000u) return (uint16_t)(0x7E00u | ((mag >> 13) & 0x1FFu));", False,
+     PINS + "test_narrowing_a_nan_gives_a_quiet_nan_of_the_same_sign"),
 ]
 
 

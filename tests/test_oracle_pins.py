@@ -309,6 +309,44 @@ def test_bf16_rounding_is_nearest_even_exact():
     assert np.array_equal(got, expect)
 
 
+def _f32_arg(bits: int):
+    """A ctypes float holding exactly these bits: passing a Python float instead would go through
+    a double and quiet a signalling NaN on the way, which is the very case under test."""
+    import ctypes
+    return ctypes.c_float.from_buffer_copy(np.uint32(bits).tobytes())
+
+
+# signalling and quiet NaNs of both signs; several have mantissa bits only in the part narrowing drops
+NAN_BITS = [0x7F800001, 0xFF800001, 0x7FC00000, 0xFFC00000, 0x7FFFFFFF, 0xFFFFFFFF, 0x7F80FFFF, 0xFF801FFF,
+            0x7FA00000, 0x7F800100, 0xFF80E000, 0x7FBFFFFF]
+
+
+def test_narrowing_a_nan_gives_a_quiet_nan_of_the_same_sign():
+    """IEEE 754 fixes what a format conversion does with a NaN: the result is a NaN (never an
+    infinity, a zero or a finite value, whatever rounding would do to the pattern), quiet, and of
+    the same sign.  numpy's binary16 conversion is the third opinion for NaN-ness."""
+    for u in NAN_BITS:
+        f = np.array([u], dtype=np.uint32).view(np.float32)
+        assert np.isnan(f[0])
+        sign = (u >> 16) & 0x8000
+        b = int(oracle.lib().orc_f32_to_bf16(_f32_arg(u)))
+        assert (b & 0x7F80) == 0x7F80 and (b & 0x007F) != 0, hex(u)   # a bf16 NaN
+        assert (b & 0x0040) and (b & 0x8000) == sign, hex(u)          # quiet, same sign
+        h = int(oracle.lib().orc_f32_to_f16(_f32_arg(u)))
+        assert (h & 0x7C00) == 0x7C00 and (h & 0x03FF) != 0, hex(u)   # a binary16 NaN
+        assert (h & 0x0200) and (h & 0x8000) == sign, hex(u)
+        assert np.isnan(f.astype(np.float16)[0]) and np.isnan(np.array([h], np.uint16).view(np.float16)[0])
+    # through the data path: a NaN element stays NaN in every 16-bit sum, whatever the other operand
+    for a, r in ((0x7E00, 0x3C00), (0x7C01, 0x0000), (0xFE00, 0x7C00), (0x7C00, 0xFC00)):
+        got = np.array([oracle.combine_f16(a, r, SUM), oracle.combine_f16(r, a, SUM)], np.uint16).view(np.float16)
+        with np.errstate(invalid="ignore"):
+            ref = np.array([a], np.uint16).view(np.float16) + np.array([r], np.uint16).view(np.float16)
+        assert np.isnan(ref[0]) and np.all(np.isnan(got)), (hex(a), hex(r))
+    for a, r in ((0x7FC0, 0x3F80), (0x7F81, 0x0000), (0xFFC0, 0x7F80), (0x7F80, 0xFF80)):
+        got = [oracle.combine_bf16(a, r, SUM), oracle.combine_bf16(r, a, SUM)]
+        assert all((g & 0x7F80) == 0x7F80 and (g & 0x7F) for g in got), (hex(a), hex(r))
+
+
 def test_bf16_golden_ties():
     """Hand-derived cases, one per line: a_bits r_bits expected_bits (hex)."""
     rows = [l.split() for l in open(os.path.join(GOLDEN, "bf16_sum_cases.txt")) if l.strip() and l[0] != "#"]
