@@ -437,472 +437,6 @@ def calibration_copy(torch):
     torch.cuda.synchronize()
 
 
-def cpu_baselines(w, calls, payload, arrivals):
-    """The oracle timed on this machine's host cores over the same step: on one core (the parity
-    authority) and, for plain apply calls, on all cores of the machine's share.  Returns the two
-    report entries and the oracle's result (acc, out_stage, bitmap words) of one pass."""
-    import oracle
-    reps, cpu_t, exp = 0, 0.0, None
-    while cpu_t < 10.0 and reps < 64:
-        eacc = w.acc.copy()
-        eout = np.zeros(max(w.out_bytes, 16), dtype=np.uint8)
-        seen = oracle.new_seen(w.n_bits)
-        t0 = time.perf_counter()
-        for c in calls:
-            if c.get("gather"):
-                oracle.reduce_gather(eacc, None, w.recv_stage, c["descs"], seen, w.dtype, c["op"])
-            elif c["scatter"]:
-                oracle.scatter(eacc.view(np.uint8), w.recv_stage, c["descs"], seen, check=False)
-            else:
-                oracle.apply(eacc, eout, w.recv_stage, c["descs"], seen, w.dtype, c["op"], check=False)
-        cpu_t += time.perf_counter() - t0
-        reps += 1
-        if exp is None:
-            exp = (eacc, eout[:w.out_bytes], oracle.pack_bitmap(seen))
-    single = {
-        "value": round(payload * reps / cpu_t / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-        "cpu": cpu_model(),
-        "sample": f"the whole step ({len(calls)} calls, {arrivals} arrivals, {payload} payload bytes) x {reps} repetitions, {cpu_t:.1f} s",
-    }
-    if any(c.get("gather") or c["scatter"] for c in calls):
-        return single, None, exp
-    # serial dedup, then the unique chunks dealt to threads, each applied through the oracle's own function
-    threads = max(1, min(16, os.cpu_count() or 1))
-    reps_t, cpu_tt, same_t = 0, 0.0, True
-    while cpu_tt < 5.0 and reps_t < 64:
-        tacc = w.acc.copy()
-        tout = np.zeros(max(w.out_bytes, 16), dtype=np.uint8)
-        seen = oracle.new_seen(w.n_bits)
-        t0 = time.perf_counter()
-        for c in calls:
-            oracle.apply_threaded(tacc, tout, w.recv_stage, c["descs"], seen, w.dtype, c["op"], threads)
-        cpu_tt += time.perf_counter() - t0
-        reps_t += 1
-        if reps_t == 1:
-            same_t = (np.array_equal(tacc.view(np.uint8), exp[0].view(np.uint8)) and
-                      np.array_equal(tout[:w.out_bytes], exp[1]))
-    threaded = {
-        "value": round(payload * reps_t / cpu_tt / 1e9, 3), "unit": "GB/s", "cores": threads,
-        "kind": "oracle, unique chunks dealt to threads after a serial dedup pass",
-        "equals_single_core_result": bool(same_t),
-        "sample": f"the whole step x {reps_t} repetitions, {cpu_tt:.1f} s",
-    }
-    return single, threaded, exp
-
-
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="config2", choices=sorted(WORKLOADS))
-    ap.add_argument("--seed", type=int, default=1)
-    ap.add_argument("--sets", type=int, default=4, help="buffer sets the steps rotate over")
-    ap.add_argument("--messages", type=int, default=10000, help="config5: number of messages")
-    ap.add_argument("--streams", type=int, default=1,
-                    help="config5: issue consecutive message batches round-robin on this many streams "
-                         "(batches are independent of each other; the two calls of a batch stay ordered)")
-    ap.add_argument("--messages-per-call", type=int, default=128,
-                    help="config5: messages batched into one call (128 = in-flight messages of one connection)")
-    ap.add_argument("--shape", type=int, default=0, help="launch shape id (0 = auto)")
-    ap.add_argument("--no-chunk-hint", action="store_true")
-    ap.add_argument("--chunk-hint", type=int, default=None, help="override the chunk-size hint (bytes)")
-    ap.add_argument("--records-per-call", type=int, default=0,
-                    help="cut every phase into calls of this many records, queued back to back (0 = one call per phase)")
-    ap.add_argument("--packet-bytes", type=int, default=0,
-                    help="config1-3: arrivals are packets of this many bytes instead of whole chunks (Section 3.1, "
-                         "unreliable datagrams: one MTU-sized payload per arrival); with --two-pass the reduction "
-                         "reads the transport buffer at the configuration's chunk size")
-    ap.add_argument("--relay", action="store_true",
-                    help="ring workloads: flag intermediate reduce-scatter steps forward-only (their partial "
-                         "sums are not written back to the accumulator: 3 instead of 4 bytes per payload byte)")
-    ap.add_argument("--two-pass", action="store_true",
-                    help="ring workloads: run the paper's literal two-pass form (scattered memcpy into a transport "
-                         "buffer, then reduce) instead of the fused single pass, for comparison")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--also-warm", action="store_true",
-                    help="additionally time the same loop over a single buffer set (cache-resident accumulator)")
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic that "
-                         "hardware counters of the same run can be scaled by)")
-    args = ap.parse_args()
-    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
-        print("bench.py: the path is measured as one GPU's share on one GPU; --gpus N>1 is not supported "
-              "(the path shards as one independent rank per GPU, there is nothing to aggregate)", file=sys.stderr)
-        sys.exit(2)
-
-    import torch
-    import paper_2504_17307_amd as pkg
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    pkg.load()
-    pkg.uccl_set_launch_shape(args.shape)
-    if args.workload == "config5-graph":
-        return bench_graph_feed(args, pkg, torch)
-    if args.workload == "config5-feed":
-        return bench_feed(args, pkg, torch)
-    t0 = time.time()
-    w, calls, chunk_bytes = build_job(args.workload, args.seed, args.messages, args.relay, args.messages_per_call,
-                                      args.packet_bytes)
-    collective_chunk = {"config1": 64 << 10, "config2": 32 << 10, "config3": 128 << 10}.get(args.workload, chunk_bytes)
-    if args.chunk_hint is not None:
-        chunk_bytes = args.chunk_hint
-    if not args.no_chunk_hint:
-        pkg.uccl_set_chunk_hint(chunk_bytes)
-    transport_bytes = 0
-    if args.two_pass:
-        calls, transport_bytes = two_pass_calls(w, chunk_bytes, collective_chunk // chunk_bytes if args.packet_bytes else 1)
-        args.no_cpu_baseline = True  # the oracle defines the fused result; parity of this mode is checked below
-    print(f"[bench] built {w.name} in {time.time() - t0:.1f}s: {w.note}", file=sys.stderr, flush=True)
-
-    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1)).cuda()
-    sets = []
-    for _ in range(max(1, args.sets)):
-        sets.append(dict(acc=dev(w.acc), recv=dev(w.recv_stage),
-                         out=torch.zeros(max(w.out_bytes, 16), dtype=torch.uint8, device="cuda"),
-                         transport=torch.zeros(max(transport_bytes, 16), dtype=torch.uint8, device="cuda")))
-    bitmap = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
-    bitmap2 = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
-    descs = [dev(c["descs"]) for c in calls]
-    counts = [len(c["descs"]) for c in calls]
-
-    streams = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else None
-
-    def call(i, s):
-        c = calls[i]
-        if streams is not None:  # calls come in (reduce-scatter, allgather) pairs per batch
-            with torch.cuda.stream(streams[(i // 2) % len(streams)]):
-                return call_on_current(i, s)
-        return call_on_current(i, s)
-
-    def call_on_current(i, s):
-        c = calls[i]
-        bm = bitmap2 if c.get("bm") == "bitmap2" else bitmap
-        rec = 160 if c.get("gather") else 32
-        per = args.records_per_call or counts[i]
-        for lo in range(0, counts[i], max(per, 1)):
-            n = min(per, counts[i] - lo)
-            d = descs[i][lo * rec:(lo + n) * rec]
-            if c.get("gather"):
-                pkg.uccl_chunk_reduce_gather(s["acc"], None, s["recv"], d, n, bm, w.dtype, c["op"])
-            elif c["scatter"]:
-                pkg.uccl_chunk_scatter(s[c.get("dst", "acc")], s[c.get("src", "recv")], d, n, bm)
-            else:
-                pkg.uccl_chunk_apply(s["acc"], s["out"], s[c.get("src", "recv")], d, n, bm, w.dtype, c["op"])
-
-    def step(k, timed=None):
-        s = sets[k % len(sets)]
-        if streams is not None:
-            for st in streams:
-                torch.cuda.current_stream().wait_stream(st)
-        pkg.uccl_dedup_reset(bitmap, w.n_bits)
-        if streams is not None:
-            for st in streams:
-                st.wait_stream(torch.cuda.current_stream())
-        if args.two_pass:
-            pkg.uccl_dedup_reset(bitmap2, w.n_bits)
-        for i in range(len(calls)):
-            if timed is not None and i in timed and k % EVENT_STRIDE == 0:
-                # a pre-made event pair attached to the dispatch itself: the kernel's own begin and end
-                pkg.uccl_time_next_launch(*timed[i][k // EVENT_STRIDE])
-            call(i, s)
-
-    # one pass from the pristine state, kept for the parity check against the oracle
-    step(0)
-    torch.cuda.synchronize()
-    first = (sets[0]["acc"].cpu().numpy(), sets[0]["out"][:w.out_bytes].cpu().numpy(),
-             bitmap.cpu().numpy().view(np.uint32))
-
-    # Per-launch durations are taken INSIDE the timed steps (every EVENT_STRIDE-th one): a HIP
-    # event pair, made and recorded once beforehand, is attached to the dispatch of the kernel on
-    # the stream it runs on (torch's current stream).  Workloads with many calls per step time the largest call
-    # of each op.
-    by_op = {}
-    for i, c in enumerate(calls):
-        if c["op"] not in by_op or c["algo_bytes"] > calls[by_op[c["op"]]]["algo_bytes"]:
-            by_op[c["op"]] = i
-    timed = {}
-    if streams is None and not args.records_per_call:
-        for i in by_op.values():
-            timed[i] = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-                        for _ in range((args.steps + EVENT_STRIDE - 1) // EVENT_STRIDE)]
-            for a, b in timed[i]:
-                a.record()
-                b.record()
-    torch.cuda.synchronize()
-
-    def timed_loop(n_sets, events=None):
-        nonlocal sets
-        keep, sets = sets, sets[:n_sets]
-        for k in range(args.warmup):
-            step(k)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for k in range(args.steps):
-            step(k, events)
-        torch.cuda.synchronize()
-        el = time.perf_counter() - t0
-        sets = keep
-        return el
-
-    elapsed = timed_loop(len(sets), timed)
-    warm_elapsed = timed_loop(1) if (args.also_warm and len(sets) > 1) else None
-    if not timed:  # overlapping streams, or phases cut into several launches: no per-kernel attribution
-        timed = {i: [] for i in by_op.values()}
-    kernels = []
-    for i, evs in timed.items():
-        t = np.array([a.elapsed_time(b) for a, b in evs]) if evs else np.array([float("nan")])
-        c = calls[i]
-        kernels.append(dict(call=c["name"], op=["SUM", "MAX", "MIN", "COPY"][c["op"]], records=counts[i],
-                            algorithmic_bytes=c["algo_bytes"], avg_ms=round(float(t.mean()), 5),
-                            median_ms=round(float(np.median(t)), 5), min_ms=round(float(t.min()), 5),
-                            hbm_frac=round(c["algo_bytes"] / (t.mean() * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)))
-    dom = max(kernels, key=lambda k: k["algorithmic_bytes"])
-
-    def timed_ms(i):
-        evs = timed.get(i) or []
-        return float(np.mean([a.elapsed_time(b) for a, b in evs])) if evs else 0.0
-
-    report_us, status_us = time_feedback_kernels(pkg, torch, bitmap, w.n_bits)
-    stream_ceiling = stream_ceilings(torch)
-    if args.calibration_copy:
-        calibration_copy(torch)
-
-    payload = sum(c["payload_bytes"] for c in calls)
-    unique = sum(c["n_unique"] for c in calls)
-    arrivals = sum(counts)
-    algo = sum(c["algo_bytes"] for c in calls)
-    per_step = elapsed / args.steps
-    per_kernel = not np.isnan(dom["avg_ms"])
-    achieved = dom["algorithmic_bytes"] / (dom["avg_ms"] * 1e-3) / 1e9 if per_kernel else algo / per_step / 1e9
-    cache_note = ("buffers rotate over %d sets: HBM resident, not cache resident" % len(sets)
-                  if (w.acc.nbytes + w.recv_stage.nbytes + w.out_bytes) * len(sets) > (1 << 30)
-                  else "working set fits the 256 MB last-level cache: an effective, not an HBM, figure")
-
-    result = {
-        "metric": "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk stream), 1x MI355X",
-        "value": round(payload / per_step / 1e9, 2),
-        "unit": "GB/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": round(per_step * 1e3, 4),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "bf16" if w.dtype == 1 else "f32",
-        "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "seed": args.seed,
-                   "unique_chunks": unique, "arrivals": arrivals, "payload_bytes": payload,
-                   "algorithmic_bytes": algo, "launch_shape": args.shape,
-                   "chunk_hint": 0 if args.no_chunk_hint else chunk_bytes, "buffer_sets": len(sets),
-                   "forward_only_intermediate_steps": bool(args.relay), "two_pass": bool(args.two_pass), "packet_bytes": args.packet_bytes or None,
-                   "calls_per_step": 1 + sum(-(-n // (args.records_per_call or max(n, 1))) for n in counts),
-                   "records_per_call": args.records_per_call or None, "streams": args.streams, "cache": cache_note},
-        "chunks_per_s": round(unique / per_step, 1),
-        "arrivals_per_s": round(arrivals / per_step, 1),
-        "step_hbm_frac": round(algo / per_step / 1e9 / PEAK_HBM_GBS, 4),
-        "warm_cache": None if warm_elapsed is None else {
-            "ms_per_step": round(warm_elapsed / args.steps * 1e3, 4),
-            "value": round(payload / (warm_elapsed / args.steps) / 1e9, 2),
-            "step_hbm_frac": round(algo / (warm_elapsed / args.steps) / 1e9 / PEAK_HBM_GBS, 4),
-            "note": "same loop over one buffer set; the accumulator stays in the last-level cache"},
-        "roofline": {
-            "bound": "hbm",
-            "kernel": (f"chunk_gather_kernel, {dom['call']} call ({dom['op']})" if calls[0].get("gather") else
-                       f"chunk_flat_kernel, {dom['call']} call ({dom['op']})" if args.shape in (0, 4) else
-                       f"chunk_apply_kernel, {dom['call']} call ({dom['op']})"),
-            "basis": "the dominant kernel's own duration" if per_kernel else "whole step (kernels of several streams overlap)",
-            "achieved": round(achieved, 1),
-            "peak": PEAK_HBM_GBS,
-            "unit": "GB/s",
-            "frac": round(achieved / PEAK_HBM_GBS, 4),
-            "traffic": MEASURED_TRAFFIC.get((args.workload, source_hash())),
-            "algorithmic_bytes_per_launch": dom["algorithmic_bytes"],
-            "avg_launch_ms": dom["avg_ms"] if per_kernel else None,
-        },
-        "kernels": kernels if per_kernel else [],
-        # the reduce phase alone (its call's unique payload over its kernel's own duration)
-        "reduce_phase_payload_GBps": (round(calls[by_op[0]]["payload_bytes"] / (timed_ms(by_op[0]) * 1e-3) / 1e9, 1)
-                                      if per_kernel and 0 in by_op and timed_ms(by_op[0]) > 0 else None),
-        "stream_ceiling": stream_ceiling,
-        "device": device_info(torch),
-        "dedup_report": {"n_bits": w.n_bits, "median_us": round(report_us, 2),
-                         "what": "ack_report_kernel: cumulative ack, applied count, selective ranges"},
-        "message_status": {"slots": 128, "bits_per_slot": 256, "median_us": round(status_us, 2),
-                           "what": "message_status_kernel: per-slot cumulative point, applied count, completion"},
-    }
-    if args.workload.startswith("config5"):
-        result["us_per_message"] = round(per_step * 1e6 / w.extra["n_msgs"], 3)
-        result["config"]["messages"] = w.extra["n_msgs"]
-
-    if args.two_pass:
-        import oracle
-        eacc, eout, seen = w.acc.copy(), np.zeros(max(w.out_bytes, 16), dtype=np.uint8), oracle.new_seen(w.n_bits)
-        for ph in w.phases:
-            oracle.apply(eacc, eout, w.recv_stage, ph.descs, seen, w.dtype, ph.op, check=False)
-        same = (np.array_equal(first[0], eacc.view(np.uint8).reshape(-1)) and
-                np.array_equal(first[1], eout[:w.out_bytes]))
-        result["parity_first_pass"] = ("two-pass result bit-exact vs the oracle's single-pass definition (acc, out_stage)"
-                                       if same else "MISMATCH")
-        if not same:
-            print(json.dumps(result))
-            sys.exit(1)
-    if not args.no_cpu_baseline:
-        single, threaded, exp = cpu_baselines(w, calls, payload, arrivals)
-        result["cpu_baseline"] = single
-        if threaded is not None:
-            result["cpu_baseline_threaded"] = threaded
-        same = all(np.array_equal(np.ascontiguousarray(g).view(np.uint8).reshape(-1),
-                                  np.ascontiguousarray(e).view(np.uint8).reshape(-1))
-                   for g, e in zip(first, (eacc, eout, oracle.pack_bitmap(seen))))
-        result["parity_first_pass"] = "bit-exact vs oracle (acc, out_stage, bitmap)" if same else "MISMATCH"
-        if not same:
-            print(json.dumps(result))
-            sys.exit(1)
-    print(json.dumps(result))
-
-
-def bench_feed(args, pkg, torch):
-    """Small-message regime through uccl_feed: per message two pushes and a poll."""
-    from synth import workloads as wl
-    from synth.layout import SUM, COPY, F32
-    import oracle
-    w, msgs = wl.config5(seed=args.seed, n_msgs=args.messages)
-    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1)).cuda()
-    acc, recv = dev(w.acc), dev(w.recv_stage)
-    out = torch.zeros(w.out_bytes, dtype=torch.uint8, device="cuda")
-    bitmap = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
-    pkg.uccl_set_chunk_hint(4096)
-    feed = pkg.uccl_feed_create(acc, out, recv, bitmap, F32, SUM, COPY, 65536, 8)
-    recs = [(np.ascontiguousarray(m["rs"]), np.ascontiguousarray(m["ag"])) for m in msgs]
-
-    def one_pass():
-        pkg.uccl_dedup_reset(bitmap, w.n_bits)
-        for rs, ag in recs:
-            pkg.uccl_feed_push(feed, 0, rs)
-            pkg.uccl_feed_push(feed, 1, ag)
-            pkg.uccl_feed_poll(feed)
-        pkg.uccl_feed_sync(feed)
-
-    one_pass()
-    first = (acc.cpu().numpy(), out.cpu().numpy(), bitmap.cpu().numpy().view(np.uint32))
-    before = pkg.uccl_feed_get_stats(feed)
-    reps = max(1, args.steps // 10)
-    t0 = time.perf_counter()
-    for _ in range(reps):
-        one_pass()
-    per_msg = (time.perf_counter() - t0) / reps / len(msgs)
-    after = pkg.uccl_feed_get_stats(feed)
-    lat = []
-    pkg.uccl_dedup_reset(bitmap, w.n_bits)
-    torch.cuda.synchronize()
-    for rs, ag in recs[:300]:
-        t0 = time.perf_counter()
-        pkg.uccl_feed_push(feed, 0, rs)
-        pkg.uccl_feed_push(feed, 1, ag)
-        pkg.uccl_feed_sync(feed)
-        lat.append(time.perf_counter() - t0)
-    pkg.uccl_feed_destroy(feed)
-    payload = sum(m["payload_bytes"] for m in msgs)
-    unique = sum(m["n_unique"] for m in msgs)
-    algo = sum(m["algo_bytes"] for m in msgs)
-    flushes = (after["flushes"] - before["flushes"]) / reps
-    result = {
-        "metric": "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk stream), 1x MI355X",
-        "value": round(payload / (per_msg * len(msgs)) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
-        "steps": reps, "warmup": 1, "ms_per_step": round(per_msg * len(msgs) * 1e3, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"config5-feed: {WORKLOADS['config5-feed']}", "seed": args.seed,
-                   "messages": len(msgs), "unique_chunks": unique, "payload_bytes": payload,
-                   "algorithmic_bytes": algo, "slots": 8, "slot_capacity_records": 65536},
-        "chunks_per_s": round(unique / (per_msg * len(msgs)), 1),
-        "us_per_message": round(per_msg * 1e6, 3),
-        "step_hbm_frac": round(algo / (per_msg * len(msgs)) / 1e9 / PEAK_HBM_GBS, 4),
-        "feed": {"hand_overs_per_pass": round(flushes, 1), "messages_per_hand_over": round(len(msgs) / max(flushes, 1), 1),
-                 "largest_hand_over_records": after["max_batch"], "slot_waits": after["slot_waits"]},
-        "completion_latency_us": {"median": round(float(np.median(lat)) * 1e6, 2),
-                                  "p99": round(float(np.percentile(lat, 99)) * 1e6, 2)},
-        "roofline": None,
-    }
-    if not args.no_cpu_baseline:
-        eacc, eout, seen = w.acc.copy(), np.zeros(w.out_bytes, dtype=np.uint8), oracle.new_seen(w.n_bits)
-        t0 = time.perf_counter()
-        for m in msgs:
-            oracle.apply(eacc, eout, w.recv_stage, m["rs"], seen, F32, SUM, check=False)
-            oracle.apply(eacc, eout, w.recv_stage, m["ag"], seen, F32, COPY, check=False)
-        cpu_t = time.perf_counter() - t0
-        result["cpu_baseline"] = {"value": round(payload / cpu_t / 1e9, 3), "unit": "GB/s", "cores": 1,
-                                  "kind": "oracle", "sample": f"all {len(msgs)} messages once, {cpu_t:.1f} s"}
-        same = all(np.array_equal(np.ascontiguousarray(g).view(np.uint8).reshape(-1),
-                                  np.ascontiguousarray(e).view(np.uint8).reshape(-1))
-                   for g, e in zip(first, (eacc, eout, oracle.pack_bitmap(seen))))
-        result["parity_first_pass"] = "bit-exact vs oracle (acc, out_stage, bitmap)" if same else "MISMATCH"
-        if not same:
-            print(json.dumps(result))
-            sys.exit(1)
-    print(json.dumps(result))
-
-
-def launch_time_us(pkg, torch, launch, reps=30, skip=5):
-    """Median duration of one launch, from event pairs attached to the dispatch."""
-    evs = []
-    for _ in range(reps):
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        b.record()
-        pkg.uccl_time_next_launch(a, b)
-        launch()
-        evs.append((a, b))
-    torch.cuda.synchronize()
-    return float(np.median([a.elapsed_time(b) for a, b in evs[skip:]])) * 1e3
-
-
-def time_feedback_kernels(pkg, torch, bitmap, n_bits):
-    """(acknowledgement report over this workload's bitmap, status of a 128 x 256-bit message window), in us."""
-    report = torch.zeros(32 + 16 * 64, dtype=torch.uint8, device="cuda")
-    report_us = launch_time_us(pkg, torch, lambda: pkg.uccl_dedup_report(bitmap, n_bits, report, 64))
-    hdr = report.cpu().numpy()
-    assert int(hdr[:8].view(np.uint64)[0]) == n_bits and int(hdr[20:24].view(np.uint32)[0]) == 1, \
-        "after a full step every chunk is acknowledged"
-    win = torch.zeros(128 * 8, dtype=torch.int32, device="cuda")
-    win[: 64 * 8] = -1                                   # half of the slots complete
-    n_chunks = torch.full((128,), 200, dtype=torch.int32, device="cuda")
-    status = torch.zeros(128 * 4, dtype=torch.int32, device="cuda")
-    status_us = launch_time_us(pkg, torch, lambda: pkg.uccl_message_status(win, n_chunks, 128, 256, status, False))
-    assert int(status.view(128, 4)[:, 2].sum()) == 64
-    return report_us, status_us
-
-
-def stream_ceilings(torch, nbytes=240 << 20, nsets=4, reps=20):
-    """The machine's own streaming rates beside the published peak: the framework's c = a and
-    c = a + b on buffers of the headline workload's order of size, rotating over nsets sets."""
-    def ceiling(fn, streams):
-        bufs = [[torch.empty(nbytes // 2, dtype=torch.bfloat16, device="cuda").normal_() for _ in range(3)]
-                for _ in range(nsets)]
-        for k in range(4):
-            fn(*bufs[k % nsets])
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for k in range(reps):
-            fn(*bufs[k % nsets])
-        b.record()
-        torch.cuda.synchronize()
-        return round(streams * nbytes * reps / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
-    return {"copy_1r1w_GBps": ceiling(lambda x, y, z: z.copy_(x), 2),
-            "add_2r1w_GBps": ceiling(lambda x, y, z: torch.add(x, y, out=z), 3),
-            "what": "torch copy_ and add on 240 MiB bf16 tensors rotating over 4 sets, same run"}
-
-
-def calibration_copy(torch):
-    """One plain 1 GiB device-to-device copy, the known quantity the traffic counters are scaled by."""
-    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-    dst = torch.empty_like(src)
-    torch.cuda.synchronize()
-    dst.copy_(src)
-    torch.cuda.synchronize()
-
-
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)

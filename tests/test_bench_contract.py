@@ -57,3 +57,24 @@ def test_measured_traffic_is_keyed_by_the_kernel_source():
         assert workload in bench.WORKLOADS and len(key) == 16 and nbytes > 0
     # a figure measured on another source must not be reported for this one
     assert bench.MEASURED_TRAFFIC.get(("config2", "0" * 16)) is None
+
+
+def test_bench_is_one_program():
+    """Every top-level name of bench.py is defined once (a second definition would silently
+    shadow the first, and an edit to the shadowed copy would do nothing) and every top-level
+    function is reachable from main()."""
+    import ast
+    import collections
+    src = open(os.path.join(ROOT, "bench.py")).read()
+    tree = ast.parse(src)
+    defs = [n for n in tree.body if isinstance(n, (ast.FunctionDef, ast.ClassDef))]
+    twice = [name for name, k in collections.Counter(n.name for n in defs).items() if k > 1]
+    assert not twice, f"defined more than once: {twice}"
+    assigned = collections.Counter(t.id for n in tree.body if isinstance(n, ast.Assign)
+                                   for t in n.targets if isinstance(t, ast.Name))
+    assert not [k for k, v in assigned.items() if v > 1]
+    used = {n.id for n in ast.walk(tree) if isinstance(n, ast.Name)} | \
+           {n.attr for n in ast.walk(tree) if isinstance(n, ast.Attribute)}
+    unused = [n.name for n in defs if n.name not in used]
+    assert not unused, f"never referenced: {unused}"
+    assert len(src.splitlines()) < 1000
