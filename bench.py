@@ -195,7 +195,6 @@ def bench_graph_feed(args, pkg, torch):
     out = torch.zeros(w.out_bytes, dtype=torch.uint8, device="cuda")
     bitmap = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
     cap = max(max(len(m["rs"]), len(m["ag"])) for m in msgs)
-    pkg.uccl_set_chunk_hint(4096)
     K = 32
     slots = []
     side = torch.cuda.Stream()
@@ -206,8 +205,8 @@ def bench_graph_feed(args, pkg, torch):
         g = torch.cuda.CUDAGraph()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.graph(g, stream=side):
-            pkg.uccl_chunk_apply_indirect(acc, out, recv, d_rs, cnt[0:4], cap, bitmap, F32, SUM)
-            pkg.uccl_chunk_apply_indirect(acc, out, recv, d_ag, cnt[4:8], cap, bitmap, F32, COPY)
+            pkg.uccl_chunk_apply_indirect(acc, out, recv, d_rs, cnt[0:4], cap, bitmap, F32, SUM, opts=(4096, 0))
+            pkg.uccl_chunk_apply_indirect(acc, out, recv, d_ag, cnt[4:8], cap, bitmap, F32, COPY, opts=(4096, 0))
         slots.append(dict(rs=d_rs.numpy(), ag=d_ag.numpy(), cnt=cnt.numpy().view(np.uint32), graph=g,
                           done=torch.cuda.Event(), keep=(d_rs, d_ag, cnt)))
     raw = [(m["rs"].view(np.uint8).reshape(-1), m["ag"].view(np.uint8).reshape(-1), len(m["rs"]), len(m["ag"]))
@@ -307,7 +306,6 @@ def bench_feed(args, pkg, torch):
     acc, recv = dev(w.acc), dev(w.recv_stage)
     out = torch.zeros(w.out_bytes, dtype=torch.uint8, device="cuda")
     bitmap = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
-    pkg.uccl_set_chunk_hint(4096)
     feed = pkg.uccl_feed_create(acc, out, recv, bitmap, F32, SUM, COPY, 65536, 8)
     recs = [(np.ascontiguousarray(m["rs"]), np.ascontiguousarray(m["ag"])) for m in msgs]
 
@@ -451,9 +449,10 @@ def main():
                          "(batches are independent of each other; the two calls of a batch stay ordered)")
     ap.add_argument("--messages-per-call", type=int, default=128,
                     help="config5: messages batched into one call (128 = in-flight messages of one connection)")
-    ap.add_argument("--shape", type=int, default=0, help="launch shape id (0 = auto)")
-    ap.add_argument("--no-chunk-hint", action="store_true")
-    ap.add_argument("--chunk-hint", type=int, default=None, help="override the chunk-size hint (bytes)")
+    ap.add_argument("--parts", type=int, default=0,
+                    help="workgroups per record for calls of few large records (0 = the library decides, 1 = never cut)")
+    ap.add_argument("--no-chunk-hint", action="store_true", help="do not tell the library the chunk size")
+    ap.add_argument("--chunk-hint", type=int, default=None, help="override the chunk size given with each call (bytes)")
     ap.add_argument("--records-per-call", type=int, default=0,
                     help="cut every phase into calls of this many records, queued back to back (0 = one call per phase)")
     ap.add_argument("--packet-bytes", type=int, default=0,
@@ -483,7 +482,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     pkg.load()
-    pkg.uccl_set_launch_shape(args.shape)
+    pkg.uccl_init()
     if args.workload == "config5-graph":
         return bench_graph_feed(args, pkg, torch)
     if args.workload == "config5-feed":
@@ -494,8 +493,7 @@ def main():
     collective_chunk = {"config1": 64 << 10, "config2": 32 << 10, "config3": 128 << 10}.get(args.workload, chunk_bytes)
     if args.chunk_hint is not None:
         chunk_bytes = args.chunk_hint
-    if not args.no_chunk_hint:
-        pkg.uccl_set_chunk_hint(chunk_bytes)
+    opts = (0 if args.no_chunk_hint else chunk_bytes, args.parts)   # per-call tuning, passed with every call
     transport_bytes = 0
     if args.two_pass:
         calls, transport_bytes = two_pass_calls(w, chunk_bytes, collective_chunk // chunk_bytes if args.packet_bytes else 1)
@@ -531,11 +529,12 @@ def main():
             n = min(per, counts[i] - lo)
             d = descs[i][lo * rec:(lo + n) * rec]
             if c.get("gather"):
-                pkg.uccl_chunk_reduce_gather(s["acc"], None, s["recv"], d, n, bm, w.dtype, c["op"])
+                pkg.uccl_chunk_reduce_gather(s["acc"], None, s["recv"], d, n, bm, w.dtype, c["op"], opts=opts)
             elif c["scatter"]:
-                pkg.uccl_chunk_scatter(s[c.get("dst", "acc")], s[c.get("src", "recv")], d, n, bm)
+                pkg.uccl_chunk_scatter_opts(s[c.get("dst", "acc")], s[c.get("src", "recv")], d, n, bm, opts=opts)
             else:
-                pkg.uccl_chunk_apply(s["acc"], s["out"], s[c.get("src", "recv")], d, n, bm, w.dtype, c["op"])
+                pkg.uccl_chunk_apply_opts(s["acc"], s["out"], s[c.get("src", "recv")], d, n, bm, w.dtype, c["op"],
+                                          opts=opts)
 
     def step(k, timed=None):
         s = sets[k % len(sets)]
@@ -641,8 +640,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "seed": args.seed,
                    "unique_chunks": unique, "arrivals": arrivals, "payload_bytes": payload,
-                   "algorithmic_bytes": algo, "launch_shape": args.shape,
-                   "chunk_hint": 0 if args.no_chunk_hint else chunk_bytes, "buffer_sets": len(sets),
+                   "algorithmic_bytes": algo, "parts": args.parts,
+                   "chunk_hint": opts[0], "buffer_sets": len(sets),
                    "forward_only_intermediate_steps": bool(args.relay), "two_pass": bool(args.two_pass), "packet_bytes": args.packet_bytes or None,
                    "calls_per_step": 1 + sum(-(-n // (args.records_per_call or max(n, 1))) for n in counts),
                    "records_per_call": args.records_per_call or None, "streams": args.streams, "cache": cache_note},
@@ -657,8 +656,7 @@ def main():
         "roofline": {
             "bound": "hbm",
             "kernel": (f"chunk_gather_kernel, {dom['call']} call ({dom['op']})" if calls[0].get("gather") else
-                       f"chunk_flat_kernel, {dom['call']} call ({dom['op']})" if args.shape in (0, 4) else
-                       f"chunk_apply_kernel, {dom['call']} call ({dom['op']})"),
+                       f"chunk_flat_kernel, {dom['call']} call ({dom['op']})"),
             "basis": "the dominant kernel's own duration" if per_kernel else "whole step (kernels of several streams overlap)",
             "achieved": round(achieved, 1),
             "peak": PEAK_HBM_GBS,

@@ -35,7 +35,7 @@
 extern "C" {
 #endif
 
-#define UCCL_CHUNK_VERSION 1
+#define UCCL_CHUNK_VERSION 2
 
 /* One record per ARRIVAL, written by the control path in arrival order (Section 3.1:
  * "the right order given by the receiver CPU"; Section 5: packet pointers passed via
@@ -76,7 +76,8 @@ enum {
   UCCL_EINVAL = -1,  /* null pointer with n_descs > 0, unknown dtype/op/shape, aliasing buffers */
   UCCL_EALIGN = -2,  /* a base pointer is not 16-byte aligned (bitmap / counter: 4-byte) */
   UCCL_ELAUNCH = -3, /* HIP refused the launch; uccl_last_error_detail() has HIP's message */
-  UCCL_ENOMEM = -4   /* uccl_feed_create could not get host, pinned or device memory */
+  UCCL_ENOMEM = -4,  /* uccl_feed_create / uccl_init could not get host, pinned or device memory */
+  UCCL_ETOOBIG = -5  /* more records than the entry point's stated maximum: split the call */
 };
 
 /* Buffer sizes for the checked entry points (HOST struct, read during the call). */
@@ -86,6 +87,21 @@ typedef struct uccl_extents {
   uint64_t recv_bytes; /* size of recv_stage */
   uint64_t n_bits;     /* number of valid bits in dedup_bitmap */
 } uccl_extents;
+
+/* Per-call tuning (HOST struct, read during the call; a NULL pointer means all zeros).  Results
+ * never depend on it, only speed does.
+ *   chunk_bytes  the transport's chunk size (the control path chooses it per connection: 32 KB by
+ *                default, Section 3.3 "control coalescing"; Appendix A onChunkSize), 0 = unknown.
+ *                Sets how many records a workgroup takes: about 32 KiB of payload per workgroup.
+ *   parts        workgroups per record for calls of few, large records (Appendix C.4: small
+ *                messages are where the kernel's fixed costs show): 0 = the library decides,
+ *                1 = never cut a record, 2..16 = that many.  Honoured only when a workgroup takes
+ *                a single record and the call has at most 2048 of them. */
+typedef struct uccl_launch_opts {
+  uint32_t chunk_bytes;
+  uint32_t parts;
+  uint32_t reserved[2]; /* 0 */
+} uccl_launch_opts;
 
 /*
  * uccl_chunk_apply -- dedup, place, combine, write back and forward (see top of file).
@@ -114,10 +130,22 @@ typedef struct uccl_extents {
  * on error nothing has been enqueued.  One launch covers the whole call with one workgroup
  * per 1..32 records; a record count whose workgroup count exceeds what the device accepts
  * in one launch comes back as UCCL_ELAUNCH (split the call).
+ *
+ * Scratch memory.  A call of fewer than 512 records, each the only record of its workgroup, is
+ * launched with several workgroups per record so that it fills the machine; those workgroups
+ * agree on the record's fate through one 64-bit claim word per record in a pool the library
+ * allocates once per device (1 MiB + 8 bytes, hipMalloc at the first such call or in
+ * uccl_init, kept until the process ends).  If the pool cannot be had, or the stream is being
+ * captured into a graph, the call is launched with one workgroup per record instead: slower,
+ * same result.  Apart from that one-time allocation no data-path call allocates.
  */
 int uccl_chunk_apply(void* acc, void* out_stage, const void* recv_stage,
                      const uccl_chunk_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
                      uccl_dtype dtype, uccl_op op, void* stream);
+
+/* Eagerly make the current device's claim pool (see "Scratch memory" above), so that no later
+ * call allocates.  Idempotent; UCCL_OK or UCCL_ENOMEM.  Utility, no passage of the paper. */
+int uccl_init(void);
 
 /*
  * uccl_chunk_apply_checked -- same operation; additionally every record is validated ON
@@ -133,6 +161,17 @@ int uccl_chunk_apply_checked(void* acc, void* out_stage, const void* recv_stage,
                              const uccl_extents* extents, uint32_t* n_rejected, void* stream);
 
 /*
+ * uccl_chunk_apply_opts -- the general form: uccl_chunk_apply with optional validation
+ * (`extents` and `n_rejected` as in uccl_chunk_apply_checked, both may be NULL = unchecked) and
+ * optional per-call tuning (`opts`, may be NULL).  UCCL_EINVAL for parts > 16 or non-zero
+ * reserved fields.
+ */
+int uccl_chunk_apply_opts(void* acc, void* out_stage, const void* recv_stage,
+                          const uccl_chunk_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
+                          uccl_dtype dtype, uccl_op op, const uccl_extents* extents,
+                          uint32_t* n_rejected, const uccl_launch_opts* opts, void* stream);
+
+/*
  * uccl_chunk_apply_indirect -- the same operation fed from a descriptor slot the control
  * path refills, with no argument changing between launches (Section 5: the receiver CPU
  * passes the pointer list through CPU-GPU shared memory; Appendix C.4: per-batch kernel
@@ -142,13 +181,14 @@ int uccl_chunk_apply_checked(void* acc, void* out_stage, const void* recv_stage,
  * the kernel runs, not when the call is made.  A count above max_descs is capped.  Because
  * every argument is fixed, the call can be captured once in a HIP graph and replayed after
  * the control path has rewritten the slot.  The launch is sized for max_descs.  `extents`
- * and `n_rejected` are as in uccl_chunk_apply_checked; both may be NULL (unchecked).
+ * and `n_rejected` are as in uccl_chunk_apply_checked; both may be NULL (unchecked); `opts` may
+ * be NULL.  A call made while its stream is being captured is never cut into parts.
  */
 int uccl_chunk_apply_indirect(void* acc, void* out_stage, const void* recv_stage,
                               const uccl_chunk_desc* descs, const uint32_t* n_descs_ptr,
                               uint32_t max_descs, uint32_t* dedup_bitmap, uccl_dtype dtype,
                               uccl_op op, const uccl_extents* extents, uint32_t* n_rejected,
-                              void* stream);
+                              const uccl_launch_opts* opts, void* stream);
 
 /*
  * uccl_chunk_reduce_gather -- several senders' chunks for ONE destination chunk in one
@@ -165,7 +205,7 @@ int uccl_chunk_apply_indirect(void* acc, void* out_stage, const void* recv_stage
  * once per chunk: (n_src + 1) reads and 1 (+1 forwarding) writes per payload byte of one source.
  * `seq` dedups the record as a whole: the control path issues it when all its sources are
  * in, and may issue it again.  `extents` / `n_rejected` as in uccl_chunk_apply_checked, both
- * may be NULL.  Records: 160 bytes, 16-byte aligned array.
+ * may be NULL; `opts` may be NULL (only chunk_bytes is used).  Records: 160 bytes, 16-byte aligned array.
  */
 #define UCCL_MAX_SOURCES 16
 typedef struct uccl_gather_desc {
@@ -180,7 +220,7 @@ typedef struct uccl_gather_desc {
 int uccl_chunk_reduce_gather(void* acc, void* out_stage, const void* recv_stage,
                              const uccl_gather_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
                              uccl_dtype dtype, uccl_op op, const uccl_extents* extents,
-                             uint32_t* n_rejected, void* stream);
+                             uint32_t* n_rejected, const uccl_launch_opts* opts, void* stream);
 
 /*
  * uccl_chunk_scatter -- all-to-all receive side (Section 2.1: copy from transport
@@ -195,8 +235,15 @@ int uccl_chunk_scatter_checked(void* dst, const void* recv_stage, const uccl_chu
                                uint32_t n_descs, uint32_t* dedup_bitmap,
                                const uccl_extents* extents, uint32_t* n_rejected, void* stream);
 
+/* The general form of the scatter: `extents`, `n_rejected` and `opts` may each be NULL. */
+int uccl_chunk_scatter_opts(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,
+                            uint32_t n_descs, uint32_t* dedup_bitmap, const uccl_extents* extents,
+                            uint32_t* n_rejected, const uccl_launch_opts* opts, void* stream);
+
 /* Clear the first n_bits bits (rounded up to whole 32-bit words) of the bitmap: starts a
- * new message / connection epoch.  Uses a fill kernel, so it may be captured in a graph. */
+ * new message / connection epoch (Section 3.1: a message id, and with it its chunk sequence
+ * numbers, is reused once its message is complete).  Uses a fill kernel, so it may be captured
+ * in a graph. */
 int uccl_dedup_reset(uint32_t* dedup_bitmap, uint64_t n_bits, void* stream);
 
 /*
@@ -226,7 +273,7 @@ int uccl_dedup_report(const uint32_t* dedup_bitmap, uint64_t n_bits, void* repor
 
 /*
  * uccl_message_status -- per-message receiver state for one connection's window of in-flight
- * messages (Section 3.2: a 7-bit message id allows 128 messages in flight, an 8-bit chunk
+ * messages (Section 3.1: a 7-bit message id allows 128 messages in flight, an 8-bit chunk
  * sequence number 256 chunks each, and a last-chunk mark tells the receiver the chunk count).
  * The bitmap is read as n_slots windows of bits_per_slot bits; window i holds the chunks of
  * the message in slot i at bits [i * bits_per_slot, + limit), where limit = n_chunks[i]
@@ -265,7 +312,9 @@ int uccl_message_status(uint32_t* dedup_bitmap, const uint32_t* n_chunks, uint32
  *   sync   flush, then wait until every hand-over has finished
  *   destroy  waits for the hand-overs in flight, frees the slots; records pushed but not yet
  *          handed over are dropped (call sync first to keep them)
- * Buffers, bitmap and element type are fixed at creation; lane ops are given there too.  The
+ * Buffers, bitmap and element type are fixed at creation; lane ops are given there too.  Each
+ * hand-over is launched with the largest `len` among its lane's records as the chunk size, so
+ * feeds of connections with different chunk sizes do not interfere.  The
  * slots live on the device that is current at creation; use the feed with that device current.
  * If a hand-over fails half way (UCCL_ELAUNCH), its records stay in the slot and the next
  * flush offers them again; records already applied are then dropped by the bitmap.
@@ -288,27 +337,6 @@ int uccl_feed_sync(uccl_feed* feed);
 int uccl_feed_get_stats(const uccl_feed* feed, uccl_feed_stats* stats);
 int uccl_feed_destroy(uccl_feed* feed);
 
-/*
- * Launch shape: how records are mapped onto the machine.
- *   AUTO   = FLAT
- *   FLAT   a 1024-thread workgroup dedups a tile of records, cuts the winners into
- *          2 KiB units and deals the units to its 16 wavefronts (any chunk size)
- *   WAVE   a 256-thread workgroup dedups a tile of records and each of its four
- *          wavefronts streams whole chunks
- *   GROUP  all 256 threads of a workgroup stream one chunk
- * WAVE and GROUP exist so that the alternatives can be measured; FLAT is the fastest.
- * Process-wide setting, intended for tuning runs; returns UCCL_EINVAL for unknown ids.
- */
-typedef enum uccl_shape {
-  UCCL_SHAPE_AUTO = 0, UCCL_SHAPE_WAVE = 1, UCCL_SHAPE_GROUP = 2, UCCL_SHAPE_FLAT = 4
-} uccl_shape;
-int uccl_set_launch_shape(int shape);
-
-/* The transport's chunk size in bytes (the control path chooses it per connection:
- * 32 KB by default, Section 3.3 "control coalescing"), 0 = unknown.  Only a tuning hint:
- * it sets how many records a workgroup takes; results never depend on it. */
-int uccl_set_chunk_hint(uint32_t chunk_bytes);
-
 /* Measurement aid: the next apply / scatter / report call made by THIS host thread attaches the
  * two hipEvent_t (either may be NULL) to its kernel dispatch, so that
  * hipEventElapsedTime(start, stop) is that kernel's own execution time on the device,
@@ -316,8 +344,14 @@ int uccl_set_chunk_hint(uint32_t chunk_bytes);
  * include.  One-shot: cleared by the launch (also by a launch that fails). */
 int uccl_time_next_launch(void* start_event, void* stop_event);
 
+/* Diagnostics: parts of split records that gave up waiting for their record's decision since the
+ * pool was made, on the current device (synchronous read-back; always 0 on working hardware). */
+int uccl_claim_timeouts(uint64_t* count);
+
+/* Utilities, no passage of the paper: text of a return code; HIP's text for the last
+ * UCCL_ELAUNCH on this thread; UCCL_CHUNK_VERSION of the loaded library. */
 const char* uccl_strerror(int code);
-const char* uccl_last_error_detail(void); /* HIP's text for the last UCCL_ELAUNCH on this thread */
+const char* uccl_last_error_detail(void);
 int uccl_version(void);
 
 #ifdef __cplusplus

@@ -106,7 +106,7 @@ int64_t orc_apply_threaded(void* acc, uint64_t acc_bytes, void* out_stage, uint6
 void orc_ack_report(const uint32_t* words, uint64_t n_bits, uint64_t* cum_ack, uint64_t* n_applied,
                     uint32_t* n_ranges, uint64_t* ranges, uint32_t max_ranges);
 
-/* Per-message receiver state (Section 3.2: up to 128 messages in flight per connection, each
+/* Per-message receiver state (Section 3.1: up to 128 messages in flight per connection, each
  * of up to 256 chunks, a last-chunk mark that tells the receiver the chunk count).  The bitmap
  * is n_slots windows of bits_per_slot bits (a multiple of 32); window i holds message slot i
  * at bits [i * bits_per_slot, + limit) with limit = n_chunks[i] clamped to bits_per_slot, or

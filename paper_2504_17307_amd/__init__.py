@@ -16,9 +16,8 @@ HEADER_PATH = os.path.join(os.path.dirname(_PKG), "include", "uccl_chunk.h")
 
 UCCL_F32, UCCL_BF16, UCCL_F16, UCCL_I32 = 0, 1, 2, 3
 UCCL_SUM, UCCL_MAX, UCCL_MIN, UCCL_COPY, UCCL_PROD = 0, 1, 2, 3, 4
-UCCL_OK, UCCL_EINVAL, UCCL_EALIGN, UCCL_ELAUNCH, UCCL_ENOMEM = 0, -1, -2, -3, -4
+UCCL_OK, UCCL_EINVAL, UCCL_EALIGN, UCCL_ELAUNCH, UCCL_ENOMEM, UCCL_ETOOBIG = 0, -1, -2, -3, -4, -5
 UCCL_NO_FORWARD = 0xFFFFFFFFFFFFFFFF
-UCCL_SHAPE_AUTO, UCCL_SHAPE_WAVE, UCCL_SHAPE_GROUP, UCCL_SHAPE_FLAT = 0, 1, 2, 4
 DESC_BYTES = 32
 GATHER_DESC_BYTES = 160
 UCCL_MAX_SOURCES = 16
@@ -27,6 +26,10 @@ UCCL_MAX_SOURCES = 16
 class uccl_extents(C.Structure):
     _fields_ = [("acc_bytes", C.c_uint64), ("out_bytes", C.c_uint64),
                 ("recv_bytes", C.c_uint64), ("n_bits", C.c_uint64)]
+
+
+class uccl_launch_opts(C.Structure):
+    _fields_ = [("chunk_bytes", C.c_uint32), ("parts", C.c_uint32), ("reserved", C.c_uint32 * 2)]
 
 
 class uccl_feed_stats(C.Structure):
@@ -52,18 +55,28 @@ _SIGNATURES = {
     "uccl_chunk_apply_checked": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_uint32, C.c_void_p, C.c_int, C.c_int,
                                            C.POINTER(uccl_extents), C.c_void_p, C.c_void_p]),
+    "uccl_chunk_apply_opts": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                        C.c_uint32, C.c_void_p, C.c_int, C.c_int,
+                                        C.POINTER(uccl_extents), C.c_void_p, C.POINTER(uccl_launch_opts),
+                                        C.c_void_p]),
     "uccl_chunk_apply_indirect": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                             C.c_void_p, C.c_uint32, C.c_void_p, C.c_int, C.c_int,
-                                            C.POINTER(uccl_extents), C.c_void_p, C.c_void_p]),
+                                            C.POINTER(uccl_extents), C.c_void_p, C.POINTER(uccl_launch_opts),
+                                            C.c_void_p]),
     "uccl_chunk_reduce_gather": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
                                            C.c_void_p, C.c_int, C.c_int, C.POINTER(uccl_extents),
-                                           C.c_void_p, C.c_void_p]),
+                                           C.c_void_p, C.POINTER(uccl_launch_opts), C.c_void_p]),
     "uccl_chunk_scatter": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
                                      C.c_void_p]),
     "uccl_chunk_scatter_checked": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
                                              C.c_void_p, C.POINTER(uccl_extents), C.c_void_p,
                                              C.c_void_p]),
+    "uccl_chunk_scatter_opts": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
+                                          C.POINTER(uccl_extents), C.c_void_p, C.POINTER(uccl_launch_opts),
+                                          C.c_void_p]),
     "uccl_dedup_reset": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p]),
+    "uccl_init": (C.c_int, []),
+    "uccl_claim_timeouts": (C.c_int, [C.POINTER(C.c_uint64)]),
     "uccl_feed_create": (C.c_int, [C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_int, C.c_int, C.c_int, C.c_uint32, C.c_uint32, C.c_void_p]),
     "uccl_feed_push": (C.c_int, [C.c_void_p, C.c_int, C.c_void_p, C.c_uint32]),
@@ -75,8 +88,6 @@ _SIGNATURES = {
     "uccl_dedup_report": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p]),
     "uccl_message_status": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_int,
                                       C.c_void_p]),
-    "uccl_set_launch_shape": (C.c_int, [C.c_int]),
-    "uccl_set_chunk_hint": (C.c_int, [C.c_uint32]),
     "uccl_time_next_launch": (C.c_int, [C.c_void_p, C.c_void_p]),
     "uccl_strerror": (C.c_char_p, [C.c_int]),
     "uccl_last_error_detail": (C.c_char_p, []),
@@ -147,6 +158,15 @@ def _extents(extents, acc, out_stage, recv_stage, n_bits):
     return uccl_extents(_nbytes(acc), _nbytes(out_stage), _nbytes(recv_stage), int(n_bits))
 
 
+def _opts(opts):
+    """None, a uccl_launch_opts, or a (chunk_bytes, parts) pair -> a pointer argument."""
+    if opts is None:
+        return None
+    if not isinstance(opts, uccl_launch_opts):
+        opts = uccl_launch_opts(int(opts[0]), int(opts[1]))
+    return C.byref(opts)
+
+
 def uccl_chunk_apply(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, stream=None):
     _check(load().uccl_chunk_apply(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
                                    int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op),
@@ -164,8 +184,20 @@ def uccl_chunk_apply_checked(acc, out_stage, recv_stage, descs, n_descs, dedup_b
                                            _stream(stream)), "uccl_chunk_apply_checked")
 
 
+def uccl_chunk_apply_opts(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op,
+                          extents=None, n_rejected=None, opts=None, stream=None, n_bits=None):
+    """The general form.  Checked when ``extents`` or ``n_bits`` is given, unchecked otherwise;
+    ``opts`` is None, a uccl_launch_opts, or a (chunk_bytes, parts) pair."""
+    e = None
+    if extents is not None or n_bits is not None:
+        e = C.byref(_extents(extents, acc, out_stage, recv_stage, n_bits))
+    _check(load().uccl_chunk_apply_opts(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
+                                        int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op), e,
+                                        _ptr(n_rejected), _opts(opts), _stream(stream)), "uccl_chunk_apply_opts")
+
+
 def uccl_chunk_apply_indirect(acc, out_stage, recv_stage, descs, n_descs_ptr, max_descs, dedup_bitmap,
-                              dtype, op, extents=None, n_rejected=None, stream=None, n_bits=None):
+                              dtype, op, extents=None, n_rejected=None, opts=None, stream=None, n_bits=None):
     """``descs`` / ``n_descs_ptr`` may be pinned host tensors.  With ``n_bits`` given (or an
     explicit ``extents``) records are validated on the GPU, otherwise the call is unchecked."""
     e = None
@@ -173,18 +205,19 @@ def uccl_chunk_apply_indirect(acc, out_stage, recv_stage, descs, n_descs_ptr, ma
         e = C.byref(_extents(extents, acc, out_stage, recv_stage, n_bits))
     _check(load().uccl_chunk_apply_indirect(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
                                             _ptr(n_descs_ptr), int(max_descs), _ptr(dedup_bitmap),
-                                            int(dtype), int(op), e, _ptr(n_rejected), _stream(stream)),
-           "uccl_chunk_apply_indirect")
+                                            int(dtype), int(op), e, _ptr(n_rejected), _opts(opts),
+                                            _stream(stream)), "uccl_chunk_apply_indirect")
 
 
 def uccl_chunk_reduce_gather(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op,
-                             extents=None, n_rejected=None, stream=None, n_bits=None):
+                             extents=None, n_rejected=None, opts=None, stream=None, n_bits=None):
     e = None
     if extents is not None or n_bits is not None:
         e = C.byref(_extents(extents, acc, out_stage, recv_stage, n_bits))
     _check(load().uccl_chunk_reduce_gather(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
                                            int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op), e,
-                                           _ptr(n_rejected), _stream(stream)), "uccl_chunk_reduce_gather")
+                                           _ptr(n_rejected), _opts(opts), _stream(stream)),
+           "uccl_chunk_reduce_gather")
 
 
 def uccl_chunk_scatter(dst, recv_stage, descs, n_descs, dedup_bitmap, stream=None):
@@ -199,6 +232,26 @@ def uccl_chunk_scatter_checked(dst, recv_stage, descs, n_descs, dedup_bitmap, ex
                                              int(n_descs), _ptr(dedup_bitmap), C.byref(e),
                                              _ptr(n_rejected), _stream(stream)),
            "uccl_chunk_scatter_checked")
+
+
+def uccl_chunk_scatter_opts(dst, recv_stage, descs, n_descs, dedup_bitmap, extents=None, n_rejected=None,
+                            opts=None, stream=None, n_bits=None):
+    e = None
+    if extents is not None or n_bits is not None:
+        e = C.byref(_extents(extents, dst, None, recv_stage, n_bits))
+    _check(load().uccl_chunk_scatter_opts(_ptr(dst), _ptr(recv_stage), _ptr(descs), int(n_descs),
+                                          _ptr(dedup_bitmap), e, _ptr(n_rejected), _opts(opts),
+                                          _stream(stream)), "uccl_chunk_scatter_opts")
+
+
+def uccl_init():
+    _check(load().uccl_init(), "uccl_init")
+
+
+def uccl_claim_timeouts() -> int:
+    n = C.c_uint64(0)
+    _check(load().uccl_claim_timeouts(C.byref(n)), "uccl_claim_timeouts")
+    return n.value
 
 
 def uccl_dedup_reset(dedup_bitmap, n_bits, stream=None):
@@ -256,14 +309,6 @@ def uccl_dedup_report(dedup_bitmap, n_bits, report, max_ranges, stream=None):
     """``report``: a tensor of at least 32 + 16 * max_ranges bytes (device or pinned host)."""
     _check(load().uccl_dedup_report(_ptr(dedup_bitmap), int(n_bits), _ptr(report), int(max_ranges),
                                     _stream(stream)), "uccl_dedup_report")
-
-
-def uccl_set_launch_shape(shape):
-    _check(load().uccl_set_launch_shape(int(shape)), "uccl_set_launch_shape")
-
-
-def uccl_set_chunk_hint(chunk_bytes):
-    _check(load().uccl_set_chunk_hint(int(chunk_bytes)), "uccl_set_chunk_hint")
 
 
 def uccl_time_next_launch(start_event, stop_event):

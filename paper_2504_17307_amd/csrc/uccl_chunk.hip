@@ -27,6 +27,7 @@
 #include <string.h>
 
 #include <atomic>
+#include <mutex>
 #include <new>
 #include <tuple>
 #include <utility>
@@ -43,10 +44,6 @@ namespace {
 
 thread_local char t_detail[256] = "";
 thread_local hipEvent_t t_start = nullptr, t_stop = nullptr;  // one-shot, see uccl_time_next_launch
-// process-wide tuning knobs; atomics so that a setter racing with a launch on another thread
-// yields the old or the new value, never a torn one
-std::atomic<int> g_shape{UCCL_SHAPE_AUTO};
-std::atomic<uint32_t> g_chunk_hint{0};
 
 int launch_failed(hipError_t e) {
   snprintf(t_detail, sizeof(t_detail), "%s: %s", hipGetErrorName(e), hipGetErrorString(e));
@@ -80,10 +77,87 @@ uint32_t tiles_for(uint32_t n_descs, uint32_t tile) {
   return static_cast<uint32_t>((static_cast<uint64_t>(n_descs) + tile - 1) / tile);
 }
 
-template <int NT, int T, int SG, int U, class Op>
-int launch(const Args& a, hipStream_t s) {
-  return launch_kernel(chunk_apply_kernel<NT, T, SG, U, Op>, tiles_for(a.n_descs, T), NT, s, a);
+// ---- claim words for records cut into parts ---------------------------------------------------
+//
+// Scratch memory of the split launch (see claim_record): one 64-bit word per record of the call.
+// The library owns one pool per device, made at the first call that needs it (or by uccl_init)
+// and kept until the process ends: kRegions regions of kRegionWords words, one region per stream
+// handle that has issued a split call.  Calls on one stream run in order, so they can share a
+// region; calls on different streams may overlap, so they never do.  A call whose stream finds
+// no free region, or that is being captured into a graph (a replay would carry the captured tag
+// again, and could overlap with anything), is launched with one workgroup per record.
+constexpr uint32_t kRegionWords = 2048;  // most records a split call can have
+constexpr uint32_t kRegions = 64;
+constexpr int kMaxDevices = 64;
+constexpr size_t kPoolBytes = sizeof(unsigned long long) * kRegions * kRegionWords + 8;  // + fault counter
+
+struct ClaimPool {
+  std::atomic<unsigned long long*> base{nullptr};
+  std::mutex lock;                       // guards creation and the stream table's growth
+  std::atomic<uint32_t> n_streams{0};
+  std::atomic<uintptr_t> stream_of[kRegions];
+};
+ClaimPool g_pools[kMaxDevices];
+std::atomic<unsigned long long> g_next_tag{1};  // tags are unique across streams, devices and threads
+
+unsigned long long* pool_base(int dev, bool may_allocate) {
+  ClaimPool& p = g_pools[dev];
+  unsigned long long* b = p.base.load(std::memory_order_acquire);
+  if (b != nullptr || !may_allocate) return b;
+  std::lock_guard<std::mutex> hold(p.lock);
+  b = p.base.load(std::memory_order_acquire);
+  if (b != nullptr) return b;
+  void* mem = nullptr;
+  if (hipMalloc(&mem, kPoolBytes) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  if (hipMemset(mem, 0, kPoolBytes) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipFree(mem);
+    return nullptr;
+  }
+  p.base.store(static_cast<unsigned long long*>(mem), std::memory_order_release);
+  return static_cast<unsigned long long*>(mem);
 }
+
+uint32_t* pool_faults(unsigned long long* base) {
+  return reinterpret_cast<uint32_t*>(base + static_cast<size_t>(kRegions) * kRegionWords);
+}
+
+// The claim region of `stream` on the current device, or nullptr (then the call is not split).
+unsigned long long* claim_region(hipStream_t stream, uint32_t** faults) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
+  hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &cap) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  if (cap != hipStreamCaptureStatusNone) return nullptr;
+  unsigned long long* base = pool_base(dev, true);
+  if (base == nullptr) return nullptr;
+  ClaimPool& p = g_pools[dev];
+  const uintptr_t key = reinterpret_cast<uintptr_t>(stream) + 1;  // 0 marks a free entry; the null stream is 1
+  uint32_t n = p.n_streams.load(std::memory_order_acquire);
+  uint32_t at = kRegions;
+  for (uint32_t i = 0; i < n; ++i)
+    if (p.stream_of[i].load(std::memory_order_relaxed) == key) { at = i; break; }
+  if (at == kRegions) {
+    std::lock_guard<std::mutex> hold(p.lock);
+    n = p.n_streams.load(std::memory_order_acquire);
+    for (uint32_t i = 0; i < n; ++i)
+      if (p.stream_of[i].load(std::memory_order_relaxed) == key) { at = i; break; }
+    if (at == kRegions) {
+      if (n == kRegions) return nullptr;
+      p.stream_of[n].store(key, std::memory_order_relaxed);
+      p.n_streams.store(n + 1, std::memory_order_release);
+      at = n;
+    }
+  }
+  *faults = pool_faults(base);
+  return base + static_cast<size_t>(at) * kRegionWords;
+}
+
+// Per-call tuning (uccl_launch_opts); zero = let the library decide.
+struct Tuning {
+  uint32_t chunk_bytes;
+  uint32_t parts;
+};
 
 template <int T, int U, class Op>
 int launch_flat(const Args& a, hipStream_t s) {
@@ -91,13 +165,12 @@ int launch_flat(const Args& a, hipStream_t s) {
                        UCCL_FLAT_THREADS, s, a);
 }
 
-// Records per workgroup for the flat shape: enough that a tile holds about 32 KiB of
-// payload per stream when the chunk size is known, otherwise grown with the record count.
-uint32_t flat_tile(uint32_t n_descs) {
+// Records per workgroup: enough that a tile holds about 32 KiB of payload per stream when the
+// chunk size is known, otherwise grown with the record count.
+uint32_t flat_tile(uint32_t n_descs, uint32_t chunk_bytes) {
   uint32_t t;
-  const uint32_t hint = g_chunk_hint.load(std::memory_order_relaxed);
-  if (hint) {
-    t = (32768u + hint - 1) / hint;
+  if (chunk_bytes) {
+    t = (32768u + chunk_bytes - 1) / chunk_bytes;
   } else {
     // Unknown chunk size: a tile too large for big chunks costs a few percent, a tile too
     // small for 4 KiB chunks costs a factor of two, so grow the tile once the record count
@@ -107,29 +180,45 @@ uint32_t flat_tile(uint32_t n_descs) {
   return t < 1u ? 1u : t > 32u ? 32u : t;
 }
 
+// Calls of fewer single-record tiles than this are launched with chunk_few_kernel.
+constexpr uint32_t kFewRecords = 512;
+// Payload bytes per stream that one part's wavefronts take in their first, eagerly loaded trip.
+constexpr uint32_t kPartBytes = UCCL_PART_THREADS * UCCL_PART_UNROLL * 16u;
+
+// Workgroups per record for a call of few single-record tiles: as many as it takes to put about
+// 512 workgroups on the machine, at most 8, and no more than the chunk has trips for.  Parts
+// that find no unit in a shorter record leave at once, so a generous count costs little.
+uint32_t auto_parts(uint32_t n_descs, uint32_t chunk_bytes) {
+  uint32_t parts = 1u;
+  while (parts < 8u && n_descs * parts * 2u <= kFewRecords) parts *= 2u;
+  if (chunk_bytes)
+    while (parts > 1u && (parts - 1u) * kPartBytes >= chunk_bytes) parts /= 2u;
+  return parts;
+}
+
 template <class Op>
-int launch_flat_tile(const Args& a, hipStream_t s) {
-  const uint32_t t = flat_tile(a.n_descs);
+int launch_flat_tile(Args& a, hipStream_t s, const Tuning& tune) {
+  const uint32_t t = flat_tile(a.n_descs, tune.chunk_bytes);
   if (t >= 32) return launch_flat<32, UCCL_FLAT_UNROLL, Op>(a, s);
   if (t >= 16) return launch_flat<16, UCCL_FLAT_UNROLL, Op>(a, s);
   if (t >= 8) return launch_flat<8, UCCL_FLAT_UNROLL, Op>(a, s);
   if (t >= 4) return launch_flat<4, UCCL_FLAT_UNROLL, Op>(a, s);
   if (t >= 2) return launch_flat<2, UCCL_FLAT_UNROLL, Op>(a, s);
+  const uint32_t parts = tune.parts ? tune.parts : (a.n_descs < kFewRecords ? auto_parts(a.n_descs, tune.chunk_bytes) : 1u);
+  if (parts > 1u && a.n_descs <= kRegionWords) {
+    a.claims = claim_region(s, &a.faults);
+    if (a.claims != nullptr) {
+      a.tag = g_next_tag.fetch_add(1, std::memory_order_relaxed);
+      a.parts = parts;
+      return launch_kernel(chunk_few_kernel<UCCL_PART_THREADS, UCCL_PART_UNROLL, Op, true>, a.n_descs * parts,
+                           UCCL_PART_THREADS, s, a);
+    }
+  }
+  if (a.n_descs < kFewRecords)
+    return launch_kernel(chunk_few_kernel<UCCL_FEW_THREADS, UCCL_FEW_UNROLL, Op, false>, a.n_descs,
+                         UCCL_FEW_THREADS, s, a);
   return launch_flat<1, UCCL_FLAT_UNROLL, Op>(a, s);
 }
-
-template <class Op>
-int launch_shape(const Args& a, hipStream_t s) {
-  const int shape = g_shape.load(std::memory_order_relaxed);
-  if (shape == UCCL_SHAPE_AUTO || shape == UCCL_SHAPE_FLAT) return launch_flat_tile<Op>(a, s);
-  if (shape == UCCL_SHAPE_WAVE) {
-    if (a.n_descs >= 65536u) return launch<256, UCCL_WAVE_TILE_SMALL, 64, UCCL_WAVE_UNROLL, Op>(a, s);
-    return launch<256, UCCL_WAVE_TILE, 64, UCCL_WAVE_UNROLL, Op>(a, s);
-  }
-  if (shape == UCCL_SHAPE_GROUP) return launch<256, UCCL_GROUP_TILE, 256, UCCL_GROUP_UNROLL, Op>(a, s);
-  return UCCL_EINVAL;
-}
-
 
 template <int T, class Op>
 int launch_gather(const GatherArgs& a, hipStream_t s) {
@@ -137,8 +226,8 @@ int launch_gather(const GatherArgs& a, hipStream_t s) {
 }
 
 template <class Op>
-int launch_gather_tile(const GatherArgs& a, hipStream_t s) {
-  const uint32_t t = flat_tile(a.n_descs);
+int launch_gather_tile(const GatherArgs& a, hipStream_t s, const Tuning& tune) {
+  const uint32_t t = flat_tile(a.n_descs, tune.chunk_bytes);
   if (t >= 16) return launch_gather<16, Op>(a, s);
   if (t >= 8) return launch_gather<8, Op>(a, s);
   if (t >= 4) return launch_gather<4, Op>(a, s);
@@ -154,9 +243,17 @@ bool overlaps(const void* p, uint64_t pn, const void* q, uint64_t qn) {
   return a < b + qn && b < a + pn;
 }
 
+bool tuning_from(const uccl_launch_opts* opts, Tuning* t) {
+  *t = Tuning{0u, 0u};
+  if (opts == nullptr) return true;
+  if (opts->parts > 16u || opts->reserved[0] != 0u || opts->reserved[1] != 0u) return false;
+  *t = Tuning{opts->chunk_bytes, opts->parts};
+  return true;
+}
+
 int apply_common(void* acc, void* out_stage, const void* recv_stage, const uccl_chunk_desc* descs,
                  uint32_t n_descs, uint32_t* bitmap, int dtype, int op, bool allow_forward,
-                 const uccl_extents* ext, uint32_t* n_rejected, void* stream,
+                 const uccl_extents* ext, uint32_t* n_rejected, const Tuning& tune, void* stream,
                  const uint32_t* n_ptr = nullptr) {
   if (dtype < UCCL_F32 || dtype > UCCL_I32) return UCCL_EINVAL;
   if (op < UCCL_SUM || op > UCCL_PROD) return UCCL_EINVAL;
@@ -176,6 +273,10 @@ int apply_common(void* acc, void* out_stage, const void* recv_stage, const uccl_
   a.n_ptr = n_ptr;
   a.n_descs = n_descs;
   a.allow_forward = allow_forward ? 1u : 0u;
+  a.claims = nullptr;
+  a.faults = nullptr;
+  a.parts = 1u;
+  a.tag = 0ull;
   if (ext) {
     if (overlaps(recv_stage, ext->recv_bytes, acc, ext->acc_bytes) ||
         overlaps(recv_stage, ext->recv_bytes, out_stage, ext->out_bytes) ||
@@ -186,24 +287,24 @@ int apply_common(void* acc, void* out_stage, const void* recv_stage, const uccl_
     a.ext = Extents{UINT64_MAX, UINT64_MAX, UINT64_MAX, UINT64_MAX};
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
-  if (op == UCCL_COPY) return launch_shape<Copy>(a, s);
+  if (op == UCCL_COPY) return launch_flat_tile<Copy>(a, s, tune);
   switch (dtype * 8 + op) {
-    case UCCL_F32 * 8 + UCCL_SUM: return launch_shape<OpF32<kSum>>(a, s);
-    case UCCL_F32 * 8 + UCCL_MAX: return launch_shape<OpF32<kMax>>(a, s);
-    case UCCL_F32 * 8 + UCCL_MIN: return launch_shape<OpF32<kMin>>(a, s);
-    case UCCL_F32 * 8 + UCCL_PROD: return launch_shape<OpF32<kProd>>(a, s);
-    case UCCL_BF16 * 8 + UCCL_SUM: return launch_shape<Op16<kSum, WidenBF16>>(a, s);
-    case UCCL_BF16 * 8 + UCCL_MAX: return launch_shape<Op16<kMax, WidenBF16>>(a, s);
-    case UCCL_BF16 * 8 + UCCL_MIN: return launch_shape<Op16<kMin, WidenBF16>>(a, s);
-    case UCCL_BF16 * 8 + UCCL_PROD: return launch_shape<Op16<kProd, WidenBF16>>(a, s);
-    case UCCL_F16 * 8 + UCCL_SUM: return launch_shape<Op16<kSum, WidenF16>>(a, s);
-    case UCCL_F16 * 8 + UCCL_MAX: return launch_shape<Op16<kMax, WidenF16>>(a, s);
-    case UCCL_F16 * 8 + UCCL_MIN: return launch_shape<Op16<kMin, WidenF16>>(a, s);
-    case UCCL_F16 * 8 + UCCL_PROD: return launch_shape<Op16<kProd, WidenF16>>(a, s);
-    case UCCL_I32 * 8 + UCCL_SUM: return launch_shape<OpI32<kSum>>(a, s);
-    case UCCL_I32 * 8 + UCCL_MAX: return launch_shape<OpI32<kMax>>(a, s);
-    case UCCL_I32 * 8 + UCCL_MIN: return launch_shape<OpI32<kMin>>(a, s);
-    case UCCL_I32 * 8 + UCCL_PROD: return launch_shape<OpI32<kProd>>(a, s);
+    case UCCL_F32 * 8 + UCCL_SUM: return launch_flat_tile<OpF32<kSum>>(a, s, tune);
+    case UCCL_F32 * 8 + UCCL_MAX: return launch_flat_tile<OpF32<kMax>>(a, s, tune);
+    case UCCL_F32 * 8 + UCCL_MIN: return launch_flat_tile<OpF32<kMin>>(a, s, tune);
+    case UCCL_F32 * 8 + UCCL_PROD: return launch_flat_tile<OpF32<kProd>>(a, s, tune);
+    case UCCL_BF16 * 8 + UCCL_SUM: return launch_flat_tile<Op16<kSum, WidenBF16>>(a, s, tune);
+    case UCCL_BF16 * 8 + UCCL_MAX: return launch_flat_tile<Op16<kMax, WidenBF16>>(a, s, tune);
+    case UCCL_BF16 * 8 + UCCL_MIN: return launch_flat_tile<Op16<kMin, WidenBF16>>(a, s, tune);
+    case UCCL_BF16 * 8 + UCCL_PROD: return launch_flat_tile<Op16<kProd, WidenBF16>>(a, s, tune);
+    case UCCL_F16 * 8 + UCCL_SUM: return launch_flat_tile<Op16<kSum, WidenF16>>(a, s, tune);
+    case UCCL_F16 * 8 + UCCL_MAX: return launch_flat_tile<Op16<kMax, WidenF16>>(a, s, tune);
+    case UCCL_F16 * 8 + UCCL_MIN: return launch_flat_tile<Op16<kMin, WidenF16>>(a, s, tune);
+    case UCCL_F16 * 8 + UCCL_PROD: return launch_flat_tile<Op16<kProd, WidenF16>>(a, s, tune);
+    case UCCL_I32 * 8 + UCCL_SUM: return launch_flat_tile<OpI32<kSum>>(a, s, tune);
+    case UCCL_I32 * 8 + UCCL_MAX: return launch_flat_tile<OpI32<kMax>>(a, s, tune);
+    case UCCL_I32 * 8 + UCCL_MIN: return launch_flat_tile<OpI32<kMin>>(a, s, tune);
+    case UCCL_I32 * 8 + UCCL_PROD: return launch_flat_tile<OpI32<kProd>>(a, s, tune);
     default: return UCCL_EINVAL;
   }
 }
@@ -227,6 +328,7 @@ struct FeedSlot {
   uccl_chunk_desc* host[2];
   uccl_chunk_desc* dev[2];
   uint32_t count[2];
+  uint32_t max_len[2];  // largest payload length among the lane's records: the hand-over's chunk size
   hipEvent_t done;
   bool in_flight;
 };
@@ -280,7 +382,8 @@ int feed_flush(uccl_feed* f) {
       records = sl.dev[l];
     }
     const int rc = apply_common(f->acc, f->out_stage, f->recv_stage, records, sl.count[l], f->bitmap,
-                                f->dtype, f->op[l], true, nullptr, nullptr, f->stream);
+                                f->dtype, f->op[l], true, nullptr, nullptr, Tuning{sl.max_len[l], 0u},
+                                f->stream);
     if (rc != UCCL_OK) return rc;
   }
   const hipError_t e = hipEventRecord(sl.done, f->stream);
@@ -290,6 +393,7 @@ int feed_flush(uccl_feed* f) {
   f->stats.records += n;
   if (n > f->stats.max_batch) f->stats.max_batch = n;
   sl.count[0] = sl.count[1] = 0;
+  sl.max_len[0] = sl.max_len[1] = 0;
   // move on to the next slot; it may still be read by the copy of an earlier flush
   f->cur = (f->cur + 1) % f->n_slots;
   FeedSlot& nx = f->slots[f->cur];
@@ -365,6 +469,8 @@ int uccl_feed_push(uccl_feed* f, int lane, const uccl_chunk_desc* host_records, 
     const uint32_t room = f->capacity - sl.count[lane];
     const uint32_t take = n < room ? n : room;
     memcpy(sl.host[lane] + sl.count[lane], host_records, sizeof(uccl_chunk_desc) * take);
+    for (uint32_t i = 0; i < take; ++i)
+      if (host_records[i].len > sl.max_len[lane]) sl.max_len[lane] = host_records[i].len;
     sl.count[lane] += take;
     host_records += take;
     n -= take;
@@ -427,7 +533,17 @@ int uccl_chunk_apply(void* acc, void* out_stage, const void* recv_stage,
                      const uccl_chunk_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
                      uccl_dtype dtype, uccl_op op, void* stream) {
   return apply_common(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, true,
-                      nullptr, nullptr, stream);
+                      nullptr, nullptr, Tuning{0u, 0u}, stream);
+}
+
+int uccl_chunk_apply_opts(void* acc, void* out_stage, const void* recv_stage,
+                          const uccl_chunk_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
+                          uccl_dtype dtype, uccl_op op, const uccl_extents* extents,
+                          uint32_t* n_rejected, const uccl_launch_opts* opts, void* stream) {
+  Tuning tune;
+  if (!tuning_from(opts, &tune)) return UCCL_EINVAL;
+  return apply_common(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, true,
+                      extents, n_rejected, tune, stream);
 }
 
 int uccl_chunk_apply_checked(void* acc, void* out_stage, const void* recv_stage,
@@ -436,25 +552,29 @@ int uccl_chunk_apply_checked(void* acc, void* out_stage, const void* recv_stage,
                              const uccl_extents* extents, uint32_t* n_rejected, void* stream) {
   if (!extents) return UCCL_EINVAL;
   return apply_common(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, true,
-                      extents, n_rejected, stream);
+                      extents, n_rejected, Tuning{0u, 0u}, stream);
 }
 
 int uccl_chunk_apply_indirect(void* acc, void* out_stage, const void* recv_stage,
                               const uccl_chunk_desc* descs, const uint32_t* n_descs_ptr,
                               uint32_t max_descs, uint32_t* dedup_bitmap, uccl_dtype dtype,
                               uccl_op op, const uccl_extents* extents, uint32_t* n_rejected,
-                              void* stream) {
+                              const uccl_launch_opts* opts, void* stream) {
   if (max_descs > 0 && !n_descs_ptr) return UCCL_EINVAL;
+  Tuning tune;
+  if (!tuning_from(opts, &tune)) return UCCL_EINVAL;
   return apply_common(acc, out_stage, recv_stage, descs, max_descs, dedup_bitmap, dtype, op, true,
-                      extents, n_rejected, stream, n_descs_ptr);
+                      extents, n_rejected, tune, stream, n_descs_ptr);
 }
 
 int uccl_chunk_reduce_gather(void* acc, void* out_stage, const void* recv_stage,
                              const uccl_gather_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
                              uccl_dtype dtype, uccl_op op, const uccl_extents* extents,
-                             uint32_t* n_rejected, void* stream) {
+                             uint32_t* n_rejected, const uccl_launch_opts* opts, void* stream) {
   if (dtype < UCCL_F32 || dtype > UCCL_I32) return UCCL_EINVAL;
   if (op != UCCL_SUM && op != UCCL_MAX && op != UCCL_MIN && op != UCCL_PROD) return UCCL_EINVAL;
+  Tuning tune;
+  if (!tuning_from(opts, &tune)) return UCCL_EINVAL;
   if (n_descs == 0) return UCCL_OK;
   if (!acc || !recv_stage || !descs || !dedup_bitmap) return UCCL_EINVAL;
   if (misaligned(acc, 16) || misaligned(out_stage, 16) || misaligned(recv_stage, 16) ||
@@ -479,22 +599,22 @@ int uccl_chunk_reduce_gather(void* acc, void* out_stage, const void* recv_stage,
   }
   hipStream_t s = static_cast<hipStream_t>(stream);
   switch (dtype * 8 + op) {
-    case UCCL_F32 * 8 + UCCL_SUM: return launch_gather_tile<OpF32<kSum>>(a, s);
-    case UCCL_F32 * 8 + UCCL_MAX: return launch_gather_tile<OpF32<kMax>>(a, s);
-    case UCCL_F32 * 8 + UCCL_MIN: return launch_gather_tile<OpF32<kMin>>(a, s);
-    case UCCL_F32 * 8 + UCCL_PROD: return launch_gather_tile<OpF32<kProd>>(a, s);
-    case UCCL_BF16 * 8 + UCCL_SUM: return launch_gather_tile<Op16<kSum, WidenBF16>>(a, s);
-    case UCCL_BF16 * 8 + UCCL_MAX: return launch_gather_tile<Op16<kMax, WidenBF16>>(a, s);
-    case UCCL_BF16 * 8 + UCCL_MIN: return launch_gather_tile<Op16<kMin, WidenBF16>>(a, s);
-    case UCCL_BF16 * 8 + UCCL_PROD: return launch_gather_tile<Op16<kProd, WidenBF16>>(a, s);
-    case UCCL_F16 * 8 + UCCL_SUM: return launch_gather_tile<Op16<kSum, WidenF16>>(a, s);
-    case UCCL_F16 * 8 + UCCL_MAX: return launch_gather_tile<Op16<kMax, WidenF16>>(a, s);
-    case UCCL_F16 * 8 + UCCL_MIN: return launch_gather_tile<Op16<kMin, WidenF16>>(a, s);
-    case UCCL_F16 * 8 + UCCL_PROD: return launch_gather_tile<Op16<kProd, WidenF16>>(a, s);
-    case UCCL_I32 * 8 + UCCL_SUM: return launch_gather_tile<OpI32<kSum>>(a, s);
-    case UCCL_I32 * 8 + UCCL_MAX: return launch_gather_tile<OpI32<kMax>>(a, s);
-    case UCCL_I32 * 8 + UCCL_MIN: return launch_gather_tile<OpI32<kMin>>(a, s);
-    case UCCL_I32 * 8 + UCCL_PROD: return launch_gather_tile<OpI32<kProd>>(a, s);
+    case UCCL_F32 * 8 + UCCL_SUM: return launch_gather_tile<OpF32<kSum>>(a, s, tune);
+    case UCCL_F32 * 8 + UCCL_MAX: return launch_gather_tile<OpF32<kMax>>(a, s, tune);
+    case UCCL_F32 * 8 + UCCL_MIN: return launch_gather_tile<OpF32<kMin>>(a, s, tune);
+    case UCCL_F32 * 8 + UCCL_PROD: return launch_gather_tile<OpF32<kProd>>(a, s, tune);
+    case UCCL_BF16 * 8 + UCCL_SUM: return launch_gather_tile<Op16<kSum, WidenBF16>>(a, s, tune);
+    case UCCL_BF16 * 8 + UCCL_MAX: return launch_gather_tile<Op16<kMax, WidenBF16>>(a, s, tune);
+    case UCCL_BF16 * 8 + UCCL_MIN: return launch_gather_tile<Op16<kMin, WidenBF16>>(a, s, tune);
+    case UCCL_BF16 * 8 + UCCL_PROD: return launch_gather_tile<Op16<kProd, WidenBF16>>(a, s, tune);
+    case UCCL_F16 * 8 + UCCL_SUM: return launch_gather_tile<Op16<kSum, WidenF16>>(a, s, tune);
+    case UCCL_F16 * 8 + UCCL_MAX: return launch_gather_tile<Op16<kMax, WidenF16>>(a, s, tune);
+    case UCCL_F16 * 8 + UCCL_MIN: return launch_gather_tile<Op16<kMin, WidenF16>>(a, s, tune);
+    case UCCL_F16 * 8 + UCCL_PROD: return launch_gather_tile<Op16<kProd, WidenF16>>(a, s, tune);
+    case UCCL_I32 * 8 + UCCL_SUM: return launch_gather_tile<OpI32<kSum>>(a, s, tune);
+    case UCCL_I32 * 8 + UCCL_MAX: return launch_gather_tile<OpI32<kMax>>(a, s, tune);
+    case UCCL_I32 * 8 + UCCL_MIN: return launch_gather_tile<OpI32<kMin>>(a, s, tune);
+    case UCCL_I32 * 8 + UCCL_PROD: return launch_gather_tile<OpI32<kProd>>(a, s, tune);
     default: return UCCL_EINVAL;
   }
 }
@@ -502,7 +622,7 @@ int uccl_chunk_reduce_gather(void* acc, void* out_stage, const void* recv_stage,
 int uccl_chunk_scatter(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,
                        uint32_t n_descs, uint32_t* dedup_bitmap, void* stream) {
   return apply_common(dst, nullptr, recv_stage, descs, n_descs, dedup_bitmap, UCCL_BF16, UCCL_COPY,
-                      false, nullptr, nullptr, stream);
+                      false, nullptr, nullptr, Tuning{0u, 0u}, stream);
 }
 
 int uccl_chunk_scatter_checked(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,
@@ -510,7 +630,38 @@ int uccl_chunk_scatter_checked(void* dst, const void* recv_stage, const uccl_chu
                                const uccl_extents* extents, uint32_t* n_rejected, void* stream) {
   if (!extents) return UCCL_EINVAL;
   return apply_common(dst, nullptr, recv_stage, descs, n_descs, dedup_bitmap, UCCL_BF16, UCCL_COPY,
-                      false, extents, n_rejected, stream);
+                      false, extents, n_rejected, Tuning{0u, 0u}, stream);
+}
+
+int uccl_chunk_scatter_opts(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,
+                            uint32_t n_descs, uint32_t* dedup_bitmap, const uccl_extents* extents,
+                            uint32_t* n_rejected, const uccl_launch_opts* opts, void* stream) {
+  Tuning tune;
+  if (!tuning_from(opts, &tune)) return UCCL_EINVAL;
+  return apply_common(dst, nullptr, recv_stage, descs, n_descs, dedup_bitmap, UCCL_BF16, UCCL_COPY,
+                      false, extents, n_rejected, tune, stream);
+}
+
+int uccl_init(void) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return launch_failed(hipGetLastError());
+  if (dev < 0 || dev >= kMaxDevices) return UCCL_EINVAL;
+  return pool_base(dev, true) != nullptr ? UCCL_OK : UCCL_ENOMEM;
+}
+
+int uccl_claim_timeouts(uint64_t* count) {
+  if (!count) return UCCL_EINVAL;
+  *count = 0;
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess) return launch_failed(hipGetLastError());
+  if (dev < 0 || dev >= kMaxDevices) return UCCL_EINVAL;
+  unsigned long long* base = pool_base(dev, false);
+  if (base == nullptr) return UCCL_OK;  // no pool, no split call so far
+  uint32_t n = 0;
+  const hipError_t e = hipMemcpy(&n, pool_faults(base), sizeof(n), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return launch_failed(e);
+  *count = n;
+  return UCCL_OK;
 }
 
 int uccl_dedup_reset(uint32_t* dedup_bitmap, uint64_t n_bits, void* stream) {
@@ -553,19 +704,6 @@ int uccl_time_next_launch(void* start_event, void* stop_event) {
   return UCCL_OK;
 }
 
-int uccl_set_chunk_hint(uint32_t chunk_bytes) {
-  g_chunk_hint.store(chunk_bytes, std::memory_order_relaxed);
-  return UCCL_OK;
-}
-
-int uccl_set_launch_shape(int shape) {
-  if (shape != UCCL_SHAPE_AUTO && shape != UCCL_SHAPE_WAVE && shape != UCCL_SHAPE_GROUP &&
-      shape != UCCL_SHAPE_FLAT)
-    return UCCL_EINVAL;
-  g_shape.store(shape, std::memory_order_relaxed);
-  return UCCL_OK;
-}
-
 const char* uccl_strerror(int code) {
   switch (code) {
     case UCCL_OK: return "ok";
@@ -573,6 +711,7 @@ const char* uccl_strerror(int code) {
     case UCCL_EALIGN: return "misaligned pointer";
     case UCCL_ELAUNCH: return "HIP launch failed";
     case UCCL_ENOMEM: return "out of memory";
+    case UCCL_ETOOBIG: return "too many records for this entry point";
     default: return "unknown error code";
   }
 }

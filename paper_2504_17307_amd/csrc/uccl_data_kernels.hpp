@@ -1,27 +1,12 @@
-// Data-path kernels: dedup of a tile of records, and the three launch shapes that stream the
-// winners (flat, one wavefront per chunk, one workgroup per chunk), the multi-source fold, and the
-// bitmap fill.  Internal to the library: included by uccl_chunk.hip only.
+// Data-path kernels: dedup of a tile of records, the kernel that streams the winners (whole tiles
+// per workgroup, or one record cut into parts over several workgroups), the multi-source fold,
+// and the bitmap fill.  Internal to the library: included by uccl_chunk.hip only.
 #pragma once
 
 #include "uccl_chunk.h"
 #include "uccl_elements.hpp"
 
 // Tunable compile-time shape constants (defaults chosen by measurement on MI355X).
-#ifndef UCCL_WAVE_TILE
-#define UCCL_WAVE_TILE 4      // records per 256-thread workgroup, one wavefront per chunk
-#endif
-#ifndef UCCL_WAVE_UNROLL
-#define UCCL_WAVE_UNROLL 4
-#endif
-#ifndef UCCL_WAVE_TILE_SMALL
-#define UCCL_WAVE_TILE_SMALL 16  // same shape, used when a call carries very many records
-#endif
-#ifndef UCCL_GROUP_TILE
-#define UCCL_GROUP_TILE 1     // records per workgroup, 256 threads per chunk
-#endif
-#ifndef UCCL_GROUP_UNROLL
-#define UCCL_GROUP_UNROLL 4
-#endif
 #ifndef UCCL_GATHER_UNROLL
 #define UCCL_GATHER_UNROLL 2  // multi-sender reduce: vectors per lane per unit
 #endif
@@ -33,6 +18,21 @@
 #endif
 #ifndef UCCL_FLAT_UNROLL
 #define UCCL_FLAT_UNROLL 2    // vectors per lane per unit: a unit is 64*U*16 bytes per stream
+#endif
+#ifndef UCCL_FEW_THREADS
+#define UCCL_FEW_THREADS 1024   // calls of few records: one workgroup per record
+#endif
+#ifndef UCCL_FEW_UNROLL
+#define UCCL_FEW_UNROLL 4
+#endif
+#ifndef UCCL_PART_THREADS
+#define UCCL_PART_THREADS 256   // workgroup size when one record is cut into parts
+#endif
+#ifndef UCCL_PART_UNROLL
+#define UCCL_PART_UNROLL 2
+#endif
+#ifndef UCCL_CLAIM_SPIN_LIMIT
+#define UCCL_CLAIM_SPIN_LIMIT (1u << 16)  // polls of a claim word before a part gives up (see claim_record)
 #endif
 namespace {
 
@@ -51,44 +51,53 @@ struct Args {
   const uint32_t* n_ptr;  // optional: the record count is read from here (capped by n_descs)
   uint32_t n_descs;
   uint32_t allow_forward;
+  // one record cut into `parts` workgroups (see claim_record): claims[k] is record k's claim word,
+  // tag is this call's own value, faults counts parts that gave up waiting for a decision
+  unsigned long long* claims;
+  uint32_t* faults;
+  unsigned long long tag;
+  uint32_t parts;
 };
 
-// Stream one chunk with SG cooperating threads: U independent 16-byte vectors per thread
-// per trip, loads first, then combine and store.  Which streams carry a non-temporal
-// hint depends on the kind of chunk (see the policy masks above).
-template <int SG, int U, class Op, bool FWD, bool WB>
-__device__ __forceinline__ void stream_vectors(const u32x4* __restrict__ r, u32x4* __restrict__ a,
-                                               u32x4* __restrict__ o, uint32_t nvec,
-                                               uint32_t lane) {
-  constexpr uint32_t kPolicy = cache_policy<Op, FWD, WB>();
-  constexpr bool kNtRecv = (kPolicy & 8u) != 0, kNtOut = (kPolicy & 4u) != 0;
-  constexpr bool kNtAccLoad = (kPolicy & 2u) != 0, kNtAccStore = (kPolicy & 1u) != 0;
-  constexpr uint32_t kTrip = SG * U;
-  const uint32_t full = nvec - nvec % kTrip;
-  for (uint32_t base = lane; base < full; base += kTrip) {
-    u32x4 rv[U], av[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) rv[u] = load16<kNtRecv>(r + base + u * SG);
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if constexpr (Op::kReadsAcc) av[u] = load16<kNtAccLoad>(a + base + u * SG);
-      else av[u] = rv[u];
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      const u32x4 t = combine<Op>(av[u], rv[u]);
-      if (WB) store16<kNtAccStore>(a + base + u * SG, t);
-      if (FWD) store16<kNtOut>(o + base + u * SG, t);
-    }
+// ---- one record, several workgroups ------------------------------------------------------
+//
+// A call of few, large records (a 4 MiB message in 64 KiB chunks is 57 of them per phase) puts
+// one workgroup per record on the machine, and a single compute unit moves its 4 x 64 KiB far
+// below its share of the memory system's rate.  Such a call is launched with `parts` workgroups
+// per record, and the record's units are dealt over the wavefronts of all of them.  The sequence
+// number must still be decided exactly once, by one atomic OR on the bitmap, and every part that
+// has units must learn the outcome.  Record k of the call has a 64-bit claim word in scratch
+// memory.  Part 0 decides (bitmap atomic) and publishes `tag * 4 + outcome` with one atomic store;
+// the other parts poll the word until it carries the call's tag.  Tags are unique per call (the
+// host draws them from a 62-bit counter), so whatever an earlier call left in the word is
+// recognised as stale and nothing has to be cleared or signed off.  A part without units (short
+// record) reads the record and leaves; only part 0 always stays, to decide.
+//
+// The wait ends because workgroups of a launch start in index order on each XCD and part 0 has
+// the lowest index of its record: take the lowest-indexed part 0 that has not started; every
+// workgroup ahead of it on its XCD either has finished or waits for a part 0 of still lower
+// index, which has started and needs nothing but two memory operations to publish; so the ones
+// ahead drain and it starts.  The wait is bounded all the same: a part that gives up counts
+// itself in `faults` and streams nothing.  Claim words are read and written with device-scope
+// atomics only, so every part sees the one coherent copy whichever XCD it runs on.
+__device__ __forceinline__ bool claim_record(unsigned long long* claim, uint32_t* bitmap_word, uint32_t bit,
+                                             uint32_t* faults, uint32_t part, unsigned long long tag) {
+  if (part == 0u) {
+    const uint32_t old = atomicOr(bitmap_word, bit);
+    const bool win = (old & bit) == 0u;
+    __hip_atomic_store(claim, (tag << 2) | (win ? 1ull : 2ull), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return win;
   }
-  for (uint32_t i = full + lane; i < nvec; i += SG) {
-    const u32x4 rv = load16<kNtRecv>(r + i);
-    u32x4 av = rv;
-    if constexpr (Op::kReadsAcc) av = load16<kNtAccLoad>(a + i);
-    const u32x4 t = combine<Op>(av, rv);
-    if (WB) store16<kNtAccStore>(a + i, t);
-    if (FWD) store16<kNtOut>(o + i, t);
+  unsigned long long seen = __hip_atomic_load(claim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (uint32_t polls = 0; (seen >> 2) != tag; ++polls) {
+    if (polls >= UCCL_CLAIM_SPIN_LIMIT) {
+      atomicAdd(faults, 1u);
+      return false;
+    }
+    __builtin_amdgcn_s_sleep(1);
+    seen = __hip_atomic_load(claim, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+  return (seen & 3ull) == 1ull;
 }
 
 // The last len % 16 bytes of a chunk, element by element.
@@ -118,17 +127,20 @@ __device__ __forceinline__ void stream_tail(const char* r, char* a, char* o, uin
   }
 }
 
-template <int SG, int U, class Op, bool FWD, bool WB>
-__device__ __forceinline__ void stream_chunk(const char* r, char* a, char* o, uint32_t len,
-                                             uint32_t lane) {
-  const uint32_t nvec = len >> 4;
-  stream_vectors<SG, U, Op, FWD, WB>(reinterpret_cast<const u32x4*>(r), reinterpret_cast<u32x4*>(a),
-                                 reinterpret_cast<u32x4*>(o), nvec, lane);
-  const uint32_t rem = len & 15u;
-  if (rem) {
-    const uint64_t off = static_cast<uint64_t>(nvec) << 4;
-    stream_tail<Op, FWD, WB>(r + off, a + off, FWD ? o + off : o, rem, lane);
-  }
+// What a record must satisfy before its bit is touched (the unchecked entry points pass
+// unbounded extents, which leaves alignment, granularity and the forward rules).
+template <class Op>
+__device__ __forceinline__ bool record_ok(const Args& g, uint64_t src, uint64_t dst, uint64_t out,
+                                          uint32_t len, uint32_t seq) {
+  const bool fwd = out != UCCL_NO_FORWARD;
+  const uint64_t out_at = out & ~UCCL_FORWARD_ONLY;
+  bool ok = seq < g.ext.n_bits && ((src | dst) & 15u) == 0 && len % Op::kEs == 0 &&
+            src <= g.ext.recv_bytes && len <= g.ext.recv_bytes - src &&
+            dst <= g.ext.acc_bytes && len <= g.ext.acc_bytes - dst;
+  if (fwd)
+    ok = ok && g.allow_forward && g.out != nullptr && (out_at & 15u) == 0 &&
+         out_at <= g.ext.out_bytes && len <= g.ext.out_bytes - out_at;
+  return ok;
 }
 
 // Winners of one tile of records, compacted; first[] is the exclusive prefix sum of
@@ -160,14 +172,7 @@ __device__ __forceinline__ void dedup_tile(const Args& g, Tile<T>& s, uint32_t t
     out = hi.x | (static_cast<uint64_t>(hi.y) << 32);
     len = hi.z;
     const uint32_t seq = hi.w;
-    const bool fwd = out != UCCL_NO_FORWARD;
-    const uint64_t out_at = out & ~UCCL_FORWARD_ONLY;
-    bool ok = seq < g.ext.n_bits && ((src | dst) & 15u) == 0 && len % Op::kEs == 0 &&
-              src <= g.ext.recv_bytes && len <= g.ext.recv_bytes - src &&
-              dst <= g.ext.acc_bytes && len <= g.ext.acc_bytes - dst;
-    if (fwd)
-      ok = ok && g.allow_forward && g.out != nullptr && (out_at & 15u) == 0 &&
-           out_at <= g.ext.out_bytes && len <= g.ext.out_bytes - out_at;
+    const bool ok = record_ok<Op>(g, src, dst, out, len, seq);
     if (k >= live) {
       // beyond the published count: not a record at all, neither applied nor rejected
     } else if (ok) {
@@ -200,34 +205,6 @@ __device__ __forceinline__ void dedup_tile(const Args& g, Tile<T>& s, uint32_t t
     }
     if (win) s.first[pos] = incl - units;
     if (tid == 63) s.first[count] = incl;
-  }
-}
-
-// Shapes WAVE / GROUP: subgroups of SG threads take whole winners in turn.  Kept
-// selectable because they are the obvious alternatives (one wavefront per chunk, one
-// workgroup per chunk); both measure slower than the flat shape on MI355X.
-template <int NT, int T, int SG, int U, class Op>
-__global__ void __launch_bounds__(NT) chunk_apply_kernel(const Args g) {
-  static_assert(NT % SG == 0 && SG % 64 == 0, "subgroups are whole wavefronts");
-  constexpr uint32_t kSubgroups = NT / SG;
-  __shared__ Tile<T> s;
-  const uint32_t tid = threadIdx.x;
-  if (tid < 64) dedup_tile<T, Op, 0>(g, s, tid);
-  __syncthreads();
-
-  const uint32_t count = s.count;
-  const uint32_t sg = tid / SG, lane = tid % SG;
-  for (uint32_t w = sg; w < count; w += kSubgroups) {
-    const uint64_t src = wave_uniform(s.src[w]);
-    const uint64_t dst = wave_uniform(s.dst[w]);
-    const uint64_t out = wave_uniform(s.out[w]);
-    const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
-    if (out == UCCL_NO_FORWARD)
-      stream_chunk<SG, U, Op, false, true>(g.recv + src, g.acc + dst, nullptr, len, lane);
-    else if (out & UCCL_FORWARD_ONLY)
-      stream_chunk<SG, U, Op, true, false>(g.recv + src, g.acc + dst, g.out + (out & ~UCCL_FORWARD_ONLY), len, lane);
-    else
-      stream_chunk<SG, U, Op, true, true>(g.recv + src, g.acc + dst, g.out + out, len, lane);
   }
 }
 
@@ -280,9 +257,9 @@ __device__ __forceinline__ void stream_unit(const char* r, char* a, char* o, uin
   }
 }
 
-// Shape FLAT: the winners' units are numbered consecutively across the tile and dealt
-// round-robin to the 16 wavefronts of a 1024-thread workgroup, so the machine sees the
-// same stream whether a tile holds one 128 KiB chunk or thirty-two 4 KiB chunks.
+// The winners' units are numbered consecutively across the tile and dealt round-robin to the
+// wavefronts of the workgroup, so the machine sees the same stream whether a tile holds one
+// 128 KiB chunk or thirty-two 4 KiB chunks.
 template <int NT, int T, int U, class Op>
 __global__ void __launch_bounds__(NT) chunk_flat_kernel(const Args g) {
   constexpr uint32_t kUnit = 64u * U;
@@ -313,6 +290,115 @@ __global__ void __launch_bounds__(NT) chunk_flat_kernel(const Args g) {
       stream_unit<U, Op, true, false>(g.recv + src, g.acc + dst, g.out + (out & ~UCCL_FORWARD_ONLY), len, trip, lane);
     else
       stream_unit<U, Op, true, true>(g.recv + src, g.acc + dst, g.out + out, len, trip, lane);
+  }
+}
+
+// ---- calls of few records --------------------------------------------------------------------
+//
+// A call of a few dozen records (a 4 MiB message in 64 KiB chunks is 57 of them per phase) cannot
+// fill the machine; what it costs is one workgroup's chain of latencies: read the record, decide
+// the sequence number (one atomic round trip), read the payload, write it.  This kernel shortens
+// the chain instead of the stream: one record per workgroup (or per group of `parts` workgroups),
+// every wavefront reads the record for itself and issues the loads of its first unit at once,
+// while one lane decides the sequence number; after one barrier the winners combine and store
+// what is already in registers.  A duplicate therefore costs its payload reads (never a write),
+// which is why calls of many records, where duplicates are many and latency is hidden by the
+// number of workgroups anyway, use chunk_flat_kernel.  PARTS: blockIdx.x = record * parts + part
+// (see claim_record).
+template <int U, class Op, bool FWD, bool WB>
+__device__ __forceinline__ void finish_unit(const u32x4 (&rv)[U], const u32x4 (&av)[U], u32x4* ap,
+                                            u32x4* op, uint32_t first_vec, uint32_t nvec) {
+  constexpr uint32_t kPolicy = cache_policy<Op, FWD, WB>();
+  constexpr bool kNtOut = (kPolicy & 4u) != 0, kNtAccStore = (kPolicy & 1u) != 0;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (first_vec + u * 64 < nvec) {
+      const u32x4 t = combine<Op>(Op::kReadsAcc ? av[u] : rv[u], rv[u]);
+      if (WB) store16<kNtAccStore>(ap + u * 64, t);
+      if (FWD) store16<kNtOut>(op + u * 64, t);
+    }
+  }
+}
+
+template <int NT, int U, class Op, bool PARTS>
+__global__ void __launch_bounds__(NT) chunk_few_kernel(const Args g) {
+  constexpr uint32_t kUnit = 64u * U;
+  constexpr uint32_t kWaves = NT / 64;
+  __shared__ uint32_t s_win;
+  const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63u;
+  const uint32_t k = PARTS ? blockIdx.x / g.parts : blockIdx.x;   // the launch has n_descs (* parts) workgroups
+  const uint32_t part = PARTS ? blockIdx.x % g.parts : 0u;
+
+  // every lane reads the same 32 bytes: one request per wavefront
+  const u32x4* p = reinterpret_cast<const u32x4*>(g.descs + k);
+  const u32x4 lo = p[0], hi = p[1];
+  const uint32_t live = g.n_ptr != nullptr ? *g.n_ptr : g.n_descs;
+  const uint64_t src = wave_uniform(lo.x | (static_cast<uint64_t>(lo.y) << 32));
+  const uint64_t dst = wave_uniform(lo.z | (static_cast<uint64_t>(lo.w) << 32));
+  const uint64_t out = wave_uniform(hi.x | (static_cast<uint64_t>(hi.y) << 32));
+  const uint32_t len = __builtin_amdgcn_readfirstlane(hi.z);
+  const uint32_t seq = __builtin_amdgcn_readfirstlane(hi.w);
+  const bool is_record = k < live;
+  const bool ok = is_record && record_ok<Op>(g, src, dst, out, len, seq);
+
+  const uint32_t nvec = len >> 4;
+  const uint32_t vecs = nvec + ((len & 15u) != 0u ? 1u : 0u);
+  const uint32_t total = (vecs + kUnit - 1u) / kUnit;
+  const uint32_t stride = PARTS ? kWaves * g.parts : kWaves;
+  const uint32_t u0 = part * kWaves + wave;
+  const uint32_t first_vec = u0 * kUnit + lane;
+  const bool have = ok && u0 < total;
+  if (PARTS && part != 0u && part * kWaves >= total) return;  // no unit for any wavefront of this part: all leave together
+  const u32x4* rp = reinterpret_cast<const u32x4*>(g.recv + src) + first_vec;
+  u32x4* ap = reinterpret_cast<u32x4*>(g.acc + dst) + first_vec;
+  u32x4 rv[U], av[U];
+  if (have) {  // in bounds whether or not this record turns out to be the first arrival
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+      if (first_vec + u * 64 < nvec) rv[u] = __builtin_nontemporal_load(rp + u * 64);
+    if constexpr (Op::kReadsAcc) {
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (first_vec + u * 64 < nvec) av[u] = ap[u * 64];
+    }
+  }
+  if (tid == 0) {
+    uint32_t win = 0u;
+    if (ok) {
+      const uint32_t bit = 1u << (seq & 31u);
+      if constexpr (PARTS) {
+        win = claim_record(g.claims + k, g.bitmap + (seq >> 5), bit, g.faults, part, g.tag) ? 1u : 0u;
+      } else {
+        win = (atomicOr(g.bitmap + (seq >> 5), bit) & bit) == 0u ? 1u : 0u;
+      }
+    } else if (is_record && g.rejected != nullptr && part == 0u) {  // a rejected record is counted once
+      atomicAdd(g.rejected, 1u);
+    }
+    s_win = win;
+  }
+  __syncthreads();
+  if (s_win != 0u) {
+    const bool fwd = out != UCCL_NO_FORWARD;
+    const bool relay = fwd && (out & UCCL_FORWARD_ONLY) != 0;
+    char* o = g.out + (out & ~UCCL_FORWARD_ONLY);
+    if (have) {
+      u32x4* op = reinterpret_cast<u32x4*>(o) + first_vec;
+      if (!fwd) finish_unit<U, Op, false, true>(rv, av, ap, op, first_vec, nvec);
+      else if (relay) finish_unit<U, Op, true, false>(rv, av, ap, op, first_vec, nvec);
+      else finish_unit<U, Op, true, true>(rv, av, ap, op, first_vec, nvec);
+      const uint32_t rem = len & 15u;
+      if (rem != 0u && nvec >= u0 * kUnit && nvec < (u0 + 1u) * kUnit) {  // the unit that holds the partial vector
+        const uint64_t off = static_cast<uint64_t>(nvec) << 4;
+        if (!fwd) stream_tail<Op, false, true>(g.recv + src + off, g.acc + dst + off, nullptr, rem, lane);
+        else if (relay) stream_tail<Op, true, false>(g.recv + src + off, g.acc + dst + off, o + off, rem, lane);
+        else stream_tail<Op, true, true>(g.recv + src + off, g.acc + dst + off, o + off, rem, lane);
+      }
+    }
+    for (uint32_t u = u0 + stride; u < total; u += stride) {
+      if (!fwd) stream_unit<U, Op, false, true>(g.recv + src, g.acc + dst, nullptr, len, u, lane);
+      else if (relay) stream_unit<U, Op, true, false>(g.recv + src, g.acc + dst, o, len, u, lane);
+      else stream_unit<U, Op, true, true>(g.recv + src, g.acc + dst, o, len, u, lane);
+    }
   }
 }
 

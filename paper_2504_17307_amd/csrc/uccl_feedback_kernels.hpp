@@ -107,7 +107,7 @@ __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __rest
   }
 }
 
-// Per-message window status (Section 3.2's message id / chunk sequence number / last-chunk
+// Per-message window status (Section 3.1's message id / chunk sequence number / last-chunk
 // mark): one wavefront per slot.  Lane l owns word l of the slot's window (a window is at
 // most 64 words), masks it to the slot's limit, and the wavefront combines: a ballot of
 // "has a clear bit below the limit" locates the first hole, a butterfly sum gives the

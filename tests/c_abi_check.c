@@ -118,7 +118,6 @@ static int feed_check(hipStream_t st) {
   CK(hipMemcpy(d_recv, h_recv, recv_bytes, hipMemcpyHostToDevice));
   float* g_acc = (float*)malloc(acc_bytes);
   unsigned char* g_out = (unsigned char*)malloc(out_bytes);
-  UC(uccl_set_chunk_hint(CH));
   double us[2];
   uccl_feed_stats stats[2];
   for (int mode = 0; mode < 2; ++mode) { /* 0: adaptive (poll), 1: hand over after every message */
@@ -144,7 +143,6 @@ static int feed_check(hipStream_t st) {
     if (memcmp(g_acc, o_acc, acc_bytes)) { fprintf(stderr, "feed mode %d: acc differs\n", mode); return 8; }
     if (memcmp(g_out, o_out, out_bytes)) { fprintf(stderr, "feed mode %d: out_stage differs\n", mode); return 8; }
   }
-  UC(uccl_set_chunk_hint(0));
   printf("FEED OK: %d messages, %llu records; adaptive %.2f us/message (%llu hand-overs, largest %llu records, "
          "%llu slot waits); one hand-over per message %.2f us/message (%llu hand-overs, %llu slot waits)\n",
          (int)M, (unsigned long long)n_rec, us[0], (unsigned long long)stats[0].flushes,

@@ -18,8 +18,9 @@ def to_host(t: torch.Tensor, like_dtype) -> np.ndarray:
 class DeviceRun:
     """Device-resident buffers of one workload."""
 
-    def __init__(self, w, guard=0xA5):
+    def __init__(self, w, guard=0xA5, opts=None):
         self.w = w
+        self.opts = opts  # None, or (chunk_bytes, parts): per-call tuning passed to the general entry point
         self.acc = to_dev(w.acc)
         self.recv = to_dev(w.recv_stage)
         self.out = torch.full((w.out_bytes,), guard, dtype=torch.uint8, device="cuda") if w.out_bytes else None
@@ -31,7 +32,11 @@ class DeviceRun:
         pkg.uccl_dedup_reset(self.bitmap, self.w.n_bits)
 
     def apply(self, descs_dev, n, op, checked=True, stream=None):
-        if checked:
+        if self.opts is not None:
+            pkg.uccl_chunk_apply_opts(self.acc, self.out, self.recv, descs_dev, n, self.bitmap, self.w.dtype, op,
+                                      n_rejected=self.rejected if checked else None,
+                                      n_bits=self.w.n_bits if checked else None, opts=self.opts, stream=stream)
+        elif checked:
             pkg.uccl_chunk_apply_checked(self.acc, self.out, self.recv, descs_dev, n, self.bitmap,
                                          self.w.dtype, op, n_rejected=self.rejected,
                                          n_bits=self.w.n_bits, stream=stream)

@@ -20,12 +20,13 @@ def test_library_exports_every_declared_symbol():
     names = declared_functions()
     assert {"uccl_chunk_apply", "uccl_chunk_scatter", "uccl_dedup_reset", "uccl_strerror",
             "uccl_version", "uccl_chunk_apply_checked", "uccl_chunk_apply_indirect", "uccl_chunk_scatter_checked",
-            "uccl_set_launch_shape", "uccl_set_chunk_hint", "uccl_dedup_report", "uccl_time_next_launch",
-            "uccl_last_error_detail"} <= set(names)
+            "uccl_chunk_apply_opts", "uccl_chunk_scatter_opts", "uccl_init", "uccl_dedup_report",
+            "uccl_time_next_launch", "uccl_last_error_detail"} <= set(names)
+    assert not [n for n in names if n.startswith("uccl_set_")], "no process-wide tuning knob in the ABI"
     for n in names:
         assert hasattr(lib, n), n
     assert set(names) == set(pkg._SIGNATURES), "binding and header list the same entry points"
-    assert lib.uccl_version() == 1
+    assert lib.uccl_version() == 2
 
 
 def test_record_layout_matches_generators():
@@ -63,9 +64,19 @@ def test_host_side_error_codes_enqueue_nothing():
     e = pkg.uccl_extents(0x1000, 0, 0x1000, 8)
     assert g(A, None, B, D, 1, M, 0, 0, C.byref(e), 0x50002, None) == pkg.UCCL_EALIGN
     i = lib.uccl_chunk_apply_indirect
-    assert i(A, None, B, D, None, 4, M, 0, 0, None, None, None) == pkg.UCCL_EINVAL   # count pointer required
-    assert i(A, None, B, D, 0x60002, 4, M, 0, 0, None, None, None) == pkg.UCCL_EALIGN
-    assert i(None, None, None, None, None, 0, None, 0, 0, None, None, None) == pkg.UCCL_OK
+    assert i(A, None, B, D, None, 4, M, 0, 0, None, None, None, None) == pkg.UCCL_EINVAL   # count pointer required
+    assert i(A, None, B, D, 0x60002, 4, M, 0, 0, None, None, None, None) == pkg.UCCL_EALIGN
+    assert i(None, None, None, None, None, 0, None, 0, 0, None, None, None, None) == pkg.UCCL_OK
+    o = lib.uccl_chunk_apply_opts
+    assert o(None, None, None, None, 0, None, 0, 0, None, None, None, None) == pkg.UCCL_OK
+    assert o(A, None, B, D, 1, M, 0, 0, None, None, C.byref(pkg.uccl_launch_opts(4096, 17)), None) == pkg.UCCL_EINVAL
+    bad = pkg.uccl_launch_opts(4096, 2)
+    bad.reserved[1] = 1
+    assert o(A, None, B, D, 1, M, 0, 0, None, None, C.byref(bad), None) == pkg.UCCL_EINVAL
+    assert o(A + 8, None, B, D, 1, M, 0, 0, None, None, C.byref(pkg.uccl_launch_opts(4096, 2)), None) == pkg.UCCL_EALIGN
+    assert lib.uccl_chunk_scatter_opts(A, B, D, 1, M, None, None, C.byref(pkg.uccl_launch_opts(0, 99)), None) == pkg.UCCL_EINVAL
+    assert lib.uccl_chunk_reduce_gather(A, None, B, D, 1, M, 0, 0, None, None, C.byref(pkg.uccl_launch_opts(0, 99)), None) == pkg.UCCL_EINVAL
+    assert lib.uccl_claim_timeouts(None) == pkg.UCCL_EINVAL
     s = lib.uccl_chunk_scatter
     assert s(None, B, D, 1, M, None) == pkg.UCCL_EINVAL
     assert s(A + 1, B, D, 1, M, None) == pkg.UCCL_EALIGN
@@ -97,7 +108,6 @@ def test_host_side_error_codes_enqueue_nothing():
     for fn in (lib.uccl_feed_poll, lib.uccl_feed_flush, lib.uccl_feed_sync, lib.uccl_feed_destroy):
         assert fn(None) == pkg.UCCL_EINVAL
     assert lib.uccl_feed_push(None, 0, D, 1) == pkg.UCCL_EINVAL
-    assert lib.uccl_set_launch_shape(9) == pkg.UCCL_EINVAL and lib.uccl_set_launch_shape(3) == pkg.UCCL_EINVAL and lib.uccl_set_launch_shape(0) == pkg.UCCL_OK
     assert pkg.uccl_strerror(pkg.UCCL_EALIGN) == "misaligned pointer"
     with pytest.raises(pkg.UcclError) as err:
         pkg.uccl_chunk_apply(None, None, B, D, 1, M, 0, 0, stream=0)

@@ -240,7 +240,7 @@ def test_rejects_malformed_records():
 
 # ---- GPU parity ----------------------------------------------------------------------------------
 
-def gpu_run(pkg, w, op=None, checked=True):
+def gpu_run(pkg, w, op=None, checked=True, opts=None):
     import torch
     from gpuhelp import to_dev, to_host
     ph = w.phases[0]
@@ -250,7 +250,7 @@ def gpu_run(pkg, w, op=None, checked=True):
     rej = torch.zeros(1, dtype=torch.int32, device="cuda")
     pkg.uccl_chunk_reduce_gather(acc, out, recv, to_dev(ph.descs), len(ph.descs), bm, w.dtype,
                                  ph.op if op is None else op, n_rejected=rej if checked else None,
-                                 n_bits=w.n_bits if checked else None)
+                                 n_bits=w.n_bits if checked else None, opts=opts)
     torch.cuda.synchronize()
     return (to_host(acc, w.acc.dtype), None if out is None else out.cpu().numpy(),
             bm.cpu().numpy().view(np.uint32), int(rej.item()))
@@ -263,21 +263,17 @@ def gpu_run(pkg, w, op=None, checked=True):
 def test_gpu_gather_reduce_parity(gpu_lib, dtype, op, hint):
     from gpuhelp import assert_same
     w = make(dtype, dist="normal" if dtype == BF16 else "uniform", op=op, R=8, C=4112, chunks=29)
-    gpu_lib.uccl_set_chunk_hint(hint)
-    try:
-        for checked in (True, False):
-            acc, out, bm, rej = gpu_run(gpu_lib, w, checked=checked)
-            eacc, eout, ebm, _ = run_oracle(w)
-            assert rej == 0
-            assert_same(bm, ebm, "bitmap")
-            wide = {F32: lambda x: x, BF16: lambda x: (x.astype(np.uint32) << 16).view(np.float32),
-                    F16: lambda x: x.view(np.float16).astype(np.float32), I32: lambda x: x.astype(np.float32)}[dtype]
-            with np.errstate(over="ignore", invalid="ignore"):
-                nan = np.isnan(wide(eacc))
-            assert np.array_equal(np.isnan(wide(acc)), nan)
-            assert_same(acc[~nan], eacc[~nan], "acc")
-    finally:
-        gpu_lib.uccl_set_chunk_hint(0)
+    for checked in (True, False):
+        acc, out, bm, rej = gpu_run(gpu_lib, w, checked=checked, opts=(hint, 0))
+        eacc, eout, ebm, _ = run_oracle(w)
+        assert rej == 0
+        assert_same(bm, ebm, "bitmap")
+        wide = {F32: lambda x: x, BF16: lambda x: (x.astype(np.uint32) << 16).view(np.float32),
+                F16: lambda x: x.view(np.float16).astype(np.float32), I32: lambda x: x.astype(np.float32)}[dtype]
+        with np.errstate(over="ignore", invalid="ignore"):
+            nan = np.isnan(wide(eacc))
+        assert np.array_equal(np.isnan(wide(acc)), nan)
+        assert_same(acc[~nan], eacc[~nan], "acc")
 
 
 @pytest.mark.gpu

@@ -74,16 +74,16 @@ def test_graph_replay_per_message(gpu_lib):
     slots = {k: pinned(cap * 32) for k in ("rs", "ag")}
     counts_t, counts_v = pinned(8)
     counts = counts_v.view(np.uint32)
-    gpu_lib.uccl_set_chunk_hint(4096)
     g = torch.cuda.CUDAGraph()
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.graph(g, stream=side):
         gpu_lib.uccl_chunk_apply_indirect(run.acc, run.out, run.recv, slots["rs"][0], counts_t[0:4], cap,
-                                          run.bitmap, F32, SUM, n_rejected=run.rejected, n_bits=w.n_bits)
+                                          run.bitmap, F32, SUM, n_rejected=run.rejected, n_bits=w.n_bits,
+                                          opts=(4096, 0))
         gpu_lib.uccl_chunk_apply_indirect(run.acc, run.out, run.recv, slots["ag"][0], counts_t[4:8], cap,
-                                          run.bitmap, F32, COPY, n_rejected=run.rejected, n_bits=w.n_bits)
-    gpu_lib.uccl_set_chunk_hint(0)
+                                          run.bitmap, F32, COPY, n_rejected=run.rejected, n_bits=w.n_bits,
+                                          opts=(4096, 0))
     eacc = w.acc.copy()
     eout = np.zeros(w.out_bytes, dtype=np.uint8)
     seen = oracle.new_seen(w.n_bits)
@@ -117,7 +117,6 @@ def test_host_side_feed_batches_messages(gpu_lib, capacity, poll):
     larger than everything: the result is the oracle's, and the batcher really batched."""
     w, msgs = wl.config5(seed=8, n_msgs=40)
     run = DeviceRun(w, guard=0)
-    gpu_lib.uccl_set_chunk_hint(4096)
     feed = gpu_lib.uccl_feed_create(run.acc, run.out, run.recv, run.bitmap, F32, SUM, COPY, capacity, 4)
     try:
         for m in msgs:
@@ -129,7 +128,6 @@ def test_host_side_feed_batches_messages(gpu_lib, capacity, poll):
         stats = gpu_lib.uccl_feed_get_stats(feed)
     finally:
         gpu_lib.uccl_feed_destroy(feed)
-        gpu_lib.uccl_set_chunk_hint(0)
     total = sum(len(m["rs"]) + len(m["ag"]) for m in msgs)
     assert stats["records"] == total and stats["flushes"] >= 1 and stats["max_batch"] <= 2 * capacity
     if capacity == 100000 and not poll:
@@ -148,7 +146,6 @@ def test_host_side_feed_large_hand_over(gpu_lib):
     same result either way."""
     w, msgs = wl.config5(seed=9, n_msgs=220)
     run = DeviceRun(w, guard=0)
-    gpu_lib.uccl_set_chunk_hint(4096)
     feed = gpu_lib.uccl_feed_create(run.acc, run.out, run.recv, run.bitmap, F32, SUM, COPY, 1 << 17, 2)
     try:
         for m in msgs:
@@ -158,7 +155,6 @@ def test_host_side_feed_large_hand_over(gpu_lib):
         stats = gpu_lib.uccl_feed_get_stats(feed)
     finally:
         gpu_lib.uccl_feed_destroy(feed)
-        gpu_lib.uccl_set_chunk_hint(0)
     assert stats["flushes"] == 1 and stats["max_batch"] > 2 * 16384, stats  # both lanes above the direct-read limit
     eacc, eout, seen = w.acc.copy(), np.zeros(w.out_bytes, dtype=np.uint8), oracle.new_seen(w.n_bits)
     for m in msgs:
@@ -222,3 +218,50 @@ def test_host_side_feed_random_push_pattern(gpu_lib, seed):
     assert_same(bitmap.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap")
     assert_same(d_acc.cpu().numpy().view(np.float32), eacc, "acc")
     assert_same(d_out.cpu().numpy(), eout, "out")
+
+
+def test_two_feeds_with_different_chunk_sizes_interleaved(gpu_lib):
+    """Two connections in one process, one with 4 KiB chunks and one with 128 KiB chunks, each
+    with a feed of its own on a stream of its own, pushed alternately from one thread: the
+    launch of each hand-over is sized from that feed's own records (nothing process-wide), and
+    both results are the oracle's.  The 128 KiB connection hands over few records at a time, so
+    its records are cut into parts; both feeds' streams then hold claim regions of their own."""
+    from synth.layout import BF16
+    small = wl.ring_share("small", 51, R=4, M=4 * 300 * 4096, C=4096, dtype=F32, paths=8, window=64, dup=0.05,
+                          dist="uniform")
+    large = wl.ring_share("large", 52, R=4, M=4 * 24 * (128 << 10), C=128 << 10, dtype=BF16, paths=8, window=16,
+                          dup=0.05, dist="normal")
+    runs = [DeviceRun(small, guard=0), DeviceRun(large, guard=0)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for s in streams:
+        s.wait_stream(torch.cuda.current_stream())
+    feeds = [gpu_lib.uccl_feed_create(r.acc, r.out, r.recv, r.bitmap, r.w.dtype, SUM, COPY, cap, 4, stream=s)
+             for r, cap, s in zip(runs, (512, 40), streams)]
+    try:
+        cursors = [[0, 0], [0, 0]]
+        steps = [97, 7]
+        busy = True
+        while busy:
+            busy = False
+            for f, (feed, run, step) in enumerate(zip(feeds, runs, steps)):
+                for lane, ph in enumerate(run.w.phases):
+                    lo = cursors[f][lane]
+                    # the allgather lane starts only once the reduce-scatter lane has been pushed completely
+                    if lo >= len(ph.descs) or (lane == 1 and cursors[f][0] < len(run.w.phases[0].descs)):
+                        continue
+                    gpu_lib.uccl_feed_push(feed, lane, np.ascontiguousarray(ph.descs[lo:lo + step]))
+                    cursors[f][lane] = lo + step
+                    busy = True
+                gpu_lib.uccl_feed_poll(feed)
+        for feed in feeds:
+            gpu_lib.uccl_feed_sync(feed)
+    finally:
+        for feed in feeds:
+            gpu_lib.uccl_feed_destroy(feed)
+    assert gpu_lib.uccl_claim_timeouts() == 0
+    for run in runs:
+        eacc, eout, ebm = oracle_results(run.w, guard=0)
+        acc, out, bm, _ = run.results()
+        assert_same(bm, ebm, run.w.name + " bitmap")
+        assert_same(acc, eacc, run.w.name + " acc")
+        assert_same(out, eout, run.w.name + " out")

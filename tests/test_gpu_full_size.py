@@ -1,5 +1,5 @@
-"""Full-size parity, in the launch configuration bench.py times: the unchecked entry
-point, automatic launch shape, the transport's chunk size given as a hint.  Every output
+"""Full-size parity, in the launch configuration bench.py times: the unchecked general entry
+point, the transport's chunk size given with the call, everything else left to the library.  Every output
 element of every configuration is compared with the oracle (the oracle finishes each of
 them in seconds, so no sampling is needed)."""
 import sys
@@ -23,15 +23,21 @@ def say(*a):
 
 
 def run_full(pkg, w, chunk):
-    pkg.uccl_set_launch_shape(0)
-    pkg.uccl_set_chunk_hint(chunk)
-    try:
-        run = DeviceRun(w)
-        run.reset()
-        run.run_phases(checked=False)
-        return run.results()
-    finally:
-        pkg.uccl_set_chunk_hint(0)
+    run = DeviceRun(w, opts=(chunk, 0))
+    run.reset()
+    run.run_phases(checked=False)
+    assert pkg.uccl_claim_timeouts() == 0
+    return run.results()
+
+
+def test_config1_full_size_as_benchmarked(gpu_lib):
+    """4 MiB fp32 in 64 KiB chunks: 57 + 56 records, each cut into parts by the library's own choice."""
+    w = wl.config1(seed=1)
+    eacc, eout, ebm = oracle_results(w)
+    acc, out, bm, _ = run_full(gpu_lib, w, 64 << 10)
+    assert_same(bm, ebm, "bitmap")
+    assert_same(acc, eacc, "acc")
+    assert_same(out, eout, "out_stage")
 
 
 @pytest.mark.parametrize("name,chunk", [("config2", 32 << 10), ("config3", 128 << 10)])
@@ -56,14 +62,11 @@ def test_ring_share_full_size(gpu_lib, name, chunk):
 def test_alltoall_full_size(gpu_lib):
     w = wl.config4(seed=1)
     ph = w.phases[0]
-    gpu_lib.uccl_set_chunk_hint(16 << 10)
-    try:
-        dst = torch.zeros(w.acc.nbytes, dtype=torch.uint8, device="cuda")
-        bm = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
-        gpu_lib.uccl_chunk_scatter(dst, to_dev(w.recv_stage), to_dev(ph.descs), len(ph.descs), bm)
-        torch.cuda.synchronize()
-    finally:
-        gpu_lib.uccl_set_chunk_hint(0)
+    dst = torch.zeros(w.acc.nbytes, dtype=torch.uint8, device="cuda")
+    bm = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
+    gpu_lib.uccl_chunk_scatter_opts(dst, to_dev(w.recv_stage), to_dev(ph.descs), len(ph.descs), bm,
+                                    opts=(16 << 10, 0))
+    torch.cuda.synchronize()
     edst = np.zeros(w.acc.nbytes, dtype=np.uint8)
     seen = oracle.new_seen(w.n_bits)
     assert oracle.scatter(edst, w.recv_stage, ph.descs, seen) == ph.n_unique
@@ -73,27 +76,25 @@ def test_alltoall_full_size(gpu_lib):
     assert_same(bm.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap")
 
 
-def test_small_messages_2000(gpu_lib):
-    """2000 of the 10000 small allreduces (same recipe), 128 messages per call."""
+def test_small_messages_all_10000(gpu_lib):
+    """All 10000 small allreduces of the recipe (1.57 M unique chunks), 128 messages per call."""
     t0 = time.time()
-    w, msgs = wl.config5(seed=1, n_msgs=2000)
+    w, msgs = wl.config5(seed=1, n_msgs=10000)
     say(f"config5: built {len(msgs)} messages in {time.time() - t0:.1f}s")
     eacc = w.acc.copy()
     eout = np.zeros(w.out_bytes, dtype=np.uint8)
     seen = oracle.new_seen(w.n_bits)
-    gpu_lib.uccl_set_chunk_hint(4 << 10)
-    try:
-        run = DeviceRun(w, guard=0)
-        for lo in range(0, len(msgs), 128):
-            rs = np.concatenate([m["rs"] for m in msgs[lo:lo + 128]])
-            ag = np.concatenate([m["ag"] for m in msgs[lo:lo + 128]])
-            run.apply(to_dev(rs), len(rs), SUM, checked=False)
-            run.apply(to_dev(ag), len(ag), COPY, checked=False)
-            oracle.apply(eacc, eout, w.recv_stage, rs, seen, F32, SUM, check=False)
-            oracle.apply(eacc, eout, w.recv_stage, ag, seen, F32, COPY, check=False)
-        torch.cuda.synchronize()
-    finally:
-        gpu_lib.uccl_set_chunk_hint(0)
+    run = DeviceRun(w, guard=0, opts=(4 << 10, 0))
+    for lo in range(0, len(msgs), 128):
+        rs = np.concatenate([m["rs"] for m in msgs[lo:lo + 128]])
+        ag = np.concatenate([m["ag"] for m in msgs[lo:lo + 128]])
+        run.apply(to_dev(rs), len(rs), SUM, checked=False)
+        run.apply(to_dev(ag), len(ag), COPY, checked=False)
+        oracle.apply(eacc, eout, w.recv_stage, rs, seen, F32, SUM, check=False)
+        oracle.apply(eacc, eout, w.recv_stage, ag, seen, F32, COPY, check=False)
+        if lo % (128 * 16) == 0:
+            say(f"config5: {lo} messages at {time.time() - t0:.0f}s")
+    torch.cuda.synchronize()
     acc, out, bm, _ = run.results()
     assert_same(bm, oracle.pack_bitmap(seen), "bitmap")
     assert_same(acc, eacc, "acc")
@@ -105,7 +106,7 @@ def test_16bit_every_pair(gpu_lib, dtype, op):
     """All 65536 x 65536 pairs of bf16 / binary16 bit patterns through SUM and PROD, bit-exact
     against the oracle (NaN results: NaN-ness only, their payload is not fixed by the method)."""
     from synth.layout import DESC, NO_FORWARD
-    BF16, SUM = dtype, op  # the body below was written for bf16 SUM; the codes are parameters now
+    what = f"{ {1: 'bf16', 2: 'f16'}[dtype]} { {0: 'SUM', 4: 'PROD'}[op]} pairs"
     blk = 2048                                     # a-values per block: 134 M pairs
     n = blk * 65536
     r_np = np.tile(np.arange(65536, dtype=np.uint16), blk)
@@ -123,10 +124,10 @@ def test_16bit_every_pair(gpu_lib, dtype, op):
         a_np = np.repeat(np.arange(b * blk, (b + 1) * blk, dtype=np.uint16), 65536)
         acc = to_dev(a_np)
         bm.zero_()
-        gpu_lib.uccl_chunk_apply(acc, None, r_dev, d_dev, pieces, bm, BF16, SUM)
+        gpu_lib.uccl_chunk_apply(acc, None, r_dev, d_dev, pieces, bm, dtype, op)
         exp = a_np.copy()
         seen = oracle.new_seen(pieces)
-        oracle.apply(exp, None, r_np, d, seen, BF16, SUM, check=False)
+        oracle.apply(exp, None, r_np, d, seen, dtype, op, check=False)
         got = acc.cpu().numpy().view(np.uint16)
         if not np.array_equal(got, exp):
             nan = np.isnan(wide(exp))
@@ -135,7 +136,7 @@ def test_16bit_every_pair(gpu_lib, dtype, op):
             assert len(bad) == 0, (f"block {b}: {len(bad)} mismatches, first a={a_np[bad[0]]:#06x} "
                                    f"r={r_np[bad[0]]:#06x} got={got[bad[0]]:#06x} exp={exp[bad[0]]:#06x}")
         if b % 8 == 7:
-            say(f"bf16 pairs: block {b + 1}/{65536 // blk} at {time.time() - t0:.0f}s")
+            say(f"{what}: block {b + 1}/{65536 // blk} at {time.time() - t0:.0f}s")
 
 
 def test_direct_reduce_scatter_full_size(gpu_lib):
@@ -151,12 +152,8 @@ def test_direct_reduce_scatter_full_size(gpu_lib):
     say(f"direct-rs: oracle done at {time.time() - t0:.1f}s")
     acc, recv = to_dev(w.acc), to_dev(w.recv_stage)
     bitmap = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
-    gpu_lib.uccl_set_launch_shape(0)
-    gpu_lib.uccl_set_chunk_hint(128 << 10)
-    try:
-        gpu_lib.uccl_chunk_reduce_gather(acc, None, recv, to_dev(ph.descs), len(ph.descs), bitmap, F32, SUM)
-        torch.cuda.synchronize()
-    finally:
-        gpu_lib.uccl_set_chunk_hint(0)
+    gpu_lib.uccl_chunk_reduce_gather(acc, None, recv, to_dev(ph.descs), len(ph.descs), bitmap, F32, SUM,
+                                     opts=(128 << 10, 0))
+    torch.cuda.synchronize()
     assert_same(bitmap.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap")
     assert_same(acc.cpu().numpy().view(np.float32), eacc, "acc")

@@ -20,66 +20,66 @@ from ringloop import closed_loop_allreduce
 
 pytestmark = pytest.mark.gpu
 
-SHAPES = [0, 1, 2, 4]  # AUTO (= FLAT), WAVE, GROUP, FLAT
+# Launch configurations every case runs under: the library's own choice, then (chunk_bytes, parts)
+# pairs forcing one workgroup per record and 2, 5 and 16 workgroups per record (calls of at most
+# 2048 single-record tiles; otherwise `parts` is ignored and the call runs unsplit).
+LAUNCHES = [None, (0, 1), (0, 2), (0, 5), (0, 16)]
 
 
 def say(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def check_workload(pkg, w, shape=0, checked=True, split=None):
+def check_workload(pkg, w, opts=None, checked=True, split=None):
     eacc, eout, ebm = oracle_results(w)  # first: the oracle also validates the records
-    pkg.uccl_set_launch_shape(shape)
-    try:
-        run = DeviceRun(w)
-        run.run_phases(checked=checked, split=split)
-        acc, out, bm, rej = run.results()
-    finally:
-        pkg.uccl_set_launch_shape(0)
+    run = DeviceRun(w, opts=opts)
+    run.run_phases(checked=checked, split=split)
+    acc, out, bm, rej = run.results()
     assert rej == 0
+    assert pkg.uccl_claim_timeouts() == 0
     assert_same(bm, ebm, "bitmap")
     assert_same(acc, eacc, "acc")
     if eout is not None:
         assert_same(out, eout, "out_stage")
 
 
-# ---- the five recipes at sizes the oracle finishes in seconds, every launch shape ------
+# ---- the five recipes at sizes the oracle finishes in seconds, every launch configuration ------
 
-@pytest.mark.parametrize("shape", SHAPES)
-def test_config1_full_size(gpu_lib, shape):
-    say("config1 full size shape", shape)
-    check_workload(gpu_lib, wl.config1(seed=1), shape)
+@pytest.mark.parametrize("opts", LAUNCHES)
+def test_config1_full_size(gpu_lib, opts):
+    say("config1 full size, launch", opts)
+    check_workload(gpu_lib, wl.config1(seed=1), opts)
 
 
-@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("opts", LAUNCHES)
 @pytest.mark.parametrize("seed", [1, 2])
-def test_config2_recipe_reduced(gpu_lib, shape, seed):
-    say("config2 16 MiB shape", shape, "seed", seed)
-    check_workload(gpu_lib, wl.config2(seed=seed, M=16 << 20), shape)
+def test_config2_recipe_reduced(gpu_lib, opts, seed):
+    say("config2 16 MiB, launch", opts, "seed", seed)
+    check_workload(gpu_lib, wl.config2(seed=seed, M=16 << 20), opts)
 
 
-@pytest.mark.parametrize("shape", SHAPES)
-def test_config3_recipe_reduced(gpu_lib, shape):
-    say("config3 32 MiB shape", shape)
-    check_workload(gpu_lib, wl.config3(seed=3, M=32 << 20), shape)
+@pytest.mark.parametrize("opts", LAUNCHES)
+def test_config3_recipe_reduced(gpu_lib, opts):
+    say("config3 32 MiB, launch", opts)
+    check_workload(gpu_lib, wl.config3(seed=3, M=32 << 20), opts)
 
 
-@pytest.mark.parametrize("shape", SHAPES)
-def test_config4_recipe_reduced(gpu_lib, shape):
-    say("config4 max 2 MiB per source shape", shape)
+@pytest.mark.parametrize("opts", LAUNCHES)
+def test_config4_recipe_reduced(gpu_lib, opts):
+    say("config4 max 2 MiB per source, launch", opts)
     w = wl.config4(seed=2, max_bytes=2 << 20)
-    gpu_lib.uccl_set_launch_shape(shape)
-    try:
-        dst = torch.full((w.acc.nbytes + 512,), 0xEE, dtype=torch.uint8, device="cuda")
-        recv = to_dev(w.recv_stage)
-        d = to_dev(w.phases[0].descs)
-        bm = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
-        rej = torch.zeros(1, dtype=torch.int32, device="cuda")
+    dst = torch.full((w.acc.nbytes + 512,), 0xEE, dtype=torch.uint8, device="cuda")
+    recv = to_dev(w.recv_stage)
+    d = to_dev(w.phases[0].descs)
+    bm = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
+    rej = torch.zeros(1, dtype=torch.int32, device="cuda")
+    if opts is None:
         gpu_lib.uccl_chunk_scatter_checked(dst[256:256 + w.acc.nbytes], recv, d, len(w.phases[0].descs), bm,
                                            n_rejected=rej, n_bits=w.n_bits)
-        torch.cuda.synchronize()
-    finally:
-        gpu_lib.uccl_set_launch_shape(0)
+    else:
+        gpu_lib.uccl_chunk_scatter_opts(dst[256:256 + w.acc.nbytes], recv, d, len(w.phases[0].descs), bm,
+                                        n_rejected=rej, n_bits=w.n_bits, opts=opts)
+    torch.cuda.synchronize()
     got = dst.cpu().numpy()
     edst = np.zeros(w.acc.nbytes, dtype=np.uint8)
     seen = oracle.new_seen(w.n_bits)
@@ -102,13 +102,10 @@ def test_config5_recipe_batched_and_per_message(gpu_lib):
         oracle.apply(eacc, eout, w.recv_stage, m["rs"], seen, F32, SUM)
         oracle.apply(eacc, eout, w.recv_stage, m["ag"], seen, F32, COPY)
     ebm = oracle.pack_bitmap(seen)
-    for mode in ("per-message", "batched", "batched-flat-hint"):
+    for mode in ("per-message", "per-message-split", "batched", "batched-hint"):
         say("config5", mode)
-        run = DeviceRun(w)
-        if mode == "batched-flat-hint":
-            gpu_lib.uccl_set_launch_shape(4)
-            gpu_lib.uccl_set_chunk_hint(4096)
-        if mode == "per-message":
+        run = DeviceRun(w, opts={"batched-hint": (4096, 0), "per-message-split": (0, 4)}.get(mode))
+        if mode.startswith("per-message"):
             for m in msgs:
                 run.apply(to_dev(m["rs"]), len(m["rs"]), SUM)
                 run.apply(to_dev(m["ag"]), len(m["ag"]), COPY)
@@ -119,26 +116,21 @@ def test_config5_recipe_batched_and_per_message(gpu_lib):
                 run.apply(to_dev(rs), len(rs), SUM)
                 run.apply(to_dev(ag), len(ag), COPY)
         torch.cuda.synchronize()
-        gpu_lib.uccl_set_launch_shape(0)
-        gpu_lib.uccl_set_chunk_hint(0)
         acc, out, bm, rej = run.results()
-        assert rej == 0
+        assert rej == 0 and gpu_lib.uccl_claim_timeouts() == 0
         assert_same(bm, ebm, "bitmap")
         assert_same(acc, eacc, "acc")
         assert_same(out, eout, "out")
 
 
 @pytest.mark.parametrize("hint", [512, 1024, 2048, 4096, 8192, 16384, 1 << 20])
-def test_flat_shape_every_tile_size(gpu_lib, hint):
-    """The chunk-size hint only changes how many records a workgroup takes (32, 32, 16, 8, 4, 2, 1)."""
-    gpu_lib.uccl_set_chunk_hint(hint)
-    try:
-        C = 5008
-        w = wl.ring_share("tiles", 13, R=4, M=4 * (9 * C + 1040), C=C, dtype=BF16, paths=5, window=11,
-                          dup=0.2, dist="normal")
-        check_workload(gpu_lib, w, 4)
-    finally:
-        gpu_lib.uccl_set_chunk_hint(0)
+def test_every_tile_size(gpu_lib, hint):
+    """The chunk size given with the call only changes how many records a workgroup takes
+    (32, 32, 16, 8, 4, 2, 1), and, for the last, into how many parts a record is cut."""
+    C = 5008
+    w = wl.ring_share("tiles", 13, R=4, M=4 * (9 * C + 1040), C=C, dtype=BF16, paths=5, window=11,
+                      dup=0.2, dist="normal")
+    check_workload(gpu_lib, w, (hint, 0))
 
 
 def test_very_many_tiny_records_without_hint(gpu_lib):
@@ -157,22 +149,22 @@ def test_very_many_tiny_records_without_hint(gpu_lib):
     recv = vals[seq].reshape(-1).copy()
     w = wl.Workload("tiny", F32, pl.uniform_f32(31, 3, n * C // 4), recv, n * C, n,
                     [wl.Phase("p", SUM, d, n, n * C, 0)])
-    check_workload(gpu_lib, w, 0, checked=False, split=lambda m: [5000, 25000, 125000])
-    check_workload(gpu_lib, w, 0, checked=True)
+    check_workload(gpu_lib, w, None, checked=False, split=lambda m: [5000, 25000, 125000])
+    check_workload(gpu_lib, w, None, checked=True)
 
 
 # ---- ops, dtypes, ragged tails, odd lengths ------------------------------------------
 
-@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("opts", LAUNCHES)
 @pytest.mark.parametrize("dtype", [F32, BF16, F16, I32])
 @pytest.mark.parametrize("op", [SUM, MAX, MIN, COPY, PROD])
-def test_ops_dtypes_ragged(gpu_lib, shape, dtype, op):
-    say("ops ragged", shape, dtype, op)
+def test_ops_dtypes_ragged(gpu_lib, opts, dtype, op):
+    say("ops ragged", opts, dtype, op)
     C = 20000 - 20000 % 16 + 16  # 20000: many 16-byte vectors plus trips that do not divide evenly
     dist = "normal" if dtype == BF16 else "uniform"
     w = wl.ring_share("ragged", 11, R=4, M=4 * (5 * C + 4112), C=C, dtype=dtype, paths=7, window=9,
                       dup=0.15, dist=dist, op=op, allgather=True)
-    check_workload(gpu_lib, w, shape)
+    check_workload(gpu_lib, w, opts)
 
 
 def _records(rows):
@@ -182,10 +174,10 @@ def _records(rows):
     return d
 
 
-@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("opts", LAUNCHES)
 @pytest.mark.parametrize("dtype,op", [(F32, SUM), (BF16, SUM), (BF16, MAX), (F32, COPY), (BF16, COPY), (F16, PROD),
                                       (I32, MIN)])
-def test_lengths_not_multiple_of_16(gpu_lib, shape, dtype, op):
+def test_lengths_not_multiple_of_16(gpu_lib, opts, dtype, op):
     """len is any multiple of the element size, including 0."""
     es = ELEM_SIZE[dtype]
     lens = [0, es, 2 * es, 16 - es, 16, 16 + es, 48 - es, 1024 + 3 * es, 4096 + 16 - es, 9 * 1024 + es, 70000 + es]
@@ -195,18 +187,17 @@ def test_lengths_not_multiple_of_16(gpu_lib, shape, dtype, op):
         rows.append((k * slot, ((n - 1 - k) * slot), k * slot if k % 2 else NO_FORWARD, ln, k))
     rows.append((n * slot, (n - 1 - 3) * slot, 3 * slot, lens[3], 3))  # a duplicate of record 3
     d = _records(rows)
-    g = pl.rng(5, shape)
     nel = (n + 1) * slot // ELEM_SIZE[dtype]
     acc0 = wl._draw("normal" if dtype == BF16 else "uniform", dtype, 5, 1, nel)
     recv = wl._draw("normal" if dtype == BF16 else "uniform", dtype, 5, 2, nel)
     recv.view(np.uint8)[n * slot:n * slot + lens[3]] = recv.view(np.uint8)[3 * slot:3 * slot + lens[3]]
     w = wl.Workload("odd", dtype, acc0, recv, (n + 1) * slot, n, [wl.Phase("p", op, d, n, sum(lens), 0)])
-    check_workload(gpu_lib, w, shape)
-    check_workload(gpu_lib, w, shape, checked=False)
+    check_workload(gpu_lib, w, opts)
+    check_workload(gpu_lib, w, opts, checked=False)
 
 
-@pytest.mark.parametrize("shape", SHAPES)
-def test_scatter_any_byte_length(gpu_lib, shape):
+@pytest.mark.parametrize("opts", LAUNCHES)
+def test_scatter_any_byte_length(gpu_lib, opts):
     """The all-to-all scatter is a byte copy: any length, including odd ones."""
     lens = [0, 1, 2, 3, 15, 16, 17, 31, 33, 1000, 4097, 65535, 70001]
     slot = 70016
@@ -217,37 +208,37 @@ def test_scatter_any_byte_length(gpu_lib, shape):
     for j in range(3):
         recv[(n + j) * slot:(n + j) * slot + lens[12]] = recv[12 * slot:12 * slot + lens[12]]
     dst0 = np.full(n * slot, 0x5C, dtype=np.uint8)
-    gpu_lib.uccl_set_launch_shape(shape)
-    try:
+    dst = to_dev(dst0)
+    bm = torch.zeros(1, dtype=torch.int32, device="cuda")
+    for checked in (True, False):
+        if opts is not None:
+            gpu_lib.uccl_chunk_scatter_opts(dst, to_dev(recv), to_dev(d), len(d), bm, n_bits=n if checked else None,
+                                            opts=opts)
+        elif checked:
+            gpu_lib.uccl_chunk_scatter_checked(dst, to_dev(recv), to_dev(d), len(d), bm, n_bits=n)
+        else:
+            gpu_lib.uccl_chunk_scatter(dst, to_dev(recv), to_dev(d), len(d), bm)
+        torch.cuda.synchronize()
+        edst = dst0.copy()
+        seen = oracle.new_seen(n)
+        assert oracle.scatter(edst, recv, d, seen) == n
+        assert_same(dst.cpu().numpy(), edst, "dst")
+        assert_same(bm.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap")
         dst = to_dev(dst0)
-        bm = torch.zeros(1, dtype=torch.int32, device="cuda")
-        for checked in (True, False):
-            if checked:
-                gpu_lib.uccl_chunk_scatter_checked(dst, to_dev(recv), to_dev(d), len(d), bm, n_bits=n)
-            else:
-                gpu_lib.uccl_chunk_scatter(dst, to_dev(recv), to_dev(d), len(d), bm)
-            torch.cuda.synchronize()
-            edst = dst0.copy()
-            seen = oracle.new_seen(n)
-            assert oracle.scatter(edst, recv, d, seen) == n
-            assert_same(dst.cpu().numpy(), edst, "dst")
-            assert_same(bm.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap")
-            dst = to_dev(dst0)
-            bm.zero_()
-    finally:
-        gpu_lib.uccl_set_launch_shape(0)
+        bm.zero_()
+    assert gpu_lib.uccl_claim_timeouts() == 0
 
 
-@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("opts", LAUNCHES)
 @pytest.mark.parametrize("dtype,op", [(BF16, SUM), (F32, MAX), (F32, COPY)])
-def test_forward_only_records(gpu_lib, shape, dtype, op):
+def test_forward_only_records(gpu_lib, opts, dtype, op):
     """Intermediate reduce-scatter steps flagged forward-only: staging gets the combined
     value, the accumulator keeps its bytes; ragged chunk sizes."""
     C = 12304
     w = wl.ring_share("relay", 17, R=5, M=5 * (4 * C + 2064), C=C, dtype=dtype, paths=6, window=8, dup=0.15,
                       dist="uniform" if dtype == F32 else "normal", op=op, relay=True)
-    check_workload(gpu_lib, w, shape)
-    check_workload(gpu_lib, w, shape, checked=False)
+    check_workload(gpu_lib, w, opts)
+    check_workload(gpu_lib, w, opts, checked=False)
 
 
 def test_closed_loop_ring_with_relay(gpu_lib):
@@ -286,15 +277,16 @@ def test_empty_call_and_all_duplicates(gpu_lib):
 
 # ---- exactly-once under concurrency ---------------------------------------------------
 
-@pytest.mark.parametrize("shape", SHAPES)
+@pytest.mark.parametrize("opts", LAUNCHES)
 @pytest.mark.parametrize("dtype", [F32, BF16])
-def test_exactly_once_many_copies_everywhere(gpu_lib, shape, dtype):
+def test_exactly_once_many_copies_everywhere(gpu_lib, opts, dtype):
     """Payload all ones, acc zero, SUM; every seq is repeated many times: adjacent records
     (same wavefront, same bitmap word), far apart (different workgroups), and across two
-    calls.  A double apply shows as 2, a lost chunk as 0."""
+    calls.  A double apply shows as 2, a lost chunk as 0.  With records cut into parts, every
+    part of every copy has to learn the one decision taken for its record."""
     es = ELEM_SIZE[dtype]
     C, n = 4096, 96
-    g = pl.rng(21, shape)
+    g = pl.rng(21, LAUNCHES.index(opts))
     arr = np.concatenate([np.repeat(np.arange(n), 3), np.arange(n), g.integers(0, n, 700), np.repeat(np.arange(8), 40)])
     arr = np.concatenate([arr[:300], g.permutation(arr[300:])])
     d = np.zeros(len(arr), dtype=DESC)
@@ -307,24 +299,20 @@ def test_exactly_once_many_copies_everywhere(gpu_lib, shape, dtype):
     recv = np.full(len(arr) * C // es, one, dtype=pl.np_dtype(dtype))
     acc0 = np.zeros(n * C // es, dtype=pl.np_dtype(dtype))
     w = wl.Workload("once", dtype, acc0, recv, n * C, n, [wl.Phase("p", SUM, d, n, n * C, 0)])
-    gpu_lib.uccl_set_launch_shape(shape)
-    try:
-        run = DeviceRun(w)
-        run.run_phases(split=lambda m: [m // 3, m // 2])
-        acc, out, bm, rej = run.results()
-    finally:
-        gpu_lib.uccl_set_launch_shape(0)
-    assert rej == 0
+    run = DeviceRun(w, opts=opts)
+    run.run_phases(split=lambda m: [m // 3, m // 2])
+    acc, out, bm, rej = run.results()
+    assert rej == 0 and gpu_lib.uccl_claim_timeouts() == 0
     assert np.all(acc == one), f"{np.count_nonzero(acc != one)} elements are not exactly 1"
     assert np.array_equal(out.view(acc.dtype), acc)
     assert sum(bin(int(x)).count("1") for x in bm) == n
 
 
-@pytest.mark.parametrize("shape", [1, 2])
-def test_split_calls_equal_single_call(gpu_lib, shape):
+@pytest.mark.parametrize("opts", [None, (0, 4)])
+def test_split_calls_equal_single_call(gpu_lib, opts):
     w = wl.config2(seed=5, M=8 << 20)
     g = pl.rng(6, 6)
-    check_workload(gpu_lib, w, shape, split=lambda m: sorted(g.choice(np.arange(1, m), 5, replace=False).tolist()))
+    check_workload(gpu_lib, w, opts, split=lambda m: sorted(g.choice(np.arange(1, m), 5, replace=False).tolist()))
 
 
 def test_missing_chunk_leaves_hole(gpu_lib):
@@ -360,13 +348,11 @@ def test_checked_rejects_bad_records_and_moves_nothing(gpu_lib):
     ]
     d = _records([good] + bad + [(2 * C, 2 * C, C, C, 2)])
     w = wl.Workload("bad", F32, acc0, recv, 2 * C, n_bits, [wl.Phase("p", SUM, d, 2, 2 * C, 0)])
-    for shape in SHAPES:
-        gpu_lib.uccl_set_launch_shape(shape)
-        run = DeviceRun(w)
+    for opts in LAUNCHES:
+        run = DeviceRun(w, opts=opts)
         run.run_phases()
         acc, out, bm, rej = run.results()
-        gpu_lib.uccl_set_launch_shape(0)
-        assert rej == len(bad)
+        assert rej == len(bad), opts   # a rejected record is counted once however many parts look at it
         assert bm[0] == 0b101
         exp = acc0.copy()
         exp[:C // 4] += recv[:C // 4]
@@ -642,9 +628,9 @@ def test_closed_loop_ring_matches_textbook(gpu_lib, dtype, R, n, C):
         assert_same(got[r], pl.ints_as(vals.sum(axis=0), dtype), "integer inputs: exact column sum")
 
 
-@pytest.mark.parametrize("shape", [0, 1])
+@pytest.mark.parametrize("opts", [None, (0, 3)])
 @pytest.mark.parametrize("scheme", ["window", "swift", "credit"])
-def test_stream_from_control_path_model(gpu_lib, shape, scheme):
+def test_stream_from_control_path_model(gpu_lib, opts, scheme):
     """Arrival order from the discrete-event control-path model (power-of-two path choice, loss, fast
     and timeout retransmission; window-, delay- or credit-based sending) instead of the random-spray model."""
     from synth.control_sim import simulated_arrivals
@@ -654,7 +640,7 @@ def test_stream_from_control_path_model(gpu_lib, shape, scheme):
            for i, l in enumerate(lg[:2])]
     w = wl.ring_share("sim", 21, arrivals=arr, **kw)
     assert sum(len(a) for a in arr) > w.n_bits, "the model produced duplicates"
-    check_workload(gpu_lib, w, shape)
+    check_workload(gpu_lib, w, opts)
 
 
 def test_rejected_calls_leave_buffers_untouched(gpu_lib):
@@ -703,54 +689,48 @@ def test_side_stream(gpu_lib):
 # ---- randomized mix of every feature --------------------------------------------------------------
 
 @pytest.mark.parametrize("dtype", [F32, BF16, F16, I32])
-@pytest.mark.parametrize("shape", SHAPES)
-def test_random_streams_all_features(gpu_lib, dtype, shape):
-    """200 random small streams per (type, shape): odd and zero lengths, duplicates adjacent
+@pytest.mark.parametrize("parts", [0, 1, 3, 8])
+def test_random_streams_all_features(gpu_lib, dtype, parts):
+    """200 random small streams per (type, parts): odd and zero lengths, duplicates adjacent
     and far, forward / keep / forward-only, every op, checked and unchecked entry, one call or
-    two, with and without a chunk-size hint."""
+    two, with and without a chunk size (so every tile size, and records cut into parts)."""
     from randstream import random_stream
-    gpu_lib.uccl_set_launch_shape(shape)
-    try:
-        base = int(os.environ.get("UCCL_TEST_SEED_BASE", "7000"))      # other seeds and more streams for a soak run
-        for seed in range(int(os.environ.get("UCCL_TEST_STREAMS", "50"))):
-            for op in (SUM, MAX, COPY, PROD):
-                s = random_stream(base + 100 * dtype + 17 * seed + op, dtype, op, max_chunks=48, max_len=9000)
-                gpu_lib.uccl_set_chunk_hint([0, 1024, 4096, 65536][seed % 4])
-                acc, recv = to_dev(s["acc"]), to_dev(s["recv"])
-                out = torch.full((s["out_bytes"],), 0x3C, dtype=torch.uint8, device="cuda")
-                bm = torch.zeros((s["n_bits"] + 31) // 32, dtype=torch.int32, device="cuda")
-                rej = torch.zeros(1, dtype=torch.int32, device="cuda")
-                d = to_dev(s["descs"])
-                n = len(s["descs"])
-                cuts = [0, n] if seed % 3 else [0, n // 2, n]
-                for lo, hi in zip(cuts[:-1], cuts[1:]):
-                    if seed % 2:
-                        gpu_lib.uccl_chunk_apply_checked(acc, out, recv, d[lo * 32:], hi - lo, bm, dtype, op,
-                                                         n_rejected=rej, n_bits=s["n_bits"])
-                    else:
-                        gpu_lib.uccl_chunk_apply(acc, out, recv, d[lo * 32:], hi - lo, bm, dtype, op)
-                torch.cuda.synchronize()
-                eacc, eout, seen = s["acc"].copy(), np.full(s["out_bytes"], 0x3C, np.uint8), oracle.new_seen(s["n_bits"])
-                oracle.apply(eacc, eout, s["recv"], s["descs"], seen, dtype, op)
-                what = f"dtype {dtype} shape {shape} seed {seed} op {op}"
-                assert rej.item() == 0, what
-                assert_same(bm.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap " + what)
-                got = to_host(acc, s["acc"].dtype)
-                if dtype in (F32, BF16, F16):
-                    wide = {F32: lambda x: x, BF16: lambda x: (x.astype(np.uint32) << 16).view(np.float32),
-                            F16: lambda x: x.view(np.float16).astype(np.float32)}[dtype]
-                    nan = np.isnan(wide(eacc))
-                    assert np.array_equal(np.isnan(wide(got)), nan), what
-                    assert_same(got[~nan], eacc[~nan], "acc " + what)
-                    go, eo = out.cpu().numpy().view(s["acc"].dtype), eout.view(s["acc"].dtype)
-                    nan_o = np.isnan(wide(eo))
-                    assert_same(go[~nan_o], eo[~nan_o], "out " + what)
-                else:
-                    assert_same(got, eacc, "acc " + what)
-                    assert_same(out.cpu().numpy(), eout, "out " + what)
-    finally:
-        gpu_lib.uccl_set_launch_shape(0)
-        gpu_lib.uccl_set_chunk_hint(0)
+    base = int(os.environ.get("UCCL_TEST_SEED_BASE", "7000"))      # other seeds and more streams for a soak run
+    for seed in range(int(os.environ.get("UCCL_TEST_STREAMS", "50"))):
+        for op in (SUM, MAX, COPY, PROD):
+            s = random_stream(base + 100 * dtype + 17 * seed + op, dtype, op, max_chunks=48, max_len=9000)
+            opts = ([0, 1024, 4096, 65536][seed % 4], parts)
+            acc, recv = to_dev(s["acc"]), to_dev(s["recv"])
+            out = torch.full((s["out_bytes"],), 0x3C, dtype=torch.uint8, device="cuda")
+            bm = torch.zeros((s["n_bits"] + 31) // 32, dtype=torch.int32, device="cuda")
+            rej = torch.zeros(1, dtype=torch.int32, device="cuda")
+            d = to_dev(s["descs"])
+            n = len(s["descs"])
+            cuts = [0, n] if seed % 3 else [0, n // 2, n]
+            for lo, hi in zip(cuts[:-1], cuts[1:]):
+                gpu_lib.uccl_chunk_apply_opts(acc, out, recv, d[lo * 32:], hi - lo, bm, dtype, op,
+                                              n_rejected=rej if seed % 2 else None,
+                                              n_bits=s["n_bits"] if seed % 2 else None, opts=opts)
+            torch.cuda.synchronize()
+            eacc, eout, seen = s["acc"].copy(), np.full(s["out_bytes"], 0x3C, np.uint8), oracle.new_seen(s["n_bits"])
+            oracle.apply(eacc, eout, s["recv"], s["descs"], seen, dtype, op)
+            what = f"dtype {dtype} opts {opts} seed {seed} op {op}"
+            assert rej.item() == 0, what
+            assert_same(bm.cpu().numpy().view(np.uint32), oracle.pack_bitmap(seen), "bitmap " + what)
+            got = to_host(acc, s["acc"].dtype)
+            if dtype in (F32, BF16, F16):
+                wide = {F32: lambda x: x, BF16: lambda x: (x.astype(np.uint32) << 16).view(np.float32),
+                        F16: lambda x: x.view(np.float16).astype(np.float32)}[dtype]
+                nan = np.isnan(wide(eacc))
+                assert np.array_equal(np.isnan(wide(got)), nan), what
+                assert_same(got[~nan], eacc[~nan], "acc " + what)
+                go, eo = out.cpu().numpy().view(s["acc"].dtype), eout.view(s["acc"].dtype)
+                nan_o = np.isnan(wide(eo))
+                assert_same(go[~nan_o], eo[~nan_o], "out " + what)
+            else:
+                assert_same(got, eacc, "acc " + what)
+                assert_same(out.cpu().numpy(), eout, "out " + what)
+    assert gpu_lib.uccl_claim_timeouts() == 0
 
 
 def test_same_records_on_two_streams_apply_once(gpu_lib):
@@ -794,15 +774,63 @@ def test_hand_derived_rounding_cases_on_the_gpu(gpu_lib, name, dtype):
     d = np.zeros(1, dtype=DESC)
     d[0] = (0, 0, 0, 2 * len(a), 0)
     bitmap = torch.zeros(1, dtype=torch.int32, device="cuda")
-    for shape in SHAPES:
-        gpu_lib.uccl_set_launch_shape(shape)
-        try:
-            acc_k = acc.clone()
-            bitmap.zero_()
-            gpu_lib.uccl_chunk_apply(acc_k, out, recv, to_dev(d), 1, bitmap, dtype, SUM)
-            torch.cuda.synchronize()
-        finally:
-            gpu_lib.uccl_set_launch_shape(0)
+    for opts in LAUNCHES:
+        acc_k = acc.clone()
+        bitmap.zero_()
+        gpu_lib.uccl_chunk_apply_opts(acc_k, out, recv, to_dev(d), 1, bitmap, dtype, SUM, opts=opts)
+        torch.cuda.synchronize()
         got = acc_k.cpu().numpy().view(np.uint16)[:len(a)]
-        assert np.array_equal(got, e), (shape, [f"{x:04X}" for x in got], [f"{x:04X}" for x in e])
+        assert np.array_equal(got, e), (opts, [f"{x:04X}" for x in got], [f"{x:04X}" for x in e])
         assert np.array_equal(out.cpu().numpy().view(np.uint16)[:len(a)], e)
+
+
+@pytest.mark.parametrize("parts", [0, 4, 16])
+def test_cut_records_on_two_streams_apply_once(gpu_lib, parts):
+    """Few, large records (so every record is cut into parts), the same list issued concurrently
+    on two streams: each stream has its own claim words, the bitmap decides between the streams,
+    and every part of every record learns exactly one decision."""
+    dtype, C, n = F32, 96 << 10, 120
+    arr = pl.rng(43, 1).permutation(n)
+    d = np.zeros(n, dtype=DESC)
+    d["src_off"] = np.arange(n, dtype=np.uint64) * C
+    d["dst_off"] = d["out_off"] = arr.astype(np.uint64) * C
+    d["len"], d["seq"] = C, arr
+    recv = np.ones(n * C // 4, dtype=np.float32)
+    w = wl.Workload("two-cut", dtype, np.zeros(n * C // 4, dtype=np.float32), recv, n * C, n,
+                    [wl.Phase("p", SUM, d, n, n * C, 0)])
+    for trial in range(3):
+        run = DeviceRun(w, opts=(0, parts))
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        run.apply(run.descs[0], n, SUM, stream=s1)
+        run.apply(run.descs[0], n, SUM, stream=s2)
+        run.apply(run.descs[0], n, SUM, stream=s1)
+        s1.synchronize(); s2.synchronize()
+        acc, out, bm, rej = run.results()
+        assert rej == 0 and gpu_lib.uccl_claim_timeouts() == 0
+        assert np.all(acc == 1.0), f"trial {trial}: {np.count_nonzero(acc != 1.0)} elements not exactly 1"
+        assert np.array_equal(out.view(np.float32), acc) and sum(int(x).bit_count() for x in bm) == n
+
+
+def test_cut_records_in_a_captured_graph(gpu_lib):
+    """A call made under stream capture is never cut into parts (its replays could overlap with
+    other work on the claim words), whatever `parts` asks for; replays give the oracle's result."""
+    w = wl.config1(seed=5)
+    eacc, eout, ebm = oracle_results(w)
+    run = DeviceRun(w, opts=(64 << 10, 8))
+    g = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(g, stream=side):
+        gpu_lib.uccl_dedup_reset(run.bitmap, w.n_bits)
+        for ph, dd in zip(w.phases, run.descs):
+            run.apply(dd, len(ph.descs), ph.op, checked=False)
+    acc0 = run.acc.clone()
+    for rep in range(3):
+        run.acc.copy_(acc0)
+        g.replay()
+        torch.cuda.synchronize()
+        acc, out, bm, _ = run.results()
+        assert_same(bm, ebm, f"bitmap, replay {rep}")
+        assert_same(acc, eacc, f"acc, replay {rep}")
+        assert_same(out, eout, f"out, replay {rep}")
