@@ -143,9 +143,30 @@ int uccl_chunk_apply(void* acc, void* out_stage, const void* recv_stage,
                      const uccl_chunk_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
                      uccl_dtype dtype, uccl_op op, void* stream);
 
-/* Eagerly make the current device's claim pool (see "Scratch memory" above), so that no later
- * call allocates.  Idempotent; UCCL_OK or UCCL_ENOMEM.  Utility, no passage of the paper. */
+/* Eagerly make the current device's claim pool (see "Scratch memory" above) and look up the
+ * address of the array uccl_chunk_apply_noalloc uses, so that no later call allocates or loads
+ * anything.  Idempotent; UCCL_OK or a negative code.  Utility, no passage of the paper. */
 int uccl_init(void);
+
+/*
+ * uccl_chunk_apply_noalloc -- uccl_chunk_apply for callers that cannot allocate device memory:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * operation and result; the claim words of records cut into parts (see "Scratch memory" above)
+ * live in an array inside the library's code object instead of the pool: UCCL_NOALLOC_MAX_DESCS
+ * 64-bit words + 256 bytes = 16.25 KiB, held by every GPU the library runs on until the process
+ * ends.  The call makes no hipMalloc / hipFree and creates no pool; the first call on a device
+ * (or uccl_init) looks the array's device address up.
+ *   - n_descs > UCCL_NOALLOC_MAX_DESCS returns UCCL_ETOOBIG and enqueues nothing.  (Calls that
+ *     large are never cut into parts, so uccl_chunk_apply serves them without any scratch memory.)
+ *   - Every call on a GPU shares that GPU's array, whatever the stream: a split call first clears
+ *     its own words with a small fill kernel, then runs; the pair may be captured and replayed.
+ *     Calls (or replays) that overlap in time on one GPU race on the array: keep them on one
+ *     stream, or order them with events.
+ */
+#define UCCL_NOALLOC_MAX_DESCS 2048
+int uccl_chunk_apply_noalloc(void* acc, void* out_stage, const void* recv_stage,
+                             const uccl_chunk_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
+                             uccl_dtype dtype, uccl_op op, void* stream);
 
 /*
  * uccl_chunk_apply_checked -- same operation; additionally every record is validated ON

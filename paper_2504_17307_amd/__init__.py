@@ -19,6 +19,7 @@ UCCL_SUM, UCCL_MAX, UCCL_MIN, UCCL_COPY, UCCL_PROD = 0, 1, 2, 3, 4
 UCCL_OK, UCCL_EINVAL, UCCL_EALIGN, UCCL_ELAUNCH, UCCL_ENOMEM, UCCL_ETOOBIG = 0, -1, -2, -3, -4, -5
 UCCL_NO_FORWARD = 0xFFFFFFFFFFFFFFFF
 DESC_BYTES = 32
+UCCL_NOALLOC_MAX_DESCS = 2048
 GATHER_DESC_BYTES = 160
 UCCL_MAX_SOURCES = 16
 
@@ -52,6 +53,8 @@ _lib = None
 _SIGNATURES = {
     "uccl_chunk_apply": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
                                    C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
+    "uccl_chunk_apply_noalloc": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32,
+                                           C.c_void_p, C.c_int, C.c_int, C.c_void_p]),
     "uccl_chunk_apply_checked": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                            C.c_uint32, C.c_void_p, C.c_int, C.c_int,
                                            C.POINTER(uccl_extents), C.c_void_p, C.c_void_p]),
@@ -171,6 +174,12 @@ def uccl_chunk_apply(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, d
     _check(load().uccl_chunk_apply(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
                                    int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op),
                                    _stream(stream)), "uccl_chunk_apply")
+
+
+def uccl_chunk_apply_noalloc(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, stream=None):
+    _check(load().uccl_chunk_apply_noalloc(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
+                                           int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op),
+                                           _stream(stream)), "uccl_chunk_apply_noalloc")
 
 
 def uccl_chunk_apply_checked(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op,

@@ -38,6 +38,12 @@
 #include "uccl_data_kernels.hpp"
 #include "uccl_feedback_kernels.hpp"
 
+// Claim words for uccl_chunk_apply_noalloc (see claim_record): UCCL_NOALLOC_MAX_DESCS words, one
+// per record of a call, then the word that counts parts that gave up waiting.  Every GPU the
+// library runs on holds its own copy at its own address until the process ends.  In host code
+// this name only stands for the symbol: the device address is looked up per device (static_claims).
+static __device__ __align__(256) unsigned long long scratch[UCCL_NOALLOC_MAX_DESCS + 32];
+
 namespace {
 
 // ---- host side ----------------------------------------------------------------------
@@ -153,10 +159,38 @@ unsigned long long* claim_region(hipStream_t stream, uint32_t** faults) {
   return base + static_cast<size_t>(at) * kRegionWords;
 }
 
-// Per-call tuning (uccl_launch_opts); zero = let the library decide.
+// The current device's copy of `scratch`, looked up once per device with that device current.
+std::atomic<unsigned long long*> g_static_claims[kMaxDevices];
+std::mutex g_static_lock;
+
+int static_claims(unsigned long long** out) {
+  int dev = 0;
+  const hipError_t d = hipGetDevice(&dev);
+  if (d != hipSuccess) return launch_failed(d);
+  if (dev < 0 || dev >= kMaxDevices) return UCCL_EINVAL;
+  unsigned long long* p = g_static_claims[dev].load(std::memory_order_acquire);
+  if (p == nullptr) {
+    std::lock_guard<std::mutex> hold(g_static_lock);
+    p = g_static_claims[dev].load(std::memory_order_acquire);
+    if (p == nullptr) {
+      void* at = nullptr;
+      const hipError_t e = hipGetSymbolAddress(&at, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return launch_failed(e);
+      if (at == nullptr) return UCCL_ELAUNCH;
+      p = static_cast<unsigned long long*>(at);
+      g_static_claims[dev].store(p, std::memory_order_release);
+    }
+  }
+  *out = p;
+  return UCCL_OK;
+}
+
+// Per-call tuning (uccl_launch_opts); zero = let the library decide.  static_claims: the call
+// must not allocate; records are cut into parts only with these claim words.
 struct Tuning {
   uint32_t chunk_bytes;
   uint32_t parts;
+  unsigned long long* static_claims = nullptr;
 };
 
 template <int T, int U, class Op>
@@ -205,7 +239,26 @@ int launch_flat_tile(Args& a, hipStream_t s, const Tuning& tune) {
   if (t >= 4) return launch_flat<4, UCCL_FLAT_UNROLL, Op>(a, s);
   if (t >= 2) return launch_flat<2, UCCL_FLAT_UNROLL, Op>(a, s);
   const uint32_t parts = tune.parts ? tune.parts : (a.n_descs < kFewRecords ? auto_parts(a.n_descs, tune.chunk_bytes) : 1u);
-  if (parts > 1u && a.n_descs <= kRegionWords) {
+  if (parts > 1u && tune.static_claims != nullptr && a.n_descs <= UCCL_NOALLOC_MAX_DESCS) {
+    // Every call shares the device's one array, which keeps what the last call (or the last replay
+    // of this very launch) left in it: clear this call's words first, with a fill kernel (no memset
+    // node, so that the pair can be captured), then launch with a tag the cleared words cannot carry.
+    a.claims = tune.static_claims;
+    a.faults = reinterpret_cast<uint32_t*>(tune.static_claims + UCCL_NOALLOC_MAX_DESCS);
+    a.tag = 1ull;
+    a.parts = parts;
+    const hipEvent_t keep0 = t_start, keep1 = t_stop;  // the timing events belong to the data kernel
+    t_start = t_stop = nullptr;
+    const uint64_t words = 2ull * a.n_descs;
+    const int rc = launch_kernel(fill_words_kernel, static_cast<uint32_t>((words + 255) / 256), 256, s,
+                                 reinterpret_cast<uint32_t*>(a.claims), words, 0u);
+    t_start = keep0;
+    t_stop = keep1;
+    if (rc != UCCL_OK) { t_start = t_stop = nullptr; return rc; }
+    return launch_kernel(chunk_few_kernel<UCCL_PART_THREADS, UCCL_PART_UNROLL, Op, true>, a.n_descs * parts,
+                         UCCL_PART_THREADS, s, a);
+  }
+  if (parts > 1u && tune.static_claims == nullptr && a.n_descs <= kRegionWords) {
     a.claims = claim_region(s, &a.faults);
     if (a.claims != nullptr) {
       a.tag = g_next_tag.fetch_add(1, std::memory_order_relaxed);
@@ -244,10 +297,10 @@ bool overlaps(const void* p, uint64_t pn, const void* q, uint64_t qn) {
 }
 
 bool tuning_from(const uccl_launch_opts* opts, Tuning* t) {
-  *t = Tuning{0u, 0u};
+  *t = Tuning{0u, 0u, nullptr};
   if (opts == nullptr) return true;
   if (opts->parts > 16u || opts->reserved[0] != 0u || opts->reserved[1] != 0u) return false;
-  *t = Tuning{opts->chunk_bytes, opts->parts};
+  *t = Tuning{opts->chunk_bytes, opts->parts, nullptr};
   return true;
 }
 
@@ -382,7 +435,7 @@ int feed_flush(uccl_feed* f) {
       records = sl.dev[l];
     }
     const int rc = apply_common(f->acc, f->out_stage, f->recv_stage, records, sl.count[l], f->bitmap,
-                                f->dtype, f->op[l], true, nullptr, nullptr, Tuning{sl.max_len[l], 0u},
+                                f->dtype, f->op[l], true, nullptr, nullptr, Tuning{sl.max_len[l], 0u, nullptr},
                                 f->stream);
     if (rc != UCCL_OK) return rc;
   }
@@ -533,7 +586,7 @@ int uccl_chunk_apply(void* acc, void* out_stage, const void* recv_stage,
                      const uccl_chunk_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
                      uccl_dtype dtype, uccl_op op, void* stream) {
   return apply_common(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, true,
-                      nullptr, nullptr, Tuning{0u, 0u}, stream);
+                      nullptr, nullptr, Tuning{0u, 0u, nullptr}, stream);
 }
 
 int uccl_chunk_apply_opts(void* acc, void* out_stage, const void* recv_stage,
@@ -552,7 +605,7 @@ int uccl_chunk_apply_checked(void* acc, void* out_stage, const void* recv_stage,
                              const uccl_extents* extents, uint32_t* n_rejected, void* stream) {
   if (!extents) return UCCL_EINVAL;
   return apply_common(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, true,
-                      extents, n_rejected, Tuning{0u, 0u}, stream);
+                      extents, n_rejected, Tuning{0u, 0u, nullptr}, stream);
 }
 
 int uccl_chunk_apply_indirect(void* acc, void* out_stage, const void* recv_stage,
@@ -622,7 +675,7 @@ int uccl_chunk_reduce_gather(void* acc, void* out_stage, const void* recv_stage,
 int uccl_chunk_scatter(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,
                        uint32_t n_descs, uint32_t* dedup_bitmap, void* stream) {
   return apply_common(dst, nullptr, recv_stage, descs, n_descs, dedup_bitmap, UCCL_BF16, UCCL_COPY,
-                      false, nullptr, nullptr, Tuning{0u, 0u}, stream);
+                      false, nullptr, nullptr, Tuning{0u, 0u, nullptr}, stream);
 }
 
 int uccl_chunk_scatter_checked(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,
@@ -630,7 +683,7 @@ int uccl_chunk_scatter_checked(void* dst, const void* recv_stage, const uccl_chu
                                const uccl_extents* extents, uint32_t* n_rejected, void* stream) {
   if (!extents) return UCCL_EINVAL;
   return apply_common(dst, nullptr, recv_stage, descs, n_descs, dedup_bitmap, UCCL_BF16, UCCL_COPY,
-                      false, extents, n_rejected, Tuning{0u, 0u}, stream);
+                      false, extents, n_rejected, Tuning{0u, 0u, nullptr}, stream);
 }
 
 int uccl_chunk_scatter_opts(void* dst, const void* recv_stage, const uccl_chunk_desc* descs,
@@ -646,7 +699,24 @@ int uccl_init(void) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return launch_failed(hipGetLastError());
   if (dev < 0 || dev >= kMaxDevices) return UCCL_EINVAL;
+  unsigned long long* fixed = nullptr;
+  const int rc = static_claims(&fixed);
+  if (rc != UCCL_OK) return rc;
   return pool_base(dev, true) != nullptr ? UCCL_OK : UCCL_ENOMEM;
+}
+
+int uccl_chunk_apply_noalloc(void* acc, void* out_stage, const void* recv_stage,
+                             const uccl_chunk_desc* descs, uint32_t n_descs, uint32_t* dedup_bitmap,
+                             uccl_dtype dtype, uccl_op op, void* stream) {
+  if (dtype < UCCL_F32 || dtype > UCCL_I32) return UCCL_EINVAL;
+  if (op < UCCL_SUM || op > UCCL_PROD) return UCCL_EINVAL;
+  if (n_descs > UCCL_NOALLOC_MAX_DESCS) return UCCL_ETOOBIG;
+  if (n_descs == 0) return UCCL_OK;
+  Tuning tune{0u, 0u, nullptr};
+  const int rc = static_claims(&tune.static_claims);
+  if (rc != UCCL_OK) return rc;
+  return apply_common(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, true,
+                      nullptr, nullptr, tune, stream);
 }
 
 int uccl_claim_timeouts(uint64_t* count) {
@@ -655,12 +725,22 @@ int uccl_claim_timeouts(uint64_t* count) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess) return launch_failed(hipGetLastError());
   if (dev < 0 || dev >= kMaxDevices) return UCCL_EINVAL;
+  uint64_t total = 0;
   unsigned long long* base = pool_base(dev, false);
-  if (base == nullptr) return UCCL_OK;  // no pool, no split call so far
-  uint32_t n = 0;
-  const hipError_t e = hipMemcpy(&n, pool_faults(base), sizeof(n), hipMemcpyDeviceToHost);
-  if (e != hipSuccess) return launch_failed(e);
-  *count = n;
+  if (base != nullptr) {  // no pool: no split call through it so far
+    uint32_t n = 0;
+    const hipError_t e = hipMemcpy(&n, pool_faults(base), sizeof(n), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return launch_failed(e);
+    total += n;
+  }
+  unsigned long long* fixed = g_static_claims[dev].load(std::memory_order_acquire);
+  if (fixed != nullptr) {
+    uint32_t n = 0;
+    const hipError_t e = hipMemcpy(&n, fixed + UCCL_NOALLOC_MAX_DESCS, sizeof(n), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return launch_failed(e);
+    total += n;
+  }
+  *count = total;
   return UCCL_OK;
 }
 

@@ -77,6 +77,11 @@ def test_host_side_error_codes_enqueue_nothing():
     assert lib.uccl_chunk_scatter_opts(A, B, D, 1, M, None, None, C.byref(pkg.uccl_launch_opts(0, 99)), None) == pkg.UCCL_EINVAL
     assert lib.uccl_chunk_reduce_gather(A, None, B, D, 1, M, 0, 0, None, None, C.byref(pkg.uccl_launch_opts(0, 99)), None) == pkg.UCCL_EINVAL
     assert lib.uccl_claim_timeouts(None) == pkg.UCCL_EINVAL
+    na = lib.uccl_chunk_apply_noalloc
+    assert na(A, None, B, D, pkg.UCCL_NOALLOC_MAX_DESCS + 1, M, 0, 0, None) == pkg.UCCL_ETOOBIG   # before any GPU call
+    assert na(A, None, B, D, 1, M, 7, 0, None) == pkg.UCCL_EINVAL
+    assert na(None, None, None, None, 0, None, 0, 0, None) == pkg.UCCL_OK
+    assert "UCCL_NOALLOC_MAX_DESCS %d" % pkg.UCCL_NOALLOC_MAX_DESCS in open(pkg.HEADER_PATH).read()
     s = lib.uccl_chunk_scatter
     assert s(None, B, D, 1, M, None) == pkg.UCCL_EINVAL
     assert s(A + 1, B, D, 1, M, None) == pkg.UCCL_EALIGN
