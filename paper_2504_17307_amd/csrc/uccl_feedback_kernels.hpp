@@ -9,101 +9,214 @@ namespace {
 
 // Receiver feedback from the dedup bitmap: cumulative acknowledgement (first clear bit),
 // number of applied chunks, and the runs of set bits above the cumulative point in
-// ascending order (what a selective-acknowledgement option would carry).  One 1024-thread
-// workgroup walks the words in order, 1024 words per round: thread i owns word i of the
-// round, finds run starts (bit set, previous bit clear) and run ends (bit set, next bit
-// clear) with two word-wide shifts, and a block-wide exclusive scan of the per-word counts
-// gives every start and end its ordinal, so the k-th start and the k-th end land in the
-// same output pair.  The bitmap is tiny next to the payload (one bit per chunk), so this is
-// a latency problem, not a bandwidth one: one workgroup, no atomics, no second pass.
+// ascending order (what a selective-acknowledgement option would carry).  The bitmap is tiny
+// next to the payload (one bit per chunk), so this is a latency problem, not a bandwidth one:
+// one 1024-thread workgroup, one launch, no atomics in global memory.
+//
+// Each of the 16 wavefronts owns one contiguous sixteenth of the words and walks it 256 words at
+// a time: lane l takes words 4l .. 4l+3 of the step with one 128-bit load (a compute unit issues
+// a wavefront's load in the same time whether a lane asks for 4 or 16 bytes, so this is what
+// bounds the walk).  A word's run starts (bit set, previous bit clear) and run ends (bit set,
+// next bit clear) come from two word-wide shifts and the edge bits of the neighbouring words:
+// the lane's own, the next lane's (shuffle), or, at the step's edges, the previous step's last
+// word and one look-ahead word.  First walk: every wavefront counts its starts, ends and set
+// bits and finds its first clear bit; no barrier inside the walk.  One barrier; the counts of
+// the wavefronts before it give each wavefront the ordinal of its first start and first end.
+// Second walk (only if a range is to be written): a wavefront-wide prefix sum per step, by lane
+// shuffles, gives every start and end its ordinal, so the k-th start and the k-th end land in
+// the same output pair.
 struct AckHeader {
   uint64_t cum_ack, n_applied;
   uint32_t n_ranges, complete;
   uint64_t reserved;
 };
 
-__device__ __forceinline__ uint32_t block_exclusive_scan(uint32_t v, uint32_t tid, uint32_t* s_wave,
-                                                         uint32_t* total) {
-  uint32_t incl = v;
+constexpr int kAckBatch = 6;          // steps whose loads are issued together
+constexpr uint32_t kAckStep = 256;    // words per wavefront and step
+
+// Words w .. w+3 (0 for words at and beyond n_words); `aligned`: the bitmap starts on a 16-byte
+// boundary (w is always a multiple of 4), so a full group is one 128-bit load.
+__device__ __forceinline__ uint4 ack_load4(const uint32_t* __restrict__ bitmap, uint64_t w, uint64_t n_words,
+                                           bool aligned) {
+  uint4 v = make_uint4(0u, 0u, 0u, 0u);
+  if (aligned && w + 4 <= n_words) {
+    v = *reinterpret_cast<const uint4*>(bitmap + w);
+  } else {
+    if (w < n_words) v.x = bitmap[w];
+    if (w + 1 < n_words) v.y = bitmap[w + 1];
+    if (w + 2 < n_words) v.z = bitmap[w + 2];
+    if (w + 3 < n_words) v.w = bitmap[w + 3];
+  }
+  return v;
+}
+
+// Bits of word w that lie inside the bitmap.
+__device__ __forceinline__ uint32_t ack_mask(uint64_t w, uint64_t n_bits) {
+  const uint64_t lo = w * 32;
+  return n_bits >= lo + 32 ? ~0u : (n_bits > lo ? (1u << (n_bits - lo)) - 1u : 0u);
+}
+
+// One lane's four words of a step, masked, with their run starts and run ends.
+struct AckQuad {
+  uint32_t word[4], starts[4], ends[4], mask[4];
+};
+
+// raw: the lane's words w4 .. w4+3; before: the word just below the step (0 if none); after: the
+// word just above it (0 if none).  Neighbouring lanes exchange their edge words by shuffle.
+__device__ __forceinline__ AckQuad ack_quad(uint4 raw, uint64_t w4, uint64_t n_bits, uint32_t before,
+                                            uint32_t after, uint32_t lane) {
+  AckQuad q;
+  const uint32_t in[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-  for (uint32_t d = 1; d < 64; d <<= 1) {
-    const uint32_t below = __shfl_up(incl, d, 64);
-    if ((tid & 63u) >= d) incl += below;
+  for (int j = 0; j < 4; ++j) {
+    q.mask[j] = ack_mask(w4 + j, n_bits);
+    q.word[j] = in[j] & q.mask[j];
   }
-  if ((tid & 63u) == 63u) s_wave[tid >> 6] = incl;
-  __syncthreads();
-  uint32_t base = 0, sum = 0;
-  for (uint32_t w = 0; w < 16; ++w) {
-    const uint32_t x = s_wave[w];
-    if (w < (tid >> 6)) base += x;
-    sum += x;
+  uint32_t below = __shfl_up(q.word[3], 1, 64);   // the word under this lane's first
+  if (lane == 0) below = before;
+  uint32_t above = __shfl_down(q.word[0], 1, 64);  // the word over this lane's last
+  if (lane == 63) above = after;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const uint32_t prev = j == 0 ? below : q.word[j - 1];
+    const uint32_t next = j == 3 ? above : q.word[j + 1];
+    q.starts[j] = q.word[j] & ~((q.word[j] << 1) | (prev >> 31));
+    q.ends[j] = q.word[j] & ~((q.word[j] >> 1) | (next << 31));
   }
-  __syncthreads();  // s_wave is reused by the next scan
-  *total = sum;
-  return base + incl - v;
+  return q;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
+#pragma unroll
+  for (uint32_t d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+  return v;
 }
 
 __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __restrict__ bitmap,
                                                           uint64_t n_bits, AckHeader* hdr,
                                                           uint64_t* ranges, uint32_t max_ranges) {
-  __shared__ uint32_t s_wave[16];
-  __shared__ unsigned long long s_first_clear;
-  const uint32_t tid = threadIdx.x;
+  __shared__ uint32_t s_starts[16], s_ends[16];
+  __shared__ unsigned long long s_applied[16], s_first_clear[16];
+  const uint32_t tid = threadIdx.x, lane = tid & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const uint64_t n_words = (n_bits + 31) / 32;
-  if (tid == 0) s_first_clear = ~0ull;
-  __syncthreads();
-  uint64_t applied = 0;      // per-thread partial popcount
-  uint32_t starts_seen = 0;  // runs started / ended in earlier rounds (same in every thread)
-  uint32_t ends_seen = 0;
-  for (uint64_t w0 = 0; w0 < n_words; w0 += 1024) {
-    const uint64_t w = w0 + tid;
-    uint32_t word = 0, prev_msb = 0, next_lsb = 0;
-    if (w < n_words) {
-      word = bitmap[w];
-      const uint64_t valid = n_bits - w * 32;  // bits of this word inside the bitmap
-      if (valid < 32) word &= (1u << valid) - 1u;
-      if (w > 0) prev_msb = bitmap[w - 1] >> 31;
-      if (w + 1 < n_words) {
-        uint32_t nx = bitmap[w + 1];
-        const uint64_t nvalid = n_bits - (w + 1) * 32;
-        if (nvalid < 32) nx &= (1u << nvalid) - 1u;
-        next_lsb = nx & 1u;
-      }
-      applied += __popc(word);
-      const uint32_t clear = ~word & (valid < 32 ? (1u << valid) - 1u : ~0u);
-      if (clear) atomicMin(&s_first_clear, w * 32 + (__ffs(clear) - 1));  // LDS atomic
+  const uint64_t per_wave = (((n_words + 15) / 16) + kAckStep - 1) / kAckStep * kAckStep;  // whole steps
+  const uint64_t w_lo = wave * per_wave;
+  const uint64_t w_hi = w_lo + per_wave < n_words ? w_lo + per_wave : n_words;
+  const bool aligned = (reinterpret_cast<uintptr_t>(bitmap) & 15u) == 0;
+  // beyond the last word of the bitmap a masked word is 0, so the last run ends at n_bits by itself
+  const uint32_t seg_before = (w_lo > 0 && w_lo < n_words) ? bitmap[w_lo - 1] : 0u;
+
+  uint32_t my_starts = 0, my_ends = 0;
+  unsigned long long my_applied = 0, my_first_clear = ~0ull;
+  uint32_t before = seg_before;
+  for (uint64_t wb = w_lo; wb < w_hi; wb += kAckStep * kAckBatch) {
+    uint4 raw[kAckBatch];
+    uint32_t after[kAckBatch];
+#pragma unroll
+    for (int i = 0; i < kAckBatch; ++i) {
+      const uint64_t w0 = wb + static_cast<uint64_t>(i) * kAckStep;  // wavefront-uniform
+      raw[i] = ack_load4(bitmap, w0 + 4 * lane, w0 < w_hi ? n_words : 0, aligned);
+      after[i] = (w0 < w_hi && w0 + kAckStep < n_words) ? bitmap[w0 + kAckStep] : 0u;
     }
-    const uint32_t starts = word & ~((word << 1) | prev_msb);
-    const uint32_t ends = word & ~((word >> 1) | (next_lsb << 31));
-    uint32_t n_starts, n_ends;
-    const uint32_t s_at = starts_seen + block_exclusive_scan(__popc(starts), tid, s_wave, &n_starts);
-    const uint32_t e_at = ends_seen + block_exclusive_scan(__popc(ends), tid, s_wave, &n_ends);
-    // ordinal 0 is the run that begins at bit 0, if there is one: that is the cumulative
-    // part, not a selective range; `skip` shifts the ordinals accordingly
-    const uint32_t skip = bitmap[0] & 1u;
-    uint32_t k = s_at;
-    for (uint32_t m = starts; m; m &= m - 1, ++k)
-      if (k >= skip && k - skip < max_ranges) ranges[2 * (k - skip)] = w * 32 + (__ffs(m) - 1);
-    k = e_at;
-    for (uint32_t m = ends; m; m &= m - 1, ++k)
-      if (k >= skip && k - skip < max_ranges) ranges[2 * (k - skip) + 1] = w * 32 + (__ffs(m) - 1) + 1;
-    starts_seen += n_starts;
-    ends_seen += n_ends;
+#pragma unroll
+    for (int i = 0; i < kAckBatch; ++i) {
+      const uint64_t w0 = wb + static_cast<uint64_t>(i) * kAckStep;
+      if (w0 < w_hi) {  // else the batch reaches past the wavefront's words (uniform)
+        const uint64_t w4 = w0 + 4 * lane;
+        const AckQuad q = ack_quad(raw[i], w4, n_bits, before, after[i], lane);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          my_starts += __popc(q.starts[j]);
+          my_ends += __popc(q.ends[j]);
+          my_applied += __popc(q.word[j]);
+          const uint32_t clear = ~q.word[j] & q.mask[j];
+          if (clear != 0u && my_first_clear == ~0ull) my_first_clear = (w4 + j) * 32 + (__ffs(clear) - 1);  // ascending per lane
+        }
+        before = __shfl(q.word[3], 63, 64);  // the step's last word
+      }
+    }
   }
-  // block-wide sum of the popcounts: 64-bit totals as two 32-bit scans would overflow only
-  // beyond 2^32 set bits per thread-lane, impossible for n_bits < 2^42; keep it simple
-  uint32_t tot_lo, tot_hi;
-  block_exclusive_scan(static_cast<uint32_t>(applied & 0xFFFFFu), tid, s_wave, &tot_lo);
-  block_exclusive_scan(static_cast<uint32_t>(applied >> 20), tid, s_wave, &tot_hi);
+  my_starts = wave_sum(my_starts);
+  my_ends = wave_sum(my_ends);
+  const uint32_t app_lo = wave_sum(static_cast<uint32_t>(my_applied & 0xFFFFFu));   // per lane < 2^35 set bits:
+  const uint32_t app_hi = wave_sum(static_cast<uint32_t>(my_applied >> 20));        // both halves fit 32-bit sums
+#pragma unroll
+  for (uint32_t d = 32; d >= 1; d >>= 1) {
+    const uint32_t lo = __shfl_xor(static_cast<uint32_t>(my_first_clear), d, 64);
+    const uint32_t hi = __shfl_xor(static_cast<uint32_t>(my_first_clear >> 32), d, 64);
+    const unsigned long long other = lo | (static_cast<unsigned long long>(hi) << 32);
+    if (other < my_first_clear) my_first_clear = other;
+  }
+  if (lane == 0) {
+    s_starts[wave] = my_starts;
+    s_ends[wave] = my_ends;
+    s_applied[wave] = static_cast<unsigned long long>(app_lo) + (static_cast<unsigned long long>(app_hi) << 20);
+    s_first_clear[wave] = my_first_clear;
+  }
+  __syncthreads();
+
+  uint32_t s_at = 0, e_at = 0, n_starts = 0;
+  unsigned long long applied = 0, first_clear = ~0ull;
+  for (uint32_t v = 0; v < 16; ++v) {
+    if (v < wave) { s_at += s_starts[v]; e_at += s_ends[v]; }
+    n_starts += s_starts[v];
+    applied += s_applied[v];
+    if (s_first_clear[v] < first_clear) first_clear = s_first_clear[v];
+  }
+  // ordinal 0 is the run that begins at bit 0, if there is one: that is the cumulative part,
+  // not a selective range; `skip` shifts the ordinals accordingly
+  const uint32_t skip = n_bits > 0 ? (bitmap[0] & 1u) : 0u;
   if (tid == 0) {
-    const uint64_t total = static_cast<uint64_t>(tot_lo) + (static_cast<uint64_t>(tot_hi) << 20);
-    const uint64_t first_clear = s_first_clear == ~0ull ? n_bits : s_first_clear;
-    const uint32_t skip = n_bits > 0 ? (bitmap[0] & 1u) : 0u;
-    hdr->cum_ack = first_clear;
-    hdr->n_applied = total;
-    hdr->n_ranges = starts_seen - skip;
-    hdr->complete = (total == n_bits) ? 1u : 0u;
+    hdr->cum_ack = first_clear == ~0ull ? n_bits : first_clear;
+    hdr->n_applied = applied;
+    hdr->n_ranges = n_starts - skip;
+    hdr->complete = applied == n_bits ? 1u : 0u;
     hdr->reserved = 0;
+  }
+  if (max_ranges == 0u || n_starts <= skip) return;  // nothing to list: uniform over the workgroup
+
+  before = seg_before;
+  for (uint64_t wb = w_lo; wb < w_hi; wb += kAckStep * kAckBatch) {
+    uint4 raw[kAckBatch];
+    uint32_t after[kAckBatch];
+#pragma unroll
+    for (int i = 0; i < kAckBatch; ++i) {
+      const uint64_t w0 = wb + static_cast<uint64_t>(i) * kAckStep;
+      raw[i] = ack_load4(bitmap, w0 + 4 * lane, w0 < w_hi ? n_words : 0, aligned);
+      after[i] = (w0 < w_hi && w0 + kAckStep < n_words) ? bitmap[w0 + kAckStep] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < kAckBatch; ++i) {
+      const uint64_t w0 = wb + static_cast<uint64_t>(i) * kAckStep;
+      if (w0 >= w_hi) continue;
+      const uint64_t w4 = w0 + 4 * lane;
+      const AckQuad q = ack_quad(raw[i], w4, n_bits, before, after[i], lane);
+      before = __shfl(q.word[3], 63, 64);
+      // starts in the low half, ends in the high half: at most 64 of each per lane, 4096 per step
+      uint32_t mine = 0;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) mine += __popc(q.starts[j]) | (static_cast<uint32_t>(__popc(q.ends[j])) << 16);
+      uint32_t incl = mine;
+#pragma unroll
+      for (uint32_t d = 1; d < 64; d <<= 1) {
+        const uint32_t below = __shfl_up(incl, d, 64);
+        if (lane >= d) incl += below;
+      }
+      uint32_t ks = s_at + ((incl - mine) & 0xFFFFu), ke = e_at + ((incl - mine) >> 16);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        for (uint32_t m = q.starts[j]; m; m &= m - 1, ++ks)
+          if (ks >= skip && ks - skip < max_ranges)
+            ranges[2 * static_cast<uint64_t>(ks - skip)] = (w4 + j) * 32 + (__ffs(m) - 1);
+        for (uint32_t m = q.ends[j]; m; m &= m - 1, ++ke)
+          if (ke >= skip && ke - skip < max_ranges)
+            ranges[2 * static_cast<uint64_t>(ke - skip) + 1] = (w4 + j) * 32 + (__ffs(m) - 1) + 1;
+      }
+      const uint32_t step_total = __shfl(incl, 63, 64);
+      s_at += step_total & 0xFFFFu;
+      e_at += step_total >> 16;
+    }
   }
 }
 
