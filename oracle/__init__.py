@@ -27,6 +27,7 @@ ERRORS = {-1: "ARG", -2: "SEQ", -3: "ALIGN", -4: "BOUNDS", -5: "MISMATCH", -6: "
 
 DESC = np.dtype([("src_off", "<u8"), ("dst_off", "<u8"), ("out_off", "<u8"),
                  ("len", "<u4"), ("seq", "<u4")])
+SEND_DESC = np.dtype([("stage_off", "<u8"), ("len", "<u4"), ("header", "<u4")])
 GATHER_DESC = np.dtype([("dst_off", "<u8"), ("out_off", "<u8"), ("len", "<u4"), ("seq", "<u4"),
                         ("n_src", "<u4"), ("reserved", "<u4"), ("src_off", "<u8", (16,))])
 
@@ -76,6 +77,9 @@ def lib():
         L.orc_message_status.argtypes = [vp, vp, C.c_uint32, C.c_uint32, vp, C.c_int]
         L.orc_ack_report.restype = None
         L.orc_ack_report.argtypes = [vp, u64, vp, vp, vp, vp, C.c_uint32]
+        L.orc_segment.restype = i64
+        L.orc_segment.argtypes = [vp, u64, vp, u64, u64, u64, C.c_uint32, u64, u64, vp, C.c_uint32, C.c_uint32,
+                                  C.c_uint32]
         L.orc_ring_allreduce.restype = C.c_int
         L.orc_ring_allreduce.argtypes = [vp, C.c_uint32, u64, C.c_int, C.c_int, vp]
         L.orc_combine_f32.restype = C.c_float
@@ -192,6 +196,23 @@ def message_status(words, n_chunks, bits_per_slot, recycle=False):
     lib().orc_message_status(_ptr(words), _ptr(n_chunks), len(n_chunks), int(bits_per_slot), _ptr(out),
                              int(bool(recycle)))
     return out
+
+
+def segment(stage, tensor, tensor_off, nbytes, chunk_bytes, stage_off=0, slot_stride=None, conn_id=0, msg_id=0,
+            first_csn=0, want_descs=True):
+    """Cut tensor[tensor_off, +nbytes) into staged chunks (in place in ``stage``, a uint8 array);
+    returns the send records (SEND_DESC array, or None)."""
+    assert stage.flags.c_contiguous and tensor.flags.c_contiguous
+    slot_stride = chunk_bytes if slot_stride is None else slot_stride
+    n = -(-int(nbytes) // int(chunk_bytes)) if chunk_bytes else 0
+    descs = np.zeros(n, dtype=SEND_DESC) if want_descs else None
+    rc = lib().orc_segment(_ptr(stage), stage.nbytes, _ptr(tensor), tensor.nbytes, int(tensor_off), int(nbytes),
+                           int(chunk_bytes), int(stage_off), int(slot_stride), _ptr(descs), int(conn_id), int(msg_id),
+                           int(first_csn))
+    if rc < 0:
+        raise OraclePrecondition(rc)
+    assert rc == n
+    return descs
 
 
 def ring_allreduce(x, dtype, op=SUM) -> np.ndarray:

@@ -331,6 +331,42 @@ void orc_message_status(uint32_t* words, const uint32_t* n_chunks, uint32_t n_sl
   }
 }
 
+/* ---- sender side: tensor buffer -> staged chunks + send records ---------------- */
+
+int64_t orc_segment(void* stage, uint64_t stage_bytes, const void* tensor, uint64_t tensor_bytes,
+                    uint64_t tensor_off, uint64_t bytes, uint32_t chunk_bytes, uint64_t stage_off,
+                    uint64_t slot_stride, orc_send_desc* descs, uint32_t conn_id, uint32_t msg_id,
+                    uint32_t first_csn) {
+  if (conn_id > 255u || msg_id > 127u) return ORC_E_ARG;
+  if (chunk_bytes == 0u || (chunk_bytes & 15u) || (tensor_off & 15u) || (stage_off & 15u) || (slot_stride & 15u))
+    return ORC_E_ALIGN;
+  if (bytes == 0) return 0;
+  if (!stage || !tensor) return ORC_E_ARG;
+  if (slot_stride < chunk_bytes) return ORC_E_BOUNDS; /* slots would overlap */
+  if (!range_ok(tensor_off, bytes, tensor_bytes)) return ORC_E_BOUNDS;
+  const uint64_t n = (bytes + chunk_bytes - 1) / chunk_bytes;
+  const uint64_t last_len = bytes - (n - 1) * chunk_bytes;
+  if (stage_off > stage_bytes || (n - 1) > (stage_bytes - stage_off) / slot_stride ||
+      !range_ok(stage_off + (n - 1) * slot_stride, last_len, stage_bytes))
+    return ORC_E_BOUNDS;
+  for (uint64_t i = 0; i < n; ++i) {
+    const uint64_t len = i + 1 < n ? chunk_bytes : last_len;
+    const unsigned char* from = (const unsigned char*)tensor + tensor_off + i * chunk_bytes;
+    unsigned char* to = (unsigned char*)stage + stage_off + i * slot_stride;
+    for (uint64_t b = 0; b < len; ++b) to[b] = from[b];
+    if (descs) {
+      const uint64_t number = (uint64_t)first_csn + i; /* position in the run of chunks of this connection */
+      const uint32_t csn = (uint32_t)(number % 256u);
+      const uint32_t msg = (uint32_t)((msg_id + number / 256u) % 128u);
+      const uint32_t mark = (csn == 255u || i + 1 == n) ? 1u : 0u;
+      descs[i].stage_off = stage_off + i * slot_stride;
+      descs[i].len = (uint32_t)len;
+      descs[i].header = csn | (mark << 8) | (msg << 9) | (conn_id << 16);
+    }
+  }
+  return (int64_t)n;
+}
+
 /* ---- whole-call preconditions ---------------------------------------------- */
 
 typedef struct { uint64_t key, end; uint64_t idx; } ivl;

@@ -18,7 +18,7 @@
  *
  * Parity status: every function is pinned by tests/test_oracle_pins.py (multi-source fold:
  * tests/test_gather_reduce.py; whole definition against a brute-force model:
- * tests/test_oracle_bruteforce.py) except
+ * tests/test_oracle_bruteforce.py; sender-side segmentation: tests/test_segment.py) except
  *  - MAX/MIN on NaN or mixed-sign zeros, and which copy of a duplicated sequence
  *    number supplies the bytes: the paper fixes neither ("parity unpinned"; the
  *    behaviour below is a definition made here, see the comments at each).
@@ -115,6 +115,30 @@ void orc_ack_report(const uint32_t* words, uint64_t n_bits, uint64_t* cum_ack, u
  * all set, 0}.  recycle != 0 clears the whole window of every complete slot afterwards. */
 void orc_message_status(uint32_t* words, const uint32_t* n_chunks, uint32_t n_slots,
                         uint32_t bits_per_slot, uint32_t* out4, int recycle);
+
+/* Sender side (Section 2.1: the kernel copies from the tensor buffer to the transport buffer;
+ * Section 3.1: the sender CPU names the address of every data chunk and sends a 32-bit control
+ * header with it -- 8-bit connection id, 7-bit message id, 8-bit chunk sequence number, a
+ * last-chunk mark; Appendix A: onChunkSize gives the chunk size, then a chunk_desc is built).
+ * The bytes tensor[tensor_off, +bytes) are cut into payloads of chunk_bytes (the last may be
+ * shorter; none if bytes == 0); payload i is copied to stage + stage_off + i * slot_stride and
+ * described by descs[i] = { its staging offset, its length, its header }.  The chunks are numbered
+ * first_csn, first_csn + 1, ...: a message holds 256 of them, so chunk number c travels as
+ * message (msg_id + c / 256) mod 128 with sequence number c mod 256, and the last chunk of every
+ * message (sequence number 255, or the final chunk of the transfer) carries the mark.  Header
+ * layout (a choice of this interface): sequence number in bits 0-7, mark in bit 8, message id in
+ * bits 9-15, connection id in bits 16-23, bits 24-31 zero.  Returns the number of chunks or a
+ * negative code (ORC_E_ALIGN: an offset, chunk_bytes or slot_stride not a multiple of 16, or
+ * chunk_bytes == 0; ORC_E_BOUNDS: a range leaves its buffer or slots overlap; ORC_E_ARG). */
+typedef struct {
+  uint64_t stage_off;
+  uint32_t len;
+  uint32_t header;
+} orc_send_desc;
+int64_t orc_segment(void* stage, uint64_t stage_bytes, const void* tensor, uint64_t tensor_bytes,
+                    uint64_t tensor_off, uint64_t bytes, uint32_t chunk_bytes, uint64_t stage_off,
+                    uint64_t slot_stride, orc_send_desc* descs, uint32_t conn_id, uint32_t msg_id,
+                    uint32_t first_csn);
 
 /* Textbook in-order ring allreduce of R vectors of n elements (n % R == 0),
  * no chunks, no transport: x is R*n elements (rank-major), result is R*n
