@@ -261,6 +261,41 @@ int uccl_chunk_scatter_opts(void* dst, const void* recv_stage, const uccl_chunk_
                             uint32_t n_descs, uint32_t* dedup_bitmap, const uccl_extents* extents,
                             uint32_t* n_rejected, const uccl_launch_opts* opts, void* stream);
 
+/*
+ * uccl_chunk_segment -- sender side: cut a range of the tensor buffer into chunks in the outbound
+ * staging buffer and write one send record per chunk for the control path (Section 2.1: the kernel
+ * copies from the tensor buffer to the transport buffer; Section 3.1: the sender CPU gives the
+ * address of every data chunk and a 32-bit control header travels with it -- connection id 8 bits,
+ * message id 7 bits, chunk sequence number 8 bits, a last-chunk mark; Appendix A: onChunkSize
+ * returns the permitted chunk size, then a chunk_desc is built).  A ring's first step sends the
+ * rank's own segment this way; every later step sends what uccl_chunk_apply forwarded.
+ *
+ *   tensor[tensor_off, +bytes) is cut into n = ceil(bytes / chunk_bytes) payloads (the last may be
+ *   shorter, of any byte length; bytes == 0 enqueues nothing); payload i is copied to
+ *   out_stage + stage_off + i * slot_stride and send_descs[i] = { that offset, its length, its header }.
+ *   Chunks are numbered first_csn, first_csn + 1, ...; a message holds 256, so chunk number c is
+ *   chunk c mod 256 of message (msg_id + c / 256) mod 128, and the last chunk of every message
+ *   (sequence number 255, or the final chunk of the call) carries the mark.  Header layout:
+ *   sequence number in bits 0-7, mark in bit 8, message id in bits 9-15, connection id in bits
+ *   16-23, bits 24-31 zero (left to receiver-driven congestion control).
+ *
+ * out_stage, tensor: DEVICE memory, 16-byte aligned; send_descs: device or pinned host memory, room
+ * for n records, 8-byte aligned, may be NULL (copy only).  tensor_off, stage_off, chunk_bytes and
+ * slot_stride are multiples of 16 (UCCL_EALIGN), chunk_bytes > 0, slot_stride >= chunk_bytes,
+ * conn_id < 256, msg_id < 128, at most 2^32 - 1 chunks (UCCL_EINVAL).  A control path that changes the
+ * chunk size as it goes (onChunkSize) makes one call per run of equal-sized chunks.  Ranges must lie
+ * inside their buffers and must not overlap (not checked).  Stream ordered.
+ */
+typedef struct uccl_send_desc {
+  uint64_t stage_off; /* byte offset of the chunk's payload in out_stage */
+  uint32_t len;       /* payload bytes */
+  uint32_t header;    /* control header, layout above */
+} uccl_send_desc;
+int uccl_chunk_segment(void* out_stage, const void* tensor, uint64_t tensor_off, uint64_t bytes,
+                       uint32_t chunk_bytes, uint64_t stage_off, uint64_t slot_stride,
+                       uccl_send_desc* send_descs, uint32_t conn_id, uint32_t msg_id, uint32_t first_csn,
+                       void* stream);
+
 /* Clear the first n_bits bits (rounded up to whole 32-bit words) of the bitmap: starts a
  * new message / connection epoch (Section 3.1: a message id, and with it its chunk sequence
  * numbers, is reused once its message is complete).  Uses a fill kernel, so it may be captured

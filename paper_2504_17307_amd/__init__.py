@@ -77,6 +77,8 @@ _SIGNATURES = {
     "uccl_chunk_scatter_opts": (C.c_int, [C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint32, C.c_void_p,
                                           C.POINTER(uccl_extents), C.c_void_p, C.POINTER(uccl_launch_opts),
                                           C.c_void_p]),
+    "uccl_chunk_segment": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint64, C.c_uint64, C.c_uint32, C.c_uint64,
+                                     C.c_uint64, C.c_void_p, C.c_uint32, C.c_uint32, C.c_uint32, C.c_void_p]),
     "uccl_dedup_reset": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p]),
     "uccl_init": (C.c_int, []),
     "uccl_claim_timeouts": (C.c_int, [C.POINTER(C.c_uint64)]),
@@ -261,6 +263,18 @@ def uccl_claim_timeouts() -> int:
     n = C.c_uint64(0)
     _check(load().uccl_claim_timeouts(C.byref(n)), "uccl_claim_timeouts")
     return n.value
+
+
+SEND_DESC_BYTES = 16
+
+
+def uccl_chunk_segment(out_stage, tensor, tensor_off, nbytes, chunk_bytes, stage_off=0, slot_stride=None,
+                       send_descs=None, conn_id=0, msg_id=0, first_csn=0, stream=None):
+    """``send_descs``: a tensor (device or pinned host) with room for ceil(nbytes / chunk_bytes) 16-byte records, or None."""
+    _check(load().uccl_chunk_segment(_ptr(out_stage), _ptr(tensor), int(tensor_off), int(nbytes), int(chunk_bytes),
+                                     int(stage_off), int(chunk_bytes if slot_stride is None else slot_stride),
+                                     _ptr(send_descs), int(conn_id), int(msg_id), int(first_csn), _stream(stream)),
+           "uccl_chunk_segment")
 
 
 def uccl_dedup_reset(dedup_bitmap, n_bits, stream=None):

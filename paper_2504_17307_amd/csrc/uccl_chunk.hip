@@ -744,6 +744,36 @@ int uccl_claim_timeouts(uint64_t* count) {
   return UCCL_OK;
 }
 
+int uccl_chunk_segment(void* out_stage, const void* tensor, uint64_t tensor_off, uint64_t bytes,
+                       uint32_t chunk_bytes, uint64_t stage_off, uint64_t slot_stride,
+                       uccl_send_desc* send_descs, uint32_t conn_id, uint32_t msg_id, uint32_t first_csn,
+                       void* stream) {
+  if (conn_id > 255u || msg_id > 127u || chunk_bytes == 0u) return UCCL_EINVAL;
+  if ((chunk_bytes & 15u) || (tensor_off & 15u) || (stage_off & 15u) || (slot_stride & 15u)) return UCCL_EALIGN;
+  if (slot_stride < chunk_bytes) return UCCL_EINVAL;
+  if (bytes == 0) return UCCL_OK;
+  if (!out_stage || !tensor) return UCCL_EINVAL;
+  if (misaligned(out_stage, 16) || misaligned(tensor, 16) || misaligned(send_descs, 8)) return UCCL_EALIGN;
+  const uint64_t n_chunks = (bytes + chunk_bytes - 1) / chunk_bytes;
+  if (n_chunks > 0xFFFFFFFFull) return UCCL_EINVAL;
+  SegmentArgs a;
+  a.stage = static_cast<char*>(out_stage) + stage_off;
+  a.tensor = static_cast<const char*>(tensor) + tensor_off;
+  a.descs = send_descs;
+  a.bytes = bytes;
+  a.slot_stride = slot_stride;
+  a.stage_off = stage_off;
+  a.n_chunks = n_chunks;
+  a.chunk_bytes = chunk_bytes;
+  a.units_per_chunk = (chunk_bytes + 2047u) / 2048u;
+  a.conn_id = conn_id;
+  a.msg_id = msg_id;
+  a.first_csn = first_csn;
+  const uint64_t groups = (n_chunks * a.units_per_chunk + 15) / 16;  // 16 units per workgroup
+  if (groups > 0x7FFFFFFFull) return UCCL_EINVAL;
+  return launch_kernel(segment_kernel, static_cast<uint32_t>(groups), 1024, static_cast<hipStream_t>(stream), a);
+}
+
 int uccl_dedup_reset(uint32_t* dedup_bitmap, uint64_t n_bits, void* stream) {
   if (n_bits == 0) return UCCL_OK;
   if (!dedup_bitmap) return UCCL_EINVAL;

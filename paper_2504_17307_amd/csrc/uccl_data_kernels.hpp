@@ -587,6 +587,67 @@ __global__ void __launch_bounds__(NT) chunk_gather_kernel(const GatherArgs g) {
   }
 }
 
+// ---- sender side: tensor buffer -> staged chunks + send records --------------------------------
+//
+// Section 2.1: the kernel copies from the tensor buffer to the transport buffer the NIC sends
+// from; Section 3.1: the sender CPU names each chunk's address and sends a 32-bit control header
+// with it.  A dense copy: chunk i of the range goes to slot i of the staging buffer, cut into
+// 2 KiB units (64 lanes x 2 x 16 bytes), one unit per wavefront, 16 per workgroup.  The wavefront
+// that takes a chunk's first unit also writes the chunk's send record.  The tensor is read with
+// default policy (it is the accumulator, read again by the next step), staging is written
+// non-temporally (the NIC reads it, the GPU does not).
+struct SegmentArgs {
+  char* stage;
+  const char* tensor;
+  uccl_send_desc* descs;
+  uint64_t bytes;        // length of the range (tensor already points at its start)
+  uint64_t slot_stride;
+  uint64_t stage_off;    // of slot 0, for the records (stage already points there)
+  uint64_t n_chunks;
+  uint32_t chunk_bytes;
+  uint32_t units_per_chunk;
+  uint32_t conn_id, msg_id, first_csn;
+};
+
+__global__ void __launch_bounds__(1024) segment_kernel(const SegmentArgs g) {
+  constexpr uint32_t kUnit = 128u;  // 16-byte vectors per unit
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint64_t unit = static_cast<uint64_t>(blockIdx.x) * 16u + (threadIdx.x >> 6);
+  const uint64_t i = unit / g.units_per_chunk;           // chunk
+  const uint32_t u = static_cast<uint32_t>(unit % g.units_per_chunk);
+  if (i >= g.n_chunks) return;                            // whole wavefronts leave; no barrier follows
+  const uint64_t from = i * g.chunk_bytes;
+  const uint64_t left = g.bytes - from;
+  const uint32_t len = left < g.chunk_bytes ? static_cast<uint32_t>(left) : g.chunk_bytes;
+  if (u == 0 && lane == 0 && g.descs != nullptr) {
+    const uint64_t number = static_cast<uint64_t>(g.first_csn) + i;
+    const uint32_t csn = static_cast<uint32_t>(number & 255u);
+    const uint32_t msg = static_cast<uint32_t>((g.msg_id + (number >> 8)) & 127u);
+    const uint32_t mark = (csn == 255u || i + 1 == g.n_chunks) ? 1u : 0u;
+    uccl_send_desc d;
+    d.stage_off = g.stage_off + i * g.slot_stride;
+    d.len = len;
+    d.header = csn | (mark << 8) | (msg << 9) | (g.conn_id << 16);
+    g.descs[i] = d;
+  }
+  const uint32_t nvec = len >> 4;
+  const uint32_t v0 = u * kUnit;
+  const u32x4* sp = reinterpret_cast<const u32x4*>(g.tensor + from) + v0 + lane;
+  u32x4* dp = reinterpret_cast<u32x4*>(g.stage + i * g.slot_stride) + v0 + lane;
+  u32x4 v[2];
+#pragma unroll
+  for (int k = 0; k < 2; ++k)
+    if (v0 + lane + k * 64 < nvec) v[k] = sp[k * 64];
+#pragma unroll
+  for (int k = 0; k < 2; ++k)
+    if (v0 + lane + k * 64 < nvec) __builtin_nontemporal_store(v[k], dp + k * 64);
+  const uint32_t rem = len & 15u;  // the last, partial vector: byte by byte, by the unit that holds it
+  if (rem != 0u && nvec >= v0 && nvec < v0 + kUnit && lane < rem) {
+    const uint64_t at = (static_cast<uint64_t>(nvec) << 4) + lane;
+    g.stage[i * g.slot_stride + at] = g.tensor[from + at];
+  }
+}
+
 __global__ void __launch_bounds__(256) fill_words_kernel(uint32_t* p, uint64_t n, uint32_t v) {
   for (uint64_t i = static_cast<uint64_t>(blockIdx.x) * 256 + threadIdx.x; i < n;
        i += static_cast<uint64_t>(gridDim.x) * 256)

@@ -9,6 +9,9 @@ library), passed in as an object with:
     apply(handle, recv_np, descs_np, dtype, op) -> None
     read_out(handle, off, nbytes) -> np.uint8 array
     read_acc(handle) -> np array (same storage dtype as acc_init)
+    segment(handle, off, nbytes, C) -> list of np.uint8 arrays   (optional: the very first step's
+        hand-off, the rank's own segment cut into chunks by the backend's sender-side path; without
+        it the driver slices the input on the host)
 """
 import numpy as np
 
@@ -33,6 +36,8 @@ def closed_loop_allreduce(backend, x, dtype, C, seed, paths=4, window=None, dup=
     for phase in (0, 1):
         for s in range(R - 1):
             staged = []
+            first_hop = phase == 0 and s == 0 and hasattr(backend, "segment")
+            sent = [backend.segment(ranks[q], q * S, S, C) for q in range(R)] if first_hop else None
             for r in range(R):
                 left = (r - 1) % R
                 mine = plans[r][phase][s * cps:(s + 1) * cps]
@@ -41,7 +46,10 @@ def closed_loop_allreduce(backend, x, dtype, C, seed, paths=4, window=None, dup=
                 chunks = []
                 for c in range(cps):
                     ln = int(mine[c]["len"])
-                    if phase == 0 and s == 0:
+                    if first_hop:
+                        assert len(sent[left]) == cps and len(sent[left][c]) == ln
+                        chunks.append(sent[left][c])
+                    elif phase == 0 and s == 0:
                         o = left * S + c * C
                         chunks.append(xb[left, o:o + ln])
                     else:

@@ -77,6 +77,17 @@ def test_host_side_error_codes_enqueue_nothing():
     assert lib.uccl_chunk_scatter_opts(A, B, D, 1, M, None, None, C.byref(pkg.uccl_launch_opts(0, 99)), None) == pkg.UCCL_EINVAL
     assert lib.uccl_chunk_reduce_gather(A, None, B, D, 1, M, 0, 0, None, None, C.byref(pkg.uccl_launch_opts(0, 99)), None) == pkg.UCCL_EINVAL
     assert lib.uccl_claim_timeouts(None) == pkg.UCCL_EINVAL
+    sg = lib.uccl_chunk_segment
+    assert sg(A, B, 0, 4096, 0, 0, 64, None, 0, 0, 0, None) == pkg.UCCL_EINVAL        # chunk size 0
+    assert sg(A, B, 0, 4096, 24, 0, 64, None, 0, 0, 0, None) == pkg.UCCL_EALIGN
+    assert sg(A, B, 8, 4096, 64, 0, 64, None, 0, 0, 0, None) == pkg.UCCL_EALIGN
+    assert sg(A, B, 0, 4096, 64, 4, 64, None, 0, 0, 0, None) == pkg.UCCL_EALIGN
+    assert sg(A, B, 0, 4096, 64, 0, 32, None, 0, 0, 0, None) == pkg.UCCL_EINVAL        # slots would overlap
+    assert sg(A, B, 0, 4096, 64, 0, 64, None, 256, 0, 0, None) == pkg.UCCL_EINVAL      # connection id is 8 bits
+    assert sg(A, B, 0, 4096, 64, 0, 64, None, 0, 128, 0, None) == pkg.UCCL_EINVAL      # message id is 7 bits
+    assert sg(None, None, 0, 0, 64, 0, 64, None, 0, 0, 0, None) == pkg.UCCL_OK         # nothing to cut
+    assert sg(None, B, 0, 64, 64, 0, 64, None, 0, 0, 0, None) == pkg.UCCL_EINVAL
+    assert sg(A, B, 0, 64, 64, 0, 64, 0x70004, 0, 0, 0, None) == pkg.UCCL_EALIGN
     na = lib.uccl_chunk_apply_noalloc
     assert na(A, None, B, D, pkg.UCCL_NOALLOC_MAX_DESCS + 1, M, 0, 0, None) == pkg.UCCL_ETOOBIG   # before any GPU call
     assert na(A, None, B, D, 1, M, 7, 0, None) == pkg.UCCL_EINVAL

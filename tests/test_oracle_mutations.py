@@ -14,6 +14,7 @@ import oracle
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 PINS = "tests/test_oracle_pins.py::"
 GATHER = "tests/test_gather_reduce.py::"
+SEGMENT = "tests/test_segment.py::"
 
 # (name, text in chunk_oracle.c, replacement, replace every occurrence?, pin that must fail)
 MISTAKES = [
@@ -105,6 +106,21 @@ MISTAKES = [
     ("binary16 narrowing has no NaN branch",
      "if (mag > 0x7F800000u) return (uint16_t)(sign | 0x7E00u | ((mag >> 13) & 0x1FFu)); /* NaN, quieted */", ";", False,
      PINS + "test_narrowing_a_nan_gives_a_quiet_nan_of_the_same_sign"),
+    ("segmentation: slots packed at the chunk size", "unsigned char* to = (unsigned char*)stage + stage_off + i * slot_stride;",
+     "unsigned char* to = (unsigned char*)stage + stage_off + i * chunk_bytes;", False,
+     SEGMENT + "test_whole_chunks_are_a_reshape"),
+    ("segmentation: source offset ignored", "(const unsigned char*)tensor + tensor_off + i * chunk_bytes;",
+     "(const unsigned char*)tensor + i * chunk_bytes;", False, SEGMENT + "test_ragged_tail_and_concatenation"),
+    ("segmentation: last chunk padded to full length", "const uint64_t len = i + 1 < n ? chunk_bytes : last_len;",
+     "const uint64_t len = chunk_bytes;", False, SEGMENT + "test_ragged_tail_and_concatenation"),
+    ("segmentation: no mark at a message boundary", "const uint32_t mark = (csn == 255u || i + 1 == n) ? 1u : 0u;",
+     "const uint32_t mark = (i + 1 == n) ? 1u : 0u;", False, SEGMENT + "test_headers_follow_the_field_widths"),
+    ("segmentation: message id does not advance", "const uint32_t msg = (uint32_t)((msg_id + number / 256u) % 128u);",
+     "const uint32_t msg = msg_id;", False, SEGMENT + "test_headers_follow_the_field_widths"),
+    ("segmentation: numbering ignores the first sequence number", "const uint64_t number = (uint64_t)first_csn + i;",
+     "const uint64_t number = i;", False, SEGMENT + "test_headers_follow_the_field_widths"),
+    ("segmentation: record offset relative to the first slot", "descs[i].stage_off = stage_off + i * slot_stride;",
+     "descs[i].stage_off = i * slot_stride;", False, SEGMENT + "test_whole_chunks_are_a_reshape"),
     ("binary16 NaN loses its sign",
      "if (mag > 0x7F800000u) return (uint16_t)(sign | 0x7E00u | ((mag >> 13) & 0x1FFu)); /* NaN, quieted */",
      "if (mag > 0x7F800000u) return (uint16_t)(0x7E00u | ((mag >> 13) & 0x1FFu));", False,

@@ -131,6 +131,15 @@ class OracleBackend:
         return h["acc"]
 
 
+class OracleBackendWithSegment(OracleBackend):
+    """The same, with the first hop's chunks produced by the oracle's sender-side segmentation."""
+
+    def segment(self, h, off, nbytes, C):
+        stage = np.zeros(-(-nbytes // C) * (C + 32), dtype=np.uint8)
+        d = oracle.segment(stage, h["acc"].view(np.uint8), off, nbytes, C, 0, C + 32)
+        return [stage[o:o + n].copy() for o, n in zip(d["stage_off"], d["len"])]
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("R,n,C", [(2, 64, 16), (3, 96, 32), (4, 512, 64), (8, 4096, 48)])
 def test_closed_loop_small_integers_exact(dtype, R, n, C):
@@ -144,6 +153,15 @@ def test_closed_loop_small_integers_exact(dtype, R, n, C):
     expect = pl.ints_as(vals.sum(axis=0), dtype)
     for r in range(R):
         assert np.array_equal(got[r], expect)
+
+
+def test_closed_loop_with_segmented_first_hop():
+    """Step 0 of the ring sends each rank's own segment: cut into chunks by the sender-side path
+    instead of host slicing, the closed loop still equals the textbook ring (ragged last chunk)."""
+    R, n, C = 4, 4 * 100, 48
+    x = pl.uniform_f32(15, 3, R * n).reshape(R, n)
+    got = closed_loop_allreduce(OracleBackendWithSegment(), x, F32, C, seed=3, paths=3, window=4, dup=0.2)
+    assert np.array_equal(got, oracle.ring_allreduce(x, F32, SUM))
 
 
 @pytest.mark.parametrize("dtype,op", [(F32, SUM), (BF16, SUM), (F32, MAX), (BF16, MIN)])

@@ -95,3 +95,98 @@ def test_rejections():
                            args["slot_stride"], args["conn_id"], args["msg_id"])
         assert e.value.code == code, kw
     assert not stage.any(), "a rejected call writes nothing"
+
+
+# ---- GPU parity ----------------------------------------------------------------------------------
+
+def gpu_segment(pkg, t, off, nbytes, chunk, stage_bytes, stage_off=0, stride=None, pinned_descs=False, **hdr):
+    import torch
+    from gpuhelp import to_dev
+    n = -(-nbytes // chunk)
+    stage = torch.full((stage_bytes,), 0xC3, dtype=torch.uint8, device="cuda")
+    recs = (torch.zeros(max(n, 1) * 16 + 16, dtype=torch.uint8, pin_memory=True) if pinned_descs else
+            torch.full((max(n, 1) * 16 + 16,), 0x99, dtype=torch.uint8, device="cuda"))
+    pkg.uccl_chunk_segment(stage, to_dev(t), off, nbytes, chunk, stage_off, stride, recs, **hdr)
+    torch.cuda.synchronize()
+    raw = recs.cpu().numpy() if not pinned_descs else recs.numpy()
+    return stage.cpu().numpy(), raw[:n * 16].view(oracle.SEND_DESC).copy(), raw[n * 16:]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("nbytes,chunk,stride", [(1, 16, 16), (15, 16, 32), (4096, 4096, 4096), (300000, 4096, 4096),
+                                                 (300001, 32768, 32768 + 64), (70000 * 16 + 7, 2048 + 16, 4096),
+                                                 (5 << 20, 128 << 10, 128 << 10), (600 * 48 - 9, 48, 48)])
+def test_gpu_segment_parity(gpu_lib, nbytes, chunk, stride):
+    t = tensor_bytes(nbytes % 97, nbytes + 4096)
+    off, base = 2048, 64
+    n = -(-nbytes // chunk)
+    stage_bytes = base + n * stride + 256
+    hdr = dict(conn_id=77, msg_id=120, first_csn=200)
+    got_stage, got_d, beyond = gpu_segment(gpu_lib, t, off, nbytes, chunk, stage_bytes, base, stride, **hdr)
+    exp_stage = np.full(stage_bytes, 0xC3, dtype=np.uint8)
+    exp_d = oracle.segment(exp_stage, t, off, nbytes, chunk, base, stride, **hdr)
+    assert np.array_equal(got_stage, exp_stage), "staging bytes (payloads, gaps and surroundings)"
+    assert np.array_equal(got_d, exp_d), "send records"
+    assert np.all(beyond == 0x99), "wrote past the records"
+
+
+@pytest.mark.gpu
+def test_gpu_segment_records_in_pinned_memory_and_copy_only(gpu_lib):
+    import torch
+    from gpuhelp import to_dev
+    t = tensor_bytes(9, 1 << 20)
+    stage, d, _ = gpu_segment(gpu_lib, t, 0, 1 << 20, 32 << 10, 1 << 20, pinned_descs=True, conn_id=1, msg_id=2)
+    exp = np.zeros(1 << 20, dtype=np.uint8)
+    assert np.array_equal(d, oracle.segment(exp, t, 0, 1 << 20, 32 << 10, conn_id=1, msg_id=2)) and np.array_equal(stage, exp)
+    st = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    gpu_lib.uccl_chunk_segment(st, to_dev(t), 0, 1 << 20, 32 << 10)   # no records asked for
+    gpu_lib.uccl_chunk_segment(st, to_dev(t), 0, 0, 32 << 10)         # nothing to do
+    torch.cuda.synchronize()
+    assert np.array_equal(st.cpu().numpy(), exp)
+
+
+@pytest.mark.gpu
+def test_gpu_segment_equals_scatter_with_identity_records(gpu_lib):
+    """The same staging bytes come out of the all-to-all scatter when it is given one record per
+    chunk with the tensor as its source: segmentation needs no kernel of its own to be correct,
+    the dedicated one only saves the record list, the bitmap and a host-side loop."""
+    import torch
+    from gpuhelp import to_dev
+    nbytes, chunk, stride = 3 * (1 << 20) + 4000, 32 << 10, (32 << 10) + 256
+    t = tensor_bytes(11, nbytes + 512)
+    n = -(-nbytes // chunk)
+    stage, d, _ = gpu_segment(gpu_lib, t, 256, nbytes, chunk, n * stride, 0, stride)
+    rec = np.zeros(n, dtype=DESC)
+    rec["src_off"], rec["dst_off"], rec["out_off"] = 256 + chunk * np.arange(n), d["stage_off"], NO_FORWARD
+    rec["len"], rec["seq"] = d["len"], np.arange(n)
+    other = torch.full((n * stride,), 0xC3, dtype=torch.uint8, device="cuda")
+    gpu_lib.uccl_chunk_scatter(other, to_dev(t), to_dev(rec), n, torch.zeros((n + 31) // 32, dtype=torch.int32, device="cuda"))
+    torch.cuda.synchronize()
+    assert np.array_equal(other.cpu().numpy(), stage)
+
+
+@pytest.mark.gpu
+def test_gpu_closed_loop_ring_with_segmented_first_hop(gpu_lib):
+    """All ranks on the GPU path, the first hop's chunks cut by uccl_chunk_segment from each rank's
+    accumulator (ragged last chunk): equals the textbook ring."""
+    import torch
+    from gpuhelp import assert_same, to_host
+    from ringloop import closed_loop_allreduce
+    from test_gpu_parity import GpuBackend
+    from synth.layout import F32, BF16, SUM
+
+    class WithSegment(GpuBackend):
+        def segment(self, h, off, nbytes, C):
+            n = -(-nbytes // C)
+            stage = torch.zeros(n * (C + 64), dtype=torch.uint8, device="cuda")
+            recs = torch.zeros(n * 16, dtype=torch.uint8, pin_memory=True)
+            self.pkg.uccl_chunk_segment(stage, h["acc"], off, nbytes, C, 0, C + 64, recs)
+            torch.cuda.synchronize()
+            d = recs.numpy().view(oracle.SEND_DESC)
+            host = stage.cpu().numpy()
+            return [host[o:o + ln].copy() for o, ln in zip(d["stage_off"], d["len"])]
+
+    for dtype, R, n, C in ((F32, 8, 1 << 20, 64 << 10), (BF16, 3, 3 * 5000, 2048)):
+        x = pl.uniform_f32(18, 8, R * n).reshape(R, n) if dtype == F32 else pl.normal_bf16(18, 8, R * n).reshape(R, n)
+        got = closed_loop_allreduce(WithSegment(gpu_lib), x, dtype, C, seed=6, paths=4, window=None, dup=0.05)
+        assert_same(got, oracle.ring_allreduce(x, dtype, SUM), "closed loop, segmented first hop")
