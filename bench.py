@@ -105,37 +105,21 @@ def call_stats(descs, op):
 
 
 def two_pass_calls(w, chunk, group=1):
-    """The paper's literal form (Section 3.1): first a scattered memcpy of the arrivals into an
-    in-order transport buffer (dedup + place), then the reduction from the transport buffer.
-    With group > 1 the arrivals are packets of `chunk` bytes and the reduction reads the
-    transport buffer in pieces of `group` packets (the collective's own chunk size).
-    Returns the call list and the transport buffer size."""
-    from synth.layout import DESC, COPY
-    calls, seq0, most = [], 0, 0
-    for ph, lg in zip(w.phases, w.extra["logical"]):
-        d1 = ph.descs.copy()
-        d1["dst_off"] = (d1["seq"].astype(np.uint64) - np.uint64(seq0)) * np.uint64(chunk)
-        d1["out_off"] = np.uint64(0xFFFFFFFFFFFFFFFF)
-        u, pay, algo = call_stats(d1, COPY)
+    """The paper's literal form (Section 3.1) as a call list: per phase a scattered memcpy of the
+    arrivals into an in-order transport buffer, then the reduction from it (records from
+    synth.workloads.two_pass_records).  Returns the call list and the transport buffer size."""
+    from synth import workloads as wl
+    from synth.layout import COPY
+    pairs, transport_bytes = wl.two_pass_records(w, chunk, group)
+    calls = []
+    for ph, (d1, d2) in zip(w.phases, pairs):
+        _, _, algo = call_stats(d1, COPY)
         calls.append(dict(name=ph.name + ": scatter to transport buffer", op=COPY, descs=d1, n_unique=0,
                           payload_bytes=0, algo_bytes=algo, scatter=True, dst="transport", src="recv", bm="bitmap"))
-        assert len(lg) % group == 0 and np.all(lg["len"] == chunk), "whole groups of full packets"
-        head = lg[::group]
-        d2 = np.zeros(len(head), dtype=DESC)
-        d2["src_off"] = np.arange(len(head), dtype=np.uint64) * np.uint64(chunk * group)
-        d2["dst_off"], d2["out_off"], d2["len"] = head["dst_off"], head["out_off"], chunk * group
-        d2["seq"] = head["seq"]
-        if group > 1:  # the packets of a group are consecutive in the accumulator and in the staging buffer
-            nxt = lg[1::group]
-            assert np.all(nxt["dst_off"] == head["dst_off"] + np.uint64(chunk))
-            fwd = head["out_off"] != np.uint64(0xFFFFFFFFFFFFFFFF)
-            assert np.all(nxt["out_off"][fwd] == head["out_off"][fwd] + np.uint64(chunk))
         u, pay, algo = call_stats(d2, ph.op)
         calls.append(dict(name=ph.name + ": reduce from transport buffer", op=ph.op, descs=d2, n_unique=u,
                           payload_bytes=pay, algo_bytes=algo, scatter=False, dst="acc", src="transport", bm="bitmap2"))
-        seq0 += len(lg)
-        most = max(most, len(lg))
-    return calls, most * chunk
+    return calls, transport_bytes
 
 
 def build_job(name, seed, n_msgs, relay=False, per_call=128, packet_bytes=0):

@@ -201,6 +201,37 @@ def ring_share(name: str, seed: int, R: int, M: int, C: int, dtype: int, paths: 
     return w
 
 
+def two_pass_records(w: Workload, arrival_bytes: int, group: int = 1):
+    """The paper's literal form of the receive path (Section 3.1): first a scattered memcpy of the
+    arrivals into an in-order transport buffer, then the reduction from the transport buffer.
+    For a ring workload ``w`` whose arrivals are ``arrival_bytes`` long, returns per phase a pair
+    (scatter records, reduce records) and the transport buffer's size.  The scatter records place
+    arrival ``seq`` at ``(seq - first seq of the phase) * arrival_bytes`` and never forward; the
+    reduce records read the transport buffer in pieces of ``group`` arrivals (with packet-sized
+    arrivals, the collective's own chunk) and carry the phase's destinations.  Records only: the
+    two passes are run by whoever calls this."""
+    pairs, seq0, most = [], 0, 0
+    for ph, lg in zip(w.phases, w.extra["logical"]):
+        first = ph.descs.copy()
+        first["dst_off"] = (first["seq"].astype(np.uint64) - np.uint64(seq0)) * np.uint64(arrival_bytes)
+        first["out_off"] = NO_FORWARD
+        assert len(lg) % group == 0 and np.all(lg["len"] == arrival_bytes), "whole groups of full arrivals"
+        head = lg[::group]
+        second = np.zeros(len(head), dtype=DESC)
+        second["src_off"] = np.arange(len(head), dtype=np.uint64) * np.uint64(arrival_bytes * group)
+        second["dst_off"], second["out_off"], second["len"] = head["dst_off"], head["out_off"], arrival_bytes * group
+        second["seq"] = head["seq"]
+        if group > 1:  # the arrivals of a group are consecutive in the accumulator and in the staging buffer
+            nxt = lg[1::group]
+            assert np.all(nxt["dst_off"] == head["dst_off"] + np.uint64(arrival_bytes))
+            fwd = head["out_off"] != NO_FORWARD
+            assert np.all(nxt["out_off"][fwd] == head["out_off"][fwd] + np.uint64(arrival_bytes))
+        pairs.append((first, second))
+        seq0 += len(lg)
+        most = max(most, len(lg))
+    return pairs, most * arrival_bytes
+
+
 def alltoall_dispatch(name: str, seed: int, n_src: int, row_bytes: int, max_bytes: int, C: int,
                       paths: int, dup: float, dtype: int = BF16, lengths=None) -> Workload:
     """All-to-all dispatch receive side: ``n_src`` remote sources each send

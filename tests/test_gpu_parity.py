@@ -834,3 +834,30 @@ def test_cut_records_in_a_captured_graph(gpu_lib):
         assert_same(bm, ebm, f"bitmap, replay {rep}")
         assert_same(acc, eacc, f"acc, replay {rep}")
         assert_same(out, eout, f"out, replay {rep}")
+
+
+@pytest.mark.parametrize("packet_bytes", [0, 4096, 8192])
+def test_two_pass_form_equals_the_single_pass_definition(gpu_lib, packet_bytes):
+    """The paper's literal receive path (Section 3.1: scattered memcpy of the out-of-order payloads
+    into the transport buffer, then the original reduction), composed from uccl_chunk_scatter and
+    uccl_chunk_apply: its accumulator and staging bytes equal the oracle's single-pass result on
+    the same arrivals.  packet_bytes > 0: every arrival is one datagram payload, reassembled into
+    the transport buffer and then reduced at the collective's 32 KiB chunk size (Appendix C.4)."""
+    C = 32 << 10
+    arrival = packet_bytes or C
+    w = wl.config2(seed=12, M=16 << 20, C=arrival, window=1024 * C // arrival)
+    eacc, eout, _ = oracle_results(w)
+    pairs, transport_bytes = wl.two_pass_records(w, arrival, C // arrival)
+    run = DeviceRun(w)
+    transport = torch.zeros(transport_bytes, dtype=torch.uint8, device="cuda")
+    placed = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")   # dedup state of the first pass
+    for ph, (first, second) in zip(w.phases, pairs):
+        gpu_lib.uccl_chunk_scatter_opts(transport, run.recv, to_dev(first), len(first), placed, opts=(arrival, 0))
+        gpu_lib.uccl_chunk_apply_opts(run.acc, run.out, transport, to_dev(second), len(second), run.bitmap, w.dtype,
+                                      ph.op, opts=(C, 0))
+    torch.cuda.synchronize()
+    acc, out, bm, _ = run.results()
+    assert_same(acc, eacc, "acc"); assert_same(out, eout, "out_stage")
+    assert sum(int(x).bit_count() for x in placed.cpu().numpy().view(np.uint32)) == w.n_bits
+    # the second pass dedups per collective chunk: one bit per group of arrivals
+    assert sum(int(x).bit_count() for x in bm) == w.n_bits // (C // arrival)
