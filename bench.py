@@ -11,10 +11,12 @@ is still in the 256 MB last-level cache when its turn comes again: the headline 
 an HBM number.  `--also-warm` adds the same loop over a single buffer set (`warm_cache`).
 
 Prints one JSON line: whole-job reduced-payload GB/s, the HBM-roofline fraction of the
-dominant kernel (algorithmic bytes / measured kernel time / 8 TB/s), and the CPU oracle
-timed on the host cores of the same machine as a reported baseline.
+dominant kernel (algorithmic bytes / measured kernel time / 8 TB/s), dense streaming kernels
+of the same traffic shape at the same footprint (`stream_ceiling`), and the CPU oracle timed
+on the host cores of the same machine as a reported baseline.
 """
 import argparse
+import ctypes
 import hashlib
 import json
 import os
@@ -28,17 +30,13 @@ PEAK_HBM_GBS = 8000.0  # MI355X published HBM3E peak, GB/s
 # adds a completion signal between kernels (about 5 us each), which would otherwise slow every step.
 EVENT_STRIDE = 4
 ROOT = os.path.dirname(os.path.abspath(__file__))
+METRIC = "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk stream), 1x MI355X"
 
-# HBM bytes per launch of the dominant kernel of config2 from rocprofv3 counters
-# (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, see profiles/): valid only for the kernel
-# source it was measured on, identified by the hash of the HIP source files.
+# HBM bytes per launch of the dominant kernel from rocprofv3 counters (FETCH_SIZE and WRITE_SIZE,
+# each scaled by what it reads for a plain copy of known size, see profiles/): valid only for the
+# kernel source it was measured on, identified by the hash of the HIP source files.
 MEASURED_TRAFFIC = {
     # (workload, source_hash() of the files under csrc/): bytes per launch
-    ("config2", "8426488e76ddd234"): 1008004812,
-    ("config3", "8426488e76ddd234"): 3625074368,
-    ("direct-rs", "8426488e76ddd234"): 1208242841,
-    ("config1", "8426488e76ddd234"): 14752659,
-    ("config4", "8426488e76ddd234"): 107503647,
 }
 
 WORKLOADS = {
@@ -54,6 +52,8 @@ WORKLOADS = {
                     "slot is handed to the GPU whenever the previous hand-over has finished (adaptive batching)",
     "config5-graph": "small allreduces, one message at a time: the control path rewrites a pinned descriptor "
                      "slot and replays a captured graph of the two calls (no per-message argument marshalling)",
+    "segment": "sender side: this rank's own segment of a ring (config2's shape: 16 MiB in 32 KiB chunks; config3's: "
+               "128 MiB in 128 KiB chunks) cut into staged chunks with send records",
 }
 
 
@@ -102,6 +102,14 @@ def call_stats(descs, op):
     reads = ln if op == 3 else 2 * ln
     algo = int(reads.sum() + ln[~relay].sum() + ln[fwd].sum()) + 36 * len(descs)
     return len(first), int(ln.sum()), algo
+
+
+def kernel_label(n_records, chunk_hint, gather):
+    """Which kernel the library launches for a call (the rule of launch_flat_tile in uccl_chunk.hip)."""
+    if gather:
+        return "chunk_gather_kernel"
+    tile = -(-32768 // chunk_hint) if chunk_hint else (1 if n_records < 8192 else 4)
+    return "chunk_few_kernel" if tile <= 1 and n_records < 512 else "chunk_flat_kernel"
 
 
 def two_pass_calls(w, chunk, group=1):
@@ -165,19 +173,88 @@ def build_job(name, seed, n_msgs, relay=False, per_call=128, packet_bytes=0):
     raise SystemExit(f"unknown workload {name}; choose from {sorted(WORKLOADS)}")
 
 
+def to_dev(torch, a, shift=0):
+    """Device copy of a numpy buffer as raw bytes, `shift` bytes into a larger allocation."""
+    flat = torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1))
+    if not shift:
+        return flat.cuda()
+    t = torch.empty(flat.numel() + shift, dtype=torch.uint8, device="cuda")[shift:]
+    t.copy_(flat)
+    return t
+
+
+def headline(workload, args, payload, seconds, steps, warmup, dtype, config):
+    """The fields every line carries; `seconds` is the time of one step."""
+    return {
+        "metric": METRIC, "value": round(payload / seconds / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
+        "steps": steps, "warmup": warmup, "ms_per_step": round(seconds * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": dtype, "data": "synthetic",
+        "config": {"workload": f"{workload}: {WORKLOADS[workload]}", "seed": args.seed, **config},
+    }
+
+
+def same_bytes(got, expected):
+    return all(np.array_equal(np.ascontiguousarray(g).view(np.uint8).reshape(-1),
+                              np.ascontiguousarray(e).view(np.uint8).reshape(-1)) for g, e in zip(got, expected))
+
+
+def finish(result, ok=True):
+    print(json.dumps(result))
+    if not ok:
+        sys.exit(1)
+
+
+# ---- small messages fed one at a time ------------------------------------------------------------
+
+def small_message_job(args, torch):
+    from synth import workloads as wl
+    w, msgs = wl.config5(seed=args.seed, n_msgs=args.messages)
+    acc, recv = to_dev(torch, w.acc), to_dev(torch, w.recv_stage)
+    out = torch.zeros(w.out_bytes, dtype=torch.uint8, device="cuda")
+    bitmap = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
+    return w, msgs, acc, recv, out, bitmap
+
+
+def small_message_result(name, args, w, msgs, per_msg, reps, first, extra_config):
+    """The JSON line of a one-message-at-a-time feed, with the oracle's single-core time over the
+    same messages and the parity of the first pass against it."""
+    from synth.layout import SUM, COPY, F32
+    payload = sum(m["payload_bytes"] for m in msgs)
+    unique = sum(m["n_unique"] for m in msgs)
+    algo = sum(m["algo_bytes"] for m in msgs)
+    step = per_msg * len(msgs)
+    result = headline(name, args, payload, step, reps, 1, "f32",
+                      dict(messages=len(msgs), unique_chunks=unique, payload_bytes=payload, algorithmic_bytes=algo,
+                           **extra_config))
+    result.update({"chunks_per_s": round(unique / step, 1), "us_per_message": round(per_msg * 1e6, 3),
+                   "step_hbm_frac": round(algo / step / 1e9 / PEAK_HBM_GBS, 4), "roofline": None})
+    ok = True
+    if not args.no_cpu_baseline:
+        import oracle
+        eacc, eout, seen = w.acc.copy(), np.zeros(w.out_bytes, dtype=np.uint8), oracle.new_seen(w.n_bits)
+        t0 = time.perf_counter()
+        for m in msgs:
+            oracle.apply(eacc, eout, w.recv_stage, m["rs"], seen, F32, SUM, check=False)
+            oracle.apply(eacc, eout, w.recv_stage, m["ag"], seen, F32, COPY, check=False)
+        cpu_t = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": round(payload / cpu_t / 1e9, 3), "unit": "GB/s", "cores": 1,
+                                  "kind": "oracle", "sample": f"all {len(msgs)} messages once, {cpu_t:.1f} s"}
+        ok = same_bytes(first, (eacc, eout, oracle.pack_bitmap(seen)))
+        result["parity_first_pass"] = "bit-exact vs oracle (acc, out_stage, bitmap)" if ok else "MISMATCH"
+    return result, ok
+
+
+def latency_us(samples):
+    return {"median": round(float(np.median(samples)) * 1e6, 2), "p99": round(float(np.percentile(samples, 99)) * 1e6, 2)}
+
+
 def bench_graph_feed(args, pkg, torch):
     """Small-message regime fed through descriptor slots: K pinned slots (records + counts for
     the two phases), one captured graph per slot.  Per message the host copies the records
     into the next slot and replays its graph; a slot is reused only after its previous replay
     has finished.  Also measures the host-observed completion latency of one message."""
-    from synth import workloads as wl
     from synth.layout import SUM, COPY, F32
-    import oracle
-    w, msgs = wl.config5(seed=args.seed, n_msgs=args.messages)
-    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1)).cuda()
-    acc, recv = dev(w.acc), dev(w.recv_stage)
-    out = torch.zeros(w.out_bytes, dtype=torch.uint8, device="cuda")
-    bitmap = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
+    w, msgs, acc, recv, out, bitmap = small_message_job(args, torch)
     cap = max(max(len(m["rs"]), len(m["ag"])) for m in msgs)
     K = 32
     slots = []
@@ -231,7 +308,7 @@ def bench_graph_feed(args, pkg, torch):
         slots[i % K]["done"].synchronize()
         lat.append(time.perf_counter() - t0)
     # the same with two eager calls per message and device-resident records
-    d_dev = [(dev(m["rs"]), dev(m["ag"])) for m in msgs[:300]]
+    d_dev = [(to_dev(torch, m["rs"]), to_dev(torch, m["ag"])) for m in msgs[:300]]
     lat_eager = []
     pkg.uccl_dedup_reset(bitmap, w.n_bits)
     torch.cuda.synchronize()
@@ -241,55 +318,16 @@ def bench_graph_feed(args, pkg, torch):
         pkg.uccl_chunk_apply(acc, out, recv, b, raw[i][3], bitmap, F32, COPY)
         torch.cuda.synchronize()
         lat_eager.append(time.perf_counter() - t0)
-
-    payload = sum(m["payload_bytes"] for m in msgs)
-    unique = sum(m["n_unique"] for m in msgs)
-    algo = sum(m["algo_bytes"] for m in msgs)
-    result = {
-        "metric": "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk stream), 1x MI355X",
-        "value": round(payload / (per_msg * len(msgs)) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
-        "steps": reps, "warmup": 1, "ms_per_step": round(per_msg * len(msgs) * 1e3, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"config5-graph: {WORKLOADS['config5-graph']}", "seed": args.seed,
-                   "messages": len(msgs), "unique_chunks": unique, "payload_bytes": payload,
-                   "algorithmic_bytes": algo, "slots": K, "slot_capacity_records": cap},
-        "chunks_per_s": round(unique / (per_msg * len(msgs)), 1),
-        "us_per_message": round(per_msg * 1e6, 3),
-        "completion_latency_us": {"graph_slot": {"median": round(float(np.median(lat)) * 1e6, 2),
-                                                 "p99": round(float(np.percentile(lat, 99)) * 1e6, 2)},
-                                  "two_eager_calls": {"median": round(float(np.median(lat_eager)) * 1e6, 2),
-                                                      "p99": round(float(np.percentile(lat_eager, 99)) * 1e6, 2)}},
-        "roofline": None,
-    }
-    if not args.no_cpu_baseline:
-        eacc, eout, seen = w.acc.copy(), np.zeros(w.out_bytes, dtype=np.uint8), oracle.new_seen(w.n_bits)
-        t0 = time.perf_counter()
-        for m in msgs:
-            oracle.apply(eacc, eout, w.recv_stage, m["rs"], seen, F32, SUM, check=False)
-            oracle.apply(eacc, eout, w.recv_stage, m["ag"], seen, F32, COPY, check=False)
-        cpu_t = time.perf_counter() - t0
-        result["cpu_baseline"] = {"value": round(payload / cpu_t / 1e9, 3), "unit": "GB/s", "cores": 1,
-                                  "kind": "oracle", "sample": f"all {len(msgs)} messages once, {cpu_t:.1f} s"}
-        same = all(np.array_equal(np.ascontiguousarray(g).view(np.uint8).reshape(-1),
-                                  np.ascontiguousarray(e).view(np.uint8).reshape(-1))
-                   for g, e in zip(first, (eacc, eout, oracle.pack_bitmap(seen))))
-        result["parity_first_pass"] = "bit-exact vs oracle (acc, out_stage, bitmap)" if same else "MISMATCH"
-        if not same:
-            print(json.dumps(result))
-            sys.exit(1)
-    print(json.dumps(result))
+    result, ok = small_message_result("config5-graph", args, w, msgs, per_msg, reps, first,
+                                      dict(slots=K, slot_capacity_records=cap))
+    result["completion_latency_us"] = {"graph_slot": latency_us(lat), "two_eager_calls": latency_us(lat_eager)}
+    finish(result, ok)
 
 
 def bench_feed(args, pkg, torch):
     """Small-message regime through uccl_feed: per message two pushes and a poll."""
-    from synth import workloads as wl
     from synth.layout import SUM, COPY, F32
-    import oracle
-    w, msgs = wl.config5(seed=args.seed, n_msgs=args.messages)
-    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1)).cuda()
-    acc, recv = dev(w.acc), dev(w.recv_stage)
-    out = torch.zeros(w.out_bytes, dtype=torch.uint8, device="cuda")
-    bitmap = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
+    w, msgs, acc, recv, out, bitmap = small_message_job(args, torch)
     feed = pkg.uccl_feed_create(acc, out, recv, bitmap, F32, SUM, COPY, 65536, 8)
     recs = [(np.ascontiguousarray(m["rs"]), np.ascontiguousarray(m["ag"])) for m in msgs]
 
@@ -320,45 +358,16 @@ def bench_feed(args, pkg, torch):
         pkg.uccl_feed_sync(feed)
         lat.append(time.perf_counter() - t0)
     pkg.uccl_feed_destroy(feed)
-    payload = sum(m["payload_bytes"] for m in msgs)
-    unique = sum(m["n_unique"] for m in msgs)
-    algo = sum(m["algo_bytes"] for m in msgs)
     flushes = (after["flushes"] - before["flushes"]) / reps
-    result = {
-        "metric": "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk stream), 1x MI355X",
-        "value": round(payload / (per_msg * len(msgs)) / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
-        "steps": reps, "warmup": 1, "ms_per_step": round(per_msg * len(msgs) * 1e3, 4),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"config5-feed: {WORKLOADS['config5-feed']}", "seed": args.seed,
-                   "messages": len(msgs), "unique_chunks": unique, "payload_bytes": payload,
-                   "algorithmic_bytes": algo, "slots": 8, "slot_capacity_records": 65536},
-        "chunks_per_s": round(unique / (per_msg * len(msgs)), 1),
-        "us_per_message": round(per_msg * 1e6, 3),
-        "step_hbm_frac": round(algo / (per_msg * len(msgs)) / 1e9 / PEAK_HBM_GBS, 4),
-        "feed": {"hand_overs_per_pass": round(flushes, 1), "messages_per_hand_over": round(len(msgs) / max(flushes, 1), 1),
-                 "largest_hand_over_records": after["max_batch"], "slot_waits": after["slot_waits"]},
-        "completion_latency_us": {"median": round(float(np.median(lat)) * 1e6, 2),
-                                  "p99": round(float(np.percentile(lat, 99)) * 1e6, 2)},
-        "roofline": None,
-    }
-    if not args.no_cpu_baseline:
-        eacc, eout, seen = w.acc.copy(), np.zeros(w.out_bytes, dtype=np.uint8), oracle.new_seen(w.n_bits)
-        t0 = time.perf_counter()
-        for m in msgs:
-            oracle.apply(eacc, eout, w.recv_stage, m["rs"], seen, F32, SUM, check=False)
-            oracle.apply(eacc, eout, w.recv_stage, m["ag"], seen, F32, COPY, check=False)
-        cpu_t = time.perf_counter() - t0
-        result["cpu_baseline"] = {"value": round(payload / cpu_t / 1e9, 3), "unit": "GB/s", "cores": 1,
-                                  "kind": "oracle", "sample": f"all {len(msgs)} messages once, {cpu_t:.1f} s"}
-        same = all(np.array_equal(np.ascontiguousarray(g).view(np.uint8).reshape(-1),
-                                  np.ascontiguousarray(e).view(np.uint8).reshape(-1))
-                   for g, e in zip(first, (eacc, eout, oracle.pack_bitmap(seen))))
-        result["parity_first_pass"] = "bit-exact vs oracle (acc, out_stage, bitmap)" if same else "MISMATCH"
-        if not same:
-            print(json.dumps(result))
-            sys.exit(1)
-    print(json.dumps(result))
+    result, ok = small_message_result("config5-feed", args, w, msgs, per_msg, reps, first,
+                                      dict(slots=8, slot_capacity_records=65536))
+    result["feed"] = {"hand_overs_per_pass": round(flushes, 1), "messages_per_hand_over": round(len(msgs) / max(flushes, 1), 1),
+                      "largest_hand_over_records": after["max_batch"], "slot_waits": after["slot_waits"]}
+    result["completion_latency_us"] = latency_us(lat)
+    finish(result, ok)
 
+
+# ---- single kernels ----------------------------------------------------------------------------
 
 def launch_time_us(pkg, torch, launch, reps=30, skip=5):
     """Median duration of one launch, from event pairs attached to the dispatch."""
@@ -390,24 +399,58 @@ def time_feedback_kernels(pkg, torch, bitmap, n_bits):
     return report_us, status_us
 
 
-def stream_ceilings(torch, nbytes=240 << 20, nsets=4, reps=20):
-    """The machine's own streaming rates beside the published peak: the framework's c = a and
-    c = a + b on buffers of the headline workload's order of size, rotating over nsets sets."""
-    def ceiling(fn, streams):
-        bufs = [[torch.empty(nbytes // 2, dtype=torch.bfloat16, device="cuda").normal_() for _ in range(3)]
-                for _ in range(nsets)]
+# name -> (mode id of the probe library, streams the shape touches)
+PROBE_MODES = {"read_1r": (0, 1), "write_1w": (1, 1), "copy_1r1w": (2, 2), "reduce_forward_2r2w": (3, 4),
+               "copy_forward_1r2w": (4, 3), "reduce_keep_2r1w": (5, 3)}
+
+
+def stream_ceilings(torch, sets, stream_bytes, block_bytes, gather_sources=0, reps=20):
+    """What the memory system of this GPU delivers for the data path's traffic shapes with nothing
+    in the way: dense kernels (no records, no dedup, no scatter; paper_2504_17307_amd/probe) over the
+    workload's own buffers, `stream_bytes` per stream (the dominant call's payload), one
+    `block_bytes` block per workgroup (the chunk), the same cache policies, rotating over the same
+    buffer sets.  GB/s over all streams a shape touches."""
+    from paper_2504_17307_amd.build import PROBE_LIB
+    if not os.path.exists(PROBE_LIB):
+        return {"error": f"{PROBE_LIB} is not built (python -m paper_2504_17307_amd.build)"}
+    fn = ctypes.CDLL(PROBE_LIB).uccl_probe_stream
+    fn.restype = ctypes.c_int
+    fn.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32,
+                   ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p]
+    modes = dict(PROBE_MODES)
+    if gather_sources:   # the multi-sender reduce: its sources are consecutive regions of recv_stage, no staging copy
+        modes = {f"gather_{gather_sources + 1}r1w": (6, gather_sources + 2), "read_1r": (0, 1)}
+        nbytes = min([stream_bytes] + [min(s["recv"].numel() // gather_sources, s["acc"].numel()) for s in sets])
+    elif min(s["out"].numel() for s in sets) < 2048:   # nothing is forwarded (all-to-all): slot -> destination only
+        modes = {k: PROBE_MODES[k] for k in ("read_1r", "write_1w", "copy_1r1w")}
+        nbytes = min([stream_bytes] + [min(s["recv"].numel(), s["acc"].numel()) for s in sets])
+    else:
+        nbytes = min([stream_bytes] + [min(s["recv"].numel(), s["acc"].numel(), s["out"].numel()) for s in sets])
+    nbytes -= nbytes % 2048
+    block = max(2048, block_bytes - block_bytes % 2048)
+    if nbytes < 2048:
+        return {"error": "buffers too small for the probe"}
+    stream = torch.cuda.current_stream().cuda_stream
+    out = {}
+    for name, (mode, n_streams) in modes.items():
+        def run(k):
+            s = sets[k % len(sets)]
+            stage = s["out"] if s["out"].numel() >= nbytes else s["acc"]   # no staging buffer: write the destination
+            rc = fn(mode, s["recv"].data_ptr(), s["acc"].data_ptr(), stage.data_ptr(), nbytes, block,
+                    gather_sources, None, stream)
+            assert rc == 0, f"probe mode {name} refused"
         for k in range(4):
-            fn(*bufs[k % nsets])
+            run(k)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         for k in range(reps):
-            fn(*bufs[k % nsets])
+            run(k)
         b.record()
         torch.cuda.synchronize()
-        return round(streams * nbytes * reps / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
-    return {"copy_1r1w_GBps": ceiling(lambda x, y, z: z.copy_(x), 2),
-            "add_2r1w_GBps": ceiling(lambda x, y, z: torch.add(x, y, out=z), 3),
-            "what": "torch copy_ and add on 240 MiB bf16 tensors rotating over 4 sets, same run"}
+        out[name + "_GBps"] = round(n_streams * nbytes * reps / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
+    out["what"] = (f"dense kernels of the path's traffic shapes: {nbytes} bytes per stream, {block}-byte block per "
+                   f"workgroup, the workload's own buffers rotating over {len(sets)} sets, same run")
+    return out
 
 
 def calibration_copy(torch):
@@ -419,7 +462,128 @@ def calibration_copy(torch):
     torch.cuda.synchronize()
 
 
-def main():
+def bench_segment(args, pkg, torch):
+    """Sender side: the rank's own segment cut into staged chunks with send records (the first hop
+    of a ring).  One step = one uccl_chunk_segment call; 1 byte read + 1 byte written per payload byte."""
+    import oracle
+    from synth import payload as pl
+    rows = {}
+    for shape, seg_bytes, chunk in (("config2", (256 << 20) // 16, 32 << 10), ("config3", (1 << 30) // 8, 128 << 10)):
+        n = seg_bytes // chunk
+        host = pl.rng(args.seed, 5).integers(0, 256, seg_bytes, dtype=np.uint8)
+        sets = [dict(t=to_dev(torch, host), stage=torch.zeros(seg_bytes, dtype=torch.uint8, device="cuda"),
+                     recs=torch.zeros(n * 16, dtype=torch.uint8, device="cuda")) for _ in range(max(1, args.sets))]
+
+        def step(k, sets=sets, seg_bytes=seg_bytes, chunk=chunk):
+            s = sets[k % len(sets)]
+            pkg.uccl_chunk_segment(s["stage"], s["t"], 0, seg_bytes, chunk, 0, chunk, s["recs"], 3, 0, 0)
+        step(0)
+        torch.cuda.synchronize()
+        exp = np.zeros(seg_bytes, dtype=np.uint8)
+        exp_d = oracle.segment(exp, host, 0, seg_bytes, chunk, conn_id=3)
+        ok = (np.array_equal(sets[0]["stage"].cpu().numpy(), exp) and
+              np.array_equal(sets[0]["recs"].cpu().numpy().view(oracle.SEND_DESC), exp_d))
+        for k in range(args.warmup):
+            step(k)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            step(k)
+        torch.cuda.synchronize()
+        per = (time.perf_counter() - t0) / args.steps
+        turn = [0]
+
+        def one():
+            turn[0] += 1
+            step(turn[0])
+        kernel_us = launch_time_us(pkg, torch, one)
+        algo = 2 * seg_bytes + 16 * n
+        rows[shape] = dict(segment_bytes=seg_bytes, chunk_bytes=chunk, chunks=n, ms_per_step=round(per * 1e3, 4),
+                           payload_GBps=round(seg_bytes / per / 1e9, 1), kernel_us=round(kernel_us, 2),
+                           kernel_hbm_frac=round(algo / (kernel_us * 1e-6) / 1e9 / PEAK_HBM_GBS, 4),
+                           parity="bit-exact vs oracle (staging, send records)" if ok else "MISMATCH")
+        del sets
+    big = rows["config3"]
+    result = headline("segment", args, big["segment_bytes"], big["ms_per_step"] * 1e-3, args.steps, args.warmup, "u8",
+                      dict(buffer_sets=max(1, args.sets)))
+    result["segments"] = rows
+    algo = 2 * big["segment_bytes"] + 16 * big["chunks"]
+    achieved = algo / (big["kernel_us"] * 1e-6) / 1e9
+    result["roofline"] = {"bound": "hbm", "kernel": "segment_kernel (config3's shape)", "achieved": round(achieved, 1),
+                          "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": None,
+                          "algorithmic_bytes_per_launch": algo, "avg_launch_ms": round(big["kernel_us"] * 1e-3, 5)}
+    finish(result, all(r["parity"] != "MISMATCH" for r in rows.values()))
+
+
+# ---- the CPU oracle beside it ----------------------------------------------------------------------
+
+def cpu_baselines(w, calls, payload, arrivals, first):
+    """The oracle as it stands on one host core (about 10 s of repetitions of the whole step) and,
+    for plain apply calls, the same definition dealt over the host cores; also the parity of the
+    GPU's first pass against the oracle's result.  Returns (fields to add to the line, parity ok)."""
+    import oracle
+    out = {}
+    reps, cpu_t, exp = 0, 0.0, None
+    while cpu_t < 10.0 and reps < 64:
+        eacc = w.acc.copy()
+        eout = np.zeros(max(w.out_bytes, 16), dtype=np.uint8)
+        seen = oracle.new_seen(w.n_bits)
+        t0 = time.perf_counter()
+        for c in calls:
+            if c.get("gather"):
+                oracle.reduce_gather(eacc, None, w.recv_stage, c["descs"], seen, w.dtype, c["op"])
+            elif c["scatter"]:
+                oracle.scatter(eacc.view(np.uint8), w.recv_stage, c["descs"], seen, check=False)
+            else:
+                oracle.apply(eacc, eout, w.recv_stage, c["descs"], seen, w.dtype, c["op"], check=False)
+        cpu_t += time.perf_counter() - t0
+        reps += 1
+        if exp is None:
+            exp = (eacc, eout[:w.out_bytes], oracle.pack_bitmap(seen))
+    out["cpu_baseline"] = {
+        "value": round(payload * reps / cpu_t / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+        "cpu": cpu_model(),
+        "sample": f"the whole step ({len(calls)} calls, {arrivals} arrivals, {payload} payload bytes) x {reps} repetitions, {cpu_t:.1f} s",
+    }
+    # the same definition on all host cores of this machine's share (serial dedup, then the unique
+    # chunks dealt to threads); reported beside the single-core figure, only for plain apply calls
+    if not any(c.get("gather") or c["scatter"] for c in calls):
+        threads = max(1, min(16, os.cpu_count() or 1))
+        reps_t, cpu_tt, same_t = 0, 0.0, True
+        while cpu_tt < 5.0 and reps_t < 64:
+            tacc = w.acc.copy()
+            tout = np.zeros(max(w.out_bytes, 16), dtype=np.uint8)
+            seen = oracle.new_seen(w.n_bits)
+            t0 = time.perf_counter()
+            for c in calls:
+                oracle.apply_threaded(tacc, tout, w.recv_stage, c["descs"], seen, w.dtype, c["op"], threads)
+            cpu_tt += time.perf_counter() - t0
+            reps_t += 1
+            if reps_t == 1:
+                same_t = (np.array_equal(tacc.view(np.uint8), exp[0].view(np.uint8)) and
+                          np.array_equal(tout[:w.out_bytes], exp[1]))
+        out["cpu_baseline_threaded"] = {
+            "value": round(payload * reps_t / cpu_tt / 1e9, 3), "unit": "GB/s", "cores": threads,
+            "kind": "oracle, unique chunks dealt to threads after a serial dedup pass",
+            "equals_single_core_result": bool(same_t),
+            "sample": f"the whole step x {reps_t} repetitions, {cpu_tt:.1f} s",
+        }
+    ok = same_bytes(first, exp)
+    out["parity_first_pass"] = "bit-exact vs oracle (acc, out_stage, bitmap)" if ok else "MISMATCH"
+    return out, ok
+
+
+def two_pass_parity(w, first):
+    """The two-pass mode's first pass against the oracle's single-pass definition (acc, out_stage)."""
+    import oracle
+    eacc, eout, seen = w.acc.copy(), np.zeros(max(w.out_bytes, 16), dtype=np.uint8), oracle.new_seen(w.n_bits)
+    for ph in w.phases:
+        oracle.apply(eacc, eout, w.recv_stage, ph.descs, seen, w.dtype, ph.op, check=False)
+    return (np.array_equal(first[0], eacc.view(np.uint8).reshape(-1)) and
+            np.array_equal(first[1], eout[:w.out_bytes]))
+
+
+def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
@@ -449,17 +613,30 @@ def main():
     ap.add_argument("--two-pass", action="store_true",
                     help="ring workloads: run the paper's literal two-pass form (scattered memcpy into a transport "
                          "buffer, then reduce) instead of the fused single pass, for comparison")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture each buffer set's step (reset + calls) in a HIP graph once and replay it: what a "
+                         "launch-bound caller does (no per-kernel timing; captured calls are never cut into parts)")
+    ap.add_argument("--stagger", type=int, default=0,
+                    help="place acc and out_stage 1 and 2 times this many bytes (a multiple of 256) into their "
+                         "allocations, to move the streams' relative alignment in the memory channels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ceilings", action="store_true", help="skip the dense streaming kernels")
     ap.add_argument("--also-warm", action="store_true",
                     help="additionally time the same loop over a single buffer set (cache-resident accumulator)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic that "
                          "hardware counters of the same run can be scaled by)")
-    args = ap.parse_args()
+    return ap.parse_args()
+
+
+def main():
+    args = parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: the path is measured as one GPU's share on one GPU; --gpus N>1 is not supported "
               "(the path shards as one independent rank per GPU, there is nothing to aggregate)", file=sys.stderr)
         sys.exit(2)
+    if args.stagger % 256:
+        raise SystemExit("--stagger must be a multiple of 256")
 
     import torch
     import paper_2504_17307_amd as pkg
@@ -471,6 +648,8 @@ def main():
         return bench_graph_feed(args, pkg, torch)
     if args.workload == "config5-feed":
         return bench_feed(args, pkg, torch)
+    if args.workload == "segment":
+        return bench_segment(args, pkg, torch)
     t0 = time.time()
     w, calls, chunk_bytes = build_job(args.workload, args.seed, args.messages, args.relay, args.messages_per_call,
                                       args.packet_bytes)
@@ -481,24 +660,20 @@ def main():
     transport_bytes = 0
     if args.two_pass:
         calls, transport_bytes = two_pass_calls(w, chunk_bytes, collective_chunk // chunk_bytes if args.packet_bytes else 1)
-        args.no_cpu_baseline = True  # the oracle defines the fused result; parity of this mode is checked below
     print(f"[bench] built {w.name} in {time.time() - t0:.1f}s: {w.note}", file=sys.stderr, flush=True)
 
-    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.uint8).reshape(-1)).cuda()
     sets = []
     for _ in range(max(1, args.sets)):
-        sets.append(dict(acc=dev(w.acc), recv=dev(w.recv_stage),
-                         out=torch.zeros(max(w.out_bytes, 16), dtype=torch.uint8, device="cuda"),
+        out = torch.zeros(max(w.out_bytes, 16) + 2 * args.stagger, dtype=torch.uint8, device="cuda")[2 * args.stagger:]
+        sets.append(dict(acc=to_dev(torch, w.acc, args.stagger), recv=to_dev(torch, w.recv_stage), out=out,
                          transport=torch.zeros(max(transport_bytes, 16), dtype=torch.uint8, device="cuda")))
     bitmap = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
     bitmap2 = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
-    descs = [dev(c["descs"]) for c in calls]
+    descs = [to_dev(torch, c["descs"]) for c in calls]
     counts = [len(c["descs"]) for c in calls]
-
     streams = [torch.cuda.Stream() for _ in range(args.streams)] if args.streams > 1 else None
 
     def call(i, s):
-        c = calls[i]
         if streams is not None:  # calls come in (reduce-scatter, allgather) pairs per batch
             with torch.cuda.stream(streams[(i // 2) % len(streams)]):
                 return call_on_current(i, s)
@@ -520,7 +695,8 @@ def main():
                 pkg.uccl_chunk_apply_opts(s["acc"], s["out"], s[c.get("src", "recv")], d, n, bm, w.dtype, c["op"],
                                           opts=opts)
 
-    def step(k, timed=None):
+    def issue(k, timed=None):
+        """Enqueue one step on buffer set k % len(sets)."""
         s = sets[k % len(sets)]
         if streams is not None:
             for st in streams:
@@ -538,21 +714,39 @@ def main():
             call(i, s)
 
     # one pass from the pristine state, kept for the parity check against the oracle
-    step(0)
+    issue(0)
     torch.cuda.synchronize()
     first = (sets[0]["acc"].cpu().numpy(), sets[0]["out"][:w.out_bytes].cpu().numpy(),
              bitmap.cpu().numpy().view(np.uint32))
 
+    graphs = None
+    if args.graph:
+        assert streams is None, "--graph and --streams do not combine"
+        graphs, side = [], torch.cuda.Stream()
+        for k in range(len(sets)):
+            g = torch.cuda.CUDAGraph()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.graph(g, stream=side):
+                issue(k)
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+    def step(k, timed=None):
+        if graphs is not None:
+            graphs[k % len(graphs)].replay()
+        else:
+            issue(k, timed)
+
     # Per-launch durations are taken INSIDE the timed steps (every EVENT_STRIDE-th one): a HIP
     # event pair, made and recorded once beforehand, is attached to the dispatch of the kernel on
-    # the stream it runs on (torch's current stream).  Workloads with many calls per step time the largest call
-    # of each op.
+    # the stream it runs on (torch's current stream).  Workloads with many calls per step time the
+    # largest call of each op.
     by_op = {}
     for i, c in enumerate(calls):
         if c["op"] not in by_op or c["algo_bytes"] > calls[by_op[c["op"]]]["algo_bytes"]:
             by_op[c["op"]] = i
     timed = {}
-    if streams is None and not args.records_per_call:
+    if streams is None and not args.records_per_call and graphs is None:
         for i in by_op.values():
             timed[i] = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
                         for _ in range((args.steps + EVENT_STRIDE - 1) // EVENT_STRIDE)]
@@ -562,8 +756,9 @@ def main():
     torch.cuda.synchronize()
 
     def timed_loop(n_sets, events=None):
-        nonlocal sets
-        keep, sets = sets, sets[:n_sets]
+        nonlocal sets, graphs
+        keep, keep_g = sets, graphs
+        sets, graphs = sets[:n_sets], (graphs[:n_sets] if graphs is not None else None)
         for k in range(args.warmup):
             step(k)
         torch.cuda.synchronize()
@@ -572,20 +767,21 @@ def main():
             step(k, events)
         torch.cuda.synchronize()
         el = time.perf_counter() - t0
-        sets = keep
+        sets, graphs = keep, keep_g
         return el
 
     elapsed = timed_loop(len(sets), timed)
     warm_elapsed = timed_loop(1) if (args.also_warm and len(sets) > 1) else None
-    if not timed:  # overlapping streams, or phases cut into several launches: no per-kernel attribution
+    if not timed:  # overlapping streams, graph replays, or phases cut into several launches: no per-kernel attribution
         timed = {i: [] for i in by_op.values()}
     kernels = []
     for i, evs in timed.items():
         t = np.array([a.elapsed_time(b) for a, b in evs]) if evs else np.array([float("nan")])
         c = calls[i]
         kernels.append(dict(call=c["name"], op=["SUM", "MAX", "MIN", "COPY"][c["op"]], records=counts[i],
-                            algorithmic_bytes=c["algo_bytes"], avg_ms=round(float(t.mean()), 5),
-                            median_ms=round(float(np.median(t)), 5), min_ms=round(float(t.min()), 5),
+                            algorithmic_bytes=c["algo_bytes"], payload_bytes=c["payload_bytes"],
+                            avg_ms=round(float(t.mean()), 5), median_ms=round(float(np.median(t)), 5),
+                            min_ms=round(float(t.min()), 5),
                             hbm_frac=round(c["algo_bytes"] / (t.mean() * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)))
     dom = max(kernels, key=lambda k: k["algorithmic_bytes"])
 
@@ -594,7 +790,12 @@ def main():
         return float(np.mean([a.elapsed_time(b) for a, b in evs])) if evs else 0.0
 
     report_us, status_us = time_feedback_kernels(pkg, torch, bitmap, w.n_bits)
-    stream_ceiling = stream_ceilings(torch)
+    timeouts = pkg.uccl_claim_timeouts()
+    stream_ceiling = None
+    if not args.no_ceilings:  # last: the dense kernels overwrite the accumulators and staging buffers
+        n_src = int(calls[0]["descs"]["n_src"].max()) if calls[0].get("gather") else 0
+        stream_ceiling = stream_ceilings(torch, sets, max(dom["payload_bytes"] // max(n_src, 1), 2048),
+                                         max(collective_chunk, 32 << 10), n_src)
     if args.calibration_copy:
         calibration_copy(torch)
 
@@ -608,27 +809,18 @@ def main():
     cache_note = ("buffers rotate over %d sets: HBM resident, not cache resident" % len(sets)
                   if (w.acc.nbytes + w.recv_stage.nbytes + w.out_bytes) * len(sets) > (1 << 30)
                   else "working set fits the 256 MB last-level cache: an effective, not an HBM, figure")
+    kernel_name = kernel_label(args.records_per_call or dom["records"], opts[0], calls[0].get("gather"))
 
-    result = {
-        "metric": "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk stream), 1x MI355X",
-        "value": round(payload / per_step / 1e9, 2),
-        "unit": "GB/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": round(per_step * 1e3, 4),
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "bf16" if w.dtype == 1 else "f32",
-        "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {WORKLOADS[args.workload]}", "seed": args.seed,
-                   "unique_chunks": unique, "arrivals": arrivals, "payload_bytes": payload,
-                   "algorithmic_bytes": algo, "parts": args.parts,
-                   "chunk_hint": opts[0], "buffer_sets": len(sets),
-                   "forward_only_intermediate_steps": bool(args.relay), "two_pass": bool(args.two_pass), "packet_bytes": args.packet_bytes or None,
-                   "calls_per_step": 1 + sum(-(-n // (args.records_per_call or max(n, 1))) for n in counts),
-                   "records_per_call": args.records_per_call or None, "streams": args.streams, "cache": cache_note},
+    result = headline(args.workload, args, payload, per_step, args.steps, args.warmup,
+                      {0: "f32", 1: "bf16", 2: "f16", 3: "i32"}[w.dtype],
+                      {"unique_chunks": unique, "arrivals": arrivals, "payload_bytes": payload,
+                       "algorithmic_bytes": algo, "parts": args.parts, "chunk_hint": opts[0], "buffer_sets": len(sets),
+                       "forward_only_intermediate_steps": bool(args.relay), "two_pass": bool(args.two_pass),
+                       "packet_bytes": args.packet_bytes or None, "graph_replay": bool(args.graph),
+                       "stagger_bytes": args.stagger or None,
+                       "calls_per_step": 1 + sum(-(-n // (args.records_per_call or max(n, 1))) for n in counts),
+                       "records_per_call": args.records_per_call or None, "streams": args.streams, "cache": cache_note})
+    result.update({
         "chunks_per_s": round(unique / per_step, 1),
         "arrivals_per_s": round(arrivals / per_step, 1),
         "step_hbm_frac": round(algo / per_step / 1e9 / PEAK_HBM_GBS, 4),
@@ -639,9 +831,8 @@ def main():
             "note": "same loop over one buffer set; the accumulator stays in the last-level cache"},
         "roofline": {
             "bound": "hbm",
-            "kernel": (f"chunk_gather_kernel, {dom['call']} call ({dom['op']})" if calls[0].get("gather") else
-                       f"chunk_flat_kernel, {dom['call']} call ({dom['op']})"),
-            "basis": "the dominant kernel's own duration" if per_kernel else "whole step (kernels of several streams overlap)",
+            "kernel": f"{kernel_name}, {dom['call']} call ({dom['op']})",
+            "basis": "the dominant kernel's own duration" if per_kernel else "whole step (no per-kernel attribution in this mode)",
             "achieved": round(achieved, 1),
             "peak": PEAK_HBM_GBS,
             "unit": "GB/s",
@@ -660,78 +851,23 @@ def main():
                          "what": "ack_report_kernel: cumulative ack, applied count, selective ranges"},
         "message_status": {"slots": 128, "bits_per_slot": 256, "median_us": round(status_us, 2),
                            "what": "message_status_kernel: per-slot cumulative point, applied count, completion"},
-    }
+        "claim_timeouts": timeouts,
+    })
     if args.workload.startswith("config5"):
         result["us_per_message"] = round(per_step * 1e6 / w.extra["n_msgs"], 3)
         result["config"]["messages"] = w.extra["n_msgs"]
 
+    ok = timeouts == 0
     if args.two_pass:
-        import oracle
-        eacc, eout, seen = w.acc.copy(), np.zeros(max(w.out_bytes, 16), dtype=np.uint8), oracle.new_seen(w.n_bits)
-        for ph in w.phases:
-            oracle.apply(eacc, eout, w.recv_stage, ph.descs, seen, w.dtype, ph.op, check=False)
-        same = (np.array_equal(first[0], eacc.view(np.uint8).reshape(-1)) and
-                np.array_equal(first[1], eout[:w.out_bytes]))
+        same = two_pass_parity(w, first)
         result["parity_first_pass"] = ("two-pass result bit-exact vs the oracle's single-pass definition (acc, out_stage)"
                                        if same else "MISMATCH")
-        if not same:
-            print(json.dumps(result))
-            sys.exit(1)
-    if not args.no_cpu_baseline:
-        import oracle
-        reps, cpu_t, exp = 0, 0.0, None
-        while cpu_t < 10.0 and reps < 64:
-            eacc = w.acc.copy()
-            eout = np.zeros(max(w.out_bytes, 16), dtype=np.uint8)
-            seen = oracle.new_seen(w.n_bits)
-            t0 = time.perf_counter()
-            for c in calls:
-                if c.get("gather"):
-                    oracle.reduce_gather(eacc, None, w.recv_stage, c["descs"], seen, w.dtype, c["op"])
-                elif c["scatter"]:
-                    oracle.scatter(eacc.view(np.uint8), w.recv_stage, c["descs"], seen, check=False)
-                else:
-                    oracle.apply(eacc, eout, w.recv_stage, c["descs"], seen, w.dtype, c["op"], check=False)
-            cpu_t += time.perf_counter() - t0
-            reps += 1
-            if exp is None:
-                exp = (eacc, eout[:w.out_bytes], oracle.pack_bitmap(seen))
-        result["cpu_baseline"] = {
-            "value": round(payload * reps / cpu_t / 1e9, 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
-            "cpu": cpu_model(),
-            "sample": f"the whole step ({len(calls)} calls, {arrivals} arrivals, {payload} payload bytes) x {reps} repetitions, {cpu_t:.1f} s",
-        }
-        # the same definition on all host cores of this machine's share (serial dedup, then the unique
-        # chunks dealt to threads); reported beside the single-core figure, only for plain apply calls
-        if not any(c.get("gather") or c["scatter"] for c in calls):
-            threads = max(1, min(16, os.cpu_count() or 1))
-            reps_t, cpu_tt, same_t = 0, 0.0, True
-            while cpu_tt < 5.0 and reps_t < 64:
-                tacc = w.acc.copy()
-                tout = np.zeros(max(w.out_bytes, 16), dtype=np.uint8)
-                seen = oracle.new_seen(w.n_bits)
-                t0 = time.perf_counter()
-                for c in calls:
-                    oracle.apply_threaded(tacc, tout, w.recv_stage, c["descs"], seen, w.dtype, c["op"], threads)
-                cpu_tt += time.perf_counter() - t0
-                reps_t += 1
-                if reps_t == 1:
-                    same_t = (np.array_equal(tacc.view(np.uint8), exp[0].view(np.uint8)) and
-                              np.array_equal(tout[:w.out_bytes], exp[1]))
-            result["cpu_baseline_threaded"] = {
-                "value": round(payload * reps_t / cpu_tt / 1e9, 3), "unit": "GB/s", "cores": threads,
-                "kind": "oracle, unique chunks dealt to threads after a serial dedup pass",
-                "equals_single_core_result": bool(same_t),
-                "sample": f"the whole step x {reps_t} repetitions, {cpu_tt:.1f} s",
-            }
-        same = all(np.array_equal(np.ascontiguousarray(g).view(np.uint8).reshape(-1),
-                                  np.ascontiguousarray(e).view(np.uint8).reshape(-1))
-                   for g, e in zip(first, exp))
-        result["parity_first_pass"] = "bit-exact vs oracle (acc, out_stage, bitmap)" if same else "MISMATCH"
-        if not same:
-            print(json.dumps(result))
-            sys.exit(1)
-    print(json.dumps(result))
+        ok = ok and same
+    elif not args.no_cpu_baseline:
+        extra, same = cpu_baselines(w, calls, payload, arrivals, first)
+        result.update(extra)
+        ok = ok and same
+    finish(result, ok)
 
 
 if __name__ == "__main__":

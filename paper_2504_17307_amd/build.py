@@ -9,6 +9,9 @@ CSRC = os.path.join(PKG, "csrc")
 SRC = os.path.join(CSRC, "uccl_chunk.hip")  # the one translation unit; it includes the .hpp files beside it
 INC = os.path.join(ROOT, "include")
 LIB = os.path.join(PKG, "libuccl_chunk.so")
+# measurement aid of bench.py (dense streaming kernels), a library of its own
+PROBE_SRC = os.path.join(PKG, "probe", "stream_probe.hip")
+PROBE_LIB = os.path.join(PKG, "probe", "libuccl_probe.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
@@ -36,5 +39,17 @@ def build(extra_flags=(), out=LIB, verbose=False) -> str:
     return out
 
 
+def build_probe(verbose=False) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = PROBE_LIB + f".tmp{os.getpid()}"
+    cmd = [hipcc, *HIPCC_FLAGS, PROBE_SRC, "-o", tmp]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    os.replace(tmp, PROBE_LIB)
+    return PROBE_LIB
+
+
 if __name__ == "__main__":
     print(build(sys.argv[1:], verbose=True))
+    print(build_probe(verbose=True))

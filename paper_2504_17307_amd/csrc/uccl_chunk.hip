@@ -219,12 +219,15 @@ constexpr uint32_t kFewRecords = 512;
 // Payload bytes per stream that one part's wavefronts take in their first, eagerly loaded trip.
 constexpr uint32_t kPartBytes = UCCL_PART_THREADS * UCCL_PART_UNROLL * 16u;
 
-// Workgroups per record for a call of few single-record tiles: as many as it takes to put about
-// 512 workgroups on the machine, at most 8, and no more than the chunk has trips for.  Parts
-// that find no unit in a shorter record leave at once, so a generous count costs little.
+// Workgroups per record for a call of few single-record tiles.  Cutting pays when the records
+// alone leave more than half of the compute units idle (measured: 57 records of 64 KiB run 1.4x
+// faster in 8 parts, 256 records of 32 KiB 7 % slower in 2): up to 128 records are cut, into as
+// many parts as keep the launch within 512 workgroups, at most 8, and no more than the chunk has
+// trips for.  Parts that find no unit in a shorter record leave at once.
 uint32_t auto_parts(uint32_t n_descs, uint32_t chunk_bytes) {
+  if (n_descs > 128u) return 1u;
   uint32_t parts = 1u;
-  while (parts < 8u && n_descs * parts * 2u <= kFewRecords) parts *= 2u;
+  while (parts < 8u && n_descs * parts * 2u <= 512u) parts *= 2u;
   if (chunk_bytes)
     while (parts > 1u && (parts - 1u) * kPartBytes >= chunk_bytes) parts /= 2u;
   return parts;
