@@ -73,7 +73,7 @@ typedef enum uccl_op {
 
 enum {
   UCCL_OK = 0,
-  UCCL_EINVAL = -1,  /* null pointer with n_descs > 0, unknown dtype/op/shape, aliasing buffers */
+  UCCL_EINVAL = -1,  /* null pointer with n_descs > 0, unknown dtype/op, bad launch options, aliasing buffers */
   UCCL_EALIGN = -2,  /* a base pointer is not 16-byte aligned (bitmap / counter: 4-byte) */
   UCCL_ELAUNCH = -3, /* HIP refused the launch; uccl_last_error_detail() has HIP's message */
   UCCL_ENOMEM = -4,  /* uccl_feed_create / uccl_init could not get host, pinned or device memory */

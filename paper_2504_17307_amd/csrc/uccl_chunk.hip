@@ -19,6 +19,14 @@
 // combines, then stores, and the workgroup retires.  Duplicates cost their record and one
 // atomic, nothing else.  Two lanes holding the same seq each issue their own atomic, so
 // the hardware serialises them and exactly one sees the bit clear.
+//
+// Calls of few records (Appendix C.4: small messages are where fixed costs show) take another
+// kernel, which shortens the chain of latencies instead: one record per workgroup, payload
+// loads issued before the sequence number is decided, and, when the records alone would leave
+// most compute units idle, each record cut into parts over several workgroups that agree on
+// its fate through a claim word in scratch memory (uccl_data_kernels.hpp).  The sender side
+// (tensor range -> staged chunks + send records) and the feedback kernels (acknowledgement
+// report, per-message status) are dense, small kernels of their own.
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 

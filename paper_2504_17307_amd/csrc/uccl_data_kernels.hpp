@@ -14,7 +14,7 @@
 #define UCCL_GATHER_BATCH 4   // and how many sources are loaded before the folds start
 #endif
 #ifndef UCCL_FLAT_THREADS
-#define UCCL_FLAT_THREADS 1024  // workgroup size of the flat shape
+#define UCCL_FLAT_THREADS 1024  // workgroup size of chunk_flat_kernel
 #endif
 #ifndef UCCL_FLAT_UNROLL
 #define UCCL_FLAT_UNROLL 2    // vectors per lane per unit: a unit is 64*U*16 bytes per stream
@@ -144,7 +144,7 @@ __device__ __forceinline__ bool record_ok(const Args& g, uint64_t src, uint64_t 
 }
 
 // Winners of one tile of records, compacted; first[] is the exclusive prefix sum of
-// their unit counts (flat shape only) with the total in first[count].
+// their unit counts with the total in first[count].
 template <int T>
 struct Tile {
   uint64_t src[T], dst[T], out[T];
@@ -409,7 +409,7 @@ __global__ void __launch_bounds__(NT) chunk_few_kernel(const Args g) {
 // destination chunk; they are folded into the accumulator's value in the order listed, so
 // the floating-point result is fixed by the record, not by arrival timing.  The accumulator
 // is read and written once per chunk however many sources there are.  Same tile / unit
-// dealing as the flat shape; per unit a wavefront keeps the running value in registers
+// dealing as chunk_flat_kernel; per unit a wavefront keeps the running value in registers
 // (widened to binary32 for 16-bit types); sources are loaded in batches, all loads of a
 // batch in flight before the folds, which then run in the listed order.
 struct GatherArgs {
