@@ -861,3 +861,22 @@ def test_two_pass_form_equals_the_single_pass_definition(gpu_lib, packet_bytes):
     assert sum(int(x).bit_count() for x in placed.cpu().numpy().view(np.uint32)) == w.n_bits
     # the second pass dedups per collective chunk: one bit per group of arrivals
     assert sum(int(x).bit_count() for x in bm) == w.n_bits // (C // arrival)
+
+
+def test_more_streams_than_claim_regions(gpu_lib):
+    """The claim pool has one region per stream for 64 streams; a call on a stream that finds none is
+    launched with one workgroup per record instead.  80 streams, each with a call of few large
+    records on buffers of its own: every result is the oracle's."""
+    w = wl.ring_share("regions", 61, R=4, M=4 * 6 * (48 << 10), C=48 << 10, dtype=F32, paths=3, window=None, dup=0.1,
+                      dist="uniform", allgather=False)
+    eacc, eout, ebm = oracle_results(w)
+    streams = [torch.cuda.Stream() for _ in range(80)]
+    runs = [DeviceRun(w, opts=(48 << 10, 4)) for _ in streams]
+    torch.cuda.synchronize()
+    for s, run in zip(streams, runs):
+        run.apply(run.descs[0], len(w.phases[0].descs), SUM, checked=False, stream=s)
+    torch.cuda.synchronize()
+    assert gpu_lib.uccl_claim_timeouts() == 0
+    for k, run in enumerate(runs):
+        acc, out, bm, _ = run.results()
+        assert_same(acc, eacc, f"acc, stream {k}"); assert_same(out, eout, f"out, stream {k}"); assert_same(bm, ebm, f"bitmap {k}")
