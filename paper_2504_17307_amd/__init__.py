@@ -163,13 +163,20 @@ def _extents(extents, acc, out_stage, recv_stage, n_bits):
     return uccl_extents(_nbytes(acc), _nbytes(out_stage), _nbytes(recv_stage), int(n_bits))
 
 
+_opts_cache = {}
+
+
 def _opts(opts):
     """None, a uccl_launch_opts, or a (chunk_bytes, parts) pair -> a pointer argument."""
     if opts is None:
         return None
-    if not isinstance(opts, uccl_launch_opts):
-        opts = uccl_launch_opts(int(opts[0]), int(opts[1]))
-    return C.byref(opts)
+    if isinstance(opts, uccl_launch_opts):
+        return C.byref(opts)
+    key = (int(opts[0]), int(opts[1]))
+    ref = _opts_cache.get(key)
+    if ref is None:
+        ref = _opts_cache[key] = C.byref(uccl_launch_opts(*key))   # byref keeps the struct alive
+    return ref
 
 
 def uccl_chunk_apply(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, stream=None):

@@ -31,7 +31,7 @@ struct AckHeader {
   uint64_t reserved;
 };
 
-constexpr int kAckBatch = 6;          // steps whose loads are issued together
+constexpr int kAckBatch = 12;         // steps whose loads are issued together (1.5 M bits in one go)
 constexpr uint32_t kAckStep = 256;    // words per wavefront and step
 
 // Words w .. w+3 (0 for words at and beyond n_words); `aligned`: the bitmap starts on a 16-byte
@@ -63,13 +63,17 @@ struct AckQuad {
 
 // raw: the lane's words w4 .. w4+3; before: the word just below the step (0 if none); after: the
 // word just above it (0 if none).  Neighbouring lanes exchange their edge words by shuffle.
+// FULL: every word of the step lies wholly inside the bitmap (all steps but the last of a bitmap):
+// no masks to compute.  The whole workgroup's arithmetic runs on one compute unit, so the walk is
+// bound by instructions per word, not by memory.
+template <bool FULL>
 __device__ __forceinline__ AckQuad ack_quad(uint4 raw, uint64_t w4, uint64_t n_bits, uint32_t before,
                                             uint32_t after, uint32_t lane) {
   AckQuad q;
   const uint32_t in[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
-    q.mask[j] = ack_mask(w4 + j, n_bits);
+    q.mask[j] = FULL ? ~0u : ack_mask(w4 + j, n_bits);
     q.word[j] = in[j] & q.mask[j];
   }
   uint32_t below = __shfl_up(q.word[3], 1, 64);   // the word under this lane's first
@@ -107,8 +111,9 @@ __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __rest
   // beyond the last word of the bitmap a masked word is 0, so the last run ends at n_bits by itself
   const uint32_t seg_before = (w_lo > 0 && w_lo < n_words) ? bitmap[w_lo - 1] : 0u;
 
-  uint32_t my_starts = 0, my_ends = 0;
-  unsigned long long my_applied = 0, my_first_clear = ~0ull;
+  uint32_t my_starts = 0, my_ends = 0, my_applied = 0;
+  unsigned long long my_first_clear = ~0ull;
+  bool found = false;
   uint32_t before = seg_before;
   for (uint64_t wb = w_lo; wb < w_hi; wb += kAckStep * kAckBatch) {
     uint4 raw[kAckBatch];
@@ -117,25 +122,39 @@ __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __rest
     for (int i = 0; i < kAckBatch; ++i) {
       const uint64_t w0 = wb + static_cast<uint64_t>(i) * kAckStep;  // wavefront-uniform
       raw[i] = ack_load4(bitmap, w0 + 4 * lane, w0 < w_hi ? n_words : 0, aligned);
-      after[i] = (w0 < w_hi && w0 + kAckStep < n_words) ? bitmap[w0 + kAckStep] : 0u;
     }
+#pragma unroll
+    for (int i = 0; i < kAckBatch; ++i) {  // the word just above step i: the next step's first, if this batch holds it
+      const uint64_t up = wb + static_cast<uint64_t>(i + 1) * kAckStep;
+      if (i + 1 < kAckBatch && up < w_hi) after[i] = __shfl(raw[i + 1 < kAckBatch ? i + 1 : i].x, 0, 64);
+      else after[i] = (up - kAckStep < w_hi && up < n_words) ? bitmap[up] : 0u;
+    }
+    uint32_t my_edges = 0;  // this batch's run starts in the low half, run ends in the high half (<= 64 each per step)
 #pragma unroll
     for (int i = 0; i < kAckBatch; ++i) {
       const uint64_t w0 = wb + static_cast<uint64_t>(i) * kAckStep;
       if (w0 < w_hi) {  // else the batch reaches past the wavefront's words (uniform)
         const uint64_t w4 = w0 + 4 * lane;
-        const AckQuad q = ack_quad(raw[i], w4, n_bits, before, after[i], lane);
+        const bool full = (w0 + kAckStep) * 32 <= n_bits;  // uniform
+        const AckQuad q = full ? ack_quad<true>(raw[i], w4, n_bits, before, after[i], lane)
+                               : ack_quad<false>(raw[i], w4, n_bits, before, after[i], lane);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          my_starts += __popc(q.starts[j]);
-          my_ends += __popc(q.ends[j]);
+          my_edges += __popc(q.starts[j]) + (static_cast<uint32_t>(__popc(q.ends[j])) << 16);
           my_applied += __popc(q.word[j]);
-          const uint32_t clear = ~q.word[j] & q.mask[j];
-          if (clear != 0u && my_first_clear == ~0ull) my_first_clear = (w4 + j) * 32 + (__ffs(clear) - 1);  // ascending per lane
+        }
+        if (!found) {  // the lane's words ascend, so its first clear bit is the first it meets
+#pragma unroll
+          for (int j = 3; j >= 0; --j) {
+            const uint32_t clear = ~q.word[j] & q.mask[j];
+            if (clear != 0u) { my_first_clear = (w4 + j) * 32 + (__ffs(clear) - 1); found = true; }
+          }
         }
         before = __shfl(q.word[3], 63, 64);  // the step's last word
       }
     }
+    my_starts += my_edges & 0xFFFFu;
+    my_ends += my_edges >> 16;
   }
   my_starts = wave_sum(my_starts);
   my_ends = wave_sum(my_ends);
@@ -184,14 +203,19 @@ __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __rest
     for (int i = 0; i < kAckBatch; ++i) {
       const uint64_t w0 = wb + static_cast<uint64_t>(i) * kAckStep;
       raw[i] = ack_load4(bitmap, w0 + 4 * lane, w0 < w_hi ? n_words : 0, aligned);
-      after[i] = (w0 < w_hi && w0 + kAckStep < n_words) ? bitmap[w0 + kAckStep] : 0u;
+    }
+#pragma unroll
+    for (int i = 0; i < kAckBatch; ++i) {  // the word just above step i: the next step's first, if this batch holds it
+      const uint64_t up = wb + static_cast<uint64_t>(i + 1) * kAckStep;
+      if (i + 1 < kAckBatch && up < w_hi) after[i] = __shfl(raw[i + 1 < kAckBatch ? i + 1 : i].x, 0, 64);
+      else after[i] = (up - kAckStep < w_hi && up < n_words) ? bitmap[up] : 0u;
     }
 #pragma unroll
     for (int i = 0; i < kAckBatch; ++i) {
       const uint64_t w0 = wb + static_cast<uint64_t>(i) * kAckStep;
       if (w0 >= w_hi) continue;
       const uint64_t w4 = w0 + 4 * lane;
-      const AckQuad q = ack_quad(raw[i], w4, n_bits, before, after[i], lane);
+      const AckQuad q = ack_quad<false>(raw[i], w4, n_bits, before, after[i], lane);
       before = __shfl(q.word[3], 63, 64);
       // starts in the low half, ends in the high half: at most 64 of each per lane, 4096 per step
       uint32_t mine = 0;
