@@ -133,9 +133,9 @@ typedef struct uccl_launch_opts {
  *
  * Scratch memory.  A call of fewer than 512 records, each the only record of its workgroup, is
  * launched with several workgroups per record so that it fills the machine; those workgroups
- * agree on the record's fate through one 64-bit claim word per record in a pool the library
- * allocates once per device (1 MiB + 8 bytes, hipMalloc at the first such call or in
- * uccl_init, kept until the process ends).  If the pool cannot be had, or the stream is being
+ * agree on the record's fate through one 64-bit claim word per record (on a 128-byte line of its
+ * own) in a pool the library allocates once per device (16 MiB + 8 bytes, hipMalloc at the first
+ * such call or in uccl_init, kept until the process ends).  If the pool cannot be had, or the stream is being
  * captured into a graph, the call is launched with one workgroup per record instead: slower,
  * same result.  Apart from that one-time allocation no data-path call allocates.
  */
@@ -153,8 +153,8 @@ int uccl_init(void);
  * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
  * operation and result; the claim words of records cut into parts (see "Scratch memory" above)
  * live in an array inside the library's code object instead of the pool: UCCL_NOALLOC_MAX_DESCS
- * 64-bit words + 256 bytes = 16.25 KiB, held by every GPU the library runs on until the process
- * ends.  The call makes no hipMalloc / hipFree and creates no pool; the first call on a device
+ * lines of 128 bytes + 256 bytes = 256.25 KiB, held by every GPU the library runs on until the
+ * process ends.  The call makes no hipMalloc / hipFree and creates no pool; the first call on a device
  * (or uccl_init) looks the array's device address up.
  *   - n_descs > UCCL_NOALLOC_MAX_DESCS returns UCCL_ETOOBIG and enqueues nothing.  (Calls that
  *     large are never cut into parts, so uccl_chunk_apply serves them without any scratch memory.)

@@ -46,11 +46,12 @@
 #include "uccl_data_kernels.hpp"
 #include "uccl_feedback_kernels.hpp"
 
-// Claim words for uccl_chunk_apply_noalloc (see claim_record): UCCL_NOALLOC_MAX_DESCS words, one
-// per record of a call, then the word that counts parts that gave up waiting.  Every GPU the
+// Claim words for uccl_chunk_apply_noalloc (see claim_enter): one per record of a call, each on a
+// 128-byte line of its own, UCCL_NOALLOC_MAX_DESCS of them, then the word that counts parts that
+// gave up waiting: 256.25 KiB.  Every GPU the
 // library runs on holds its own copy at its own address until the process ends.  In host code
 // this name only stands for the symbol: the device address is looked up per device (static_claims).
-static __device__ __align__(256) unsigned long long scratch[UCCL_NOALLOC_MAX_DESCS + 32];
+static __device__ __align__(256) unsigned long long scratch[UCCL_NOALLOC_MAX_DESCS * UCCL_CLAIM_STRIDE + 32];
 
 namespace {
 
@@ -93,14 +94,21 @@ uint32_t tiles_for(uint32_t n_descs, uint32_t tile) {
 
 // ---- claim words for records cut into parts ---------------------------------------------------
 //
-// Scratch memory of the split launch (see claim_record): one 64-bit word per record of the call.
-// The library owns one pool per device, made at the first call that needs it (or by uccl_init)
-// and kept until the process ends: kRegions regions of kRegionWords words, one region per stream
+// Scratch memory of the split launch (see claim_enter): one 64-bit word per record of the call,
+// on a 128-byte line of its own.  The library owns one pool per device (16 MiB), made at the first
+// call that needs it (or by uccl_init) and kept until the process ends: kRegions regions for
+// kRegionRecords records each, one region per stream
 // handle that has issued a split call.  Calls on one stream run in order, so they can share a
 // region; calls on different streams may overlap, so they never do.  A call whose stream finds
 // no free region, or that is being captured into a graph (a replay would carry the captured tag
 // again, and could overlap with anything), is launched with one workgroup per record.
-constexpr uint32_t kRegionWords = 2048;  // most records a split call can have
+//
+// Tags must grow in the order in which the calls that share a word run.  They come from one
+// process-wide counter, and a split call draws its tag and enqueues its launch while holding the
+// device's launch lock, so on any one stream the later launch always carries the larger tag, also
+// when several host threads issue calls on that stream.
+constexpr uint32_t kRegionRecords = 2048;  // most records a split call can have
+constexpr uint32_t kRegionWords = kRegionRecords * UCCL_CLAIM_STRIDE;
 constexpr uint32_t kRegions = 64;
 constexpr int kMaxDevices = 64;
 constexpr size_t kPoolBytes = sizeof(unsigned long long) * kRegions * kRegionWords + 8;  // + fault counter
@@ -108,6 +116,7 @@ constexpr size_t kPoolBytes = sizeof(unsigned long long) * kRegions * kRegionWor
 struct ClaimPool {
   std::atomic<unsigned long long*> base{nullptr};
   std::mutex lock;                       // guards creation and the stream table's growth
+  std::mutex launch_lock;                // held from drawing a tag until its launch is enqueued
   std::atomic<uint32_t> n_streams{0};
   std::atomic<uintptr_t> stream_of[kRegions];
 };
@@ -137,7 +146,7 @@ uint32_t* pool_faults(unsigned long long* base) {
 }
 
 // The claim region of `stream` on the current device, or nullptr (then the call is not split).
-unsigned long long* claim_region(hipStream_t stream, uint32_t** faults) {
+unsigned long long* claim_region(hipStream_t stream, uint32_t** faults, ClaimPool** pool) {
   int dev = 0;
   if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { (void)hipGetLastError(); return nullptr; }
   hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
@@ -164,6 +173,7 @@ unsigned long long* claim_region(hipStream_t stream, uint32_t** faults) {
     }
   }
   *faults = pool_faults(base);
+  *pool = &p;
   return base + static_cast<size_t>(at) * kRegionWords;
 }
 
@@ -253,14 +263,14 @@ int launch_flat_tile(Args& a, hipStream_t s, const Tuning& tune) {
   if (parts > 1u && tune.static_claims != nullptr && a.n_descs <= UCCL_NOALLOC_MAX_DESCS) {
     // Every call shares the device's one array, which keeps what the last call (or the last replay
     // of this very launch) left in it: clear this call's words first, with a fill kernel (no memset
-    // node, so that the pair can be captured), then launch with a tag the cleared words cannot carry.
+    // node, so that the pair can be captured), then launch with a tag larger than a cleared word's.
     a.claims = tune.static_claims;
-    a.faults = reinterpret_cast<uint32_t*>(tune.static_claims + UCCL_NOALLOC_MAX_DESCS);
+    a.faults = reinterpret_cast<uint32_t*>(tune.static_claims + UCCL_NOALLOC_MAX_DESCS * UCCL_CLAIM_STRIDE);
     a.tag = 1ull;
     a.parts = parts;
     const hipEvent_t keep0 = t_start, keep1 = t_stop;  // the timing events belong to the data kernel
     t_start = t_stop = nullptr;
-    const uint64_t words = 2ull * a.n_descs;
+    const uint64_t words = 2ull * a.n_descs * UCCL_CLAIM_STRIDE;
     const int rc = launch_kernel(fill_words_kernel, static_cast<uint32_t>((words + 255) / 256), 256, s,
                                  reinterpret_cast<uint32_t*>(a.claims), words, 0u);
     t_start = keep0;
@@ -269,9 +279,11 @@ int launch_flat_tile(Args& a, hipStream_t s, const Tuning& tune) {
     return launch_kernel(chunk_few_kernel<UCCL_PART_THREADS, UCCL_PART_UNROLL, Op, true>, a.n_descs * parts,
                          UCCL_PART_THREADS, s, a);
   }
-  if (parts > 1u && tune.static_claims == nullptr && a.n_descs <= kRegionWords) {
-    a.claims = claim_region(s, &a.faults);
+  if (parts > 1u && tune.static_claims == nullptr && a.n_descs <= kRegionRecords) {
+    ClaimPool* pool = nullptr;
+    a.claims = claim_region(s, &a.faults, &pool);
     if (a.claims != nullptr) {
+      std::lock_guard<std::mutex> in_order(pool->launch_lock);
       a.tag = g_next_tag.fetch_add(1, std::memory_order_relaxed);
       a.parts = parts;
       return launch_kernel(chunk_few_kernel<UCCL_PART_THREADS, UCCL_PART_UNROLL, Op, true>, a.n_descs * parts,
@@ -747,7 +759,7 @@ int uccl_claim_timeouts(uint64_t* count) {
   unsigned long long* fixed = g_static_claims[dev].load(std::memory_order_acquire);
   if (fixed != nullptr) {
     uint32_t n = 0;
-    const hipError_t e = hipMemcpy(&n, fixed + UCCL_NOALLOC_MAX_DESCS, sizeof(n), hipMemcpyDeviceToHost);
+    const hipError_t e = hipMemcpy(&n, fixed + UCCL_NOALLOC_MAX_DESCS * UCCL_CLAIM_STRIDE, sizeof(n), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return launch_failed(e);
     total += n;
   }

@@ -880,3 +880,40 @@ def test_more_streams_than_claim_regions(gpu_lib):
     for k, run in enumerate(runs):
         acc, out, bm, _ = run.results()
         assert_same(acc, eacc, f"acc, stream {k}"); assert_same(out, eout, f"out, stream {k}"); assert_same(bm, ebm, f"bitmap {k}")
+
+
+def test_cut_records_from_several_host_threads_on_one_stream(gpu_lib):
+    """Four host threads issue calls of few large records (each cut into parts) on ONE stream at the
+    same time, each thread on buffers of its own.  The calls share the stream's claim words, and a
+    part recognises its own call by a tag that must grow in the order the calls run: tags are drawn
+    and launches enqueued under one lock, so no part ever waits for a tag that has been passed."""
+    import threading
+    w = wl.ring_share("threads", 71, R=4, M=4 * 9 * (40 << 10), C=40 << 10, dtype=F32, paths=3, window=None,
+                      dup=0.15, dist="uniform", allgather=False)
+    eacc, eout, ebm = oracle_results(w)
+    stream = torch.cuda.Stream()
+    n_threads, rounds = 4, 25
+    runs = [[DeviceRun(w, opts=(40 << 10, 4)) for _ in range(rounds)] for _ in range(n_threads)]
+    torch.cuda.synchronize()
+    errors = []
+
+    def issue(mine):
+        try:
+            torch.cuda.set_device(0)
+            for run in mine:
+                run.apply(run.descs[0], len(w.phases[0].descs), SUM, checked=False, stream=stream)
+        except Exception as e:  # noqa: BLE001 - reported by the main thread
+            errors.append(e)
+    threads = [threading.Thread(target=issue, args=(r,)) for r in runs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    stream.synchronize()
+    assert not errors, errors
+    assert gpu_lib.uccl_claim_timeouts() == 0
+    for a, mine in enumerate(runs):
+        for b, run in enumerate(mine):
+            acc, out, bm, _ = run.results()
+            assert_same(acc, eacc, f"acc, thread {a} call {b}"); assert_same(out, eout, f"out, thread {a} call {b}")
+            assert_same(bm, ebm, f"bitmap, thread {a} call {b}")
