@@ -131,8 +131,9 @@ typedef struct uccl_launch_opts {
  * per 1..32 records; a record count whose workgroup count exceeds what the device accepts
  * in one launch comes back as UCCL_ELAUNCH (split the call).
  *
- * Scratch memory.  A call of fewer than 512 records, each the only record of its workgroup, is
- * launched with several workgroups per record so that it fills the machine; those workgroups
+ * Scratch memory.  A call of few large records (at most 16 MiB of payload in chunks above 32 KiB, or at
+ * most 32 chunks of 32 KiB; at most 128 records when no chunk size is given) is launched with several
+ * workgroups per record so that it fills the machine; those workgroups
  * agree on the record's fate through one 64-bit claim word per record (on a 128-byte line of its
  * own) in a pool the library allocates once per device (16 MiB + 8 bytes, hipMalloc at the first
  * such call or in uccl_init, kept until the process ends).  If the pool cannot be had, or the stream is being

@@ -232,22 +232,34 @@ uint32_t flat_tile(uint32_t n_descs, uint32_t chunk_bytes) {
   return t < 1u ? 1u : t > 32u ? 32u : t;
 }
 
-// Calls of fewer single-record tiles than this are launched with chunk_few_kernel.
-constexpr uint32_t kFewRecords = 512;
+// Calls of fewer single-record tiles than this are launched with chunk_few_kernel (measured with
+// 32 / 64 / 128 KiB chunks and no duplicates: 512 records 12-20 % faster than chunk_flat_kernel,
+// 1024 records 1-9 %, 2048 records 1-3 %; a duplicate costs chunk_few_kernel its payload reads, so
+// large calls, where the difference has gone, stay with chunk_flat_kernel).
+#ifndef UCCL_FEW_RECORDS
+#define UCCL_FEW_RECORDS 2048
+#endif
+constexpr uint32_t kFewRecords = UCCL_FEW_RECORDS;
 // Payload bytes per stream that one part's wavefronts take in their first, eagerly loaded trip.
 constexpr uint32_t kPartBytes = UCCL_PART_THREADS * UCCL_PART_UNROLL * 16u;
 
-// Workgroups per record for a call of few single-record tiles.  Cutting pays when the records
-// alone leave more than half of the compute units idle (measured: 57 records of 64 KiB run 1.4x
-// faster in 8 parts, 256 records of 32 KiB 7 % slower in 2): up to 128 records are cut, into as
-// many parts as keep the launch within 512 workgroups, at most 8, and no more than the chunk has
-// trips for.  Parts that find no unit in a shorter record leave at once.
+// Workgroups per record for a call of few single-record tiles.  One compute unit moves its record's
+// 3-4 streams at a small fraction of the memory system's rate, so while the records alone leave
+// compute units idle a record is spread over several of them.  Measured (kernel time, fp32 SUM with
+// forward, records x chunk size: uncut -> cut): 57 x 64 KiB 6.4 -> 5.2 us in 8 parts; 256 x 64 KiB
+// 14.6 -> 12.4 us in 8; 128 x 128 KiB 17.4 -> 12.3 us in 16; 256 x 128 KiB 25.8 -> 24.1 us in 8;
+// 32 x 32 KiB 4.4 -> 4.1 us in 8; but 128 x 32 KiB 5.6 -> 5.9 us in 4 and 512 x 64 KiB 24.7 ->
+// 25.4 us in 8.  Hence: chunks above 32 KiB are cut into parts of about 8 KiB (at most 16) while
+// the call holds at most 16 MiB of payload and the launch stays within 2048 workgroups; chunks of
+// up to 32 KiB only in calls of at most 32 records; with the chunk size unknown, by record count
+// alone.  Parts that find no unit in a shorter record leave at once.
 uint32_t auto_parts(uint32_t n_descs, uint32_t chunk_bytes) {
-  if (n_descs > 128u) return 1u;
-  uint32_t parts = 1u;
-  while (parts < 8u && n_descs * parts * 2u <= 512u) parts *= 2u;
-  if (chunk_bytes)
-    while (parts > 1u && (parts - 1u) * kPartBytes >= chunk_bytes) parts /= 2u;
+  if (chunk_bytes == 0u) return n_descs <= 64u ? 8u : n_descs <= 128u ? 4u : 1u;
+  if (chunk_bytes <= 32768u) return n_descs <= 32u && chunk_bytes > kPartBytes ? 8u : 1u;
+  if (static_cast<uint64_t>(n_descs) * chunk_bytes > (16ull << 20)) return 1u;
+  uint32_t parts = 16u;
+  while (parts > 1u && parts * kPartBytes > chunk_bytes) parts /= 2u;   // about kPartBytes per part
+  while (parts > 1u && n_descs * parts > 2048u) parts /= 2u;
   return parts;
 }
 
