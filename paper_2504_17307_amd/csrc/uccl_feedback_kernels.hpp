@@ -19,9 +19,10 @@ namespace {
 // bounds the walk).  A word's run starts (bit set, previous bit clear) and run ends (bit set,
 // next bit clear) come from two word-wide shifts and the edge bits of the neighbouring words:
 // the lane's own, the next lane's (shuffle), or, at the step's edges, the previous step's last
-// word and one look-ahead word.  First walk: every wavefront counts its starts, ends and set
-// bits and finds its first clear bit; no barrier inside the walk.  One barrier; the counts of
-// the wavefronts before it give each wavefront the ordinal of its first start and first end.
+// word and one look-ahead word.  First walk: every wavefront counts its starts and set bits and
+// finds its first clear bit; no barrier inside the walk.  One barrier; the counts of the
+// wavefronts before it give each wavefront the ordinal of its first start, and of its first end
+// (the same, less one if a run is open where the wavefront's words begin).
 // Second walk (only if a range is to be written): a wavefront-wide prefix sum per step, by lane
 // shuffles, gives every start and end its ordinal, so the k-th start and the k-th end land in
 // the same output pair.
@@ -66,7 +67,8 @@ struct AckQuad {
 // FULL: every word of the step lies wholly inside the bitmap (all steps but the last of a bitmap):
 // no masks to compute.  The whole workgroup's arithmetic runs on one compute unit, so the walk is
 // bound by instructions per word, not by memory.
-template <bool FULL>
+// ENDS: also compute the run ends (the counting walk needs only the starts).
+template <bool FULL, bool ENDS>
 __device__ __forceinline__ AckQuad ack_quad(uint4 raw, uint64_t w4, uint64_t n_bits, uint32_t before,
                                             uint32_t after, uint32_t lane) {
   AckQuad q;
@@ -78,14 +80,21 @@ __device__ __forceinline__ AckQuad ack_quad(uint4 raw, uint64_t w4, uint64_t n_b
   }
   uint32_t below = __shfl_up(q.word[3], 1, 64);   // the word under this lane's first
   if (lane == 0) below = before;
-  uint32_t above = __shfl_down(q.word[0], 1, 64);  // the word over this lane's last
-  if (lane == 63) above = after;
+  uint32_t above = 0u;
+  if constexpr (ENDS) {
+    above = __shfl_down(q.word[0], 1, 64);  // the word over this lane's last
+    if (lane == 63) above = after;
+  }
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const uint32_t prev = j == 0 ? below : q.word[j - 1];
-    const uint32_t next = j == 3 ? above : q.word[j + 1];
     q.starts[j] = q.word[j] & ~((q.word[j] << 1) | (prev >> 31));
-    q.ends[j] = q.word[j] & ~((q.word[j] >> 1) | (next << 31));
+    if constexpr (ENDS) {
+      const uint32_t next = j == 3 ? above : q.word[j + 1];
+      q.ends[j] = q.word[j] & ~((q.word[j] >> 1) | (next << 31));
+    } else {
+      q.ends[j] = 0u;
+    }
   }
   return q;
 }
@@ -99,7 +108,7 @@ __device__ __forceinline__ uint32_t wave_sum(uint32_t v) {
 __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __restrict__ bitmap,
                                                           uint64_t n_bits, AckHeader* hdr,
                                                           uint64_t* ranges, uint32_t max_ranges) {
-  __shared__ uint32_t s_starts[16], s_ends[16];
+  __shared__ uint32_t s_starts[16];
   __shared__ unsigned long long s_applied[16], s_first_clear[16];
   const uint32_t tid = threadIdx.x, lane = tid & 63u;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -111,36 +120,28 @@ __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __rest
   // beyond the last word of the bitmap a masked word is 0, so the last run ends at n_bits by itself
   const uint32_t seg_before = (w_lo > 0 && w_lo < n_words) ? bitmap[w_lo - 1] : 0u;
 
-  uint32_t my_starts = 0, my_ends = 0, my_applied = 0;
+  uint32_t my_starts = 0, my_applied = 0;
   unsigned long long my_first_clear = ~0ull;
   bool found = false;
   uint32_t before = seg_before;
   for (uint64_t wb = w_lo; wb < w_hi; wb += kAckStep * kAckBatch) {
     uint4 raw[kAckBatch];
-    uint32_t after[kAckBatch];
 #pragma unroll
     for (int i = 0; i < kAckBatch; ++i) {
       const uint64_t w0 = wb + static_cast<uint64_t>(i) * kAckStep;  // wavefront-uniform
       raw[i] = ack_load4(bitmap, w0 + 4 * lane, w0 < w_hi ? n_words : 0, aligned);
     }
 #pragma unroll
-    for (int i = 0; i < kAckBatch; ++i) {  // the word just above step i: the next step's first, if this batch holds it
-      const uint64_t up = wb + static_cast<uint64_t>(i + 1) * kAckStep;
-      if (i + 1 < kAckBatch && up < w_hi) after[i] = __shfl(raw[i + 1 < kAckBatch ? i + 1 : i].x, 0, 64);
-      else after[i] = (up - kAckStep < w_hi && up < n_words) ? bitmap[up] : 0u;
-    }
-    uint32_t my_edges = 0;  // this batch's run starts in the low half, run ends in the high half (<= 64 each per step)
-#pragma unroll
     for (int i = 0; i < kAckBatch; ++i) {
       const uint64_t w0 = wb + static_cast<uint64_t>(i) * kAckStep;
       if (w0 < w_hi) {  // else the batch reaches past the wavefront's words (uniform)
         const uint64_t w4 = w0 + 4 * lane;
         const bool full = (w0 + kAckStep) * 32 <= n_bits;  // uniform
-        const AckQuad q = full ? ack_quad<true>(raw[i], w4, n_bits, before, after[i], lane)
-                               : ack_quad<false>(raw[i], w4, n_bits, before, after[i], lane);
+        const AckQuad q = full ? ack_quad<true, false>(raw[i], w4, n_bits, before, 0u, lane)
+                               : ack_quad<false, false>(raw[i], w4, n_bits, before, 0u, lane);
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          my_edges += __popc(q.starts[j]) + (static_cast<uint32_t>(__popc(q.ends[j])) << 16);
+          my_starts += __popc(q.starts[j]);
           my_applied += __popc(q.word[j]);
         }
         if (!found) {  // the lane's words ascend, so its first clear bit is the first it meets
@@ -153,11 +154,8 @@ __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __rest
         before = __shfl(q.word[3], 63, 64);  // the step's last word
       }
     }
-    my_starts += my_edges & 0xFFFFu;
-    my_ends += my_edges >> 16;
   }
   my_starts = wave_sum(my_starts);
-  my_ends = wave_sum(my_ends);
   const uint32_t app_lo = wave_sum(static_cast<uint32_t>(my_applied & 0xFFFFFu));   // per lane < 2^35 set bits:
   const uint32_t app_hi = wave_sum(static_cast<uint32_t>(my_applied >> 20));        // both halves fit 32-bit sums
 #pragma unroll
@@ -169,16 +167,15 @@ __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __rest
   }
   if (lane == 0) {
     s_starts[wave] = my_starts;
-    s_ends[wave] = my_ends;
     s_applied[wave] = static_cast<unsigned long long>(app_lo) + (static_cast<unsigned long long>(app_hi) << 20);
     s_first_clear[wave] = my_first_clear;
   }
   __syncthreads();
 
-  uint32_t s_at = 0, e_at = 0, n_starts = 0;
+  uint32_t s_at = 0, n_starts = 0;
   unsigned long long applied = 0, first_clear = ~0ull;
   for (uint32_t v = 0; v < 16; ++v) {
-    if (v < wave) { s_at += s_starts[v]; e_at += s_ends[v]; }
+    if (v < wave) s_at += s_starts[v];
     n_starts += s_starts[v];
     applied += s_applied[v];
     if (s_first_clear[v] < first_clear) first_clear = s_first_clear[v];
@@ -195,6 +192,10 @@ __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __rest
   }
   if (max_ranges == 0u || n_starts <= skip) return;  // nothing to list: uniform over the workgroup
 
+  // Every run that starts below this wavefront's first bit also ends below it, except one that is
+  // still open there (the bit below and the first bit both set): ends before = starts before - open.
+  uint32_t e_at = s_at;
+  if (w_lo > 0 && w_lo < n_words) e_at -= (seg_before >> 31) & bitmap[w_lo] & ack_mask(w_lo, n_bits) & 1u;
   before = seg_before;
   for (uint64_t wb = w_lo; wb < w_hi; wb += kAckStep * kAckBatch) {
     uint4 raw[kAckBatch];
@@ -215,7 +216,7 @@ __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __rest
       const uint64_t w0 = wb + static_cast<uint64_t>(i) * kAckStep;
       if (w0 >= w_hi) continue;
       const uint64_t w4 = w0 + 4 * lane;
-      const AckQuad q = ack_quad<false>(raw[i], w4, n_bits, before, after[i], lane);
+      const AckQuad q = ack_quad<false, true>(raw[i], w4, n_bits, before, after[i], lane);
       before = __shfl(q.word[3], 63, 64);
       // starts in the low half, ends in the high half: at most 64 of each per lane, 4096 per step
       uint32_t mine = 0;
