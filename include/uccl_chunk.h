@@ -92,7 +92,8 @@ typedef struct uccl_extents {
  * never depend on it, only speed does.
  *   chunk_bytes  the transport's chunk size (the control path chooses it per connection: 32 KB by
  *                default, Section 3.3 "control coalescing"; Appendix A onChunkSize), 0 = unknown.
- *                Sets how many records a workgroup takes: about 32 KiB of payload per workgroup.
+ *                Sets how many records a workgroup takes: about 32 KiB of payload per workgroup (calls of
+ *                at most 128 records take one workgroup per record, sized to the chunk).
  *   parts        workgroups per record for calls of few, large records (Appendix C.4: small
  *                messages are where the kernel's fixed costs show): 0 = the library decides,
  *                1 = never cut a record, 2..16 = that many.  Honoured only when a workgroup takes
