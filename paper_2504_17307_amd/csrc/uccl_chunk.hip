@@ -263,21 +263,25 @@ uint32_t auto_parts(uint32_t n_descs, uint32_t chunk_bytes) {
   return parts;
 }
 
-// Calls of at most this many small chunks (a message of a few dozen 4 KiB packets) take chunk_few_kernel
-// with one small workgroup per record instead of a tile of records per large workgroup: the call is
-// far too small to fill the machine either way, and the shorter chain of latencies wins (kernel time,
-// fp32 SUM with forward, 57 records: 4 KiB 4.7 -> 3.1 us, 8 KiB 5.3 -> 3.3 us, 16 KiB 5.6 -> 3.7 us;
-// 128 records 15-30 % faster; 512 records of 4 or 8 KiB 15-45 % slower, hence the limit).
+// Calls of few small chunks (a message of a few dozen 4 KiB packets) take chunk_few_kernel with one
+// small workgroup per record instead of a tile of records per large workgroup: the call is far too
+// small to fill the machine either way, and the shorter chain of latencies wins (kernel time, fp32
+// SUM with forward, 57 records: 4 KiB 4.7 -> 3.1 us, 8 KiB 5.3 -> 3.3 us, 16 KiB 5.6 -> 3.7 us; 128
+// records 15-30 % faster; 512 records of 4 or 8 KiB 15-45 % slower, hence the limit).  Chunks above
+// 8 KiB fill a 512-thread workgroup and keep an edge for much longer (16 KiB: 1024 records 15 %
+// faster, 4096 records 10 %, 8192 records 1 %).
 constexpr uint32_t kSmallCallRecords = 128;
+constexpr uint32_t kHalfTileRecords = 8192;
 
 template <class Op>
 int launch_flat_tile(Args& a, hipStream_t s, const Tuning& tune) {
   const uint32_t t = flat_tile(a.n_descs, tune.chunk_bytes);
+  if (t >= 2 && tune.chunk_bytes > 8192u && a.n_descs < kHalfTileRecords)
+    return launch_kernel(chunk_few_kernel<512, 2, Op, false>, a.n_descs, 512, s, a);
   if (t >= 2 && tune.chunk_bytes != 0u && a.n_descs <= kSmallCallRecords) {
     // workgroup sized to the chunk: one trip of 16 bytes x unroll per lane covers it
     if (tune.chunk_bytes <= 4096u) return launch_kernel(chunk_few_kernel<256, 1, Op, false>, a.n_descs, 256, s, a);
-    if (tune.chunk_bytes <= 8192u) return launch_kernel(chunk_few_kernel<256, 2, Op, false>, a.n_descs, 256, s, a);
-    return launch_kernel(chunk_few_kernel<512, 2, Op, false>, a.n_descs, 512, s, a);
+    return launch_kernel(chunk_few_kernel<256, 2, Op, false>, a.n_descs, 256, s, a);
   }
   if (t >= 32) return launch_flat<32, UCCL_FLAT_UNROLL, Op>(a, s);
   if (t >= 16) return launch_flat<16, UCCL_FLAT_UNROLL, Op>(a, s);
