@@ -57,6 +57,8 @@ WORKLOADS = {
                     "slot is handed to the GPU whenever the previous hand-over has finished (adaptive batching)",
     "config5-graph": "small allreduces, one message at a time: the control path rewrites a pinned descriptor "
                      "slot and replays a captured graph of the two calls (no per-message argument marshalling)",
+    "calls": "single calls of n records of C bytes (fp32 SUM with forward, no duplicates, scattered destinations): kernel "
+             "time as the library launches them and with the records never cut / cut into 8 / 16 parts",
     "segment": "sender side: this rank's own segment of a ring (config2's shape: 16 MiB in 32 KiB chunks; config3's: "
                "128 MiB in 128 KiB chunks) cut into staged chunks with send records",
 }
@@ -520,6 +522,59 @@ def bench_segment(args, pkg, torch):
     finish(result, all(r["parity"] != "MISMATCH" for r in rows.values()))
 
 
+def bench_calls(args, pkg, torch):
+    """Where the launch choices of the library come from: kernel time (event pair attached to the
+    dispatch, median) of one call of n records of C bytes each, over buffers rotating over four sets.
+    `auto` is the library's own choice for (n, C); the other columns force the number of parts."""
+    from synth.layout import DESC, F32, SUM
+    rng = np.random.default_rng(args.seed)
+    sizes = [(4 << 10, (16, 57, 128, 512, 2048)), (8 << 10, (16, 57, 128, 512, 2048, 8192)),
+             (16 << 10, (16, 57, 128, 1024, 4096, 8192)), (32 << 10, (8, 32, 57, 128, 512, 1024, 2047, 2048)),
+             (64 << 10, (8, 57, 128, 256, 512, 1024, 2048)), (128 << 10, (8, 57, 128, 256, 512, 1024, 2048))]
+    most = max(c * max(ns) for c, ns in sizes)
+    n_sets = max(1, args.sets)
+    sets = [dict(acc=torch.zeros(most, dtype=torch.uint8, device="cuda"), recv=torch.ones(most, dtype=torch.uint8, device="cuda"),
+                 out=torch.zeros(most, dtype=torch.uint8, device="cuda"), bm=torch.zeros(8192 // 32, dtype=torch.int32, device="cuda"))
+            for _ in range(n_sets)]
+    rows = []
+    for chunk, counts in sizes:
+        for n in counts:
+            perm = rng.permutation(n)
+            d = np.zeros(n, dtype=DESC)
+            d["src_off"] = np.arange(n, dtype=np.uint64) * chunk
+            d["dst_off"] = d["out_off"] = perm.astype(np.uint64) * chunk
+            d["len"], d["seq"] = chunk, perm
+            recs = to_dev(torch, d)
+            row = dict(chunk_bytes=chunk, records=n, algorithmic_bytes=n * (4 * chunk + 36))
+            for label, parts in (("auto", 0), ("uncut", 1), ("parts8", 8), ("parts16", 16)):
+                if parts > 1 and (chunk < (32 << 10) or n * parts > 4096):
+                    continue   # a workgroup takes several records of smaller chunks: parts do not apply
+                # the bitmap reset is a launch of its own: the events are attached to the apply call only
+                evs = []
+                for k in range(args.steps):
+                    s = sets[k % n_sets]
+                    pkg.uccl_dedup_reset(s["bm"], n)
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    b.record()
+                    pkg.uccl_time_next_launch(a, b)
+                    pkg.uccl_chunk_apply_opts(s["acc"], s["out"], s["recv"], recs, n, s["bm"], F32, SUM, opts=(chunk, parts))
+                    evs.append((a, b))
+                torch.cuda.synchronize()
+                row[label + "_us"] = round(float(np.median([a.elapsed_time(b) for a, b in evs[args.warmup:]])) * 1e3, 2)
+            rows.append(row)
+    ok = pkg.uccl_claim_timeouts() == 0
+    big = rows[-1]
+    result = headline("calls", args, big["records"] * big["chunk_bytes"], big["auto_us"] * 1e-6, args.steps, args.warmup, "f32",
+                      dict(buffer_sets=n_sets))
+    result["calls"] = rows
+    result["claim_timeouts"] = pkg.uccl_claim_timeouts()
+    result["roofline"] = {"bound": "hbm", "kernel": "the largest call of the sweep", "achieved": round(big["algorithmic_bytes"] / (big["auto_us"] * 1e-6) / 1e9, 1),
+                          "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(big["algorithmic_bytes"] / (big["auto_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS, 4),
+                          "traffic": None, "algorithmic_bytes_per_launch": big["algorithmic_bytes"], "avg_launch_ms": round(big["auto_us"] * 1e-3, 5)}
+    finish(result, ok)
+
+
 # ---- the CPU oracle beside it ----------------------------------------------------------------------
 
 def cpu_baselines(w, calls, payload, arrivals, first):
@@ -653,6 +708,8 @@ def main():
         return bench_graph_feed(args, pkg, torch)
     if args.workload == "config5-feed":
         return bench_feed(args, pkg, torch)
+    if args.workload == "calls":
+        return bench_calls(args, pkg, torch)
     if args.workload == "segment":
         return bench_segment(args, pkg, torch)
     t0 = time.time()

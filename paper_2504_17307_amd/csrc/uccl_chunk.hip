@@ -270,8 +270,14 @@ uint32_t auto_parts(uint32_t n_descs, uint32_t chunk_bytes) {
 // records 15-30 % faster; 512 records of 4 or 8 KiB 15-45 % slower, hence the limit).  Chunks above
 // 8 KiB fill a 512-thread workgroup and keep an edge for much longer (16 KiB: 1024 records 15 %
 // faster, 4096 records 10 %, 8192 records 1 %).
-constexpr uint32_t kSmallCallRecords = 128;
-constexpr uint32_t kHalfTileRecords = 8192;
+#ifndef UCCL_SMALL_CALL_RECORDS
+#define UCCL_SMALL_CALL_RECORDS 128
+#endif
+#ifndef UCCL_HALF_TILE_RECORDS
+#define UCCL_HALF_TILE_RECORDS 8192
+#endif
+constexpr uint32_t kSmallCallRecords = UCCL_SMALL_CALL_RECORDS;
+constexpr uint32_t kHalfTileRecords = UCCL_HALF_TILE_RECORDS;
 
 template <class Op>
 int launch_flat_tile(Args& a, hipStream_t s, const Tuning& tune) {
