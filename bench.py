@@ -37,11 +37,11 @@ METRIC = "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk s
 # kernel source it was measured on, identified by the hash of the HIP source files.
 MEASURED_TRAFFIC = {
     # (workload, source_hash() of the files under csrc/): bytes per launch
-    ("config1", "fd61b7f85b7211ac"): 14876639,
-    ("config2", "fd61b7f85b7211ac"): 1008015830,
-    ("config3", "fd61b7f85b7211ac"): 3625034768,
-    ("config4", "fd61b7f85b7211ac"): 107504177,
-    ("direct-rs", "fd61b7f85b7211ac"): 1208240369,
+    ("config1", "8d888672356a2ba6"): 14894365,
+    ("config2", "8d888672356a2ba6"): 1008003066,
+    ("config3", "8d888672356a2ba6"): 3625047062,
+    ("config4", "8d888672356a2ba6"): 108258186,
+    ("direct-rs", "8d888672356a2ba6"): 1208247676,
 }
 
 WORKLOADS = {
