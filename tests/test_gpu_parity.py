@@ -123,12 +123,17 @@ def test_config5_recipe_batched_and_per_message(gpu_lib):
         assert_same(out, eout, "out")
 
 
-@pytest.mark.parametrize("hint", [512, 1024, 2048, 4096, 8192, 16384, 1 << 20])
-def test_every_tile_size(gpu_lib, hint):
-    """The chunk size given with the call only changes how many records a workgroup takes
-    (32, 32, 16, 8, 4, 2, 1), and, for the last, into how many parts a record is cut."""
+@pytest.mark.parametrize("hint,per_segment",
+                         [(h, n) for n in (10, 100) for h in (512, 1024, 2048, 4096, 8192, 16384, 1 << 20)] +
+                         [(16384, 2800), (1 << 20, 2800)])   # the largest call only where it selects another kernel
+def test_every_tile_size(gpu_lib, hint, per_segment):
+    """The chunk size given with the call and the record count only choose the kernel and how many
+    records a workgroup takes; the result never changes.  Calls of about 35 records (one small
+    workgroup per record for chunk sizes up to 16 KiB; records cut into parts for the largest),
+    of about 350 records (tiles of 32, 32, 16, 8, 4 records per workgroup; one record per
+    workgroup from 16 KiB on), and of about 9 700 records (tiles of 2 records too)."""
     C = 5008
-    w = wl.ring_share("tiles", 13, R=4, M=4 * (9 * C + 1040), C=C, dtype=BF16, paths=5, window=11,
+    w = wl.ring_share("tiles", 13, R=4, M=4 * ((per_segment - 1) * C + 1040), C=C, dtype=BF16, paths=5, window=11,
                       dup=0.2, dist="normal")
     check_workload(gpu_lib, w, (hint, 0))
 
