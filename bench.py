@@ -397,13 +397,26 @@ def time_feedback_kernels(pkg, torch, bitmap, n_bits):
     hdr = report.cpu().numpy()
     assert int(hdr[:8].view(np.uint64)[0]) == n_bits and int(hdr[20:24].view(np.uint32)[0]) == 1, \
         "after a full step every chunk is acknowledged"
+    # the same bitmap with every 97th chunk missing (a lossy phase): the report then lists ranges
+    words = bitmap.cpu().numpy().view(np.uint32).copy()
+    holes = np.arange(50, n_bits, 97, dtype=np.int64)
+    np.bitwise_and.at(words, holes >> 5, ~(np.uint32(1) << (holes & 31).astype(np.uint32)))
+    lossy = torch.from_numpy(words.view(np.int32)).cuda()
+    lossy_us = {}
+    for max_ranges in (64, 4096):
+        rep = torch.zeros(32 + 16 * max_ranges, dtype=torch.uint8, device="cuda")
+        lossy_us[max_ranges] = launch_time_us(pkg, torch, lambda: pkg.uccl_dedup_report(lossy, n_bits, rep, max_ranges))
+        h = rep.cpu().numpy()
+        if len(holes):
+            assert int(h[:8].view(np.uint64)[0]) == 50 and int(h[8:16].view(np.uint64)[0]) == n_bits - len(holes)
+            assert int(h[16:20].view(np.uint32)[0]) == len(holes) - (1 if holes[-1] == n_bits - 1 else 0)
     win = torch.zeros(128 * 8, dtype=torch.int32, device="cuda")
     win[: 64 * 8] = -1                                   # half of the slots complete
     n_chunks = torch.full((128,), 200, dtype=torch.int32, device="cuda")
     status = torch.zeros(128 * 4, dtype=torch.int32, device="cuda")
     status_us = launch_time_us(pkg, torch, lambda: pkg.uccl_message_status(win, n_chunks, 128, 256, status, False))
     assert int(status.view(128, 4)[:, 2].sum()) == 64
-    return report_us, status_us
+    return report_us, status_us, {"holes": int(len(holes)), "median_us_by_max_ranges": {str(k): round(v, 2) for k, v in lossy_us.items()}}
 
 
 # name -> (mode id of the probe library, streams the shape touches)
@@ -851,7 +864,7 @@ def main():
         evs = timed.get(i) or []
         return float(np.mean([a.elapsed_time(b) for a, b in evs])) if evs else 0.0
 
-    report_us, status_us = time_feedback_kernels(pkg, torch, bitmap, w.n_bits)
+    report_us, status_us, lossy_report = time_feedback_kernels(pkg, torch, bitmap, w.n_bits)
     timeouts = pkg.uccl_claim_timeouts()
     stream_ceiling = None
     if not args.no_ceilings:  # last: the dense kernels overwrite the accumulators and staging buffers
@@ -910,7 +923,8 @@ def main():
         "stream_ceiling": stream_ceiling,
         "device": device_info(torch),
         "dedup_report": {"n_bits": w.n_bits, "median_us": round(report_us, 2),
-                         "what": "ack_report_kernel: cumulative ack, applied count, selective ranges"},
+                         "what": "ack_report_kernel: cumulative ack, applied count, selective ranges",
+                         "every_97th_chunk_missing": lossy_report},
         "message_status": {"slots": 128, "bits_per_slot": 256, "median_us": round(status_us, 2),
                            "what": "message_status_kernel: per-slot cumulative point, applied count, completion"},
         "claim_timeouts": timeouts,

@@ -196,8 +196,11 @@ __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __rest
   // still open there (the bit below and the first bit both set): ends before = starts before - open.
   uint32_t e_at = s_at;
   if (w_lo > 0 && w_lo < n_words) e_at -= (seg_before >> 31) & bitmap[w_lo] & ack_mask(w_lo, n_bits) & 1u;
+  // ordinals only grow along the walk: once the next start and the next end both lie beyond the
+  // ranges that are to be written, nothing further has to be looked at (uniform over the wavefront)
+  const uint64_t beyond = static_cast<uint64_t>(skip) + max_ranges;
   before = seg_before;
-  for (uint64_t wb = w_lo; wb < w_hi; wb += kAckStep * kAckBatch) {
+  for (uint64_t wb = w_lo; wb < w_hi && (s_at < beyond || e_at < beyond); wb += kAckStep * kAckBatch) {
     uint4 raw[kAckBatch];
     uint32_t after[kAckBatch];
 #pragma unroll
@@ -214,7 +217,7 @@ __global__ void __launch_bounds__(1024) ack_report_kernel(const uint32_t* __rest
 #pragma unroll
     for (int i = 0; i < kAckBatch; ++i) {
       const uint64_t w0 = wb + static_cast<uint64_t>(i) * kAckStep;
-      if (w0 >= w_hi) continue;
+      if (w0 >= w_hi || (s_at >= beyond && e_at >= beyond)) continue;  // uniform
       const uint64_t w4 = w0 + 4 * lane;
       const AckQuad q = ack_quad<false, true>(raw[i], w4, n_bits, before, after[i], lane);
       before = __shfl(q.word[3], 63, 64);
