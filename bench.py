@@ -37,11 +37,11 @@ METRIC = "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk s
 # kernel source it was measured on, identified by the hash of the HIP source files.
 MEASURED_TRAFFIC = {
     # (workload, source_hash() of the files under csrc/): bytes per launch
-    ("config1", "8d888672356a2ba6"): 14894365,
-    ("config2", "8d888672356a2ba6"): 1008003066,
-    ("config3", "8d888672356a2ba6"): 3625047062,
-    ("config4", "8d888672356a2ba6"): 108258186,
-    ("direct-rs", "8d888672356a2ba6"): 1208247676,
+    ("config1", "c6591d05b05e407d"): 14872914,
+    ("config2", "c6591d05b05e407d"): 1008022718,
+    ("config3", "c6591d05b05e407d"): 3625039580,
+    ("config4", "c6591d05b05e407d"): 108249292,
+    ("direct-rs", "c6591d05b05e407d"): 1208245185,
 }
 
 WORKLOADS = {
