@@ -213,8 +213,9 @@ struct Tuning {
 
 template <int T, int U, class Op>
 int launch_flat(const Args& a, hipStream_t s) {
-  return launch_kernel(chunk_flat_kernel<UCCL_FLAT_THREADS, T, U, Op>, tiles_for(a.n_descs, T),
-                       UCCL_FLAT_THREADS, s, a);
+  uint32_t tiles = tiles_for(a.n_descs, T);
+  if (UCCL_XCD_CONTIGUOUS) tiles = (tiles + 7u) / 8u * 8u;   // whole eighths; tiles past the records find none
+  return launch_kernel(chunk_flat_kernel<UCCL_FLAT_THREADS, T, U, Op>, tiles, UCCL_FLAT_THREADS, s, a);
 }
 
 // Records per workgroup: enough that a tile holds about 32 KiB of payload per stream when the

@@ -31,6 +31,9 @@
 #ifndef UCCL_PART_UNROLL
 #define UCCL_PART_UNROLL 2
 #endif
+#ifndef UCCL_XCD_CONTIGUOUS
+#define UCCL_XCD_CONTIGUOUS 0   // 1: chunk_flat_kernel gives each of the 8 XCDs one contiguous eighth of the tiles
+#endif
 #ifndef UCCL_CLAIM_STRIDE
 #define UCCL_CLAIM_STRIDE 16    // 64-bit words from one record's claim word to the next: one 128-byte line each
 #endif
@@ -174,9 +177,9 @@ struct Tile {
 // it, claims its sequence number, and the winners are compacted into LDS in record order.
 // kUnitVecs > 0 also computes how many units of kUnitVecs 16-byte vectors each winner has.
 template <int T, class Op, uint32_t kUnitVecs>
-__device__ __forceinline__ void dedup_tile(const Args& g, Tile<T>& s, uint32_t tid) {
+__device__ __forceinline__ void dedup_tile(const Args& g, Tile<T>& s, uint32_t tile, uint32_t tid) {
   static_assert(T >= 1 && T <= 64, "one wavefront dedups the tile");
-  const uint64_t k = static_cast<uint64_t>(blockIdx.x) * T + tid;
+  const uint64_t k = static_cast<uint64_t>(tile) * T + tid;
   bool win = false;
   uint64_t src = 0, dst = 0, out = 0;
   uint32_t len = 0;
@@ -283,7 +286,16 @@ __global__ void __launch_bounds__(NT) chunk_flat_kernel(const Args g) {
   constexpr uint32_t kWaves = NT / 64;
   __shared__ Tile<T> s;
   const uint32_t tid = threadIdx.x;
-  if (tid < 64) dedup_tile<T, Op, kUnit>(g, s, tid);
+  // Consecutive workgroups run on different XCDs (each with an L2 of its own) and take consecutive
+  // tiles, so at any moment the whole chip works on one contiguous window of receive slots.  The
+  // alternative, one contiguous eighth of the tiles per XCD, keeps records and bitmap words inside
+  // one L2 but makes the chip work on eight distant windows at once: measured slower (build switch).
+  uint32_t tile = blockIdx.x;
+  if (UCCL_XCD_CONTIGUOUS) {
+    const uint32_t per_xcd = (gridDim.x + 7u) / 8u;   // the launch has 8 * per_xcd workgroups
+    tile = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  }
+  if (tid < 64) dedup_tile<T, Op, kUnit>(g, s, tile, tid);
   __syncthreads();
 
   const uint32_t count = s.count;
