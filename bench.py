@@ -37,11 +37,11 @@ METRIC = "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk s
 # kernel source it was measured on, identified by the hash of the HIP source files.
 MEASURED_TRAFFIC = {
     # (workload, source_hash() of the files under csrc/): bytes per launch
-    ("config1", "c6591d05b05e407d"): 14872914,
-    ("config2", "c6591d05b05e407d"): 1008022718,
-    ("config3", "c6591d05b05e407d"): 3625039580,
-    ("config4", "c6591d05b05e407d"): 108249292,
-    ("direct-rs", "c6591d05b05e407d"): 1208245185,
+    ("config1", "7147460e5292d0b9"): 14877198,
+    ("config2", "7147460e5292d0b9"): 1008018003,
+    ("config3", "7147460e5292d0b9"): 3625043579,
+    ("config4", "7147460e5292d0b9"): 108240712,
+    ("direct-rs", "7147460e5292d0b9"): 1208245076,
 }
 
 WORKLOADS = {
