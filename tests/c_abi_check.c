@@ -2,8 +2,8 @@
  * The C ABI used from plain C, no Python and no PyTorch: device memory from hipMalloc, a
  * small deterministic chunk stream built here (reordered, with duplicates), one call of
  * each entry point, results compared byte for byte with the CPU oracle (linked as a
- * separate library); then a stream of small messages through the host-side batcher.
- * Prints "C ABI OK" and "FEED OK" and exits 0 on success.
+ * separate library); then the remaining entry points, and a stream of small messages through the
+ * host-side batcher.  Prints "C ABI OK", "MORE OK" and "FEED OK" and exits 0 on success.
  *
  * Build: hipcc -I include -I oracle tests/c_abi_check.c -L<pkg> -luccl_chunk -L oracle -lchunk_oracle
  */
@@ -151,6 +151,140 @@ static int feed_check(hipStream_t st) {
   return 0;
 }
 
+
+/*
+ * The entry points beyond apply / scatter, each once from C against the oracle: a call of few
+ * large records through uccl_chunk_apply_noalloc and through uccl_chunk_apply_opts with records
+ * cut into parts, uccl_chunk_apply_indirect with the count in device memory, a multi-source fold,
+ * sender-side segmentation, and the per-message status with recycling.
+ */
+static int more_entry_points(hipStream_t st) {
+  enum { N = 24, C = 65536, NS = 3, SLOTS = 16, BPS = 64 };
+  const uint64_t bytes = (uint64_t)N * C;
+  uint32_t seed = 4242u;
+  float* h_recv = (float*)malloc(bytes * NS);
+  float* h_acc = (float*)malloc(bytes);
+  for (uint64_t i = 0; i < bytes * NS / 4; ++i) h_recv[i] = (float)(lcg(&seed) % 4001) / 1000.0f - 2.0f;
+  for (uint64_t i = 0; i < bytes / 4; ++i) h_acc[i] = (float)(lcg(&seed) % 4001) / 2000.0f - 1.0f;
+  uccl_chunk_desc h_desc[N + 4];
+  for (uint32_t k = 0; k < N + 4; ++k) { /* arrival k < N carries chunk 7 k mod N; the last four repeat chunks 0..3 */
+    const uint32_t s = k < N ? (k * 7u) % N : k - N;
+    h_desc[k].src_off = (uint64_t)k * C;
+    h_desc[k].dst_off = (uint64_t)s * C;
+    h_desc[k].out_off = (uint64_t)(N - 1 - s) * C;
+    h_desc[k].len = (s == 5) ? C - 1040 : C;
+    h_desc[k].seq = s;
+  }
+  for (uint32_t k = N; k < N + 4; ++k) /* a retransmitted chunk: the same bytes, here read from the same slot */
+    for (uint32_t j = 0; j < N; ++j)
+      if (h_desc[j].seq == h_desc[k].seq) h_desc[k].src_off = h_desc[j].src_off;
+
+  float* o_acc = (float*)malloc(bytes);
+  unsigned char* o_out = (unsigned char*)calloc(bytes, 1);
+  uint8_t seen[N];
+  uint32_t o_words[1], g_words[1];
+  memcpy(o_acc, h_acc, bytes); memset(seen, 0, N);
+  if (orc_apply(o_acc, bytes, o_out, bytes, h_recv, bytes, (const orc_desc*)h_desc, N + 4, seen, N, ORC_F32, ORC_SUM) != N) return 7;
+  orc_pack_bitmap(seen, N, o_words);
+
+  void *d_acc, *d_out, *d_recv, *d_desc, *d_bm, *d_cnt;
+  CK(hipMalloc(&d_acc, bytes)); CK(hipMalloc(&d_out, bytes)); CK(hipMalloc(&d_recv, bytes * NS));
+  CK(hipMalloc(&d_desc, sizeof(h_desc))); CK(hipMalloc(&d_bm, 4 * SLOTS * BPS / 32)); CK(hipMalloc(&d_cnt, 4));
+  CK(hipMemcpy(d_recv, h_recv, bytes * NS, hipMemcpyHostToDevice));
+  CK(hipMemcpy(d_desc, h_desc, sizeof(h_desc), hipMemcpyHostToDevice));
+  float* g_acc = (float*)malloc(bytes);
+  unsigned char* g_out = (unsigned char*)malloc(bytes);
+  UC(uccl_init());
+  for (int variant = 0; variant < 3; ++variant) {
+    CK(hipMemcpy(d_acc, h_acc, bytes, hipMemcpyHostToDevice));
+    CK(hipMemset(d_out, 0, bytes));
+    UC(uccl_dedup_reset((uint32_t*)d_bm, N, st));
+    if (variant == 0) {
+      UC(uccl_chunk_apply_noalloc(d_acc, d_out, d_recv, (const uccl_chunk_desc*)d_desc, N + 4, (uint32_t*)d_bm,
+                                  UCCL_F32, UCCL_SUM, st));
+    } else if (variant == 1) {
+      const uccl_launch_opts opts = {C, 4, {0, 0}};
+      UC(uccl_chunk_apply_opts(d_acc, d_out, d_recv, (const uccl_chunk_desc*)d_desc, N + 4, (uint32_t*)d_bm,
+                               UCCL_F32, UCCL_SUM, NULL, NULL, &opts, st));
+    } else {
+      const uint32_t live = N + 4;
+      CK(hipMemcpy(d_cnt, &live, 4, hipMemcpyHostToDevice));
+      UC(uccl_chunk_apply_indirect(d_acc, d_out, d_recv, (const uccl_chunk_desc*)d_desc, (const uint32_t*)d_cnt,
+                                   N + 4, (uint32_t*)d_bm, UCCL_F32, UCCL_SUM, NULL, NULL, NULL, st));
+    }
+    CK(hipStreamSynchronize(st));
+    CK(hipMemcpy(g_acc, d_acc, bytes, hipMemcpyDeviceToHost));
+    CK(hipMemcpy(g_out, d_out, bytes, hipMemcpyDeviceToHost));
+    CK(hipMemcpy(g_words, d_bm, 4, hipMemcpyDeviceToHost));
+    if (memcmp(g_acc, o_acc, bytes) || memcmp(g_out, o_out, bytes) || g_words[0] != o_words[0]) {
+      fprintf(stderr, "few-record call, variant %d: differs from the oracle\n", variant);
+      return 7;
+    }
+  }
+  uint64_t gave_up = 1;
+  UC(uccl_claim_timeouts(&gave_up));
+  if (gave_up != 0) { fprintf(stderr, "%llu parts gave up waiting\n", (unsigned long long)gave_up); return 7; }
+
+  /* multi-source fold: chunk s folds source regions 2, 0, 1 in that order */
+  uccl_gather_desc h_g[N];
+  memset(h_g, 0, sizeof(h_g));
+  for (uint32_t s = 0; s < N; ++s) {
+    h_g[s].dst_off = (uint64_t)s * C; h_g[s].out_off = UCCL_NO_FORWARD; h_g[s].len = C; h_g[s].seq = s; h_g[s].n_src = NS;
+    h_g[s].src_off[0] = 2 * bytes + (uint64_t)s * C; h_g[s].src_off[1] = (uint64_t)s * C; h_g[s].src_off[2] = bytes + (uint64_t)s * C;
+  }
+  if (sizeof(orc_gather_desc) != sizeof(uccl_gather_desc)) return 8;
+  memcpy(o_acc, h_acc, bytes); memset(seen, 0, N);
+  if (orc_reduce_gather(o_acc, bytes, NULL, 0, h_recv, bytes * NS, (const orc_gather_desc*)h_g, N, seen, N, ORC_F32, ORC_SUM) != N) return 8;
+  void* d_g;
+  CK(hipMalloc(&d_g, sizeof(h_g)));
+  CK(hipMemcpy(d_g, h_g, sizeof(h_g), hipMemcpyHostToDevice));
+  CK(hipMemcpy(d_acc, h_acc, bytes, hipMemcpyHostToDevice));
+  UC(uccl_dedup_reset((uint32_t*)d_bm, N, st));
+  UC(uccl_chunk_reduce_gather(d_acc, NULL, d_recv, (const uccl_gather_desc*)d_g, N, (uint32_t*)d_bm, UCCL_F32, UCCL_SUM,
+                              NULL, NULL, NULL, st));
+  CK(hipStreamSynchronize(st));
+  CK(hipMemcpy(g_acc, d_acc, bytes, hipMemcpyDeviceToHost));
+  if (memcmp(g_acc, o_acc, bytes)) { fprintf(stderr, "multi-source fold differs\n"); return 8; }
+
+  /* sender side: 1 000 003 bytes of the tensor from offset 4096 in 48 KiB chunks, slots 64 KiB apart */
+  enum { SEG = 1000003, CHUNK = 49152, STRIDE = 65536, NCH = (SEG + CHUNK - 1) / CHUNK };
+  orc_send_desc o_sd[NCH];
+  uccl_send_desc g_sd[NCH];
+  if (sizeof(orc_send_desc) != sizeof(uccl_send_desc)) return 9;
+  memset(o_out, 0, bytes);
+  if (orc_segment(o_out, bytes, h_acc, bytes, 4096, SEG, CHUNK, 128, STRIDE, o_sd, 9, 127, 250) != NCH) return 9;
+  void* d_sd;
+  CK(hipMalloc(&d_sd, sizeof(g_sd)));
+  CK(hipMemcpy(d_acc, h_acc, bytes, hipMemcpyHostToDevice));
+  CK(hipMemset(d_out, 0, bytes));
+  UC(uccl_chunk_segment(d_out, d_acc, 4096, SEG, CHUNK, 128, STRIDE, (uccl_send_desc*)d_sd, 9, 127, 250, st));
+  CK(hipStreamSynchronize(st));
+  CK(hipMemcpy(g_out, d_out, bytes, hipMemcpyDeviceToHost));
+  CK(hipMemcpy(g_sd, d_sd, sizeof(g_sd), hipMemcpyDeviceToHost));
+  if (memcmp(g_out, o_out, bytes) || memcmp(g_sd, o_sd, sizeof(g_sd))) { fprintf(stderr, "segmentation differs\n"); return 9; }
+
+  /* per-message status of 16 windows of 64 bits, with recycling */
+  uint32_t h_bits[SLOTS * BPS / 32], o_bits[SLOTS * BPS / 32], h_cnt[SLOTS], o_st[SLOTS * 4], g_st[SLOTS * 4];
+  for (uint32_t i = 0; i < SLOTS * BPS / 32; ++i) h_bits[i] = (i % 3 == 0) ? 0xFFFFFFFFu : (lcg(&seed) | (lcg(&seed) << 16));
+  for (uint32_t i = 0; i < SLOTS; ++i) h_cnt[i] = (i % 4 == 0) ? 0u : 1u + lcg(&seed) % BPS;
+  h_bits[2] = h_bits[3] = 0xFFFFFFFFu; h_cnt[1] = 40;   /* slot 1: complete */
+  memcpy(o_bits, h_bits, sizeof(h_bits));
+  orc_message_status(o_bits, h_cnt, SLOTS, BPS, o_st, 1);
+  void *d_n, *d_st;
+  CK(hipMalloc(&d_n, sizeof(h_cnt))); CK(hipMalloc(&d_st, sizeof(g_st)));
+  CK(hipMemcpy(d_bm, h_bits, sizeof(h_bits), hipMemcpyHostToDevice));
+  CK(hipMemcpy(d_n, h_cnt, sizeof(h_cnt), hipMemcpyHostToDevice));
+  UC(uccl_message_status((uint32_t*)d_bm, (const uint32_t*)d_n, SLOTS, BPS, (uccl_msg_status*)d_st, 1, st));
+  CK(hipStreamSynchronize(st));
+  CK(hipMemcpy(g_st, d_st, sizeof(g_st), hipMemcpyDeviceToHost));
+  CK(hipMemcpy(h_bits, d_bm, sizeof(h_bits), hipMemcpyDeviceToHost));
+  if (memcmp(g_st, o_st, sizeof(g_st)) || memcmp(h_bits, o_bits, sizeof(h_bits))) { fprintf(stderr, "message status differs\n"); return 10; }
+  if (o_st[1 * 4 + 2] != 1u || o_bits[2] != 0u) { fprintf(stderr, "slot 1 was to be complete and recycled\n"); return 10; }
+
+  printf("MORE OK: no-alloc / cut / indirect apply, multi-source fold, segmentation (%d chunks), message status\n", (int)NCH);
+  return 0;
+}
+
 int main(void) {
   enum { N = 300, C = 8192, DUP = 37 }; /* 300 logical chunks of 8 KiB, 37 retransmitted */
   const uint64_t n_arr = N + DUP, acc_bytes = (uint64_t)N * C, recv_bytes = n_arr * C;
@@ -246,5 +380,7 @@ int main(void) {
   if (memcmp(g_out, o_dst, acc_bytes)) { fprintf(stderr, "scatter differs\n"); return 6; }
 
   printf("C ABI OK: %d chunks, %d duplicates, version %d\n", (int)N, (int)DUP, uccl_version());
+  const int more = more_entry_points(st);
+  if (more != 0) return more;
   return feed_check(st);
 }

@@ -674,7 +674,7 @@ def test_c_abi_from_plain_c(gpu_lib):
     exe = os.path.join(os.path.dirname(os.path.abspath(__file__)), "c_abi_check")
     assert os.path.exists(exe), "tests/c_abi_check is not built: run __graft_entry__.build()"
     r = subprocess.run([exe], capture_output=True, text=True, timeout=120)
-    assert r.returncode == 0 and "C ABI OK" in r.stdout and "FEED OK" in r.stdout, (r.returncode, r.stdout, r.stderr)
+    assert r.returncode == 0 and all(k in r.stdout for k in ("C ABI OK", "MORE OK", "FEED OK")), (r.returncode, r.stdout, r.stderr)
     print(r.stdout.strip())
 
 
