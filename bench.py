@@ -576,11 +576,42 @@ def bench_calls(args, pkg, torch):
                 torch.cuda.synchronize()
                 row[label + "_us"] = round(float(np.median([a.elapsed_time(b) for a, b in evs[args.warmup:]])) * 1e3, 2)
             rows.append(row)
+    # the multi-source fold (seven senders per destination chunk) on calls of few records
+    GATHER = np.dtype([("dst_off", "<u8"), ("out_off", "<u8"), ("len", "<u4"), ("seq", "<u4"), ("n_src", "<u4"),
+                       ("reserved", "<u4"), ("src_off", "<u8", (16,))])
+    n_src, gather_rows = 7, []
+    for chunk in (32 << 10, 64 << 10, 128 << 10):
+        for n in (1, 8, 32, 128, 512):
+            if n * chunk * n_src > most:
+                continue
+            d = np.zeros(n, dtype=GATHER)
+            d["dst_off"] = np.arange(n, dtype=np.uint64) * chunk
+            d["out_off"] = np.uint64(0xFFFFFFFFFFFFFFFF)
+            d["len"], d["seq"], d["n_src"] = chunk, np.arange(n), n_src
+            for j in range(n_src):
+                d["src_off"][:, j] = (j * n + np.arange(n, dtype=np.uint64)) * chunk
+            recs = to_dev(torch, d)
+            row = dict(chunk_bytes=chunk, records=n, sources=n_src, algorithmic_bytes=n * ((n_src + 2) * chunk + 164))
+            for label, parts in (("auto", 0), ("uncut", 1)):
+                evs = []
+                for k in range(args.steps):
+                    s = sets[k % n_sets]
+                    pkg.uccl_dedup_reset(s["bm"], n)
+                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    a.record()
+                    b.record()
+                    pkg.uccl_time_next_launch(a, b)
+                    pkg.uccl_chunk_reduce_gather(s["acc"], None, s["recv"], recs, n, s["bm"], F32, SUM, opts=(chunk, parts))
+                    evs.append((a, b))
+                torch.cuda.synchronize()
+                row[label + "_us"] = round(float(np.median([a.elapsed_time(b) for a, b in evs[args.warmup:]])) * 1e3, 2)
+            gather_rows.append(row)
     ok = pkg.uccl_claim_timeouts() == 0
     big = rows[-1]
     result = headline("calls", args, big["records"] * big["chunk_bytes"], big["auto_us"] * 1e-6, args.steps, args.warmup, "f32",
                       dict(buffer_sets=n_sets))
     result["calls"] = rows
+    result["gather_calls"] = gather_rows
     result["claim_timeouts"] = pkg.uccl_claim_timeouts()
     result["roofline"] = {"bound": "hbm", "kernel": "the largest call of the sweep", "achieved": round(big["algorithmic_bytes"] / (big["auto_us"] * 1e-6) / 1e9, 1),
                           "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(big["algorithmic_bytes"] / (big["auto_us"] * 1e-6) / 1e9 / PEAK_HBM_GBS, 4),

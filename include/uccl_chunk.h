@@ -228,7 +228,9 @@ int uccl_chunk_apply_indirect(void* acc, void* out_stage, const void* recv_stage
  * once per chunk: (n_src + 1) reads and 1 (+1 forwarding) writes per payload byte of one source.
  * `seq` dedups the record as a whole: the control path issues it when all its sources are
  * in, and may issue it again.  `extents` / `n_rejected` as in uccl_chunk_apply_checked, both
- * may be NULL; `opts` may be NULL (only chunk_bytes is used).  Records: 160 bytes, 16-byte aligned array.
+ * may be NULL; `opts` may be NULL.  A call of few records of 32 KiB or more is cut into parts like
+ * uccl_chunk_apply's (same claim pool, same fallback under graph capture).  Records: 160 bytes, 16-byte
+ * aligned array.
  */
 #define UCCL_MAX_SOURCES 16
 typedef struct uccl_gather_desc {

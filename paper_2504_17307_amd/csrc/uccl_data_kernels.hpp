@@ -455,7 +455,92 @@ struct GatherArgs {
   uint32_t* rejected;
   Extents ext;
   uint32_t n_descs;
+  // records cut into parts (chunk_gather_parts_kernel; see claim_enter)
+  unsigned long long* claims;
+  uint32_t* faults;
+  unsigned long long tag;
+  uint32_t parts;
 };
+
+// One unit (64 * U vectors from vector v0 on) of one destination chunk: the accumulator's value,
+// the sources folded into it in the listed order (src[] in LDS), the result written back and / or
+// forwarded.  Sources are loaded in batches, all loads of a batch issued before the folds.
+template <int U, class Op>
+__device__ __forceinline__ void gather_unit(const GatherArgs& g, uint64_t dst, uint64_t out, uint32_t len,
+                                            uint32_t n_src, const uint64_t* src, uint32_t v0, uint32_t lane) {
+  constexpr uint32_t kUnit = 64u * U;
+  constexpr uint32_t kBatch = UCCL_GATHER_BATCH;
+  const uint32_t nvec = len >> 4;
+  const bool fwd = out != UCCL_NO_FORWARD;
+  const bool keep = !(fwd && (out & UCCL_FORWARD_ONLY));
+  u32x4* ap = reinterpret_cast<u32x4*>(g.acc + dst) + v0 + lane;
+  u32x4* op = reinterpret_cast<u32x4*>(g.out + (out & ~UCCL_FORWARD_ONLY)) + v0 + lane;
+  bool live[U];
+  typename Op::State st[U][4];
+#pragma unroll
+  for (int i = 0; i < U; ++i) {
+    live[i] = v0 + lane + i * 64 < nvec;
+    u32x4 a = {0u, 0u, 0u, 0u};
+    if (live[i]) a = ap[i * 64];
+    st[i][0] = Op::open(a.x); st[i][1] = Op::open(a.y); st[i][2] = Op::open(a.z); st[i][3] = Op::open(a.w);
+  }
+  for (uint32_t j0 = 0; j0 < n_src; j0 += kBatch) {
+    u32x4 rv[kBatch][U];
+#pragma unroll
+    for (uint32_t b = 0; b < kBatch; ++b) {
+      if (j0 + b < n_src) {
+        const u32x4* rp = reinterpret_cast<const u32x4*>(g.recv + wave_uniform(src[j0 + b])) + v0 + lane;
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+          rv[b][i] = u32x4{0u, 0u, 0u, 0u};
+          if (live[i]) rv[b][i] = __builtin_nontemporal_load(rp + i * 64);
+        }
+      }
+    }
+#pragma unroll
+    for (uint32_t b = 0; b < kBatch; ++b) {
+      if (j0 + b < n_src) {
+#pragma unroll
+        for (int i = 0; i < U; ++i) {
+          Op::fold(st[i][0], rv[b][i].x); Op::fold(st[i][1], rv[b][i].y);
+          Op::fold(st[i][2], rv[b][i].z); Op::fold(st[i][3], rv[b][i].w);
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < U; ++i) {
+    if (!live[i]) continue;
+    u32x4 t;
+    t.x = Op::close(st[i][0]); t.y = Op::close(st[i][1]); t.z = Op::close(st[i][2]); t.w = Op::close(st[i][3]);
+    if (keep) ap[i * 64] = t;
+    if (fwd) __builtin_nontemporal_store(t, op + i * 64);
+  }
+  // the last len % 16 bytes, element by element, by the unit that holds vector index nvec
+  const uint32_t rem = len & 15u;
+  if (rem && nvec >= v0 && nvec < v0 + kUnit && lane < rem / Op::kEs) {
+    const uint64_t off = (static_cast<uint64_t>(nvec) << 4) + lane * Op::kEs;
+    uint32_t a_el;
+    if constexpr (Op::kEs == 4) a_el = *reinterpret_cast<const uint32_t*>(g.acc + dst + off);
+    else a_el = *reinterpret_cast<const uint16_t*>(g.acc + dst + off);
+    typename Op::State t = Op::open(a_el);
+    for (uint32_t j = 0; j < n_src; ++j) {
+      const char* rp = g.recv + wave_uniform(src[j]) + off;
+      uint32_t r_el;
+      if constexpr (Op::kEs == 4) r_el = *reinterpret_cast<const uint32_t*>(rp);
+      else r_el = *reinterpret_cast<const uint16_t*>(rp);
+      Op::fold(t, r_el);
+    }
+    const uint32_t res = Op::close(t);
+    if constexpr (Op::kEs == 4) {
+      if (keep) *reinterpret_cast<uint32_t*>(g.acc + dst + off) = res;
+      if (fwd) *reinterpret_cast<uint32_t*>(g.out + (out & ~UCCL_FORWARD_ONLY) + off) = res;
+    } else {
+      if (keep) *reinterpret_cast<uint16_t*>(g.acc + dst + off) = static_cast<uint16_t>(res);
+      if (fwd) *reinterpret_cast<uint16_t*>(g.out + (out & ~UCCL_FORWARD_ONLY) + off) = static_cast<uint16_t>(res);
+    }
+  }
+}
 
 template <int T>
 struct GatherTile {
@@ -470,7 +555,6 @@ template <int NT, int T, int U, class Op>
 __global__ void __launch_bounds__(NT) chunk_gather_kernel(const GatherArgs g) {
   static_assert(T >= 1 && T <= 64, "one wavefront dedups the tile");
   constexpr uint32_t kUnit = 64u * U;
-  constexpr uint32_t kBatch = UCCL_GATHER_BATCH;
   __shared__ GatherTile<T> s;
   const uint32_t tid = threadIdx.x;
   if (tid < 64) {
@@ -543,82 +627,69 @@ __global__ void __launch_bounds__(NT) chunk_gather_kernel(const GatherArgs g) {
     }
     w = __builtin_amdgcn_readfirstlane(w);
     const uint32_t v0 = (u - __builtin_amdgcn_readfirstlane(s.first[w])) * kUnit;
-    const uint64_t dst = wave_uniform(s.dst[w]);
-    const uint64_t out = wave_uniform(s.out[w]);
-    const uint32_t len = __builtin_amdgcn_readfirstlane(s.len[w]);
-    const uint32_t n_src = __builtin_amdgcn_readfirstlane(s.n_src[w]);
-    const uint32_t nvec = len >> 4;
+    gather_unit<U, Op>(g, wave_uniform(s.dst[w]), wave_uniform(s.out[w]), __builtin_amdgcn_readfirstlane(s.len[w]),
+                       __builtin_amdgcn_readfirstlane(s.n_src[w]), s.src[w], v0, lane);
+  }
+}
+
+// A call of few multi-source records: `parts` workgroups per record share its units (one compute
+// unit reads a record's n + 1 streams far below its share of the memory system's rate: eight
+// records of 128 KiB from seven senders take 25 us uncut).  The record's fate is decided once, by
+// the first part to arrive (see claim_enter); blockIdx.x = record * parts + part.
+template <int NT, int U, class Op>
+__global__ void __launch_bounds__(NT) chunk_gather_parts_kernel(const GatherArgs g) {
+  constexpr uint32_t kUnit = 64u * U;
+  constexpr uint32_t kWaves = NT / 64;
+  __shared__ uint64_t s_src[UCCL_MAX_SOURCES];
+  __shared__ uint32_t s_win;
+  const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63u;
+  const uint32_t k = blockIdx.x / g.parts, part = blockIdx.x % g.parts;   // the launch has n_descs * parts workgroups
+  const uccl_gather_desc* d = g.descs + k;
+  const u32x4* p = reinterpret_cast<const u32x4*>(d);
+  const u32x4 lo = p[0], hi = p[1];   // every lane reads the same 32 bytes
+  const uint64_t dst = wave_uniform(lo.x | (static_cast<uint64_t>(lo.y) << 32));
+  const uint64_t out = wave_uniform(lo.z | (static_cast<uint64_t>(lo.w) << 32));
+  const uint32_t len = __builtin_amdgcn_readfirstlane(hi.x);
+  const uint32_t seq = __builtin_amdgcn_readfirstlane(hi.y);
+  const uint32_t n_src = __builtin_amdgcn_readfirstlane(hi.z);
+  const uint32_t vecs = (len >> 4) + ((len & 15u) != 0u ? 1u : 0u);
+  const uint32_t total = (vecs + kUnit - 1u) / kUnit;
+  if (wave == 0) {
     const bool fwd = out != UCCL_NO_FORWARD;
-    const bool keep = !(fwd && (out & UCCL_FORWARD_ONLY));
-    u32x4* ap = reinterpret_cast<u32x4*>(g.acc + dst) + v0 + lane;
-    u32x4* op = reinterpret_cast<u32x4*>(g.out + (out & ~UCCL_FORWARD_ONLY)) + v0 + lane;
-    bool live[U];
-    typename Op::State st[U][4];
-#pragma unroll
-    for (int i = 0; i < U; ++i) {
-      live[i] = v0 + lane + i * 64 < nvec;
-      u32x4 a = {0u, 0u, 0u, 0u};
-      if (live[i]) a = ap[i * 64];
-      st[i][0] = Op::open(a.x); st[i][1] = Op::open(a.y); st[i][2] = Op::open(a.z); st[i][3] = Op::open(a.w);
+    const uint64_t out_at = out & ~UCCL_FORWARD_ONLY;
+    bool ok = seq < g.ext.n_bits && (dst & 15u) == 0 && len % Op::kEs == 0 && n_src >= 1 &&
+              n_src <= UCCL_MAX_SOURCES && dst <= g.ext.acc_bytes && len <= g.ext.acc_bytes - dst;
+    if (fwd)
+      ok = ok && g.out != nullptr && (out_at & 15u) == 0 && out_at <= g.ext.out_bytes && len <= g.ext.out_bytes - out_at;
+    bool src_ok = true;
+    if (lane < UCCL_MAX_SOURCES && lane < n_src) {  // lane j checks and stages source j
+      const uint64_t so = d->src_off[lane];
+      s_src[lane] = so;
+      src_ok = (so & 15u) == 0 && so <= g.ext.recv_bytes && len <= g.ext.recv_bytes - so;
     }
-    // sources in batches: all loads of a batch are issued before the first fold waits
-    for (uint32_t j0 = 0; j0 < n_src; j0 += kBatch) {
-      u32x4 rv[kBatch][U];
-#pragma unroll
-      for (uint32_t b = 0; b < kBatch; ++b) {
-        if (j0 + b < n_src) {
-          const u32x4* rp = reinterpret_cast<const u32x4*>(g.recv + wave_uniform(s.src[w][j0 + b])) + v0 + lane;
-#pragma unroll
-          for (int i = 0; i < U; ++i) {
-            rv[b][i] = u32x4{0u, 0u, 0u, 0u};
-            if (live[i]) rv[b][i] = __builtin_nontemporal_load(rp + i * 64);
-          }
+    ok = ok && __all(src_ok);
+    if (lane == 0) {
+      uint32_t win = 0u;
+      unsigned long long* const claim = g.claims + static_cast<size_t>(k) * UCCL_CLAIM_STRIDE;
+      const unsigned long long entered = claim_enter(claim, g.tag);
+      if (claim_decides(entered, g.tag)) {
+        if (ok) {
+          const uint32_t bit = 1u << (seq & 31u);
+          win = (atomicOr(g.bitmap + (seq >> 5), bit) & bit) == 0u ? 1u : 0u;
+        } else if (g.rejected != nullptr) {
+          atomicAdd(g.rejected, 1u);
         }
+        claim_publish(claim, g.tag, win != 0u);
+      } else if (ok && part * kWaves < total) {  // a part without units has nothing to wait for
+        win = claim_await(claim, entered, g.tag, g.faults) ? 1u : 0u;
       }
-#pragma unroll
-      for (uint32_t b = 0; b < kBatch; ++b) {
-        if (j0 + b < n_src) {
-#pragma unroll
-          for (int i = 0; i < U; ++i) {
-            Op::fold(st[i][0], rv[b][i].x); Op::fold(st[i][1], rv[b][i].y);
-            Op::fold(st[i][2], rv[b][i].z); Op::fold(st[i][3], rv[b][i].w);
-          }
-        }
-      }
-    }
-#pragma unroll
-    for (int i = 0; i < U; ++i) {
-      if (!live[i]) continue;
-      u32x4 t;
-      t.x = Op::close(st[i][0]); t.y = Op::close(st[i][1]); t.z = Op::close(st[i][2]); t.w = Op::close(st[i][3]);
-      if (keep) ap[i * 64] = t;
-      if (fwd) __builtin_nontemporal_store(t, op + i * 64);
-    }
-    // the last len % 16 bytes, element by element, by the unit that holds vector index nvec
-    const uint32_t rem = len & 15u;
-    if (rem && nvec >= v0 && nvec < v0 + kUnit && lane < rem / Op::kEs) {
-      const uint64_t off = (static_cast<uint64_t>(nvec) << 4) + lane * Op::kEs;
-      uint32_t a_el;
-      if constexpr (Op::kEs == 4) a_el = *reinterpret_cast<const uint32_t*>(g.acc + dst + off);
-      else a_el = *reinterpret_cast<const uint16_t*>(g.acc + dst + off);
-      typename Op::State t = Op::open(a_el);
-      for (uint32_t j = 0; j < n_src; ++j) {
-        const char* rp = g.recv + wave_uniform(s.src[w][j]) + off;
-        uint32_t r_el;
-        if constexpr (Op::kEs == 4) r_el = *reinterpret_cast<const uint32_t*>(rp);
-        else r_el = *reinterpret_cast<const uint16_t*>(rp);
-        Op::fold(t, r_el);
-      }
-      const uint32_t res = Op::close(t);
-      if constexpr (Op::kEs == 4) {
-        if (keep) *reinterpret_cast<uint32_t*>(g.acc + dst + off) = res;
-        if (fwd) *reinterpret_cast<uint32_t*>(g.out + (out & ~UCCL_FORWARD_ONLY) + off) = res;
-      } else {
-        if (keep) *reinterpret_cast<uint16_t*>(g.acc + dst + off) = static_cast<uint16_t>(res);
-        if (fwd) *reinterpret_cast<uint16_t*>(g.out + (out & ~UCCL_FORWARD_ONLY) + off) = static_cast<uint16_t>(res);
-      }
+      s_win = win;
     }
   }
+  __syncthreads();
+  if (s_win == 0u) return;   // uniform over the workgroup
+  for (uint32_t u = part * kWaves + wave; u < total; u += kWaves * g.parts)
+    gather_unit<U, Op>(g, dst, out, len, n_src, s_src, u * kUnit, lane);
 }
 
 // ---- sender side: tensor buffer -> staged chunks + send records --------------------------------

@@ -298,12 +298,40 @@ def test_gpu_gather_source_counts_forward_and_rejects(gpu_lib, R):
 
 
 @pytest.mark.gpu
-def test_gpu_gather_exactly_once_all_ones(gpu_lib):
+@pytest.mark.parametrize("opts", [None, (8192, 1), (8192, 5), (65536, 16)])
+def test_gpu_gather_exactly_once_all_ones(gpu_lib, opts):
+    """Every record several times, far apart, also with each record cut into 5 or 16 parts: 15 = each of
+    the 15 sources folded exactly once (a double apply shows as 30, a lost part as 0)."""
     w = make(BF16, dist="ones", R=16, C=8192, chunks=64)
     w.acc[:] = pl.ints_as(np.zeros(1, dtype=np.int64), BF16)[0]
     d = w.phases[0].descs
     w.phases[0].descs = np.concatenate([d, d[::2], d[::-1]])  # every record several times, far apart
-    acc, _, bm, rej = gpu_run(gpu_lib, w)
+    acc, _, bm, rej = gpu_run(gpu_lib, w, opts=opts)
     fifteen = pl.ints_as(np.array([15]), BF16)[0]
     assert rej == 0 and np.all(acc == fifteen)
     assert sum(int(x).bit_count() for x in bm) == w.n_bits
+    assert gpu_lib.uccl_claim_timeouts() == 0
+
+
+@pytest.mark.gpu
+def test_gpu_gather_cut_records_on_two_streams(gpu_lib):
+    """The same multi-source records issued on two streams at once, every record cut into parts: each
+    stream has claim words of its own, the bitmap decides between the streams, every part learns the one
+    decision taken for its record."""
+    import torch
+    from gpuhelp import to_dev, to_host
+    w = make(F32, dist="ones", R=8, C=48 << 10, chunks=40)
+    w.acc[:] = 0
+    ph = w.phases[0]
+    for trial in range(3):
+        acc, recv, descs = to_dev(w.acc), to_dev(w.recv_stage), to_dev(ph.descs)
+        bm = torch.zeros((w.n_bits + 31) // 32, dtype=torch.int32, device="cuda")
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        for s in (s1, s2, s1):
+            gpu_lib.uccl_chunk_reduce_gather(acc, None, recv, descs, len(ph.descs), bm, F32, SUM, opts=(48 << 10, 4), stream=s)
+        s1.synchronize(); s2.synchronize()
+        got = to_host(acc, np.float32)
+        assert np.all(got == 7.0), f"trial {trial}: {np.count_nonzero(got != 7.0)} elements not exactly 7"
+        assert sum(int(x).bit_count() for x in bm.cpu().numpy().view(np.uint32)) == w.n_bits
+    assert gpu_lib.uccl_claim_timeouts() == 0
