@@ -37,11 +37,11 @@ METRIC = "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk s
 # kernel source it was measured on, identified by the hash of the HIP source files.
 MEASURED_TRAFFIC = {
     # (workload, source_hash() of the files under csrc/): bytes per launch
-    ("config1", "7147460e5292d0b9"): 14877198,
-    ("config2", "7147460e5292d0b9"): 1008018003,
-    ("config3", "7147460e5292d0b9"): 3625043579,
-    ("config4", "7147460e5292d0b9"): 108240712,
-    ("direct-rs", "7147460e5292d0b9"): 1208245076,
+    ("config1", "c6abf0d6d21601ff"): 14888083,
+    ("config2", "c6abf0d6d21601ff"): 1008018040,
+    ("config3", "c6abf0d6d21601ff"): 3625035711,
+    ("config4", "c6abf0d6d21601ff"): 108259459,
+    ("direct-rs", "c6abf0d6d21601ff"): 1208247125,
 }
 
 WORKLOADS = {
