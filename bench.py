@@ -376,15 +376,18 @@ def bench_feed(args, pkg, torch):
 
 # ---- single kernels ----------------------------------------------------------------------------
 
-def launch_time_us(pkg, torch, launch, reps=30, skip=5):
-    """Median duration of one launch, from event pairs attached to the dispatch."""
+def launch_time_us(pkg, torch, launch, reps=30, skip=5, before=None):
+    """Median duration of launch(k), from event pairs attached to its dispatch; before(k), if given,
+    runs ahead of it untimed (launches of its own, such as a bitmap reset)."""
     evs = []
-    for _ in range(reps):
+    for k in range(reps):
+        if before is not None:
+            before(k)
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record()
         b.record()
         pkg.uccl_time_next_launch(a, b)
-        launch()
+        launch(k)
         evs.append((a, b))
     torch.cuda.synchronize()
     return float(np.median([a.elapsed_time(b) for a, b in evs[skip:]])) * 1e3
@@ -393,7 +396,7 @@ def launch_time_us(pkg, torch, launch, reps=30, skip=5):
 def time_feedback_kernels(pkg, torch, bitmap, n_bits):
     """(acknowledgement report over this workload's bitmap, status of a 128 x 256-bit message window), in us."""
     report = torch.zeros(32 + 16 * 64, dtype=torch.uint8, device="cuda")
-    report_us = launch_time_us(pkg, torch, lambda: pkg.uccl_dedup_report(bitmap, n_bits, report, 64))
+    report_us = launch_time_us(pkg, torch, lambda k: pkg.uccl_dedup_report(bitmap, n_bits, report, 64))
     hdr = report.cpu().numpy()
     assert int(hdr[:8].view(np.uint64)[0]) == n_bits and int(hdr[20:24].view(np.uint32)[0]) == 1, \
         "after a full step every chunk is acknowledged"
@@ -405,7 +408,7 @@ def time_feedback_kernels(pkg, torch, bitmap, n_bits):
     lossy_us = {}
     for max_ranges in (64, 4096):
         rep = torch.zeros(32 + 16 * max_ranges, dtype=torch.uint8, device="cuda")
-        lossy_us[max_ranges] = launch_time_us(pkg, torch, lambda: pkg.uccl_dedup_report(lossy, n_bits, rep, max_ranges))
+        lossy_us[max_ranges] = launch_time_us(pkg, torch, lambda k: pkg.uccl_dedup_report(lossy, n_bits, rep, max_ranges))
         h = rep.cpu().numpy()
         if len(holes):
             assert int(h[:8].view(np.uint64)[0]) == 50 and int(h[8:16].view(np.uint64)[0]) == n_bits - len(holes)
@@ -414,7 +417,7 @@ def time_feedback_kernels(pkg, torch, bitmap, n_bits):
     win[: 64 * 8] = -1                                   # half of the slots complete
     n_chunks = torch.full((128,), 200, dtype=torch.int32, device="cuda")
     status = torch.zeros(128 * 4, dtype=torch.int32, device="cuda")
-    status_us = launch_time_us(pkg, torch, lambda: pkg.uccl_message_status(win, n_chunks, 128, 256, status, False))
+    status_us = launch_time_us(pkg, torch, lambda k: pkg.uccl_message_status(win, n_chunks, 128, 256, status, False))
     assert int(status.view(128, 4)[:, 2].sum()) == 64
     return report_us, status_us, {"holes": int(len(holes)), "median_us_by_max_ranges": {str(k): round(v, 2) for k, v in lossy_us.items()}}
 
@@ -424,7 +427,20 @@ PROBE_MODES = {"read_1r": (0, 1), "write_1w": (1, 1), "copy_1r1w": (2, 2), "redu
                "copy_forward_1r2w": (4, 3), "reduce_keep_2r1w": (5, 3)}
 
 
-def stream_ceilings(torch, sets, stream_bytes, block_bytes, gather_sources=0, reps=20):
+def back_to_back_s(torch, run, reps):
+    """Seconds per launch of run(k), k = 0 .. reps-1 queued back to back (after four warm-up launches)."""
+    for k in range(4):
+        run(k)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record()
+    for k in range(reps):
+        run(k)
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e-3 / reps
+
+
+def stream_ceilings(torch, sets, stream_bytes, block_bytes, gather_sources=0, reps=20, window_blocks=0):
     """What the memory system of this GPU delivers for the data path's traffic shapes with nothing
     in the way: dense kernels (no records, no dedup, no scatter; paper_2504_17307_amd/probe) over the
     workload's own buffers, `stream_bytes` per stream (the dominant call's payload), one
@@ -459,17 +475,30 @@ def stream_ceilings(torch, sets, stream_bytes, block_bytes, gather_sources=0, re
             rc = fn(mode, s["recv"].data_ptr(), s["acc"].data_ptr(), stage.data_ptr(), nbytes, block,
                     gather_sources, None, stream)
             assert rc == 0, f"probe mode {name} refused"
-        for k in range(4):
-            run(k)
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        a.record()
-        for k in range(reps):
-            run(k)
-        b.record()
-        torch.cuda.synchronize()
-        out[name + "_GBps"] = round(n_streams * nbytes * reps / (a.elapsed_time(b) * 1e-3) / 1e9, 1)
+        out[name + "_GBps"] = round(n_streams * nbytes / back_to_back_s(torch, run, reps) / 1e9, 1)
+    if window_blocks > 1 and "reduce_forward_2r2w" in modes and nbytes >= 2 * block:
+        # the same two forwarding shapes with destinations scattered the way arrivals are: block b of the
+        # slot stream goes to a random block of the accumulator / staging streams within its reorder window
+        scat = ctypes.CDLL(PROBE_LIB).uccl_probe_scattered
+        scat.restype = ctypes.c_int
+        scat.argtypes = [ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_uint64, ctypes.c_uint32,
+                         ctypes.c_void_p, ctypes.c_void_p]
+        n_blocks = nbytes // block
+        rng = np.random.default_rng(7)
+        perm = np.arange(n_blocks, dtype=np.uint32)
+        for lo in range(0, n_blocks, window_blocks):
+            rng.shuffle(perm[lo:lo + window_blocks])
+        perm_dev = torch.from_numpy(perm.view(np.int32)).cuda()
+        for name, mode, n_streams in (("reduce_forward_2r2w_scattered", 3, 4), ("copy_forward_1r2w_scattered", 4, 3)):
+            def run_scattered(k):
+                s = sets[k % len(sets)]
+                rc = scat(mode, s["recv"].data_ptr(), s["acc"].data_ptr(), s["out"].data_ptr(), n_blocks * block, block,
+                          perm_dev.data_ptr(), stream)
+                assert rc == 0, f"probe mode {name} refused"
+            out[name + "_GBps"] = round(n_streams * n_blocks * block / back_to_back_s(torch, run_scattered, reps) / 1e9, 1)
     out["what"] = (f"dense kernels of the path's traffic shapes: {nbytes} bytes per stream, {block}-byte block per "
-                   f"workgroup, the workload's own buffers rotating over {len(sets)} sets, same run")
+                   f"workgroup, the workload's own buffers rotating over {len(sets)} sets, same run"
+                   + (f"; `_scattered`: destination blocks permuted within windows of {window_blocks} blocks" if window_blocks > 1 else ""))
     return out
 
 
@@ -511,12 +540,7 @@ def bench_segment(args, pkg, torch):
             step(k)
         torch.cuda.synchronize()
         per = (time.perf_counter() - t0) / args.steps
-        turn = [0]
-
-        def one():
-            turn[0] += 1
-            step(turn[0])
-        kernel_us = launch_time_us(pkg, torch, one)
+        kernel_us = launch_time_us(pkg, torch, lambda k: step(k + 1))
         algo = 2 * seg_bytes + 16 * n
         rows[shape] = dict(segment_bytes=seg_bytes, chunk_bytes=chunk, chunks=n, ms_per_step=round(per * 1e3, 4),
                            payload_GBps=round(seg_bytes / per / 1e9, 1), kernel_us=round(kernel_us, 2),
@@ -549,6 +573,11 @@ def bench_calls(args, pkg, torch):
     sets = [dict(acc=torch.zeros(most, dtype=torch.uint8, device="cuda"), recv=torch.ones(most, dtype=torch.uint8, device="cuda"),
                  out=torch.zeros(most, dtype=torch.uint8, device="cuda"), bm=torch.zeros(8192 // 32, dtype=torch.int32, device="cuda"))
             for _ in range(n_sets)]
+    def call_us(call, n_bits):
+        """Median kernel time of call(buffer set); the bitmap reset before it is a launch of its own."""
+        return round(launch_time_us(pkg, torch, lambda k: call(sets[k % n_sets]), reps=args.steps, skip=args.warmup,
+                                    before=lambda k: pkg.uccl_dedup_reset(sets[k % n_sets]["bm"], n_bits)), 2)
+
     rows = []
     for chunk, counts in sizes:
         for n in counts:
@@ -562,19 +591,8 @@ def bench_calls(args, pkg, torch):
             for label, parts in (("auto", 0), ("uncut", 1), ("parts8", 8), ("parts16", 16)):
                 if parts > 1 and (chunk < (32 << 10) or n * parts > 4096):
                     continue   # a workgroup takes several records of smaller chunks: parts do not apply
-                # the bitmap reset is a launch of its own: the events are attached to the apply call only
-                evs = []
-                for k in range(args.steps):
-                    s = sets[k % n_sets]
-                    pkg.uccl_dedup_reset(s["bm"], n)
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record()
-                    b.record()
-                    pkg.uccl_time_next_launch(a, b)
-                    pkg.uccl_chunk_apply_opts(s["acc"], s["out"], s["recv"], recs, n, s["bm"], F32, SUM, opts=(chunk, parts))
-                    evs.append((a, b))
-                torch.cuda.synchronize()
-                row[label + "_us"] = round(float(np.median([a.elapsed_time(b) for a, b in evs[args.warmup:]])) * 1e3, 2)
+                row[label + "_us"] = call_us(lambda s: pkg.uccl_chunk_apply_opts(
+                    s["acc"], s["out"], s["recv"], recs, n, s["bm"], F32, SUM, opts=(chunk, parts)), n)
             rows.append(row)
     # the multi-source fold (seven senders per destination chunk) on calls of few records
     GATHER = np.dtype([("dst_off", "<u8"), ("out_off", "<u8"), ("len", "<u4"), ("seq", "<u4"), ("n_src", "<u4"),
@@ -593,18 +611,8 @@ def bench_calls(args, pkg, torch):
             recs = to_dev(torch, d)
             row = dict(chunk_bytes=chunk, records=n, sources=n_src, algorithmic_bytes=n * ((n_src + 2) * chunk + 164))
             for label, parts in (("auto", 0), ("uncut", 1)):
-                evs = []
-                for k in range(args.steps):
-                    s = sets[k % n_sets]
-                    pkg.uccl_dedup_reset(s["bm"], n)
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record()
-                    b.record()
-                    pkg.uccl_time_next_launch(a, b)
-                    pkg.uccl_chunk_reduce_gather(s["acc"], None, s["recv"], recs, n, s["bm"], F32, SUM, opts=(chunk, parts))
-                    evs.append((a, b))
-                torch.cuda.synchronize()
-                row[label + "_us"] = round(float(np.median([a.elapsed_time(b) for a, b in evs[args.warmup:]])) * 1e3, 2)
+                row[label + "_us"] = call_us(lambda s: pkg.uccl_chunk_reduce_gather(
+                    s["acc"], None, s["recv"], recs, n, s["bm"], F32, SUM, opts=(chunk, parts)), n)
             gather_rows.append(row)
     ok = pkg.uccl_claim_timeouts() == 0
     big = rows[-1]
@@ -900,8 +908,9 @@ def main():
     stream_ceiling = None
     if not args.no_ceilings:  # last: the dense kernels overwrite the accumulators and staging buffers
         n_src = int(calls[0]["descs"]["n_src"].max()) if calls[0].get("gather") else 0
+        reorder_window = {"config2": 1024, "config3": 256}.get(args.workload, 0)   # in chunks, as the recipe states
         stream_ceiling = stream_ceilings(torch, sets, max(dom["payload_bytes"] // max(n_src, 1), 2048),
-                                         max(collective_chunk, 32 << 10), n_src)
+                                         max(collective_chunk, 32 << 10), n_src, window_blocks=reorder_window)
     if args.calibration_copy:
         calibration_copy(torch)
 

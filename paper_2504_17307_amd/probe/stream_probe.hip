@@ -36,13 +36,21 @@ __device__ __forceinline__ u32x4 add_f32(u32x4 a, u32x4 r) {
   return t;
 }
 
+// `perm` (may be null): block b of the slot stream goes to block perm[b] of the accumulator and
+// staging streams, the way arrivals go to scattered destinations (whole blocks only).
 template <int MODE>
 __global__ void __launch_bounds__(1024) stream_probe_kernel(const u32x4* __restrict__ slot, u32x4* __restrict__ acc,
                                                             u32x4* __restrict__ stage, uint64_t total_vecs,
-                                                            uint32_t block_vecs, uint32_t* sink) {
+                                                            uint32_t block_vecs, uint32_t* sink,
+                                                            const uint32_t* __restrict__ perm) {
   constexpr uint32_t kUnit = 128;  // vectors per unit: 64 lanes x 2
   const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
   const uint64_t base = static_cast<uint64_t>(blockIdx.x) * block_vecs;
+  if (perm != nullptr) {
+    const int64_t shift = (static_cast<int64_t>(perm[blockIdx.x]) - static_cast<int64_t>(blockIdx.x)) * block_vecs;
+    acc += shift;
+    stage += shift;
+  }
   uint32_t fold = 0;
   for (uint32_t u = wave * kUnit; u < block_vecs; u += 16 * kUnit) {
     const uint64_t v0 = base + u + lane, v1 = v0 + 64;
@@ -112,13 +120,14 @@ __global__ void __launch_bounds__(1024) gather_probe_kernel(const u32x4* __restr
 
 template <int MODE>
 hipError_t launch(const void* slot, void* acc, void* stage, uint64_t bytes, uint32_t block_bytes, uint32_t* sink,
-                  hipStream_t s) {
+                  hipStream_t s, const uint32_t* perm = nullptr) {
   const uint64_t total_vecs = bytes / 16;
   const uint32_t block_vecs = block_bytes / 16;
   const uint64_t blocks = (total_vecs + block_vecs - 1) / block_vecs;
   if (blocks == 0 || blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
   stream_probe_kernel<MODE><<<dim3(static_cast<uint32_t>(blocks)), dim3(1024), 0, s>>>(
-      static_cast<const u32x4*>(slot), static_cast<u32x4*>(acc), static_cast<u32x4*>(stage), total_vecs, block_vecs, sink);
+      static_cast<const u32x4*>(slot), static_cast<u32x4*>(acc), static_cast<u32x4*>(stage), total_vecs, block_vecs, sink,
+      perm);
   return hipGetLastError();
 }
 
@@ -151,5 +160,20 @@ extern "C" int uccl_probe_stream(int mode, const void* slot, void* acc, void* st
     case kCopyFwd: e = launch<kCopyFwd>(slot, acc, stage, bytes, block_bytes, sink, s); break;
     case kReduceKeep: e = launch<kReduceKeep>(slot, acc, stage, bytes, block_bytes, sink, s); break;
   }
+  return e == hipSuccess ? 0 : -1;
+}
+
+// The reduce-and-forward (mode 3) and copy-and-forward (mode 4) shapes with scattered destinations:
+// block b of the slot stream is combined into block perm[b] of acc and stage.  perm: DEVICE array of
+// bytes / block_bytes entries, a permutation of 0 .. bytes / block_bytes - 1 (not checked); bytes
+// must be a multiple of block_bytes.  Returns 0, or -1 for bad arguments / a refused launch.
+extern "C" int uccl_probe_scattered(int mode, const void* slot, void* acc, void* stage, uint64_t bytes,
+                                    uint32_t block_bytes, const uint32_t* perm, void* stream) {
+  if ((mode != kReduceFwd && mode != kCopyFwd) || bytes == 0 || block_bytes == 0 || (block_bytes % 2048) ||
+      (bytes % block_bytes) || perm == nullptr)
+    return -1;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const hipError_t e = mode == kReduceFwd ? launch<kReduceFwd>(slot, acc, stage, bytes, block_bytes, nullptr, s, perm)
+                                          : launch<kCopyFwd>(slot, acc, stage, bytes, block_bytes, nullptr, s, perm);
   return e == hipSuccess ? 0 : -1;
 }
