@@ -37,11 +37,11 @@ METRIC = "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk s
 # kernel source it was measured on, identified by the hash of the HIP source files.
 MEASURED_TRAFFIC = {
     # (workload, source_hash() of the files under csrc/): bytes per launch
-    ("config1", "c6abf0d6d21601ff"): 14888083,
-    ("config2", "c6abf0d6d21601ff"): 1008018040,
-    ("config3", "c6abf0d6d21601ff"): 3625035711,
-    ("config4", "c6abf0d6d21601ff"): 108259459,
-    ("direct-rs", "c6abf0d6d21601ff"): 1208247125,
+    ("config1", "aa439b6db27867ca"): 14886081,
+    ("config2", "aa439b6db27867ca"): 1007987344,
+    ("config3", "aa439b6db27867ca"): 3625024139,
+    ("config4", "aa439b6db27867ca"): 108272676,
+    ("direct-rs", "aa439b6db27867ca"): 1208246789,
 }
 
 WORKLOADS = {

@@ -14,11 +14,12 @@
 // load one 32-byte record with two 128-bit loads, validate it, and test-and-set its bit
 // with one device-scope atomic OR; the returned old word tells the lane whether it is the
 // first arrival.  A wave ballot compacts the winners into LDS and a wave scan numbers
-// their 2 KiB units.  After one barrier the 16 wavefronts take units round-robin and
-// stream them with 128-bit loads and stores: every thread issues all its loads, then
-// combines, then stores, and the workgroup retires.  Duplicates cost their record and one
-// atomic, nothing else.  Two lanes holding the same seq each issue their own atomic, so
-// the hardware serialises them and exactly one sees the bit clear.
+// their units (2 KiB; 1 KiB where a workgroup reduces a single record).  After one barrier
+// the 16 wavefronts take units round-robin and stream them with 128-bit loads and stores:
+// every thread issues all loads of a unit, then combines, then stores, and the workgroup
+// retires.  Duplicates cost their record and one atomic, nothing else.  Two lanes holding
+// the same seq each issue their own atomic, so the hardware serialises them and exactly one
+// sees the bit clear.
 //
 // Calls of few records (Appendix C.4: small messages are where fixed costs show) take another
 // kernel, which shortens the chain of latencies instead: one record per workgroup, payload
@@ -329,7 +330,11 @@ int launch_flat_tile(Args& a, hipStream_t s, const Tuning& tune) {
   if (a.n_descs < kFewRecords)
     return launch_kernel(chunk_few_kernel<UCCL_FEW_THREADS, UCCL_FEW_UNROLL, Op, false>, a.n_descs,
                          UCCL_FEW_THREADS, s, a);
-  return launch_flat<1, UCCL_FLAT_UNROLL, Op>(a, s);
+  // One record per workgroup.  Kernels that read the accumulator take 1 KiB units here (a wavefront
+  // makes two trips through a 32 KiB chunk, eight through a 128 KiB one, its stores of one trip
+  // between the loads of two): measured 0.7 % faster on 32 KiB chunks and 1.9 % on 128 KiB ones
+  // than 2 KiB units; copies are 5 % slower that way and keep 2 KiB units.
+  return launch_flat<1, Op::kReadsAcc ? UCCL_FLAT1_REDUCE_UNROLL : UCCL_FLAT_UNROLL, Op>(a, s);
 }
 
 template <int T, class Op>

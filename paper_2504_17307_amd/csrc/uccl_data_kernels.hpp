@@ -19,6 +19,9 @@
 #ifndef UCCL_FLAT_UNROLL
 #define UCCL_FLAT_UNROLL 2    // vectors per lane per unit: a unit is 64*U*16 bytes per stream
 #endif
+#ifndef UCCL_FLAT1_REDUCE_UNROLL
+#define UCCL_FLAT1_REDUCE_UNROLL 1  // the same for one-record tiles of kernels that read the accumulator
+#endif
 #ifndef UCCL_FEW_THREADS
 #define UCCL_FEW_THREADS 1024   // calls of few records: one workgroup per record
 #endif
