@@ -137,7 +137,11 @@ typedef struct uccl_launch_opts {
  * workgroups per record so that it fills the machine; those workgroups
  * agree on the record's fate through one 64-bit claim word per record (on a 128-byte line of its
  * own) in a pool the library allocates once per device (16 MiB + 8 bytes, hipMalloc at the first
- * such call or in uccl_init, kept until the process ends).  If the pool cannot be had, or the stream is being
+ * such call or in uccl_init, kept until the process ends).  The pool has one region per stream
+ * handle, for the first 64 handles that issue such a call on the device; a region is never given
+ * back, so do not destroy a stream while such a call is still running on it (a stream created
+ * next may be given the same handle, and with it the region).  If the pool cannot be had, the
+ * stream is the 65th or later, or the stream is being
  * captured into a graph, the call is launched with one workgroup per record instead: slower,
  * same result.  Apart from that one-time allocation no data-path call allocates.
  */
