@@ -315,14 +315,15 @@ def bench_graph_feed(args, pkg, torch):
         slots[i % K]["done"].synchronize()
         lat.append(time.perf_counter() - t0)
     # the same with two eager calls per message and device-resident records
-    d_dev = [(to_dev(torch, m["rs"]), to_dev(torch, m["ag"])) for m in msgs[:300]]
+    eager = lambda m, k, op: pkg.uccl_prepare(pkg.uccl_chunk_apply, acc, out, recv, to_dev(torch, m[k]), len(m[k]), bitmap, F32, op)
+    d_dev = [(eager(m, "rs", SUM), eager(m, "ag", COPY)) for m in msgs[:300]]
     lat_eager = []
     pkg.uccl_dedup_reset(bitmap, w.n_bits)
     torch.cuda.synchronize()
-    for i, (a, b) in enumerate(d_dev):
+    for a, b in d_dev:
         t0 = time.perf_counter()
-        pkg.uccl_chunk_apply(acc, out, recv, a, raw[i][2], bitmap, F32, SUM)
-        pkg.uccl_chunk_apply(acc, out, recv, b, raw[i][3], bitmap, F32, COPY)
+        a()
+        b()
         torch.cuda.synchronize()
         lat_eager.append(time.perf_counter() - t0)
     result, ok = small_message_result("config5-graph", args, w, msgs, per_msg, reps, first,
@@ -336,14 +337,17 @@ def bench_feed(args, pkg, torch):
     from synth.layout import SUM, COPY, F32
     w, msgs, acc, recv, out, bitmap = small_message_job(args, torch)
     feed = pkg.uccl_feed_create(acc, out, recv, bitmap, F32, SUM, COPY, 65536, 8)
-    recs = [(np.ascontiguousarray(m["rs"]), np.ascontiguousarray(m["ag"])) for m in msgs]
+    # every push marshalled once (pkg.uccl_prepare): what is timed is the C calls, as a native control path makes them
+    recs = [tuple(pkg.uccl_prepare(pkg.uccl_feed_push, feed, lane, np.ascontiguousarray(m[k])) for lane, k in ((0, "rs"), (1, "ag")))
+            for m in msgs]
+    poll = pkg.uccl_prepare(pkg.uccl_feed_poll, feed)
 
     def one_pass():
         pkg.uccl_dedup_reset(bitmap, w.n_bits)
         for rs, ag in recs:
-            pkg.uccl_feed_push(feed, 0, rs)
-            pkg.uccl_feed_push(feed, 1, ag)
-            pkg.uccl_feed_poll(feed)
+            rs()
+            ag()
+            poll()
         pkg.uccl_feed_sync(feed)
 
     one_pass()
@@ -360,8 +364,8 @@ def bench_feed(args, pkg, torch):
     torch.cuda.synchronize()
     for rs, ag in recs[:300]:
         t0 = time.perf_counter()
-        pkg.uccl_feed_push(feed, 0, rs)
-        pkg.uccl_feed_push(feed, 1, ag)
+        rs()
+        ag()
         pkg.uccl_feed_sync(feed)
         lat.append(time.perf_counter() - t0)
     pkg.uccl_feed_destroy(feed)
@@ -704,6 +708,7 @@ def parse_args():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--sets", type=int, default=4, help="buffer sets the steps rotate over")
     ap.add_argument("--messages", type=int, default=10000, help="config5: number of messages")
+    ap.add_argument("--no-prepare", action="store_true", help="marshal every call's arguments anew instead of once")
     ap.add_argument("--streams", type=int, default=1,
                     help="config5: issue consecutive message batches round-robin on this many streams "
                          "(batches are independent of each other; the two calls of a batch stay ordered)")
@@ -733,11 +738,9 @@ def parse_args():
                          "allocations, to move the streams' relative alignment in the memory channels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true", help="skip the dense streaming kernels")
-    ap.add_argument("--also-warm", action="store_true",
-                    help="additionally time the same loop over a single buffer set (cache-resident accumulator)")
+    ap.add_argument("--also-warm", action="store_true", help="also time the loop over one buffer set (cache resident)")
     ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one plain 1 GiB device-to-device copy (a kernel of known traffic that "
-                         "hardware counters of the same run can be scaled by)")
+                    help="also run one plain 1 GiB device-to-device copy (known traffic to scale hardware counters by)")
     return ap.parse_args()
 
 
@@ -752,10 +755,8 @@ def main():
 
     import torch
     import paper_2504_17307_amd as pkg
-
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    pkg.load()
-    pkg.uccl_init()
+    pkg.uccl_init()   # loads the library (raises if it is not built) and makes its scratch memory
     if args.workload == "config5-graph":
         return bench_graph_feed(args, pkg, torch)
     if args.workload == "config5-feed":
@@ -793,21 +794,31 @@ def main():
                 return call_on_current(i, s)
         return call_on_current(i, s)
 
+    # arguments are marshalled once per (call, buffer set) (pkg.uccl_prepare), unless the stream changes between calls
+    prepared = {} if streams is None and not args.graph and not args.no_prepare else None
+
     def call_on_current(i, s):
         c = calls[i]
         bm = bitmap2 if c.get("bm") == "bitmap2" else bitmap
         rec = 160 if c.get("gather") else 32
         per = args.records_per_call or counts[i]
         for lo in range(0, counts[i], max(per, 1)):
+            if prepared is not None and (i, lo, id(s)) in prepared:
+                prepared[(i, lo, id(s))]()
+                continue
             n = min(per, counts[i] - lo)
             d = descs[i][lo * rec:(lo + n) * rec]
             if c.get("gather"):
-                pkg.uccl_chunk_reduce_gather(s["acc"], None, s["recv"], d, n, bm, w.dtype, c["op"], opts=opts)
+                f = (pkg.uccl_chunk_reduce_gather, s["acc"], None, s["recv"], d, n, bm, w.dtype, c["op"])
             elif c["scatter"]:
-                pkg.uccl_chunk_scatter_opts(s[c.get("dst", "acc")], s[c.get("src", "recv")], d, n, bm, opts=opts)
+                f = (pkg.uccl_chunk_scatter_opts, s[c.get("dst", "acc")], s[c.get("src", "recv")], d, n, bm)
             else:
-                pkg.uccl_chunk_apply_opts(s["acc"], s["out"], s[c.get("src", "recv")], d, n, bm, w.dtype, c["op"],
-                                          opts=opts)
+                f = (pkg.uccl_chunk_apply_opts, s["acc"], s["out"], s[c.get("src", "recv")], d, n, bm, w.dtype, c["op"])
+            if prepared is None:
+                f[0](*f[1:], opts=opts)
+            else:
+                prepared[(i, lo, id(s))] = pkg.uccl_prepare(*f, opts=opts)
+                prepared[(i, lo, id(s))]()
 
     def issue(k, timed=None):
         """Enqueue one step on buffer set k % len(sets)."""
@@ -832,6 +843,8 @@ def main():
     torch.cuda.synchronize()
     first = (sets[0]["acc"].cpu().numpy(), sets[0]["out"][:w.out_bytes].cpu().numpy(),
              bitmap.cpu().numpy().view(np.uint32))
+    for k in range(1, len(sets) if prepared is not None else 0):   # marshal the other sets' calls before anything is timed
+        issue(k)
 
     graphs = None
     if args.graph:
@@ -932,12 +945,11 @@ def main():
                        "algorithmic_bytes": algo, "parts": args.parts, "chunk_hint": opts[0], "buffer_sets": len(sets),
                        "forward_only_intermediate_steps": bool(args.relay), "two_pass": bool(args.two_pass),
                        "packet_bytes": args.packet_bytes or None, "graph_replay": bool(args.graph),
-                       "stagger_bytes": args.stagger or None,
+                       "stagger_bytes": args.stagger or None, "prepared_calls": prepared is not None,
                        "calls_per_step": 1 + sum(-(-n // (args.records_per_call or max(n, 1))) for n in counts),
                        "records_per_call": args.records_per_call or None, "streams": args.streams, "cache": cache_note})
     result.update({
-        "chunks_per_s": round(unique / per_step, 1),
-        "arrivals_per_s": round(arrivals / per_step, 1),
+        "chunks_per_s": round(unique / per_step, 1), "arrivals_per_s": round(arrivals / per_step, 1),
         "step_hbm_frac": round(algo / per_step / 1e9 / PEAK_HBM_GBS, 4),
         "warm_cache": None if warm_elapsed is None else {
             "ms_per_step": round(warm_elapsed / args.steps * 1e3, 4),
@@ -948,13 +960,10 @@ def main():
             "bound": "hbm",
             "kernel": f"{kernel_name}, {dom['call']} call ({dom['op']})",
             "basis": "the dominant kernel's own duration" if per_kernel else "whole step (no per-kernel attribution in this mode)",
-            "achieved": round(achieved, 1),
-            "peak": PEAK_HBM_GBS,
-            "unit": "GB/s",
+            "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
             "frac": round(achieved / PEAK_HBM_GBS, 4),
             "traffic": MEASURED_TRAFFIC.get((args.workload, source_hash())),
-            "algorithmic_bytes_per_launch": dom["algorithmic_bytes"],
-            "avg_launch_ms": dom["avg_ms"] if per_kernel else None,
+            "algorithmic_bytes_per_launch": dom["algorithmic_bytes"], "avg_launch_ms": dom["avg_ms"] if per_kernel else None,
         },
         "kernels": kernels if per_kernel else [],
         # the reduce phase alone (its call's unique payload over its kernel's own duration)

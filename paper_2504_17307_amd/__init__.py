@@ -9,6 +9,7 @@ There is no CPU fallback: if the shared library cannot be loaded, load() raises.
 """
 import ctypes as C
 import os
+import threading
 
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libuccl_chunk.so")
@@ -155,6 +156,43 @@ def _check(code, what):
         raise UcclError(code, what)
 
 
+_tls = threading.local()
+
+
+def _call(name, *cargs):
+    """Make the C call with marshalled arguments, or, inside uccl_prepare, hand the call back instead."""
+    fn = getattr(load(), name)
+    pending = getattr(_tls, "pending", None)
+    if pending is not None:
+        pending.append((fn, cargs, name))
+        return
+    _check(fn(*cargs), name)
+
+
+def uccl_prepare(func, *args, **kwargs):
+    """Marshal a call once, enqueue it many times (a control path that issues two small calls per
+    message spends as long turning tensors into pointers as the launch itself takes).  ``func`` is
+    one of this module's functions that make exactly one C call (uccl_chunk_apply*,
+    uccl_chunk_scatter*, uccl_chunk_reduce_gather, uccl_chunk_segment, uccl_dedup_reset,
+    uccl_dedup_report, uccl_message_status); the result is a zero-argument callable that makes that
+    C call with the same pointers, sizes and stream handle every time: the stream is the one given,
+    or torch's current one, WHEN THE CALL WAS PREPARED.  The callable keeps the arguments alive."""
+    _tls.pending = []
+    try:
+        func(*args, **kwargs)
+        (fn, cargs, name), = _tls.pending
+    finally:
+        _tls.pending = None
+
+    def enqueue():
+        code = fn(*cargs)
+        if code != UCCL_OK:
+            raise UcclError(code, name)
+
+    enqueue.keeps = (args, kwargs)
+    return enqueue
+
+
 def _extents(extents, acc, out_stage, recv_stage, n_bits):
     if extents is not None:
         return extents
@@ -180,15 +218,13 @@ def _opts(opts):
 
 
 def uccl_chunk_apply(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, stream=None):
-    _check(load().uccl_chunk_apply(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
-                                   int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op),
-                                   _stream(stream)), "uccl_chunk_apply")
+    _call("uccl_chunk_apply", _ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs), int(n_descs),
+          _ptr(dedup_bitmap), int(dtype), int(op), _stream(stream))
 
 
 def uccl_chunk_apply_noalloc(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op, stream=None):
-    _check(load().uccl_chunk_apply_noalloc(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
-                                           int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op),
-                                           _stream(stream)), "uccl_chunk_apply_noalloc")
+    _call("uccl_chunk_apply_noalloc", _ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
+          int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op), _stream(stream))
 
 
 def uccl_chunk_apply_checked(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op,
@@ -196,10 +232,9 @@ def uccl_chunk_apply_checked(acc, out_stage, recv_stage, descs, n_descs, dedup_b
     """``extents`` is a uccl_extents; when None it is filled from the tensors' sizes and
     ``n_bits`` (the bitmap's valid bit count)."""
     e = _extents(extents, acc, out_stage, recv_stage, n_bits)
-    _check(load().uccl_chunk_apply_checked(_ptr(acc), _ptr(out_stage), _ptr(recv_stage),
-                                           _ptr(descs), int(n_descs), _ptr(dedup_bitmap),
-                                           int(dtype), int(op), C.byref(e), _ptr(n_rejected),
-                                           _stream(stream)), "uccl_chunk_apply_checked")
+    _call("uccl_chunk_apply_checked", _ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
+          int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op), C.byref(e), _ptr(n_rejected),
+          _stream(stream))
 
 
 def uccl_chunk_apply_opts(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op,
@@ -209,9 +244,8 @@ def uccl_chunk_apply_opts(acc, out_stage, recv_stage, descs, n_descs, dedup_bitm
     e = None
     if extents is not None or n_bits is not None:
         e = C.byref(_extents(extents, acc, out_stage, recv_stage, n_bits))
-    _check(load().uccl_chunk_apply_opts(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
-                                        int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op), e,
-                                        _ptr(n_rejected), _opts(opts), _stream(stream)), "uccl_chunk_apply_opts")
+    _call("uccl_chunk_apply_opts", _ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs), int(n_descs),
+          _ptr(dedup_bitmap), int(dtype), int(op), e, _ptr(n_rejected), _opts(opts), _stream(stream))
 
 
 def uccl_chunk_apply_indirect(acc, out_stage, recv_stage, descs, n_descs_ptr, max_descs, dedup_bitmap,
@@ -221,10 +255,9 @@ def uccl_chunk_apply_indirect(acc, out_stage, recv_stage, descs, n_descs_ptr, ma
     e = None
     if extents is not None or n_bits is not None:
         e = C.byref(_extents(extents, acc, out_stage, recv_stage, n_bits))
-    _check(load().uccl_chunk_apply_indirect(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
-                                            _ptr(n_descs_ptr), int(max_descs), _ptr(dedup_bitmap),
-                                            int(dtype), int(op), e, _ptr(n_rejected), _opts(opts),
-                                            _stream(stream)), "uccl_chunk_apply_indirect")
+    _call("uccl_chunk_apply_indirect", _ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
+          _ptr(n_descs_ptr), int(max_descs), _ptr(dedup_bitmap), int(dtype), int(op), e, _ptr(n_rejected),
+          _opts(opts), _stream(stream))
 
 
 def uccl_chunk_reduce_gather(acc, out_stage, recv_stage, descs, n_descs, dedup_bitmap, dtype, op,
@@ -232,24 +265,21 @@ def uccl_chunk_reduce_gather(acc, out_stage, recv_stage, descs, n_descs, dedup_b
     e = None
     if extents is not None or n_bits is not None:
         e = C.byref(_extents(extents, acc, out_stage, recv_stage, n_bits))
-    _check(load().uccl_chunk_reduce_gather(_ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
-                                           int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op), e,
-                                           _ptr(n_rejected), _opts(opts), _stream(stream)),
-           "uccl_chunk_reduce_gather")
+    _call("uccl_chunk_reduce_gather", _ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(descs),
+          int(n_descs), _ptr(dedup_bitmap), int(dtype), int(op), e, _ptr(n_rejected), _opts(opts),
+          _stream(stream))
 
 
 def uccl_chunk_scatter(dst, recv_stage, descs, n_descs, dedup_bitmap, stream=None):
-    _check(load().uccl_chunk_scatter(_ptr(dst), _ptr(recv_stage), _ptr(descs), int(n_descs),
-                                     _ptr(dedup_bitmap), _stream(stream)), "uccl_chunk_scatter")
+    _call("uccl_chunk_scatter", _ptr(dst), _ptr(recv_stage), _ptr(descs), int(n_descs), _ptr(dedup_bitmap),
+          _stream(stream))
 
 
 def uccl_chunk_scatter_checked(dst, recv_stage, descs, n_descs, dedup_bitmap, extents=None,
                                n_rejected=None, stream=None, n_bits=None):
     e = _extents(extents, dst, None, recv_stage, n_bits)
-    _check(load().uccl_chunk_scatter_checked(_ptr(dst), _ptr(recv_stage), _ptr(descs),
-                                             int(n_descs), _ptr(dedup_bitmap), C.byref(e),
-                                             _ptr(n_rejected), _stream(stream)),
-           "uccl_chunk_scatter_checked")
+    _call("uccl_chunk_scatter_checked", _ptr(dst), _ptr(recv_stage), _ptr(descs), int(n_descs),
+          _ptr(dedup_bitmap), C.byref(e), _ptr(n_rejected), _stream(stream))
 
 
 def uccl_chunk_scatter_opts(dst, recv_stage, descs, n_descs, dedup_bitmap, extents=None, n_rejected=None,
@@ -257,18 +287,17 @@ def uccl_chunk_scatter_opts(dst, recv_stage, descs, n_descs, dedup_bitmap, exten
     e = None
     if extents is not None or n_bits is not None:
         e = C.byref(_extents(extents, dst, None, recv_stage, n_bits))
-    _check(load().uccl_chunk_scatter_opts(_ptr(dst), _ptr(recv_stage), _ptr(descs), int(n_descs),
-                                          _ptr(dedup_bitmap), e, _ptr(n_rejected), _opts(opts),
-                                          _stream(stream)), "uccl_chunk_scatter_opts")
+    _call("uccl_chunk_scatter_opts", _ptr(dst), _ptr(recv_stage), _ptr(descs), int(n_descs),
+          _ptr(dedup_bitmap), e, _ptr(n_rejected), _opts(opts), _stream(stream))
 
 
 def uccl_init():
-    _check(load().uccl_init(), "uccl_init")
+    _call("uccl_init")
 
 
 def uccl_claim_timeouts() -> int:
     n = C.c_uint64(0)
-    _check(load().uccl_claim_timeouts(C.byref(n)), "uccl_claim_timeouts")
+    _call("uccl_claim_timeouts", C.byref(n))
     return n.value
 
 
@@ -278,52 +307,49 @@ SEND_DESC_BYTES = 16
 def uccl_chunk_segment(out_stage, tensor, tensor_off, nbytes, chunk_bytes, stage_off=0, slot_stride=None,
                        send_descs=None, conn_id=0, msg_id=0, first_csn=0, stream=None):
     """``send_descs``: a tensor (device or pinned host) with room for ceil(nbytes / chunk_bytes) 16-byte records, or None."""
-    _check(load().uccl_chunk_segment(_ptr(out_stage), _ptr(tensor), int(tensor_off), int(nbytes), int(chunk_bytes),
-                                     int(stage_off), int(chunk_bytes if slot_stride is None else slot_stride),
-                                     _ptr(send_descs), int(conn_id), int(msg_id), int(first_csn), _stream(stream)),
-           "uccl_chunk_segment")
+    _call("uccl_chunk_segment", _ptr(out_stage), _ptr(tensor), int(tensor_off), int(nbytes),
+          int(chunk_bytes), int(stage_off), int(chunk_bytes if slot_stride is None else slot_stride),
+          _ptr(send_descs), int(conn_id), int(msg_id), int(first_csn), _stream(stream))
 
 
 def uccl_dedup_reset(dedup_bitmap, n_bits, stream=None):
-    _check(load().uccl_dedup_reset(_ptr(dedup_bitmap), int(n_bits), _stream(stream)),
-           "uccl_dedup_reset")
+    _call("uccl_dedup_reset", _ptr(dedup_bitmap), int(n_bits), _stream(stream))
 
 
 def uccl_feed_create(acc, out_stage, recv_stage, dedup_bitmap, dtype, lane0_op, lane1_op, capacity_records,
                      n_slots, stream=None):
     """Returns an opaque feed handle (keep the tensors alive for as long as the feed is)."""
     h = C.c_void_p()
-    _check(load().uccl_feed_create(C.byref(h), _ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(dedup_bitmap),
-                                   int(dtype), int(lane0_op), int(lane1_op), int(capacity_records), int(n_slots),
-                                   _stream(stream)), "uccl_feed_create")
+    _call("uccl_feed_create", C.byref(h), _ptr(acc), _ptr(out_stage), _ptr(recv_stage), _ptr(dedup_bitmap),
+          int(dtype), int(lane0_op), int(lane1_op), int(capacity_records), int(n_slots), _stream(stream))
     return h
 
 
 def uccl_feed_push(feed, lane, host_records):
     """``host_records``: a contiguous numpy array of 32-byte records in host memory."""
-    _check(load().uccl_feed_push(feed, int(lane), host_records.ctypes.data, len(host_records)), "uccl_feed_push")
+    _call("uccl_feed_push", feed, int(lane), host_records.ctypes.data, len(host_records))
 
 
 def uccl_feed_poll(feed):
-    _check(load().uccl_feed_poll(feed), "uccl_feed_poll")
+    _call("uccl_feed_poll", feed)
 
 
 def uccl_feed_flush(feed):
-    _check(load().uccl_feed_flush(feed), "uccl_feed_flush")
+    _call("uccl_feed_flush", feed)
 
 
 def uccl_feed_sync(feed):
-    _check(load().uccl_feed_sync(feed), "uccl_feed_sync")
+    _call("uccl_feed_sync", feed)
 
 
 def uccl_feed_get_stats(feed) -> dict:
     s = uccl_feed_stats()
-    _check(load().uccl_feed_get_stats(feed, C.byref(s)), "uccl_feed_get_stats")
+    _call("uccl_feed_get_stats", feed, C.byref(s))
     return {k: getattr(s, k) for k, _ in uccl_feed_stats._fields_}
 
 
 def uccl_feed_destroy(feed):
-    _check(load().uccl_feed_destroy(feed), "uccl_feed_destroy")
+    _call("uccl_feed_destroy", feed)
 
 
 ACK_HEADER_BYTES = 32
@@ -331,21 +357,21 @@ ACK_HEADER_BYTES = 32
 
 def uccl_message_status(dedup_bitmap, n_chunks, n_slots, bits_per_slot, status, recycle=False, stream=None):
     """Per-slot {cum_ack, n_applied, complete, 0} of a connection's message window into `status`."""
-    _check(load().uccl_message_status(_ptr(dedup_bitmap), _ptr(n_chunks), int(n_slots), int(bits_per_slot),
-                                      _ptr(status), int(bool(recycle)), _stream(stream)), "uccl_message_status")
+    _call("uccl_message_status", _ptr(dedup_bitmap), _ptr(n_chunks), int(n_slots), int(bits_per_slot),
+          _ptr(status), int(bool(recycle)), _stream(stream))
 
 
 def uccl_dedup_report(dedup_bitmap, n_bits, report, max_ranges, stream=None):
     """``report``: a tensor of at least 32 + 16 * max_ranges bytes (device or pinned host)."""
-    _check(load().uccl_dedup_report(_ptr(dedup_bitmap), int(n_bits), _ptr(report), int(max_ranges),
-                                    _stream(stream)), "uccl_dedup_report")
+    _call("uccl_dedup_report", _ptr(dedup_bitmap), int(n_bits), _ptr(report), int(max_ranges),
+          _stream(stream))
 
 
 def uccl_time_next_launch(start_event, stop_event):
     """Events are torch.cuda.Event(enable_timing=True) objects (recorded once before, so
     that their HIP handles exist) or integer hipEvent_t handles."""
     h = lambda e: None if e is None else (e if isinstance(e, int) else e.cuda_event)
-    _check(load().uccl_time_next_launch(h(start_event), h(stop_event)), "uccl_time_next_launch")
+    _call("uccl_time_next_launch", h(start_event), h(stop_event))
 
 
 def uccl_strerror(code) -> str:

@@ -146,3 +146,22 @@ def test_product_never_touches_the_oracle():
         if fn.endswith((".py", ".c", ".h")):
             src = open(os.path.join(root, "oracle", fn)).read()
             assert "paper_2504_17307_amd" not in src and "uccl_chunk.h" not in src, fn
+
+
+def test_prepare_marshals_once_and_repeats_the_c_call():
+    """Host logic of pkg.uccl_prepare on calls that return before anything is enqueued."""
+    A, B, D, M = 0x10000, 0x20000, 0x30000, 0x40000
+    empty = pkg.uccl_prepare(pkg.uccl_chunk_apply, A, None, B, D, 0, M, 0, 0, stream=0)   # no records: a no-op
+    empty()
+    empty()
+    bad = pkg.uccl_prepare(pkg.uccl_chunk_apply_opts, A + 8, None, B, D, 1, M, 0, 0, opts=(4096, 0), stream=0)
+    for _ in range(2):                       # the prepared call fails the same way every time it is made
+        with pytest.raises(pkg.UcclError) as e:
+            bad()
+        assert e.value.code == pkg.UCCL_EALIGN
+    with pytest.raises(ValueError):          # a function that makes no C call cannot be prepared
+        pkg.uccl_prepare(lambda: None)
+    with pytest.raises(ValueError):          # nor one whose own marshalling fails; and neither leaves the
+        pkg.uccl_prepare(pkg.uccl_chunk_apply_checked, A, None, B, D, 1, M, 0, 0, stream=0)   # binding capturing
+    with pytest.raises(pkg.UcclError):       # an ordinary call is made, not captured
+        pkg.uccl_chunk_apply(A + 8, None, B, D, 1, M, 0, 0, stream=0)

@@ -922,3 +922,40 @@ def test_cut_records_from_several_host_threads_on_one_stream(gpu_lib):
             acc, out, bm, _ = run.results()
             assert_same(acc, eacc, f"acc, thread {a} call {b}"); assert_same(out, eout, f"out, thread {a} call {b}")
             assert_same(bm, ebm, f"bitmap, thread {a} call {b}")
+
+
+def test_prepared_calls_equal_the_marshalled_ones(gpu_lib):
+    """pkg.uccl_prepare marshals once; invoking the result makes the same C call again: two
+    passes over config 1 (reset + every phase), each checked against the oracle, then an error
+    code surfaces as the same exception."""
+    pkg = gpu_lib
+    w = wl.config1(seed=4)
+    say("prepared calls, config1")
+    eacc, eout, ebm = oracle_results(w)
+    run = DeviceRun(w)
+    acc0 = run.acc.clone()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):      # prepared on `side`: that is where every later invocation goes
+        reset = pkg.uccl_prepare(pkg.uccl_dedup_reset, run.bitmap, w.n_bits)
+        steps = [pkg.uccl_prepare(pkg.uccl_chunk_apply_opts, run.acc, run.out, run.recv, d, len(ph.descs), run.bitmap,
+                                  w.dtype, ph.op, n_rejected=run.rejected, n_bits=w.n_bits, opts=(64 << 10, 0))
+                 for ph, d in zip(w.phases, run.descs)]
+    for rep in range(2):
+        run.acc.copy_(acc0)
+        run.out.fill_(0xA5)
+        side.wait_stream(torch.cuda.current_stream())
+        reset()
+        for s in steps:
+            s()
+        side.synchronize()
+        acc, out, bm, rej = run.results()
+        assert rej == 0 and pkg.uccl_claim_timeouts() == 0
+        assert_same(bm, ebm, f"bitmap, pass {rep}")
+        assert_same(acc, eacc, f"acc, pass {rep}")
+        assert_same(out, eout, f"out_stage, pass {rep}")
+    bad = pkg.uccl_prepare(pkg.uccl_chunk_apply, run.acc, run.out, run.recv, run.descs[0], 1, run.bitmap, 99, SUM)
+    with pytest.raises(pkg.UcclError) as e:
+        bad()
+    assert e.value.code == pkg.UCCL_EINVAL
+    with pytest.raises(ValueError):    # not exactly one C call
+        pkg.uccl_prepare(lambda: None)
