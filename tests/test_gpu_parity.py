@@ -313,6 +313,45 @@ def test_exactly_once_many_copies_everywhere(gpu_lib, opts, dtype):
     assert sum(bin(int(x)).count("1") for x in bm) == n
 
 
+DIFFER = [(None, 4096), (None, 65536), ((0, 1), 4096), ((0, 1), 65536), ((0, 5), 4096), ((0, 5), 65536),
+          ((0, 16), 65536), ((4096, 0), 4096), ((65536, 0), 65536)]
+
+
+@pytest.mark.parametrize("opts,C", DIFFER)
+def test_copies_that_differ_one_wins_whole(gpu_lib, opts, C):
+    """Which copy of a retransmitted chunk is applied is not defined; that it is ONE copy, whole, is.
+    Here the copies of a chunk break the rule that they are identical: copy j carries the value
+    j + 1 everywhere.  With acc zero and SUM every destination chunk must end up constant, equal
+    to one of its copies' values (a mix of two copies, or a sum of two, shows), the staging copy
+    equal to it; the oracle is not asked (it rejects such input), the check is closed form."""
+    n, copies = 48, 3
+    g = pl.rng(23, DIFFER.index((opts, C)))
+    arr = g.permutation(np.repeat(np.arange(n), copies))
+    which = np.zeros(len(arr), dtype=np.int64)            # arrival k is copy which[k] of chunk arr[k]
+    seen = np.zeros(n, dtype=np.int64)
+    for k, a in enumerate(arr):
+        which[k] = seen[a]
+        seen[a] += 1
+    d = np.zeros(len(arr), dtype=DESC)
+    d["src_off"] = np.arange(len(arr), dtype=np.uint64) * C
+    d["dst_off"] = arr.astype(np.uint64) * C
+    d["out_off"] = arr.astype(np.uint64) * C
+    d["len"] = C
+    d["seq"] = arr
+    recv = np.repeat((which + 1).astype(np.float32), C // 4)
+    acc0 = np.zeros(n * C // 4, dtype=np.float32)
+    w = wl.Workload("differ", F32, acc0, recv, n * C, n, [wl.Phase("p", SUM, d, n, n * C, 0)])
+    run = DeviceRun(w, opts=opts)
+    run.run_phases(split=lambda m: [m // 2])
+    acc, out, bm, rej = run.results()
+    assert rej == 0 and gpu_lib.uccl_claim_timeouts() == 0
+    chunks = acc.reshape(n, -1)
+    assert np.all(chunks == chunks[:, :1]), "a destination chunk mixes two copies"
+    assert set(np.unique(chunks[:, 0]).tolist()) <= {1.0, 2.0, 3.0}, np.unique(chunks[:, 0])
+    assert np.array_equal(out.view(np.float32), acc)
+    assert sum(bin(int(x)).count("1") for x in bm) == n
+
+
 @pytest.mark.parametrize("opts", [None, (0, 4)])
 def test_split_calls_equal_single_call(gpu_lib, opts):
     w = wl.config2(seed=5, M=8 << 20)
