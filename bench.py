@@ -37,11 +37,11 @@ METRIC = "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk s
 # kernel source it was measured on, identified by the hash of the HIP source files.
 MEASURED_TRAFFIC = {
     # (workload, source_hash() of the files under csrc/): bytes per launch
-    ("config1", "aa439b6db27867ca"): 14886081,
-    ("config2", "aa439b6db27867ca"): 1007987344,
-    ("config3", "aa439b6db27867ca"): 3625024139,
-    ("config4", "aa439b6db27867ca"): 108272676,
-    ("direct-rs", "aa439b6db27867ca"): 1208246789,
+    ("config1", "35ca5604592e0fae"): 14890510,
+    ("config2", "35ca5604592e0fae"): 1007974278,
+    ("config3", "35ca5604592e0fae"): 3625023353,
+    ("config4", "35ca5604592e0fae"): 108176972,
+    ("direct-rs", "35ca5604592e0fae"): 1208244727,
 }
 
 WORKLOADS = {
@@ -115,8 +115,8 @@ def kernel_label(n_records, chunk_hint, gather):
     """Which kernel the library launches for a call (the rule of launch_flat_tile in uccl_chunk.hip)."""
     if gather:
         return "chunk_gather_kernel"
-    tile = -(-32768 // chunk_hint) if chunk_hint else (1 if n_records < 8192 else 4)
-    return "chunk_few_kernel" if tile <= 1 and n_records < 512 else "chunk_flat_kernel"
+    few = 2048 if not chunk_hint or chunk_hint >= 32768 else 8192 if chunk_hint > 8192 else 129   # records below which
+    return "chunk_few_kernel" if n_records < few else "chunk_flat_kernel"
 
 
 def two_pass_calls(w, chunk, group=1):

@@ -270,8 +270,10 @@ uint32_t auto_parts(uint32_t n_descs, uint32_t chunk_bytes) {
 // small to fill the machine either way, and the shorter chain of latencies wins (kernel time, fp32
 // SUM with forward, 57 records: 4 KiB 4.7 -> 3.1 us, 8 KiB 5.3 -> 3.3 us, 16 KiB 5.6 -> 3.7 us; 128
 // records 15-30 % faster; 512 records of 4 or 8 KiB 15-45 % slower, hence the limit).  Chunks above
-// 8 KiB fill a 512-thread workgroup and keep an edge for much longer (16 KiB: 1024 records 15 %
-// faster, 4096 records 10 %, 8192 records 1 %).
+// 8 KiB fill a workgroup and keep an edge for much longer (16 KiB: 1024 records 15 % faster, 4096
+// records 10 %, 8192 records 1 %); one 16-byte vector per lane of a 1024-thread workgroup covers a
+// 16 KiB chunk in one trip and is 2-6 % faster than two vectors per lane of a 512-thread one
+// (all-to-all of 3 600 records 21.2 against 21.6 us, 1 024 reduced records 14.3 against 15.3 us).
 #ifndef UCCL_SMALL_CALL_RECORDS
 #define UCCL_SMALL_CALL_RECORDS 128
 #endif
@@ -285,7 +287,7 @@ template <class Op>
 int launch_flat_tile(Args& a, hipStream_t s, const Tuning& tune) {
   const uint32_t t = flat_tile(a.n_descs, tune.chunk_bytes);
   if (t >= 2 && tune.chunk_bytes > 8192u && a.n_descs < kHalfTileRecords)
-    return launch_kernel(chunk_few_kernel<512, 2, Op, false>, a.n_descs, 512, s, a);
+    return launch_kernel(chunk_few_kernel<1024, 1, Op, false>, a.n_descs, 1024, s, a);
   if (t >= 2 && tune.chunk_bytes != 0u && a.n_descs <= kSmallCallRecords) {
     // workgroup sized to the chunk: one trip of 16 bytes x unroll per lane covers it
     if (tune.chunk_bytes <= 4096u) return launch_kernel(chunk_few_kernel<256, 1, Op, false>, a.n_descs, 256, s, a);
