@@ -37,11 +37,11 @@ METRIC = "reduced payload GB/s (dedup+place+reduce+forward of one rank's chunk s
 # kernel source it was measured on, identified by the hash of the HIP source files.
 MEASURED_TRAFFIC = {
     # (workload, source_hash() of the files under csrc/): bytes per launch
-    ("config1", "35ca5604592e0fae"): 14890510,
-    ("config2", "35ca5604592e0fae"): 1007974278,
-    ("config3", "35ca5604592e0fae"): 3625023353,
-    ("config4", "35ca5604592e0fae"): 108176972,
-    ("direct-rs", "35ca5604592e0fae"): 1208244727,
+    ("config1", "c123f02476acd1e3"): 14883934,
+    ("config2", "c123f02476acd1e3"): 1007972699,
+    ("config3", "c123f02476acd1e3"): 3625022876,
+    ("config4", "c123f02476acd1e3"): 108173818,
+    ("direct-rs", "c123f02476acd1e3"): 1208245583,
 }
 
 WORKLOADS = {
@@ -109,14 +109,6 @@ def call_stats(descs, op):
     reads = ln if op == 3 else 2 * ln
     algo = int(reads.sum() + ln[~relay].sum() + ln[fwd].sum()) + 36 * len(descs)
     return len(first), int(ln.sum()), algo
-
-
-def kernel_label(n_records, chunk_hint, gather):
-    """Which kernel the library launches for a call (the rule of launch_flat_tile in uccl_chunk.hip)."""
-    if gather:
-        return "chunk_gather_kernel"
-    few = 2048 if not chunk_hint or chunk_hint >= 32768 else 8192 if chunk_hint > 8192 else 129   # records below which
-    return "chunk_few_kernel" if n_records < few else "chunk_flat_kernel"
 
 
 def two_pass_calls(w, chunk, group=1):
@@ -591,7 +583,7 @@ def bench_calls(args, pkg, torch):
             d["dst_off"] = d["out_off"] = perm.astype(np.uint64) * chunk
             d["len"], d["seq"] = chunk, perm
             recs = to_dev(torch, d)
-            row = dict(chunk_bytes=chunk, records=n, algorithmic_bytes=n * (4 * chunk + 36))
+            row = dict(chunk_bytes=chunk, records=n, algorithmic_bytes=n * (4 * chunk + 36), launch=pkg.uccl_launch_plan(n, (chunk, 0)))
             for label, parts in (("auto", 0), ("uncut", 1), ("parts8", 8), ("parts16", 16)):
                 if parts > 1 and (chunk < (32 << 10) or n * parts > 4096):
                     continue   # a workgroup takes several records of smaller chunks: parts do not apply
@@ -613,7 +605,8 @@ def bench_calls(args, pkg, torch):
             for j in range(n_src):
                 d["src_off"][:, j] = (j * n + np.arange(n, dtype=np.uint64)) * chunk
             recs = to_dev(torch, d)
-            row = dict(chunk_bytes=chunk, records=n, sources=n_src, algorithmic_bytes=n * ((n_src + 2) * chunk + 164))
+            row = dict(chunk_bytes=chunk, records=n, sources=n_src, algorithmic_bytes=n * ((n_src + 2) * chunk + 164),
+                       launch=pkg.uccl_launch_plan(n, (chunk, 0), gather=True))
             for label, parts in (("auto", 0), ("uncut", 1)):
                 row[label + "_us"] = call_us(lambda s: pkg.uccl_chunk_reduce_gather(
                     s["acc"], None, s["recv"], recs, n, s["bm"], F32, SUM, opts=(chunk, parts)), n)
@@ -937,7 +930,8 @@ def main():
     cache_note = ("buffers rotate over %d sets: HBM resident, not cache resident" % len(sets)
                   if (w.acc.nbytes + w.recv_stage.nbytes + w.out_bytes) * len(sets) > (1 << 30)
                   else "working set fits the 256 MB last-level cache: an effective, not an HBM, figure")
-    kernel_name = kernel_label(args.records_per_call or dom["records"], opts[0], calls[0].get("gather"))
+    kernel_name = pkg.uccl_launch_plan(args.records_per_call or dom["records"], (opts[0], args.parts), bool(calls[0].get("gather")),
+                                       dom["op"] != "COPY")["kernel"]   # what the library says it launches for the dominant call
 
     result = headline(args.workload, args, payload, per_step, args.steps, args.warmup,
                       {0: "f32", 1: "bf16", 2: "f16", 3: "i32"}[w.dtype],

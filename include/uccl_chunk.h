@@ -401,6 +401,27 @@ int uccl_feed_sync(uccl_feed* feed);
 int uccl_feed_get_stats(const uccl_feed* feed, uccl_feed_stats* stats);
 int uccl_feed_destroy(uccl_feed* feed);
 
+/* What a call of `n_descs` records with these options is launched as: which kernel, how many
+ * records a workgroup takes or how many workgroups a record, the workgroup size, the grid, and the
+ * bytes per stream one wavefront moves per trip.  Pure host arithmetic on the arguments (no GPU
+ * call, no state; the same rule the data-path calls apply), for tests, tuning and profiling tools.
+ * `gather` != 0: uccl_chunk_reduce_gather, else the apply / scatter family; `reads_acc` != 0: the
+ * op combines with the accumulator (anything but UCCL_COPY).  `parts` > 1 assumes that claim words
+ * are to be had (see "Scratch memory"); a call that finds none is launched with parts = 1.
+ * UCCL_EINVAL for a NULL `plan` or options the data-path calls would refuse.  Utility, no passage
+ * of the paper. */
+enum { UCCL_KERNEL_FLAT = 0, UCCL_KERNEL_FEW = 1, UCCL_KERNEL_GATHER = 2, UCCL_KERNEL_GATHER_PARTS = 3 };
+typedef struct uccl_plan {
+  uint32_t kernel;            /* UCCL_KERNEL_* */
+  uint32_t records_per_group; /* records one workgroup takes (1 when a record is cut into parts) */
+  uint32_t parts;             /* workgroups per record */
+  uint32_t threads;           /* workgroup size */
+  uint32_t groups;            /* workgroups in the launch */
+  uint32_t unit_bytes;        /* bytes per stream a wavefront moves per trip */
+  uint32_t reserved[2];       /* 0 */
+} uccl_plan;
+int uccl_launch_plan(uint32_t n_descs, const uccl_launch_opts* opts, int gather, int reads_acc, uccl_plan* plan);
+
 /* Measurement aid: the next apply / scatter / report call made by THIS host thread attaches the
  * two hipEvent_t (either may be NULL) to its kernel dispatch, so that
  * hipEventElapsedTime(start, stop) is that kernel's own execution time on the device,

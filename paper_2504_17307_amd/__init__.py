@@ -34,6 +34,14 @@ class uccl_launch_opts(C.Structure):
     _fields_ = [("chunk_bytes", C.c_uint32), ("parts", C.c_uint32), ("reserved", C.c_uint32 * 2)]
 
 
+class uccl_plan(C.Structure):
+    _fields_ = [("kernel", C.c_uint32), ("records_per_group", C.c_uint32), ("parts", C.c_uint32),
+                ("threads", C.c_uint32), ("groups", C.c_uint32), ("unit_bytes", C.c_uint32), ("reserved", C.c_uint32 * 2)]
+
+
+KERNEL_NAMES = ("chunk_flat_kernel", "chunk_few_kernel", "chunk_gather_kernel", "chunk_gather_parts_kernel")
+
+
 class uccl_feed_stats(C.Structure):
     _fields_ = [("flushes", C.c_uint64), ("records", C.c_uint64), ("max_batch", C.c_uint64),
                 ("slot_waits", C.c_uint64)]
@@ -94,6 +102,7 @@ _SIGNATURES = {
     "uccl_dedup_report": (C.c_int, [C.c_void_p, C.c_uint64, C.c_void_p, C.c_uint32, C.c_void_p]),
     "uccl_message_status": (C.c_int, [C.c_void_p, C.c_void_p, C.c_uint32, C.c_uint32, C.c_void_p, C.c_int,
                                       C.c_void_p]),
+    "uccl_launch_plan": (C.c_int, [C.c_uint32, C.POINTER(uccl_launch_opts), C.c_int, C.c_int, C.POINTER(uccl_plan)]),
     "uccl_time_next_launch": (C.c_int, [C.c_void_p, C.c_void_p]),
     "uccl_strerror": (C.c_char_p, [C.c_int]),
     "uccl_last_error_detail": (C.c_char_p, []),
@@ -365,6 +374,15 @@ def uccl_dedup_report(dedup_bitmap, n_bits, report, max_ranges, stream=None):
     """``report``: a tensor of at least 32 + 16 * max_ranges bytes (device or pinned host)."""
     _call("uccl_dedup_report", _ptr(dedup_bitmap), int(n_bits), _ptr(report), int(max_ranges),
           _stream(stream))
+
+
+def uccl_launch_plan(n_descs, opts=None, gather=False, reads_acc=True) -> dict:
+    """What a call of ``n_descs`` records with these options is launched as (host arithmetic only)."""
+    p = uccl_plan()
+    _call("uccl_launch_plan", int(n_descs), _opts(opts), int(bool(gather)), int(bool(reads_acc)), C.byref(p))
+    d = {k: getattr(p, k) for k, _ in uccl_plan._fields_ if k != "reserved"}
+    d["kernel"] = KERNEL_NAMES[p.kernel]
+    return d
 
 
 def uccl_time_next_launch(start_event, stop_event):

@@ -283,60 +283,92 @@ uint32_t auto_parts(uint32_t n_descs, uint32_t chunk_bytes) {
 constexpr uint32_t kSmallCallRecords = UCCL_SMALL_CALL_RECORDS;
 constexpr uint32_t kHalfTileRecords = UCCL_HALF_TILE_RECORDS;
 
+// Which launch a call gets: decided here, in one place, from the record count and the tuning alone
+// (pure host arithmetic; uccl_launch_plan reports it).  `parts` > 1 is a wish: it needs claim words,
+// and a call that finds none (no free region, stream being captured) takes the uncut route instead.
+enum Route : uint32_t {
+  kRouteTile,       // chunk_flat_kernel, `tile` >= 2 records per workgroup
+  kRouteOne,        // chunk_flat_kernel, one record per workgroup
+  kRouteFew,        // chunk_few_kernel, one UCCL_FEW_THREADS workgroup per record (calls of < kFewRecords large records)
+  kRouteParts,      // chunk_few_kernel, `parts` workgroups of UCCL_PART_THREADS per record
+  kRouteHalf,       // chunk_few_kernel<1024, 1>: chunks of 8-16 KiB, one workgroup per record
+  kRouteSmall1,     // chunk_few_kernel<256, 1>: at most kSmallCallRecords chunks of up to 4 KiB
+  kRouteSmall2,     // chunk_few_kernel<256, 2>: the same, chunks of up to 8 KiB
+};
+struct Plan {
+  Route route;
+  uint32_t tile, parts, threads, unroll;
+};
+
+Plan plan_apply(uint32_t n_descs, const Tuning& tune, bool reads_acc) {
+  const uint32_t t = flat_tile(n_descs, tune.chunk_bytes);
+  if (t >= 2 && tune.chunk_bytes > 8192u && n_descs < kHalfTileRecords) return {kRouteHalf, 1u, 1u, 1024u, 1u};
+  if (t >= 2 && tune.chunk_bytes != 0u && n_descs <= kSmallCallRecords) {
+    // workgroup sized to the chunk: one trip of 16 bytes x unroll per lane covers it
+    if (tune.chunk_bytes <= 4096u) return {kRouteSmall1, 1u, 1u, 256u, 1u};
+    return {kRouteSmall2, 1u, 1u, 256u, 2u};
+  }
+  if (t >= 2) return {kRouteTile, t >= 32 ? 32u : t >= 16 ? 16u : t >= 8 ? 8u : t >= 4 ? 4u : 2u, 1u, UCCL_FLAT_THREADS, UCCL_FLAT_UNROLL};
+  const uint32_t parts = tune.parts ? tune.parts : (n_descs < kFewRecords ? auto_parts(n_descs, tune.chunk_bytes) : 1u);
+  if (parts > 1u && n_descs <= kRegionRecords) return {kRouteParts, 1u, parts, UCCL_PART_THREADS, UCCL_PART_UNROLL};
+  if (n_descs < kFewRecords) return {kRouteFew, 1u, 1u, UCCL_FEW_THREADS, UCCL_FEW_UNROLL};
+  // One record per workgroup.  Kernels that read the accumulator take 1 KiB units here (a wavefront
+  // makes two trips through a 32 KiB chunk, eight through a 128 KiB one, its stores of one trip
+  // between the loads of two): measured 0.7 % faster on 32 KiB chunks and 1.9 % on 128 KiB ones
+  // than 2 KiB units; copies are 5 % slower that way and keep 2 KiB units.
+  const uint32_t unroll = reads_acc ? UCCL_FLAT1_REDUCE_UNROLL : UCCL_FLAT_UNROLL;
+  return {kRouteOne, 1u, 1u, UCCL_FLAT_THREADS, unroll};
+}
+
 template <class Op>
 int launch_flat_tile(Args& a, hipStream_t s, const Tuning& tune) {
-  const uint32_t t = flat_tile(a.n_descs, tune.chunk_bytes);
-  if (t >= 2 && tune.chunk_bytes > 8192u && a.n_descs < kHalfTileRecords)
-    return launch_kernel(chunk_few_kernel<1024, 1, Op, false>, a.n_descs, 1024, s, a);
-  if (t >= 2 && tune.chunk_bytes != 0u && a.n_descs <= kSmallCallRecords) {
-    // workgroup sized to the chunk: one trip of 16 bytes x unroll per lane covers it
-    if (tune.chunk_bytes <= 4096u) return launch_kernel(chunk_few_kernel<256, 1, Op, false>, a.n_descs, 256, s, a);
-    return launch_kernel(chunk_few_kernel<256, 2, Op, false>, a.n_descs, 256, s, a);
-  }
-  if (t >= 32) return launch_flat<32, UCCL_FLAT_UNROLL, Op>(a, s);
-  if (t >= 16) return launch_flat<16, UCCL_FLAT_UNROLL, Op>(a, s);
-  if (t >= 8) return launch_flat<8, UCCL_FLAT_UNROLL, Op>(a, s);
-  if (t >= 4) return launch_flat<4, UCCL_FLAT_UNROLL, Op>(a, s);
-  if (t >= 2) return launch_flat<2, UCCL_FLAT_UNROLL, Op>(a, s);
-  const uint32_t parts = tune.parts ? tune.parts : (a.n_descs < kFewRecords ? auto_parts(a.n_descs, tune.chunk_bytes) : 1u);
-  if (parts > 1u && tune.static_claims != nullptr && a.n_descs <= UCCL_NOALLOC_MAX_DESCS) {
-    // Every call shares the device's one array, which keeps what the last call (or the last replay
-    // of this very launch) left in it: clear this call's words first, with a fill kernel (no memset
-    // node, so that the pair can be captured), then launch with a tag larger than a cleared word's.
-    a.claims = tune.static_claims;
-    a.faults = reinterpret_cast<uint32_t*>(tune.static_claims + UCCL_NOALLOC_MAX_DESCS * UCCL_CLAIM_STRIDE);
-    a.tag = 1ull;
-    a.parts = parts;
-    const hipEvent_t keep0 = t_start, keep1 = t_stop;  // the timing events belong to the data kernel
-    t_start = t_stop = nullptr;
-    const uint64_t words = 2ull * a.n_descs * UCCL_CLAIM_STRIDE;
-    const int rc = launch_kernel(fill_words_kernel, static_cast<uint32_t>((words + 255) / 256), 256, s,
-                                 reinterpret_cast<uint32_t*>(a.claims), words, 0u);
-    t_start = keep0;
-    t_stop = keep1;
-    if (rc != UCCL_OK) { t_start = t_stop = nullptr; return rc; }
-    return launch_kernel(chunk_few_kernel<UCCL_PART_THREADS, UCCL_PART_UNROLL, Op, true>, a.n_descs * parts,
-                         UCCL_PART_THREADS, s, a);
-  }
-  if (parts > 1u && tune.static_claims == nullptr && a.n_descs <= kRegionRecords) {
+  Plan p = plan_apply(a.n_descs, tune, Op::kReadsAcc);
+  if (p.route == kRouteParts) {
+    if (tune.static_claims != nullptr) {
+      // Every call shares the device's one array, which keeps what the last call (or the last replay
+      // of this very launch) left in it: clear this call's words first, with a fill kernel (no memset
+      // node, so that the pair can be captured), then launch with a tag larger than a cleared word's.
+      a.claims = tune.static_claims;
+      a.faults = reinterpret_cast<uint32_t*>(tune.static_claims + UCCL_NOALLOC_MAX_DESCS * UCCL_CLAIM_STRIDE);
+      a.tag = 1ull;
+      a.parts = p.parts;
+      const hipEvent_t keep0 = t_start, keep1 = t_stop;  // the timing events belong to the data kernel
+      t_start = t_stop = nullptr;
+      const uint64_t words = 2ull * a.n_descs * UCCL_CLAIM_STRIDE;
+      const int rc = launch_kernel(fill_words_kernel, static_cast<uint32_t>((words + 255) / 256), 256, s,
+                                   reinterpret_cast<uint32_t*>(a.claims), words, 0u);
+      t_start = keep0;
+      t_stop = keep1;
+      if (rc != UCCL_OK) { t_start = t_stop = nullptr; return rc; }
+      return launch_kernel(chunk_few_kernel<UCCL_PART_THREADS, UCCL_PART_UNROLL, Op, true>, a.n_descs * p.parts,
+                           UCCL_PART_THREADS, s, a);
+    }
     ClaimPool* pool = nullptr;
     a.claims = claim_region(s, &a.faults, &pool);
     if (a.claims != nullptr) {
       std::lock_guard<std::mutex> in_order(pool->launch_lock);
       a.tag = g_next_tag.fetch_add(1, std::memory_order_relaxed);
-      a.parts = parts;
-      return launch_kernel(chunk_few_kernel<UCCL_PART_THREADS, UCCL_PART_UNROLL, Op, true>, a.n_descs * parts,
+      a.parts = p.parts;
+      return launch_kernel(chunk_few_kernel<UCCL_PART_THREADS, UCCL_PART_UNROLL, Op, true>, a.n_descs * p.parts,
                            UCCL_PART_THREADS, s, a);
     }
+    p.route = a.n_descs < kFewRecords ? kRouteFew : kRouteOne;   // no claim words to be had: uncut
   }
-  if (a.n_descs < kFewRecords)
-    return launch_kernel(chunk_few_kernel<UCCL_FEW_THREADS, UCCL_FEW_UNROLL, Op, false>, a.n_descs,
-                         UCCL_FEW_THREADS, s, a);
-  // One record per workgroup.  Kernels that read the accumulator take 1 KiB units here (a wavefront
-  // makes two trips through a 32 KiB chunk, eight through a 128 KiB one, its stores of one trip
-  // between the loads of two): measured 0.7 % faster on 32 KiB chunks and 1.9 % on 128 KiB ones
-  // than 2 KiB units; copies are 5 % slower that way and keep 2 KiB units.
-  return launch_flat<1, Op::kReadsAcc ? UCCL_FLAT1_REDUCE_UNROLL : UCCL_FLAT_UNROLL, Op>(a, s);
+  switch (p.route) {
+    case kRouteHalf: return launch_kernel(chunk_few_kernel<1024, 1, Op, false>, a.n_descs, 1024, s, a);
+    case kRouteSmall1: return launch_kernel(chunk_few_kernel<256, 1, Op, false>, a.n_descs, 256, s, a);
+    case kRouteSmall2: return launch_kernel(chunk_few_kernel<256, 2, Op, false>, a.n_descs, 256, s, a);
+    case kRouteFew:
+      return launch_kernel(chunk_few_kernel<UCCL_FEW_THREADS, UCCL_FEW_UNROLL, Op, false>, a.n_descs,
+                           UCCL_FEW_THREADS, s, a);
+    case kRouteTile:
+      if (p.tile >= 32) return launch_flat<32, UCCL_FLAT_UNROLL, Op>(a, s);
+      if (p.tile >= 16) return launch_flat<16, UCCL_FLAT_UNROLL, Op>(a, s);
+      if (p.tile >= 8) return launch_flat<8, UCCL_FLAT_UNROLL, Op>(a, s);
+      if (p.tile >= 4) return launch_flat<4, UCCL_FLAT_UNROLL, Op>(a, s);
+      return launch_flat<2, UCCL_FLAT_UNROLL, Op>(a, s);
+    default: return launch_flat<1, Op::kReadsAcc ? UCCL_FLAT1_REDUCE_UNROLL : UCCL_FLAT_UNROLL, Op>(a, s);
+  }
 }
 
 template <int T, class Op>
@@ -360,22 +392,31 @@ uint32_t gather_parts(uint32_t n_descs, uint32_t chunk_bytes) {
   return parts;
 }
 
+Plan plan_gather(uint32_t n_descs, const Tuning& tune) {
+  const uint32_t t = flat_tile(n_descs, tune.chunk_bytes);
+  if (t >= 2) return {kRouteTile, t >= 16 ? 16u : t >= 8 ? 8u : t >= 4 ? 4u : 2u, 1u, 1024u, UCCL_GATHER_UNROLL};
+  const uint32_t parts = tune.parts ? tune.parts : gather_parts(n_descs, tune.chunk_bytes);
+  if (parts > 1u && n_descs <= kRegionRecords) return {kRouteParts, 1u, parts, UCCL_PART_THREADS, UCCL_GATHER_UNROLL};
+  return {kRouteOne, 1u, 1u, 1024u, UCCL_GATHER_UNROLL};
+}
+
 template <class Op>
 int launch_gather_tile(GatherArgs& a, hipStream_t s, const Tuning& tune) {
-  const uint32_t t = flat_tile(a.n_descs, tune.chunk_bytes);
-  if (t >= 16) return launch_gather<16, Op>(a, s);
-  if (t >= 8) return launch_gather<8, Op>(a, s);
-  if (t >= 4) return launch_gather<4, Op>(a, s);
-  if (t >= 2) return launch_gather<2, Op>(a, s);
-  const uint32_t parts = tune.parts ? tune.parts : gather_parts(a.n_descs, tune.chunk_bytes);
-  if (parts > 1u && a.n_descs <= kRegionRecords) {
+  const Plan p = plan_gather(a.n_descs, tune);
+  if (p.route == kRouteTile) {
+    if (p.tile >= 16) return launch_gather<16, Op>(a, s);
+    if (p.tile >= 8) return launch_gather<8, Op>(a, s);
+    if (p.tile >= 4) return launch_gather<4, Op>(a, s);
+    return launch_gather<2, Op>(a, s);
+  }
+  if (p.route == kRouteParts) {
     ClaimPool* pool = nullptr;
     a.claims = claim_region(s, &a.faults, &pool);
     if (a.claims != nullptr) {
       std::lock_guard<std::mutex> in_order(pool->launch_lock);
       a.tag = g_next_tag.fetch_add(1, std::memory_order_relaxed);
-      a.parts = parts;
-      return launch_kernel(chunk_gather_parts_kernel<UCCL_PART_THREADS, UCCL_GATHER_UNROLL, Op>, a.n_descs * parts,
+      a.parts = p.parts;
+      return launch_kernel(chunk_gather_parts_kernel<UCCL_PART_THREADS, UCCL_GATHER_UNROLL, Op>, a.n_descs * p.parts,
                            UCCL_PART_THREADS, s, a);
     }
   }
@@ -904,6 +945,23 @@ int uccl_message_status(uint32_t* dedup_bitmap, const uint32_t* n_chunks, uint32
   return launch_kernel(message_status_kernel, grid, 256, static_cast<hipStream_t>(stream), dedup_bitmap,
                        n_chunks, n_slots, bits_per_slot / 32, reinterpret_cast<uint4*>(status),
                        recycle ? 1u : 0u);
+}
+
+int uccl_launch_plan(uint32_t n_descs, const uccl_launch_opts* opts, int gather, int reads_acc, uccl_plan* plan) {
+  Tuning tune;
+  if (!plan || !tuning_from(opts, &tune)) return UCCL_EINVAL;
+  const Plan p = gather ? plan_gather(n_descs, tune) : plan_apply(n_descs, tune, reads_acc != 0);
+  const bool few = !gather && p.route != kRouteTile && p.route != kRouteOne;
+  plan->kernel = gather ? (p.route == kRouteParts ? UCCL_KERNEL_GATHER_PARTS : UCCL_KERNEL_GATHER)
+                        : (few ? UCCL_KERNEL_FEW : UCCL_KERNEL_FLAT);
+  plan->records_per_group = p.tile;
+  plan->parts = p.parts;
+  plan->threads = p.threads;
+  plan->unit_bytes = 64u * 16u * p.unroll;
+  const uint64_t groups = p.route == kRouteTile ? tiles_for(n_descs, p.tile) : static_cast<uint64_t>(n_descs) * p.parts;
+  plan->groups = static_cast<uint32_t>(groups);
+  plan->reserved[0] = plan->reserved[1] = 0u;
+  return UCCL_OK;
 }
 
 int uccl_time_next_launch(void* start_event, void* stop_event) {

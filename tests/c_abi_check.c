@@ -160,6 +160,15 @@ static int feed_check(hipStream_t st) {
  */
 static int more_entry_points(hipStream_t st) {
   enum { N = 24, C = 65536, NS = 3, SLOTS = 16, BPS = 64 };
+  { /* what the library says it launches for the calls made below (host arithmetic only) */
+    const uccl_launch_opts four = {C, 4, {0, 0}};
+    uccl_plan pl;
+    if (uccl_launch_plan(N + 4, &four, 0, 1, &pl) != UCCL_OK || pl.kernel != UCCL_KERNEL_FEW || pl.parts != 4 ||
+        pl.groups != (N + 4) * 4 || uccl_launch_plan(N, NULL, 1, 1, &pl) != UCCL_OK || pl.kernel != UCCL_KERNEL_GATHER_PARTS) {
+      printf("launch plan\n");
+      return 1;
+    }
+  }
   const uint64_t bytes = (uint64_t)N * C;
   uint32_t seed = 4242u;
   float* h_recv = (float*)malloc(bytes * NS);

@@ -165,3 +165,55 @@ def test_prepare_marshals_once_and_repeats_the_c_call():
         pkg.uccl_prepare(pkg.uccl_chunk_apply_checked, A, None, B, D, 1, M, 0, 0, stream=0)   # binding capturing
     with pytest.raises(pkg.UcclError):       # an ordinary call is made, not captured
         pkg.uccl_chunk_apply(A + 8, None, B, D, 1, M, 0, 0, stream=0)
+
+
+def test_launch_plan_rules():
+    """Host logic: which launch a call gets (uccl_launch_plan is the rule the data-path calls apply)."""
+    plan = pkg.uccl_launch_plan
+    KiB = 1024
+    # the routing table of the design, one row each
+    assert plan(7856, (32 * KiB, 0)) == dict(kernel="chunk_flat_kernel", records_per_group=1, parts=1, threads=1024,
+                                             groups=7856, unit_bytes=1024)
+    assert plan(7856, (32 * KiB, 0), reads_acc=False)["unit_bytes"] == 2048          # copies keep 2 KiB units
+    assert plan(2047, (32 * KiB, 0))["kernel"] == "chunk_few_kernel" and plan(2048, (32 * KiB, 0))["kernel"] == "chunk_flat_kernel"
+    assert plan(57, (64 * KiB, 0)) == dict(kernel="chunk_few_kernel", records_per_group=1, parts=8, threads=256,
+                                           groups=456, unit_bytes=2048)
+    assert plan(8, (128 * KiB, 0))["parts"] == 16 and plan(256, (128 * KiB, 0))["parts"] == 1   # 32 MiB: not cut
+    assert plan(32, (32 * KiB, 0))["parts"] == 8 and plan(33, (32 * KiB, 0))["parts"] == 1
+    assert plan(3620, (16 * KiB, 0)) == dict(kernel="chunk_few_kernel", records_per_group=1, parts=1, threads=1024,
+                                             groups=3620, unit_bytes=1024)
+    assert plan(8192, (16 * KiB, 0)) == dict(kernel="chunk_flat_kernel", records_per_group=2, parts=1, threads=1024,
+                                             groups=4096, unit_bytes=2048)
+    assert plan(128, (4 * KiB, 0))["threads"] == 256 and plan(128, (4 * KiB, 0))["unit_bytes"] == 1024
+    assert plan(128, (8 * KiB, 0))["unit_bytes"] == 2048
+    assert plan(129, (4 * KiB, 0)) == dict(kernel="chunk_flat_kernel", records_per_group=8, parts=1, threads=1024,
+                                           groups=17, unit_bytes=2048)
+    assert plan(1000, (1 * KiB, 0))["records_per_group"] == 32 and plan(1000, (64, 0))["records_per_group"] == 32
+    # no chunk size given: by record count alone
+    assert [plan(n)["parts"] for n in (1, 64, 65, 128, 129)] == [8, 8, 4, 4, 1]
+    assert [plan(n)["records_per_group"] for n in (8191, 8192, 32768, 131072)] == [1, 4, 8, 16]
+    # a stated number of parts is honoured where a workgroup takes one record and the call has at most 2048
+    assert plan(57, (64 * KiB, 5))["parts"] == 5 and plan(2048, (64 * KiB, 2))["groups"] == 4096
+    assert plan(2049, (64 * KiB, 2))["parts"] == 1 and plan(57, (4 * KiB, 5))["parts"] == 1
+    assert plan(0, (32 * KiB, 0))["groups"] == 0
+    # the multi-source fold
+    assert plan(8, (128 * KiB, 0), gather=True) == dict(kernel="chunk_gather_parts_kernel", records_per_group=1, parts=16,
+                                                        threads=256, groups=128, unit_bytes=2048)
+    assert plan(128, (32 * KiB, 0), gather=True)["parts"] == 4 and plan(1024, (128 * KiB, 0), gather=True)["parts"] == 1
+    assert plan(5000, (4 * KiB, 0), gather=True)["records_per_group"] == 8
+    # invariants over a sweep: a cut launch stays within 2048 workgroups of at most 16 per record;
+    # the grid covers every record
+    for c in (0, 64, 4 * KiB, 8 * KiB, 12 * KiB, 16 * KiB, 24 * KiB, 32 * KiB, 48 * KiB, 64 * KiB, 128 * KiB, 1 << 20):
+        for n in (1, 2, 31, 32, 33, 64, 127, 128, 129, 512, 2047, 2048, 2049, 8191, 8192, 100000, 2 ** 32 - 1):
+            for g in (False, True):
+                p = plan(n, (c, 0), gather=g)
+                assert 1 <= p["parts"] <= 16 and 1 <= p["records_per_group"] <= 32
+                assert p["parts"] == 1 or (p["records_per_group"] == 1 and n * p["parts"] <= 2048)
+                assert p["groups"] * p["records_per_group"] >= n * p["parts"] and p["groups"] <= n * p["parts"]
+                assert p["threads"] in (256, 1024) and p["unit_bytes"] in (1024, 2048, 4096)
+    # what the data-path calls refuse, the plan refuses
+    lib = pkg.load()
+    out = pkg.uccl_plan()
+    bad = pkg.uccl_launch_opts(4096, 17)
+    assert lib.uccl_launch_plan(10, C.byref(bad), 0, 1, C.byref(out)) == pkg.UCCL_EINVAL
+    assert lib.uccl_launch_plan(10, None, 0, 1, None) == pkg.UCCL_EINVAL
