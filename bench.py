@@ -129,17 +129,17 @@ def two_pass_calls(w, chunk, group=1):
     return calls, transport_bytes
 
 
-def build_job(name, seed, n_msgs, relay=False, per_call=128, packet_bytes=0):
+def build_job(name, seed, n_msgs, relay=False, per_call=128, packet_bytes=0, dup=None):
     """Returns (workload, calls, chunk_bytes) with calls = list of dicts
     {name, op, descs (numpy), n_unique, payload_bytes, algo_bytes, scatter}."""
     from synth import workloads as wl
     from synth.layout import SUM, COPY
     if name in ("config1", "config2", "config3"):
         chunk = {"config1": 64 << 10, "config2": 32 << 10, "config3": 128 << 10}[name]
-        kw = {}
+        kw = {} if dup is None else dict(dup=dup)
         if packet_bytes:  # arrivals are MTU-sized packets; the reorder window keeps its size in bytes
             window = {"config1": None, "config2": 1024, "config3": 256}[name]
-            kw = dict(C=packet_bytes, window=None if window is None else window * chunk // packet_bytes)
+            kw.update(C=packet_bytes, window=None if window is None else window * chunk // packet_bytes)
         w = getattr(wl, name)(seed=seed, relay=relay, **kw)
         calls = [dict(name=ph.name, op=ph.op, descs=ph.descs, n_unique=ph.n_unique,
                       payload_bytes=ph.payload_bytes, algo_bytes=ph.algo_bytes, scatter=False)
@@ -701,6 +701,7 @@ def parse_args():
     ap.add_argument("--seed", type=int, default=1)
     ap.add_argument("--sets", type=int, default=4, help="buffer sets the steps rotate over")
     ap.add_argument("--messages", type=int, default=10000, help="config5: number of messages")
+    ap.add_argument("--duplicates", type=float, default=None, help="config1-3: retransmitted share of the chunks instead of the recipe's")
     ap.add_argument("--no-prepare", action="store_true", help="marshal every call's arguments anew instead of once")
     ap.add_argument("--streams", type=int, default=1,
                     help="config5: issue consecutive message batches round-robin on this many streams "
@@ -760,7 +761,7 @@ def main():
         return bench_segment(args, pkg, torch)
     t0 = time.time()
     w, calls, chunk_bytes = build_job(args.workload, args.seed, args.messages, args.relay, args.messages_per_call,
-                                      args.packet_bytes)
+                                      args.packet_bytes, args.duplicates)
     collective_chunk = {"config1": 64 << 10, "config2": 32 << 10, "config3": 128 << 10}.get(args.workload, chunk_bytes)
     if args.chunk_hint is not None:
         chunk_bytes = args.chunk_hint
@@ -938,7 +939,7 @@ def main():
                       {"unique_chunks": unique, "arrivals": arrivals, "payload_bytes": payload,
                        "algorithmic_bytes": algo, "parts": args.parts, "chunk_hint": opts[0], "buffer_sets": len(sets),
                        "forward_only_intermediate_steps": bool(args.relay), "two_pass": bool(args.two_pass),
-                       "packet_bytes": args.packet_bytes or None, "graph_replay": bool(args.graph),
+                       "packet_bytes": args.packet_bytes or None, "duplicates": args.duplicates, "graph_replay": bool(args.graph),
                        "stagger_bytes": args.stagger or None, "prepared_calls": prepared is not None,
                        "calls_per_step": 1 + sum(-(-n // (args.records_per_call or max(n, 1))) for n in counts),
                        "records_per_call": args.records_per_call or None, "streams": args.streams, "cache": cache_note})
