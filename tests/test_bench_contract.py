@@ -77,4 +77,4 @@ def test_bench_is_one_program():
            {n.attr for n in ast.walk(tree) if isinstance(n, ast.Attribute)}
     unused = [n.name for n in defs if n.name not in used]
     assert not unused, f"never referenced: {unused}"
-    assert len(src.splitlines()) < 1000
+    assert len(src.splitlines()) < 950
